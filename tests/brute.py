@@ -1,0 +1,121 @@
+"""Independent brute-force decoder used to pin the oracle on tiny traces.
+
+Pure Python, written differently from oracle/ref_decode.c on purpose:
+  * ordering uses a dict keyed by rank instead of a slot_of_rank array,
+  * pairing uses one "open START" cell per region (a depth-1 stack) instead of
+    walking each region's subsequence for adjacent START/END,
+  * overlap is a tick-by-tick simulation of which regions are active in at
+    least one wave, instead of an event sweep.
+It reads the raw words directly and knows the trace layout only from the
+format description (Sec. 4.2 of the paper for record size and flag bit).
+"""
+import numpy as np
+
+
+def brute_decode(raw: np.ndarray) -> dict:
+    raw = [int(x) for x in raw]
+    assert raw[0] == 0x4652504B and raw[1] == 1
+    n_wg, W, R, cap, rec_cost, flags = raw[2:8]
+    flush = flags & 1
+    rec0 = (64 + 128 * n_wg) // 4
+    st = dict(n_slots_valid=0, n_pairs=0, n_orphan_start=0, n_orphan_end=0, n_invalid=0, n_dropped=0,
+              n_disorder=0, n_span_overflow_wgs=0, n_nonmonotonic=0, n_overlap_wgs=0)
+    hist = np.zeros((R, 64), dtype=np.uint64)
+    cnt = np.zeros(R, dtype=np.uint64)
+    ssum = np.zeros(R, dtype=np.uint64)
+    smin = np.full(R, np.iinfo(np.uint64).max, dtype=np.uint64)
+    smax = np.zeros(R, dtype=np.uint64)
+    U = np.zeros(R, dtype=np.uint64)
+    O = np.zeros((R, R), dtype=np.uint64)
+    per = np.zeros((n_wg, W, R, 3), dtype=np.uint64)
+    for wg in range(n_wg):
+        h = (64 + 128 * wg) // 4
+        t_begin = raw[h + 2] | (raw[h + 3] << 32)
+        t_end = raw[h + 4] | (raw[h + 5] << 32)
+        span = (t_end - t_begin) % (1 << 64)
+        intervals = []  # (region, start, end)
+        bad = 0
+        nonmono = 0
+        for w in range(W):
+            T = raw[h + 8 + w]
+            V = min(T, cap)
+            st["n_dropped"] += T - V
+            st["n_slots_valid"] += V
+            first = 0 if flush else T - V
+            by_rank = {}
+            for s in range(V):
+                tag = raw[rec0 + 2 * ((wg * W + w) * cap + s)]
+                ts = raw[rec0 + 2 * ((wg * W + w) * cap + s) + 1]
+                seq, wave, region, phase = tag & 0xFFFFF, (tag >> 20) & 15, (tag >> 24) & 127, tag >> 31
+                k = (seq - first) % (1 << 20)
+                if k >= V or wave != w or region >= R:
+                    bad += 1
+                    continue
+                if k in by_rank:
+                    bad += 1
+                by_rank[k] = (s, seq, region, phase, ts)
+            seqn = [by_rank[k] for k in sorted(by_rank)]
+            st["n_disorder"] += sum(1 for (s, seq, *_r) in seqn if s != seq % cap)
+            nonmono += sum(1 for a, b in zip(seqn, seqn[1:]) if b[4] < a[4])
+            open_ts = [None] * R
+            for (_s, _seq, region, phase, ts) in seqn:
+                if phase == 0:
+                    if open_ts[region] is not None:
+                        st["n_orphan_start"] += 1
+                    open_ts[region] = ts
+                else:
+                    if open_ts[region] is None:
+                        st["n_orphan_end"] += 1
+                    else:
+                        d_raw = (ts - open_ts[region]) % (1 << 32)
+                        d = max(0, d_raw - rec_cost)
+                        st["n_pairs"] += 1
+                        b = 0 if d < 2 else int(d).bit_length() - 1
+                        hist[region, b] += np.uint64(1)
+                        cnt[region] += np.uint64(1)
+                        ssum[region] += np.uint64(d)
+                        smin[region] = min(int(smin[region]), d)
+                        smax[region] = max(int(smax[region]), d)
+                        per[wg, w, region, 0] += np.uint64(d)
+                        per[wg, w, region, 1] += np.uint64(1)
+                        per[wg, w, region, 2] = max(int(per[wg, w, region, 2]), d)
+                        intervals.append((region, open_ts[region], open_ts[region] + d_raw))
+                        open_ts[region] = None
+            st["n_orphan_start"] += sum(1 for x in open_ts if x is not None)
+        st["n_invalid"] += bad
+        st["n_nonmonotonic"] += nonmono
+        if span >= (1 << 32):
+            st["n_span_overflow_wgs"] += 1
+            continue
+        if bad or nonmono:
+            continue
+        st["n_overlap_wgs"] += 1
+        if intervals:
+            horizon = max(e for _r, _s, e in intervals)
+            assert horizon < 200000, "brute force is for tiny traces"
+            act = np.zeros((R, horizon), dtype=bool)
+            for r, s, e in intervals:
+                act[r, s:e] = True
+            for a in range(R):
+                U[a] += np.uint64(int(act[a].sum()))
+                for b in range(R):
+                    O[a, b] += np.uint64(int((act[a] & act[b]).sum()))
+    F = np.zeros((R, R))
+    for a in range(R):
+        for b in range(R):
+            F[a, b] = float(O[a, b]) / float(U[a]) if U[a] else 0.0
+    st.update(hist=hist, cnt=cnt, sum=ssum, min=smin, max=smax, U=U, O=O, F=F, per=per)
+    return st
+
+
+def assert_same(ref: dict, got: dict):
+    for k in ("n_slots_valid", "n_pairs", "n_orphan_start", "n_orphan_end", "n_invalid", "n_dropped",
+              "n_disorder", "n_span_overflow_wgs", "n_nonmonotonic", "n_overlap_wgs"):
+        assert ref[k] == got[k], (k, ref[k], got[k])
+    for k in ("hist", "cnt", "sum", "min", "max", "U", "O"):
+        assert np.array_equal(np.asarray(ref[k]), np.asarray(got[k])), k
+    assert np.array_equal(np.asarray(ref["F"]), np.asarray(got["F"])), "F"
+    p = got["per"]
+    assert np.array_equal(ref["per"][..., 0], p["sum"])
+    assert np.array_equal(ref["per"][..., 1], p["n"].astype(np.uint64))
+    assert np.array_equal(ref["per"][..., 2], p["max"].astype(np.uint64))
