@@ -1,0 +1,154 @@
+/*
+ * libkperf -- region-level intra-kernel timing on MI355X (gfx950): C ABI.
+ *
+ * The library implements the data-parallel hot path of the region-based timing
+ * tool of "KPerfIR" (arXiv 2505.21661, Sec. 4): kernels record START/END clock
+ * events of marked code regions per wavefront into an LDS ring (Sec. 4.2),
+ * copy the ring to a caller-provided trace buffer in HBM before returning
+ * (Sec. 4.2 "Global Program Trace"), and a GPU decoder pairs the events into
+ * durations and overlap statistics (Sec. 4.3 "Trace Replay", moved onto the
+ * GPU).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller unless the
+ *     parameter comment says "host".  The library keeps no device allocation.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously; results are valid once the caller has
+ *     synchronised the stream.  Exception: kp_trace_reduce (see there).
+ *   - Return value: KP_OK or a negative kp_status.  Nothing throws or aborts;
+ *     kp_last_error() gives a human-readable reason for the calling thread.
+ */
+#ifndef KPERF_H
+#define KPERF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int kp_status;
+enum {
+  KP_OK = 0,
+  KP_ERR_INVALID_ARG = -1,       /* NULL pointer, negative size, bad flag                      */
+  KP_ERR_UNSUPPORTED_SHAPE = -2, /* shape/geometry outside what the kernels are built for      */
+  KP_ERR_TRACE_TOO_SMALL = -3,   /* trace_cap not usable (see each call)                       */
+  KP_ERR_BAD_TRACE = -4,         /* trace header magic/version/geometry does not match `n`     */
+  KP_ERR_HIP = -5                /* a HIP runtime call failed; message holds hipGetErrorString */
+};
+
+/* ---- raw trace format (Sec. 4.2: 8-byte records, per-wave slot runs, metadata) ------------
+ *
+ *   [ kp_trace_hdr : 64 B ][ kp_wg_hdr : 128 B x n_wg ][ records : n_wg x waves x cap_wave x 8 B ]
+ *
+ * A record is a 4-byte tag followed by a 4-byte payload (Sec. 4.2 "Warp-level Region Data
+ * Structure").  The paper fixes one START/END flag bit and leaves the other 31 tag bits to
+ * the backend; this library uses
+ *   tag[31]    phase: 0 = START, 1 = END
+ *   tag[30:24] region id
+ *   tag[23:20] wave index inside the workgroup
+ *   tag[19:0]  seq: the wave's record counter (mod 2^20) when the record was written
+ *   payload    low 32 bits of (s_memtime - t_begin of the workgroup)
+ * The segment of (workgroup g, wave w) is the cap_wave slots starting at record index
+ * (g*waves + w)*cap_wave.  Circular strategy: a record lives in slot seq mod cap_wave and
+ * only the newest cap_wave records of a wave survive (Sec. 4.2 "Shared Memory Circular
+ * Buffer").  Flush strategy: slot = seq, records beyond cap_wave are dropped and counted.
+ */
+#define KP_TRACE_MAGIC 0x4652504Bu /* bytes 'K','P','R','F' */
+#define KP_TRACE_VERSION 1u
+#define KP_FLAG_FLUSH 1u            /* kp_trace_hdr.flags bit 0: 0 circular, 1 flush */
+#define KP_MAX_WAVES 16
+#define KP_MAX_REGIONS 32           /* decoder limit; the tag field itself holds 7 bits */
+#define KP_HIST_BINS 64
+
+typedef struct kp_trace_hdr {
+  uint32_t magic, version;
+  uint32_t n_wg;          /* recorded workgroups                                   */
+  uint32_t waves_per_wg;  /* 1..KP_MAX_WAVES                                        */
+  uint32_t n_regions;     /* region ids are 0..n_regions-1                          */
+  uint32_t cap_wave;      /* slots per wave segment, power of two                   */
+  uint32_t rec_cost;      /* ticks subtracted (saturating) from every duration      */
+  uint32_t flags;         /* KP_FLAG_*                                              */
+  uint32_t pad[8];
+} kp_trace_hdr;            /* 64 bytes */
+
+typedef struct kp_wg_hdr {
+  uint32_t wg_id;                         /* linear workgroup index                        */
+  uint32_t hw_id;                         /* low bits of the hardware id register          */
+  uint64_t t_begin;                       /* 64-bit clock at ring init                     */
+  uint64_t t_end;                         /* 64-bit clock at flush                         */
+  uint64_t reserved;
+  uint32_t total_written[KP_MAX_WAVES];   /* records each wave tried to write              */
+  uint32_t pad[8];
+} kp_wg_hdr;               /* 128 bytes */
+
+/* ---- statistics block written by the decoder ------------------------------------------------
+ *
+ *   kp_stats_hdr (128 B)
+ *   u64 hist[R][64]      log2 duration histogram: bin 0 holds d in {0,1}, bin b holds 2^b <= d < 2^(b+1)
+ *   u64 cnt[R], sum[R], min[R], max[R]      (min = UINT64_MAX where cnt = 0)
+ *   u64 U[R]             ticks during which region a is active in at least one wave of a workgroup
+ *   u64 O[R][R]          ticks during which a and b are both active (O[a][a] = U[a], symmetric)
+ *   f64 F[R][R]          O[a][b] / U[a]  (0 where U[a] = 0)
+ *   { u64 sum; u32 n; u32 max } per[n_wg][waves][R]
+ * with R = n_regions.  All sums are exact integers.
+ */
+typedef struct kp_stats_hdr {
+  uint64_t n_slots_valid;       /* slots that hold a record                                    */
+  uint64_t n_pairs;             /* START immediately followed by END of the same (wave,region) */
+  uint64_t n_orphan_start;
+  uint64_t n_orphan_end;
+  uint64_t n_invalid;           /* bad wave/region/seq fields, or displaced by a duplicate seq */
+  uint64_t n_dropped;           /* records that did not fit (overwritten or never stored)      */
+  uint64_t n_disorder;          /* records found in a slot other than seq mod cap_wave         */
+  uint64_t n_span_overflow_wgs; /* workgroups whose t_end - t_begin >= 2^32                    */
+  uint64_t n_nonmonotonic;      /* adjacent records of a wave whose clock decreases            */
+  uint64_t n_overlap_wgs;       /* workgroups that contributed to U and O                      */
+  uint64_t status;              /* 0, or a nonzero code when the device header did not match   */
+  uint64_t n_wg, waves_per_wg, n_regions, cap_wave;
+  uint64_t reserved;
+} kp_stats_hdr;             /* 128 bytes */
+
+typedef struct kp_wave_region_stat {
+  uint64_t sum;
+  uint32_t n;
+  uint32_t max;
+} kp_wave_region_stat;      /* 16 bytes */
+
+/* Reason for the most recent failure on the calling thread ("" if none).  Static storage. */
+const char* kp_last_error(void);
+
+/* Bytes of a trace buffer for n_wg workgroups of waves_per_wg waves sharing cap_per_wg record
+ * slots (cap_per_wg / waves_per_wg slots per wave).  0 on invalid arguments. */
+size_t kp_trace_bytes(int n_wg, int waves_per_wg, int cap_per_wg);
+
+/* Bytes of the statistics block.  0 on invalid arguments. */
+size_t kp_stats_bytes(int n_wg, int waves_per_wg, int n_regions);
+
+/*
+ * Decode, pair and reduce a raw trace (Sec. 4.3: records are stored unpaired and are aligned
+ * at replay; the constant record overhead rec_cost is subtracted).
+ *
+ *   raw        device, the whole trace buffer (headers + records), 16-byte aligned
+ *   n          number of record slots = n_wg * waves_per_wg * cap_wave; must match the header
+ *   out_stats  device, kp_stats_bytes(...) bytes, 16-byte aligned; fully overwritten
+ *
+ * kp_trace_reduce reads the 64-byte trace header back from the device to learn the geometry:
+ * it synchronises `stream` once before it enqueues the kernels.  kp_trace_reduce_hdr takes
+ * the geometry from a HOST copy of the header instead and never synchronises; if the device
+ * header disagrees, no statistics are produced and kp_stats_hdr.status is set to 1.
+ *
+ * Limits: waves_per_wg <= 16, n_regions <= 32, cap_wave a power of two >= 2, and one
+ * workgroup's records must fit the decoder's LDS staging (waves_per_wg * cap_wave <= 16384,
+ * less for n_regions > 16): otherwise KP_ERR_UNSUPPORTED_SHAPE.  Header/`n` mismatch:
+ * KP_ERR_BAD_TRACE.
+ */
+kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats, void* stream);
+kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                              void* out_stats, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KPERF_H */

@@ -1,0 +1,126 @@
+"""GPU decoder (kp_trace_reduce, through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+from inputs import PHASE_END as E
+from inputs import PHASE_START as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kp():
+    import paper_2505_21661_amd as kp
+
+    return kp
+
+
+def check(raw, oracle_mod, use_hdr=False, threads=8):
+    from tests.gpu_util import assert_stats_equal, gpu_decode_bytes
+
+    want = oracle_mod.decode_bytes(raw, threads)
+    got = gpu_decode_bytes(raw, use_hdr=use_hdr)
+    assert_stats_equal(want, got, oracle_mod)
+
+
+def test_hand_patterns(kp, oracle_mod):
+    cases = [
+        ([[(S, 0, 10), (E, 0, 30), (S, 1, 40), (E, 1, 100)]], 2, 16),
+        ([[(S, 0, 10), (S, 1, 20), (E, 1, 50), (E, 0, 90)]], 2, 16),
+        ([[(S, 0, 0), (E, 0, 5), (S, 0, 8), (E, 0, 16), (S, 0, 20), (E, 0, 21)]], 1, 16),
+        ([[(S, 0, 0), (E, 0, 10)], [(S, 1, 5), (S, 0, 12), (E, 1, 15), (E, 0, 20)]], 2, 16),
+        ([[(S, 0, 0), (E, 0, 10)], [(S, 0, 5), (E, 0, 15)]], 1, 16),
+        ([[(S, 0, 0), (E, 0, 10), (S, 1, 20), (E, 1, 30), (S, 0, 40), (E, 0, 50), (S, 1, 60)]], 2, 4),
+        ([[(S, 0, 0), (S, 0, 7), (E, 0, 10), (E, 0, 30)]], 1, 16),
+        ([[], []], 2, 8),
+        # equal timestamps across waves and inside a wave
+        ([[(S, 0, 5), (E, 0, 5), (S, 1, 5), (E, 1, 9)], [(S, 1, 5), (E, 1, 9), (S, 0, 9), (E, 0, 9)],
+          [(S, 0, 5), (S, 1, 5), (E, 0, 9), (E, 1, 9)]], 2, 8),
+    ]
+    for evs, R, cap in cases:
+        for flush in (False, True):
+            wg = inputs.events_to_wg(evs, cap, flush=flush)
+            raw = inputs.encode_trace([wg], len(evs), R, cap, rec_cost=1, flush=flush)
+            check(raw, oracle_mod)
+            check(raw, oracle_mod, use_hdr=True)
+
+
+def test_clock_wrap_and_span_overflow(kp, oracle_mod):
+    wg = inputs.events_to_wg([[(S, 0, 0xFFFFFFF0), (E, 0, 0x10)]], 8, t_end=1000 + (1 << 32) + 100)
+    check(inputs.encode_trace([wg], 1, 1, 8), oracle_mod)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_messy_traces(kp, oracle_mod, seed):
+    waves = [1, 2, 3, 4, 7, 8, 16][seed % 7]
+    n_regions = [1, 3, 5, 16, 17, 32][seed % 6]
+    cap = [2, 8, 16, 64, 256][seed % 5]
+    raw = inputs.messy_trace(1000 + seed, n_wg=9, waves=waves, n_regions=n_regions, cap_wave=cap,
+                             p_bad=0.03 if seed % 3 else 0.0, allow_nonmono=bool(seed % 2),
+                             flush=(seed % 4 == 3))
+    check(raw, oracle_mod, use_hdr=bool(seed & 1))
+
+
+def test_small_gemm_shape_trace(kp, oracle_mod):
+    raw, _ = inputs.gen_trace(inputs.spec_small_gemm_shape())
+    check(raw, oracle_mod)
+
+
+@pytest.mark.parametrize("log2n,wrap", [(17, False), (20, False), (20, True), (22, False)])
+def test_decode_workload_scaled(kp, oracle_mod, log2n, wrap):
+    raw, _ = inputs.gen_trace(inputs.spec_decode_standalone(log2n, wrap=wrap))
+    check(raw, oracle_mod, use_hdr=True)
+
+
+@pytest.mark.parametrize("W,R,cap,total", [(4, 5, 1024, 1500), (8, 20, 1024, 1024), (16, 16, 1024, 700),
+                                             (2, 32, 4096, 4096), (5, 3, 512, 512), (1, 2, 16384, 20000)])
+def test_other_geometries(kp, oracle_mod, W, R, cap, total):
+    spec = inputs.TraceSpec(n_wg=37, waves=W, n_regions=R, cap_wave=cap, total_per_wave=total, total_var=total // 3,
+                            seed=W * 100 + R, dist="lognormal", p0=5.0, p1=1.2, p_orphan=0.03, p_swap=0.002)
+    raw, _ = inputs.gen_trace(spec)
+    check(raw, oracle_mod)
+
+
+def test_empty_trace(kp, oracle_mod):
+    check(inputs.encode_trace([], 4, 3, 8), oracle_mod)
+
+
+def test_errors(kp):
+    raw, _ = inputs.gen_trace(inputs.spec_small_gemm_shape())
+    n_wg, W, R, cap = (int(x) for x in raw[2:6])
+    dev = torch.from_numpy(raw.view(np.int32)).cuda()
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, W, R), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_trace_reduce(dev, n_wg * W * cap + 1, out)
+    assert e.value.status == kp.KP_ERR_BAD_TRACE
+    bad = raw.copy(); bad[0] ^= 4
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_trace_reduce(torch.from_numpy(bad.view(np.int32)).cuda(), n_wg * W * cap, out)
+    assert e.value.status == kp.KP_ERR_BAD_TRACE
+    # too many records per workgroup for the LDS staging
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_trace_reduce_hdr(dev, 16 * 2048, kp.make_hdr(1, 16, 4, 2048), out)
+    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, 40, cap), out)
+    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+    # host header that disagrees with the device header: flagged in the stats block, no statistics
+    kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, R + 1, cap),
+                           torch.zeros(kp.kp_stats_bytes(n_wg, W, R + 1), dtype=torch.uint8, device="cuda"))
+    st_buf = torch.zeros(kp.kp_stats_bytes(n_wg, W, R + 1), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, R + 1, cap), st_buf)
+    torch.cuda.synchronize()
+    st = kp.parse_stats(st_buf)
+    assert st["status"] == 1 and st["n_pairs"] == 0
+
+
+def test_repeated_calls_are_deterministic(kp, oracle_mod):
+    from tests.gpu_util import gpu_decode_bytes
+
+    raw, _ = inputs.gen_trace(inputs.spec_decode_standalone(19))
+    dev = torch.from_numpy(raw.view(np.int32)).cuda()
+    first = gpu_decode_bytes(raw, dev_raw=dev)
+    for _ in range(3):
+        assert np.array_equal(first, gpu_decode_bytes(raw, use_hdr=True, dev_raw=dev))
