@@ -19,13 +19,14 @@
 // Decoder workgroups are persistent; totals live in LDS and reach HBM once per workgroup.
 #include "kp_common.h"
 
+#include <cstdlib>
+
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kMRegion = 0x1Fu, kMEnd = 0x20u, kMValid = 0x40u, kMPaired = 0x80u;
-constexpr int kMaxChunk = 16;
 constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
 
@@ -57,8 +58,16 @@ struct DecodeParams {
   const u32x4* records;     // two records per 16-byte load
   uint64_t* out;
   uint32_t n_wg, W, R, cap, cap_log2, rec_cost, flush;
-  uint32_t nrec, chunk, ncell;
+  uint32_t nrec, span, ncell;
+  uint32_t dbg;
 };
+#ifdef KP_DBG
+#define KP_SKIP(bit) (p.dbg & (bit))
+#define KP_TICK(i) do { if (tid == 0) { unsigned long long now_ = __builtin_readcyclecounter(); dbg_acc[i] += now_ - dbg_last; dbg_last = now_; } } while (0)
+#else
+#define KP_SKIP(bit) false
+#define KP_TICK(i) do {} while (0)
+#endif
 
 struct LdsLayout {  // byte offsets
   uint32_t ts, om, grid, hist, oacc, reg_sum, reg_max, reg_min, pw_pack, pw_max, pw_min, ctr, tmp,
@@ -142,6 +151,79 @@ __global__ void kp_reduce_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uin
 }
 
 // ------------------------------------------------------------------------------------------
+// Overlap sweep.  One lane owns one time cell and merges the W per-wave record runs that fall
+// into it in the total order (clock, wave, rank), carrying every wave's open-region mask.  When
+// a paired record switches its region on or off for the whole workgroup (no other wave has it
+// open), -t or +t goes to the region-pair accumulators of all regions active at that instant:
+// the integral of A_a(t)*A_b(t) collapses to a signed sum over its switching times.
+template <int WMAX, typename MaskT>
+__device__ __forceinline__ void sweep_cells(const uint32_t* ts, const MaskT* om, const uint16_t* grid,
+                                            const uint32_t* sV, unsigned long long* oacc, uint32_t W,
+                                            uint32_t R, uint32_t cl2, uint32_t nrec, uint32_t ncell,
+                                            uint32_t shift, uint32_t tid, uint32_t nthreads) {
+  const uint32_t capm = (1u << cl2) - 1u;
+  for (uint32_t c = tid; c < ncell; c += nthreads) {
+    unsigned long long key[WMAX];  // (clock << 32) | position of each wave's next record; ~0 = none
+    uint32_t msk[WMAX];            // regions each wave has open right now
+    uint32_t n = 0;
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+      key[w] = ~0ull; msk[w] = 0u;
+      if ((uint32_t)w < W) {
+        const uint32_t V = sV[w];
+        const uint32_t g0 = grid[w * ncell + c];
+        const uint32_t g1r = grid[w * ncell + (c + 1 < ncell ? c + 1 : c)];
+        const uint32_t g1 = (c + 1 < ncell) ? g1r : V;
+        const uint32_t i0 = ((uint32_t)w << cl2) + g0;
+        const uint32_t ic = i0 < nrec ? i0 : nrec - 1;
+        const uint32_t m = om[ic], t = ts[ic];
+        msk[w] = g0 < V ? m : 0u;
+        key[w] = g0 < g1 ? (((unsigned long long)t << 32) | i0) : ~0ull;
+        n += g1 - g0;
+      }
+    }
+    for (; n; --n) {
+      unsigned long long best = key[0];
+#pragma unroll
+      for (int w = 1; w < WMAX; ++w) best = key[w] < best ? key[w] : best;
+      const uint32_t idx = (uint32_t)best, tt = (uint32_t)(best >> 32);
+      const uint32_t b = idx >> cl2, pos = idx & capm, V = sV[b];
+      const uint32_t inx = idx + 1 < nrec ? idx + 1 : idx;
+      const uint32_t before = om[idx];
+      const uint32_t nm = om[inx], nts = ts[inx];
+      const bool more = pos + 1 < V;
+      const uint32_t after = more ? nm : 0u;
+      const uint32_t nc0 = nts >> shift;
+      const uint32_t ncl = nc0 < ncell ? nc0 : ncell - 1;
+      const unsigned long long nkey = (more && ncl == c) ? (((unsigned long long)nts << 32) | (idx + 1)) : ~0ull;
+      uint32_t others = 0;
+#pragma unroll
+      for (int w = 0; w < WMAX; ++w) {
+        const bool sel = (uint32_t)w == b;
+        others |= sel ? 0u : msk[w];
+        msk[w] = sel ? after : msk[w];
+        key[w] = sel ? nkey : key[w];
+      }
+      const uint32_t x = before ^ after;  // the region bit this record toggles; 0 if unpaired
+      if (x && !(others & x)) {
+        const uint32_t a = __ffs(x) - 1;
+        const unsigned long long val = (before & x) ? (unsigned long long)tt : (0ull - (unsigned long long)tt);
+        atomicAdd(&oacc[a * R + a], val);
+        uint32_t set = (others | before) & ~x;
+        while (set) {
+          const uint32_t bb = __ffs(set) - 1;
+          set &= set - 1;
+          atomicAdd(&oacc[a * R + bb], val);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Position p = wave*cap_wave + rank indexes the LDS arrays.  Every hardware wave of the decoder
+// owns `span` consecutive positions and walks them 64 at a time, lane l taking position
+// base + 64*round + l, so that neighbouring lanes touch neighbouring LDS words.
 template <typename MaskT, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -163,9 +245,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* sFirst = reinterpret_cast<uint32_t*>(smem + L.first);
   uint32_t* wave_tot = reinterpret_cast<uint32_t*>(smem + L.wave_tot);
 
-  const uint32_t tid = threadIdx.x;
-  const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec, CH = p.chunk, ncell = p.ncell;
-  const uint32_t capm = cap - 1;
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, hw = tid >> 6;
+  const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec, ncell = p.ncell;
+  const uint32_t capm = cap - 1, cl2 = p.cap_log2;
+  const uint32_t span = p.span;              // positions per hardware wave, power of two >= 64
+  const uint32_t pbase = hw * span;
+  const uint32_t pend = pbase + span < nrec ? pbase + span : nrec;  // may be <= pbase: idle wave
   const StatsLayout SL = stats_layout(p.n_wg, W, R);
   if (p.out[H_STATUS] != 0) return;  // device header did not match the launch geometry
 
@@ -174,19 +259,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   for (uint32_t i = tid; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
   for (uint32_t i = tid; i < W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
   if (tid < 16) ctr[tid] = 0;
-
-  // this thread's chunk of consecutive ranks (all inside one wave segment)
-  const uint32_t nchunks = nrec / CH;
-  const bool has_chunk = tid < nchunks;
-  const uint32_t cbase = tid * CH;               // flat position of the chunk
-  const uint32_t cw = has_chunk ? (cbase >> p.cap_log2) : 0;  // its wave
-  const uint32_t ck = cbase & capm;              // rank of its first element
-  const uint32_t wofs = cw * cap;
-  const uint32_t tps = cap / CH;                 // threads per wave segment (power of two)
   __syncthreads();
 
+#ifdef KP_DBG
+  unsigned long long dbg_acc[12] = {0}; unsigned long long dbg_last = __builtin_readcyclecounter();
+#endif
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
+    KP_TICK(0);
     // ---- workgroup header -----------------------------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
@@ -196,46 +276,64 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       atomicAdd(&ctr[H_DROPPED], (unsigned long long)(T - V));
       atomicAdd(&ctr[H_SLOTS_VALID], (unsigned long long)V);
     }
-    if (tid < T_COUNT) tmp[tid] = 0;
+    if (tid >= 64 && tid < 64 + T_COUNT) tmp[tid - 64] = 0;
     if (tid == 32) {
       const uint64_t tb = (uint64_t)wh[2] | ((uint64_t)wh[3] << 32);
       const uint64_t te = (uint64_t)wh[4] | ((uint64_t)wh[5] << 32);
-      const uint64_t span = te - tb;
-      uint32_t shift = 0;
-      if (span >> 32) {
-        tmp[T_SPANOVF] = 1;
-      } else {
-        while ((span >> shift) >= ncell) ++shift;
-      }
-      tmp[T_SHIFT] = shift;
+      const uint64_t sp = te - tb;
+      uint32_t shift = 0, ovf = 0;
+      if (sp >> 32) ovf = 1; else while ((sp >> shift) >= ncell) ++shift;
+      wave_tot[0] = ovf;  // parked here until tmp[] has been cleared
+      wave_tot[1] = shift;
     }
-    for (uint32_t i = tid; i < nrec; i += BLOCK) om[i] = 0;
+    {
+      u32x4* z = reinterpret_cast<u32x4*>(om);
+      const uint32_t nz = (nrec * (uint32_t)sizeof(MaskT) + 15u) / 16u;
+      for (uint32_t i = tid; i < nz; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
+    }
     __syncthreads();
+    // table default: "no record of this wave at or after this cell" (ncell is even)
+    for (uint32_t i = tid; i < W * ncell / 2; i += BLOCK) {
+      const uint32_t V = sV[(2 * i) / ncell];
+      reinterpret_cast<uint32_t*>(grid)[i] = V | (V << 16);
+    }
+    if (tid == 0) { tmp[T_SPANOVF] = wave_tot[0]; tmp[T_SHIFT] = wave_tot[1]; }
 
+    KP_TICK(1);
     // ---- A: load and scatter by rank ------------------------------------------------------
     {
       const u32x4* rec = p.records + (size_t)wg * (nrec / 2);
+      const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
       uint32_t c_invalid = 0, c_field = 0, c_dis = 0;
-      for (uint32_t i = tid; i < nrec / 2; i += BLOCK) {
-        const u32x4 v = __builtin_nontemporal_load(rec + i);
-        const uint32_t f0 = 2 * i;
-        const uint32_t w = f0 >> p.cap_log2;
-        const uint32_t V = sV[w], first = sFirst[w];
+      for (uint32_t i0 = tid; i0 < n16; i0 += 4 * BLOCK) {
+        u32x4 v[4];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const uint32_t tag = h ? v.z : v.x, pay = h ? v.w : v.y;
-          const uint32_t s = (f0 + h) & capm;
-          if (s < V) {
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t i = i0 + u * BLOCK;
+          v[u] = __builtin_nontemporal_load(rec + (i < n16 ? i : i0));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t i = i0 + u * BLOCK;
+          const bool live = i < n16;
+          const uint32_t f0 = 2 * (live ? i : i0);
+          const uint32_t w = f0 >> cl2;
+          const uint32_t V = live ? sV[w] : 0u, first = sFirst[w];
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const uint32_t tag = h ? v[u].z : v[u].x, pay = h ? v[u].w : v[u].y;
+            const uint32_t s = (f0 + h) & capm;
             const uint32_t seq = tag & kSeqMask;
             const uint32_t k = (seq - first) & kSeqMask;
             const uint32_t region = (tag >> 24) & 0x7Fu;
-            if (k >= V || ((tag >> 20) & 0xFu) != w || region >= R) {
-              ++c_invalid;
-            } else {
-              ts[w * cap + k] = pay;
-              om[w * cap + k] = (MaskT)(region | ((tag >> 31) ? kMEnd : 0u) | kMValid);
-              ++c_field;
-              c_dis += (s != (seq & capm));
+            const bool held = s < V;
+            const bool good = held && k < V && ((tag >> 20) & 0xFu) == w && region < R;
+            c_invalid += (held && !good) ? 1u : 0u;
+            c_field += good ? 1u : 0u;
+            c_dis += (good && s != (seq & capm)) ? 1u : 0u;
+            if (good) {
+              ts[(w << cl2) + k] = pay;
+              om[(w << cl2) + k] = (MaskT)(region | ((tag >> 31) ? kMEnd : 0u) | kMValid);
             }
           }
         }
@@ -245,16 +343,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_DISORDER, c_dis);
     }
     __syncthreads();
-
+    KP_TICK(2);
     // ---- occupancy check: a duplicated seq leaves fewer occupied ranks than valid records ----
-    uint32_t m[kMaxChunk], t[kMaxChunk];
     {
       uint32_t occ = 0;
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        m[j] = 0; t[j] = 0;
-        if (has_chunk && (uint32_t)j < CH) { m[j] = om[cbase + j]; t[j] = ts[cbase + j]; occ += (m[j] & kMValid) ? 1u : 0u; }
-      }
+      for (uint32_t q = pbase + lane; q < pend; q += 64) occ += (om[q] & kMValid) ? 1u : 0u;
       add_tmp(tmp, T_OCCUPIED, occ);
     }
     __syncthreads();
@@ -287,159 +380,149 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         atomicAdd(&tmp[T_OCCUPIED], occ);
       }
       __syncthreads();
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j)
-        if (has_chunk && (uint32_t)j < CH) { m[j] = om[cbase + j]; t[j] = ts[cbase + j]; }
     }
 
+    KP_TICK(3);
     // ---- B: pairing, durations, per-(wave,region) statistics, monotonicity --------------------
+    // An END is paired iff the nearest earlier record of its (wave, region) is a START; every
+    // START that is not claimed this way is an orphan, so only ENDs have to search, and in
+    // traces of real kernels the START sits a few ranks back.  The four ranks just below are
+    // fetched unconditionally (clamped addresses); deeper searches are the rare slow path.
     {
-      uint32_t c_nonmono = 0, c_pairs = 0, c_os = 0;
-      const uint32_t V = has_chunk ? sV[cw] : 0;
+      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0;
+      for (uint32_t qb = pbase; qb < pend; qb += 64) {
+        const uint32_t q0 = (qb + lane < pend) ? qb + lane : pend - 1;
+        const uint32_t m0 = (qb + lane < pend) ? (uint32_t)om[q0] : 0u;
+        const uint32_t t0 = ts[q0];
+        const uint32_t w = q0 >> cl2, wofs = w << cl2, k = q0 & capm;
+        const bool valid = (m0 & kMValid) != 0;
+        const uint32_t region = m0 & kMRegion;
+        uint32_t mp[4], tp[4];
 #pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        if (!has_chunk || (uint32_t)j >= CH) continue;
-        const uint32_t k = ck + j;
-        if (k >= V || !(m[j] & kMValid)) continue;
-        // next record of this wave in rank order (ranks can be missing after invalid records)
-        uint32_t q = k + 1;
-        while (q < V && !(om[wofs + q] & kMValid)) ++q;
-        if (q < V && ts[wofs + q] < t[j]) ++c_nonmono;
-        if (!(m[j] & kMEnd)) {
-          const uint32_t region = m[j] & kMRegion;
-          bool paired = false;
-          for (; q < V; ++q) {
-            const uint32_t mq = om[wofs + q];
-            if (!(mq & kMValid) || (mq & kMRegion) != region) continue;
-            if (mq & kMEnd) {
-              paired = true;
-              om[wofs + q] = (MaskT)(mq | kMPaired);
-              const uint32_t d_raw = ts[wofs + q] - t[j];
-              const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
-              const uint32_t e = cw * R + region;
-              atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
-              atomicMax(&pw_max[e], d);
-              atomicMin(&pw_min[e], d);
-              atomicAdd(&hist[region * 64 + (d ? 31 - __clz(d) : 0)], 1u);
-            }
-            break;
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t back = k > (uint32_t)j ? (uint32_t)j + 1u : 0u;  // 0: no such rank, reads itself
+          const uint32_t mm = om[q0 - back];
+          tp[j] = ts[q0 - back];
+          mp[j] = back ? mm : 0u;
+        }
+        // previous record of this wave (ranks can be missing after invalid records)
+        uint32_t tprev = t0;
+        bool have_prev = false;
+#pragma unroll
+        for (int j = 3; j >= 0; --j) { const bool v = (mp[j] & kMValid) != 0; tprev = v ? tp[j] : tprev; have_prev |= v; }
+        // nearest earlier record of the same region
+        uint32_t pm = 0, pt = 0, pq = q0;
+        bool have = false;
+#pragma unroll
+        for (int j = 3; j >= 0; --j) {
+          const bool hit = (mp[j] & kMValid) && (mp[j] & kMRegion) == region;
+          pm = hit ? mp[j] : pm; pt = hit ? tp[j] : pt; pq = hit ? q0 - 1 - j : pq; have |= hit;
+        }
+        const bool is_end = valid && (m0 & kMEnd);
+        if (valid && k > 4 && (!have_prev || (is_end && !have))) {  // slow path: look further back
+          for (uint32_t kk = k - 4; kk-- > 0;) {
+            const uint32_t mq = om[wofs + kk];
+            if (!(mq & kMValid)) continue;
+            if (!have_prev) { have_prev = true; tprev = ts[wofs + kk]; }
+            if (!is_end || have) break;
+            if ((mq & kMRegion) == region) { have = true; pm = mq; pt = ts[wofs + kk]; pq = wofs + kk; break; }
           }
-          if (paired) { m[j] |= kMPaired; ++c_pairs; } else { ++c_os; }
+        }
+        c_nonmono += (valid && t0 < tprev) ? 1u : 0u;
+        c_starts += (valid && !(m0 & kMEnd)) ? 1u : 0u;
+        c_ends += is_end ? 1u : 0u;
+        if (is_end && have && !(pm & kMEnd)) {
+          ++c_pairs;
+          om[pq] = (MaskT)(pm | kMPaired);
+          om[q0] = (MaskT)(m0 | kMPaired);
+          const uint32_t d_raw = t0 - pt;
+          const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
+          const uint32_t e = w * R + region;
+          if (!KP_SKIP(1)) {
+          atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
+          atomicMax(&pw_max[e], d);
+          atomicMin(&pw_min[e], d);
+          atomicAdd(&hist[region * 64 + (d ? 31 - __clz(d) : 0)], 1u);
+          }
         }
       }
       add_tmp(tmp, T_NONMONO, c_nonmono);
       add_tmp(tmp, T_PAIRS, c_pairs);
-      add_tmp(tmp, T_ORPH_S, c_os);
+      add_tmp(tmp, T_ORPH_S, c_starts);  // turned into orphan counts once T_PAIRS is complete
+      add_tmp(tmp, T_ORPH_E, c_ends);
     }
     __syncthreads();
+    KP_TICK(4);
+    // ---- C1: XOR of the paired region bits of every span ---------------------------------------
     {
-      uint32_t c_oe = 0;
-      const uint32_t V = has_chunk ? sV[cw] : 0;
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        if (!has_chunk || (uint32_t)j >= CH || ck + j >= V) continue;
-        if ((m[j] & (kMValid | kMEnd)) == (kMValid | kMEnd)) {
-          m[j] = om[cbase + j];
-          c_oe += (m[j] & kMPaired) ? 0u : 1u;
-        }
+      uint32_t x = 0;
+      for (uint32_t q0 = pbase + lane; q0 < pend; q0 += 64) {
+        const uint32_t m0 = om[q0];
+        if (m0 & kMPaired) x ^= 1u << (m0 & kMRegion);
       }
-      add_tmp(tmp, T_ORPH_E, c_oe);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) x ^= __shfl_xor(x, d, 64);
+      if (lane == 0) wave_tot[hw] = x;
     }
-    __syncthreads();  // every thread is done reading metadata from `om`
+    __syncthreads();
 
+    KP_TICK(5);
     const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - tmp[T_OCCUPIED]);
     const bool eligible = !tmp[T_SPANOVF] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
 
-    if (eligible) {
-      const uint32_t V = has_chunk ? sV[cw] : 0;
-      // ---- C: open-region mask before every position (exclusive XOR scan per wave) ------------
-      uint32_t ex[kMaxChunk];
-      uint32_t x_tot = 0;
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        ex[j] = x_tot;
-        if ((uint32_t)j < CH && (m[j] & kMPaired)) x_tot ^= 1u << (m[j] & kMRegion);
-      }
-      uint32_t carry;
-      {
-        const uint32_t lane = tid & 63;
-        uint32_t v = x_tot;
-        if (tps <= 64) {
-          for (uint32_t d = 1; d < tps; d <<= 1) {
-            const uint32_t y = __shfl_up(v, d, 64);
-            if ((lane & (tps - 1)) >= d) v ^= y;
-          }
-          carry = v ^ x_tot;
-        } else {
-          for (uint32_t d = 1; d < 64; d <<= 1) {
-            const uint32_t y = __shfl_up(v, d, 64);
-            if (lane >= d) v ^= y;
-          }
-          if (lane == 63) wave_tot[tid >> 6] = v;
-          __syncthreads();
-          const uint32_t hw = tid >> 6, wps = tps >> 6, firsthw = hw & ~(wps - 1);
-          uint32_t c = 0;
-          for (uint32_t i = firsthw; i < hw; ++i) c ^= wave_tot[i];
-          carry = c ^ v ^ x_tot;
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        ex[j] ^= carry;
-        if (has_chunk && (uint32_t)j < CH) om[cbase + j] = (MaskT)ex[j];
-      }
-      // ---- D: coarse time -> position table -----------------------------------------------------
+    if (eligible && !KP_SKIP(2)) {
       const uint32_t shift = tmp[T_SHIFT];
-      if (has_chunk) {
-        uint16_t* g = grid + cw * ncell;
-        if (V == 0) {
-          if (ck == 0) for (uint32_t c = 0; c < ncell; ++c) g[c] = 0;
-        } else {
-          int32_t c_prev = -1;
-          if (ck > 0 && ck < V) { const uint32_t c0 = ts[cbase - 1] >> shift; c_prev = (int32_t)(c0 < ncell ? c0 : ncell - 1); }
+      // ---- C2: open-region mask before every position (exclusive XOR scan per wave) ------------
+      // ---- D : coarse time -> position table ------------------------------------------------------
+      {
+        uint32_t carry = 0;
+        if (span < cap) {  // this span continues a wave that started in an earlier span
+          const uint32_t firsthw = ((pbase >> cl2) << cl2) / span;
+          for (uint32_t i = firsthw; i < hw; ++i) carry ^= wave_tot[i];
+        }
+        for (uint32_t qb = pbase; qb < pend; qb += 64) {
+          const uint32_t q0 = qb + lane;
+          const bool in = q0 < pend;
+          const uint32_t m0 = in ? (uint32_t)om[q0] : 0u;
+          const uint32_t x = (m0 & kMPaired) ? (1u << (m0 & kMRegion)) : 0u;
+          uint32_t v = x;
+          if (cap >= 64) {
 #pragma unroll
-          for (int j = 0; j < kMaxChunk; ++j) {
-            if ((uint32_t)j >= CH || ck + j >= V) continue;
-            const uint32_t c0 = t[j] >> shift;
-            const int32_t c = (int32_t)(c0 < ncell ? c0 : ncell - 1);
-            for (int32_t cc = c_prev + 1; cc <= c; ++cc) g[cc] = (uint16_t)(ck + j);
-            c_prev = c;
-            if (ck + j == V - 1) for (uint32_t cc = c + 1; cc < ncell; ++cc) g[cc] = (uint16_t)V;
+            for (uint32_t d = 1; d < 64; d <<= 1) { const uint32_t y = __shfl_up(v, d, 64); if (lane >= d) v ^= y; }
+          } else {
+            for (uint32_t d = 1; d < cap; d <<= 1) { const uint32_t y = __shfl_up(v, d, 64); if ((lane & capm) >= d) v ^= y; }
           }
+          const uint32_t ex = v ^ x ^ carry;
+          if (cap >= 64) {
+            carry ^= __shfl(v, 63, 64);
+            if (((qb + 64) & capm) == 0) carry = 0;  // next round starts a new wave segment
+          }
+          // table entry: grid[w][c] = first rank of wave w whose clock falls in cell >= c
+          if (in) {
+            const uint32_t w = q0 >> cl2, k = q0 & capm, V = sV[w];
+            uint16_t* g = grid + w * ncell;
+            if (k < V) {
+              const uint32_t c0 = ts[q0] >> shift;
+              const int32_t c = (int32_t)(c0 < ncell ? c0 : ncell - 1);
+              int32_t c_prev = -1;
+              if (k > 0) { const uint32_t c1 = ts[q0 - 1] >> shift; c_prev = (int32_t)(c1 < ncell ? c1 : ncell - 1); }
+              for (int32_t cc = c_prev + 1; cc <= c; ++cc) g[cc] = (uint16_t)k;
+            }
+          }
+          if (in) om[q0] = (MaskT)ex;  // every lane has read its metadata by now (shuffles above)
         }
       }
       __syncthreads();
-      // ---- E: region-pair overlap from workgroup-level switching times ------------------------------
-#pragma unroll
-      for (int j = 0; j < kMaxChunk; ++j) {
-        if (!has_chunk || (uint32_t)j >= CH || !(m[j] & kMPaired)) continue;
-        const uint32_t tt = t[j];
-        const uint32_t a = m[j] & kMRegion;
-        const uint32_t c0 = tt >> shift;
-        const uint32_t cell = c0 < ncell ? c0 : ncell - 1;
-        uint32_t others = 0;
-        for (uint32_t w2 = 0; w2 < W; ++w2) {
-          if (w2 == cw) continue;
-          const uint32_t V2 = sV[w2];
-          uint32_t pos = grid[w2 * ncell + cell];
-          const uint32_t* ts2 = ts + w2 * cap;
-          if (w2 < cw) { while (pos < V2 && ts2[pos] <= tt) ++pos; }
-          else         { while (pos < V2 && ts2[pos] < tt) ++pos; }
-          if (pos < V2) others |= (uint32_t)om[w2 * cap + pos];
-        }
-        if (!((others >> a) & 1u)) {
-          const unsigned long long val = (m[j] & kMEnd) ? (unsigned long long)tt : (0ull - (unsigned long long)tt);
-          atomicAdd(&oacc[a * R + a], val);
-          uint32_t set = (others | ex[j]) & ~(1u << a);
-          while (set) {
-            const uint32_t b = __ffs(set) - 1;
-            set &= set - 1;
-            atomicAdd(&oacc[a * R + b], val);
-          }
-        }
+      KP_TICK(6);
+      // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
+      if (!KP_SKIP(8)) {
+        if (W <= 4)      sweep_cells<4, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
+        else             sweep_cells<16, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
       }
     }
     __syncthreads();
+    KP_TICK(7);
 
     // ---- F: per-(workgroup, wave, region) output, fold into running totals ------------------------
     for (uint32_t e = tid; e < W * R; e += BLOCK) {
@@ -463,13 +546,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_DISORDER] += tmp[T_DISORDER];
       ctr[H_NONMONO] += tmp[T_NONMONO];
       ctr[H_PAIRS] += tmp[T_PAIRS];
-      ctr[H_ORPHAN_START] += tmp[T_ORPH_S];
-      ctr[H_ORPHAN_END] += tmp[T_ORPH_E];
+      ctr[H_ORPHAN_START] += tmp[T_ORPH_S] - tmp[T_PAIRS];
+      ctr[H_ORPHAN_END] += tmp[T_ORPH_E] - tmp[T_PAIRS];
       ctr[H_SPAN_OVF] += tmp[T_SPANOVF];
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
     }
     __syncthreads();
+    KP_TICK(8);
   }
+#ifdef KP_DBG
+  if (tid == 0 && blockIdx.x == 7) printf("phase ticks: top %llu hdr %llu A %llu occ %llu B %llu C1 %llu C2D %llu E %llu F %llu\n", dbg_acc[0], dbg_acc[1], dbg_acc[2], dbg_acc[3], dbg_acc[4], dbg_acc[5], dbg_acc[6], dbg_acc[7], dbg_acc[8]);
+#endif
 
   // ---- flush this decoder workgroup's totals --------------------------------------------------
   unsigned long long* out = reinterpret_cast<unsigned long long*>(p.out);
@@ -487,24 +574,25 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   if (tid < H_STATUS && ctr[tid]) atomicAdd(&out[tid], ctr[tid]);
 }
 
-struct DeviceInfo { int cus = 0; };
-DeviceInfo& device_info() {
-  static thread_local DeviceInfo di;
-  return di;
-}
+// Launch shape of one kernel instantiation for one LDS size, queried once per device.
+struct LaunchCache { int dev = -1; uint32_t lds = 0; uint32_t max_grid = 0; };
 
 template <typename MaskT, int BLOCK>
 kp_status launch_main(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
   auto kern = kp_reduce_main<MaskT, BLOCK>;
-  KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-  int per_cu = 0;
-  KP_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, BLOCK, lds_bytes));
-  if (per_cu < 1) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder kernel does not fit one CU (LDS %u B)", lds_bytes);
-  int dev = 0, cus = 0;
+  static thread_local LaunchCache cache;
+  int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
-  KP_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  uint32_t grid = (uint32_t)per_cu * (uint32_t)cus;
+  if (cache.dev != dev || cache.lds != lds_bytes) {
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    int per_cu = 0, cus = 0;
+    KP_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, BLOCK, lds_bytes));
+    if (per_cu < 1) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder kernel does not fit one CU (LDS %u B)", lds_bytes);
+    KP_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    cache.dev = dev; cache.lds = lds_bytes; cache.max_grid = (uint32_t)per_cu * (uint32_t)cus;
+  }
+  uint32_t grid = cache.max_grid;
   if (grid > p.n_wg) grid = p.n_wg;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds_bytes, s, p);
   KP_HIP_TRY(hipGetLastError());
@@ -531,10 +619,9 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
 
   const uint32_t W = h.waves_per_wg, R = h.n_regions, cap = h.cap_wave;
   const int block = nrec >= 8192 ? 1024 : (nrec >= 2048 ? 512 : 256);
-  uint32_t chunk = 1;
-  while (chunk * (uint32_t)block < nrec) chunk <<= 1;
-  if (chunk > cap) chunk = cap;
-  if (chunk > (uint32_t)kMaxChunk) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "internal: chunk %u", chunk);
+  // positions per hardware wave of the decoder: a power of two >= 64 covering nrec
+  uint32_t span = 64;
+  while (span * (uint32_t)(block / 64) < nrec) span <<= 1;
   const uint32_t ncell = cap < 1024 ? cap : 1024;
   const uint32_t mask_bytes = R <= 16 ? 2 : 4;
   const LdsLayout L = lds_layout(nrec, W, R, ncell, mask_bytes, block);
@@ -558,7 +645,11 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     p.n_wg = h.n_wg; p.W = W; p.R = R; p.cap = cap;
     p.cap_log2 = 0; while ((1u << p.cap_log2) < cap) ++p.cap_log2;
     p.rec_cost = h.rec_cost; p.flush = h.flags & KP_FLAG_FLUSH;
-    p.nrec = nrec; p.chunk = chunk; p.ncell = ncell;
+    p.nrec = nrec; p.span = span; p.ncell = ncell;
+    p.dbg = 0;
+#ifdef KP_DBG
+    if (const char* e = getenv("KP_DBG")) p.dbg = (uint32_t)atoi(e);
+#endif
     kp_status st;
     if (mask_bytes == 2) {
       st = block == 1024 ? launch_main<uint16_t, 1024>(p, L.total, s)
