@@ -148,6 +148,55 @@ kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats, void* stre
 kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
                               void* out_stats, void* stream);
 
+/* ---- instrumented targets ---------------------------------------------------------------------
+ *
+ * region_mask: bit r (r < 31) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
+ * selects the flush strategy instead of the default circular one (Sec. 4.2: "Circular" keeps
+ * the newest records in LDS and copies them out once at kernel exit; "Flush" writes a full
+ * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..30 all zero
+ * launches the separately compiled uninstrumented kernel: no ring, no record sites; trace_buf
+ * may then be NULL.  Instrumented and uninstrumented kernels produce bit-identical outputs.
+ *
+ * trace_buf: device, kp_trace_bytes(n_wg, waves, trace_cap) bytes, 16-byte aligned; headers and
+ * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written
+ * hold unspecified bytes).  trace_cap: record slots per workgroup in HBM; trace_cap / waves must
+ * be a power of two >= 2, else KP_ERR_TRACE_TOO_SMALL.  Circular: the whole ring also lives in
+ * LDS (KP_ERR_UNSUPPORTED_SHAPE if it exceeds the kernel's LDS budget).
+ */
+#define KP_MASK_FLUSH 0x80000000u
+
+/* Launch geometry kp_gemm_instrumented will use for M x N x K: recorded workgroups, waves per
+ * workgroup, number of regions.  KP_ERR_UNSUPPORTED_SHAPE if no kernel covers the shape. */
+kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg, int* n_regions);
+
+/*
+ * C[M,N] = A[M,K] * B[K,N]; bf16 inputs, fp32 accumulation on MFMA, bf16 (round to nearest even)
+ * output; all three row-major, device memory, 16-byte aligned.  The paper instruments
+ * software-pipelined GEMMs stage by stage (Sec. 5.3 "Profiling Overhead", GEMM-SWP-2/3); the
+ * regions here are
+ *   M, N multiples of 256 and K of 64 (>= 2 K-steps): tile 256x256x64, 8 waves,
+ *       0 global-load issue, 1 load wait, 2 LDS write, 3 MFMA (each once per K-step), 4 epilogue
+ *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
+ *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
+ * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.
+ */
+kp_status kp_gemm_instrumented(const void* A, const void* B, void* C, int M, int N, int K,
+                               uint32_t region_mask, void* trace_buf, size_t trace_cap, void* stream);
+
+/*
+ * Timer calibration (Sec. 5.4 "Cycle-level Overhead": cost of one record; Sec. 4.3: that
+ * constant is subtracted at replay).  Launches n_wg workgroups of `waves` waves, one workgroup
+ * per CU at a time; every wave runs regions 0..n_regions-1 back to back, region r being
+ *   mode bit0 = 0: cycles[r]/4 dependent v_fma_f32 (rounded down to a multiple of 16 FMAs)
+ *   mode bit0 = 1: cycles[r]/64 executions of s_sleep 1
+ * bracketed by a START and an END record; cycles[r] = 0 gives an empty region whose duration is
+ * the cost of one record.  mode bit1 selects the flush strategy with an 8-slot LDS sub-ring.
+ *   cycles     HOST pointer to n_regions values (n_regions <= 32)
+ *   trace_buf  device, kp_trace_bytes(n_wg, waves, trace_cap) bytes; trace_cap as above
+ */
+kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_wg, int waves, int mode,
+                       void* trace_buf, size_t trace_cap, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

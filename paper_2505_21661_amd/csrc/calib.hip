@@ -1,0 +1,98 @@
+// Calibration kernel (kp_calibrate): regions of known length bracketed by records.
+//
+// The paper quantifies the cost of one record with a micro-benchmark (Sec. 5.4 "Cycle-level
+// Overhead") and compensates measured regions by that constant at replay (Sec. 4.3).  This
+// kernel provides both numbers for gfx950: every wave runs n_regions regions back to back,
+// region r being a chain of dependent v_fma_f32 (mode 0) or a run of s_sleep (mode 1) whose
+// length is given by the caller; a region of length 0 measures the bare cost of a START/END
+// record pair.  The decoded durations give ticks per FMA (timer unit) and the record cost.
+#include "kp_common.h"
+#include "kp_record.h"
+
+namespace {
+
+struct CalibArgs {
+  uint32_t cycles[KP_MAX_REGIONS];
+  uint32_t n_regions;
+  uint32_t mode;
+};
+
+// n dependent FMAs (rounded down to a multiple of 16); each waits for the previous result.
+__device__ __forceinline__ void busy_fma(uint32_t n, float& x) {
+  const float c = 1.0000001f;
+  for (uint32_t i = n >> 4; i; --i) {
+    asm volatile(
+        "v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n"
+        "v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n"
+        "v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n"
+        "v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n v_fma_f32 %0, %0, %1, %1\n"
+        : "+v"(x)
+        : "v"(c));
+  }
+}
+
+__device__ __forceinline__ void busy_sleep(uint32_t n) {
+  for (uint32_t i = n; i; --i) asm volatile("s_sleep 1");
+}
+
+__global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace, uint32_t cap_lds,
+                                                        uint32_t cap_hbm, uint32_t flush, uint32_t n_wg,
+                                                        uint32_t waves, float* sink) {
+  extern __shared__ __align__(16) uint32_t lds_ring[];  // ring first, the rest only limits occupancy
+  __shared__ uint64_t t_begin[2];
+  kp::Ring r = kp::ring_init(lds_ring, t_begin, cap_lds, 0xFFFFFFFFu, flush, cap_hbm, trace, n_wg, waves, blockIdx.x);
+  float x = (float)threadIdx.x;
+  // Two identical passes: the first warms the instruction cache and is then discarded by
+  // resetting the ring state, so that no recorded region pays for a cold code fetch.
+  for (int pass = 0; pass < 2; ++pass) {
+    r.cnt = 0;
+    r.pend_tag = kp::kNoPending;
+    for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
+      const uint32_t len = a.cycles[rg];
+      kp::record(r, rg, kp::kPhaseStart);
+      if (a.mode == 0) busy_fma(len >> 2, x); else busy_sleep(len >> 6);
+      kp::record(r, rg, kp::kPhaseEnd);
+    }
+    if (pass == 0 && r.pend_tag != kp::kNoPending) kp::store_pending(r);
+  }
+  if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
+  kp::TraceGeom g{n_wg, waves, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
+  kp::ring_finish(r, lds_ring, t_begin, cap_lds, trace, g, blockIdx.x, 0u);
+}
+
+}  // namespace
+
+extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_wg, int waves, int mode,
+                                  void* trace_buf, size_t trace_cap, void* stream) {
+  kp::clear_error();
+  if (!cycles || !trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
+  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~3))
+    return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
+  if (trace_cap % (size_t)waves) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of waves");
+  const size_t cap_wave = trace_cap / (size_t)waves;
+  if (!kp::is_pow2(cap_wave) || cap_wave < 2 || cap_wave > (1u << 19))
+    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/waves = %zu must be a power of two >= 2", cap_wave);
+  const uint32_t flush = (mode & 2) ? 1u : 0u;
+  // circular: the LDS sub-ring is the whole segment; flush: a small LDS sub-ring is spilled in chunks
+  uint32_t cap_lds = (uint32_t)cap_wave;
+  if (flush && cap_lds > 8) cap_lds = 8;
+  if ((size_t)cap_lds * 8 * waves > 64 * 1024)
+    return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "ring of %zu records per workgroup exceeds 64 KiB of LDS", trace_cap);
+  CalibArgs a{};
+  for (int i = 0; i < n_regions; ++i) a.cycles[i] = cycles[i];
+  a.n_regions = (uint32_t)n_regions;
+  a.mode = (uint32_t)(mode & 1);
+  // more than half of the CU's LDS per workgroup: one workgroup per CU, one wave per SIMD for waves <= 4
+  const uint32_t lds_bytes = 96 * 1024;
+  static thread_local bool attr_set = false;
+  if (!attr_set) {
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kp_calib_kernel, dim3(n_wg), dim3(waves * 64), lds_bytes, static_cast<hipStream_t>(stream),
+                     a, trace_buf, cap_lds, (uint32_t)cap_wave, flush, (uint32_t)n_wg, (uint32_t)waves,
+                     static_cast<float*>(nullptr));
+  KP_HIP_TRY(hipGetLastError());
+  return KP_OK;
+}

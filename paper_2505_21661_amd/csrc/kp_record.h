@@ -1,0 +1,160 @@
+// Device-side record path: ring init, record, flush (Sec. 3.1 InitOp / ReadCounterOp /
+// StoreCounterOp / FinalizeOp semantics; Sec. 4.2 record layout and circular buffer).
+//
+// Every wave owns a private sub-ring of cap_wave 8-byte slots inside the workgroup's LDS ring
+// (Sec. 4.2 "SM-level Data Layout": non-overlapping slots per profiling space), so recording
+// needs no atomics.  The record counter and all tag fields are wave-uniform and live in scalar
+// registers; the slot index is counter & (cap_wave-1) (Sec. 4.2: a cheap modular op with a
+// precomputed capacity).  A record site only samples s_memtime; the 8-byte store of a record
+// (one lane writes) is deferred to the next record site, after that site's own clock sample,
+// so neither the wait for the clock value nor the LDS write is charged to the region that a
+// START opens (the paper's split into ReadCounterOp and StoreCounterOp, Sec. 3.1).
+//
+// Circular strategy: the sub-ring is overwritten cyclically and copied to HBM once, at exit.
+// Flush strategy: whenever a sub-ring fills up, its wave copies it to the next chunk of its HBM
+// segment; records that no longer fit are counted as dropped (total_written - cap_wave).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kperf.h"
+
+namespace kp {
+
+constexpr uint32_t kPhaseStart = 0u, kPhaseEnd = 1u;
+constexpr uint32_t kNoPending = 0xFFFFFFFFu;
+
+struct Ring {
+  uint32_t* sub;       // LDS: this wave's sub-ring (2 dwords per slot)
+  uint32_t cnt;        // records written by this wave so far
+  uint32_t lds_mask;   // LDS sub-ring capacity - 1
+  uint32_t tag_wave;   // wave index << 20
+  uint32_t t0_lo;      // low 32 bits of the workgroup's t_begin
+  uint32_t mask;       // enabled regions
+  uint32_t pend_tag;   // record whose clock was sampled but which is not in LDS yet (kNoPending: none)
+  uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
+  // flush strategy only
+  uint32_t flush;      // 0 circular, 1 flush
+  uint32_t cap_hbm;    // slots of this wave's HBM segment
+  uint32_t* seg;       // HBM: this wave's segment
+};
+
+struct TraceGeom {
+  uint32_t n_wg, waves, n_regions, cap_wave, flags;
+};
+
+__device__ __forceinline__ uint32_t wave_uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Workgroup prologue.  `ring_lds` holds waves * cap_lds slots; t_begin_lds[2] receives the 64-bit
+// s_memtime and s_memrealtime at start (thread 0 samples them, everyone reads them after a barrier).
+__device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* t_begin_lds, uint32_t cap_lds,
+                                          uint32_t region_mask, uint32_t flush, uint32_t cap_hbm,
+                                          void* trace_buf, uint32_t n_wg, uint32_t waves, uint32_t wg) {
+  const uint32_t wave = wave_uniform(threadIdx.x >> 6);
+  if (threadIdx.x == 0) {
+    t_begin_lds[0] = __builtin_readcyclecounter();
+    t_begin_lds[1] = __builtin_amdgcn_s_memrealtime();
+  }
+  __syncthreads();
+  Ring r;
+  r.sub = ring_lds + (size_t)wave * cap_lds * 2;
+  r.cnt = 0;
+  r.lds_mask = cap_lds - 1;
+  r.tag_wave = wave << 20;
+  r.t0_lo = wave_uniform((uint32_t)*t_begin_lds);
+  r.mask = region_mask;
+  r.pend_tag = kNoPending;
+  r.pend_t = 0;
+  r.flush = flush;
+  r.cap_hbm = cap_hbm;
+  r.seg = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(trace_buf) + sizeof(kp_trace_hdr) +
+                                      sizeof(kp_wg_hdr) * (size_t)n_wg) +
+          ((size_t)wg * waves + wave) * cap_hbm * 2;
+  return r;
+}
+
+// Copy `n` slots of a wave's LDS sub-ring to HBM, 16 bytes per lane (n even or the tail lane copies 8).
+__device__ __forceinline__ void wave_copy_slots(const uint32_t* src, uint32_t* dst, uint32_t n) {
+  const uint32_t lane = threadIdx.x & 63u;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  for (uint32_t i = lane * 2; i < n; i += 128) {
+    if (i + 1 < n) {
+      *reinterpret_cast<u32x4*>(dst + 2 * i) = *reinterpret_cast<const u32x4*>(src + 2 * i);
+    } else {
+      *reinterpret_cast<u32x2*>(dst + 2 * i) = *reinterpret_cast<const u32x2*>(src + 2 * i);
+    }
+  }
+}
+
+// Put the pending record into the wave's LDS sub-ring (lane 0 only writes).
+__device__ __forceinline__ void store_pending(Ring& r) {
+  const uint32_t slot = r.pend_tag & r.lds_mask;  // seq sits in the low tag bits
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 rec;
+  rec.x = r.pend_tag;
+  rec.y = (uint32_t)r.pend_t - r.t0_lo;
+  if ((threadIdx.x & 63u) == 0u) *reinterpret_cast<u32x2*>(r.sub + 2 * slot) = rec;
+  // here r.cnt counts the records up to and including the one just stored
+  if (r.flush && (r.cnt & r.lds_mask) == 0u) {
+    // sub-ring just filled up: move it to the next chunk of the HBM segment if it still fits
+    if (r.cnt <= r.cap_hbm) wave_copy_slots(r.sub, r.seg + (size_t)(r.cnt - (r.lds_mask + 1u)) * 2, r.lds_mask + 1u);
+  }
+  r.pend_tag = kNoPending;
+}
+
+// One record.  `region` and `phase` are compile-time constants at every call site.
+// Split as in the paper's ReadCounterOp / StoreCounterOp (Sec. 3.1): the clock is sampled here,
+// but its store is deferred to the next record site, after that site has sampled its own clock.
+// The wait for s_memtime and the LDS write therefore fall outside the region a START opens.
+__device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase) {
+  if (!((r.mask >> region) & 1u)) return;  // scalar test, uniform branch
+  __builtin_amdgcn_sched_barrier(0);
+  const uint64_t now = __builtin_readcyclecounter();  // s_memtime
+  if (r.pend_tag != kNoPending) store_pending(r);
+  r.pend_tag = (phase << 31) | (region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu);
+  r.pend_t = now;
+  r.cnt += 1;
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
+__device__ __forceinline__ void ring_finish(Ring& r, uint32_t* ring_lds, const uint64_t* t_begin_lds,
+                                            uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
+                                            uint32_t rec_cost) {
+  const uint64_t t_end = __builtin_readcyclecounter();
+  const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
+  if (r.pend_tag != kNoPending) store_pending(r);
+  unsigned char* base = static_cast<unsigned char*>(trace_buf);
+  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+  if (r.flush) {
+    const uint32_t tail = r.cnt & r.lds_mask;           // records not yet copied
+    const uint32_t done = r.cnt - tail;
+    if (tail && done < r.cap_hbm) {
+      const uint32_t room = r.cap_hbm - done;
+      wave_copy_slots(r.sub, r.seg + (size_t)done * 2, tail < room ? tail : room);
+    }
+  } else {
+    wave_copy_slots(r.sub, r.seg, cap_lds);  // whole sub-ring; the decoder ignores slots >= total
+  }
+  kp_wg_hdr* wh = reinterpret_cast<kp_wg_hdr*>(base + sizeof(kp_trace_hdr)) + wg;
+  if (lane == 0) wh->total_written[wave] = r.cnt;
+  if (threadIdx.x == 0) {
+    wh->wg_id = wg;
+    wh->hw_id = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (11 << 11));  // HW_ID, low 12 bits
+    wh->t_begin = t_begin_lds[0];
+    wh->t_end = t_end;
+    wh->reserved = rt_end - t_begin_lds[1];  // constant-rate (s_memrealtime) ticks over the same span
+    for (uint32_t w = g.waves; w < KP_MAX_WAVES; ++w) wh->total_written[w] = 0;
+    for (int i = 0; i < 8; ++i) wh->pad[i] = 0;
+    if (wg == 0) {
+      kp_trace_hdr* h = reinterpret_cast<kp_trace_hdr*>(base);
+      h->magic = KP_TRACE_MAGIC; h->version = KP_TRACE_VERSION;
+      h->n_wg = g.n_wg; h->waves_per_wg = g.waves; h->n_regions = g.n_regions;
+      h->cap_wave = g.cap_wave; h->rec_cost = rec_cost; h->flags = g.flags;
+      for (int i = 0; i < 8; ++i) h->pad[i] = 0;
+    }
+  }
+}
+
+}  // namespace kp

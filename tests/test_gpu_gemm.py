@@ -1,0 +1,149 @@
+"""Instrumented bf16 GEMM through the C ABI: outputs against the fp64 oracle and against the
+uninstrumented kernel (bitwise), traces against closed forms, the CPU decoder oracle and timer
+invariants."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+from oracle import bf16_round, ref_gemm
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kp():
+    import paper_2505_21661_amd as kp
+
+    return kp
+
+
+def run_gemm(kp, a, b, mask, trace_cap=None):
+    M, K = a.shape
+    N = b.shape[1]
+    A, B = a.cuda(), b.cuda()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    n_wg, waves, n_regions = kp.kp_gemm_launch_shape(M, N, K)
+    trace = None
+    if mask & 0x7FFFFFFF:
+        trace = torch.full((kp.kp_trace_bytes(n_wg, waves, trace_cap),), 0x77, dtype=torch.uint8, device="cuda")
+    kp.kp_gemm_instrumented(A, B, C, M, N, K, mask, trace, trace_cap or 0)
+    torch.cuda.synchronize()
+    return C, trace, (n_wg, waves, n_regions)
+
+
+def assert_close_to_oracle(C, a, b, rows=None):
+    """|gpu - ref| <= 1e-2*|ref| + 1e-2*rms(ref) per element and 1e-2 relative in Frobenius norm
+    (bf16 inputs, fp32 accumulation, bf16 output against the fp64 definition)."""
+    ref = ref_gemm(a, b, rows=rows)
+    got = C.float().cpu().numpy().astype(np.float64)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    rms = np.sqrt(np.mean(ref ** 2))
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-2 * np.abs(ref) + 1e-2 * rms), float(err.max())
+    assert np.linalg.norm(got - ref) <= 1e-2 * np.linalg.norm(ref)
+    # tighter sanity: the only rounding beyond fp32 accumulation is the final bf16 rounding
+    assert np.linalg.norm(got - bf16_round(ref)) <= 2e-3 * np.linalg.norm(ref)
+
+
+def test_small_gemm_matches_oracle_and_vanilla(kp):
+    a, b = inputs.gemm_inputs(256, 256, 256, seed=0, dist="uniform")
+    c_van, _, shape = run_gemm(kp, a, b, 0)
+    assert shape == (16, 4, 3)
+    assert_close_to_oracle(c_van, a, b)
+    c_ins, trace, _ = run_gemm(kp, a, b, 0b111, trace_cap=512)
+    assert torch.equal(c_ins.view(torch.int16), c_van.view(torch.int16))  # bit-identical
+    for mask in (0b001, 0b100, 0b110):
+        c2, _, _ = run_gemm(kp, a, b, mask, trace_cap=512)
+        assert torch.equal(c2.view(torch.int16), c_van.view(torch.int16))
+
+
+def test_exact_special_cases(kp):
+    _, b = inputs.gemm_inputs(128, 192, 128, seed=5)
+    eye = torch.eye(128, dtype=torch.bfloat16)
+    c, _, _ = run_gemm(kp, eye, b, 0b111, trace_cap=512)
+    assert torch.equal(c.cpu().view(torch.int16), b.view(torch.int16))       # A = I  =>  C = B exactly
+    ones_a = torch.ones(64, 256, dtype=torch.bfloat16)
+    ones_b = torch.ones(256, 64, dtype=torch.bfloat16)
+    c, _, _ = run_gemm(kp, ones_a, ones_b, 0)
+    assert (c.float() == 256.0).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 32), (128, 320, 96), (192, 64, 608), (320, 448, 160)])
+def test_other_shapes(kp, M, N, K):
+    a, b = inputs.gemm_inputs(M, N, K, seed=M + N + K)
+    c, _, _ = run_gemm(kp, a, b, 0b111, trace_cap=1024)
+    assert_close_to_oracle(c, a, b)
+    c0, _, _ = run_gemm(kp, a, b, 0)
+    assert torch.equal(c.view(torch.int16), c0.view(torch.int16))
+
+
+def test_small_gemm_trace(kp, oracle_mod):
+    from tests.gpu_util import assert_stats_equal
+
+    a, b = inputs.gemm_inputs(256, 256, 256, seed=0, dist="uniform")
+    _, trace, (n_wg, waves, R) = run_gemm(kp, a, b, 0b111, trace_cap=512)
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[:8]) == (0x4652504B, 1, n_wg, waves, R, 128, 0, 0)
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * 128, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), got, oracle_mod)
+    st = kp.parse_stats(got)
+    # closed form: 8 K-steps x 3 regions x 2 records per wave
+    k_steps = 256 // 32
+    assert st["n_slots_valid"] == n_wg * waves * 3 * 2 * k_steps
+    assert st["n_pairs"] == n_wg * waves * 3 * k_steps and (st["per"]["n"] == k_steps).all()
+    for k in ("n_orphan_start", "n_orphan_end", "n_invalid", "n_dropped", "n_disorder", "n_nonmonotonic",
+              "n_span_overflow_wgs"):
+        assert st[k] == 0, k
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    span = ((hdr[:, 4].astype(np.uint64) | (hdr[:, 5].astype(np.uint64) << np.uint64(32)))
+            - (hdr[:, 2].astype(np.uint64) | (hdr[:, 3].astype(np.uint64) << np.uint64(32)))).astype(np.int64)
+    # regions of one wave are disjoint: their total time fits in the workgroup span
+    assert (st["per"]["sum"].sum(axis=2).astype(np.int64) <= span[:, None]).all()
+    assert (st["U"].astype(np.int64) <= span.sum()).all()
+    # masked-off regions leave no records
+    _, trace2, _ = run_gemm(kp, a, b, 0b101, trace_cap=512)
+    out2 = torch.zeros_like(out)
+    kp.kp_trace_reduce(trace2, n_wg * waves * 128, out2)
+    torch.cuda.synchronize()
+    st2 = kp.parse_stats(out2)
+    assert st2["cnt"].tolist() == [n_wg * waves * k_steps, 0, n_wg * waves * k_steps]
+
+
+def test_gemm_ring_wrap_and_flush(kp, oracle_mod):
+    from tests.gpu_util import assert_stats_equal
+
+    a, b = inputs.gemm_inputs(128, 128, 512, seed=9)       # 16 K-steps -> 96 records per wave
+    for mask, cap_wave, dropped in ((0b111, 64, 32), (0b111 | (1 << 31), 128, 0), (0b111 | (1 << 31), 64, 32)):
+        c, trace, (n_wg, waves, R) = run_gemm(kp, a, b, mask, trace_cap=cap_wave * 4)
+        raw = trace.cpu().numpy().view(np.uint32).copy()
+        out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+        kp.kp_trace_reduce(trace, n_wg * waves * cap_wave, out)
+        torch.cuda.synchronize()
+        assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+        st = kp.parse_stats(out)
+        assert st["n_dropped"] == dropped * n_wg * waves, (mask, cap_wave)
+        assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0
+        assert_close_to_oracle(c, a, b)
+
+
+def test_gemm_errors(kp):
+    a = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(64, 64, dtype=torch.bfloat16, device="cuda")
+    tr = torch.zeros(kp.kp_trace_bytes(1, 4, 512), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_gemm_instrumented(a, a, c, 60, 64, 64, 0, None, 0)
+    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_gemm_instrumented(a, a, c, 64, 64, 64, 7, tr, 500)
+    assert e.value.status == kp.KP_ERR_TRACE_TOO_SMALL
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_gemm_instrumented(a, a, c, 64, 64, 64, 7, None, 512)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_gemm_instrumented(a, a, c, 64, 64, 64, 0b1000, tr, 512)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG

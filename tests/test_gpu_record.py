@@ -1,0 +1,141 @@
+"""Record path on the GPU (ring init, record, flush) through the calibration kernel: real traces
+are decoded by the GPU decoder and by the CPU oracle (bit-exact), and checked against closed
+forms and timer invariants."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+CYCLES = [0, 256, 1024, 4096, 16384]
+
+
+def run_calibrate(kp, cycles, n_wg, waves, mode, trace_cap):
+    buf = torch.full((kp.kp_trace_bytes(n_wg, waves, trace_cap),), 0x5A, dtype=torch.uint8, device="cuda")
+    kp.kp_calibrate(cycles, n_wg, waves, mode, buf, trace_cap)
+    torch.cuda.synchronize()
+    raw = buf.cpu().numpy().view(np.uint32).copy()
+    return buf, raw
+
+
+def decode_both(kp, oracle_mod, buf, raw):
+    from tests.gpu_util import assert_stats_equal
+
+    n_wg, W, R, cap = (int(x) for x in raw[2:6])
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, W, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(buf, n_wg * W * cap, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = oracle_mod.decode_bytes(raw, 8)
+    assert_stats_equal(want, got, oracle_mod)
+    return kp.parse_stats(got)
+
+
+@pytest.fixture(scope="module")
+def kp():
+    import paper_2505_21661_amd as kp
+
+    return kp
+
+
+def test_calibration_trace_is_wellformed(kp, oracle_mod):
+    n_wg, waves = 1024, 4
+    buf, raw = run_calibrate(kp, CYCLES, n_wg, waves, 0, 64)
+    assert raw[0] == 0x4652504B and tuple(raw[2:8]) == (n_wg, waves, len(CYCLES), 16, 0, 0)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    n_rec = n_wg * waves * 2 * len(CYCLES)
+    assert st["n_slots_valid"] == n_rec and st["n_pairs"] == n_rec // 2
+    assert st["n_orphan_start"] == 0 and st["n_orphan_end"] == 0 and st["n_invalid"] == 0
+    assert st["n_dropped"] == 0 and st["n_disorder"] == 0
+    assert st["n_nonmonotonic"] == 0 and st["n_span_overflow_wgs"] == 0 and st["n_overlap_wgs"] == n_wg
+    # every (workgroup, wave, region) saw exactly one instance
+    assert (st["per"]["n"] == 1).all()
+    # workgroup headers: ids, totals, spans that contain every record
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert (hdr[:, 0] == np.arange(n_wg)).all()
+    assert (hdr[:, 8:8 + waves] == 2 * len(CYCLES)).all() and (hdr[:, 8 + waves:24] == 0).all()
+    t_begin = hdr[:, 2].astype(np.uint64) | (hdr[:, 3].astype(np.uint64) << np.uint64(32))
+    t_end = hdr[:, 4].astype(np.uint64) | (hdr[:, 5].astype(np.uint64) << np.uint64(32))
+    span = (t_end - t_begin).astype(np.int64)
+    assert (span > 0).all()
+    recs = raw[16 + 32 * n_wg:].reshape(n_wg, waves, 16, 2)[:, :, :2 * len(CYCLES)]
+    assert (recs[..., 1].astype(np.int64) <= span[:, None, None]).all()          # payload inside the span
+    assert (np.diff(recs[..., 1].astype(np.int64), axis=2) >= 0).all()          # per-wave monotone clock
+    # regions of one wave do not nest here: their durations fit into the span
+    assert (st["per"]["sum"].sum(axis=2).astype(np.int64) <= span[:, None]).all()
+
+
+def test_timer_is_linear_within_3_percent(kp, oracle_mod):
+    n_wg, waves = 1024, 4
+    buf, raw = run_calibrate(kp, CYCLES, n_wg, waves, 0, 64)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    d = np.median(st["per"]["sum"].astype(np.float64), axis=(0, 1))  # one instance each -> sum = duration
+    rec_cost = d[0]
+    fmas = np.array(CYCLES[1:]) / 4
+    # expected duration = fixed cost per region + FMAs x ticks per FMA (least-squares line)
+    slope, icpt = np.polyfit(fmas, d[1:], 1)
+    expected = icpt + slope * fmas
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32).astype(np.uint64)
+    span = (hdr[:, 4] | (hdr[:, 5] << np.uint64(32))) - (hdr[:, 2] | (hdr[:, 3] << np.uint64(32)))
+    rt = hdr[:, 6] | (hdr[:, 7] << np.uint64(32))
+    mhz = 100.0 * span.astype(np.float64).sum() / rt.astype(np.float64).sum()
+    print(f"record cost {rec_cost:.1f} ticks, {slope:.3f} ticks per dependent FMA, fixed {icpt:.1f}, "
+          f"medians {d}, s_memtime ~ {mhz:.0f} MHz if s_memrealtime is 100 MHz")
+    assert 0 < rec_cost < 200
+    assert np.all(np.abs(d[1:] - expected) <= 0.03 * expected), (d[1:], expected)
+    # durations scale 1:4:16:64 once the fixed cost is taken out
+    net = d[1:] - icpt
+    assert np.all(np.abs(net / net[0] - fmas / fmas[0]) <= 0.03 * fmas / fmas[0]), net / net[0]
+    # the unit is the same across the chip: most waves land within 3 % for the longest region
+    # (waves that had to share a SIMD with another wave take about twice as long)
+    longest = st["per"]["sum"][:, :, -1].astype(np.float64)
+    assert np.mean(np.abs(longest - expected[-1]) <= 0.03 * expected[-1]) > 0.6
+
+
+def test_sleep_mode_runs(kp, oracle_mod):
+    buf, raw = run_calibrate(kp, [0, 1024, 4096], 64, 4, 1, 32)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    d = np.median(st["per"]["sum"].astype(np.float64), axis=(0, 1))
+    assert d[2] > d[1] > d[0]
+
+
+def test_circular_ring_wraps_and_counts_drops(kp, oracle_mod):
+    # 10 records per wave into an 8-slot sub-ring: the 2 oldest are overwritten
+    n_wg, waves = 96, 4
+    buf, raw = run_calibrate(kp, CYCLES, n_wg, waves, 0, 8 * waves)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    assert st["n_dropped"] == 2 * n_wg * waves and st["n_slots_valid"] == 8 * n_wg * waves
+    # survivors: regions 1..4 complete; region 0's records are gone
+    assert st["n_pairs"] == 4 * n_wg * waves and st["n_orphan_end"] == 0 and st["n_orphan_start"] == 0
+    assert st["cnt"].tolist() == [0] + [n_wg * waves] * 4
+    # 12 records: regions 0 and 1 are overwritten
+    buf, raw = run_calibrate(kp, CYCLES + [64], n_wg, waves, 0, 8 * waves)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    assert st["n_dropped"] == 4 * n_wg * waves and st["n_pairs"] == 4 * n_wg * waves
+    assert st["n_orphan_end"] == 0 and st["cnt"].tolist() == [0, 0] + [n_wg * waves] * 4
+
+
+def test_flush_strategy(kp, oracle_mod):
+    n_wg, waves = 80, 4
+    # 10 records per wave through an 8-slot LDS sub-ring into a 16-slot HBM segment: nothing lost
+    buf, raw = run_calibrate(kp, CYCLES, n_wg, waves, 2, 16 * waves)
+    assert raw[7] == 1
+    st = decode_both(kp, oracle_mod, buf, raw)
+    assert st["n_dropped"] == 0 and st["n_pairs"] == 5 * n_wg * waves and st["n_disorder"] == 0
+    # 24 records per wave into a 16-slot segment: the first 16 are kept, 8 are dropped
+    buf, raw = run_calibrate(kp, [64] * 12, n_wg, waves, 2, 16 * waves)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    assert st["n_dropped"] == 8 * n_wg * waves and st["n_pairs"] == 8 * n_wg * waves
+    assert st["cnt"].tolist() == [n_wg * waves] * 8 + [0] * 4
+
+
+def test_calibrate_errors(kp):
+    buf = torch.zeros(kp.kp_trace_bytes(4, 4, 64), dtype=torch.uint8, device="cuda")
+    for args, code in [((CYCLES, 4, 4, 0, buf, 63), kp.KP_ERR_TRACE_TOO_SMALL),
+                       ((CYCLES, 4, 4, 0, buf, 48), kp.KP_ERR_TRACE_TOO_SMALL),
+                       ((CYCLES, 0, 4, 0, buf, 64), kp.KP_ERR_INVALID_ARG),
+                       ((CYCLES, 4, 17, 0, buf, 68), kp.KP_ERR_INVALID_ARG),
+                       (([1] * 33, 4, 4, 0, buf, 64), kp.KP_ERR_INVALID_ARG)]:
+        with pytest.raises(kp.KperfError) as e:
+            kp.kp_calibrate(*args)
+        assert e.value.status == code, (args[1:4], args[5], e.value)
