@@ -57,7 +57,7 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
   kp::TraceGeom g{n_wg, waves, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
-  kp::ring_finish(r, lds_ring, t_begin, cap_lds, trace, g, blockIdx.x, 0u);
+  kp::ring_finish(r, cap_lds, trace, g, blockIdx.x, 0u);
 }
 
 }  // namespace

@@ -129,7 +129,166 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   }
   if constexpr (INSTR) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
-    kp::ring_finish(ring, ring_lds, t_begin, g.cap_lds, g.trace, tg, wg, 0u);
+    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
+  }
+}
+
+
+// ------------------------------------------------------------------------------------------
+// 256x256x64 tile, 8 waves as 2 (M) x 4 (N); each wave owns 128x64 of C as 4x2 MFMA tiles.
+// LDS holds two stages of the A tile [256][64] and of the transposed B tile [256 n][64 k]
+// (128 KiB); the K loop is software-pipelined over the two stages: while the MFMAs consume
+// stage s, the global loads of the next K step are in flight and are written to stage s^1.
+// MFMA operands are swapped (B^T rows as the first operand) so that a lane ends up with four
+// consecutive columns of one C row per accumulator quad and can store them as 8 bytes.
+constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64, kBigThreads = 512;
+constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // both stages
+
+template <bool INSTR>
+__global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
+  constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
+  constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  extern __shared__ __align__(16) unsigned char smem[];  // [stage0 A|B][stage1 A|B][ring]
+  uint32_t* ring_lds = reinterpret_cast<uint32_t*>(smem + 2 * STAGE);
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t tiles_m = g.M / BM, tiles_n = g.N / BN;
+  // Workgroups are dealt round-robin to the 8 XCDs; give every XCD a compact block of tiles
+  // so that the A and B panels it streams stay in its own L2.
+  uint32_t tile_r, tile_c;
+  if ((tiles_m % 4u) == 0u && (tiles_n % 2u) == 0u) {
+    const uint32_t xcd = blockIdx.x & 7u, j = blockIdx.x >> 3;
+    const uint32_t br = tiles_m / 4u, bc = tiles_n / 2u;  // block of tiles per XCD
+    tile_r = (xcd >> 1) * br + j / bc;
+    tile_c = (xcd & 1u) * bc + j % bc;
+  } else {
+    tile_r = blockIdx.x / tiles_n;
+    tile_c = blockIdx.x % tiles_n;
+  }
+  const uint32_t wg = tile_r * tiles_n + tile_c;  // recorded workgroup id = tile index
+  const uint32_t m0 = tile_r * BM, n0 = tile_c * BN;
+
+  kp::Ring ring{};
+  if constexpr (INSTR)
+    ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
+                         g.cap_hbm, g.trace, g.n_wg, 8, wg);
+
+  // ---- global -> register -> LDS mapping ---------------------------------------------------
+  // A: 256 rows x 8 chunks of 16 B; thread handles chunk (tid&7) of rows (tid>>3) + 64*i
+  const uint32_t a_row = tid >> 3, a_chunk = tid & 7u;
+  const uint16_t* a_src = g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8;
+  // B: tasks (k-group of 8 rows, column pair); task id = tid + 512*j, kg = id>>7, pair = id&127
+  const uint32_t b_pair = tid & 127u, b_kg0 = tid >> 7;  // second task: kg0 + 4
+  const uint16_t* b_src = g.B + (size_t)(b_kg0 * 8) * g.N + n0 + b_pair * 2;
+
+  u32x4 a_reg[4];
+  uint32_t b_reg[2][8];
+  auto load_tile = [&](uint32_t kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      a_reg[i] = *reinterpret_cast<const u32x4*>(a_src + (size_t)(64 * i) * g.K + (size_t)kt * BK);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        b_reg[j][r] = *reinterpret_cast<const uint32_t*>(b_src + ((size_t)kt * BK + 32 * j + r) * g.N);
+  };
+  auto store_tile = [&](uint32_t stage) {
+    unsigned char* sA = smem + stage * STAGE;
+    unsigned char* sB = sA + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row + 64 * i, a_chunk)) = a_reg[i];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t* bv = b_reg[j];
+      u32x4 lo, hi;  // columns 2*pair and 2*pair+1, eight consecutive k each
+      lo.x = (bv[0] & 0xFFFFu) | (bv[1] << 16); hi.x = (bv[0] >> 16) | (bv[1] & 0xFFFF0000u);
+      lo.y = (bv[2] & 0xFFFFu) | (bv[3] << 16); hi.y = (bv[2] >> 16) | (bv[3] & 0xFFFF0000u);
+      lo.z = (bv[4] & 0xFFFFu) | (bv[5] << 16); hi.z = (bv[4] >> 16) | (bv[5] & 0xFFFF0000u);
+      lo.w = (bv[6] & 0xFFFFu) | (bv[7] << 16); hi.w = (bv[6] >> 16) | (bv[7] & 0xFFFF0000u);
+      *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_pair * 2, b_kg0 + 4 * j)) = lo;
+      *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_pair * 2 + 1, b_kg0 + 4 * j)) = hi;
+    }
+  };
+
+  const uint32_t wm = wave >> 2, wn = wave & 3u;  // wave position: 2 x 4
+  f32x16 acc[2][4];                                // [tn][tm], transposed tiles (rows = n, cols = m)
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = f32x16{0};
+
+  // prologue: K step 0 into stage 0
+  load_tile(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  store_tile(0);
+  __syncthreads();
+
+  const uint32_t KT = g.K / BK;
+  for (uint32_t kt = 0; kt < KT; ++kt) {
+    const uint32_t stage = kt & 1u;
+    const bool more = kt + 1 < KT;
+    // ---- region 0: issue the global loads of the next K step ---------------------------------
+    KP_REC(ring, 0, kp::kPhaseStart);
+    if (more) load_tile(kt + 1);
+    KP_REC(ring, 0, kp::kPhaseEnd);
+    // ---- region 3: MFMA on the current stage -------------------------------------------------
+    KP_REC(ring, 3, kp::kPhaseStart);
+    {
+      const unsigned char* sA = smem + stage * STAGE;
+      const unsigned char* sB = sA + A_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const uint32_t chunk = ks * 2 + (lane >> 5);
+        bf16x8 af[4], bfr[2];
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+          af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off<BK>(wn * 64 + tn * 32 + (lane & 31u), chunk));
+#pragma unroll
+        for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+          for (int tm = 0; tm < 4; ++tm)
+            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
+      }
+    }
+    KP_REC(ring, 3, kp::kPhaseEnd);
+    // ---- region 1: wait for the loads ------------------------------------------------------------
+    KP_REC(ring, 1, kp::kPhaseStart);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    KP_REC(ring, 1, kp::kPhaseEnd);
+    // ---- region 2: write the next stage to LDS ---------------------------------------------------
+    KP_REC(ring, 2, kp::kPhaseStart);
+    if (more) store_tile(stage ^ 1u);
+    __syncthreads();
+    KP_REC(ring, 2, kp::kPhaseEnd);
+  }
+
+  // ---- region 4: epilogue ------------------------------------------------------------------------
+  KP_REC(ring, 4, kp::kPhaseStart);
+  // transposed tile: register v of lane l is C[m, n] with m = l%32 and n = 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm) {
+    const uint32_t row = m0 + wm * 128 + tm * 32 + (lane & 31u);
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t col = n0 + wn * 64 + tn * 32 + 8 * q + 4 * (lane >> 5);
+        u32x2 pk;
+        pk.x = f32_to_bf16_rne(acc[tn][tm][4 * q + 0]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 1]) << 16);
+        pk.y = f32_to_bf16_rne(acc[tn][tm][4 * q + 2]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 3]) << 16);
+        *reinterpret_cast<u32x2*>(g.C + (size_t)row * g.N + col) = pk;
+      }
+    }
+  }
+  KP_REC(ring, 4, kp::kPhaseEnd);
+  if constexpr (INSTR) {
+    kp::TraceGeom tg{g.n_wg, 8, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
 
@@ -142,6 +301,8 @@ struct GemmShape { int bm, bn, bk, waves, regions; };
 
 bool pick_shape(int M, int N, int K, GemmShape* s) {
   if (M <= 0 || N <= 0 || K <= 0) return false;
+  // the large tile only pays off once there are enough tiles to spread over the chip
+  if (M % 256 == 0 && N % 256 == 0 && K % 64 == 0 && (M / 256) * (N / 256) >= 16) { *s = GemmShape{256, 256, 64, 8, 5}; return true; }
   if (M % 64 == 0 && N % 64 == 0 && K % 32 == 0) { *s = GemmShape{64, 64, 32, 4, 3}; return true; }
   return false;
 }
@@ -176,8 +337,20 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.A = static_cast<const uint16_t*>(A); g.B = static_cast<const uint16_t*>(B); g.C = static_cast<uint16_t*>(C);
   g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
   g.region_mask = regions; g.trace = trace_buf; g.n_wg = (uint32_t)n_wg; g.flush = flush;
+  const bool big = s.bm == 256;
+  if (big) {
+    static thread_local bool attr_set = false;
+    if (!attr_set) {
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      attr_set = true;
+    }
+  }
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
-    hipLaunchKernelGGL(kp_gemm_small<false>, dim3(n_wg), dim3(256), 0, st, g);
+    if (big) hipLaunchKernelGGL(kp_gemm_big<false>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes, st, g);
+    else     hipLaunchKernelGGL(kp_gemm_small<false>, dim3(n_wg), dim3(256), 0, st, g);
     KP_HIP_TRY(hipGetLastError());
     return KP_OK;
   }
@@ -193,7 +366,8 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   const size_t ring_bytes = (size_t)cap_lds * 8 * s.waves;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
-  hipLaunchKernelGGL(kp_gemm_small<true>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+  if (big) hipLaunchKernelGGL(kp_gemm_big<true>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
+  else     hipLaunchKernelGGL(kp_gemm_small<true>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }

@@ -33,6 +33,8 @@ struct Ring {
   uint32_t mask;       // enabled regions
   uint32_t pend_tag;   // record whose clock was sampled but which is not in LDS yet (kNoPending: none)
   uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
+  uint64_t t_begin;    // workgroup start: s_memtime
+  uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
   // flush strategy only
   uint32_t flush;      // 0 circular, 1 flush
   uint32_t cap_hbm;    // slots of this wave's HBM segment
@@ -45,23 +47,29 @@ struct TraceGeom {
 
 __device__ __forceinline__ uint32_t wave_uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Workgroup prologue.  `ring_lds` holds waves * cap_lds slots; t_begin_lds[2] receives the 64-bit
-// s_memtime and s_memrealtime at start (thread 0 samples them, everyone reads them after a barrier).
-__device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* t_begin_lds, uint32_t cap_lds,
+// Workgroup prologue.  `ring_lds` holds waves * cap_lds slots.  `scratch_lds` (16 bytes) is only used
+// inside this call to hand thread 0's clock samples to every wave and may be reused afterwards.
+__device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_lds, uint32_t cap_lds,
                                           uint32_t region_mask, uint32_t flush, uint32_t cap_hbm,
                                           void* trace_buf, uint32_t n_wg, uint32_t waves, uint32_t wg) {
   const uint32_t wave = wave_uniform(threadIdx.x >> 6);
   if (threadIdx.x == 0) {
-    t_begin_lds[0] = __builtin_readcyclecounter();
-    t_begin_lds[1] = __builtin_amdgcn_s_memrealtime();
+    scratch_lds[0] = __builtin_readcyclecounter();
+    scratch_lds[1] = __builtin_amdgcn_s_memrealtime();
   }
   __syncthreads();
   Ring r;
+  {
+    const uint64_t a = scratch_lds[0], b = scratch_lds[1];
+    r.t_begin = ((uint64_t)wave_uniform((uint32_t)(a >> 32)) << 32) | wave_uniform((uint32_t)a);
+    r.rt_begin = ((uint64_t)wave_uniform((uint32_t)(b >> 32)) << 32) | wave_uniform((uint32_t)b);
+  }
+  __syncthreads();  // scratch_lds may be overwritten from here on
   r.sub = ring_lds + (size_t)wave * cap_lds * 2;
   r.cnt = 0;
   r.lds_mask = cap_lds - 1;
   r.tag_wave = wave << 20;
-  r.t0_lo = wave_uniform((uint32_t)*t_begin_lds);
+  r.t0_lo = (uint32_t)r.t_begin;
   r.mask = region_mask;
   r.pend_tag = kNoPending;
   r.pend_t = 0;
@@ -119,8 +127,7 @@ __device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase)
 }
 
 // Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
-__device__ __forceinline__ void ring_finish(Ring& r, uint32_t* ring_lds, const uint64_t* t_begin_lds,
-                                            uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
+__device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
                                             uint32_t rec_cost) {
   const uint64_t t_end = __builtin_readcyclecounter();
   const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
@@ -142,9 +149,9 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t* ring_lds, const u
   if (threadIdx.x == 0) {
     wh->wg_id = wg;
     wh->hw_id = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (11 << 11));  // HW_ID, low 12 bits
-    wh->t_begin = t_begin_lds[0];
+    wh->t_begin = r.t_begin;
     wh->t_end = t_end;
-    wh->reserved = rt_end - t_begin_lds[1];  // constant-rate (s_memrealtime) ticks over the same span
+    wh->reserved = rt_end - r.rt_begin;  // constant-rate (s_memrealtime) ticks over the same span
     for (uint32_t w = g.waves; w < KP_MAX_WAVES; ++w) wh->total_written[w] = 0;
     for (int i = 0; i < 8; ++i) wh->pad[i] = 0;
     if (wg == 0) {
