@@ -183,6 +183,24 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
 kp_status kp_gemm_instrumented(const void* A, const void* B, void* C, int M, int N, int K,
                                uint32_t region_mask, void* trace_buf, size_t trace_cap, void* stream);
 
+/* Launch geometry of kp_attn_instrumented: B*H*(S/128) workgroups of 4 waves, 3 regions. */
+kp_status kp_attn_launch_shape(int B, int H, int S, int D, int* n_wg, int* waves_per_wg, int* n_regions);
+
+/*
+ * Attention forward O = softmax(scale * Q K^T + mask) V per (batch, head); Q, K, V, O are
+ * [B, H, S, D] contiguous bf16 in device memory, 16-byte aligned; softmax and accumulation in
+ * fp32; causal != 0 masks key j > query i.  D must be 128 and S a multiple of 128
+ * (KP_ERR_UNSUPPORTED_SHAPE otherwise); scale must be positive and finite.
+ * The paper's flash-attention study times the two GEMMs and the softmax of every KV iteration
+ * (Sec. 5.2, Table 3); the regions here, once per KV tile of 64 keys, are
+ *   0 Q K^T (MFMA), 1 online softmax, 2 P V (MFMA).
+ * One workgroup (4 waves) handles 128 query rows; with causal masking block q records
+ * 6 * 2 * (q + 1) times per wave.  region_mask, trace_buf, trace_cap as for the GEMM.
+ */
+kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void* O, int B, int H, int S,
+                               int D, int causal, float scale, uint32_t region_mask, void* trace_buf,
+                               size_t trace_cap, void* stream);
+
 /*
  * Timer calibration (Sec. 5.4 "Cycle-level Overhead": cost of one record; Sec. 4.3: that
  * constant is subtracted at replay).  Launches n_wg workgroups of `waves` waves, one workgroup

@@ -1,0 +1,139 @@
+"""Instrumented bf16 attention forward through the C ABI: outputs against the fp64 oracle and the
+uninstrumented kernel (bitwise); traces against closed forms and the CPU decoder oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import inputs
+from oracle import ref_attn
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kp():
+    import paper_2505_21661_amd as kp
+
+    return kp
+
+
+def run_attn(kp, q, k, v, causal, mask, trace_cap=None, scale=None, dev=None):
+    B, H, S, D = q.shape
+    if dev is None:
+        dev = (q.cuda(), k.cuda(), v.cuda())
+    O = torch.full((B, H, S, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    n_wg, waves, R = kp.kp_attn_launch_shape(B, H, S, D)
+    trace = None
+    if mask & 0x7FFFFFFF:
+        trace = torch.full((kp.kp_trace_bytes(n_wg, waves, trace_cap),), 0x33, dtype=torch.uint8, device="cuda")
+    kp.kp_attn_instrumented(*dev, O, B, H, S, D, causal, scale if scale else 1.0 / math.sqrt(D), mask, trace,
+                            trace_cap or 0)
+    torch.cuda.synchronize()
+    return O, trace, (n_wg, waves, R)
+
+
+def assert_head_close(O, q, k, v, b, h, causal, rows=None, scale=None):
+    ref = ref_attn(q[b, h], k[b, h], v[b, h], causal=causal, rows=rows, scale=scale)
+    got = O[b, h].float().cpu().numpy().astype(np.float64)
+    if rows is not None:
+        got = got[np.asarray(rows)]
+    rms = np.sqrt(np.mean(ref ** 2))
+    err = np.abs(got - ref)
+    assert np.all(err <= 1e-2 * np.abs(ref) + 1e-2 * rms), (b, h, float(err.max()), float(rms))
+    assert np.linalg.norm(got - ref) <= 1e-2 * np.linalg.norm(ref)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_small_attention_matches_oracle_and_vanilla(kp, causal):
+    q, k, v = inputs.attn_inputs(2, 3, 384, 128, seed=7)
+    o_van, _, shape = run_attn(kp, q, k, v, causal, 0)
+    assert shape == (2 * 3 * 3, 4, 3)
+    for b in range(2):
+        for h in range(3):
+            assert_head_close(o_van, q, k, v, b, h, causal)
+    o_ins, _, _ = run_attn(kp, q, k, v, causal, 0b111, trace_cap=1024)
+    assert torch.equal(o_ins.view(torch.int16), o_van.view(torch.int16))
+    o_fl, _, _ = run_attn(kp, q, k, v, causal, 0b101 | (1 << 31), trace_cap=1024)
+    assert torch.equal(o_fl.view(torch.int16), o_van.view(torch.int16))
+    o_sc, _, _ = run_attn(kp, q, k, v, causal, 0, scale=0.2)
+    assert_head_close(o_sc, q, k, v, 1, 2, causal, scale=0.2)
+
+
+def test_attention_special_cases(kp):
+    q, k, v = inputs.attn_inputs(1, 1, 256, 128, seed=8)
+    vc = torch.full_like(v, 0.75)
+    o, _, _ = run_attn(kp, q, k, vc, True, 0b111, trace_cap=256)
+    assert torch.allclose(o.float().cpu(), torch.full((1, 1, 256, 128), 0.75), atol=4e-3)
+    o, _, _ = run_attn(kp, q, k, v, True, 0)
+    assert torch.equal(o[0, 0, 0].cpu().view(torch.int16), v[0, 0, 0].view(torch.int16))  # row 0 sees key 0 only
+    o, _, _ = run_attn(kp, torch.zeros_like(q), k, v, True, 0)
+    want = torch.cumsum(v[0, 0].double(), 0) / torch.arange(1, 257, dtype=torch.float64)[:, None]
+    assert torch.allclose(o[0, 0].double().cpu(), want, atol=1e-2, rtol=1e-2)
+
+
+def test_attention_trace_closed_form(kp, oracle_mod):
+    from tests.gpu_util import assert_stats_equal
+
+    B, H, S = 1, 2, 512
+    q, k, v = inputs.attn_inputs(B, H, S, 128, seed=9)
+    _, trace, (n_wg, waves, R) = run_attn(kp, q, k, v, True, 0b111, trace_cap=64)  # 16 slots per wave
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * 16, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    # query block qb runs 2*(qb+1) KV tiles and writes 6 records per tile and wave
+    totals = np.array([6 * 2 * (qb + 1) for qb in range(S // 128)])
+    assert st["n_dropped"] == B * H * waves * int(np.maximum(totals - 16, 0).sum())
+    assert st["n_slots_valid"] == B * H * waves * int(np.minimum(totals, 16).sum())
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert sorted(hdr[:, 8].tolist()) == sorted(list(totals) * (B * H))
+    assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_disorder"] == 0
+
+
+def test_full_size_attention(kp, oracle_mod):
+    """Benchmark configuration: batch 4, 32 heads, sequence 4096, head dim 128, causal, ring of 1024
+    records per workgroup (256 per wave), which wraps for query blocks 21..31."""
+    from tests.gpu_util import assert_stats_equal
+
+    B, H, S, D = 4, 32, 4096, 128
+    q, k, v = inputs.attn_inputs(B, H, S, D, seed=3)
+    dev = (q.cuda(), k.cuda(), v.cuda())
+    o_van, _, shape = run_attn(kp, q, k, v, True, 0, dev=dev)
+    assert shape == (4096, 4, 3)
+    rng = np.random.default_rng(1)
+    for b, h in ((0, 0), (3, 31), (1, 17)):
+        rows = np.sort(rng.choice(S, size=96, replace=False))
+        assert_head_close(o_van, q, k, v, b, h, True, rows=rows)
+    o_ins, trace, (n_wg, waves, R) = run_attn(kp, q, k, v, True, 0b111, trace_cap=1024, dev=dev)
+    assert torch.equal(o_ins.view(torch.int16), o_van.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * 256, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 16), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    totals = np.array([12 * (qb + 1) for qb in range(S // 128)])
+    assert st["n_dropped"] == B * H * waves * int(np.maximum(totals - 256, 0).sum()) > 0
+    assert st["n_slots_valid"] == B * H * waves * int(np.minimum(totals, 256).sum())
+    assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_span_overflow_wgs"] == 0
+
+
+def test_attention_errors(kp):
+    t = torch.zeros(1, 1, 128, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_attn_instrumented(t, t, t, t, 1, 1, 128, 64, 1, 0.1, 0, None, 0)
+    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_attn_instrumented(t, t, t, t, 1, 1, 100, 128, 1, 0.1, 0, None, 0)
+    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_attn_instrumented(t, t, t, t, 1, 1, 128, 128, 1, 0.1, 7, None, 64)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    tr = torch.zeros(kp.kp_trace_bytes(1, 4, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_attn_instrumented(t, t, t, t, 1, 1, 128, 128, 1, 0.1, 7, tr, 60)
+    assert e.value.status == kp.KP_ERR_TRACE_TOO_SMALL
