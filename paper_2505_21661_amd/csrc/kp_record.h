@@ -129,6 +129,7 @@ __device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase)
 // Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
 __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
                                             uint32_t rec_cost) {
+  __syncthreads();  // t_end must not precede any wave's last record
   const uint64_t t_end = __builtin_readcyclecounter();
   const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
   if (r.pend_tag != kNoPending) store_pending(r);

