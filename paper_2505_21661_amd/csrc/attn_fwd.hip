@@ -52,6 +52,8 @@ __device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return
 __device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) { return row * 128u + ((chunk ^ (row & 7u)) << 4); }
 
 #define KP_REC(ring, region, phase) do { if constexpr (INSTR) kp::record(ring, region, phase); } while (0)
+// END of one region and START of the next with a single clock sample
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR) kp::boundary(ring, end_r, start_r); } while (0)
 
 template <bool INSTR>
 __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
@@ -142,10 +144,9 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
         sacc[tk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[tk], 0, 0, 0);
       }
     }
-    KP_REC(ring, 0, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 0, 1);
 
     // ---- region 1: online softmax (this lane: query row qrow, 32 of the tile's 64 kv) -------------
-    KP_REC(ring, 1, kp::kPhaseStart);
     const bool diag = g.causal && (kv0 + kBkv > q0 + wave * 32);  // tile reaches past this wave's first row
     float mx = -INFINITY;
 #pragma unroll
@@ -182,12 +183,11 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-    KP_REC(ring, 1, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 1, 2);
 
     // ---- region 2: O^T += V^T P^T ---------------------------------------------------------------------
     // The kv order inside an MFMA step follows the accumulator layout of S^T (kv = 16s + 4h + e for
     // e < 4, 16s + 8 + 4h + e - 4 otherwise), so P needs no cross-lane movement; V^T is read to match.
-    KP_REC(ring, 2, kp::kPhaseStart);
 #pragma unroll
     for (int tk = 0; tk < 2; ++tk)
 #pragma unroll

@@ -46,14 +46,16 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
   // resetting the ring state, so that no recorded region pays for a cold code fetch.
   for (int pass = 0; pass < 2; ++pass) {
     r.cnt = 0;
+    r.stored = 0;
     r.pend_tag = kp::kNoPending;
+    r.pend_tag2 = kp::kNoPending;
     for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
       const uint32_t len = a.cycles[rg];
       kp::record(r, rg, kp::kPhaseStart);
       if (a.mode == 0) busy_fma(len >> 2, x); else busy_sleep(len >> 6);
       kp::record(r, rg, kp::kPhaseEnd);
     }
-    if (pass == 0 && r.pend_tag != kp::kNoPending) kp::store_pending(r);
+    if (pass == 0) kp::store_pending(r);
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
   kp::TraceGeom g{n_wg, waves, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};

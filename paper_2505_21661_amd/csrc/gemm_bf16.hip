@@ -31,11 +31,10 @@ struct GemmArgs {
   uint32_t cap_lds, cap_hbm, flush, n_wg;
 };
 
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+  const __bf16 h = (__bf16)f;
+  return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
 // LDS tiles hold rows of BK bf16 (K contiguous) in 16-byte chunks; chunk c of row r lives at chunk
@@ -48,7 +47,15 @@ __device__ __forceinline__ uint32_t tile_off(uint32_t row, uint32_t chunk) {
   return row * (BK * 2) + ((chunk ^ s) * 16);  // byte offset
 }
 
+// Same, for the transposed B tile of the large kernel (BK = 64): its 16-byte writes come from lanes
+// whose rows are 8 apart, so the swizzle also folds in the next three row bits.
+__device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
+  return row * 128u + ((chunk ^ ((row ^ (row >> 3)) & 7u)) << 4);
+}
+
 #define KP_REC(ring, region, phase) do { if constexpr (INSTR) kp::record(ring, region, phase); } while (0)
+// END of one region and START of the next with a single clock sample
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR) kp::boundary(ring, end_r, start_r); } while (0)
 
 // ------------------------------------------------------------------------------------------
 // 64x64x32 tile, 4 waves as 2x2, each wave one 32x32 accumulator tile.
@@ -82,16 +89,15 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 
   for (uint32_t kt = 0; kt < g.K / BK; ++kt) {
     // ---- region 0: global load ---------------------------------------------------------------
-    KP_REC(ring, 0, kp::kPhaseStart);
+    if (kt == 0) KP_BOUNDARY(ring, kp::kNoRegion, 0); else KP_BOUNDARY(ring, 2, 0);
     const u32x4 av = *reinterpret_cast<const u32x4*>(a_src + (size_t)kt * BK);
     uint32_t bv[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
       bv[i] = b_on ? *reinterpret_cast<const uint32_t*>(b_src + ((size_t)kt * BK + i) * g.N) : 0u;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    KP_REC(ring, 0, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 0, 1);
     // ---- region 1: LDS store -----------------------------------------------------------------
-    KP_REC(ring, 1, kp::kPhaseStart);
     __syncthreads();  // previous step's MFMA reads are done
     *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row, a_chunk)) = av;
     if (b_on) {
@@ -104,9 +110,8 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
       *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_np * 2 + 1, b_kg)) = hi;
     }
     __syncthreads();
-    KP_REC(ring, 1, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 1, 2);
     // ---- region 2: MFMA ------------------------------------------------------------------------
-    KP_REC(ring, 2, kp::kPhaseStart);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       // operand layout of v_mfma_f32_32x32x16_bf16: lane l supplies row/column l%32, k = 8*(l/32)..+7
@@ -116,8 +121,8 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc, 0, 0, 0);
     }
     asm volatile("s_nop 0" ::: "memory");
-    KP_REC(ring, 2, kp::kPhaseEnd);
   }
+  KP_BOUNDARY(ring, 2, kp::kNoRegion);
 
   // epilogue: accumulator register v of lane l is C[row, col] with col = l%32,
   // row = 8*(v/4) + 4*(l/32) + v%4 inside the wave's 32x32 tile
@@ -174,41 +179,53 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
                          g.cap_hbm, g.trace, g.n_wg, 8, wg);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
-  // A: 256 rows x 8 chunks of 16 B; thread handles chunk (tid&7) of rows (tid>>3) + 64*i
-  const uint32_t a_row = tid >> 3, a_chunk = tid & 7u;
-  const uint16_t* a_src = g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8;
-  // B: tasks (k-group of 8 rows, column pair); task id = tid + 512*j, kg = id>>7, pair = id&127
-  const uint32_t b_pair = tid & 127u, b_kg0 = tid >> 7;  // second task: kg0 + 4
-  const uint16_t* b_src = g.B + (size_t)(b_kg0 * 8) * g.N + n0 + b_pair * 2;
+  // Waves 0-3 stage A, waves 4-7 stage B, eight 16-byte loads per thread and K step (vector
+  // memory instructions are issued at a fixed rate per CU whatever their width, so wide loads
+  // keep the issue time of a K step short).
+  // A: 256 rows x 8 chunks; thread t takes chunk (t & 7) of rows (t >> 3) + 32*i.
+  // B: 8x8 blocks (k x n); thread u takes block (u >> 5, u & 31), loads its 8 rows and transposes
+  //    them in registers into eight 16-byte k-runs, one per column.
+  const bool is_a = tid < 256;
+  const uint32_t u = tid & 255u;
+  const uint32_t a_row = u >> 3, a_chunk = u & 7u;
+  const uint32_t b_kb = u >> 5, b_nb = u & 31u;
+  const uint16_t* src = is_a ? g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8
+                             : g.B + (size_t)(b_kb * 8) * g.N + n0 + b_nb * 8;
+  const size_t row_step = is_a ? (size_t)32 * g.K : (size_t)g.N;   // between the 8 loads of a thread
+  const size_t kt_step = is_a ? (size_t)BK : (size_t)BK * g.N;     // between K steps
 
-  u32x4 a_reg[4];
-  uint32_t b_reg[2][8];
+  u32x4 ld[8];
+  // loads 2*part and 2*part+1 of K step kt; the four parts are spread over the MFMA steps so that
+  // the vector-memory issue slots they occupy overlap with matrix work
+  auto load_part = [&](uint32_t kt, int part) {
+    const uint16_t* p0 = src + (size_t)kt * kt_step;
+#pragma unroll
+    for (int i = 2 * part; i < 2 * part + 2; ++i) ld[i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)i * row_step);
+  };
   auto load_tile = [&](uint32_t kt) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      a_reg[i] = *reinterpret_cast<const u32x4*>(a_src + (size_t)(64 * i) * g.K + (size_t)kt * BK);
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 8; ++r)
-        b_reg[j][r] = *reinterpret_cast<const uint32_t*>(b_src + ((size_t)kt * BK + 32 * j + r) * g.N);
+    for (int part = 0; part < 4; ++part) load_part(kt, part);
   };
   auto store_tile = [&](uint32_t stage) {
     unsigned char* sA = smem + stage * STAGE;
     unsigned char* sB = sA + A_BYTES;
+    if (is_a) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row + 64 * i, a_chunk)) = a_reg[i];
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row + 32 * i, a_chunk)) = ld[i];
+    } else {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t* bv = b_reg[j];
-      u32x4 lo, hi;  // columns 2*pair and 2*pair+1, eight consecutive k each
-      lo.x = (bv[0] & 0xFFFFu) | (bv[1] << 16); hi.x = (bv[0] >> 16) | (bv[1] & 0xFFFF0000u);
-      lo.y = (bv[2] & 0xFFFFu) | (bv[3] << 16); hi.y = (bv[2] >> 16) | (bv[3] & 0xFFFF0000u);
-      lo.z = (bv[4] & 0xFFFFu) | (bv[5] << 16); hi.z = (bv[4] >> 16) | (bv[5] & 0xFFFF0000u);
-      lo.w = (bv[6] & 0xFFFFu) | (bv[7] << 16); hi.w = (bv[6] >> 16) | (bv[7] & 0xFFFF0000u);
-      *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_pair * 2, b_kg0 + 4 * j)) = lo;
-      *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_pair * 2 + 1, b_kg0 + 4 * j)) = hi;
+      for (int c = 0; c < 8; ++c) {  // column c of the block: k = 8*b_kb .. +7
+        u32x4 o;
+        const int d = c >> 1;
+        if (c & 1) {
+          o.x = (ld[0][d] >> 16) | (ld[1][d] & 0xFFFF0000u); o.y = (ld[2][d] >> 16) | (ld[3][d] & 0xFFFF0000u);
+          o.z = (ld[4][d] >> 16) | (ld[5][d] & 0xFFFF0000u); o.w = (ld[6][d] >> 16) | (ld[7][d] & 0xFFFF0000u);
+        } else {
+          o.x = (ld[0][d] & 0xFFFFu) | (ld[1][d] << 16); o.y = (ld[2][d] & 0xFFFFu) | (ld[3][d] << 16);
+          o.z = (ld[4][d] & 0xFFFFu) | (ld[5][d] << 16); o.w = (ld[6][d] & 0xFFFFu) | (ld[7][d] << 16);
+        }
+        *reinterpret_cast<u32x4*>(sB + tile_off_bt(b_nb * 8 + c, b_kb)) = o;
+      }
     }
   };
 
@@ -226,15 +243,14 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   __syncthreads();
 
   const uint32_t KT = g.K / BK;
+  KP_BOUNDARY(ring, kp::kNoRegion, 0);
   for (uint32_t kt = 0; kt < KT; ++kt) {
     const uint32_t stage = kt & 1u;
     const bool more = kt + 1 < KT;
-    // ---- region 0: issue the global loads of the next K step ---------------------------------
-    KP_REC(ring, 0, kp::kPhaseStart);
-    if (more) load_tile(kt + 1);
-    KP_REC(ring, 0, kp::kPhaseEnd);
+    // ---- region 0: issue the first global loads of the next K step ---------------------------
+    if (more) load_part(kt + 1, 0);
+    KP_BOUNDARY(ring, 0, 3);
     // ---- region 3: MFMA on the current stage -------------------------------------------------
-    KP_REC(ring, 3, kp::kPhaseStart);
     {
       const unsigned char* sA = smem + stage * STAGE;
       const unsigned char* sB = sA + A_BYTES;
@@ -247,28 +263,30 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
           af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn)
-          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off<BK>(wn * 64 + tn * 32 + (lane & 31u), chunk));
+          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * 64 + tn * 32 + (lane & 31u), chunk));
 #pragma unroll
         for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
           for (int tm = 0; tm < 4; ++tm)
             acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
+        if (ks < 3) {  // remaining loads of the next K step ride along with the MFMAs
+          asm volatile("" ::: "memory");
+          if (more) load_part(kt + 1, ks + 1);
+          asm volatile("" ::: "memory");
+        }
       }
     }
-    KP_REC(ring, 3, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 3, 1);
     // ---- region 1: wait for the loads ------------------------------------------------------------
-    KP_REC(ring, 1, kp::kPhaseStart);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    KP_REC(ring, 1, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 1, 2);
     // ---- region 2: write the next stage to LDS ---------------------------------------------------
-    KP_REC(ring, 2, kp::kPhaseStart);
     if (more) store_tile(stage ^ 1u);
     __syncthreads();
-    KP_REC(ring, 2, kp::kPhaseEnd);
+    if (more) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, 4);
   }
 
   // ---- region 4: epilogue ------------------------------------------------------------------------
-  KP_REC(ring, 4, kp::kPhaseStart);
   // transposed tile: register v of lane l is C[m, n] with m = l%32 and n = 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm) {
@@ -285,7 +303,7 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_REC(ring, 4, kp::kPhaseEnd);
+  KP_BOUNDARY(ring, 4, kp::kNoRegion);
   if constexpr (INSTR) {
     kp::TraceGeom tg{g.n_wg, 8, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);

@@ -6,9 +6,10 @@
 // needs no atomics.  The record counter and all tag fields are wave-uniform and live in scalar
 // registers; the slot index is counter & (cap_wave-1) (Sec. 4.2: a cheap modular op with a
 // precomputed capacity).  A record site only samples s_memtime; the 8-byte store of a record
-// (one lane writes) is deferred to the next record site, after that site's own clock sample,
-// so neither the wait for the clock value nor the LDS write is charged to the region that a
-// START opens (the paper's split into ReadCounterOp and StoreCounterOp, Sec. 3.1).
+// (one lane writes) is deferred to the next record site, so no site ever waits for the clock
+// value it has just requested (the paper's split into ReadCounterOp and StoreCounterOp,
+// Sec. 3.1).  A region's measured length therefore includes the constant cost of storing its
+// own START record, which the decoder's rec_cost subtracts.
 //
 // Circular strategy: the sub-ring is overwritten cyclically and copied to HBM once, at exit.
 // Flush strategy: whenever a sub-ring fills up, its wave copies it to the next chunk of its HBM
@@ -23,15 +24,19 @@ namespace kp {
 
 constexpr uint32_t kPhaseStart = 0u, kPhaseEnd = 1u;
 constexpr uint32_t kNoPending = 0xFFFFFFFFu;
+constexpr uint32_t kNoRegion = 0xFFu;
 
 struct Ring {
   uint32_t* sub;       // LDS: this wave's sub-ring (2 dwords per slot)
+  uint32_t sub_lds;    // the same as a 32-bit LDS byte address
   uint32_t cnt;        // records written by this wave so far
   uint32_t lds_mask;   // LDS sub-ring capacity - 1
   uint32_t tag_wave;   // wave index << 20
   uint32_t t0_lo;      // low 32 bits of the workgroup's t_begin
   uint32_t mask;       // enabled regions
-  uint32_t pend_tag;   // record whose clock was sampled but which is not in LDS yet (kNoPending: none)
+  uint32_t pend_tag;   // up to two records that share the last clock sample and are not in LDS yet
+  uint32_t pend_tag2;  //   (an END and the START that follows it); kNoPending: none
+  uint32_t stored;     // records already written to the LDS sub-ring
   uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
   uint64_t t_begin;    // workgroup start: s_memtime
   uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
@@ -66,12 +71,16 @@ __device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_
   }
   __syncthreads();  // scratch_lds may be overwritten from here on
   r.sub = ring_lds + (size_t)wave * cap_lds * 2;
+  // the low 32 bits of a flat pointer into LDS are its LDS byte address
+  r.sub_lds = wave_uniform((uint32_t)(uintptr_t)ring_lds) + wave * cap_lds * 8;
   r.cnt = 0;
   r.lds_mask = cap_lds - 1;
   r.tag_wave = wave << 20;
   r.t0_lo = (uint32_t)r.t_begin;
   r.mask = region_mask;
   r.pend_tag = kNoPending;
+  r.pend_tag2 = kNoPending;
+  r.stored = 0;
   r.pend_t = 0;
   r.flush = flush;
   r.cap_hbm = cap_hbm;
@@ -95,35 +104,67 @@ __device__ __forceinline__ void wave_copy_slots(const uint32_t* src, uint32_t* d
   }
 }
 
-// Put the pending record into the wave's LDS sub-ring (lane 0 only writes).
-__device__ __forceinline__ void store_pending(Ring& r) {
-  const uint32_t slot = r.pend_tag & r.lds_mask;  // seq sits in the low tag bits
-  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-  u32x2 rec;
-  rec.x = r.pend_tag;
-  rec.y = (uint32_t)r.pend_t - r.t0_lo;
-  if ((threadIdx.x & 63u) == 0u) *reinterpret_cast<u32x2*>(r.sub + 2 * slot) = rec;
-  // here r.cnt counts the records up to and including the one just stored
-  if (r.flush && (r.cnt & r.lds_mask) == 0u) {
-    // sub-ring just filled up: move it to the next chunk of the HBM segment if it still fits
-    if (r.cnt <= r.cap_hbm) wave_copy_slots(r.sub, r.seg + (size_t)(r.cnt - (r.lds_mask + 1u)) * 2, r.lds_mask + 1u);
+// Put one record into the wave's LDS sub-ring; in the flush strategy a sub-ring that has just
+// filled up is copied to the next chunk of the wave's HBM segment if it still fits.
+// The store is seven instructions with no branch: narrow EXEC to lane 0, move the three scalar
+// values into VGPRs, one ds_write2_b32, restore EXEC.
+__device__ __forceinline__ void store_one(Ring& r, uint32_t tag, uint32_t ts) {
+  const uint32_t addr = r.sub_lds + ((r.stored & r.lds_mask) << 3);  // LDS byte address
+  uint64_t saved_exec;
+  uint32_t va, v0, v1;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, 1\n\t"
+      "v_mov_b32 %1, %4\n\t"
+      "v_mov_b32 %2, %5\n\t"
+      "v_mov_b32 %3, %6\n\t"
+      "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved_exec), "=&v"(va), "=&v"(v0), "=&v"(v1)
+      : "s"(addr), "s"(tag), "s"(ts)
+      : "memory");
+  r.stored += 1;
+  if (r.flush && (r.stored & r.lds_mask) == 0u) {
+    if (r.stored <= r.cap_hbm)
+      wave_copy_slots(r.sub, r.seg + (size_t)(r.stored - (r.lds_mask + 1u)) * 2, r.lds_mask + 1u);
   }
-  r.pend_tag = kNoPending;
 }
 
-// One record.  `region` and `phase` are compile-time constants at every call site.
-// Split as in the paper's ReadCounterOp / StoreCounterOp (Sec. 3.1): the clock is sampled here,
-// but its store is deferred to the next record site, after that site has sampled its own clock.
-// The wait for s_memtime and the LDS write therefore fall outside the region a START opens.
-__device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase) {
-  if (!((r.mask >> region) & 1u)) return;  // scalar test, uniform branch
+__device__ __forceinline__ void store_pending(Ring& r) {
+  // Keep BOTH halves of the sampled clock live up to here: if the unused high half were dead, its
+  // register could be reused right after s_memtime was issued, and that write-after-write hazard
+  // makes the hardware wait for the clock to return at the sampling site.
+  asm volatile("" ::"s"(r.pend_t));
+  const uint32_t ts = (uint32_t)r.pend_t - r.t0_lo;
+  if (r.pend_tag != kNoPending) store_one(r, r.pend_tag, ts);
+  if (r.pend_tag2 != kNoPending) store_one(r, r.pend_tag2, ts);
+  r.pend_tag = kNoPending;
+  r.pend_tag2 = kNoPending;
+}
+
+// One record site with ONE clock sample: the END of region `end_region` and/or the START of
+// region `start_region` (kNoRegion for neither); both are compile-time constants at every site.
+// Split as in the paper's ReadCounterOp / StoreCounterOp (Sec. 3.1).  The site first retires the
+// records of the previous site (their clock value returned long ago), then samples s_memtime and
+// leaves the 64-bit result untouched: lgkmcnt is shared between s_memtime and LDS, so any use
+// of a fresh value stalls the wave for the full s_memtime round trip (~200 cycles on gfx950).
+// Back-to-back END/START therefore share one sample instead of paying that stall.
+__device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t start_region) {
   __builtin_amdgcn_sched_barrier(0);
+  if ((r.pend_tag & r.pend_tag2) != kNoPending) store_pending(r);
   const uint64_t now = __builtin_readcyclecounter();  // s_memtime
-  if (r.pend_tag != kNoPending) store_pending(r);
-  r.pend_tag = (phase << 31) | (region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu);
+  const bool on_e = end_region != kNoRegion && ((r.mask >> (end_region & 31u)) & 1u) != 0u;     // scalar
+  const bool on_s = start_region != kNoRegion && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
+  r.pend_tag = on_e ? ((1u << 31) | (end_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
+  r.cnt += on_e ? 1u : 0u;
+  r.pend_tag2 = on_s ? ((start_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
+  r.cnt += on_s ? 1u : 0u;
   r.pend_t = now;
-  r.cnt += 1;
   __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase) {
+  boundary(r, phase == kPhaseEnd ? region : kNoRegion, phase == kPhaseStart ? region : kNoRegion);
 }
 
 // Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
@@ -132,7 +173,7 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
   __syncthreads();  // t_end must not precede any wave's last record
   const uint64_t t_end = __builtin_readcyclecounter();
   const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
-  if (r.pend_tag != kNoPending) store_pending(r);
+  store_pending(r);
   unsigned char* base = static_cast<unsigned char*>(trace_buf);
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   if (r.flush) {
