@@ -175,8 +175,8 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  * software-pipelined GEMMs stage by stage (Sec. 5.3 "Profiling Overhead", GEMM-SWP-2/3); the
  * regions here are
  *   M, N multiples of 256 with at least 16 tiles, K a multiple of 64: tile 256x256x64, 8 waves,
- *       0 first global-load issue, 1 load wait, 2 LDS write, 3 MFMA with the remaining loads
- *       interleaved (each once per K-step), 4 epilogue
+ *       2 LDS write of the next K-step, 0 first global-load issue, 3 MFMA with the remaining loads
+ *       interleaved, 1 wait (barrier + outstanding loads), in this order once per K-step; 4 epilogue
  *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
  *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
  * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.

@@ -51,12 +51,12 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
 __device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return row * 256u + ((chunk ^ (row & 7u)) << 4); }
 __device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) { return row * 128u + ((chunk ^ (row & 7u)) << 4); }
 
-#define KP_REC(ring, region, phase) do { if constexpr (INSTR) kp::record(ring, region, phase); } while (0)
-// END of one region and START of the next with a single clock sample
-#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR) kp::boundary(ring, end_r, start_r); } while (0)
+// END of one region and/or START of the next with a single clock sample.  INSTR: 0 no record sites,
+// 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<INSTR>(ring, end_r, start_r); } while (0)
 
-template <bool INSTR>
-__global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
+template <int INSTR>
+__global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];  // [K tile][V^T tile][ring]
   unsigned char* sK = smem;
   unsigned char* sV = smem + kKBytes;
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
   const uint32_t q0 = qb * kBq;
 
   kp::Ring ring{};
-  if constexpr (INSTR)
+  if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, 4, wg);
 
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
     if (t + 1 < n_tiles) load_tile(kv0 + kBkv);  // in flight during the three regions below
 
     // ---- region 0: S^T = K Q^T --------------------------------------------------------------------
-    KP_REC(ring, 0, kp::kPhaseStart);
+    KP_BOUNDARY(ring, kp::kNoRegion, 0);
     f32x16 sacc[2];
     sacc[0] = f32x16{0}; sacc[1] = f32x16{0};
 #pragma unroll
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
           oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, oacc[dt], 0, 0, 0);
         }
       }
-    KP_REC(ring, 2, kp::kPhaseEnd);
+    KP_BOUNDARY(ring, 2, kp::kNoRegion);
   }
 
   // epilogue: O[q][d] = O^T[d][q] / l
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kAttnThreads) void kp_attn_fwd(AttnArgs g) {
       pk2.y = bf16_rne(oacc[dt][4 * q + 2] * inv) | (bf16_rne(oacc[dt][4 * q + 3] * inv) << 16);
       *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q + 4 * h32) = pk2;
     }
-  if constexpr (INSTR) {
+  if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -265,7 +265,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   g.region_mask = regions; g.trace = trace_buf; g.flush = flush; g.n_wg = (uint32_t)n_wg;
   const uint32_t tile_bytes = kKBytes + kVBytes;
   if (regions == 0) {
-    hipLaunchKernelGGL(kp_attn_fwd<false>, dim3(n_wg), dim3(kAttnThreads), tile_bytes, st, g);
+    hipLaunchKernelGGL(kp_attn_fwd<0>, dim3(n_wg), dim3(kAttnThreads), tile_bytes, st, g);
     KP_HIP_TRY(hipGetLastError());
     return KP_OK;
   }
@@ -283,11 +283,16 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
   static thread_local bool attr_set = false;
   if (!attr_set) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<true>),
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<1>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kp_attn_fwd<true>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  if (!flush && regions == 7u)  // every region, circular: lean record sites
+    hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  else
+    hipLaunchKernelGGL(kp_attn_fwd<1>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }

@@ -4,9 +4,9 @@
 // The paper profiles software-pipelined Triton GEMMs by inserting region records around the
 // stages of the K loop (Sec. 5.3, GEMM-SWP-2/3; Sec. 2.3 software pipelining).  These kernels
 // are this library's own MFMA GEMMs with hand-placed record sites.  Each exists twice from one
-// template: INSTR=false compiles every record site away (the uninstrumented baseline),
-// INSTR=true records into the LDS ring.  Record sites contain no floating point, so both
-// variants produce bit-identical C.
+// template: INSTR=0 compiles every record site away (the uninstrumented baseline), INSTR=1 and 2
+// record into the LDS ring.  Record sites contain no floating point, so all variants produce
+// bit-identical C.
 //
 //   tile 64x64x32, 4 waves  : regions 0 global load, 1 LDS store, 2 MFMA        (per K step)
 //   tile 256x256x64, 8 waves: regions 0 load issue, 1 load wait, 2 LDS write, 3 MFMA (per K step),
@@ -53,13 +53,13 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
   return row * 128u + ((chunk ^ ((row ^ (row >> 3)) & 7u)) << 4);
 }
 
-#define KP_REC(ring, region, phase) do { if constexpr (INSTR) kp::record(ring, region, phase); } while (0)
-// END of one region and START of the next with a single clock sample
-#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR) kp::boundary(ring, end_r, start_r); } while (0)
+// END of one region and START of the next with a single clock sample.  INSTR: 0 no record sites,
+// 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<INSTR>(ring, end_r, start_r); } while (0)
 
 // ------------------------------------------------------------------------------------------
 // 64x64x32 tile, 4 waves as 2x2, each wave one 32x32 accumulator tile.
-template <bool INSTR>
+template <int INSTR>
 __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   constexpr int BM = 64, BN = 64, BK = 32;
   __shared__ __align__(16) unsigned char sA[BM * BK * 2];
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   const uint32_t wg = blockIdx.x;
   const uint32_t m0 = (wg / tiles_n) * BM, n0 = (wg % tiles_n) * BN;
   kp::Ring ring{};
-  if constexpr (INSTR)
+  if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4, wg);
 
   // global -> register mapping
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
     const uint32_t row = m0 + wr * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
     g.C[(size_t)row * g.N + col] = (uint16_t)f32_to_bf16_rne(acc[v]);
   }
-  if constexpr (INSTR) {
+  if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64, kBigThreads = 512;
 constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // both stages
 
-template <bool INSTR>
+template <int INSTR>
 __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   const uint32_t m0 = tile_r * BM, n0 = tile_c * BN;
 
   kp::Ring ring{};
-  if constexpr (INSTR)
+  if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, 8, wg);
 
@@ -236,21 +236,30 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = f32x16{0};
 
-  // prologue: K step 0 into stage 0
+  // prologue: K step 0 into stage 0, K step 1 into the staging registers
+  const uint32_t KT = g.K / BK;
   load_tile(0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   store_tile(0);
+  if (KT > 1) load_tile(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  const uint32_t KT = g.K / BK;
-  KP_BOUNDARY(ring, kp::kNoRegion, 0);
+  // Iteration kt: the registers hold K step kt+1 (loaded during the previous iteration); they go
+  // to the other LDS stage first, and those writes drain while the MFMAs below work on the current
+  // stage.  The loads of K step kt+2 then refill the registers, spread over the MFMA steps.  One
+  // barrier per iteration orders "stage written" before "stage read" and vice versa.
+  KP_BOUNDARY(ring, kp::kNoRegion, 2);
   for (uint32_t kt = 0; kt < KT; ++kt) {
     const uint32_t stage = kt & 1u;
-    const bool more = kt + 1 < KT;
-    // ---- region 0: issue the first global loads of the next K step ---------------------------
-    if (more) load_part(kt + 1, 0);
+    const bool more = kt + 1 < KT, more2 = kt + 2 < KT;
+    // ---- region 2: write K step kt+1 to the other LDS stage --------------------------------------
+    if (more) store_tile(stage ^ 1u);
+    KP_BOUNDARY(ring, 2, 0);
+    // ---- region 0: issue the first global loads of K step kt+2 -----------------------------------
+    if (more2) load_part(kt + 2, 0);
     KP_BOUNDARY(ring, 0, 3);
-    // ---- region 3: MFMA on the current stage -------------------------------------------------
+    // ---- region 3: MFMA on the current stage, remaining loads interleaved -------------------------
     {
       const unsigned char* sA = smem + stage * STAGE;
       const unsigned char* sB = sA + A_BYTES;
@@ -269,21 +278,18 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
           for (int tm = 0; tm < 4; ++tm)
             acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
-        if (ks < 3) {  // remaining loads of the next K step ride along with the MFMAs
+        if (ks < 3) {  // remaining loads of K step kt+2 ride along with the MFMAs
           asm volatile("" ::: "memory");
-          if (more) load_part(kt + 1, ks + 1);
+          if (more2) load_part(kt + 2, ks + 1);
           asm volatile("" ::: "memory");
         }
       }
     }
     KP_BOUNDARY(ring, 3, 1);
-    // ---- region 1: wait for the loads ------------------------------------------------------------
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    KP_BOUNDARY(ring, 1, 2);
-    // ---- region 2: write the next stage to LDS ---------------------------------------------------
-    if (more) store_tile(stage ^ 1u);
+    // ---- region 1: wait for the other waves and for this wave's loads ----------------------------
     __syncthreads();
-    if (more) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, 4);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (more) KP_BOUNDARY(ring, 1, 2); else KP_BOUNDARY(ring, 1, 4);
   }
 
   // ---- region 4: epilogue ------------------------------------------------------------------------
@@ -304,7 +310,7 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
     }
   }
   KP_BOUNDARY(ring, 4, kp::kNoRegion);
-  if constexpr (INSTR) {
+  if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 8, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -359,16 +365,18 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (big) {
     static thread_local bool attr_set = false;
     if (!attr_set) {
-      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<false>),
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<0>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<true>),
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<1>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<2>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
       attr_set = true;
     }
   }
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
-    if (big) hipLaunchKernelGGL(kp_gemm_big<false>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes, st, g);
-    else     hipLaunchKernelGGL(kp_gemm_small<false>, dim3(n_wg), dim3(256), 0, st, g);
+    if (big) hipLaunchKernelGGL(kp_gemm_big<0>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes, st, g);
+    else     hipLaunchKernelGGL(kp_gemm_small<0>, dim3(n_wg), dim3(256), 0, st, g);
     KP_HIP_TRY(hipGetLastError());
     return KP_OK;
   }
@@ -384,8 +392,14 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   const size_t ring_bytes = (size_t)cap_lds * 8 * s.waves;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
-  if (big) hipLaunchKernelGGL(kp_gemm_big<true>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
-  else     hipLaunchKernelGGL(kp_gemm_small<true>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+  const bool lean = !flush && regions == (1u << s.regions) - 1u;  // every region, circular: lean record sites
+  if (big) {
+    if (lean) hipLaunchKernelGGL(kp_gemm_big<2>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
+    else      hipLaunchKernelGGL(kp_gemm_big<1>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
+  } else {
+    if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+    else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+  }
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }

@@ -109,7 +109,7 @@ __device__ __forceinline__ void wave_copy_slots(const uint32_t* src, uint32_t* d
 // The store is seven instructions with no branch: narrow EXEC to lane 0, move the three scalar
 // values into VGPRs, one ds_write2_b32, restore EXEC.
 __device__ __forceinline__ void store_one(Ring& r, uint32_t tag, uint32_t ts) {
-  const uint32_t addr = r.sub_lds + ((r.stored & r.lds_mask) << 3);  // LDS byte address
+  const uint32_t addr = r.sub_lds + ((tag & r.lds_mask) << 3);  // seq sits in the low tag bits
   uint64_t saved_exec;
   uint32_t va, v0, v1;
   asm volatile(
@@ -161,6 +161,63 @@ __device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t 
   r.cnt += on_s ? 1u : 0u;
   r.pend_t = now;
   __builtin_amdgcn_sched_barrier(0);
+}
+
+// The same site for the common case "every region enabled, circular strategy": no mask tests, no
+// flush checks, and the two pending records go out under a single EXEC switch.  Every instruction
+// here is paid once per wave and site (a wave issues roughly one instruction every four cycles),
+// so the site is kept to about thirty instructions.
+__device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint32_t start_region) {
+  __builtin_amdgcn_sched_barrier(0);
+  if (r.pend_tag2 != kNoPending) {  // false only at the very first site
+    asm volatile("" ::"s"(r.pend_t));
+    const uint32_t ts = (uint32_t)r.pend_t - r.t0_lo;
+    const uint32_t a1 = r.sub_lds + ((r.pend_tag2 & r.lds_mask) << 3);
+    if (r.pend_tag != kNoPending) {
+      const uint32_t a0 = r.sub_lds + ((r.pend_tag & r.lds_mask) << 3);
+      uint64_t saved_exec;
+      uint32_t va, vb, vc, vd, ve;
+      asm volatile(
+          "s_mov_b64 %0, exec\n\t"
+          "s_mov_b64 exec, 1\n\t"
+          "v_mov_b32 %1, %6\n\t"
+          "v_mov_b32 %2, %7\n\t"
+          "v_mov_b32 %3, %8\n\t"
+          "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
+          "v_mov_b32 %4, %9\n\t"
+          "v_mov_b32 %5, %10\n\t"
+          "ds_write2_b32 %4, %5, %3 offset1:1\n\t"
+          "s_mov_b64 exec, %0"
+          : "=&s"(saved_exec), "=&v"(va), "=&v"(vb), "=&v"(vc), "=&v"(vd), "=&v"(ve)
+          : "s"(a0), "s"(r.pend_tag), "s"(ts), "s"(a1), "s"(r.pend_tag2)
+          : "memory");
+    } else {
+      store_one(r, r.pend_tag2, ts);
+    }
+  }
+  const uint64_t now = __builtin_readcyclecounter();  // s_memtime
+  if (end_region != kNoRegion) {
+    r.pend_tag = ((1u << 31) | (end_region << 24)) | r.tag_wave | (r.cnt & 0xFFFFFu);
+    r.cnt += 1;
+  } else {
+    r.pend_tag = kNoPending;
+  }
+  if (start_region != kNoRegion) {
+    r.pend_tag2 = (start_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu);
+    r.cnt += 1;
+  } else {  // final END of the kernel: keep it in the second slot so that "pending" stays one test
+    r.pend_tag2 = r.pend_tag;
+    r.pend_tag = kNoPending;
+  }
+  r.pend_t = now;
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// MODE 1: generic (region mask, either strategy); MODE 2: every region enabled, circular strategy.
+template <int MODE>
+__device__ __forceinline__ void site(Ring& r, uint32_t end_region, uint32_t start_region) {
+  if constexpr (MODE == 2) boundary_fast(r, end_region, start_region);
+  else boundary(r, end_region, start_region);
 }
 
 __device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase) {
