@@ -30,6 +30,13 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
+# read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
+TRAFFIC_BYTES = {
+    "decode_2^28": (1054808.4 * 2.0 + 36984.8) * 1024,
+    "gemm_vanilla": (98358.5 * 2.0 + 34702.5) * 1024,
+    "attn_vanilla": (1343831.0 * 2.0 + 131857.3) * 1024,
+}
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
 
@@ -183,7 +190,8 @@ def main() -> int:
             "peak": PEAK_HBM_GBS,
             "unit": "GB/s",
             "frac": round(dec_gbs / PEAK_HBM_GBS, 4),
-            "traffic": None,
+            "algorithmic_bytes": round(DECODE_BYTES_PER_RECORD * d_n),
+            "traffic": round(TRAFFIC_BYTES["decode_2^28"]) if args.log2_records == 28 else None,
         },
         "roofline_gemm": {
             "kernel": "kp_gemm_big<false> (uninstrumented 4096^3)",
@@ -192,7 +200,7 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(tf_van / PEAK_BF16_TFLOPS, 4),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["gemm_vanilla"]),
         },
         "roofline_attn": {
             "kernel": "kp_attn_fwd<false> (uninstrumented)",
@@ -201,7 +209,7 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(attn_tf_van / PEAK_BF16_TFLOPS, 4),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["attn_vanilla"]),
         },
     }
 
