@@ -152,6 +152,34 @@ def main() -> int:
     st = kp.parse_stats(d_stats)
     assert st["status"] == 0 and st["n_slots_valid"] == d_n, "decode workload did not decode"
 
+    # Overhead model of the paper, eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the
+    # per-record cost taken from the calibration kernel (an empty START/END region, i.e. two records)
+    # and the tick rate of s_memtime from the constant-rate clock sampled over the same spans.
+    c_wg, c_waves = 1024, 4
+    c_trace = torch.zeros(kp.kp_trace_bytes(c_wg, c_waves, 16), dtype=torch.uint8, device=dev)
+    kp.kp_calibrate([0, 4096], c_wg, c_waves, 0, c_trace, 16)
+    c_stats = torch.zeros(kp.kp_stats_bytes(c_wg, c_waves, 2), dtype=torch.uint8, device=dev)
+    kp.kp_trace_reduce(c_trace, c_wg * 16, c_stats)
+    torch.cuda.synchronize()
+    cst = kp.parse_stats(c_stats)
+    pair_cost = float(np.median(cst["per"]["sum"][:, :, 0]))
+    chdr = c_trace.cpu().numpy().view(np.uint32)[16:16 + 32 * c_wg].reshape(c_wg, 32).astype(np.uint64)
+    c_span = ((chdr[:, 4] | (chdr[:, 5] << np.uint64(32))) - (chdr[:, 2] | (chdr[:, 3] << np.uint64(32)))).astype(np.float64)
+    c_rt = (chdr[:, 6] | (chdr[:, 7] << np.uint64(32))).astype(np.float64)
+    tick_hz = 100e6 * c_span.sum() / c_rt.sum()
+    n_record = 2 * 4 * (K // 64) + 2
+    t_vanilla_ticks = ms["gemm_vanilla"] * 1e-3 * tick_hz
+    eq1 = {
+        "n_record_per_wave": n_record,
+        "cycle_record": round(pair_cost / 2.0, 1),
+        "s_memtime_hz": round(tick_hz),
+        "t_vanilla_ticks": round(t_vanilla_ticks),
+        "t_theoretical_ticks": round(t_vanilla_ticks + n_record * pair_cost / 2.0),
+        "t_actual_ticks": round(ms["gemm_instr"] * 1e-3 * tick_hz),
+        "note": "cycle_record is the back-to-back cost (it includes the s_memtime round trip); sites "
+                "inside long regions overlap most of it, so the actual time stays below the model",
+    }
+
     out = {
         "metric": "instrumentation overhead % + instrumented TFLOP/s; trace-decode records/s (HBM %)",
         "value": round(tf_ins, 2),
@@ -181,6 +209,7 @@ def main() -> int:
         "decode_records_per_s": round(dec_rps, 1),
         "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4),
         "kernel_ms": {n: round(x, 4) for n, x in ms.items()},
+        "overhead_model_eq1": eq1,
         "paper_context": {"overhead_pct": 8.2, "hardware": "H100 / MI300X (not split), Triton GEMM/FA3"},
         # dominant kernel of the step by time: the decoder's main kernel
         "roofline": {

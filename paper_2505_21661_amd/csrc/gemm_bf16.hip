@@ -146,12 +146,14 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 // stage s, the global loads of the next K step are in flight and are written to stage s^1.
 // MFMA operands are swapped (B^T rows as the first operand) so that a lane ends up with four
 // consecutive columns of one C row per accumulator quad and can store them as 8 bytes.
-constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64, kBigThreads = 512;
+constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64;
 constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // both stages
 
-template <int INSTR>
-__global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
+template <int INSTR, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
+  constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
+  static_assert(WAVES == 8 || WAVES == 4, "2x4 or 2x2 waves");
   constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];  // [stage0 A|B][stage1 A|B][ring]
   uint32_t* ring_lds = reinterpret_cast<uint32_t*>(smem + 2 * STAGE);
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   kp::Ring ring{};
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
-                         g.cap_hbm, g.trace, g.n_wg, 8, wg);
+                         g.cap_hbm, g.trace, g.n_wg, WAVES, wg);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Waves 0-3 stage A, waves 4-7 stage B, eight 16-byte loads per thread and K step (vector
@@ -185,22 +187,33 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   // A: 256 rows x 8 chunks; thread t takes chunk (t & 7) of rows (t >> 3) + 32*i.
   // B: 8x8 blocks (k x n); thread u takes block (u >> 5, u & 31), loads its 8 rows and transposes
   //    them in registers into eight 16-byte k-runs, one per column.
-  const bool is_a = tid < 256;
+  // With 8 waves, waves 0-3 stage A and waves 4-7 stage B (8 loads each); with 4 waves every thread
+  // stages one A share and one B block (16 loads).
+  constexpr bool SPLIT = WAVES == 8;
+  constexpr int NLD = SPLIT ? 8 : 16;
+  const bool is_a = SPLIT ? tid < 256 : true;
+  const bool is_b = SPLIT ? tid >= 256 : true;
   const uint32_t u = tid & 255u;
   const uint32_t a_row = u >> 3, a_chunk = u & 7u;
   const uint32_t b_kb = u >> 5, b_nb = u & 31u;
-  const uint16_t* src = is_a ? g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8
-                             : g.B + (size_t)(b_kb * 8) * g.N + n0 + b_nb * 8;
-  const size_t row_step = is_a ? (size_t)32 * g.K : (size_t)g.N;   // between the 8 loads of a thread
-  const size_t kt_step = is_a ? (size_t)BK : (size_t)BK * g.N;     // between K steps
+  const uint16_t* src_a = g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8;
+  const uint16_t* src_b = g.B + (size_t)(b_kb * 8) * g.N + n0 + b_nb * 8;
 
-  u32x4 ld[8];
-  // loads 2*part and 2*part+1 of K step kt; the four parts are spread over the MFMA steps so that
-  // the vector-memory issue slots they occupy overlap with matrix work
+  u32x4 ld[NLD];  // SPLIT: the thread's 8 loads; otherwise [0..7] A, [8..15] B
+  // loads 2*part and 2*part+1 of each share of K step kt; the four parts are spread over the MFMA
+  // steps so that the vector-memory issue slots they occupy overlap with matrix work
   auto load_part = [&](uint32_t kt, int part) {
-    const uint16_t* p0 = src + (size_t)kt * kt_step;
+    if (is_a) {
+      const uint16_t* p0 = src_a + (size_t)kt * BK;
 #pragma unroll
-    for (int i = 2 * part; i < 2 * part + 2; ++i) ld[i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)i * row_step);
+      for (int i = 2 * part; i < 2 * part + 2; ++i) ld[i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)(32 * i) * g.K);
+    }
+    if (is_b) {
+      const uint16_t* p0 = src_b + (size_t)kt * BK * g.N;
+      constexpr int o = SPLIT ? 0 : 8;
+#pragma unroll
+      for (int i = 2 * part; i < 2 * part + 2; ++i) ld[o + i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)i * g.N);
+    }
   };
   auto load_tile = [&](uint32_t kt) {
 #pragma unroll
@@ -212,27 +225,30 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
     if (is_a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row + 32 * i, a_chunk)) = ld[i];
-    } else {
+    }
+    if (is_b) {
+      constexpr int o = SPLIT ? 0 : 8;
 #pragma unroll
       for (int c = 0; c < 8; ++c) {  // column c of the block: k = 8*b_kb .. +7
-        u32x4 o;
+        u32x4 t;
         const int d = c >> 1;
         if (c & 1) {
-          o.x = (ld[0][d] >> 16) | (ld[1][d] & 0xFFFF0000u); o.y = (ld[2][d] >> 16) | (ld[3][d] & 0xFFFF0000u);
-          o.z = (ld[4][d] >> 16) | (ld[5][d] & 0xFFFF0000u); o.w = (ld[6][d] >> 16) | (ld[7][d] & 0xFFFF0000u);
+          t.x = (ld[o + 0][d] >> 16) | (ld[o + 1][d] & 0xFFFF0000u); t.y = (ld[o + 2][d] >> 16) | (ld[o + 3][d] & 0xFFFF0000u);
+          t.z = (ld[o + 4][d] >> 16) | (ld[o + 5][d] & 0xFFFF0000u); t.w = (ld[o + 6][d] >> 16) | (ld[o + 7][d] & 0xFFFF0000u);
         } else {
-          o.x = (ld[0][d] & 0xFFFFu) | (ld[1][d] << 16); o.y = (ld[2][d] & 0xFFFFu) | (ld[3][d] << 16);
-          o.z = (ld[4][d] & 0xFFFFu) | (ld[5][d] << 16); o.w = (ld[6][d] & 0xFFFFu) | (ld[7][d] << 16);
+          t.x = (ld[o + 0][d] & 0xFFFFu) | (ld[o + 1][d] << 16); t.y = (ld[o + 2][d] & 0xFFFFu) | (ld[o + 3][d] << 16);
+          t.z = (ld[o + 4][d] & 0xFFFFu) | (ld[o + 5][d] << 16); t.w = (ld[o + 6][d] & 0xFFFFu) | (ld[o + 7][d] << 16);
         }
-        *reinterpret_cast<u32x4*>(sB + tile_off_bt(b_nb * 8 + c, b_kb)) = o;
+        *reinterpret_cast<u32x4*>(sB + tile_off_bt(b_nb * 8 + c, b_kb)) = t;
       }
     }
   };
 
-  const uint32_t wm = wave >> 2, wn = wave & 3u;  // wave position: 2 x 4
-  f32x16 acc[2][4];                                // [tn][tm], transposed tiles (rows = n, cols = m)
+  const uint32_t wm = SPLIT ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
+  const uint32_t wn = SPLIT ? wave & 3u : wave & 1u;
+  f32x16 acc[TN][4];                               // [tn][tm], transposed tiles (rows = n, cols = m)
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TN; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = f32x16{0};
 
@@ -266,15 +282,15 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
         const uint32_t chunk = ks * 2 + (lane >> 5);
-        bf16x8 af[4], bfr[2];
+        bf16x8 af[4], bfr[TN];
 #pragma unroll
         for (int tm = 0; tm < 4; ++tm)
           af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
 #pragma unroll
-        for (int tn = 0; tn < 2; ++tn)
-          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * 64 + tn * 32 + (lane & 31u), chunk));
+        for (int tn = 0; tn < TN; ++tn)
+          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * (32 * TN) + tn * 32 + (lane & 31u), chunk));
 #pragma unroll
-        for (int tn = 0; tn < 2; ++tn)
+        for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
           for (int tm = 0; tm < 4; ++tm)
             acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
@@ -298,10 +314,10 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   for (int tm = 0; tm < 4; ++tm) {
     const uint32_t row = m0 + wm * 128 + tm * 32 + (lane & 31u);
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
+    for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const uint32_t col = n0 + wn * 64 + tn * 32 + 8 * q + 4 * (lane >> 5);
+        const uint32_t col = n0 + wn * (32 * TN) + tn * 32 + 8 * q + 4 * (lane >> 5);
         u32x2 pk;
         pk.x = f32_to_bf16_rne(acc[tn][tm][4 * q + 0]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 1]) << 16);
         pk.y = f32_to_bf16_rne(acc[tn][tm][4 * q + 2]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 3]) << 16);
@@ -311,7 +327,7 @@ __global__ __launch_bounds__(kBigThreads) void kp_gemm_big(GemmArgs g) {
   }
   KP_BOUNDARY(ring, 4, kp::kNoRegion);
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, 8, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, WAVES, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
@@ -323,12 +339,35 @@ namespace {
 
 struct GemmShape { int bm, bn, bk, waves, regions; };
 
+// Waves per workgroup of the 256x256x64 kernel.  The kernel template also builds with 4 waves
+// (128x128 of C per wave, one wave per SIMD); on MI355X that variant measured the same speed
+// (143 vs 145 us at 4096^3), so only the 8-wave form is instantiated.
+constexpr int kBigWaves = 8;
+
 bool pick_shape(int M, int N, int K, GemmShape* s) {
   if (M <= 0 || N <= 0 || K <= 0) return false;
   // the large tile only pays off once there are enough tiles to spread over the chip
-  if (M % 256 == 0 && N % 256 == 0 && K % 64 == 0 && (M / 256) * (N / 256) >= 16) { *s = GemmShape{256, 256, 64, 8, 5}; return true; }
+  if (M % 256 == 0 && N % 256 == 0 && K % 64 == 0 && (M / 256) * (N / 256) >= 16) { *s = GemmShape{256, 256, 64, kBigWaves, 5}; return true; }
   if (M % 64 == 0 && N % 64 == 0 && K % 32 == 0) { *s = GemmShape{64, 64, 32, 4, 3}; return true; }
   return false;
+}
+
+template <int INSTR, int WAVES>
+kp_status launch_big(const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
+  static thread_local bool attr_set = false;
+  if (!attr_set) {
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
+  KP_HIP_TRY(hipGetLastError());
+  return KP_OK;
+}
+
+template <int INSTR>
+kp_status launch_big_w(int /*waves*/, const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
+  return launch_big<INSTR, kBigWaves>(g, n_wg, ring_bytes, st);
 }
 
 }  // namespace
@@ -362,21 +401,9 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
   g.region_mask = regions; g.trace = trace_buf; g.n_wg = (uint32_t)n_wg; g.flush = flush;
   const bool big = s.bm == 256;
-  if (big) {
-    static thread_local bool attr_set = false;
-    if (!attr_set) {
-      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<0>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<1>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<2>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-      attr_set = true;
-    }
-  }
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
-    if (big) hipLaunchKernelGGL(kp_gemm_big<0>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes, st, g);
-    else     hipLaunchKernelGGL(kp_gemm_small<0>, dim3(n_wg), dim3(256), 0, st, g);
+    if (big) return launch_big_w<0>(s.waves, g, n_wg, 0, st);
+    hipLaunchKernelGGL(kp_gemm_small<0>, dim3(n_wg), dim3(256), 0, st, g);
     KP_HIP_TRY(hipGetLastError());
     return KP_OK;
   }
@@ -393,13 +420,9 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
   const bool lean = !flush && regions == (1u << s.regions) - 1u;  // every region, circular: lean record sites
-  if (big) {
-    if (lean) hipLaunchKernelGGL(kp_gemm_big<2>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
-    else      hipLaunchKernelGGL(kp_gemm_big<1>, dim3(n_wg), dim3(kBigThreads), kBigTileBytes + ring_bytes, st, g);
-  } else {
-    if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
-    else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);
-  }
+  if (big) return lean ? launch_big_w<2>(s.waves, g, n_wg, ring_bytes, st) : launch_big_w<1>(s.waves, g, n_wg, ring_bytes, st);
+  if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+  else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }

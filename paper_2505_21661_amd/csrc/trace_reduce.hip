@@ -19,8 +19,6 @@
 // Decoder workgroups are persistent; totals live in LDS and reach HBM once per workgroup.
 #include "kp_common.h"
 
-#include <cstdlib>
-
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -59,15 +57,7 @@ struct DecodeParams {
   uint64_t* out;
   uint32_t n_wg, W, R, cap, cap_log2, rec_cost, flush;
   uint32_t nrec, span, ncell;
-  uint32_t dbg;
 };
-#ifdef KP_DBG
-#define KP_SKIP(bit) (p.dbg & (bit))
-#define KP_TICK(i) do { if (tid == 0) { unsigned long long now_ = __builtin_readcyclecounter(); dbg_acc[i] += now_ - dbg_last; dbg_last = now_; } } while (0)
-#else
-#define KP_SKIP(bit) false
-#define KP_TICK(i) do {} while (0)
-#endif
 
 struct LdsLayout {  // byte offsets
   uint32_t ts, om, grid, hist, oacc, reg_sum, reg_max, reg_min, pw_pack, pw_max, pw_min, ctr, tmp,
@@ -261,12 +251,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   if (tid < 16) ctr[tid] = 0;
   __syncthreads();
 
-#ifdef KP_DBG
-  unsigned long long dbg_acc[12] = {0}; unsigned long long dbg_last = __builtin_readcyclecounter();
-#endif
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
-    KP_TICK(0);
     // ---- workgroup header -----------------------------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
@@ -298,8 +284,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       reinterpret_cast<uint32_t*>(grid)[i] = V | (V << 16);
     }
     if (tid == 0) { tmp[T_SPANOVF] = wave_tot[0]; tmp[T_SHIFT] = wave_tot[1]; }
-
-    KP_TICK(1);
     // ---- A: load and scatter by rank ------------------------------------------------------
     {
       const u32x4* rec = p.records + (size_t)wg * (nrec / 2);
@@ -343,7 +327,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_DISORDER, c_dis);
     }
     __syncthreads();
-    KP_TICK(2);
     // ---- occupancy check: a duplicated seq leaves fewer occupied ranks than valid records ----
     {
       uint32_t occ = 0;
@@ -381,8 +364,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       __syncthreads();
     }
-
-    KP_TICK(3);
     // ---- B: pairing, durations, per-(wave,region) statistics, monotonicity --------------------
     // An END is paired iff the nearest earlier record of its (wave, region) is a START; every
     // START that is not claimed this way is an orphan, so only ENDs have to search, and in
@@ -438,12 +419,10 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           const uint32_t d_raw = t0 - pt;
           const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
           const uint32_t e = w * R + region;
-          if (!KP_SKIP(1)) {
           atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
           atomicMax(&pw_max[e], d);
           atomicMin(&pw_min[e], d);
           atomicAdd(&hist[region * 64 + (d ? 31 - __clz(d) : 0)], 1u);
-          }
         }
       }
       add_tmp(tmp, T_NONMONO, c_nonmono);
@@ -452,7 +431,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_ORPH_E, c_ends);
     }
     __syncthreads();
-    KP_TICK(4);
     // ---- C1: XOR of the paired region bits of every span ---------------------------------------
     {
       uint32_t x = 0;
@@ -465,12 +443,10 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       if (lane == 0) wave_tot[hw] = x;
     }
     __syncthreads();
-
-    KP_TICK(5);
     const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - tmp[T_OCCUPIED]);
     const bool eligible = !tmp[T_SPANOVF] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
 
-    if (eligible && !KP_SKIP(2)) {
+    if (eligible) {
       const uint32_t shift = tmp[T_SHIFT];
       // ---- C2: open-region mask before every position (exclusive XOR scan per wave) ------------
       // ---- D : coarse time -> position table ------------------------------------------------------
@@ -513,16 +489,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         }
       }
       __syncthreads();
-      KP_TICK(6);
       // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
-      if (!KP_SKIP(8)) {
-        if (W <= 4)      sweep_cells<4, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
-        else             sweep_cells<16, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
-      }
+      if (W <= 4)      sweep_cells<4, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
+      else if (W <= 8) sweep_cells<8, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
+      else             sweep_cells<16, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
     }
     __syncthreads();
-    KP_TICK(7);
 
     // ---- F: per-(workgroup, wave, region) output, fold into running totals ------------------------
     for (uint32_t e = tid; e < W * R; e += BLOCK) {
@@ -552,11 +524,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
     }
     __syncthreads();
-    KP_TICK(8);
   }
-#ifdef KP_DBG
-  if (tid == 0 && blockIdx.x == 7) printf("phase ticks: top %llu hdr %llu A %llu occ %llu B %llu C1 %llu C2D %llu E %llu F %llu\n", dbg_acc[0], dbg_acc[1], dbg_acc[2], dbg_acc[3], dbg_acc[4], dbg_acc[5], dbg_acc[6], dbg_acc[7], dbg_acc[8]);
-#endif
 
   // ---- flush this decoder workgroup's totals --------------------------------------------------
   unsigned long long* out = reinterpret_cast<unsigned long long*>(p.out);
@@ -646,10 +614,6 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     p.cap_log2 = 0; while ((1u << p.cap_log2) < cap) ++p.cap_log2;
     p.rec_cost = h.rec_cost; p.flush = h.flags & KP_FLAG_FLUSH;
     p.nrec = nrec; p.span = span; p.ncell = ncell;
-    p.dbg = 0;
-#ifdef KP_DBG
-    if (const char* e = getenv("KP_DBG")) p.dbg = (uint32_t)atoi(e);
-#endif
     kp_status st;
     if (mask_bytes == 2) {
       st = block == 1024 ? launch_main<uint16_t, 1024>(p, L.total, s)
