@@ -38,11 +38,10 @@ constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
 constexpr uint32_t kKBytes = kBkv * kD * 2;   // K tile   [64 kv][128 d]
 constexpr uint32_t kVBytes = kD * kBkv * 2;   // V^T tile [128 d][64 kv]
 
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return u >> 16;
+  const __bf16 h = (__bf16)f;
+  return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
 // K tile: rows of 256 bytes (16 chunks of 16 B); V^T tile: rows of 128 bytes (8 chunks).
@@ -178,11 +177,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         pk[tk][v >> 1] = b0 | (b1 << 16);
       }
     l_run = l_run * alpha + psum;
+    // the running maximum settles after a few tiles; skip the rescale when no row of this wave moved
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0ull) {
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+    }
     m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
     KP_BOUNDARY(ring, 1, 2);
 
     // ---- region 2: O^T += V^T P^T ---------------------------------------------------------------------
