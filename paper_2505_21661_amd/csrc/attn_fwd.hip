@@ -5,7 +5,8 @@
 // the softmax of every KV iteration (Sec. 5.2, Table 3: GEMM0 = Q K^T, softmax, GEMM1 = P V).
 // This is the library's own MFMA kernel with the same three regions per KV tile of 64:
 //   region 0  S^T = K Q^T     (MFMA)
-//   region 1  online softmax   (VALU, fp32)
+//   region 1  online softmax   (VALU, fp32); opens with the barrier and LDS writes that stage the
+//             next K tile, which overlap the other waves' softmax
 //   region 2  O^T += V^T P^T   (MFMA)
 // One workgroup = 4 waves = 128 query rows of one (batch, head); each wave owns 32 rows.  The
 // products are formed transposed so that a lane holds all scores of ONE query row: the row
@@ -44,11 +45,17 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
 
-// K tile: rows of 256 bytes (16 chunks of 16 B); V^T tile: rows of 128 bytes (8 chunks).
-// Chunk c of row r is stored at chunk position c ^ (r & 7) so 16-byte reads of 8 neighbouring
-// rows cover all LDS banks.
+// K tile: rows of 256 bytes (16 chunks of 16 B), chunk c of row r at position c ^ (r & 7) so that
+// 16-byte reads of 8 neighbouring rows cover all LDS banks.
 __device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return row * 256u + ((chunk ^ (row & 7u)) << 4); }
-__device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) { return row * 128u + ((chunk ^ (row & 7u)) << 4); }
+// V^T tile: rows of 128 bytes (8 chunks of 16 B).  Within each group of 16 kv the four quads are
+// stored in the order 0, 2, 1, 3, so chunk 2g + h holds exactly the eight kv an MFMA step of the
+// P V product takes from lane half h.  The position also folds in row >> 3, because the transposing
+// writes hit rows that are 8 apart; rows 64..127 keep the two 8-byte halves of a chunk swapped so
+// that those writes spread over all banks.
+__device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) {
+  return row * 128u + ((chunk ^ ((row ^ (row >> 3)) & 7u)) << 4);
+}
 
 // END of one region and/or START of the next with a single clock sample.  INSTR: 0 no record sites,
 // 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
@@ -86,33 +93,35 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   // global -> LDS mapping
   // K: 64 rows x 16 chunks; thread takes chunk (tid & 15) of rows (tid >> 4) + 16*i
   const uint32_t k_row = tid >> 4, k_chunk = tid & 15u;
-  // V: tasks (kv group of 8, d pair): id = tid + 256*j, group = id >> 6, pair = id & 63
-  const uint32_t v_pair = tid & 63u, v_grp0 = tid >> 6;  // second task: group + 4
-  u32x4 k_reg[4];
-  uint32_t v_reg[2][8];
-  auto load_tile = [&](uint32_t kv0) {
+  // V: thread takes 8 d (group tid & 15) of 4 consecutive kv (quad tid >> 4) and writes them transposed
+  const uint32_t v_dg = tid & 15u, v_kq = tid >> 4;
+  u32x4 k_reg[4], v_reg[4];
+  auto load_k = [&](uint32_t kv0) {
     const uint16_t* kp_ = g.K + head + (size_t)(kv0 + k_row) * kD + k_chunk * 8;
 #pragma unroll
     for (int i = 0; i < 4; ++i) k_reg[i] = *reinterpret_cast<const u32x4*>(kp_ + (size_t)(16 * i) * kD);
-    const uint16_t* vp = g.V + head + (size_t)(kv0 + v_grp0 * 8) * kD + v_pair * 2;
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 8; ++r) v_reg[j][r] = *reinterpret_cast<const uint32_t*>(vp + (size_t)(32 * j + r) * kD);
   };
-  auto store_tile = [&]() {
+  auto load_v = [&](uint32_t kv0) {
+    const uint16_t* vp = g.V + head + (size_t)(kv0 + v_kq * 4) * kD + v_dg * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v_reg[i] = *reinterpret_cast<const u32x4*>(vp + (size_t)i * kD);
+  };
+  auto store_k = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(sK + k_off(k_row + 16 * i, k_chunk)) = k_reg[i];
+  };
+  auto store_v = [&]() {
+    const uint32_t chunk = (v_kq >> 2) * 2u + (v_kq & 1u);
+    const uint32_t half = ((v_kq >> 1) ^ (v_dg >> 3)) & 1u;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t* bv = v_reg[j];
-      u32x4 lo, hi;  // d = 2*pair and 2*pair+1, eight consecutive kv each
-      lo.x = (bv[0] & 0xFFFFu) | (bv[1] << 16); hi.x = (bv[0] >> 16) | (bv[1] & 0xFFFF0000u);
-      lo.y = (bv[2] & 0xFFFFu) | (bv[3] << 16); hi.y = (bv[2] >> 16) | (bv[3] & 0xFFFF0000u);
-      lo.z = (bv[4] & 0xFFFFu) | (bv[5] << 16); hi.z = (bv[4] >> 16) | (bv[5] & 0xFFFF0000u);
-      lo.w = (bv[6] & 0xFFFFu) | (bv[7] << 16); hi.w = (bv[6] >> 16) | (bv[7] & 0xFFFF0000u);
-      *reinterpret_cast<u32x4*>(sV + v_off(v_pair * 2, v_grp0 + 4 * j)) = lo;
-      *reinterpret_cast<u32x4*>(sV + v_off(v_pair * 2 + 1, v_grp0 + 4 * j)) = hi;
+    for (int j = 0; j < 4; ++j) {  // word j of every row: d = 8*dg + 2j (low half) and 2j + 1 (high half)
+      const uint32_t w0 = v_reg[0][j], w1 = v_reg[1][j], w2 = v_reg[2][j], w3 = v_reg[3][j];
+      u32x2 ev, od;
+      ev.x = (w0 & 0xFFFFu) | (w1 << 16); ev.y = (w2 & 0xFFFFu) | (w3 << 16);
+      od.x = (w0 >> 16) | (w1 & 0xFFFF0000u); od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
+      const uint32_t d = v_dg * 8u + 2u * (uint32_t)j;
+      *reinterpret_cast<u32x2*>(sV + v_off(d, chunk) + 8u * half) = ev;
+      *reinterpret_cast<u32x2*>(sV + v_off(d + 1u, chunk) + 8u * half) = od;
     }
   };
 
@@ -122,14 +131,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   float m_run = -INFINITY, l_run = 0.f;
 
   const uint32_t n_tiles = g.causal ? (q0 + kBq) / kBkv : g.S / kBkv;
-  load_tile(0);
+  // Staging is split so that it overlaps the other waves' arithmetic: the K tile is only read by
+  // region 0 and the V^T tile only by region 2, so tile t+1 of K is written after the barrier that
+  // follows region 0 of tile t, and tile t+1 of V after the barrier that follows region 2.
+  load_k(0);
+  load_v(0);
+  store_k();
+  store_v();
+  if (n_tiles > 1) { load_k(kBkv); load_v(kBkv); }
+  __syncthreads();
   for (uint32_t t = 0; t < n_tiles; ++t) {
     const uint32_t kv0 = t * kBkv;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // every wave is done with the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < n_tiles) load_tile(kv0 + kBkv);  // in flight during the three regions below
 
     // ---- region 0: S^T = K Q^T --------------------------------------------------------------------
     KP_BOUNDARY(ring, kp::kNoRegion, 0);
@@ -145,23 +157,28 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     }
     KP_BOUNDARY(ring, 0, 1);
 
+    // every wave is done with K tile t; the next one goes to LDS while the softmax runs
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      store_k();
+      if (t + 2 < n_tiles) load_k(kv0 + 2 * kBkv);
+    }
+
     // ---- region 1: online softmax (this lane: query row qrow, 32 of the tile's 64 kv) -------------
     const bool diag = g.causal && (kv0 + kBkv > q0 + wave * 32);  // tile reaches past this wave's first row
-    float mx = -INFINITY;
+    float mx = -INFINITY;  // maximum of the raw scores; the positive scale is applied afterwards
 #pragma unroll
     for (int tk = 0; tk < 2; ++tk)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float sv = sacc[tk][v] * g.scale_log2;
         if (diag) {
           const uint32_t kv = kv0 + 32 * tk + 8 * (v >> 2) + 4 * h32 + (v & 3);
-          if (kv > qrow) sv = -INFINITY;
+          if (kv > qrow) sacc[tk][v] = -INFINITY;
         }
-        sacc[tk][v] = sv;
-        mx = fmaxf(mx, sv);
+        mx = fmaxf(mx, sacc[tk][v]);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
+    const float m_new = fmaxf(m_run, mx * g.scale_log2);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // m_new is finite: kv = 0 is visible to every row
     float psum = 0.f;
     uint32_t pk[2][8];  // P as packed bf16 pairs, in accumulator order
@@ -169,12 +186,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     for (int tk = 0; tk < 2; ++tk)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(sacc[tk][v] - m_new);
-        const float p1 = __builtin_amdgcn_exp2f(sacc[tk][v + 1] - m_new);
-        const uint32_t b0 = bf16_rne(p0), b1 = bf16_rne(p1);
-        // the sum uses the rounded values that enter the P V product
-        psum += __uint_as_float(b0 << 16) + __uint_as_float(b1 << 16);
-        pk[tk][v >> 1] = b0 | (b1 << 16);
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v], g.scale_log2, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v + 1], g.scale_log2, -m_new));
+        psum += p0 + p1;  // fp32 sum of the unrounded probabilities
+        pk[tk][v >> 1] = bf16_rne(p0) | (bf16_rne(p1) << 16);
       }
     l_run = l_run * alpha + psum;
     // the running maximum settles after a few tiles; skip the rescale when no row of this wave moved
@@ -200,15 +215,18 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
           const uint32_t row = 32 * dt + l32;
-          const uint32_t c1 = 4 * tk + 2 * s;
-          u32x4 vw;
-          const u32x2 a = *reinterpret_cast<const u32x2*>(sV + v_off(row, c1) + 8 * h32);
-          const u32x2 b = *reinterpret_cast<const u32x2*>(sV + v_off(row, c1 + 1) + 8 * h32);
-          vw.x = a.x; vw.y = a.y; vw.z = b.x; vw.w = b.y;
+          u32x4 vw = *reinterpret_cast<const u32x4*>(sV + v_off(row, 4 * tk + 2 * s + h32));
+          if (dt >= 2) vw = u32x4{vw.z, vw.w, vw.x, vw.y};  // rows 64.. store the chunk halves swapped
           oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, oacc[dt], 0, 0, 0);
         }
       }
     KP_BOUNDARY(ring, 2, kp::kNoRegion);
+
+    __syncthreads();  // every wave is done with V^T tile t, and K tile t+1 is visible
+    if (t + 1 < n_tiles) {
+      store_v();
+      if (t + 2 < n_tiles) load_v(kv0 + 2 * kBkv);
+    }
   }
 
   // epilogue: O[q][d] = O^T[d][q] / l
