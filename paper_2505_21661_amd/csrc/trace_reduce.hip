@@ -3,17 +3,19 @@
 // The paper stores START/END records unpaired, per warp, in a ring whose tail survives, and
 // aligns them at "trace replay" on the host (Sec. 4.2 "SM-level Data Layout", "Shared Memory
 // Circular Buffer"; Sec. 4.3).  Here replay runs on the GPU: one decoder workgroup stages one
-// recorded workgroup's records in LDS and
+// recorded workgroup's records in LDS as (clock, metadata) pairs and
 //   A  scatters every record to its rank (seq - first surviving seq), which undoes ring
 //      rotation and out-of-order flushes in O(1) per record,
 //   B  pairs each START with the next record of the same (wave, region) when that is an END,
 //      takes d = (u32)(ts_end - ts_start) minus the constant record cost (Sec. 4.3), and
-//      accumulates the per-(wave, region) sums and the log2 histogram with LDS atomics,
+//      accumulates the per-(wave, region) sums and the log2 histogram with LDS atomics; the
+//      four ranks an END looks back at come from neighbouring lanes, not from LDS,
 //   C  XOR-scans the paired region bits of each wave into an "open regions" mask per position,
-//   D  builds a coarse time -> position table per wave,
-//   E  looks every paired event up in the other waves to find the set of regions active in the
-//      workgroup at that instant, and, when the event switches its region on or off for the
-//      whole workgroup, adds -t / +t to the region-pair accumulators (the integral of
+//   D  builds a coarse time -> position table per wave and orders the time cells by how many
+//      records they hold, so that the lanes of a wave get cells of similar length,
+//   E  sweeps every time cell in clock order, one lane per cell, keeping a bit-sliced count of
+//      the waves that have each region open; when a record switches its region on or off for
+//      the whole workgroup, -t / +t goes to the region-pair accumulators (the integral of
 //      A_a(t)*A_b(t) collapses to a signed sum over its switching times),
 //   F  writes the per-(workgroup, wave, region) results and folds them into running totals.
 // Decoder workgroups are persistent; totals live in LDS and reach HBM once per workgroup.
@@ -34,7 +36,7 @@ enum { H_SLOTS_VALID = 0, H_PAIRS, H_ORPHAN_START, H_ORPHAN_END, H_INVALID, H_DR
 
 // per-workgroup temporaries (u32 words in LDS)
 enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_ORPH_S, T_ORPH_E,
-       T_SPANOVF, T_SHIFT, T_COUNT };
+       T_WIDE, T_COUNT };
 
 struct StatsLayout {  // offsets in u64 words
   size_t hist, cnt, sum, min, max, U, O, F, per, total;
@@ -56,21 +58,22 @@ struct DecodeParams {
   const u32x4* records;     // two records per 16-byte load
   uint64_t* out;
   uint32_t n_wg, W, R, cap, cap_log2, rec_cost, flush;
-  uint32_t nrec, span, ncell;
+  uint32_t nrec, span, span_log2, ncell, pos_bits;
 };
 
 struct LdsLayout {  // byte offsets
-  uint32_t ts, om, grid, hist, oacc, reg_sum, reg_max, reg_min, pw_pack, pw_max, pw_min, ctr, tmp,
-      v, first, wave_tot, total;
+  uint32_t rec, grid, perm, cinfo, bucket, hist, oacc, reg_sum, reg_max, reg_min, pw_pack, pw_max,
+      pw_min, ctr, tmp, misc, v, first, wave_tot, total;
 };
 __host__ __device__ inline uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
-__host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint32_t R, uint32_t ncell,
-                                                uint32_t mask_bytes, uint32_t block) {
+__host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint32_t R, uint32_t ncell, uint32_t block) {
   LdsLayout l;
   uint32_t o = 0;
-  l.ts = o; o = align16(o + nrec * 4);
-  l.om = o; o = align16(o + nrec * mask_bytes);
-  l.grid = o; o = align16(o + W * ncell * 2);
+  l.rec = o; o = align16(o + (nrec + 1) * 8);          // one zero entry past the last position
+  l.grid = o; o = align16(o + W * (ncell + 1) * 2);    // one entry past the last cell per wave
+  l.perm = o; o = align16(o + ncell * 2);
+  l.cinfo = o; o = align16(o + ncell * 2);
+  l.bucket = o; o = align16(o + 64 * 4);
   l.hist = o; o = align16(o + R * 64 * 4);
   l.oacc = o; o = align16(o + R * R * 8);
   l.reg_sum = o; o = align16(o + R * 8);
@@ -81,6 +84,7 @@ __host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint3
   l.pw_min = o; o = align16(o + W * R * 4);
   l.ctr = o; o = align16(o + 16 * 8);
   l.tmp = o; o = align16(o + T_COUNT * 4);
+  l.misc = o; o = align16(o + 4 * 4);
   l.v = o; o = align16(o + 16 * 4);
   l.first = o; o = align16(o + 16 * 4);
   l.wave_tot = o; o = align16(o + (block / 64) * 4);
@@ -97,6 +101,23 @@ __device__ inline uint32_t wave_sum(uint32_t v) {
 __device__ inline void add_tmp(uint32_t* tmp, int which, uint32_t v) {
   v = wave_sum(v);
   if ((threadIdx.x & 63) == 0 && v) atomicAdd(&tmp[which], v);
+}
+
+// Lane l receives the value of lane l-1; lane 0 receives `lane0` (DPP wave shift right by one).
+__device__ __forceinline__ uint32_t wave_shr1(uint32_t v, uint32_t lane0) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)lane0, (int)v, 0x138, 0xF, 0xF, false);
+}
+
+// Inclusive XOR scan over the 64 lanes: four shifts inside each row of 16, then the last lane of
+// row 0/2 into row 1/3 and the last lane of the lower half into the upper half.
+__device__ __forceinline__ uint32_t wave_xor_scan(uint32_t v) {
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
+  return v;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -142,64 +163,89 @@ __global__ void kp_reduce_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uin
 
 // ------------------------------------------------------------------------------------------
 // Overlap sweep.  One lane owns one time cell and merges the W per-wave record runs that fall
-// into it in the total order (clock, wave, rank), carrying every wave's open-region mask.  When
-// a paired record switches its region on or off for the whole workgroup (no other wave has it
-// open), -t or +t goes to the region-pair accumulators of all regions active at that instant:
-// the integral of A_a(t)*A_b(t) collapses to a signed sum over its switching times.
-template <int WMAX, typename MaskT>
-__device__ __forceinline__ void sweep_cells(const uint32_t* ts, const MaskT* om, const uint16_t* grid,
-                                            const uint32_t* sV, unsigned long long* oacc, uint32_t W,
-                                            uint32_t R, uint32_t cl2, uint32_t nrec, uint32_t ncell,
-                                            uint32_t shift, uint32_t tid, uint32_t nthreads) {
-  const uint32_t capm = (1u << cl2) - 1u;
-  for (uint32_t c = tid; c < ncell; c += nthreads) {
-    unsigned long long key[WMAX];  // (clock << 32) | position of each wave's next record; ~0 = none
-    uint32_t msk[WMAX];            // regions each wave has open right now
+// into it in the total order (clock, wave, rank).  The number of waves that have each region open
+// is kept bit-sliced: plane k holds bit k of every region's count, so "some wave has it open" is
+// the OR of the planes and one record costs a ripple of PLANES steps.  When a paired record takes
+// its region's count from 0 to 1 or from 1 to 0, -t or +t goes to the region-pair accumulators of
+// all regions active at that instant.
+//
+// A merge key is (clock, position).  The narrow form keeps the clock relative to the start of the
+// cell above `pos_bits` bits of position in one 32-bit word; it needs every clock of the cell to
+// be below the cell's end and cell width * positions to fit 32 bits.  The wide form is 64 bits.
+template <typename KeyT> struct SweepKey;
+template <> struct SweepKey<uint32_t> {
+  static __device__ __forceinline__ uint32_t make(uint32_t t, uint32_t pos, uint32_t cbase, uint32_t pb) { return ((t - cbase) << pb) | pos; }
+  static __device__ __forceinline__ uint32_t pos(uint32_t k, uint32_t pmask) { return k & pmask; }
+  static __device__ __forceinline__ uint32_t clock(uint32_t k, uint32_t cbase, uint32_t pb) { return cbase + (k >> pb); }
+};
+template <> struct SweepKey<unsigned long long> {
+  static __device__ __forceinline__ unsigned long long make(uint32_t t, uint32_t pos, uint32_t, uint32_t) { return ((unsigned long long)t << 32) | pos; }
+  static __device__ __forceinline__ uint32_t pos(unsigned long long k, uint32_t) { return (uint32_t)k; }
+  static __device__ __forceinline__ uint32_t clock(unsigned long long k, uint32_t, uint32_t) { return (uint32_t)(k >> 32); }
+};
+
+template <int WMAX, int PLANES, typename KeyT>
+__device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* grid, const uint16_t* perm,
+                                            unsigned long long* oacc, uint32_t W, uint32_t R, uint32_t cl2,
+                                            uint32_t pb, uint32_t ncell, uint32_t shift, uint32_t tid,
+                                            uint32_t nthreads) {
+  typedef SweepKey<KeyT> K;
+  const KeyT none = ~(KeyT)0;
+  const uint32_t capm = (1u << cl2) - 1u, pmask = (1u << pb) - 1u, gstride = ncell + 1;
+  for (uint32_t i = tid; i < ncell; i += nthreads) {
+    const uint32_t c = perm[i];
+    const uint32_t cbase = c << shift;
+    KeyT key[WMAX];        // each wave's next record in this cell; all-ones = none
+    uint32_t pl[PLANES];   // bit-sliced count of the waves that have each region open
+#pragma unroll
+    for (int k = 0; k < PLANES; ++k) pl[k] = 0u;
     uint32_t n = 0;
 #pragma unroll
     for (int w = 0; w < WMAX; ++w) {
-      key[w] = ~0ull; msk[w] = 0u;
+      key[w] = none;
       if ((uint32_t)w < W) {
-        const uint32_t V = sV[w];
-        const uint32_t g0 = grid[w * ncell + c];
-        const uint32_t g1r = grid[w * ncell + (c + 1 < ncell ? c + 1 : c)];
-        const uint32_t g1 = (c + 1 < ncell) ? g1r : V;
-        const uint32_t i0 = ((uint32_t)w << cl2) + g0;
-        const uint32_t ic = i0 < nrec ? i0 : nrec - 1;
-        const uint32_t m = om[ic], t = ts[ic];
-        msk[w] = g0 < V ? m : 0u;
-        key[w] = g0 < g1 ? (((unsigned long long)t << 32) | i0) : ~0ull;
+        const uint32_t g0 = grid[w * gstride + c], g1 = grid[w * gstride + c + 1];
+        const uint32_t pos = ((uint32_t)w << cl2) + g0;
+        const uint2 r = rec[pos];  // metadata = regions this wave has open before rank g0
+        uint32_t carry = r.y;
+#pragma unroll
+        for (int k = 0; k < PLANES; ++k) { const uint32_t t = pl[k] & carry; pl[k] ^= carry; carry = t; }
+        key[w] = g0 < g1 ? K::make(r.x, pos, cbase, pb) : none;
         n += g1 - g0;
       }
     }
     for (; n; --n) {
-      unsigned long long best = key[0];
+      KeyT best = key[0];
 #pragma unroll
       for (int w = 1; w < WMAX; ++w) best = key[w] < best ? key[w] : best;
-      const uint32_t idx = (uint32_t)best, tt = (uint32_t)(best >> 32);
-      const uint32_t b = idx >> cl2, pos = idx & capm, V = sV[b];
-      const uint32_t inx = idx + 1 < nrec ? idx + 1 : idx;
-      const uint32_t before = om[idx];
-      const uint32_t nm = om[inx], nts = ts[inx];
-      const bool more = pos + 1 < V;
-      const uint32_t after = more ? nm : 0u;
-      const uint32_t nc0 = nts >> shift;
-      const uint32_t ncl = nc0 < ncell ? nc0 : ncell - 1;
-      const unsigned long long nkey = (more && ncl == c) ? (((unsigned long long)nts << 32) | (idx + 1)) : ~0ull;
-      uint32_t others = 0;
+      const uint32_t pos = K::pos(best, pmask), tt = K::clock(best, cbase, pb);
+      const uint32_t b = pos >> cl2;
+      const uint32_t g1 = grid[b * gstride + c + 1];
+      const uint2 cur = rec[pos], nxt = rec[pos + 1];
+      const bool more = (pos & capm) + 1u < g1;
+      const KeyT nkey = more ? K::make(nxt.x, pos + 1u, cbase, pb) : none;
 #pragma unroll
-      for (int w = 0; w < WMAX; ++w) {
-        const bool sel = (uint32_t)w == b;
-        others |= sel ? 0u : msk[w];
-        msk[w] = sel ? after : msk[w];
-        key[w] = sel ? nkey : key[w];
+      for (int w = 0; w < WMAX; ++w) key[w] = key[w] == best ? nkey : key[w];
+      const uint32_t x = cur.y ^ nxt.y;  // the region bit this record toggles; 0 if unpaired
+      const bool is_end = (cur.y & x) != 0u;
+      uint32_t act_before = pl[0];
+#pragma unroll
+      for (int k = 1; k < PLANES; ++k) act_before |= pl[k];
+      {  // count[region] += 1 (START) or -= 1 (END)
+        const uint32_t dm = is_end ? 0xFFFFFFFFu : 0u;
+        uint32_t carry = x;
+#pragma unroll
+        for (int k = 0; k < PLANES; ++k) { const uint32_t o = pl[k]; pl[k] = o ^ carry; carry &= o ^ dm; }
       }
-      const uint32_t x = before ^ after;  // the region bit this record toggles; 0 if unpaired
-      if (x && !(others & x)) {
+      uint32_t act_after = pl[0];
+#pragma unroll
+      for (int k = 1; k < PLANES; ++k) act_after |= pl[k];
+      const uint32_t act = is_end ? act_after : act_before;  // active regions other than this one
+      if (x & ~act) {  // the region was off before this START / is off after this END
         const uint32_t a = __ffs(x) - 1;
-        const unsigned long long val = (before & x) ? (unsigned long long)tt : (0ull - (unsigned long long)tt);
+        const unsigned long long val = is_end ? (unsigned long long)tt : (0ull - (unsigned long long)tt);
         atomicAdd(&oacc[a * R + a], val);
-        uint32_t set = (others | before) & ~x;
+        uint32_t set = act;
         while (set) {
           const uint32_t bb = __ffs(set) - 1;
           set &= set - 1;
@@ -211,16 +257,25 @@ __device__ __forceinline__ void sweep_cells(const uint32_t* ts, const MaskT* om,
 }
 
 // ------------------------------------------------------------------------------------------
-// Position p = wave*cap_wave + rank indexes the LDS arrays.  Every hardware wave of the decoder
-// owns `span` consecutive positions and walks them 64 at a time, lane l taking position
-// base + 64*round + l, so that neighbouring lanes touch neighbouring LDS words.
-template <typename MaskT, int BLOCK>
+// Position p = wave*cap_wave + rank indexes the staged records.  Every hardware wave of the
+// decoder owns `span` consecutive positions and walks them 64 at a time, lane l taking position
+// base + 64*round + l, so that neighbouring lanes hold neighbouring ranks.
+//
+// Staged metadata word: bits 4:0 region, 5 END, 6 valid, 7 paired, 31:16 generation.  With at
+// most 16 regions the staging area is not cleared between workgroups: a word counts only when
+// its generation is the current one (the open-region masks that phase C leaves behind have
+// generation 0, which is never current).  With more regions the masks reach into those bits, so
+// the area is cleared for every workgroup and the generation stays 0.
+template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const LdsLayout L = lds_layout(p.nrec, p.W, p.R, p.ncell, sizeof(MaskT), BLOCK);
-  uint32_t* ts = reinterpret_cast<uint32_t*>(smem + L.ts);
-  MaskT* om = reinterpret_cast<MaskT*>(smem + L.om);
+  const LdsLayout L = lds_layout(p.nrec, p.W, p.R, p.ncell, BLOCK);
+  uint2* rec = reinterpret_cast<uint2*>(smem + L.rec);
+  uint32_t* recw = reinterpret_cast<uint32_t*>(smem + L.rec);  // word 2p = clock, 2p+1 = metadata
   uint16_t* grid = reinterpret_cast<uint16_t*>(smem + L.grid);
+  uint16_t* perm = reinterpret_cast<uint16_t*>(smem + L.perm);
+  uint16_t* cinfo = reinterpret_cast<uint16_t*>(smem + L.cinfo);
+  uint32_t* bucket = reinterpret_cast<uint32_t*>(smem + L.bucket);
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
   unsigned long long* oacc = reinterpret_cast<unsigned long long*>(smem + L.oacc);
   unsigned long long* reg_sum = reinterpret_cast<unsigned long long*>(smem + L.reg_sum);
@@ -231,13 +286,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L.pw_min);
   unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L.ctr);
   uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
+  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell shift
   uint32_t* sV = reinterpret_cast<uint32_t*>(smem + L.v);
   uint32_t* sFirst = reinterpret_cast<uint32_t*>(smem + L.first);
   uint32_t* wave_tot = reinterpret_cast<uint32_t*>(smem + L.wave_tot);
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, hw = tid >> 6;
   const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec, ncell = p.ncell;
-  const uint32_t capm = cap - 1, cl2 = p.cap_log2;
+  const uint32_t capm = cap - 1, cl2 = p.cap_log2, gstride = ncell + 1;
   const uint32_t span = p.span;              // positions per hardware wave, power of two >= 64
   const uint32_t pbase = hw * span;
   const uint32_t pend = pbase + span < nrec ? pbase + span : nrec;  // may be <= pbase: idle wave
@@ -249,10 +305,15 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   for (uint32_t i = tid; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
   for (uint32_t i = tid; i < W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
   if (tid < 16) ctr[tid] = 0;
+  if (tid == 0) rec[nrec] = make_uint2(0u, 0u);
   __syncthreads();
 
-  for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
+  uint32_t iter = 0;
+  for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x, ++iter) {
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
+    const uint32_t gen = R > 16 ? 0u : 1u + iter % 0xFFFFu;
+    const uint32_t live_tag = (gen << 16) | kMValid, live_mask = 0xFFFF0000u | kMValid;
+    auto is_live = [&](uint32_t m) { return (m & live_mask) == live_tag; };
     // ---- workgroup header -----------------------------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
@@ -263,30 +324,27 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       atomicAdd(&ctr[H_SLOTS_VALID], (unsigned long long)V);
     }
     if (tid >= 64 && tid < 64 + T_COUNT) tmp[tid - 64] = 0;
+    if (tid >= 128 && tid < 128 + BLOCK / 64) wave_tot[tid - 128] = 0;
+    if (tid >= 192 && tid < 256) bucket[tid - 192] = 0;
     if (tid == 32) {
       const uint64_t tb = (uint64_t)wh[2] | ((uint64_t)wh[3] << 32);
       const uint64_t te = (uint64_t)wh[4] | ((uint64_t)wh[5] << 32);
       const uint64_t sp = te - tb;
       uint32_t shift = 0, ovf = 0;
       if (sp >> 32) ovf = 1; else while ((sp >> shift) >= ncell) ++shift;
-      wave_tot[0] = ovf;  // parked here until tmp[] has been cleared
-      wave_tot[1] = shift;
+      misc[0] = ovf;
+      misc[1] = shift;
     }
-    {
-      u32x4* z = reinterpret_cast<u32x4*>(om);
-      const uint32_t nz = (nrec * (uint32_t)sizeof(MaskT) + 15u) / 16u;
-      for (uint32_t i = tid; i < nz; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
+    if (R > 16 || gen == 1u) {  // clear the staging area (always on this workgroup's first pass)
+      u32x4* z = reinterpret_cast<u32x4*>(rec);
+      for (uint32_t i = tid; i < nrec / 2; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
-    // table default: "no record of this wave at or after this cell" (ncell is even)
-    for (uint32_t i = tid; i < W * ncell / 2; i += BLOCK) {
-      const uint32_t V = sV[(2 * i) / ncell];
-      reinterpret_cast<uint32_t*>(grid)[i] = V | (V << 16);
-    }
-    if (tid == 0) { tmp[T_SPANOVF] = wave_tot[0]; tmp[T_SHIFT] = wave_tot[1]; }
+    // table default: "no record of this wave at or after this cell"
+    for (uint32_t i = tid; i < W * gstride; i += BLOCK) grid[i] = (uint16_t)sV[i / gstride];
     // ---- A: load and scatter by rank ------------------------------------------------------
     {
-      const u32x4* rec = p.records + (size_t)wg * (nrec / 2);
+      const u32x4* recs = p.records + (size_t)wg * (nrec / 2);
       const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
       uint32_t c_invalid = 0, c_field = 0, c_dis = 0;
       for (uint32_t i0 = tid; i0 < n16; i0 += 4 * BLOCK) {
@@ -294,7 +352,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const uint32_t i = i0 + u * BLOCK;
-          v[u] = __builtin_nontemporal_load(rec + (i < n16 ? i : i0));
+          v[u] = __builtin_nontemporal_load(recs + (i < n16 ? i : i0));
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -315,10 +373,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
             c_invalid += (held && !good) ? 1u : 0u;
             c_field += good ? 1u : 0u;
             c_dis += (good && s != (seq & capm)) ? 1u : 0u;
-            if (good) {
-              ts[(w << cl2) + k] = pay;
-              om[(w << cl2) + k] = (MaskT)(region | ((tag >> 31) ? kMEnd : 0u) | kMValid);
-            }
+            if (good) rec[(w << cl2) + k] = make_uint2(pay, region | ((tag >> 31) ? kMEnd : 0u) | live_tag);
           }
         }
       }
@@ -330,7 +385,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // ---- occupancy check: a duplicated seq leaves fewer occupied ranks than valid records ----
     {
       uint32_t occ = 0;
-      for (uint32_t q = pbase + lane; q < pend; q += 64) occ += (om[q] & kMValid) ? 1u : 0u;
+      for (uint32_t q = pbase + lane; q < pend; q += 64) occ += is_live(recw[2 * q + 1]) ? 1u : 0u;
       add_tmp(tmp, T_OCCUPIED, occ);
     }
     __syncthreads();
@@ -338,7 +393,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // Rare: some seq occurs twice.  The later slot must win, so redo this workgroup's
       // scatter in slot order, one thread per wave.
       __syncthreads();
-      for (uint32_t i = tid; i < nrec; i += BLOCK) om[i] = 0;
+      for (uint32_t i = tid; i < nrec; i += BLOCK) recw[2 * i + 1] = 0;
       if (tid == 0) { tmp[T_DISORDER] = 0; tmp[T_OCCUPIED] = 0; }
       __syncthreads();
       if (tid < W) {
@@ -348,15 +403,15 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           const uint32_t tag = seg[2 * s];
           const uint32_t seq = tag & kSeqMask, k = (seq - first) & kSeqMask, region = (tag >> 24) & 0x7Fu;
           if (k >= V || ((tag >> 20) & 0xFu) != w || region >= R) continue;
-          ts[w * cap + k] = s;  // remember the winning slot for now
-          om[w * cap + k] = (MaskT)(region | ((tag >> 31) ? kMEnd : 0u) | kMValid);
+          // the clock word remembers the winning slot for now
+          rec[w * cap + k] = make_uint2(s, region | ((tag >> 31) ? kMEnd : 0u) | live_tag);
         }
         uint32_t dis = 0, occ = 0;
         for (uint32_t k = 0; k < V; ++k) {
-          if (!(om[w * cap + k] & kMValid)) continue;
-          const uint32_t s = ts[w * cap + k];
+          if (!is_live(recw[2 * (w * cap + k) + 1])) continue;
+          const uint32_t s = recw[2 * (w * cap + k)];
           dis += (s != ((seg[2 * s] & kSeqMask) & capm));
-          ts[w * cap + k] = seg[2 * s + 1];
+          recw[2 * (w * cap + k)] = seg[2 * s + 1];
           ++occ;
         }
         atomicAdd(&tmp[T_DISORDER], dis);
@@ -367,55 +422,68 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // ---- B: pairing, durations, per-(wave,region) statistics, monotonicity --------------------
     // An END is paired iff the nearest earlier record of its (wave, region) is a START; every
     // START that is not claimed this way is an orphan, so only ENDs have to search, and in
-    // traces of real kernels the START sits a few ranks back.  The four ranks just below are
-    // fetched unconditionally (clamped addresses); deeper searches are the rare slow path.
+    // traces of real kernels the START sits a few ranks back.  The metadata of the four ranks
+    // just below a lane's own comes from the lanes below it (the last four lanes of the previous
+    // round stand in for lanes 0..3); deeper searches are the rare slow path.  A pair whose
+    // START lies in an earlier hardware wave's span toggles the region bit of both spans'
+    // XOR totals, which phase C turns into each span's carry-in.
     {
-      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0;
+      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0, x_span = 0;
+      uint32_t cm[4], ct = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t back = pbase > (uint32_t)j ? (uint32_t)j + 1u : 0u;
+        const uint2 r = rec[pbase < nrec ? pbase - back : 0u];
+        cm[j] = (back && is_live(r.y)) ? r.y : 0u;
+        if (j == 0) ct = r.x;
+      }
       for (uint32_t qb = pbase; qb < pend; qb += 64) {
-        const uint32_t q0 = (qb + lane < pend) ? qb + lane : pend - 1;
-        const uint32_t m0 = (qb + lane < pend) ? (uint32_t)om[q0] : 0u;
-        const uint32_t t0 = ts[q0];
-        const uint32_t w = q0 >> cl2, wofs = w << cl2, k = q0 & capm;
-        const bool valid = (m0 & kMValid) != 0;
+        const bool in = qb + lane < pend;
+        const uint32_t q0 = in ? qb + lane : pend - 1;
+        const uint2 r0 = rec[q0];
+        const bool valid = in && is_live(r0.y);
+        const uint32_t m0 = valid ? r0.y : 0u, t0 = r0.x;
+        uint32_t m1 = wave_shr1(m0, cm[0]);
+        uint32_t m2 = wave_shr1(m1, cm[1]);
+        uint32_t m3 = wave_shr1(m2, cm[2]);
+        uint32_t m4 = wave_shr1(m3, cm[3]);
+        const uint32_t t1 = wave_shr1(t0, ct);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) cm[j] = (uint32_t)__builtin_amdgcn_readlane((int)m0, 63 - j);
+        ct = (uint32_t)__builtin_amdgcn_readlane((int)t0, 63);
+        const uint32_t k = q0 & capm, wofs = q0 - k, w = q0 >> cl2;
+        m1 = k > 0 ? m1 : 0u; m2 = k > 1 ? m2 : 0u; m3 = k > 2 ? m3 : 0u; m4 = k > 3 ? m4 : 0u;
         const uint32_t region = m0 & kMRegion;
-        uint32_t mp[4], tp[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t back = k > (uint32_t)j ? (uint32_t)j + 1u : 0u;  // 0: no such rank, reads itself
-          const uint32_t mm = om[q0 - back];
-          tp[j] = ts[q0 - back];
-          mp[j] = back ? mm : 0u;
-        }
-        // previous record of this wave (ranks can be missing after invalid records)
-        uint32_t tprev = t0;
-        bool have_prev = false;
-#pragma unroll
-        for (int j = 3; j >= 0; --j) { const bool v = (mp[j] & kMValid) != 0; tprev = v ? tp[j] : tprev; have_prev |= v; }
-        // nearest earlier record of the same region
-        uint32_t pm = 0, pt = 0, pq = q0;
-        bool have = false;
-#pragma unroll
-        for (int j = 3; j >= 0; --j) {
-          const bool hit = (mp[j] & kMValid) && (mp[j] & kMRegion) == region;
-          pm = hit ? mp[j] : pm; pt = hit ? tp[j] : pt; pq = hit ? q0 - 1 - j : pq; have |= hit;
-        }
-        const bool is_end = valid && (m0 & kMEnd);
-        if (valid && k > 4 && (!have_prev || (is_end && !have))) {  // slow path: look further back
-          for (uint32_t kk = k - 4; kk-- > 0;) {
-            const uint32_t mq = om[wofs + kk];
-            if (!(mq & kMValid)) continue;
-            if (!have_prev) { have_prev = true; tprev = ts[wofs + kk]; }
-            if (!is_end || have) break;
-            if ((mq & kMRegion) == region) { have = true; pm = mq; pt = ts[wofs + kk]; pq = wofs + kk; break; }
+        const bool is_end = (m0 & kMEnd) != 0u;  // m0 is 0 for a position that holds no record
+        const uint32_t want = kMValid | region, sel = kMValid | kMRegion;
+        const bool h1 = (m1 & sel) == want, h2 = (m2 & sel) == want, h3 = (m3 & sel) == want, h4 = (m4 & sel) == want;
+        bool have = h1 || h2 || h3 || h4;             // nearest earlier record of the same region
+        uint32_t pm = h1 ? m1 : (h2 ? m2 : (h3 ? m3 : m4));
+        uint32_t pq = q0 - (h1 ? 1u : (h2 ? 2u : (h3 ? 3u : 4u)));
+        bool have_prev = (m1 & kMValid) != 0u;        // previous record of this wave
+        uint32_t tprev = t1;
+        if (valid && k > 0 && (!have_prev || (is_end && !have && k > 4))) {  // slow path: walk back
+          have = false;
+          for (uint32_t kk = k; kk-- > 0;) {
+            const uint2 rq = rec[wofs + kk];
+            if (!is_live(rq.y)) continue;
+            if (!have_prev) { have_prev = true; tprev = rq.x; }
+            if (!is_end) break;
+            if ((rq.y & kMRegion) == region) { have = true; pm = rq.y; pq = wofs + kk; break; }
           }
         }
-        c_nonmono += (valid && t0 < tprev) ? 1u : 0u;
-        c_starts += (valid && !(m0 & kMEnd)) ? 1u : 0u;
+        c_nonmono += (valid && have_prev && t0 < tprev) ? 1u : 0u;
+        c_starts += (valid && !is_end) ? 1u : 0u;
         c_ends += is_end ? 1u : 0u;
         if (is_end && have && !(pm & kMEnd)) {
           ++c_pairs;
-          om[pq] = (MaskT)(pm | kMPaired);
-          om[q0] = (MaskT)(m0 | kMPaired);
+          const uint32_t pt = recw[2 * pq];
+          recw[2 * pq + 1] = pm | kMPaired;
+          recw[2 * q0 + 1] = m0 | kMPaired;
+          if (pq < pbase) {
+            x_span ^= 1u << region;
+            atomicXor(&wave_tot[pq >> p.span_log2], 1u << region);
+          }
           const uint32_t d_raw = t0 - pt;
           const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
           const uint32_t e = w * R + region;
@@ -425,74 +493,98 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           atomicAdd(&hist[region * 64 + (d ? 31 - __clz(d) : 0)], 1u);
         }
       }
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) x_span ^= __shfl_xor(x_span, d, 64);
+      if (lane == 0 && x_span) atomicXor(&wave_tot[hw], x_span);
       add_tmp(tmp, T_NONMONO, c_nonmono);
       add_tmp(tmp, T_PAIRS, c_pairs);
       add_tmp(tmp, T_ORPH_S, c_starts);  // turned into orphan counts once T_PAIRS is complete
       add_tmp(tmp, T_ORPH_E, c_ends);
     }
     __syncthreads();
-    // ---- C1: XOR of the paired region bits of every span ---------------------------------------
-    {
-      uint32_t x = 0;
-      for (uint32_t q0 = pbase + lane; q0 < pend; q0 += 64) {
-        const uint32_t m0 = om[q0];
-        if (m0 & kMPaired) x ^= 1u << (m0 & kMRegion);
-      }
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) x ^= __shfl_xor(x, d, 64);
-      if (lane == 0) wave_tot[hw] = x;
-    }
-    __syncthreads();
     const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - tmp[T_OCCUPIED]);
-    const bool eligible = !tmp[T_SPANOVF] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
+    const bool eligible = !misc[0] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
 
     if (eligible) {
-      const uint32_t shift = tmp[T_SHIFT];
-      // ---- C2: open-region mask before every position (exclusive XOR scan per wave) ------------
-      // ---- D : coarse time -> position table ------------------------------------------------------
+      const uint32_t shift = misc[1];
+      // ---- C: open-region mask before every position (exclusive XOR scan per wave) -------------
+      // ---- D: coarse time -> position table: grid[w][c] = first rank of wave w in a cell >= c ----
       {
         uint32_t carry = 0;
         if (span < cap) {  // this span continues a wave that started in an earlier span
-          const uint32_t firsthw = ((pbase >> cl2) << cl2) / span;
+          const uint32_t firsthw = ((pbase >> cl2) << cl2) >> p.span_log2;
           for (uint32_t i = firsthw; i < hw; ++i) carry ^= wave_tot[i];
         }
+        uint32_t cprev_carry = 0, wide = 0;
+        if (pbase > 0 && pbase < nrec) {
+          const uint32_t c1 = recw[2 * (pbase - 1)] >> shift;
+          cprev_carry = c1 < ncell ? c1 : ncell - 1;
+        }
         for (uint32_t qb = pbase; qb < pend; qb += 64) {
-          const uint32_t q0 = qb + lane;
-          const bool in = q0 < pend;
-          const uint32_t m0 = in ? (uint32_t)om[q0] : 0u;
-          const uint32_t x = (m0 & kMPaired) ? (1u << (m0 & kMRegion)) : 0u;
+          const bool in = qb + lane < pend;
+          const uint32_t q0 = in ? qb + lane : pend - 1;
+          const uint2 r0 = rec[q0];
+          const bool paired = in && is_live(r0.y) && (r0.y & kMPaired);
+          const uint32_t x = paired ? (1u << (r0.y & kMRegion)) : 0u;
           uint32_t v = x;
           if (cap >= 64) {
-#pragma unroll
-            for (uint32_t d = 1; d < 64; d <<= 1) { const uint32_t y = __shfl_up(v, d, 64); if (lane >= d) v ^= y; }
+            v = wave_xor_scan(v);
           } else {
             for (uint32_t d = 1; d < cap; d <<= 1) { const uint32_t y = __shfl_up(v, d, 64); if ((lane & capm) >= d) v ^= y; }
           }
           const uint32_t ex = v ^ x ^ carry;
           if (cap >= 64) {
-            carry ^= __shfl(v, 63, 64);
+            carry ^= (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
             if (((qb + 64) & capm) == 0) carry = 0;  // next round starts a new wave segment
           }
-          // table entry: grid[w][c] = first rank of wave w whose clock falls in cell >= c
-          if (in) {
-            const uint32_t w = q0 >> cl2, k = q0 & capm, V = sV[w];
-            uint16_t* g = grid + w * ncell;
-            if (k < V) {
-              const uint32_t c0 = ts[q0] >> shift;
-              const int32_t c = (int32_t)(c0 < ncell ? c0 : ncell - 1);
-              int32_t c_prev = -1;
-              if (k > 0) { const uint32_t c1 = ts[q0 - 1] >> shift; c_prev = (int32_t)(c1 < ncell ? c1 : ncell - 1); }
-              for (int32_t cc = c_prev + 1; cc <= c; ++cc) g[cc] = (uint16_t)k;
-            }
+          const uint32_t w = q0 >> cl2, k = q0 & capm, V = sV[w];
+          const uint32_t c0 = r0.x >> shift;
+          const uint32_t c = c0 < ncell ? c0 : ncell - 1;
+          const uint32_t cp = wave_shr1(c, cprev_carry);
+          cprev_carry = (uint32_t)__builtin_amdgcn_readlane((int)c, 63);
+          if (in && k < V) {
+            wide |= c0 >= ncell ? 1u : 0u;
+            uint16_t* g = grid + w * gstride;
+            for (uint32_t cc = k > 0 ? cp + 1 : 0u; cc <= c; ++cc) g[cc] = (uint16_t)k;
           }
-          if (in) om[q0] = (MaskT)ex;  // every lane has read its metadata by now (shuffles above)
+          if (in) recw[2 * q0 + 1] = ex;
         }
+        if (wide) tmp[T_WIDE] = 1u;  // some clock lies past the recorded span: narrow merge keys are off
+      }
+      __syncthreads();
+      // ---- order the cells by record count (counting sort, fullest first) --------------------------
+      for (uint32_t c = tid; c < ncell; c += BLOCK) {
+        uint32_t n = 0;
+        for (uint32_t w = 0; w < W; ++w) n += (uint32_t)grid[w * gstride + c + 1] - (uint32_t)grid[w * gstride + c];
+        const uint32_t nb = n < 63u ? n : 63u;
+        const uint32_t slot = atomicAdd(&bucket[nb], 1u);
+        cinfo[c] = (uint16_t)(nb | (slot << 6));
+      }
+      __syncthreads();
+      if (tid < 64) {  // exclusive prefix over the buckets, from 63 down
+        const uint32_t mine = bucket[63 - tid];
+        uint32_t incl = mine;
+#pragma unroll
+        for (uint32_t d = 1; d < 64; d <<= 1) { const uint32_t y = __shfl_up(incl, d, 64); if (tid >= d) incl += y; }
+        bucket[63 - tid] = incl - mine;
+      }
+      __syncthreads();
+      for (uint32_t c = tid; c < ncell; c += BLOCK) {
+        const uint32_t ci = cinfo[c];
+        perm[bucket[ci & 63u] + (ci >> 6)] = (uint16_t)c;
       }
       __syncthreads();
       // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
-      if (W <= 4)      sweep_cells<4, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
-      else if (W <= 8) sweep_cells<8, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
-      else             sweep_cells<16, MaskT>(ts, om, grid, sV, oacc, W, R, cl2, nrec, ncell, shift, tid, BLOCK);
+      const uint32_t pb = p.pos_bits;
+      if (!tmp[T_WIDE] && shift + pb <= 31u) {  // the all-ones key must stay free
+        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+      } else {
+        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+      }
     }
     __syncthreads();
 
@@ -520,7 +612,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_PAIRS] += tmp[T_PAIRS];
       ctr[H_ORPHAN_START] += tmp[T_ORPH_S] - tmp[T_PAIRS];
       ctr[H_ORPHAN_END] += tmp[T_ORPH_E] - tmp[T_PAIRS];
-      ctr[H_SPAN_OVF] += tmp[T_SPANOVF];
+      ctr[H_SPAN_OVF] += misc[0];
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
     }
     __syncthreads();
@@ -545,9 +637,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 // Launch shape of one kernel instantiation for one LDS size, queried once per device.
 struct LaunchCache { int dev = -1; uint32_t lds = 0; uint32_t max_grid = 0; };
 
-template <typename MaskT, int BLOCK>
+template <int BLOCK>
 kp_status launch_main(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
-  auto kern = kp_reduce_main<MaskT, BLOCK>;
+  auto kern = kp_reduce_main<BLOCK>;
   static thread_local LaunchCache cache;
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
@@ -590,9 +682,12 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
   // positions per hardware wave of the decoder: a power of two >= 64 covering nrec
   uint32_t span = 64;
   while (span * (uint32_t)(block / 64) < nrec) span <<= 1;
-  const uint32_t ncell = cap < 1024 ? cap : 1024;
-  const uint32_t mask_bytes = R <= 16 ? 2 : 4;
-  const LdsLayout L = lds_layout(nrec, W, R, ncell, mask_bytes, block);
+  uint32_t span_log2 = 0;
+  while ((1u << span_log2) < span) ++span_log2;
+  // time cells per wave: at most one per record slot, 1024, and 8192 table entries over all waves
+  uint32_t ncell = cap < 1024 ? cap : 1024;
+  while (W * ncell > 8192) ncell >>= 1;
+  const LdsLayout L = lds_layout(nrec, W, R, ncell, block);
   if (L.total > kMaxLds)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder needs %u B of LDS for this geometry (limit %u)", L.total, kMaxLds);
 
@@ -613,17 +708,11 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     p.n_wg = h.n_wg; p.W = W; p.R = R; p.cap = cap;
     p.cap_log2 = 0; while ((1u << p.cap_log2) < cap) ++p.cap_log2;
     p.rec_cost = h.rec_cost; p.flush = h.flags & KP_FLAG_FLUSH;
-    p.nrec = nrec; p.span = span; p.ncell = ncell;
-    kp_status st;
-    if (mask_bytes == 2) {
-      st = block == 1024 ? launch_main<uint16_t, 1024>(p, L.total, s)
-         : block == 512  ? launch_main<uint16_t, 512>(p, L.total, s)
-                         : launch_main<uint16_t, 256>(p, L.total, s);
-    } else {
-      st = block == 1024 ? launch_main<uint32_t, 1024>(p, L.total, s)
-         : block == 512  ? launch_main<uint32_t, 512>(p, L.total, s)
-                         : launch_main<uint32_t, 256>(p, L.total, s);
-    }
+    p.nrec = nrec; p.span = span; p.span_log2 = span_log2; p.ncell = ncell;
+    p.pos_bits = 0; while ((1u << p.pos_bits) < nrec) ++p.pos_bits;
+    const kp_status st = block == 1024 ? launch_main<1024>(p, L.total, s)
+                       : block == 512  ? launch_main<512>(p, L.total, s)
+                                       : launch_main<256>(p, L.total, s);
     if (st != KP_OK) return st;
   }
   hipLaunchKernelGGL(kp_reduce_finalize, dim3(1), dim3(256), 0, s, out, h.n_wg, W, R);
