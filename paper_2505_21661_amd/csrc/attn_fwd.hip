@@ -82,6 +82,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, 4, wg);
+  if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // Q fragments of this wave's 32 rows stay in registers: step s covers d = 16s .. 16s+15
   const uint32_t qrow = q0 + wave * 32 + l32;
@@ -244,6 +245,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     }
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    if constexpr (INSTR == 2) kp::lean_end(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
@@ -309,7 +311,8 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     attr_set = true;
   }
-  if (!flush && regions == 7u)  // every region, circular: lean record sites
+  // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
+  if (!flush && regions == 7u && S <= (1 << 22))
     hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   else
     hipLaunchKernelGGL(kp_attn_fwd<1>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);

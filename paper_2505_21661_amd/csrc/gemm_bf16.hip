@@ -74,6 +74,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   kp::Ring ring{};
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4, wg);
+  if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // global -> register mapping
   // A: 64 rows x 4 chunks = 256 chunks, one per thread
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   }
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    if constexpr (INSTR == 2) kp::lean_end(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
@@ -179,6 +181,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, WAVES, wg);
+  if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Waves 0-3 stage A, waves 4-7 stage B, eight 16-byte loads per thread and K step (vector
@@ -328,6 +331,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   KP_BOUNDARY(ring, 4, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, WAVES, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    if constexpr (INSTR == 2) kp::lean_end(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
@@ -419,7 +423,8 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   const size_t ring_bytes = (size_t)cap_lds * 8 * s.waves;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
-  const bool lean = !flush && regions == (1u << s.regions) - 1u;  // every region, circular: lean record sites
+  // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
+  const bool lean = !flush && regions == (1u << s.regions) - 1u && K <= (1 << 22);
   if (big) return lean ? launch_big_w<2>(s.waves, g, n_wg, ring_bytes, st) : launch_big_w<1>(s.waves, g, n_wg, ring_bytes, st);
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);

@@ -38,6 +38,7 @@ struct Ring {
   uint32_t pend_tag2;  //   (an END and the START that follows it); kNoPending: none
   uint32_t stored;     // records already written to the LDS sub-ring
   uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
+  uint32_t cw;         // lean sites only: tag_wave + records written so far (stands in for cnt)
   uint64_t t_begin;    // workgroup start: s_memtime
   uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
   // flush strategy only
@@ -130,12 +131,31 @@ __device__ __forceinline__ void store_one(Ring& r, uint32_t tag, uint32_t ts) {
   }
 }
 
+// The clock is sampled with s_memtime, whose 64-bit result arrives in its SGPR pair some 200
+// cycles later and is counted in lgkmcnt together with LDS traffic.  The sample is issued from
+// inline assembly so that the compiler's wait-count bookkeeping does not see it: LDS operations
+// complete in order, so with one more operation outstanding than the compiler knows of, each of
+// its partial waits "lgkmcnt(n)" still guarantees what it was meant to (it may at most wait for
+// one LDS operation more), instead of every LDS wait after a sample turning into a wait for the
+// clock.  The registers must not be read before the value has landed, so the only consumer is
+// clock_delta(): one assembly statement that waits for everything counted in lgkmcnt and then
+// subtracts.  It also names the whole pair as an input, which keeps both halves allocated up to
+// there (a dead half could be reused right after the sample was issued, and that write-after-write
+// hazard stalls the wave at the sample).
+__device__ __forceinline__ uint64_t sample_clock() {
+  uint64_t t;
+  asm volatile("s_memtime %0" : "=s"(t));
+  return t;
+}
+// low 32 bits of (t - t0) for a value returned by sample_clock()
+__device__ __forceinline__ uint32_t clock_delta(uint64_t t, uint32_t t0_lo) {
+  uint32_t d;
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_sub_u32 %0, %1, %2" : "=s"(d) : "s"((uint32_t)t), "s"(t0_lo), "s"(t) : "scc");
+  return d;
+}
+
 __device__ __forceinline__ void store_pending(Ring& r) {
-  // Keep BOTH halves of the sampled clock live up to here: if the unused high half were dead, its
-  // register could be reused right after s_memtime was issued, and that write-after-write hazard
-  // makes the hardware wait for the clock to return at the sampling site.
-  asm volatile("" ::"s"(r.pend_t));
-  const uint32_t ts = (uint32_t)r.pend_t - r.t0_lo;
+  const uint32_t ts = clock_delta(r.pend_t, r.t0_lo);
   if (r.pend_tag != kNoPending) store_one(r, r.pend_tag, ts);
   if (r.pend_tag2 != kNoPending) store_one(r, r.pend_tag2, ts);
   r.pend_tag = kNoPending;
@@ -151,8 +171,8 @@ __device__ __forceinline__ void store_pending(Ring& r) {
 // Back-to-back END/START therefore share one sample instead of paying that stall.
 __device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t start_region) {
   __builtin_amdgcn_sched_barrier(0);
-  if ((r.pend_tag & r.pend_tag2) != kNoPending) store_pending(r);
-  const uint64_t now = __builtin_readcyclecounter();  // s_memtime
+  store_pending(r);  // also when nothing is pending: the previous sample must have landed before the next
+  const uint64_t now = sample_clock();
   const bool on_e = end_region != kNoRegion && ((r.mask >> (end_region & 31u)) & 1u) != 0u;     // scalar
   const bool on_s = start_region != kNoRegion && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
   r.pend_tag = on_e ? ((1u << 31) | (end_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
@@ -163,55 +183,64 @@ __device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t 
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// The same site for the common case "every region enabled, circular strategy": no mask tests, no
-// flush checks, and the two pending records go out under a single EXEC switch.  Every instruction
-// here is paid once per wave and site (a wave issues roughly one instruction every four cycles),
-// so the site is kept to about thirty instructions.
+// The same site for the common case "every region enabled, circular strategy", without a branch.
+// Every instruction here is paid once per wave and site (a wave issues roughly one instruction
+// every four to five cycles and all waves of a workgroup reach their sites together), so the site
+// is kept to about twenty instructions:
+//   - the two tags of a site are (running counter | compile-time constant); the counter already
+//     carries the wave field, which holds as long as a wave writes fewer than 2^20 records (the
+//     host only selects these sites when that is certain),
+//   - a site always leaves exactly two records pending, so the next site retires two records under
+//     one EXEC switch.  The first site of a kernel (START only) and the last (END only) leave the
+//     same record twice: both copies go to the same slot with the same contents.  What the very
+//     first site retires is the placeholder set up by lean_begin(): it lands in slot 0, which the
+//     record with sequence number 0 overwrites one site later.
+__device__ __forceinline__ void lean_begin(Ring& r) {
+  r.cw = r.tag_wave;
+  r.pend_tag = 0u;
+  r.pend_tag2 = 0u;
+  r.pend_t = r.t_begin;
+}
+
 __device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint32_t start_region) {
   __builtin_amdgcn_sched_barrier(0);
-  if (r.pend_tag2 != kNoPending) {  // false only at the very first site
-    asm volatile("" ::"s"(r.pend_t));
-    const uint32_t ts = (uint32_t)r.pend_t - r.t0_lo;
+  {
+    const uint32_t ts = clock_delta(r.pend_t, r.t0_lo);
+    const uint32_t a0 = r.sub_lds + ((r.pend_tag & r.lds_mask) << 3);
     const uint32_t a1 = r.sub_lds + ((r.pend_tag2 & r.lds_mask) << 3);
-    if (r.pend_tag != kNoPending) {
-      const uint32_t a0 = r.sub_lds + ((r.pend_tag & r.lds_mask) << 3);
-      uint64_t saved_exec;
-      uint32_t va, vb, vc, vd, ve;
-      asm volatile(
-          "s_mov_b64 %0, exec\n\t"
-          "s_mov_b64 exec, 1\n\t"
-          "v_mov_b32 %1, %6\n\t"
-          "v_mov_b32 %2, %7\n\t"
-          "v_mov_b32 %3, %8\n\t"
-          "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
-          "v_mov_b32 %4, %9\n\t"
-          "v_mov_b32 %5, %10\n\t"
-          "ds_write2_b32 %4, %5, %3 offset1:1\n\t"
-          "s_mov_b64 exec, %0"
-          : "=&s"(saved_exec), "=&v"(va), "=&v"(vb), "=&v"(vc), "=&v"(vd), "=&v"(ve)
-          : "s"(a0), "s"(r.pend_tag), "s"(ts), "s"(a1), "s"(r.pend_tag2)
-          : "memory");
-    } else {
-      store_one(r, r.pend_tag2, ts);
-    }
+    uint64_t saved_exec;
+    uint32_t va, vb, vc, vd, ve;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 %1, %6\n\t"
+        "v_mov_b32 %2, %7\n\t"
+        "v_mov_b32 %3, %8\n\t"
+        "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
+        "v_mov_b32 %4, %9\n\t"
+        "v_mov_b32 %5, %10\n\t"
+        "ds_write2_b32 %4, %5, %3 offset1:1\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved_exec), "=&v"(va), "=&v"(vb), "=&v"(vc), "=&v"(vd), "=&v"(ve)
+        : "s"(a0), "s"(r.pend_tag), "s"(ts), "s"(a1), "s"(r.pend_tag2)
+        : "memory");
   }
-  const uint64_t now = __builtin_readcyclecounter();  // s_memtime
-  if (end_region != kNoRegion) {
-    r.pend_tag = ((1u << 31) | (end_region << 24)) | r.tag_wave | (r.cnt & 0xFFFFFu);
-    r.cnt += 1;
+  r.pend_t = sample_clock();
+  if (end_region != kNoRegion && start_region != kNoRegion) {
+    r.pend_tag = r.cw | ((1u << 31) | (end_region << 24));
+    r.pend_tag2 = (r.cw + 1u) | (start_region << 24);
+    r.cw += 2u;
   } else {
-    r.pend_tag = kNoPending;
-  }
-  if (start_region != kNoRegion) {
-    r.pend_tag2 = (start_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu);
-    r.cnt += 1;
-  } else {  // final END of the kernel: keep it in the second slot so that "pending" stays one test
+    const uint32_t k = end_region != kNoRegion ? ((1u << 31) | (end_region << 24)) : (start_region << 24);
+    r.pend_tag = r.cw | k;
     r.pend_tag2 = r.pend_tag;
-    r.pend_tag = kNoPending;
+    r.cw += 1u;
   }
-  r.pend_t = now;
   __builtin_amdgcn_sched_barrier(0);
 }
+
+// Before ring_finish() in a kernel that used the lean sites: hand the record count back.
+__device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 
 // MODE 1: generic (region mask, either strategy); MODE 2: every region enabled, circular strategy.
 template <int MODE>

@@ -221,7 +221,9 @@ __device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* gr
       const uint32_t pos = K::pos(best, pmask), tt = K::clock(best, cbase, pb);
       const uint32_t b = pos >> cl2;
       const uint32_t g1 = grid[b * gstride + c + 1];
-      const uint2 cur = rec[pos], nxt = rec[pos + 1];
+      const uint2 cur = rec[pos];
+      uint2 nxt = rec[pos + 1];
+      asm volatile("" : "+v"(nxt.x));  // fetch the next clock with the masks, not behind the test below
       const bool more = (pos & capm) + 1u < g1;
       const KeyT nkey = more ? K::make(nxt.x, pos + 1u, cbase, pb) : none;
 #pragma unroll
