@@ -33,9 +33,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1054808.4 * 2.0 + 36984.8) * 1024,
-    "gemm_vanilla": (98358.5 * 2.0 + 34702.5) * 1024,
-    "attn_vanilla": (1343831.0 * 2.0 + 131857.3) * 1024,
+    "decode_2^28": (1055619.6 * 2.0 + 45176.8) * 1024,
+    "gemm_vanilla": (98372.0 * 2.0 + 34134.4) * 1024,
+    "attn_vanilla": (1418176.1 * 2.0 + 132271.8) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 

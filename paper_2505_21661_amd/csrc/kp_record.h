@@ -206,24 +206,26 @@ __device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint
   __builtin_amdgcn_sched_barrier(0);
   {
     const uint32_t ts = clock_delta(r.pend_t, r.t0_lo);
-    const uint32_t a0 = r.sub_lds + ((r.pend_tag & r.lds_mask) << 3);
-    const uint32_t a1 = r.sub_lds + ((r.pend_tag2 & r.lds_mask) << 3);
     uint64_t saved_exec;
-    uint32_t va, vb, vc, vd, ve;
+    uint32_t a0, a1, va, vb, vc, vd, ve;
     asm volatile(
+        "s_and_b32 %1, %8, %11\n\t"          // slot = tag & (capacity - 1): seq sits in the low tag bits
+        "s_lshl3_add_u32 %1, %1, %12\n\t"    // LDS byte address = sub-ring base + 8 * slot
+        "s_and_b32 %2, %10, %11\n\t"
+        "s_lshl3_add_u32 %2, %2, %12\n\t"
         "s_mov_b64 %0, exec\n\t"
         "s_mov_b64 exec, 1\n\t"
-        "v_mov_b32 %1, %6\n\t"
-        "v_mov_b32 %2, %7\n\t"
-        "v_mov_b32 %3, %8\n\t"
-        "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
-        "v_mov_b32 %4, %9\n\t"
-        "v_mov_b32 %5, %10\n\t"
-        "ds_write2_b32 %4, %5, %3 offset1:1\n\t"
+        "v_mov_b32 %3, %1\n\t"
+        "v_mov_b32 %4, %8\n\t"
+        "v_mov_b32 %5, %9\n\t"
+        "ds_write2_b32 %3, %4, %5 offset1:1\n\t"
+        "v_mov_b32 %6, %2\n\t"
+        "v_mov_b32 %7, %10\n\t"
+        "ds_write2_b32 %6, %7, %5 offset1:1\n\t"
         "s_mov_b64 exec, %0"
-        : "=&s"(saved_exec), "=&v"(va), "=&v"(vb), "=&v"(vc), "=&v"(vd), "=&v"(ve)
-        : "s"(a0), "s"(r.pend_tag), "s"(ts), "s"(a1), "s"(r.pend_tag2)
-        : "memory");
+        : "=&s"(saved_exec), "=&s"(a0), "=&s"(a1), "=&v"(va), "=&v"(vb), "=&v"(vc), "=&v"(vd), "=&v"(ve)
+        : "s"(r.pend_tag), "s"(ts), "s"(r.pend_tag2), "s"(r.lds_mask), "s"(r.sub_lds)
+        : "memory", "scc");
   }
   r.pend_t = sample_clock();
   if (end_region != kNoRegion && start_region != kNoRegion) {
