@@ -2,7 +2,7 @@
 """Benchmark of the hot path on one MI355X.
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input:
-  1. bf16 GEMM 4096^3: one warm launch, then uninstrumented / instrumented (all 5 regions, ring of
+  1. bf16 GEMM 4096^3: one warm launch, then uninstrumented / instrumented (all 4 regions, ring of
      4096 records per workgroup) launched alternately, two of each
   2. kp_trace_reduce of the GEMM trace
   3. causal attention forward 4x32x4096x128: warm launch, then uninstrumented / instrumented
@@ -102,7 +102,7 @@ def main() -> int:
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
-        gemm_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b11111, g_trace, g_cap)
+        gemm_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1111, g_trace, g_cap)
         attn_v = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0, None, 0)
         attn_i = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0b111, a_trace, a_cap)
         calls = (
@@ -167,7 +167,7 @@ def main() -> int:
     c_span = ((chdr[:, 4] | (chdr[:, 5] << np.uint64(32))) - (chdr[:, 2] | (chdr[:, 3] << np.uint64(32)))).astype(np.float64)
     c_rt = (chdr[:, 6] | (chdr[:, 7] << np.uint64(32))).astype(np.float64)
     tick_hz = 100e6 * c_span.sum() / c_rt.sum()
-    n_record = 2 * 4 * (K // 64) + 2
+    n_record = 2 * 3 * (K // 64) + 2
     t_vanilla_ticks = ms["gemm_vanilla"] * 1e-3 * tick_hz
     eq1 = {
         "n_record_per_wave": n_record,
@@ -194,7 +194,7 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": "instrumented bf16 GEMM M=N=K=4096 (256x256x64 tiles, 5 regions, ring 4096 rec/WG) "
+            "workload": "instrumented bf16 GEMM M=N=K=4096 (256x256x64 tiles, 4 regions, ring 4096 rec/WG) "
                         "+ causal attention 4x32x4096x128 (3 regions, ring 1024 rec/WG) "
                         f"+ trace decode of 2^{args.log2_records} synthetic records (16384 WG x 8 waves x 16 regions at 2^28)",
             "decode_entry_point": "kp_trace_reduce_hdr",

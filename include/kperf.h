@@ -175,8 +175,9 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  * software-pipelined GEMMs stage by stage (Sec. 5.3 "Profiling Overhead", GEMM-SWP-2/3); the
  * regions here are
  *   M, N multiples of 256 with at least 16 tiles, K a multiple of 64: tile 256x256x64, 8 waves,
- *       2 LDS write of the next K-step, 0 first global-load issue, 3 MFMA with the remaining loads
- *       interleaved, 1 wait (barrier + outstanding loads), in this order once per K-step; 4 epilogue
+ *       per K-step, in this order: 0 first half of the MFMA steps, with the A share of the next
+ *       K-step's staging (registers -> other LDS stage, refill from global memory) threaded between
+ *       them, 1 second half with the B share, 2 wait (LDS writes landed + barrier); 3 epilogue, once
  *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
  *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
  * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.

@@ -9,8 +9,10 @@
 // bit-identical C.
 //
 //   tile 64x64x32, 4 waves  : regions 0 global load, 1 LDS store, 2 MFMA        (per K step)
-//   tile 256x256x64, 8 waves: regions 0 load issue, 1 load wait, 2 LDS write, 3 MFMA (per K step),
-//                              4 epilogue (once)
+//   tile 256x256x64, 8 waves: regions 0 / 1 first / second half of a K step's MFMAs with the
+//                              staging of the next K step threaded in, 2 barrier wait, 3 epilogue (once)
+#include <type_traits>
+
 #include "kp_common.h"
 #include "kp_record.h"
 
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 // 256x256x64 tile, 8 waves as 2 (M) x 4 (N); each wave owns 128x64 of C as 4x2 MFMA tiles.
 // LDS holds two stages of the A tile [256][64] and of the transposed B tile [256 n][64 k]
 // (128 KiB); the K loop is software-pipelined over the two stages: while the MFMAs consume
-// stage s, the global loads of the next K step are in flight and are written to stage s^1.
+// stage s, K step +1 moves from registers to stage s^1 and the global loads of K step +2 are in flight.
 // MFMA operands are swapped (B^T rows as the first operand) so that a lane ends up with four
 // consecutive columns of one C row per accumulator quad and can store them as 8 bytes.
 constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64;
@@ -154,8 +156,8 @@ constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // bot
 template <int INSTR, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
-  constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
-  static_assert(WAVES == 8 || WAVES == 4, "2x4 or 2x2 waves");
+  constexpr int TN = 2;                     // 32-column MFMA tiles per wave (wave tile 128 x 64)
+  static_assert(WAVES == 8, "2 x 4 waves");
   constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];  // [stage0 A|B][stage1 A|B][ring]
   uint32_t* ring_lds = reinterpret_cast<uint32_t*>(smem + 2 * STAGE);
@@ -184,71 +186,48 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
-  // Waves 0-3 stage A, waves 4-7 stage B, eight 16-byte loads per thread and K step (vector
-  // memory instructions are issued at a fixed rate per CU whatever their width, so wide loads
-  // keep the issue time of a K step short).
-  // A: 256 rows x 8 chunks; thread t takes chunk (t & 7) of rows (t >> 3) + 32*i.
-  // B: 8x8 blocks (k x n); thread u takes block (u >> 5, u & 31), loads its 8 rows and transposes
-  //    them in registers into eight 16-byte k-runs, one per column.
-  // With 8 waves, waves 0-3 stage A and waves 4-7 stage B (8 loads each); with 4 waves every thread
-  // stages one A share and one B block (16 loads).
-  constexpr bool SPLIT = WAVES == 8;
-  constexpr int NLD = SPLIT ? 8 : 16;
-  const bool is_a = SPLIT ? tid < 256 : true;
-  const bool is_b = SPLIT ? tid >= 256 : true;
-  const uint32_t u = tid & 255u;
-  const uint32_t a_row = u >> 3, a_chunk = u & 7u;
-  const uint32_t b_kb = u >> 5, b_nb = u & 31u;
+  // Every thread stages the same share of a K step, so all waves reach the barrier together:
+  //   A: 256 rows x 8 chunks of 16 bytes; thread t takes chunk (t & 7) of rows (t >> 3) + 64*i, i < 4;
+  //   B: blocks of 4 k x 8 n; thread t takes block (k quad t >> 5, n block t & 31), loads its four
+  //      rows (16 bytes each) and transposes them in registers into eight 8-byte k-runs, one per
+  //      column of the transposed tile.
+  // Eight 16-byte global loads per thread and K step: vector-memory instructions are issued at a
+  // fixed rate per CU whatever their width, so wide loads keep the issue time of a K step short.
+  const uint32_t a_row = tid >> 3, a_chunk = tid & 7u;
+  const uint32_t b_kq = tid >> 5, b_nb = tid & 31u;
   const uint16_t* src_a = g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8;
-  const uint16_t* src_b = g.B + (size_t)(b_kb * 8) * g.N + n0 + b_nb * 8;
+  const uint16_t* src_b = g.B + (size_t)(b_kq * 4) * g.N + n0 + b_nb * 8;
+  // LDS byte offsets inside a stage
+  uint32_t a_dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_dst[i] = tile_off<BK>(a_row + 64 * i, a_chunk);
+  // column c of the block goes to row 8*b_nb + c of the transposed tile, chunk b_kq / 2, half b_kq % 2;
+  // the rows of one block differ only in the swizzle term, so one base and c ^ const does it
+  const uint32_t b_chunk = b_kq >> 1, b_half = (b_kq & 1u) * 8u;
 
-  u32x4 ld[NLD];  // SPLIT: the thread's 8 loads; otherwise [0..7] A, [8..15] B
-  // loads 2*part and 2*part+1 of each share of K step kt; the four parts are spread over the MFMA
-  // steps so that the vector-memory issue slots they occupy overlap with matrix work
-  auto load_part = [&](uint32_t kt, int part) {
-    if (is_a) {
-      const uint16_t* p0 = src_a + (size_t)kt * BK;
-#pragma unroll
-      for (int i = 2 * part; i < 2 * part + 2; ++i) ld[i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)(32 * i) * g.K);
-    }
-    if (is_b) {
-      const uint16_t* p0 = src_b + (size_t)kt * BK * g.N;
-      constexpr int o = SPLIT ? 0 : 8;
-#pragma unroll
-      for (int i = 2 * part; i < 2 * part + 2; ++i) ld[o + i] = *reinterpret_cast<const u32x4*>(p0 + (size_t)i * g.N);
-    }
+  u32x4 la[4], lb[4];  // staging registers: A chunks, B rows
+  auto load_a = [&](uint32_t kt, int i) {
+    la[i] = *reinterpret_cast<const u32x4*>(src_a + (size_t)kt * BK + (size_t)(64 * i) * g.K);
   };
-  auto load_tile = [&](uint32_t kt) {
-#pragma unroll
-    for (int part = 0; part < 4; ++part) load_part(kt, part);
+  auto load_b = [&](uint32_t kt, int i) {
+    lb[i] = *reinterpret_cast<const u32x4*>(src_b + (size_t)kt * BK * g.N + (size_t)i * g.N);
   };
-  auto store_tile = [&](uint32_t stage) {
-    unsigned char* sA = smem + stage * STAGE;
-    unsigned char* sB = sA + A_BYTES;
-    if (is_a) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row + 32 * i, a_chunk)) = ld[i];
-    }
-    if (is_b) {
-      constexpr int o = SPLIT ? 0 : 8;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {  // column c of the block: k = 8*b_kb .. +7
-        u32x4 t;
-        const int d = c >> 1;
-        if (c & 1) {
-          t.x = (ld[o + 0][d] >> 16) | (ld[o + 1][d] & 0xFFFF0000u); t.y = (ld[o + 2][d] >> 16) | (ld[o + 3][d] & 0xFFFF0000u);
-          t.z = (ld[o + 4][d] >> 16) | (ld[o + 5][d] & 0xFFFF0000u); t.w = (ld[o + 6][d] >> 16) | (ld[o + 7][d] & 0xFFFF0000u);
-        } else {
-          t.x = (ld[o + 0][d] & 0xFFFFu) | (ld[o + 1][d] << 16); t.y = (ld[o + 2][d] & 0xFFFFu) | (ld[o + 3][d] << 16);
-          t.z = (ld[o + 4][d] & 0xFFFFu) | (ld[o + 5][d] << 16); t.w = (ld[o + 6][d] & 0xFFFFu) | (ld[o + 7][d] << 16);
-        }
-        *reinterpret_cast<u32x4*>(sB + tile_off_bt(b_nb * 8 + c, b_kb)) = t;
-      }
-    }
+  auto store_a = [&](uint32_t stage, int i) {
+    *reinterpret_cast<u32x4*>(smem + stage * STAGE + a_dst[i]) = la[i];
+  };
+  // word j of the four rows holds columns 2j (low halves) and 2j+1 (high halves)
+  auto store_b = [&](uint32_t stage, int j) {
+    unsigned char* sB = smem + stage * STAGE + A_BYTES;
+    const uint32_t w0 = lb[0][j], w1 = lb[1][j], w2 = lb[2][j], w3 = lb[3][j];
+    u32x2 ev, od;
+    ev.x = (w0 & 0xFFFFu) | (w1 << 16); ev.y = (w2 & 0xFFFFu) | (w3 << 16);
+    od.x = (w0 >> 16) | (w1 & 0xFFFF0000u); od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
+    const uint32_t n = b_nb * 8u + 2u * (uint32_t)j;
+    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n, b_chunk) + b_half) = ev;
+    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, b_chunk) + b_half) = od;
   };
 
-  const uint32_t wm = SPLIT ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
-  const uint32_t wn = SPLIT ? wave & 3u : wave & 1u;
+  const uint32_t wm = wave >> 2, wn = wave & 3u;  // wave position: 2 x 4
   f32x16 acc[TN][4];                               // [tn][tm], transposed tiles (rows = n, cols = m)
 #pragma unroll
   for (int a = 0; a < TN; ++a)
@@ -257,61 +236,75 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 
   // prologue: K step 0 into stage 0, K step 1 into the staging registers
   const uint32_t KT = g.K / BK;
-  load_tile(0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  store_tile(0);
-  if (KT > 1) load_tile(1);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { load_a(0, i); load_b(0, i); }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { store_a(0, i); store_b(0, i); }
+  if (KT > 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { load_a(1, i); load_b(1, i); }
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-  // Iteration kt: the registers hold K step kt+1 (loaded during the previous iteration); they go
-  // to the other LDS stage first, and those writes drain while the MFMAs below work on the current
-  // stage.  The loads of K step kt+2 then refill the registers, spread over the MFMA steps.  One
-  // barrier per iteration orders "stage written" before "stage read" and vice versa.
-  KP_BOUNDARY(ring, kp::kNoRegion, 2);
-  for (uint32_t kt = 0; kt < KT; ++kt) {
+  // Iteration kt runs the MFMAs of K step kt on LDS stage kt & 1 and, threaded between them, moves
+  // K step kt+1 from the staging registers to the other stage; every register is refilled with its
+  // share of K step kt+2 right after it has been written out, so each load has one whole iteration
+  // to arrive and nothing but the barrier separates two iterations.  The barrier waits for LDS
+  // traffic only, never for the global loads.
+  // MORE / MORE2 (K step kt+1 / kt+2 exists) are compile-time so that the steady-state body is one
+  // basic block: with branches between the pieces the compiler's wait-count tracking gives up and
+  // waits for ALL outstanding loads before every LDS write.
+  auto iteration = [&](uint32_t kt, auto more_c, auto more2_c) {
+    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
     const uint32_t stage = kt & 1u;
-    const bool more = kt + 1 < KT, more2 = kt + 2 < KT;
-    // ---- region 2: write K step kt+1 to the other LDS stage --------------------------------------
-    if (more) store_tile(stage ^ 1u);
-    KP_BOUNDARY(ring, 2, 0);
-    // ---- region 0: issue the first global loads of K step kt+2 -----------------------------------
-    if (more2) load_part(kt + 2, 0);
-    KP_BOUNDARY(ring, 0, 3);
-    // ---- region 3: MFMA on the current stage, remaining loads interleaved -------------------------
-    {
-      const unsigned char* sA = smem + stage * STAGE;
-      const unsigned char* sB = sA + A_BYTES;
+    const unsigned char* sA = smem + stage * STAGE;
+    const unsigned char* sB = sA + A_BYTES;
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const uint32_t chunk = ks * 2 + (lane >> 5);
-        bf16x8 af[4], bfr[TN];
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      // ---- region 0: first half of the K step, with the A share of the staging;
+      // ---- region 1: second half, with the B share
+      if (ks == BK / 32) KP_BOUNDARY(ring, 0, 1);
+      const uint32_t chunk = ks * 2 + (lane >> 5);
+      bf16x8 af[4], bfr[TN];
 #pragma unroll
-        for (int tm = 0; tm < 4; ++tm)
-          af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
+      for (int tm = 0; tm < 4; ++tm)
+        af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-          bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * (32 * TN) + tn * 32 + (lane & 31u), chunk));
+      for (int tn = 0; tn < TN; ++tn)
+        bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * (32 * TN) + tn * 32 + (lane & 31u), chunk));
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+      for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
-          for (int tm = 0; tm < 4; ++tm)
-            acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
-        if (ks < 3) {  // remaining loads of K step kt+2 ride along with the MFMAs
-          asm volatile("" ::: "memory");
-          if (more2) load_part(kt + 2, ks + 1);
-          asm volatile("" ::: "memory");
+        for (int tm = 0; tm < 4; ++tm) {
+          acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
+          // one staging piece after every second MFMA: 16 slots per K step, 12 used
+          if (tm & 1) {
+            const int slot = ks * 4 + tn * 2 + (tm >> 1);
+            if (slot < 4) {                      // A chunk `slot`: out to LDS, refill
+              if constexpr (MORE) store_a(stage ^ 1u, slot);
+              if constexpr (MORE2) load_a(kt + 2, slot);
+            } else if (slot >= 8 && slot < 12) {  // B columns 2j, 2j+1
+              if constexpr (MORE) store_b(stage ^ 1u, slot - 8);
+            } else if (slot >= 12) {              // B rows: refill
+              if constexpr (MORE2) load_b(kt + 2, slot - 12);
+            }
+          }
         }
       }
     }
-    KP_BOUNDARY(ring, 3, 1);
-    // ---- region 1: wait for the other waves and for this wave's loads ----------------------------
-    __syncthreads();
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (more) KP_BOUNDARY(ring, 1, 2); else KP_BOUNDARY(ring, 1, 4);
-  }
+    KP_BOUNDARY(ring, 1, 2);
+    // ---- region 2: this wave's LDS writes have landed, every wave is done with the stage ---------
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, 3);
+  };
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  KP_BOUNDARY(ring, kp::kNoRegion, 0);
+  for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
+  if (KT >= 2) iteration(KT - 2, yes, no);
+  iteration(KT - 1, no, no);
 
-  // ---- region 4: epilogue ------------------------------------------------------------------------
+  // ---- region 3: epilogue ------------------------------------------------------------------------
   // transposed tile: register v of lane l is C[m, n] with m = l%32 and n = 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm) {
@@ -328,9 +321,9 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_BOUNDARY(ring, 4, kp::kNoRegion);
+  KP_BOUNDARY(ring, 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, WAVES, 5, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, WAVES, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     if constexpr (INSTR == 2) kp::lean_end(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -351,7 +344,7 @@ constexpr int kBigWaves = 8;
 bool pick_shape(int M, int N, int K, GemmShape* s) {
   if (M <= 0 || N <= 0 || K <= 0) return false;
   // the large tile only pays off once there are enough tiles to spread over the chip
-  if (M % 256 == 0 && N % 256 == 0 && K % 64 == 0 && (M / 256) * (N / 256) >= 16) { *s = GemmShape{256, 256, 64, kBigWaves, 5}; return true; }
+  if (M % 256 == 0 && N % 256 == 0 && K % 64 == 0 && (M / 256) * (N / 256) >= 16) { *s = GemmShape{256, 256, 64, kBigWaves, 4}; return true; }
   if (M % 64 == 0 && N % 64 == 0 && K % 32 == 0) { *s = GemmShape{64, 64, 32, 4, 3}; return true; }
   return false;
 }

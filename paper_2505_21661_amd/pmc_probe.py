@@ -48,7 +48,7 @@ def main() -> None:
     for _ in range(2):
         kp.kp_gemm_instrumented(A, B, C, M, N, K, 0, None, 0)
     for _ in range(2):
-        kp.kp_gemm_instrumented(A, B, C, M, N, K, 0b11111, trace, 4096)
+        kp.kp_gemm_instrumented(A, B, C, M, N, K, 0b1111, trace, 4096)
     torch.cuda.synchronize()
 
     Bt, H, S, D = 4, 32, 4096, 128

@@ -51,7 +51,7 @@ def test_host_side_argument_checks_need_no_gpu():
     import paper_2505_21661_amd as kp
 
     assert kp.kp_gemm_launch_shape(256, 256, 256) == (16, 4, 3)
-    assert kp.kp_gemm_launch_shape(4096, 4096, 4096) == (256, 8, 5)
+    assert kp.kp_gemm_launch_shape(4096, 4096, 4096) == (256, 8, 4)
     assert kp.kp_attn_launch_shape(4, 32, 4096, 128) == (4096, 4, 3)
     import pytest
 
