@@ -280,13 +280,20 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
           // one staging piece after every second MFMA: 16 slots per K step, 12 used
           if (tm & 1) {
             const int slot = ks * 4 + tn * 2 + (tm >> 1);
+            // The global loads keep their place between the MFMAs (the two fences let everything but
+            // MFMA and vector-memory instructions move across): left alone, the scheduler sinks all
+            // eight to the end of the iteration and the next iteration waits for them at once.
             if (slot < 4) {                      // A chunk `slot`: out to LDS, refill
               if constexpr (MORE) store_a(stage ^ 1u, slot);
+              __builtin_amdgcn_sched_barrier(0x386);
               if constexpr (MORE2) load_a(kt + 2, slot);
+              __builtin_amdgcn_sched_barrier(0x386);
             } else if (slot >= 8 && slot < 12) {  // B columns 2j, 2j+1
               if constexpr (MORE) store_b(stage ^ 1u, slot - 8);
             } else if (slot >= 12) {              // B rows: refill
+              __builtin_amdgcn_sched_barrier(0x386);
               if constexpr (MORE2) load_b(kt + 2, slot - 12);
+              __builtin_amdgcn_sched_barrier(0x386);
             }
           }
         }
