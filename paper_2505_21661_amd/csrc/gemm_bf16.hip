@@ -156,8 +156,11 @@ constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // bot
 template <int INSTR, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
-  constexpr int TN = 2;                     // 32-column MFMA tiles per wave (wave tile 128 x 64)
-  static_assert(WAVES == 8, "2 x 4 waves");
+  constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
+  static_assert(WAVES == 8 || WAVES == 4, "2 x 4 or 2 x 2 waves");
+  constexpr int T = WAVES * 64;             // threads
+  constexpr int NA = 2048 / T;              // A chunks per thread and K step
+  constexpr int NB = 512 / T;               // B blocks (4 k x 8 n) per thread and K step
   constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];  // [stage0 A|B][stage1 A|B][ring]
   uint32_t* ring_lds = reinterpret_cast<uint32_t*>(smem + 2 * STAGE);
@@ -187,47 +190,46 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Every thread stages the same share of a K step, so all waves reach the barrier together:
-  //   A: 256 rows x 8 chunks of 16 bytes; thread t takes chunk (t & 7) of rows (t >> 3) + 64*i, i < 4;
-  //   B: blocks of 4 k x 8 n; thread t takes block (k quad t >> 5, n block t & 31), loads its four
-  //      rows (16 bytes each) and transposes them in registers into eight 8-byte k-runs, one per
-  //      column of the transposed tile.
-  // Eight 16-byte global loads per thread and K step: vector-memory instructions are issued at a
-  // fixed rate per CU whatever their width, so wide loads keep the issue time of a K step short.
+  //   A: 256 rows x 8 chunks of 16 bytes; thread t takes chunk (t & 7) of rows (t >> 3) + (T/8)*i;
+  //   B: blocks of 4 k x 8 n, 16 x 32 of them; thread t takes blocks t + T*j (k quad id >> 5, n block
+  //      id & 31), loads the four rows of each (16 bytes each) and transposes them in registers into
+  //      eight 8-byte k-runs, one per column of the transposed tile.
+  // 2048/T + 4*(512/T) 16-byte global loads per thread and K step: vector-memory instructions are
+  // issued at a fixed rate per CU whatever their width, so wide loads keep the issue time short.
   const uint32_t a_row = tid >> 3, a_chunk = tid & 7u;
-  const uint32_t b_kq = tid >> 5, b_nb = tid & 31u;
   const uint16_t* src_a = g.A + (size_t)(m0 + a_row) * g.K + a_chunk * 8;
-  const uint16_t* src_b = g.B + (size_t)(b_kq * 4) * g.N + n0 + b_nb * 8;
-  // LDS byte offsets inside a stage
-  uint32_t a_dst[4];
+  uint32_t a_dst[NA];  // LDS byte offsets inside a stage
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_dst[i] = tile_off<BK>(a_row + 64 * i, a_chunk);
-  // column c of the block goes to row 8*b_nb + c of the transposed tile, chunk b_kq / 2, half b_kq % 2;
-  // the rows of one block differ only in the swizzle term, so one base and c ^ const does it
-  const uint32_t b_chunk = b_kq >> 1, b_half = (b_kq & 1u) * 8u;
+  for (int i = 0; i < NA; ++i) a_dst[i] = tile_off<BK>(a_row + (T / 8) * i, a_chunk);
+  // column c of a block goes to row 8*nb + c of the transposed tile, chunk kq / 2, half kq % 2
+  const uint32_t b_nb = tid & 31u;
+  const uint16_t* src_b = g.B + (size_t)((tid >> 5) * 4) * g.N + n0 + b_nb * 8;
 
-  u32x4 la[4], lb[4];  // staging registers: A chunks, B rows
+  u32x4 la[NA], lb[NB][4];  // staging registers: A chunks, B rows
   auto load_a = [&](uint32_t kt, int i) {
-    la[i] = *reinterpret_cast<const u32x4*>(src_a + (size_t)kt * BK + (size_t)(64 * i) * g.K);
+    la[i] = *reinterpret_cast<const u32x4*>(src_a + (size_t)kt * BK + (size_t)((T / 8) * i) * g.K);
   };
-  auto load_b = [&](uint32_t kt, int i) {
-    lb[i] = *reinterpret_cast<const u32x4*>(src_b + (size_t)kt * BK * g.N + (size_t)i * g.N);
+  auto load_b = [&](uint32_t kt, int j, int i) {  // block j of this thread starts T/32 k quads further down
+    lb[j][i] = *reinterpret_cast<const u32x4*>(src_b + ((size_t)kt * BK + (size_t)((T / 32) * 4 * j + i)) * g.N);
   };
   auto store_a = [&](uint32_t stage, int i) {
     *reinterpret_cast<u32x4*>(smem + stage * STAGE + a_dst[i]) = la[i];
   };
-  // word j of the four rows holds columns 2j (low halves) and 2j+1 (high halves)
-  auto store_b = [&](uint32_t stage, int j) {
+  // word w of the four rows holds columns 2w (low halves) and 2w+1 (high halves)
+  auto store_b = [&](uint32_t stage, int j, int w) {
     unsigned char* sB = smem + stage * STAGE + A_BYTES;
-    const uint32_t w0 = lb[0][j], w1 = lb[1][j], w2 = lb[2][j], w3 = lb[3][j];
+    const uint32_t kq = (tid >> 5) + (T / 32) * (uint32_t)j;
+    const uint32_t w0 = lb[j][0][w], w1 = lb[j][1][w], w2 = lb[j][2][w], w3 = lb[j][3][w];
     u32x2 ev, od;
     ev.x = (w0 & 0xFFFFu) | (w1 << 16); ev.y = (w2 & 0xFFFFu) | (w3 << 16);
     od.x = (w0 >> 16) | (w1 & 0xFFFF0000u); od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
-    const uint32_t n = b_nb * 8u + 2u * (uint32_t)j;
-    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n, b_chunk) + b_half) = ev;
-    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, b_chunk) + b_half) = od;
+    const uint32_t n = b_nb * 8u + 2u * (uint32_t)w;
+    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n, kq >> 1) + (kq & 1u) * 8u) = ev;
+    *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, kq >> 1) + (kq & 1u) * 8u) = od;
   };
 
-  const uint32_t wm = wave >> 2, wn = wave & 3u;  // wave position: 2 x 4
+  const uint32_t wm = WAVES == 8 ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
+  const uint32_t wn = WAVES == 8 ? wave & 3u : wave & 1u;
   f32x16 acc[TN][4];                               // [tn][tm], transposed tiles (rows = n, cols = m)
 #pragma unroll
   for (int a = 0; a < TN; ++a)
@@ -237,12 +239,18 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // prologue: K step 0 into stage 0, K step 1 into the staging registers
   const uint32_t KT = g.K / BK;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { load_a(0, i); load_b(0, i); }
+  for (int i = 0; i < NA; ++i) load_a(0, i);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { store_a(0, i); store_b(0, i); }
+  for (int i = 0; i < 4 * NB; ++i) load_b(0, i >> 2, i & 3);
+#pragma unroll
+  for (int i = 0; i < NA; ++i) store_a(0, i);
+#pragma unroll
+  for (int i = 0; i < 4 * NB; ++i) store_b(0, i >> 2, i & 3);
   if (KT > 1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { load_a(1, i); load_b(1, i); }
+    for (int i = 0; i < NA; ++i) load_a(1, i);
+#pragma unroll
+    for (int i = 0; i < 4 * NB; ++i) load_b(1, i >> 2, i & 3);
   }
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
@@ -277,22 +285,25 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
         for (int tm = 0; tm < 4; ++tm) {
           acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
-          // one staging piece after every second MFMA: 16 slots per K step, 12 used
+          // one staging piece after every second MFMA: 8*TN slots per K step, NA + 8*NB used
           if (tm & 1) {
-            const int slot = ks * 4 + tn * 2 + (tm >> 1);
+            constexpr int S = 8 * TN;
+            const int slot = ks * (2 * TN) + tn * 2 + (tm >> 1);
             // The global loads keep their place between the MFMAs (the two fences let everything but
             // MFMA and vector-memory instructions move across): left alone, the scheduler sinks all
-            // eight to the end of the iteration and the next iteration waits for them at once.
-            if (slot < 4) {                      // A chunk `slot`: out to LDS, refill
+            // of them to the end of the iteration and the next iteration waits for them at once.
+            if (slot < NA) {                                    // A chunk `slot`: out to LDS, refill
               if constexpr (MORE) store_a(stage ^ 1u, slot);
               __builtin_amdgcn_sched_barrier(0x386);
               if constexpr (MORE2) load_a(kt + 2, slot);
               __builtin_amdgcn_sched_barrier(0x386);
-            } else if (slot >= 8 && slot < 12) {  // B columns 2j, 2j+1
-              if constexpr (MORE) store_b(stage ^ 1u, slot - 8);
-            } else if (slot >= 12) {              // B rows: refill
+            } else if (slot >= S / 2 && slot < S / 2 + 4 * NB) {  // B block j, columns 2w and 2w+1
+              const int q = slot - S / 2;
+              if constexpr (MORE) store_b(stage ^ 1u, q >> 2, q & 3);
+            } else if (slot >= S / 2 + 4 * NB && slot < S / 2 + 8 * NB) {  // B rows: refill
+              const int q = slot - S / 2 - 4 * NB;
               __builtin_amdgcn_sched_barrier(0x386);
-              if constexpr (MORE2) load_b(kt + 2, slot - 12);
+              if constexpr (MORE2) load_b(kt + 2, q >> 2, q & 3);
               __builtin_amdgcn_sched_barrier(0x386);
             }
           }
@@ -344,8 +355,9 @@ namespace {
 struct GemmShape { int bm, bn, bk, waves, regions; };
 
 // Waves per workgroup of the 256x256x64 kernel.  The kernel template also builds with 4 waves
-// (128x128 of C per wave, one wave per SIMD); on MI355X that variant measured the same speed
-// (143 vs 145 us at 4096^3), so only the 8-wave form is instantiated.
+// (128x128 of C per wave, accumulators in AGPRs, one wave per SIMD); on MI355X that variant measured
+// about the same speed (146 vs 137-142 us at 4096^3: a third less LDS read traffic and a short
+// barrier, but a single wave per SIMD hides less), so only the 8-wave form is instantiated.
 constexpr int kBigWaves = 8;
 
 bool pick_shape(int M, int N, int K, GemmShape* s) {
