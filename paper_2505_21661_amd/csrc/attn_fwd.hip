@@ -12,6 +12,8 @@
 // products are formed transposed so that a lane holds all scores of ONE query row: the row
 // maximum and sum are then in-lane reductions plus one exchange with the lane 32 away, and the
 // rescaling of the output accumulators is a per-lane multiply.
+#include <type_traits>
+
 #include "kp_common.h"
 #include "kp_record.h"
 
@@ -139,9 +141,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   load_v(0);
   store_k();
   store_v();
-  if (n_tiles > 1) { load_k(kBkv); load_v(kBkv); }
-  __syncthreads();
-  for (uint32_t t = 0; t < n_tiles; ++t) {
+  load_k(kBkv);  // there are always at least two tiles (S is a multiple of 128)
+  load_v(kBkv);
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  // One KV tile.  MORE / MORE2 (tile t+1 / t+2 exists) and MASK (the tile may reach past the diagonal)
+  // are compile-time: the steady-state body has no branch around its loads and LDS writes, so the
+  // compiler can wait for exactly the loads a write needs instead of for all outstanding ones.  The
+  // barriers wait for LDS traffic only, never for the global loads of later tiles.
+  auto tile = [&](uint32_t t, auto more_c, auto more2_c, auto mask_c) {
+    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value, MASK = decltype(mask_c)::value;
     const uint32_t kv0 = t * kBkv;
 
     // ---- region 0: S^T = K Q^T --------------------------------------------------------------------
@@ -159,14 +167,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     KP_BOUNDARY(ring, 0, 1);
 
     // every wave is done with K tile t; the next one goes to LDS while the softmax runs
-    __syncthreads();
-    if (t + 1 < n_tiles) {
-      store_k();
-      if (t + 2 < n_tiles) load_k(kv0 + 2 * kBkv);
-    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (MORE) store_k();
+    if constexpr (MORE2) load_k(kv0 + 2 * kBkv);
 
     // ---- region 1: online softmax (this lane: query row qrow, 32 of the tile's 64 kv) -------------
-    const bool diag = g.causal && (kv0 + kBkv > q0 + wave * 32);  // tile reaches past this wave's first row
+    const bool diag = MASK && g.causal && (kv0 + kBkv > q0 + wave * 32);  // tile reaches past this wave's first row
     float mx = -INFINITY;  // maximum of the raw scores; the positive scale is applied afterwards
 #pragma unroll
     for (int tk = 0; tk < 2; ++tk)
@@ -223,12 +229,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       }
     KP_BOUNDARY(ring, 2, kp::kNoRegion);
 
-    __syncthreads();  // every wave is done with V^T tile t, and K tile t+1 is visible
-    if (t + 1 < n_tiles) {
-      store_v();
-      if (t + 2 < n_tiles) load_v(kv0 + 2 * kBkv);
-    }
-  }
+    // every wave is done with V^T tile t, and K tile t+1 is visible
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (MORE) store_v();
+    if constexpr (MORE2) load_v(kv0 + 2 * kBkv);
+  };
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
+  // only the last two tiles of a causal block can reach past the diagonal
+  for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, yes, no);
+  tile(n_tiles - 2, yes, no, yes);
+  tile(n_tiles - 1, no, no, yes);
 
   // epilogue: O[q][d] = O^T[d][q] / l
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
