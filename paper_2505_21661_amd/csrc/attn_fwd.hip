@@ -134,15 +134,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   float m_run = -INFINITY, l_run = 0.f;
 
   const uint32_t n_tiles = g.causal ? (q0 + kBq) / kBkv : g.S / kBkv;
-  // Staging is split so that it overlaps the other waves' arithmetic: the K tile is only read by
-  // region 0 and the V^T tile only by region 2, so tile t+1 of K is written after the barrier that
-  // follows region 0 of tile t, and tile t+1 of V after the barrier that follows region 2.
+  // Staging overlaps arithmetic: the K tile is only read by region 0 and the V^T tile only by
+  // region 2, so K tile t+1 is written after the barrier that follows region 0 of tile t (while the
+  // softmax runs), and V^T tile t during region 0 of tile t itself, between the MFMAs of K Q^T (every
+  // wave left region 2 of tile t-1 before the barrier that precedes it).  Each staging register is
+  // refilled from global memory right after it has been written out: a whole tile ahead.
   load_k(0);
   load_v(0);
   store_k();
-  store_v();
   load_k(kBkv);  // there are always at least two tiles (S is a multiple of 128)
-  load_v(kBkv);
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   // One KV tile.  MORE / MORE2 (tile t+1 / t+2 exists) and MASK (the tile may reach past the diagonal)
   // are compile-time: the steady-state body has no branch around its loads and LDS writes, so the
@@ -152,8 +152,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value, MASK = decltype(mask_c)::value;
     const uint32_t kv0 = t * kBkv;
 
-    // ---- region 0: S^T = K Q^T --------------------------------------------------------------------
+    // ---- region 0: S^T = K Q^T, with the staging of V^T tile t threaded in ------------------------
     KP_BOUNDARY(ring, kp::kNoRegion, 0);
+    store_v();
+    if constexpr (MORE) load_v(kv0 + kBkv);
     f32x16 sacc[2];
     sacc[0] = f32x16{0}; sacc[1] = f32x16{0};
 #pragma unroll
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     }
     KP_BOUNDARY(ring, 0, 1);
 
-    // every wave is done with K tile t; the next one goes to LDS while the softmax runs
+    // every wave is done with K tile t and V^T tile t is visible; K tile t+1 goes to LDS while the softmax runs
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if constexpr (MORE) store_k();
     if constexpr (MORE2) load_k(kv0 + 2 * kBkv);
@@ -231,8 +233,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
 
     // every wave is done with V^T tile t, and K tile t+1 is visible
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if constexpr (MORE) store_v();
-    if constexpr (MORE2) load_v(kv0 + 2 * kBkv);
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
