@@ -8,6 +8,9 @@ library or its Python binding, and shares no code with them.
 
   ref_decode.c : trace decode / pair / reduce (Sec. 4.2 record layout and
                  circular buffer, Sec. 4.3 trace replay)
+  ref_pairs.c  : one timeline row per paired region instance, with its iteration
+                 index (Sec. 3.2 decoded activity records, Sec. 3.3 iteration-based
+                 timing)
   ref_dense.py : the dense kernels that get instrumented -- GEMM and causal
                  attention forward by their textbook definitions, fp64
 
@@ -36,23 +39,30 @@ HEADER_FIELDS = (
 PER_DTYPE = np.dtype([("sum", "<u8"), ("n", "<u4"), ("max", "<u4")])
 
 
+_SOURCES = ("ref_decode.c", "ref_pairs.c")
+
+
 def build(force: bool = False) -> str:
-    src = os.path.join(_HERE, "ref_decode.c")
-    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(src):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB_PATH, src])
+    srcs = [os.path.join(_HERE, f) for f in _SOURCES]
+    stale = not os.path.exists(_LIB_PATH) or any(os.path.getmtime(_LIB_PATH) < os.path.getmtime(f) for f in srcs)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB_PATH, *srcs])
     return _LIB_PATH
 
 
 def _load():
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIB_PATH):
-            build()
+        build()
         lib = ctypes.CDLL(_LIB_PATH)
         lib.kpo_stats_bytes.restype = ctypes.c_size_t
         lib.kpo_stats_bytes.argtypes = [ctypes.c_uint32] * 3
         lib.kpo_decode.restype = ctypes.c_int
         lib.kpo_decode.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        lib.kpo_pairs_bytes.restype = ctypes.c_size_t
+        lib.kpo_pairs_bytes.argtypes = [ctypes.c_uint32] * 3
+        lib.kpo_pairs.restype = ctypes.c_int
+        lib.kpo_pairs.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t]
         _lib = lib
     return _lib
 
@@ -100,6 +110,43 @@ def view_stats(buf: np.ndarray) -> dict:
 
 def decode(raw: np.ndarray, n_threads: int = 1) -> dict:
     return view_stats(decode_bytes(raw, n_threads))
+
+
+PAIR_ROW_DTYPE = np.dtype([("start", "<u4"), ("dur", "<u4"), ("iter", "<u4"), ("region", "<u4")])
+
+
+def pairs_bytes(n_wg: int, waves: int, cap_wave: int) -> int:
+    return _load().kpo_pairs_bytes(n_wg, waves, cap_wave)
+
+
+def pairs_raw(raw: np.ndarray, fill: int = 0xA5) -> np.ndarray:
+    """Run the reference timeline decoder; returns the output block bytes (unwritten rows keep `fill`)."""
+    assert raw.dtype == np.uint32 and raw.flags["C_CONTIGUOUS"]
+    n_wg, waves, R, cap = (int(x) for x in raw[2:6])
+    n_slots = n_wg * waves * cap
+    if raw.size * 4 < 64 + 128 * n_wg + 8 * n_slots:
+        raise ValueError("raw buffer shorter than its header claims")
+    out = np.full(pairs_bytes(n_wg, waves, cap), fill, dtype=np.uint8)
+    rc = _load().kpo_pairs(raw.ctypes.data, n_slots, out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError(f"kpo_pairs rejected the trace (rc={rc})")
+    return out
+
+
+def view_pairs(buf: np.ndarray, n_wg: int, waves: int, cap_wave: int):
+    """Split a pairs block into (count[n_wg, waves], rows[n_wg, waves, cap_wave // 2])."""
+    b = np.ascontiguousarray(buf).view(np.uint8)
+    n_seg = n_wg * waves
+    head = ((n_seg + 3) // 4) * 16
+    count = b[: 4 * n_seg].view("<u4").reshape(n_wg, waves)
+    rows = b[head : head + 16 * n_seg * (cap_wave // 2)].view(PAIR_ROW_DTYPE).reshape(n_wg, waves, cap_wave // 2)
+    return count, rows
+
+
+def pairs(raw: np.ndarray):
+    """Reference timeline rows: list over (wg, wave) of structured arrays, plus the counts."""
+    n_wg, waves, _R, cap = (int(x) for x in raw[2:6])
+    return view_pairs(pairs_raw(raw), n_wg, waves, cap)
 
 
 from .ref_dense import ref_gemm, ref_attn, bf16_round  # noqa: E402,F401

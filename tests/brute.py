@@ -119,3 +119,43 @@ def assert_same(ref: dict, got: dict):
     assert np.array_equal(ref["per"][..., 0], p["sum"])
     assert np.array_equal(ref["per"][..., 1], p["n"].astype(np.uint64))
     assert np.array_equal(ref["per"][..., 2], p["max"].astype(np.uint64))
+
+
+def brute_pairs(raw: np.ndarray):
+    """Independent timeline rows: per (wg, wave) a list of (start, dur, iter, region).
+
+    Written differently from oracle/ref_pairs.c on purpose: the records of a wave are sorted by
+    rank with a dict, each region's subsequence is extracted as a list and scanned for adjacent
+    START/END neighbours, and the rows are then ordered by the rank of their END record.
+    """
+    raw = [int(x) for x in raw]
+    assert raw[0] == 0x4652504B and raw[1] == 1
+    n_wg, W, R, cap, rec_cost, flags = raw[2:8]
+    flush = flags & 1
+    rec0 = (64 + 128 * n_wg) // 4
+    out = {}
+    for wg in range(n_wg):
+        h = (64 + 128 * wg) // 4
+        for w in range(W):
+            T = raw[h + 8 + w]
+            V = min(T, cap)
+            first = 0 if flush else T - V
+            by_rank = {}
+            for s in range(V):
+                tag = raw[rec0 + 2 * ((wg * W + w) * cap + s)]
+                ts = raw[rec0 + 2 * ((wg * W + w) * cap + s) + 1]
+                seq, wave, region, phase = tag & 0xFFFFF, (tag >> 20) & 15, (tag >> 24) & 127, tag >> 31
+                k = (seq - first) % (1 << 20)
+                if k >= V or wave != w or region >= R:
+                    continue
+                by_rank[k] = (region, phase, ts)
+            rows = []  # (rank of END, start, dur, iter, region)
+            for r in range(R):
+                sub = [(k, ph, ts) for k, (rg, ph, ts) in sorted(by_rank.items()) if rg == r]
+                it = 0
+                for (k0, p0, t0), (k1, p1, t1) in zip(sub, sub[1:]):
+                    if p0 == 0 and p1 == 1:
+                        rows.append((k1, t0, max(0, (t1 - t0) % (1 << 32) - rec_cost), it, r))
+                        it += 1
+            out[(wg, w)] = [row[1:] for row in sorted(rows)]
+    return out
