@@ -148,6 +148,36 @@ kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats, void* stre
 kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
                               void* out_stats, void* stream);
 
+/*
+ * Timeline rows of the same replay.  The paper decodes the profile buffer into one activity
+ * struct per timed region instance for timeline front ends such as Chrome Trace (Sec. 3.2) and
+ * associates loop iterations with the records (Sec. 3.3 "Iteration-based Timing").  One row per
+ * paired START/END, paired exactly as kp_trace_reduce pairs them:
+ *   start   payload of the START record: clock ticks since the workgroup began
+ *   dur     (u32)(end - start) minus the trace header's rec_cost, not below 0
+ *   iter    number of earlier pairs of the same (workgroup, wave, region) among the surviving
+ *           records: the loop iteration when the region is recorded once per iteration and the
+ *           ring did not wrap
+ *   region  region id
+ * Output block (device, kp_pairs_bytes(...) bytes, 16-byte aligned):
+ *   u32 count[n_wg * waves_per_wg], padded with zeros to a multiple of 4 entries, then
+ *   kp_pair_row rows[n_wg * waves_per_wg][cap_wave / 2]; the rows of a wave are ordered by their END
+ *   records and only the first count[wg * waves_per_wg + wave] of them are written.
+ * Arguments, synchronisation, limits (n_regions <= 128 here) and errors as for kp_trace_reduce /
+ * kp_trace_reduce_hdr; a device header that disagrees with hdr_host gives undefined rows.
+ */
+typedef struct {
+  uint32_t start;
+  uint32_t dur;
+  uint32_t iter;
+  uint32_t region;
+} kp_pair_row;
+
+size_t kp_pairs_bytes(int n_wg, int waves_per_wg, int cap_per_wg);
+kp_status kp_trace_pairs(const void* raw, size_t n, void* out_pairs, void* stream);
+kp_status kp_trace_pairs_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                             void* out_pairs, void* stream);
+
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
  * region_mask: bit r (r < 31) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)

@@ -61,6 +61,12 @@ def lib() -> ctypes.CDLL:
         L.kp_trace_reduce.argtypes = [vp, sz, vp, vp]
         L.kp_trace_reduce_hdr.restype = ci
         L.kp_trace_reduce_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
+        L.kp_pairs_bytes.restype = sz
+        L.kp_pairs_bytes.argtypes = [ci, ci, ci]
+        L.kp_trace_pairs.restype = ci
+        L.kp_trace_pairs.argtypes = [vp, sz, vp, vp]
+        L.kp_trace_pairs_hdr.restype = ci
+        L.kp_trace_pairs_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
         _optional(L)
         _lib = L
     return _lib
@@ -135,6 +141,34 @@ def make_hdr(n_wg: int, waves_per_wg: int, n_regions: int, cap_wave: int, rec_co
 
 def kp_trace_reduce_hdr(raw, n: int, hdr_host: kp_trace_hdr, out_stats, stream=None) -> None:
     _check(lib().kp_trace_reduce_hdr(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_stats), _stream(stream)))
+
+
+def kp_pairs_bytes(n_wg: int, waves_per_wg: int, cap_per_wg: int) -> int:
+    return lib().kp_pairs_bytes(n_wg, waves_per_wg, cap_per_wg)
+
+
+def kp_trace_pairs(raw, n: int, out_pairs, stream=None) -> None:
+    _check(lib().kp_trace_pairs(_ptr(raw), n, _ptr(out_pairs), _stream(stream)))
+
+
+def kp_trace_pairs_hdr(raw, n: int, hdr_host: kp_trace_hdr, out_pairs, stream=None) -> None:
+    _check(lib().kp_trace_pairs_hdr(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_pairs), _stream(stream)))
+
+
+PAIR_ROW_DTYPE = [("start", "<u4"), ("dur", "<u4"), ("iter", "<u4"), ("region", "<u4")]
+
+
+def parse_pairs(buf, n_wg: int, waves_per_wg: int, cap_per_wg: int):
+    """Split a pairs block (host bytes: numpy array or CPU tensor) into (count[n_wg, waves],
+    rows[n_wg, waves, cap_wave // 2]); only the first count[wg, wave] rows of a wave are meaningful."""
+    import numpy as np
+
+    b = np.ascontiguousarray(buf.numpy() if hasattr(buf, "numpy") else buf).view(np.uint8)
+    n_seg, half = n_wg * waves_per_wg, cap_per_wg // waves_per_wg // 2
+    head = ((n_seg + 3) // 4) * 16
+    count = b[: 4 * n_seg].view("<u4").reshape(n_wg, waves_per_wg)
+    rows = b[head : head + 16 * n_seg * half].view(np.dtype(PAIR_ROW_DTYPE)).reshape(n_wg, waves_per_wg, half)
+    return count, rows
 
 
 def kp_gemm_launch_shape(M: int, N: int, K: int) -> tuple[int, int, int]:
