@@ -9,6 +9,7 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
      (3 regions, ring of 1024 records per workgroup, wraps) alternately, two of each
   4. kp_trace_reduce of the attention trace
   5. kp_trace_reduce of the standalone decode workload: 2^28 synthetic records
+  6. kp_trace_pairs of the same records: one timeline row per paired region instance
 All inputs are resident in HBM before the timed region starts.  Every kernel is bracketed by
 HIP events on the launch stream inside the timed region; the per-kernel figures below are
 averages over the timed steps.
@@ -33,9 +34,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1055619.6 * 2.0 + 45176.8) * 1024,
-    "gemm_vanilla": (98372.0 * 2.0 + 34134.4) * 1024,
-    "attn_vanilla": (1418176.1 * 2.0 + 132271.8) * 1024,
+    "decode_2^28": (1055563.6 * 2.0 + 45176.8) * 1024,
+    "gemm_vanilla": (98377.0 * 2.0 + 32828.0) * 1024,
+    "attn_vanilla": (1554003.2 * 2.0 + 131970.9) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
@@ -92,13 +93,16 @@ def main() -> int:
     d_raw = torch.from_numpy(raw.view(np.int32)).to(dev)
     d_stats = torch.zeros(kp.kp_stats_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
     d_hdr = kp.make_hdr(spec.n_wg, spec.waves, spec.n_regions, spec.cap_wave)
+    d_pairs = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8,
+                          device=dev)
     torch.cuda.synchronize()
 
     # The dense kernels run as vanilla/instrumented pairs, twice, after one warm launch, so that both
     # members of a pair see the same cache and clock state (the preceding decode of a 2 GiB trace
     # leaves L2 and the memory-side cache cold); every launch is inside the timed step.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_vanilla2", "gemm_instr2", "gemm_reduce",
-             "attn_warm", "attn_vanilla", "attn_instr", "attn_vanilla2", "attn_instr2", "attn_reduce", "decode"]
+             "attn_warm", "attn_vanilla", "attn_instr", "attn_vanilla2", "attn_instr2", "attn_reduce", "decode",
+             "timeline"]
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
@@ -111,6 +115,7 @@ def main() -> int:
             attn_v, attn_v, attn_i, attn_v, attn_i,
             lambda: kp.kp_trace_reduce_hdr(a_trace, a_wg * a_cap, a_hdr, a_stats),
             lambda: kp.kp_trace_reduce_hdr(d_raw, d_n, d_hdr, d_stats),
+            lambda: kp.kp_trace_pairs_hdr(d_raw, d_n, d_hdr, d_pairs),
         )
         for i, call in enumerate(calls):
             if events is not None:
@@ -151,6 +156,12 @@ def main() -> int:
 
     st = kp.parse_stats(d_stats)
     assert st["status"] == 0 and st["n_slots_valid"] == d_n, "decode workload did not decode"
+    # timeline rows of the same trace: 8 B read per record, 16 B written per pair, 4 B per (wg, wave)
+    n_seg = spec.n_wg * spec.waves
+    pair_count = d_pairs[: 4 * n_seg].view(torch.int32).sum(dtype=torch.int64).item()
+    assert pair_count == st["n_pairs"], "timeline rows and statistics disagree on the number of pairs"
+    tl_bytes = 8.0 * d_n + 16.0 * pair_count + 4.0 * n_seg + 128.0 * spec.n_wg
+    tl_gbs = tl_bytes / (ms["timeline"] * 1e-3) / 1e9
 
     # Overhead model of the paper, eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the
     # per-record cost taken from the calibration kernel (an empty START/END region, i.e. two records)
@@ -208,6 +219,7 @@ def main() -> int:
         "attn_instrumented_tflops": round(attn_tf_ins, 2),
         "decode_records_per_s": round(dec_rps, 1),
         "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4),
+        "timeline_records_per_s": round(d_n / (ms["timeline"] * 1e-3), 1),
         "kernel_ms": {n: round(x, 4) for n, x in ms.items()},
         "overhead_model_eq1": eq1,
         "paper_context": {"overhead_pct": 8.2, "hardware": "H100 / MI300X (not split), Triton GEMM/FA3"},
@@ -239,6 +251,16 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": round(attn_tf_van / PEAK_BF16_TFLOPS, 4),
             "traffic": round(TRAFFIC_BYTES["attn_vanilla"]),
+        },
+        "roofline_timeline": {
+            "kernel": "kp_pairs_main (timeline rows of the decode workload)",
+            "bound": "hbm",
+            "achieved": round(tl_gbs, 2),
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": round(tl_gbs / PEAK_HBM_GBS, 4),
+            "algorithmic_bytes": round(tl_bytes),
+            "traffic": None,
         },
     }
 

@@ -49,6 +49,14 @@ def lib() -> ctypes.CDLL:
             raise ImportError(
                 f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`"
             )
+        # The caller's device buffers come from torch, which ships its own copy of the HIP runtime.
+        # That copy has to be the first one in the process: if this library pulled in the system's
+        # runtime before torch loaded its own, the two would not share a device context and every
+        # launch from here would fail with "no ROCm-capable device".
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, ci, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint32
         L.kp_last_error.restype = ctypes.c_char_p

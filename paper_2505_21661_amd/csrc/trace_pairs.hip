@@ -15,7 +15,7 @@
 //   - an END looks at the four ranks below through DPP wave shifts for the nearest record of its
 //     region (deeper only if needed) and is paired iff that record is a START;
 //   - its row index is the running count of paired ENDs (ballot + popcount);
-//   - its iteration index comes from byte-wide per-region counters packed eight to a 64-bit
+//   - its iteration index comes from byte-wide per-region counters packed four to a 32-bit
 //     word and prefix-summed across the lanes, on top of the per-region totals of earlier rounds.
 #include "kp_common.h"
 
@@ -45,7 +45,7 @@ __host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint3
   LdsLayout l;
   uint32_t o = 0;
   l.rec = o; o = align16(o + nrec * 8);
-  l.iter_base = o; o = align16(o + W * ((R + 7u) & ~7u) * 4);  // pairs seen so far per (wave, region)
+  l.iter_base = o; o = align16(o + W * ((R + 3u) & ~3u) * 4);  // pairs seen so far per (wave, region)
   l.tmp = o; o = align16(o + T_COUNT * 4);
   l.v = o; o = align16(o + 16 * 4);
   l.first = o; o = align16(o + 16 * 4);
@@ -64,13 +64,15 @@ __device__ __forceinline__ uint32_t wave_shr1(uint32_t v, uint32_t lane0) {
   return (uint32_t)__builtin_amdgcn_update_dpp((int)lane0, (int)v, 0x138, 0xF, 0xF, false);
 }
 
-// Inclusive prefix sum of a 64-bit value over the 64 lanes.
-__device__ __forceinline__ unsigned long long wave_scan_add(unsigned long long v, uint32_t lane) {
-#pragma unroll
-  for (uint32_t d = 1; d < 64; d <<= 1) {
-    const uint32_t lo = __shfl_up((uint32_t)v, d, 64), hi = __shfl_up((uint32_t)(v >> 32), d, 64);
-    if (lane >= d) v += ((unsigned long long)hi << 32) | lo;
-  }
+// Inclusive prefix sum over the 64 lanes: four shifts inside each row of 16, then the last lane of
+// row 0/2 into row 1/3 and the last lane of the lower half into the upper half.
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
   return v;
 }
 
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
   const uint32_t tid = threadIdx.x, lane = tid & 63u, hw = tid >> 6;
   const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec;
   const uint32_t capm = cap - 1, cl2 = p.cap_log2;
-  const uint32_t Rpad = (R + 7u) & ~7u, nwords = Rpad >> 3;
+  const uint32_t Rpad = (R + 3u) & ~3u, nwords = Rpad >> 2;
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
   // the padding entries of the count array are part of the output: zero
@@ -212,18 +214,19 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
         const bool paired = is_end && have && !(pm & kMEnd);
         const unsigned long long pb = __builtin_amdgcn_ballot_w64(paired);
         if (pb == 0ull) continue;
-        // iteration index: pairs of this region in earlier rounds + earlier lanes of this round
+        // iteration index: pairs of this region in earlier rounds + earlier lanes of this round.
+        // Four regions share a 32-bit word of byte-wide counters (at most 64 per round, so no byte
+        // carries into its neighbour and one 32-bit prefix sum counts four regions at once).
         uint32_t it = 0;
         for (uint32_t wd = 0; wd < nwords; ++wd) {
-          const bool mine = paired && (region >> 3) == wd;
+          const bool mine = paired && (region >> 2) == wd;
           if (__builtin_amdgcn_ballot_w64(mine) == 0ull) continue;
-          const unsigned long long one = mine ? (1ull << (8u * (region & 7u))) : 0ull;
-          const unsigned long long incl = wave_scan_add(one, lane);
-          if (mine) it = my_base[region] + (uint32_t)(((incl - one) >> (8u * (region & 7u))) & 0xFFu);
-          const uint32_t tot_lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)incl, 63);
-          const uint32_t tot_hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(incl >> 32), 63);
-          const unsigned long long tot = ((unsigned long long)tot_hi << 32) | tot_lo;
-          if (lane < 8) my_base[wd * 8 + lane] += (uint32_t)((tot >> (8u * lane)) & 0xFFu);
+          const uint32_t sh = 8u * (region & 3u);
+          const uint32_t one = mine ? (1u << sh) : 0u;
+          const uint32_t incl = wave_scan_add(one);
+          if (mine) it = my_base[region] + (((incl - one) >> sh) & 0xFFu);
+          const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+          if (lane < 4) my_base[wd * 4 + lane] += (tot >> (8u * lane)) & 0xFFu;
         }
         if (paired) {
           const uint32_t pt = recw[2 * pq];
