@@ -124,3 +124,32 @@ def test_repeated_calls_are_deterministic(kp, oracle_mod):
     first = gpu_decode_bytes(raw, dev_raw=dev)
     for _ in range(3):
         assert np.array_equal(first, gpu_decode_bytes(raw, use_hdr=True, dev_raw=dev))
+
+
+def test_decode_workload_full_size(kp, oracle_mod):
+    """The benchmark's decode workload at its full size (2^28 records, 16384 workgroups x 8 waves x
+    2048 records, 16 regions) in the launch configuration bench.py times (kp_trace_reduce_hdr and
+    kp_trace_pairs_hdr): the whole statistics block and every timeline row, bit for bit."""
+    import os
+
+    spec = inputs.spec_decode_standalone(28)
+    raw, _ = inputs.gen_trace(spec)
+    n = spec.n_slots
+    dev_raw = torch.from_numpy(raw.view(np.int32)).cuda()
+    hdr = kp.make_hdr(spec.n_wg, spec.waves, spec.n_regions, spec.cap_wave)
+    out = torch.full((kp.kp_stats_bytes(spec.n_wg, spec.waves, spec.n_regions),), 0xAB, dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce_hdr(dev_raw, n, hdr, out)
+    rows = torch.full((kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave),), 0xA5, dtype=torch.uint8,
+                      device="cuda")
+    kp.kp_trace_pairs_hdr(dev_raw, n, hdr, rows)
+    torch.cuda.synchronize()
+    from tests.gpu_util import assert_stats_equal
+
+    want = oracle_mod.decode_bytes(raw, min(16, os.cpu_count() or 1))
+    assert_stats_equal(want, out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    assert st["n_slots_valid"] == n and st["n_overlap_wgs"] == spec.n_wg and st["n_invalid"] == 0
+    del out, want
+    want_rows = oracle_mod.pairs_raw(raw, fill=0xA5)
+    got_rows = rows.cpu().numpy()
+    assert np.array_equal(want_rows, got_rows)
