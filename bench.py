@@ -59,6 +59,7 @@ def main() -> int:
 
     import inputs
     import paper_2505_21661_amd as kp
+    from paper_2505_21661_amd import model
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -185,7 +186,7 @@ def main() -> int:
         "cycle_record": round(pair_cost / 2.0, 1),
         "s_memtime_hz": round(tick_hz),
         "t_vanilla_ticks": round(t_vanilla_ticks),
-        "t_theoretical_ticks": round(t_vanilla_ticks + n_record * pair_cost / 2.0),
+        "t_theoretical_ticks": round(model.theoretical_ticks(t_vanilla_ticks, n_record, pair_cost / 2.0)),
         "t_actual_ticks": round(ms["gemm_instr"] * 1e-3 * tick_hz),
         "note": "cycle_record is the back-to-back cost (it includes the s_memtime round trip); sites "
                 "inside long regions overlap most of it, so the actual time stays below the model",

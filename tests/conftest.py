@@ -26,3 +26,17 @@ def inputs_mod():
 
     inputs.build()
     return inputs
+
+
+@pytest.fixture(scope="session")
+def paper_values():
+    """Values printed in the paper (tests/golden/paper_values.txt), as {key: int or float}."""
+    out = {}
+    with open(os.path.join(ROOT, "tests", "golden", "paper_values.txt")) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if not line:
+                continue
+            key, val = (x.strip() for x in line.split("=", 1))
+            out[key] = float(val) if "." in val else int(val)
+    return out

@@ -43,6 +43,9 @@ def test_size_helpers_and_struct_sizes():
     R, n_wg, W = 5, 7, 4
     assert kp.kp_stats_bytes(n_wg, W, R) == 128 + 8 * (64 * R + 5 * R + 2 * R * R) + 16 * n_wg * W * R
     assert kp.kp_stats_bytes(1, 0, 3) == 0
+    # count array padded to 16 bytes + 16-byte rows, cap_wave / 2 per (workgroup, wave)
+    assert kp.kp_pairs_bytes(3, 2, 64) == 32 + 16 * 3 * 2 * 16
+    assert kp.kp_pairs_bytes(1, 3, 64) == 0
     assert kp.kp_last_error() == "" or isinstance(kp.kp_last_error(), str)
 
 
@@ -62,10 +65,25 @@ def test_host_side_argument_checks_need_no_gpu():
         kp.kp_attn_launch_shape(1, 1, 4096, 64)
 
 
-def test_overhead_model_arithmetic():
+def test_overhead_model_against_table_5(paper_values):
     """Eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the numbers of Table 5."""
-    t_vanilla, t_theoretical, t_actual = 199381, 224981, 229663
-    assert t_theoretical - t_vanilla == 25600            # N_record * Cycle_record
-    assert round(t_actual / t_theoretical, 2) == 1.02    # "within 2 %"
-    assert round(t_vanilla / t_theoretical, 2) == 0.89
-    assert round((t_actual - t_vanilla) / t_vanilla * 100, 1) == 15.2
+    from paper_2505_21661_amd import model
+
+    pv = paper_values
+    t_vanilla, t_theoretical, t_actual = (pv[f"table5.active_cycles.{k}"] for k in ("vanilla", "theoretical", "actual"))
+    # the table's model column is the vanilla column plus records x cycles: 25600 cycles of records
+    extra = t_theoretical - t_vanilla
+    assert extra == 25600
+    assert model.theoretical_ticks(t_vanilla, 800, extra / 800) == t_theoretical
+    rel = model.relative_performance(t_vanilla, t_theoretical, t_actual)
+    assert [round(x, 2) for x in rel] == [pv[f"table5.relative_performance.{k}"] for k in ("vanilla", "theoretical", "actual")]
+    assert round((t_actual - t_vanilla) / t_vanilla * 100, 1) == 15.2   # the GEMM's overhead in per cent
+
+
+def test_layout_constants_match_the_paper(paper_values):
+    import paper_2505_21661_amd as kp
+
+    pv = paper_values
+    assert ctypes.sizeof(ctypes.c_uint32) * 2 == pv["layout.record_bytes"]
+    assert kp.kp_trace_bytes(1, 2, pv["layout.example_slots"]) - kp.kp_trace_bytes(1, 2, 0) == pv["layout.example_bytes"]
+    assert pv["layout.example_slots"] // 2 == pv["layout.example_slots_per_group"]
