@@ -39,13 +39,12 @@ struct PairsParams {
   uint32_t n_wg, W, R, cap, cap_log2, rec_cost, flush, nrec;
 };
 
-struct LdsLayout { uint32_t rec, iter_base, tmp, v, first, total; };
+struct LdsLayout { uint32_t rec, tmp, v, first, total; };
 __host__ __device__ inline uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
 __host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint32_t R) {
   LdsLayout l;
   uint32_t o = 0;
   l.rec = o; o = align16(o + nrec * 8);
-  l.iter_base = o; o = align16(o + W * ((R + 3u) & ~3u) * 4);  // pairs seen so far per (wave, region)
   l.tmp = o; o = align16(o + T_COUNT * 4);
   l.v = o; o = align16(o + 16 * 4);
   l.first = o; o = align16(o + 16 * 4);
@@ -82,7 +81,6 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
   const LdsLayout L = lds_layout(p.nrec, p.W, p.R);
   uint2* rec = reinterpret_cast<uint2*>(smem + L.rec);
   uint32_t* recw = reinterpret_cast<uint32_t*>(smem + L.rec);  // word 2p = clock, 2p+1 = metadata
-  uint32_t* iter_base = reinterpret_cast<uint32_t*>(smem + L.iter_base);
   uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
   uint32_t* sV = reinterpret_cast<uint32_t*>(smem + L.v);
   uint32_t* sFirst = reinterpret_cast<uint32_t*>(smem + L.first);
@@ -111,7 +109,6 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
       sFirst[tid] = p.flush ? 0u : T - V;
     }
     if (tid >= 64 && tid < 64 + T_COUNT) tmp[tid - 64] = 0;
-    for (uint32_t i = tid; i < W * Rpad; i += BLOCK) iter_base[i] = 0;
     if (gen == 1u) {
       u32x4* z = reinterpret_cast<u32x4*>(rec);
       for (uint32_t i = tid; i < nrec / 2; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
@@ -181,15 +178,20 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
     // ---- walk: hardware wave w pairs recorded wave w and emits its rows --------------------------------
     if (hw < W) {
       const uint32_t w = hw, wofs = w << cl2, V = sV[w];
-      uint32_t* my_base = iter_base + w * Rpad;
+      uint32_t base_lo = 0u, base_hi = 0u;  // pairs seen so far: lane r for region r / region 64 + r
       u32x4* my_rows = p.rows + ((size_t)wg * W + w) * (cap / 2);
       uint32_t n_rows = 0;
       uint32_t cm[4] = {0u, 0u, 0u, 0u};  // metadata of the last four ranks of the previous round
+      uint2 r_next = rec[wofs + (lane < V ? lane : 0u)];  // one round ahead, to hide the LDS latency
       for (uint32_t kb = 0; kb < V; kb += 64) {
         const uint32_t k = kb + lane;
         const bool in = k < V;
         const uint32_t q0 = wofs + (in ? k : V - 1);
-        const uint2 r0 = rec[q0];
+        const uint2 r0 = r_next;
+        {
+          const uint32_t kn = k + 64;
+          r_next = rec[wofs + (kn < V ? kn : 0u)];
+        }
         const bool valid = in && is_live(r0.y);
         const uint32_t m0 = valid ? r0.y : 0u, t0 = r0.x;
         const uint32_t m1 = wave_shr1(m0, cm[0]);
@@ -215,21 +217,31 @@ __global__ __launch_bounds__(BLOCK) void kp_pairs_main(PairsParams p) {
         const unsigned long long pb = __builtin_amdgcn_ballot_w64(paired);
         if (pb == 0ull) continue;
         // iteration index: pairs of this region in earlier rounds + earlier lanes of this round.
-        // Four regions share a 32-bit word of byte-wide counters (at most 64 per round, so no byte
-        // carries into its neighbour and one 32-bit prefix sum counts four regions at once).
-        uint32_t it = 0;
+        // The totals of earlier rounds live in registers: lane r holds the count of region r in
+        // base_lo and of region 64 + r in base_hi.  Within the round four regions share a 32-bit
+        // word of byte-wide counters (at most 64 per round, so no byte carries into its neighbour and
+        // one 32-bit prefix sum counts four regions at once).
+        const uint32_t pt = recw[2 * (paired ? pq : wofs)];  // the START's clock, fetched early
+        const int from = (int)((region & 63u) << 2);
+        uint32_t it = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)base_lo);
+        if (R > 64u) {  // uniform: every lane takes part in the exchange
+          const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)base_hi);
+          if (region >= 64u) it = hi;
+        }
         for (uint32_t wd = 0; wd < nwords; ++wd) {
           const bool mine = paired && (region >> 2) == wd;
           if (__builtin_amdgcn_ballot_w64(mine) == 0ull) continue;
           const uint32_t sh = 8u * (region & 3u);
           const uint32_t one = mine ? (1u << sh) : 0u;
           const uint32_t incl = wave_scan_add(one);
-          if (mine) it = my_base[region] + (((incl - one) >> sh) & 0xFFu);
+          if (mine) it += ((incl - one) >> sh) & 0xFFu;
           const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-          if (lane < 4) my_base[wd * 4 + lane] += (tot >> (8u * lane)) & 0xFFu;
+          // the four lanes that own this word's regions add their byte of the round's totals
+          const uint32_t add = (tot >> (8u * (lane & 3u))) & 0xFFu;
+          if (wd < 16u) base_lo += (lane >> 2) == wd ? add : 0u;
+          else          base_hi += (lane >> 2) == wd - 16u ? add : 0u;
         }
         if (paired) {
-          const uint32_t pt = recw[2 * pq];
           const uint32_t d_raw = t0 - pt;
           const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
           const uint32_t j = n_rows + (uint32_t)__popcll(pb & lt_mask);

@@ -57,7 +57,8 @@ def test_messy_traces(kp, oracle_mod, seed):
 
 
 @pytest.mark.parametrize("W,R,cap,total", [(4, 3, 128, 48), (8, 16, 2048, 2048), (8, 16, 2048, 6144),
-                                           (4, 7, 4096, 4096), (1, 2, 16384, 16384), (16, 16, 1024, 1000)])
+                                           (4, 7, 4096, 4096), (1, 2, 16384, 16384), (16, 16, 1024, 1000),
+                                           (4, 128, 1024, 1024), (2, 100, 512, 700), (3, 65, 256, 256)])
 def test_generated_traces(kp, oracle_mod, W, R, cap, total):
     spec = inputs.TraceSpec(n_wg=37, waves=W, n_regions=R, cap_wave=cap, total_per_wave=total, total_var=total // 3,
                             seed=W * 1000 + R, p_orphan=0.02, p_swap=1e-3)
