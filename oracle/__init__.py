@@ -11,6 +11,8 @@ library or its Python binding, and shares no code with them.
   ref_pairs.c  : one timeline row per paired region instance, with its iteration
                  index (Sec. 3.2 decoded activity records, Sec. 3.3 iteration-based
                  timing)
+  ref_waits.c  : waits behind asynchronous operations from the START / END / START
+                 placement (Sec. 4.3, asynchronous instructions)
   ref_dense.py : the dense kernels that get instrumented -- GEMM and causal
                  attention forward by their textbook definitions, fp64
 
@@ -39,7 +41,7 @@ HEADER_FIELDS = (
 PER_DTYPE = np.dtype([("sum", "<u8"), ("n", "<u4"), ("max", "<u4")])
 
 
-_SOURCES = ("ref_decode.c", "ref_pairs.c")
+_SOURCES = ("ref_decode.c", "ref_pairs.c", "ref_waits.c")
 
 
 def build(force: bool = False) -> str:
@@ -63,6 +65,10 @@ def _load():
         lib.kpo_pairs_bytes.argtypes = [ctypes.c_uint32] * 3
         lib.kpo_pairs.restype = ctypes.c_int
         lib.kpo_pairs.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t]
+        lib.kpo_waits_bytes.restype = ctypes.c_size_t
+        lib.kpo_waits_bytes.argtypes = [ctypes.c_uint32] * 3
+        lib.kpo_waits.restype = ctypes.c_int
+        lib.kpo_waits.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t]
         _lib = lib
     return _lib
 
@@ -147,6 +153,49 @@ def pairs(raw: np.ndarray):
     """Reference timeline rows: list over (wg, wave) of structured arrays, plus the counts."""
     n_wg, waves, _R, cap = (int(x) for x in raw[2:6])
     return view_pairs(pairs_raw(raw), n_wg, waves, cap)
+
+
+WAITS_HEADER_FIELDS = ("n_waits", "n_uncovered", "n_async", "_3", "_4", "_5", "_6", "_7",
+                       "n_wg", "waves", "n_regions", "cap_wave", "rec_cost", "_13", "_14", "_15")
+
+
+def waits_bytes(n_wg: int, waves: int, n_regions: int) -> int:
+    return _load().kpo_waits_bytes(n_wg, waves, n_regions)
+
+
+def waits_raw(raw: np.ndarray) -> np.ndarray:
+    """Run the reference wait replay on a raw trace (uint32 words); returns the output block bytes."""
+    assert raw.dtype == np.uint32 and raw.flags["C_CONTIGUOUS"]
+    n_wg, waves, R, cap = (int(x) for x in raw[2:6])
+    n_slots = n_wg * waves * cap
+    if raw.size * 4 < 64 + 128 * n_wg + 8 * n_slots:
+        raise ValueError("raw buffer shorter than its header claims")
+    out = np.full(waits_bytes(n_wg, waves, R), 0xEE, dtype=np.uint8)
+    rc = _load().kpo_waits(raw.ctypes.data, n_slots, out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError(f"kpo_waits rejected the trace (rc={rc})")
+    return out
+
+
+def view_waits(buf: np.ndarray) -> dict:
+    """Split a waits block (uint8 array) into named numpy views."""
+    b = np.ascontiguousarray(buf).view(np.uint8)
+    hdr = b[:128].view("<u8")
+    n_wg, W, R = int(hdr[8]), int(hdr[9]), int(hdr[10])
+    out = {name: int(hdr[i]) for i, name in enumerate(WAITS_HEADER_FIELDS) if not name.startswith("_")}
+    o = 128
+    out["hist"] = b[o : o + 8 * 64 * R].view("<u8").reshape(R, 64)
+    o += 8 * 64 * R
+    for name in ("cnt", "sum", "min", "max", "uncovered", "async_cnt", "async_sum"):
+        out[name] = b[o : o + 8 * R].view("<u8")
+        o += 8 * R
+    out["per"] = b[o : o + 16 * n_wg * W * R].view(PER_DTYPE).reshape(n_wg, W, R)
+    assert o + 16 * n_wg * W * R == b.size
+    return out
+
+
+def waits(raw: np.ndarray) -> dict:
+    return view_waits(waits_raw(raw))
 
 
 from .ref_dense import ref_gemm, ref_attn, bf16_round  # noqa: E402,F401

@@ -159,3 +159,92 @@ def brute_pairs(raw: np.ndarray):
                         it += 1
             out[(wg, w)] = [row[1:] for row in sorted(rows)]
     return out
+
+
+def brute_waits(raw: np.ndarray) -> dict:
+    """Independent wait replay: for every (wg, wave) the list of (region, gap, whole) in rank order,
+    `whole` = CLK2 - CLK0 (mod 2^32) when the END is paired, else None.
+
+    Written differently from oracle/ref_waits.c on purpose: the records of a wave are put into one
+    list in rank order, every adjacent (END, START) couple is a wait, and whether the END is paired
+    is found by searching that list backwards for the nearest record of the END's region.
+    """
+    raw = [int(x) for x in raw]
+    assert raw[0] == 0x4652504B and raw[1] == 1
+    n_wg, W, R, cap, _rec_cost, flags = raw[2:8]
+    flush = flags & 1
+    rec0 = (64 + 128 * n_wg) // 4
+    out = {}
+    for wg in range(n_wg):
+        h = (64 + 128 * wg) // 4
+        for w in range(W):
+            T = raw[h + 8 + w]
+            V = min(T, cap)
+            first = 0 if flush else T - V
+            by_rank = {}
+            for s in range(V):
+                tag = raw[rec0 + 2 * ((wg * W + w) * cap + s)]
+                ts = raw[rec0 + 2 * ((wg * W + w) * cap + s) + 1]
+                seq, wave, region, phase = tag & 0xFFFFF, (tag >> 20) & 15, (tag >> 24) & 127, tag >> 31
+                k = (seq - first) % (1 << 20)
+                if k >= V or wave != w or region >= R:
+                    continue
+                by_rank[k] = (region, phase, ts)
+            order = [by_rank[k] for k in sorted(by_rank)]
+            waits = []
+            for i in range(len(order) - 1):
+                (ra, pa, ta), (_rb, pb, tb) = order[i], order[i + 1]
+                if not (pa == 1 and pb == 0):
+                    continue
+                whole = None
+                for rq, pq, tq in reversed(order[:i]):
+                    if rq == ra:
+                        if pq == 0:
+                            whole = (tb - tq) % (1 << 32)
+                        break
+                waits.append((ra, (tb - ta) % (1 << 32), whole))
+            out[(wg, w)] = waits
+    return out
+
+
+def waits_summary(raw: np.ndarray, per_wave: dict) -> dict:
+    """Fold brute_waits' lists into the totals of the waits block (plain Python integers)."""
+    n_wg, W, R, _cap, rec_cost = (int(x) for x in raw[2:7])
+    z = lambda: [0] * R
+    s = {"n_waits": 0, "n_uncovered": 0, "n_async": 0, "cnt": z(), "sum": z(), "min": [2 ** 64 - 1] * R, "max": z(),
+         "uncovered": z(), "async_cnt": z(), "async_sum": z(), "hist": [[0] * 64 for _ in range(R)],
+         "per": {}}
+    for (wg, w), lst in per_wave.items():
+        for a, gap, whole in lst:
+            s["n_waits"] += 1
+            s["cnt"][a] += 1
+            s["sum"][a] += gap
+            s["min"][a] = min(s["min"][a], gap)
+            s["max"][a] = max(s["max"][a], gap)
+            s["hist"][a][max(gap, 1).bit_length() - 1] += 1
+            if gap <= rec_cost:
+                s["n_uncovered"] += 1
+                s["uncovered"][a] += 1
+            if whole is not None:
+                s["n_async"] += 1
+                s["async_cnt"][a] += 1
+                s["async_sum"][a] += max(whole - rec_cost, 0)
+            sm, n, mx = s["per"].get((wg, w, a), (0, 0, 0))
+            s["per"][(wg, w, a)] = (sm + gap, n + 1, max(mx, gap))
+    return s
+
+
+def assert_waits_same(ref: dict, got: dict):
+    """ref: waits_summary(); got: oracle.view_waits() / the GPU block viewed the same way."""
+    for k in ("n_waits", "n_uncovered", "n_async"):
+        assert ref[k] == got[k], (k, ref[k], got[k])
+    for k in ("cnt", "sum", "min", "max", "uncovered", "async_cnt", "async_sum"):
+        assert [int(x) for x in got[k]] == ref[k], (k, ref[k], got[k])
+    assert [[int(x) for x in row] for row in got["hist"]] == ref["hist"]
+    per = got["per"]
+    for wg in range(per.shape[0]):
+        for w in range(per.shape[1]):
+            for a in range(per.shape[2]):
+                want = ref["per"].get((wg, w, a), (0, 0, 0))
+                have = (int(per[wg, w, a]["sum"]), int(per[wg, w, a]["n"]), int(per[wg, w, a]["max"]))
+                assert want == have, ((wg, w, a), want, have)
