@@ -10,6 +10,7 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
   4. kp_trace_reduce of the attention trace
   5. kp_trace_reduce of the standalone decode workload: 2^28 synthetic records
   6. kp_trace_pairs of the same records: one timeline row per paired region instance
+  7. kp_trace_waits of the same records: the waits behind asynchronous operations
 All inputs are resident in HBM before the timed region starts.  Every kernel is bracketed by
 HIP events on the launch stream inside the timed region; the per-kernel figures below are
 averages over the timed steps.
@@ -96,6 +97,7 @@ def main() -> int:
     d_hdr = kp.make_hdr(spec.n_wg, spec.waves, spec.n_regions, spec.cap_wave)
     d_pairs = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8,
                           device=dev)
+    d_waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     # The dense kernels run as vanilla/instrumented pairs, twice, after one warm launch, so that both
@@ -103,7 +105,7 @@ def main() -> int:
     # leaves L2 and the memory-side cache cold); every launch is inside the timed step.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_vanilla2", "gemm_instr2", "gemm_reduce",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_vanilla2", "attn_instr2", "attn_reduce", "decode",
-             "timeline"]
+             "timeline", "waits"]
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
@@ -117,6 +119,7 @@ def main() -> int:
             lambda: kp.kp_trace_reduce_hdr(a_trace, a_wg * a_cap, a_hdr, a_stats),
             lambda: kp.kp_trace_reduce_hdr(d_raw, d_n, d_hdr, d_stats),
             lambda: kp.kp_trace_pairs_hdr(d_raw, d_n, d_hdr, d_pairs),
+            lambda: kp.kp_trace_waits_hdr(d_raw, d_n, d_hdr, d_waits),
         )
         for i, call in enumerate(calls):
             if events is not None:
@@ -163,6 +166,11 @@ def main() -> int:
     assert pair_count == st["n_pairs"], "timeline rows and statistics disagree on the number of pairs"
     tl_bytes = 8.0 * d_n + 16.0 * pair_count + 4.0 * n_seg + 128.0 * spec.n_wg
     tl_gbs = tl_bytes / (ms["timeline"] * 1e-3) / 1e9
+    # waits of the same trace: 8 B read per record, 16 B written per (wg, wave, region)
+    wv = kp.parse_waits(d_waits)
+    assert wv["n_wg"] == spec.n_wg and 0 < wv["n_waits"] <= st["n_pairs"] + st["n_orphan_end"], "waits block is off"
+    wt_bytes = 8.0 * d_n + 16.0 * n_seg * spec.n_regions + 128.0 * spec.n_wg
+    wt_gbs = wt_bytes / (ms["waits"] * 1e-3) / 1e9
 
     # Overhead model of the paper, eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the
     # per-record cost taken from the calibration kernel (an empty START/END region, i.e. two records)
@@ -221,6 +229,7 @@ def main() -> int:
         "decode_records_per_s": round(dec_rps, 1),
         "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4),
         "timeline_records_per_s": round(d_n / (ms["timeline"] * 1e-3), 1),
+        "waits_records_per_s": round(d_n / (ms["waits"] * 1e-3), 1),
         "kernel_ms": {n: round(x, 4) for n, x in ms.items()},
         "overhead_model_eq1": eq1,
         "paper_context": {"overhead_pct": 8.2, "hardware": "H100 / MI300X (not split), Triton GEMM/FA3"},
@@ -261,6 +270,16 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(tl_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(tl_bytes),
+            "traffic": None,
+        },
+        "roofline_waits": {
+            "kernel": "kp_waits_main (asynchronous waits of the decode workload)",
+            "bound": "hbm",
+            "achieved": round(wt_gbs, 2),
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": round(wt_gbs / PEAK_HBM_GBS, 4),
+            "algorithmic_bytes": round(wt_bytes),
             "traffic": None,
         },
     }

@@ -178,6 +178,35 @@ kp_status kp_trace_pairs(const void* raw, size_t n, void* out_pairs, void* strea
 kp_status kp_trace_pairs_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
                              void* out_pairs, void* stream);
 
+/* ---- waits behind asynchronous operations ---------------------------------------------------
+ *
+ * Sec. 4.3 (trace replay, asynchronous instructions): the records around an asynchronous operation
+ * are placed as START before its launch (clock CLK0), END right before the barrier that waits for
+ * it (CLK1) and START right after that barrier (CLK2); T_wait = CLK2 - CLK1 needs no correction
+ * because the records' own cost cancels, and it holds only while what is left of the operation at
+ * the barrier outlasts one record (T_MMA - T_exe > T_a + T_b).
+ * In the rank order of one (workgroup, wave) -- the order kp_trace_reduce uses -- every END of a
+ * region a whose successor is a START (of any region) is one wait of region a:
+ *   gap    = (u32)(CLK2 - CLK1)
+ *   uncovered if gap <= rec_cost (the trace header's cost of one record)
+ *   whole  = (u32)(CLK2 - CLK0) minus rec_cost, not below 0, when the END is paired with a START at
+ *            CLK0 (the nearest earlier record of region a in the wave)
+ * Output block (device, kp_waits_bytes(...) bytes, 16-byte aligned, fully written), u64 words:
+ *   16 header words {n_waits, n_uncovered, n_async, 0 x5, n_wg, waves_per_wg, n_regions, cap_wave,
+ *                    rec_cost, 0 x3}
+ *   hist[n_regions][64]   gaps by floor(log2 gap), gaps 0 and 1 in bin 0
+ *   cnt, sum, min, max    of the gaps per region (min is all ones when cnt is 0)
+ *   uncovered, async_cnt, async_sum   per region (async_sum adds up `whole`)
+ *   per[n_wg][waves_per_wg][n_regions] of 16 bytes {u64 sum, u32 n, u32 max} of the gaps
+ * Arguments, synchronisation, limits (n_regions <= 128) and errors as for kp_trace_pairs /
+ * kp_trace_pairs_hdr; KP_ERR_UNSUPPORTED_SHAPE also when waves, cap_wave and n_regions together
+ * exceed the kernel's LDS budget.  One wave may hold at most 2^18 waits.
+ */
+size_t kp_waits_bytes(int n_wg, int waves_per_wg, int n_regions);
+kp_status kp_trace_waits(const void* raw, size_t n, void* out_waits, void* stream);
+kp_status kp_trace_waits_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                             void* out_waits, void* stream);
+
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
  * region_mask: bit r (r < 31) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)

@@ -75,6 +75,12 @@ def lib() -> ctypes.CDLL:
         L.kp_trace_pairs.argtypes = [vp, sz, vp, vp]
         L.kp_trace_pairs_hdr.restype = ci
         L.kp_trace_pairs_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
+        L.kp_waits_bytes.restype = sz
+        L.kp_waits_bytes.argtypes = [ci, ci, ci]
+        L.kp_trace_waits.restype = ci
+        L.kp_trace_waits.argtypes = [vp, sz, vp, vp]
+        L.kp_trace_waits_hdr.restype = ci
+        L.kp_trace_waits_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
         _optional(L)
         _lib = L
     return _lib
@@ -177,6 +183,40 @@ def parse_pairs(buf, n_wg: int, waves_per_wg: int, cap_per_wg: int):
     count = b[: 4 * n_seg].view("<u4").reshape(n_wg, waves_per_wg)
     rows = b[head : head + 16 * n_seg * half].view(np.dtype(PAIR_ROW_DTYPE)).reshape(n_wg, waves_per_wg, half)
     return count, rows
+
+
+def kp_waits_bytes(n_wg: int, waves_per_wg: int, n_regions: int) -> int:
+    return lib().kp_waits_bytes(n_wg, waves_per_wg, n_regions)
+
+
+def kp_trace_waits(raw, n: int, out_waits, stream=None) -> None:
+    _check(lib().kp_trace_waits(_ptr(raw), n, _ptr(out_waits), _stream(stream)))
+
+
+def kp_trace_waits_hdr(raw, n: int, hdr_host: kp_trace_hdr, out_waits, stream=None) -> None:
+    _check(lib().kp_trace_waits_hdr(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_waits), _stream(stream)))
+
+
+WAITS_HEADER_FIELDS = ("n_waits", "n_uncovered", "n_async", None, None, None, None, None,
+                       "n_wg", "waves_per_wg", "n_regions", "cap_wave", "rec_cost", None, None, None)
+
+
+def parse_waits(buf) -> dict:
+    """Split a waits block (bytes on the host: numpy uint8 array or CPU tensor) into fields."""
+    if hasattr(buf, "numpy"):
+        buf = buf.cpu().numpy()
+    b = np.ascontiguousarray(buf).view(np.uint8)
+    hdr = b[:128].view("<u8")
+    out = {k: int(hdr[i]) for i, k in enumerate(WAITS_HEADER_FIELDS) if k}
+    n_wg, W, R = out["n_wg"], out["waves_per_wg"], out["n_regions"]
+    pos = 128
+    out["hist"] = b[pos : pos + 8 * 64 * R].view("<u8").reshape(R, 64)
+    pos += 8 * 64 * R
+    for name in ("cnt", "sum", "min", "max", "uncovered", "async_cnt", "async_sum"):
+        out[name] = b[pos : pos + 8 * R].view("<u8")
+        pos += 8 * R
+    out["per"] = b[pos : pos + 16 * n_wg * W * R].view(WAVE_REGION_DTYPE).reshape(n_wg, W, R)
+    return out
 
 
 def kp_gemm_launch_shape(M: int, N: int, K: int) -> tuple[int, int, int]:

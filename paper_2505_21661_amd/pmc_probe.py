@@ -4,7 +4,7 @@ Launches, in this order and twice each (the second launch is the one to read):
   a plain device-to-device copy of 1 GiB (reads 1 GiB, writes 1 GiB: the scale reference),
   the uninstrumented and the instrumented 4096^3 GEMM,
   the uninstrumented attention forward 4x32x4096x128,
-  kp_trace_reduce_hdr and kp_trace_pairs_hdr on the standalone decode workload (2^LOG2 records,
+  kp_trace_reduce_hdr, kp_trace_pairs_hdr and kp_trace_waits_hdr on the standalone decode workload (2^LOG2 records,
   default 28).
 
 Run it under the profiler once per counter, e.g.
@@ -71,6 +71,9 @@ def main() -> None:
     rows = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8, device=dev)
     for _ in range(2):
         kp.kp_trace_pairs_hdr(d_raw, spec.n_slots, hdr, rows)
+    waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        kp.kp_trace_waits_hdr(d_raw, spec.n_slots, hdr, waits)
     torch.cuda.synchronize()
     print("pmc_probe done")
 

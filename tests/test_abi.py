@@ -17,7 +17,7 @@ def declared_symbols():
 def test_header_declares_the_named_entry_points():
     names = declared_symbols()
     for must in ("kp_gemm_instrumented", "kp_attn_instrumented", "kp_trace_reduce", "kp_calibrate",
-                 "kp_trace_bytes", "kp_stats_bytes", "kp_last_error"):
+                 "kp_trace_bytes", "kp_stats_bytes", "kp_last_error", "kp_trace_pairs", "kp_trace_waits"):
         assert must in names
 
 
@@ -46,6 +46,9 @@ def test_size_helpers_and_struct_sizes():
     # count array padded to 16 bytes + 16-byte rows, cap_wave / 2 per (workgroup, wave)
     assert kp.kp_pairs_bytes(3, 2, 64) == 32 + 16 * 3 * 2 * 16
     assert kp.kp_pairs_bytes(1, 3, 64) == 0
+    # 16 header words, 64-bin histogram and 7 totals per region, 16 bytes per (workgroup, wave, region)
+    assert kp.kp_waits_bytes(n_wg, W, R) == 128 + 8 * (64 * R + 7 * R) + 16 * n_wg * W * R
+    assert kp.kp_waits_bytes(1, 17, 3) == 0 and kp.kp_waits_bytes(1, 4, 129) == 0
     assert kp.kp_last_error() == "" or isinstance(kp.kp_last_error(), str)
 
 

@@ -128,8 +128,9 @@ def test_repeated_calls_are_deterministic(kp, oracle_mod):
 
 def test_decode_workload_full_size(kp, oracle_mod):
     """The benchmark's decode workload at its full size (2^28 records, 16384 workgroups x 8 waves x
-    2048 records, 16 regions) in the launch configuration bench.py times (kp_trace_reduce_hdr and
-    kp_trace_pairs_hdr): the whole statistics block and every timeline row, bit for bit."""
+    2048 records, 16 regions) in the launch configuration bench.py times (kp_trace_reduce_hdr,
+    kp_trace_pairs_hdr and kp_trace_waits_hdr): the whole statistics block, every timeline row and
+    the whole waits block, bit for bit."""
     import os
 
     spec = inputs.spec_decode_standalone(28)
@@ -142,6 +143,8 @@ def test_decode_workload_full_size(kp, oracle_mod):
     rows = torch.full((kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave),), 0xA5, dtype=torch.uint8,
                       device="cuda")
     kp.kp_trace_pairs_hdr(dev_raw, n, hdr, rows)
+    waits = torch.full((kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions),), 0x5A, dtype=torch.uint8, device="cuda")
+    kp.kp_trace_waits_hdr(dev_raw, n, hdr, waits)
     torch.cuda.synchronize()
     from tests.gpu_util import assert_stats_equal
 
@@ -153,3 +156,5 @@ def test_decode_workload_full_size(kp, oracle_mod):
     want_rows = oracle_mod.pairs_raw(raw, fill=0xA5)
     got_rows = rows.cpu().numpy()
     assert np.array_equal(want_rows, got_rows)
+    del want_rows, got_rows
+    assert np.array_equal(oracle_mod.waits_raw(raw), waits.cpu().numpy())
