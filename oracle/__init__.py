@@ -13,6 +13,8 @@ library or its Python binding, and shares no code with them.
                  timing)
   ref_waits.c  : waits behind asynchronous operations from the START / END / START
                  placement (Sec. 4.3, asynchronous instructions)
+  ref_stages.c : stage latencies per (workgroup, region, iteration) folded from the timeline
+                 rows (Sec. 3.3 critical-path analysis, Sec. 5.2 / Table 4 overlap models)
   ref_dense.py : the dense kernels that get instrumented -- GEMM and causal
                  attention forward by their textbook definitions, fp64
 
@@ -41,7 +43,7 @@ HEADER_FIELDS = (
 PER_DTYPE = np.dtype([("sum", "<u8"), ("n", "<u4"), ("max", "<u4")])
 
 
-_SOURCES = ("ref_decode.c", "ref_pairs.c", "ref_waits.c")
+_SOURCES = ("ref_decode.c", "ref_pairs.c", "ref_waits.c", "ref_stages.c")
 
 
 def build(force: bool = False) -> str:
@@ -69,6 +71,10 @@ def _load():
         lib.kpo_waits_bytes.argtypes = [ctypes.c_uint32] * 3
         lib.kpo_waits.restype = ctypes.c_int
         lib.kpo_waits.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t]
+        lib.kpo_stages_bytes.restype = ctypes.c_size_t
+        lib.kpo_stages_bytes.argtypes = [ctypes.c_uint32] * 3
+        lib.kpo_stages.restype = ctypes.c_int
+        lib.kpo_stages.argtypes = [ctypes.c_void_p] + [ctypes.c_uint32] * 5 + [ctypes.c_void_p, ctypes.c_size_t]
         _lib = lib
     return _lib
 
@@ -196,6 +202,35 @@ def view_waits(buf: np.ndarray) -> dict:
 
 def waits(raw: np.ndarray) -> dict:
     return view_waits(waits_raw(raw))
+
+
+STAGE_DTYPE = np.dtype([("max_dur", "<u4"), ("min_start", "<u4"), ("max_end", "<u4"), ("n_waves", "<u4")])
+
+
+def stages_raw(pairs_block: np.ndarray, n_wg: int, waves: int, cap_wave: int, n_regions: int, max_iter: int) -> np.ndarray:
+    """Fold a timeline block (bytes, as pairs_raw returns it) into the stage table; returns the block bytes."""
+    blk = np.ascontiguousarray(pairs_block).view(np.uint8)
+    assert blk.size >= pairs_bytes(n_wg, waves, cap_wave)
+    out = np.full(_load().kpo_stages_bytes(n_wg, n_regions, max_iter), 0xEE, dtype=np.uint8)
+    rc = _load().kpo_stages(blk.ctypes.data, n_wg, waves, cap_wave, n_regions, max_iter, out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError(f"kpo_stages rejected its arguments (rc={rc})")
+    return out
+
+
+def view_stages(buf: np.ndarray, n_wg: int, n_regions: int, max_iter: int):
+    """Split a stage block into (header dict, table[n_wg, n_regions, max_iter])."""
+    b = np.ascontiguousarray(buf).view(np.uint8)
+    h = b[:32].view("<u8")
+    hdr = {"n_rows": int(h[0]), "n_clipped": int(h[1]), "n_bad_region": int(h[2])}
+    tab = b[32 : 32 + 16 * n_wg * n_regions * max_iter].view(STAGE_DTYPE).reshape(n_wg, n_regions, max_iter)
+    return hdr, tab
+
+
+def stages(raw: np.ndarray, max_iter: int):
+    """Reference stage table of a raw trace: timeline rows first, then the fold."""
+    n_wg, waves, R, cap = (int(x) for x in raw[2:6])
+    return view_stages(stages_raw(pairs_raw(raw), n_wg, waves, cap, R, max_iter), n_wg, R, max_iter)
 
 
 from .ref_dense import ref_gemm, ref_attn, bf16_round  # noqa: E402,F401

@@ -248,3 +248,19 @@ def assert_waits_same(ref: dict, got: dict):
                 want = ref["per"].get((wg, w, a), (0, 0, 0))
                 have = (int(per[wg, w, a]["sum"]), int(per[wg, w, a]["n"]), int(per[wg, w, a]["max"]))
                 assert want == have, ((wg, w, a), want, have)
+
+
+def brute_stages(raw: np.ndarray, max_iter: int):
+    """Independent stage table straight from the raw trace: brute_pairs' rows of every wave are
+    grouped by (wg, region, iter) in a dict.  Returns (n_rows, n_clipped, {key: (max_dur, min_start, max_end, n)})."""
+    rows = brute_pairs(raw)
+    tab, n_rows, n_clipped = {}, 0, 0
+    for (wg, _w), lst in rows.items():
+        for start, dur, it, region in lst:
+            if it >= max_iter:
+                n_clipped += 1
+                continue
+            n_rows += 1
+            d, s, e, n = tab.get((wg, region, it), (0, 2 ** 32 - 1, 0, 0))
+            tab[(wg, region, it)] = (max(d, dur), min(s, start), max(e, (start + dur) % (1 << 32)), n + 1)
+    return n_rows, n_clipped, tab
