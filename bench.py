@@ -11,6 +11,7 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
   5. kp_trace_reduce of the standalone decode workload: 2^28 synthetic records
   6. kp_trace_pairs of the same records: one timeline row per paired region instance
   7. kp_trace_waits of the same records: the waits behind asynchronous operations
+  8. kp_pairs_stages of the timeline rows: stage latency per (workgroup, region, iteration)
 All inputs are resident in HBM before the timed region starts.  Every kernel is bracketed by
 HIP events on the launch stream inside the timed region; the per-kernel figures below are
 averages over the timed steps.
@@ -98,6 +99,8 @@ def main() -> int:
     d_pairs = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8,
                           device=dev)
     d_waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
+    d_iters = 64  # iterations kept per region: the workload runs about 64 pairs per wave and region
+    d_stages = torch.empty(kp.kp_stages_bytes(spec.n_wg, spec.n_regions, d_iters), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     # The dense kernels run as vanilla/instrumented pairs, twice, after one warm launch, so that both
@@ -105,7 +108,7 @@ def main() -> int:
     # leaves L2 and the memory-side cache cold); every launch is inside the timed step.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_vanilla2", "gemm_instr2", "gemm_reduce",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_vanilla2", "attn_instr2", "attn_reduce", "decode",
-             "timeline", "waits"]
+             "timeline", "waits", "stages"]
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
@@ -120,6 +123,8 @@ def main() -> int:
             lambda: kp.kp_trace_reduce_hdr(d_raw, d_n, d_hdr, d_stats),
             lambda: kp.kp_trace_pairs_hdr(d_raw, d_n, d_hdr, d_pairs),
             lambda: kp.kp_trace_waits_hdr(d_raw, d_n, d_hdr, d_waits),
+            lambda: kp.kp_pairs_stages(d_pairs, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions,
+                                       d_iters, d_stages),
         )
         for i, call in enumerate(calls):
             if events is not None:
@@ -171,6 +176,11 @@ def main() -> int:
     assert wv["n_wg"] == spec.n_wg and 0 < wv["n_waits"] <= st["n_pairs"] + st["n_orphan_end"], "waits block is off"
     wt_bytes = 8.0 * d_n + 16.0 * n_seg * spec.n_regions + 128.0 * spec.n_wg
     wt_gbs = wt_bytes / (ms["waits"] * 1e-3) / 1e9
+    # stage table: 16 B read per row, 4 B per (wg, wave), 16 B written per (wg, region, iteration)
+    sg_hdr = d_stages[:32].view(torch.int64).tolist()
+    assert sg_hdr[0] + sg_hdr[1] == pair_count and sg_hdr[2] == 0, "stage table lost rows"
+    sg_bytes = 16.0 * pair_count + 4.0 * n_seg + 16.0 * spec.n_wg * spec.n_regions * d_iters
+    sg_gbs = sg_bytes / (ms["stages"] * 1e-3) / 1e9
 
     # Overhead model of the paper, eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the
     # per-record cost taken from the calibration kernel (an empty START/END region, i.e. two records)
@@ -230,6 +240,7 @@ def main() -> int:
         "decode_hbm_frac": round(dec_gbs / PEAK_HBM_GBS, 4),
         "timeline_records_per_s": round(d_n / (ms["timeline"] * 1e-3), 1),
         "waits_records_per_s": round(d_n / (ms["waits"] * 1e-3), 1),
+        "stages_rows_per_s": round(pair_count / (ms["stages"] * 1e-3), 1),
         "kernel_ms": {n: round(x, 4) for n, x in ms.items()},
         "overhead_model_eq1": eq1,
         "paper_context": {"overhead_pct": 8.2, "hardware": "H100 / MI300X (not split), Triton GEMM/FA3"},
@@ -280,6 +291,16 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(wt_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(wt_bytes),
+            "traffic": None,
+        },
+        "roofline_stages": {
+            "kernel": "kp_stages_main (stage table from the timeline rows of the decode workload)",
+            "bound": "hbm",
+            "achieved": round(sg_gbs, 2),
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": round(sg_gbs / PEAK_HBM_GBS, 4),
+            "algorithmic_bytes": round(sg_bytes),
             "traffic": None,
         },
     }

@@ -207,6 +207,40 @@ kp_status kp_trace_waits(const void* raw, size_t n, void* out_waits, void* strea
 kp_status kp_trace_waits_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
                              void* out_waits, void* stream);
 
+/* ---- stage latencies per loop iteration ----------------------------------------------------
+ *
+ * The paper's critical-path analysis and its overlap models (Sec. 3.3 "Critical-path Analysis";
+ * Sec. 5.2 "Performance Modeling for GPU Overlapping", Table 4) work on the latency of every stage
+ * (region) in every loop iteration.  A stage that the waves of a workgroup execute together lasts
+ * as long as its slowest wave: kp_pairs_stages folds the timeline rows that kp_trace_pairs wrote
+ * for the waves of a workgroup into one entry per (workgroup, region, iteration),
+ *   max_dur    max over the rows of dur
+ *   min_start  min over the rows of start
+ *   max_end    max over the rows of (u32)(start + dur)
+ *   n_waves    number of rows folded in (one per wave that ran this iteration of the region)
+ * An entry without rows reads {0, 0xFFFFFFFF, 0, 0}.
+ *   pairs        device, the block kp_trace_pairs / kp_trace_pairs_hdr wrote for (n_wg, waves_per_wg,
+ *                cap_per_wg); every count must be <= cap_wave / 2; read only
+ *   n_regions    rows whose region is not below it are left out and counted (n_bad_region)
+ *   max_iter     iterations kept per region; rows with iter >= max_iter are left out and counted
+ *   out_stages   device, kp_stages_bytes(n_wg, n_regions, max_iter) bytes, 16-byte aligned, fully
+ *                written: 4 u64 {n_rows folded, n_clipped, n_bad_region, 0}, then
+ *                kp_stage_row table[n_wg][n_regions][max_iter]
+ * Asynchronous on `stream`.  KP_ERR_INVALID_ARG for NULL or misaligned pointers and bad sizes;
+ * KP_ERR_UNSUPPORTED_SHAPE when n_regions * (max_iter + 1) * 16 exceeds 64 KiB (the table of one
+ * workgroup lives in LDS).
+ */
+typedef struct {
+  uint32_t max_dur;
+  uint32_t min_start;
+  uint32_t max_end;
+  uint32_t n_waves;
+} kp_stage_row;
+
+size_t kp_stages_bytes(int n_wg, int n_regions, int max_iter);
+kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap_per_wg, int n_regions,
+                          int max_iter, void* out_stages, void* stream);
+
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
  * region_mask: bit r (r < 31) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)

@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
         L.kp_trace_waits.argtypes = [vp, sz, vp, vp]
         L.kp_trace_waits_hdr.restype = ci
         L.kp_trace_waits_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
+        L.kp_stages_bytes.restype = sz
+        L.kp_stages_bytes.argtypes = [ci, ci, ci]
+        L.kp_pairs_stages.restype = ci
+        L.kp_pairs_stages.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         _optional(L)
         _lib = L
     return _lib
@@ -177,7 +181,7 @@ def parse_pairs(buf, n_wg: int, waves_per_wg: int, cap_per_wg: int):
     rows[n_wg, waves, cap_wave // 2]); only the first count[wg, wave] rows of a wave are meaningful."""
     import numpy as np
 
-    b = np.ascontiguousarray(buf.numpy() if hasattr(buf, "numpy") else buf).view(np.uint8)
+    b = np.ascontiguousarray(buf.cpu().numpy() if hasattr(buf, "numpy") else buf).view(np.uint8)
     n_seg, half = n_wg * waves_per_wg, cap_per_wg // waves_per_wg // 2
     head = ((n_seg + 3) // 4) * 16
     count = b[: 4 * n_seg].view("<u4").reshape(n_wg, waves_per_wg)
@@ -217,6 +221,28 @@ def parse_waits(buf) -> dict:
         pos += 8 * R
     out["per"] = b[pos : pos + 16 * n_wg * W * R].view(WAVE_REGION_DTYPE).reshape(n_wg, W, R)
     return out
+
+
+def kp_stages_bytes(n_wg: int, n_regions: int, max_iter: int) -> int:
+    return lib().kp_stages_bytes(n_wg, n_regions, max_iter)
+
+
+def kp_pairs_stages(pairs, n_wg: int, waves_per_wg: int, cap_per_wg: int, n_regions: int, max_iter: int,
+                    out_stages, stream=None) -> None:
+    _check(lib().kp_pairs_stages(_ptr(pairs), n_wg, waves_per_wg, cap_per_wg, n_regions, max_iter,
+                                 _ptr(out_stages), _stream(stream)))
+
+
+STAGE_ROW_DTYPE = [("max_dur", "<u4"), ("min_start", "<u4"), ("max_end", "<u4"), ("n_waves", "<u4")]
+
+
+def parse_stages(buf, n_wg: int, n_regions: int, max_iter: int):
+    """Split a stage block (host bytes) into (header dict, table[n_wg, n_regions, max_iter])."""
+    b = np.ascontiguousarray(buf.cpu().numpy() if hasattr(buf, "numpy") else buf).view(np.uint8)
+    h = b[:32].view("<u8")
+    hdr = {"n_rows": int(h[0]), "n_clipped": int(h[1]), "n_bad_region": int(h[2])}
+    tab = b[32 : 32 + 16 * n_wg * n_regions * max_iter].view(np.dtype(STAGE_ROW_DTYPE)).reshape(n_wg, n_regions, max_iter)
+    return hdr, tab
 
 
 def kp_gemm_launch_shape(M: int, N: int, K: int) -> tuple[int, int, int]:

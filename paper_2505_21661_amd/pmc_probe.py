@@ -4,8 +4,8 @@ Launches, in this order and twice each (the second launch is the one to read):
   a plain device-to-device copy of 1 GiB (reads 1 GiB, writes 1 GiB: the scale reference),
   the uninstrumented and the instrumented 4096^3 GEMM,
   the uninstrumented attention forward 4x32x4096x128,
-  kp_trace_reduce_hdr, kp_trace_pairs_hdr and kp_trace_waits_hdr on the standalone decode workload (2^LOG2 records,
-  default 28).
+  kp_trace_reduce_hdr, kp_trace_pairs_hdr, kp_trace_waits_hdr and kp_pairs_stages on the standalone
+  decode workload (2^LOG2 records, default 28).
 
 Run it under the profiler once per counter, e.g.
   rocprofv3 --pmc FETCH_SIZE --output-format csv -d out_fetch -- python3 -m paper_2505_21661_amd.pmc_probe
@@ -74,6 +74,9 @@ def main() -> None:
     waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
     for _ in range(2):
         kp.kp_trace_waits_hdr(d_raw, spec.n_slots, hdr, waits)
+    stages = torch.empty(kp.kp_stages_bytes(spec.n_wg, spec.n_regions, 64), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        kp.kp_pairs_stages(rows, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions, 64, stages)
     torch.cuda.synchronize()
     print("pmc_probe done")
 

@@ -17,7 +17,7 @@ def declared_symbols():
 def test_header_declares_the_named_entry_points():
     names = declared_symbols()
     for must in ("kp_gemm_instrumented", "kp_attn_instrumented", "kp_trace_reduce", "kp_calibrate",
-                 "kp_trace_bytes", "kp_stats_bytes", "kp_last_error", "kp_trace_pairs", "kp_trace_waits"):
+                 "kp_trace_bytes", "kp_stats_bytes", "kp_last_error", "kp_trace_pairs", "kp_trace_waits", "kp_pairs_stages"):
         assert must in names
 
 
@@ -49,6 +49,9 @@ def test_size_helpers_and_struct_sizes():
     # 16 header words, 64-bin histogram and 7 totals per region, 16 bytes per (workgroup, wave, region)
     assert kp.kp_waits_bytes(n_wg, W, R) == 128 + 8 * (64 * R + 7 * R) + 16 * n_wg * W * R
     assert kp.kp_waits_bytes(1, 17, 3) == 0 and kp.kp_waits_bytes(1, 4, 129) == 0
+    # 4 header words, 16 bytes per (workgroup, region, iteration)
+    assert kp.kp_stages_bytes(n_wg, R, 10) == 32 + 16 * n_wg * R * 10 and kp.kp_stages_bytes(1, 3, 0) == 0
+    assert ctypes.sizeof(ctypes.c_uint32) * 4 == 16  # kp_stage_row and kp_pair_row are four u32
     assert kp.kp_last_error() == "" or isinstance(kp.kp_last_error(), str)
 
 

@@ -129,8 +129,8 @@ def test_repeated_calls_are_deterministic(kp, oracle_mod):
 def test_decode_workload_full_size(kp, oracle_mod):
     """The benchmark's decode workload at its full size (2^28 records, 16384 workgroups x 8 waves x
     2048 records, 16 regions) in the launch configuration bench.py times (kp_trace_reduce_hdr,
-    kp_trace_pairs_hdr and kp_trace_waits_hdr): the whole statistics block, every timeline row and
-    the whole waits block, bit for bit."""
+    kp_trace_pairs_hdr, kp_trace_waits_hdr and kp_pairs_stages): the whole statistics block, every
+    timeline row, the whole waits block and the whole stage table, bit for bit."""
     import os
 
     spec = inputs.spec_decode_standalone(28)
@@ -145,6 +145,9 @@ def test_decode_workload_full_size(kp, oracle_mod):
     kp.kp_trace_pairs_hdr(dev_raw, n, hdr, rows)
     waits = torch.full((kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions),), 0x5A, dtype=torch.uint8, device="cuda")
     kp.kp_trace_waits_hdr(dev_raw, n, hdr, waits)
+    max_iter = 64
+    stages = torch.full((kp.kp_stages_bytes(spec.n_wg, spec.n_regions, max_iter),), 0x3C, dtype=torch.uint8, device="cuda")
+    kp.kp_pairs_stages(rows, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions, max_iter, stages)
     torch.cuda.synchronize()
     from tests.gpu_util import assert_stats_equal
 
@@ -156,5 +159,7 @@ def test_decode_workload_full_size(kp, oracle_mod):
     want_rows = oracle_mod.pairs_raw(raw, fill=0xA5)
     got_rows = rows.cpu().numpy()
     assert np.array_equal(want_rows, got_rows)
-    del want_rows, got_rows
+    want_stages = oracle_mod.stages_raw(want_rows, spec.n_wg, spec.waves, spec.cap_wave, spec.n_regions, max_iter)
+    assert np.array_equal(want_stages, stages.cpu().numpy())
+    del want_rows, got_rows, want_stages
     assert np.array_equal(oracle_mod.waits_raw(raw), waits.cpu().numpy())
