@@ -9,11 +9,11 @@
 //   gap <= rec_cost                                 counted as "uncovered",
 //   whole = (u32)(CLK2 - CLK0) - rec_cost, >= 0     when the END is paired with a START at CLK0.
 //
-// One decoder workgroup stages one recorded workgroup in LDS, ordered by rank; hardware wave w
-// walks recorded wave w, 64 ranks per round.  A START takes what it needs to know about the rank
-// below -- metadata, clock, whether that END is paired and with which clock -- from the lane below
-// through DPP wave shifts (the last lane of the previous round stands in for lane 0); only when
-// that rank is empty does it walk back through LDS.  Sums, extrema and the log2 histogram go to LDS
+// One decoder workgroup stages one recorded workgroup in LDS, ordered by rank; the hardware waves
+// share out the recorded waves in runs of consecutive ranks and walk them 64 ranks per round.  A
+// START takes what it needs to know about the rank below -- metadata, clock, whether that END is
+// paired and with which clock -- from the lane below through DPP wave shifts (the last lane of the
+// previous round stands in for lane 0); only when that rank is empty does it walk back through LDS.  Sums, extrema and the log2 histogram go to LDS
 // atomics; totals live in LDS across the recorded workgroups of a persistent decoder workgroup.
 #include "kp_stage.h"
 
@@ -85,7 +85,7 @@ __global__ void kp_waits_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uint
 }
 
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void kp_waits_main(Trace p, uint64_t* out_words) {
+__global__ __launch_bounds__(BLOCK) void kp_waits_main(Trace p, uint64_t* out_words, uint32_t split_log2) {
   extern __shared__ __align__(16) unsigned char smem[];
   const Lds L = lds_layout(p.nrec);
   const WaitsLds X = waits_lds(L.end, p.W, p.R);
@@ -119,20 +119,39 @@ __global__ __launch_bounds__(BLOCK) void kp_waits_main(Trace p, uint64_t* out_wo
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x, ++iter) {
     stage_workgroup<BLOCK>(p, smem, L, wg, iter);
     const uint32_t live_tag = live_tag_of(iter);
-    // ---- walk: hardware wave w handles recorded wave w -------------------------------------------------
-    if (hw < W) {
-      const uint32_t w = hw, wofs = w << cl2, V = sV[w];
-      uint32_t cm[4] = {0u, 0u, 0u, 0u};    // metadata of the last four ranks of the previous round
-      uint32_t ct = 0u, cpaired = 0u, cpt = 0u;  // clock / paired flag / START clock of its last rank
-      uint2 r_next = rec[wofs + (lane < V ? lane : 0u)];  // one round ahead, to hide the LDS latency
-      for (uint32_t kb = 0; kb < V; kb += 64) {
+    // ---- walk: 2^split_log2 hardware waves share one recorded wave, each a run of consecutive ranks ----
+    // Nothing but the look-back crosses from one run into the next, and the staged records of the
+    // earlier run are all in LDS, so the runs are independent.
+    if (hw < (W << split_log2)) {
+      const uint32_t w = hw >> split_log2, part = hw & ((1u << split_log2) - 1u);
+      const uint32_t wofs = w << cl2, V = sV[w];
+      const uint32_t plen = p.cap >> split_log2;
+      const uint32_t k0 = part * plen, k1 = V < k0 + plen ? V : k0 + plen;
+      uint32_t cm[4];                       // metadata of the four ranks below the round
+      uint32_t ct = 0u, cpaired = 0u, cpt = 0u;  // clock / paired flag / START clock of the rank just below
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint2 r = rec[wofs + (k0 > (uint32_t)j ? k0 - 1u - j : 0u)];
+        cm[j] = (k0 > (uint32_t)j && is_live(r.y, live_tag)) ? r.y : 0u;
+        if (j == 0) ct = r.x;
+      }
+      if (cm[0] & kMEnd) {  // a run that starts right above an END: is that END paired? (uniform)
+        for (uint32_t jj = k0 - 1u; jj-- > 0;) {
+          const uint2 rj = rec[wofs + jj];
+          if (!is_live(rj.y, live_tag) || ((rj.y ^ cm[0]) & kMRegion)) continue;
+          if (!(rj.y & kMEnd)) { cpaired = 1u; cpt = rj.x; }
+          break;
+        }
+      }
+      uint2 r_next = rec[wofs + (k0 + lane < k1 ? k0 + lane : 0u)];  // one round ahead, to hide the LDS latency
+      for (uint32_t kb = k0; kb < k1; kb += 64) {
         const uint32_t k = kb + lane;
-        const bool in = k < V;
-        const uint32_t q0 = wofs + (in ? k : V - 1);
+        const bool in = k < k1;
+        const uint32_t q0 = wofs + (in ? k : k1 - 1);
         const uint2 r0 = r_next;
         {
           const uint32_t kn = k + 64;
-          r_next = rec[wofs + (kn < V ? kn : 0u)];
+          r_next = rec[wofs + (kn < k1 ? kn : 0u)];
         }
         const bool valid = in && is_live(r0.y, live_tag);
         const uint32_t m0 = valid ? r0.y : 0u, t0 = r0.x;
@@ -244,13 +263,16 @@ __global__ __launch_bounds__(BLOCK) void kp_waits_main(Trace p, uint64_t* out_wo
 
 template <int BLOCK>
 kp_status launch_waits(const Trace& p, uint64_t* out, uint32_t lds_bytes, hipStream_t s) {
+  // hardware waves per recorded wave: as many as the block has, while a run keeps at least 64 ranks
+  uint32_t split_log2 = 0;
+  while ((p.W << (split_log2 + 1)) <= (uint32_t)BLOCK / 64u && (p.cap >> (split_log2 + 1)) >= 64u) ++split_log2;
   auto kern = kp_waits_main<BLOCK>;
   static thread_local LaunchCache cache;
   uint32_t grid = 0;
   const kp_status st = resident_grid(kern, BLOCK, lds_bytes, &cache, &grid);
   if (st != KP_OK) return st;
   if (grid > p.n_wg) grid = p.n_wg;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds_bytes, s, p, out);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds_bytes, s, p, out, split_log2);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }
