@@ -36,9 +36,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1055563.6 * 2.0 + 45176.8) * 1024,
-    "gemm_vanilla": (98377.0 * 2.0 + 32828.0) * 1024,
-    "attn_vanilla": (1554003.2 * 2.0 + 131970.9) * 1024,
+    "decode_2^28": (1055635.7 * 2.0 + 45176.8) * 1024,
+    "gemm_vanilla": (98377.0 * 2.0 + 32807.1) * 1024,
+    "attn_vanilla": (1554494.0 * 2.0 + 131844.2) * 1024,
+    "timeline_2^28": (1057678.9 * 2.0 + 2085829.0) * 1024,
+    "waits_2^28": (1056098.4 * 2.0 + 33216.0) * 1024,
+    "stages_2^28": (1067938.4 * 2.0 + 281870.5) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
@@ -281,7 +284,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(tl_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(tl_bytes),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["timeline_2^28"]) if args.log2_records == 28 else None,
         },
         "roofline_waits": {
             "kernel": "kp_waits_main (asynchronous waits of the decode workload)",
@@ -291,7 +294,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(wt_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(wt_bytes),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["waits_2^28"]) if args.log2_records == 28 else None,
         },
         "roofline_stages": {
             "kernel": "kp_stages_main (stage table from the timeline rows of the decode workload)",
@@ -301,7 +304,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(sg_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(sg_bytes),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["stages_2^28"]) if args.log2_records == 28 else None,
         },
     }
 
