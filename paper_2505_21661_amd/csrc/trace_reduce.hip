@@ -29,6 +29,7 @@ constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kMRegion = 0x1Fu, kMEnd = 0x20u, kMValid = 0x40u, kMPaired = 0x80u;
 constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
+constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bins of different regions, different banks
 
 // positions inside kp_stats_hdr, in u64 words
 enum { H_SLOTS_VALID = 0, H_PAIRS, H_ORPHAN_START, H_ORPHAN_END, H_INVALID, H_DROPPED, H_DISORDER,
@@ -62,7 +63,7 @@ struct DecodeParams {
 };
 
 struct LdsLayout {  // byte offsets
-  uint32_t rec, grid, perm, cinfo, bucket, hist, oacc, reg_sum, reg_max, reg_min, pw_pack, pw_max,
+  uint32_t rec, grid, perm, cinfo, bucket, hist, oacc, oacc32, reg_sum, reg_max, reg_min, pw_pack, pw_max,
       pw_min, ctr, tmp, misc, v, first, wave_tot, total;
 };
 __host__ __device__ inline uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
@@ -74,8 +75,9 @@ __host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint3
   l.perm = o; o = align16(o + ncell * 2);
   l.cinfo = o; o = align16(o + ncell * 2);
   l.bucket = o; o = align16(o + 64 * 4);
-  l.hist = o; o = align16(o + R * 64 * 4);
+  l.hist = o; o = align16(o + R * kHistStride * 4);
   l.oacc = o; o = align16(o + R * R * 8);
+  l.oacc32 = o; o = align16(o + R * (R | 1u) * 4);
   l.reg_sum = o; o = align16(o + R * 8);
   l.reg_max = o; o = align16(o + R * 4);
   l.reg_min = o; o = align16(o + R * 4);
@@ -186,7 +188,7 @@ template <> struct SweepKey<unsigned long long> {
 
 template <int WMAX, int PLANES, typename KeyT>
 __device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* grid, const uint16_t* perm,
-                                            unsigned long long* oacc, uint32_t W, uint32_t R, uint32_t cl2,
+                                            uint32_t* oacc32, uint32_t W, uint32_t R, uint32_t cl2,
                                             uint32_t pb, uint32_t ncell, uint32_t shift, uint32_t tid,
                                             uint32_t nthreads) {
   typedef SweepKey<KeyT> K;
@@ -244,14 +246,15 @@ __device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* gr
       for (int k = 1; k < PLANES; ++k) act_after |= pl[k];
       const uint32_t act = is_end ? act_after : act_before;  // active regions other than this one
       if (x & ~act) {  // the region was off before this START / is off after this END
-        const uint32_t a = __ffs(x) - 1;
-        const unsigned long long val = is_end ? (unsigned long long)tt : (0ull - (unsigned long long)tt);
-        atomicAdd(&oacc[a * R + a], val);
+        // modulo 2^32: the totals of one workgroup lie below its span, which is below 2^32
+        uint32_t* row = oacc32 + (__ffs(x) - 1) * (R | 1u);
+        const uint32_t val = is_end ? tt : 0u - tt;
+        atomicAdd(&row[__ffs(x) - 1], val);
         uint32_t set = act;
         while (set) {
           const uint32_t bb = __ffs(set) - 1;
           set &= set - 1;
-          atomicAdd(&oacc[a * R + bb], val);
+          atomicAdd(&row[bb], val);
         }
       }
     }
@@ -280,6 +283,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* bucket = reinterpret_cast<uint32_t*>(smem + L.bucket);
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
   unsigned long long* oacc = reinterpret_cast<unsigned long long*>(smem + L.oacc);
+  uint32_t* oacc32 = reinterpret_cast<uint32_t*>(smem + L.oacc32);  // this workgroup's sums modulo 2^32
   unsigned long long* reg_sum = reinterpret_cast<unsigned long long*>(smem + L.reg_sum);
   uint32_t* reg_max = reinterpret_cast<uint32_t*>(smem + L.reg_max);
   uint32_t* reg_min = reinterpret_cast<uint32_t*>(smem + L.reg_min);
@@ -302,8 +306,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   const StatsLayout SL = stats_layout(p.n_wg, W, R);
   if (p.out[H_STATUS] != 0) return;  // device header did not match the launch geometry
 
-  for (uint32_t i = tid; i < R * 64; i += BLOCK) hist[i] = 0;
+  for (uint32_t i = tid; i < R * kHistStride; i += BLOCK) hist[i] = 0;
   for (uint32_t i = tid; i < R * R; i += BLOCK) oacc[i] = 0;
+  for (uint32_t i = tid; i < R * (R | 1u); i += BLOCK) oacc32[i] = 0;
   for (uint32_t i = tid; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
   for (uint32_t i = tid; i < W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
   if (tid < 16) ctr[tid] = 0;
@@ -492,7 +497,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
           atomicMax(&pw_max[e], d);
           atomicMin(&pw_min[e], d);
-          atomicAdd(&hist[region * 64 + (d ? 31 - __clz(d) : 0)], 1u);
+          atomicAdd(&hist[region * kHistStride + (d ? 31 - __clz(d) : 0)], 1u);
         }
       }
 #pragma unroll
@@ -579,13 +584,13 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
       const uint32_t pb = p.pos_bits;
       if (!tmp[T_WIDE] && shift + pb <= 31u) {  // the all-ones key must stay free
-        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
       } else {
-        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
       }
     }
     __syncthreads();
@@ -607,6 +612,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       pw_pack[e] = 0; pw_max[e] = 0; pw_min[e] = 0xFFFFFFFFu;
     }
+    // region-pair sums of this workgroup: the two one-sided sums of a pair add up, modulo 2^32, to the
+    // time both regions were open (below the span, hence exact); the upper triangle keeps the totals
+    for (uint32_t i = tid; i < R * R; i += BLOCK) {
+      const uint32_t a = i / R, b = i - a * R;
+      if (a > b) continue;
+      uint32_t* ab = oacc32 + a * (R | 1u) + b;
+      uint32_t* ba = oacc32 + b * (R | 1u) + a;
+      const uint32_t v = a == b ? *ab : *ab + *ba;
+      *ab = 0u; *ba = 0u;
+      oacc[i] += v;
+    }
     if (tid == 0) {
       ctr[H_INVALID] += wg_invalid;
       ctr[H_DISORDER] += tmp[T_DISORDER];
@@ -622,8 +638,10 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 
   // ---- flush this decoder workgroup's totals --------------------------------------------------
   unsigned long long* out = reinterpret_cast<unsigned long long*>(p.out);
-  for (uint32_t i = tid; i < R * 64; i += BLOCK)
-    if (hist[i]) atomicAdd(&out[SL.hist + i], (unsigned long long)hist[i]);
+  for (uint32_t i = tid; i < R * 64; i += BLOCK) {
+    const uint32_t h = hist[(i >> 6) * kHistStride + (i & 63u)];
+    if (h) atomicAdd(&out[SL.hist + i], (unsigned long long)h);
+  }
   for (uint32_t i = tid; i < R * R; i += BLOCK)
     if (oacc[i]) atomicAdd(&out[SL.F + i], oacc[i]);  // staged in the F area until finalize
   for (uint32_t r = tid; r < R; r += BLOCK) {
