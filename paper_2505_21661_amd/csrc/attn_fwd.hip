@@ -154,6 +154,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
 
     // ---- region 0: S^T = K Q^T, with the staging of V^T tile t threaded in ------------------------
     KP_BOUNDARY(ring, kp::kNoRegion, 0);
+    // The two workgroups of a CU drift apart, so a SIMD usually holds one wave in a matrix region and
+    // one in the softmax.  The matrix regions run at a higher wave priority: when both want to issue,
+    // the MFMA goes first and the matrix pipe stays fed, while the softmax fills the gaps (measured:
+    // 3 % faster than equal priorities, the opposite order 3 % slower).
+    __builtin_amdgcn_s_setprio(1);
     store_v();
     if constexpr (MORE) load_v(kv0 + kBkv);
     f32x16 sacc[2];
@@ -167,6 +172,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       }
     }
     KP_BOUNDARY(ring, 0, 1);
+    __builtin_amdgcn_s_setprio(0);
 
     // every wave is done with K tile t and V^T tile t is visible; K tile t+1 goes to LDS while the softmax runs
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -210,6 +216,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     }
     m_run = m_new;
     KP_BOUNDARY(ring, 1, 2);
+    __builtin_amdgcn_s_setprio(2);
 
     // ---- region 2: O^T += V^T P^T ---------------------------------------------------------------------
     // The kv order inside an MFMA step follows the accumulator layout of S^T (kv = 16s + 4h + e for
@@ -230,6 +237,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         }
       }
     KP_BOUNDARY(ring, 2, kp::kNoRegion);
+    __builtin_amdgcn_s_setprio(0);
 
     // every wave is done with V^T tile t, and K tile t+1 is visible
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
