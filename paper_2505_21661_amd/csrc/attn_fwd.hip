@@ -4,7 +4,8 @@
 // The paper's case study profiles a flash-attention kernel whose regions are the two GEMMs and
 // the softmax of every KV iteration (Sec. 5.2, Table 3: GEMM0 = Q K^T, softmax, GEMM1 = P V).
 // This is the library's own MFMA kernel with the same three regions per KV tile of 64:
-//   region 0  S^T = K Q^T     (MFMA)
+//   region 0  S^T = K Q^T     (MFMA); from the second tile on it opens with the barrier that makes
+//             the K tile visible
 //   region 1  online softmax   (VALU, fp32); opens with the barrier and LDS writes that stage the
 //             next K tile, which overlap the other waves' softmax
 //   region 2  O^T += V^T P^T   (MFMA)
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     const uint32_t kv0 = t * kBkv;
 
     // ---- region 0: S^T = K Q^T, with the staging of V^T tile t threaded in ------------------------
-    KP_BOUNDARY(ring, kp::kNoRegion, 0);
+    // (opened by the site that closed region 2 of the tile before, or by the one ahead of the loop)
     // The two workgroups of a CU drift apart, so a SIMD usually holds one wave in a matrix region and
     // one in the softmax.  The matrix regions run at a higher wave priority: when both want to issue,
     // the MFMA goes first and the matrix pipe stays fed, while the softmax fills the gaps (measured:
@@ -236,7 +237,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
           oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, oacc[dt], 0, 0, 0);
         }
       }
-    KP_BOUNDARY(ring, 2, kp::kNoRegion);
+    // One site closes region 2 and opens region 0 of the next tile, so that region 0 begins with the
+    // wait for K tile t+1 (the barrier below) and a tile costs three sites, not four.
+    if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, kp::kNoRegion);
     __builtin_amdgcn_s_setprio(0);
 
     // every wave is done with V^T tile t, and K tile t+1 is visible
@@ -244,6 +247,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
+  KP_BOUNDARY(ring, kp::kNoRegion, 0);
   // only the last two tiles of a causal block can reach past the diagonal
   for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, yes, no);
   tile(n_tiles - 2, yes, no, yes);
