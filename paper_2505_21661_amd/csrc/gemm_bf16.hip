@@ -57,12 +57,15 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 
 // END of one region and START of the next with a single clock sample.  INSTR: 0 no record sites,
 // 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
-#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<INSTR>(ring, end_r, start_r); } while (0)
+// SITE is the form of the sites a kernel uses for INSTR (kp::site<>): the large kernel buffers its
+// lean sites in registers, the small one writes them to LDS at the next site.
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<SITE>(ring, end_r, start_r); } while (0)
 
 // ------------------------------------------------------------------------------------------
 // 64x64x32 tile, 4 waves as 2x2, each wave one 32x32 accumulator tile.
 template <int INSTR>
 __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
+  constexpr int SITE = INSTR;
   constexpr int BM = 64, BN = 64, BK = 32;
   __shared__ __align__(16) unsigned char sA[BM * BK * 2];
   __shared__ __align__(16) unsigned char sB[BN * BK * 2];
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   kp::Ring ring{};
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4, wg);
-  if constexpr (INSTR == 2) kp::lean_begin(ring);
+  kp::sites_begin<SITE>(ring);
 
   // global -> register mapping
   // A: 64 rows x 4 chunks = 256 chunks, one per thread
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   }
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
-    if constexpr (INSTR == 2) kp::lean_end(ring);
+    kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
@@ -155,6 +158,7 @@ constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // bot
 
 template <int INSTR, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
+  constexpr int SITE = INSTR == 2 ? 3 : INSTR;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
   static_assert(WAVES == 8 || WAVES == 4, "2 x 4 or 2 x 2 waves");
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, WAVES, wg);
-  if constexpr (INSTR == 2) kp::lean_begin(ring);
+  kp::sites_begin<SITE>(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Every thread stages the same share of a K step, so all waves reach the barrier together:
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   KP_BOUNDARY(ring, 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, WAVES, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
-    if constexpr (INSTR == 2) kp::lean_end(ring);
+    kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }
