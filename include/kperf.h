@@ -304,6 +304,10 @@ kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void
  *   mode bit0 = 1: cycles[r]/64 executions of s_sleep 1
  * bracketed by a START and an END record; cycles[r] = 0 gives an empty region whose duration is
  * the cost of one record.  mode bit1 selects the flush strategy with an 8-slot LDS sub-ring.
+ * mode bit2 selects the metric the records carry (the MetricType of the paper's ReadCounterOp,
+ * Sec. 3.1): 0 the shader clock (s_memtime), 1 the constant-rate 100 MHz clock (s_memrealtime); the
+ * payloads and the workgroup header's t_begin / t_end are in that clock's ticks, and the header's
+ * reserved word holds the same span on the other clock.
  *   cycles     HOST pointer to n_regions values (n_regions <= 32)
  *   trace_buf  device, kp_trace_bytes(n_wg, waves, trace_cap) bytes; trace_cap as above
  */

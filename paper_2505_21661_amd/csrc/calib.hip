@@ -6,6 +6,8 @@
 // region r being a chain of dependent v_fma_f32 (mode 0) or a run of s_sleep (mode 1) whose
 // length is given by the caller; a region of length 0 measures the bare cost of a START/END
 // record pair.  The decoded durations give ticks per FMA (timer unit) and the record cost.
+// The records can carry either of the two clocks the hardware offers (the MetricType of the
+// paper's ReadCounterOp, Sec. 3.1): the shader clock or the constant-rate 100 MHz clock.
 #include "kp_common.h"
 #include "kp_record.h"
 
@@ -35,12 +37,14 @@ __device__ __forceinline__ void busy_sleep(uint32_t n) {
   for (uint32_t i = n; i; --i) asm volatile("s_sleep 1");
 }
 
+template <bool REALTIME>
 __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace, uint32_t cap_lds,
                                                         uint32_t cap_hbm, uint32_t flush, uint32_t n_wg,
                                                         uint32_t waves, float* sink) {
   extern __shared__ __align__(16) uint32_t lds_ring[];  // ring first, the rest only limits occupancy
   __shared__ uint64_t t_begin[2];
   kp::Ring r = kp::ring_init(lds_ring, t_begin, cap_lds, 0xFFFFFFFFu, flush, cap_hbm, trace, n_wg, waves, blockIdx.x);
+  if constexpr (REALTIME) kp::ring_use_realtime(r);
   float x = (float)threadIdx.x;
   // Two identical passes: the first warms the instruction cache and is then discarded by
   // resetting the ring state, so that no recorded region pays for a cold code fetch.
@@ -51,15 +55,15 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
     r.pend_tag2 = kp::kNoPending;
     for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
       const uint32_t len = a.cycles[rg];
-      kp::record(r, rg, kp::kPhaseStart);
+      kp::record<REALTIME>(r, rg, kp::kPhaseStart);
       if (a.mode == 0) busy_fma(len >> 2, x); else busy_sleep(len >> 6);
-      kp::record(r, rg, kp::kPhaseEnd);
+      kp::record<REALTIME>(r, rg, kp::kPhaseEnd);
     }
     if (pass == 0) kp::store_pending(r);
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
   kp::TraceGeom g{n_wg, waves, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
-  kp::ring_finish(r, cap_lds, trace, g, blockIdx.x, 0u);
+  kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, 0u);
 }
 
 }  // namespace
@@ -68,7 +72,7 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
                                   void* trace_buf, size_t trace_cap, void* stream) {
   kp::clear_error();
   if (!cycles || !trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
-  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~3))
+  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~7))
     return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
   if (trace_cap % (size_t)waves) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of waves");
   const size_t cap_wave = trace_cap / (size_t)waves;
@@ -88,11 +92,14 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
   const uint32_t lds_bytes = 96 * 1024;
   static thread_local bool attr_set = false;
   if (!attr_set) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel),
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kp_calib_kernel, dim3(n_wg), dim3(waves * 64), lds_bytes, static_cast<hipStream_t>(stream),
+  auto kern = (mode & 4) ? kp_calib_kernel<true> : kp_calib_kernel<false>;
+  hipLaunchKernelGGL(kern, dim3(n_wg), dim3(waves * 64), lds_bytes, static_cast<hipStream_t>(stream),
                      a, trace_buf, cap_lds, (uint32_t)cap_wave, flush, (uint32_t)n_wg, (uint32_t)waves,
                      static_cast<float*>(nullptr));
   KP_HIP_TRY(hipGetLastError());

@@ -145,9 +145,13 @@ __device__ __forceinline__ void store_one(Ring& r, uint32_t tag, uint32_t ts) {
 // subtracts.  It also names the whole pair as an input, which keeps both halves allocated up to
 // there (a dead half could be reused right after the sample was issued, and that write-after-write
 // hazard stalls the wave at the sample).
+// REALTIME selects the metric (the paper's ReadCounterOp carries a MetricType, Sec. 3.1): the shader
+// clock (s_memtime, the default) or the constant-rate 100 MHz clock (s_memrealtime).
+template <bool REALTIME = false>
 __device__ __forceinline__ uint64_t sample_clock() {
   uint64_t t;
-  asm volatile("s_memtime %0" : "=s"(t));
+  if constexpr (REALTIME) asm volatile("s_memrealtime %0" : "=s"(t));
+  else asm volatile("s_memtime %0" : "=s"(t));
   return t;
 }
 // low 32 bits of (t - t0) for a value returned by sample_clock()
@@ -172,10 +176,11 @@ __device__ __forceinline__ void store_pending(Ring& r) {
 // leaves the 64-bit result untouched: lgkmcnt is shared between s_memtime and LDS, so any use
 // of a fresh value stalls the wave for the full s_memtime round trip (~200 cycles on gfx950).
 // Back-to-back END/START therefore share one sample instead of paying that stall.
+template <bool REALTIME = false>
 __device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t start_region) {
   __builtin_amdgcn_sched_barrier(0);
   store_pending(r);  // also when nothing is pending: the previous sample must have landed before the next
-  const uint64_t now = sample_clock();
+  const uint64_t now = sample_clock<REALTIME>();
   const bool on_e = end_region != kNoRegion && ((r.mask >> (end_region & 31u)) & 1u) != 0u;     // scalar
   const bool on_s = start_region != kNoRegion && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
   r.pend_tag = on_e ? ((1u << 31) | (end_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
@@ -358,11 +363,17 @@ __device__ __forceinline__ void sites_end(Ring& r) {
   else if constexpr (MODE == 2) lean_end(r);
 }
 
+template <bool REALTIME = false>
 __device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase) {
-  boundary(r, phase == kPhaseEnd ? region : kNoRegion, phase == kPhaseStart ? region : kNoRegion);
+  boundary<REALTIME>(r, phase == kPhaseEnd ? region : kNoRegion, phase == kPhaseStart ? region : kNoRegion);
 }
 
+// After ring_init(): record the constant-rate clock from here on.  Payloads, t_begin and t_end of
+// the trace are then in 100 MHz ticks; use record<true>() / ring_finish<true>() with it.
+__device__ __forceinline__ void ring_use_realtime(Ring& r) { r.t0_lo = (uint32_t)r.rt_begin; }
+
 // Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
+template <bool REALTIME = false>
 __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
                                             uint32_t rec_cost) {
   __syncthreads();  // t_end must not precede any wave's last record
@@ -386,9 +397,10 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
   if (threadIdx.x == 0) {
     wh->wg_id = wg;
     wh->hw_id = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (11 << 11));  // HW_ID, low 12 bits
-    wh->t_begin = r.t_begin;
-    wh->t_end = t_end;
-    wh->reserved = rt_end - r.rt_begin;  // constant-rate (s_memrealtime) ticks over the same span
+    // the header's span is in the unit of the payloads; `reserved` holds the same span on the other clock
+    wh->t_begin = REALTIME ? r.rt_begin : r.t_begin;
+    wh->t_end = REALTIME ? rt_end : t_end;
+    wh->reserved = REALTIME ? t_end - r.t_begin : rt_end - r.rt_begin;
     for (uint32_t w = g.waves; w < KP_MAX_WAVES; ++w) wh->total_written[w] = 0;
     for (int i = 0; i < 8; ++i) wh->pad[i] = 0;
     if (wg == 0) {

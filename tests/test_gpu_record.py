@@ -96,6 +96,41 @@ def test_timer_is_linear_within_3_percent(kp, oracle_mod):
     assert np.mean(np.abs(longest - expected[-1]) <= 0.03 * expected[-1]) > 0.6
 
 
+def test_constant_rate_clock_metric(kp, oracle_mod):
+    """mode bit 2: the records carry the constant-rate 100 MHz clock instead of the shader clock.
+    The same regions measured on both clocks must agree up to the ratio of the two tick rates, which
+    the workgroup headers give independently (both clocks over the same span)."""
+    n_wg, waves = 1024, 4
+    cycles = [0, 4096, 16384, 65536]
+    buf_c, raw_c = run_calibrate(kp, cycles, n_wg, waves, 0, 64)
+    buf_r, raw_r = run_calibrate(kp, cycles, n_wg, waves, 4, 64)
+    st_c = decode_both(kp, oracle_mod, buf_c, raw_c)
+    st_r = decode_both(kp, oracle_mod, buf_r, raw_r)
+    assert st_r["n_pairs"] == st_c["n_pairs"] == n_wg * waves * len(cycles)
+    assert st_r["n_nonmonotonic"] == 0 and st_r["n_span_overflow_wgs"] == 0
+
+    def spans(raw):
+        hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32).astype(np.uint64)
+        span = (hdr[:, 4] | (hdr[:, 5] << np.uint64(32))) - (hdr[:, 2] | (hdr[:, 3] << np.uint64(32)))
+        other = hdr[:, 6] | (hdr[:, 7] << np.uint64(32))
+        return span.astype(np.float64), other.astype(np.float64)
+
+    span_c, rt_of_c = spans(raw_c)     # shader ticks, 100 MHz ticks over the same spans
+    span_r, clk_of_r = spans(raw_r)    # 100 MHz ticks, shader ticks
+    ratio_c = rt_of_c.sum() / span_c.sum()   # 100 MHz ticks per shader tick
+    ratio_r = span_r.sum() / clk_of_r.sum()
+    assert abs(ratio_r - ratio_c) <= 0.03 * ratio_c, (ratio_r, ratio_c)
+    d_c = np.median(st_c["per"]["sum"].astype(np.float64), axis=(0, 1))
+    d_r = np.median(st_r["per"]["sum"].astype(np.float64), axis=(0, 1))
+    print(f"100 MHz ticks per shader tick {ratio_c:.5f} / {ratio_r:.5f}; shader-clock medians {d_c}, constant-rate medians {d_r}")
+    # one tick of the constant-rate clock is about 23 shader ticks: 3 % needs regions of 1000 ticks and more
+    for i in (2, 3):
+        assert abs(d_r[i] - d_c[i] * ratio_c) <= 0.03 * d_c[i] * ratio_c + 1.0, (i, d_r[i], d_c[i] * ratio_c)
+    # payloads stay inside the span in the clock's own unit
+    recs = raw_r[16 + 32 * n_wg:].reshape(n_wg, waves, 16, 2)[:, :, :2 * len(cycles)]
+    assert (recs[..., 1].astype(np.float64) <= span_r[:, None, None]).all()
+
+
 def test_sleep_mode_runs(kp, oracle_mod):
     buf, raw = run_calibrate(kp, [0, 1024, 4096], 64, 4, 1, 32)
     st = decode_both(kp, oracle_mod, buf, raw)
