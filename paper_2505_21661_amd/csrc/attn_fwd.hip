@@ -42,10 +42,12 @@ constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
 constexpr uint32_t kKBytes = kBkv * kD * 2;   // K tile   [64 kv][128 d]
 constexpr uint32_t kVBytes = kD * kBkv * 2;   // V^T tile [128 d][64 kv]
 
-// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-  const __bf16 h = (__bf16)f;
-  return (uint32_t)__builtin_bit_cast(uint16_t, h);
+// two fp32 -> packed bf16 pair (lo in bits 15:0), round to nearest even: one v_cvt_pk_bf16_f32
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // K tile: rows of 256 bytes (16 chunks of 16 B), chunk c of row r at position c ^ (r & 7) so that
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v], g.scale_log2, -m_new));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v + 1], g.scale_log2, -m_new));
         psum += p0 + p1;  // fp32 sum of the unrounded probabilities
-        pk[tk][v >> 1] = bf16_rne(p0) | (bf16_rne(p1) << 16);
+        pk[tk][v >> 1] = bf16_pack_rne(p0, p1);
       }
     l_run = l_run * alpha + psum;
     // the running maximum settles after a few tiles; skip the rescale when no row of this wave moved
@@ -262,8 +264,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       u32x2 pk2;
-      pk2.x = bf16_rne(oacc[dt][4 * q + 0] * inv) | (bf16_rne(oacc[dt][4 * q + 1] * inv) << 16);
-      pk2.y = bf16_rne(oacc[dt][4 * q + 2] * inv) | (bf16_rne(oacc[dt][4 * q + 3] * inv) << 16);
+      pk2.x = bf16_pack_rne(oacc[dt][4 * q + 0] * inv, oacc[dt][4 * q + 1] * inv);
+      pk2.y = bf16_pack_rne(oacc[dt][4 * q + 2] * inv, oacc[dt][4 * q + 3] * inv);
       *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q + 4 * h32) = pk2;
     }
   if constexpr (INSTR != 0) {

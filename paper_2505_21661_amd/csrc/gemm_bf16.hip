@@ -38,6 +38,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
   const __bf16 h = (__bf16)f;
   return (uint32_t)__builtin_bit_cast(uint16_t, h);
 }
+// two fp32 -> packed bf16 pair (lo in bits 15:0), round to nearest even: one v_cvt_pk_bf16_f32
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 // LDS tiles hold rows of BK bf16 (K contiguous) in 16-byte chunks; chunk c of row r lives at chunk
 // position c ^ swz(r) so that the 16-byte reads of 32 different rows spread over all banks.
@@ -337,8 +344,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       for (int q = 0; q < 4; ++q) {
         const uint32_t col = n0 + wn * (32 * TN) + tn * 32 + 8 * q + 4 * (lane >> 5);
         u32x2 pk;
-        pk.x = f32_to_bf16_rne(acc[tn][tm][4 * q + 0]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 1]) << 16);
-        pk.y = f32_to_bf16_rne(acc[tn][tm][4 * q + 2]) | (f32_to_bf16_rne(acc[tn][tm][4 * q + 3]) << 16);
+        pk.x = bf16_pack_rne(acc[tn][tm][4 * q + 0], acc[tn][tm][4 * q + 1]);
+        pk.y = bf16_pack_rne(acc[tn][tm][4 * q + 2], acc[tn][tm][4 * q + 3]);
         *reinterpret_cast<u32x2*>(g.C + (size_t)row * g.N + col) = pk;
       }
     }
