@@ -41,6 +41,7 @@ struct AttnArgs {
 constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
 constexpr uint32_t kKBytes = kBkv * kD * 2;   // K tile   [64 kv][128 d]
 constexpr uint32_t kVBytes = kD * kBkv * 2;   // V^T tile [128 d][64 kv]
+constexpr float kSlack = 8.0f;                // log2 of how far a score may exceed the softmax reference
 
 // two fp32 -> packed bf16 pair (lo in bits 15:0), round to nearest even: one v_cvt_pk_bf16_f32
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -196,28 +197,33 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         mx = fmaxf(mx, sacc[tk][v]);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * g.scale_log2);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // m_new is finite: kv = 0 is visible to every row
+    // The value the exponentials are taken against only has to keep them in range; it need not be the
+    // running maximum.  It moves (and O and l are rescaled) only when some row of the wave exceeds it
+    // by more than 2^kSlack, which after the first few tiles practically never happens; until then a
+    // probability may be as large as 2^kSlack, which fp32 sums and bf16 operands hold without loss.
+    const float mx_s = mx * g.scale_log2;
+    if (__builtin_amdgcn_ballot_w64(mx_s > m_run + kSlack) != 0ull) {  // always on the first tile (m_run = -inf)
+      const float m_new = fmaxf(m_run, mx_s);  // finite from the first tile on: kv = 0 is visible to every row
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+      m_run = m_new;
+    }
     float psum = 0.f;
     uint32_t pk[2][8];  // P as packed bf16 pairs, in accumulator order
 #pragma unroll
     for (int tk = 0; tk < 2; ++tk)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v], g.scale_log2, -m_new));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v + 1], g.scale_log2, -m_new));
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v], g.scale_log2, -m_run));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tk][v + 1], g.scale_log2, -m_run));
         psum += p0 + p1;  // fp32 sum of the unrounded probabilities
         pk[tk][v >> 1] = bf16_pack_rne(p0, p1);
       }
-    l_run = l_run * alpha + psum;
-    // the running maximum settles after a few tiles; skip the rescale when no row of this wave moved
-    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0ull) {
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-    }
-    m_run = m_new;
+    l_run += psum;
     KP_BOUNDARY(ring, 1, 2);
     __builtin_amdgcn_s_setprio(2);
 
