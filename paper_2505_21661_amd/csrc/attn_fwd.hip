@@ -124,8 +124,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     for (int j = 0; j < 4; ++j) {  // word j of every row: d = 8*dg + 2j (low half) and 2j + 1 (high half)
       const uint32_t w0 = v_reg[0][j], w1 = v_reg[1][j], w2 = v_reg[2][j], w3 = v_reg[3][j];
       u32x2 ev, od;
-      ev.x = (w0 & 0xFFFFu) | (w1 << 16); ev.y = (w2 & 0xFFFFu) | (w3 << 16);
-      od.x = (w0 >> 16) | (w1 & 0xFFFF0000u); od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
+      // low halves / high halves of two words side by side: one v_perm_b32 each (bytes 0-3 of the
+      // selector's space are the second operand, 4-7 the first)
+      ev.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u); ev.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+      od.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u); od.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
       const uint32_t d = v_dg * 8u + 2u * (uint32_t)j;
       *reinterpret_cast<u32x2*>(sV + v_off(d, chunk) + 8u * half) = ev;
       *reinterpret_cast<u32x2*>(sV + v_off(d + 1u, chunk) + 8u * half) = od;
