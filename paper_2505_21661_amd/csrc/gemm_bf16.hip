@@ -115,10 +115,10 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
     *reinterpret_cast<u32x4*>(sA + tile_off<BK>(a_row, a_chunk)) = av;
     if (b_on) {
       u32x4 lo, hi;  // column 2*b_np and 2*b_np+1, eight consecutive k each
-      lo.x = (bv[0] & 0xFFFFu) | (bv[1] << 16); hi.x = (bv[0] >> 16) | (bv[1] & 0xFFFF0000u);
-      lo.y = (bv[2] & 0xFFFFu) | (bv[3] << 16); hi.y = (bv[2] >> 16) | (bv[3] & 0xFFFF0000u);
-      lo.z = (bv[4] & 0xFFFFu) | (bv[5] << 16); hi.z = (bv[4] >> 16) | (bv[5] & 0xFFFF0000u);
-      lo.w = (bv[6] & 0xFFFFu) | (bv[7] << 16); hi.w = (bv[6] >> 16) | (bv[7] & 0xFFFF0000u);
+      lo.x = __builtin_amdgcn_perm(bv[1], bv[0], 0x05040100u); hi.x = __builtin_amdgcn_perm(bv[1], bv[0], 0x07060302u);
+      lo.y = __builtin_amdgcn_perm(bv[3], bv[2], 0x05040100u); hi.y = __builtin_amdgcn_perm(bv[3], bv[2], 0x07060302u);
+      lo.z = __builtin_amdgcn_perm(bv[5], bv[4], 0x05040100u); hi.z = __builtin_amdgcn_perm(bv[5], bv[4], 0x07060302u);
+      lo.w = __builtin_amdgcn_perm(bv[7], bv[6], 0x05040100u); hi.w = __builtin_amdgcn_perm(bv[7], bv[6], 0x07060302u);
       *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_np * 2, b_kg)) = lo;
       *reinterpret_cast<u32x4*>(sB + tile_off<BK>(b_np * 2 + 1, b_kg)) = hi;
     }
@@ -232,8 +232,10 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const uint32_t kq = (tid >> 5) + (T / 32) * (uint32_t)j;
     const uint32_t w0 = lb[j][0][w], w1 = lb[j][1][w], w2 = lb[j][2][w], w3 = lb[j][3][w];
     u32x2 ev, od;
-    ev.x = (w0 & 0xFFFFu) | (w1 << 16); ev.y = (w2 & 0xFFFFu) | (w3 << 16);
-    od.x = (w0 >> 16) | (w1 & 0xFFFF0000u); od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
+    // low halves / high halves of two words side by side: one v_perm_b32 each (bytes 0-3 of the
+    // selector's space are the second operand, 4-7 the first)
+    ev.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u); ev.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+    od.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u); od.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
     const uint32_t n = b_nb * 8u + 2u * (uint32_t)w;
     *reinterpret_cast<u32x2*>(sB + tile_off_bt(n, kq >> 1) + (kq & 1u) * 8u) = ev;
     *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, kq >> 1) + (kq & 1u) * 8u) = od;
