@@ -39,7 +39,8 @@ struct AttnArgs {
 };
 
 constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
-constexpr uint32_t kKBytes = kBkv * kD * 2;   // K tile   [64 kv][128 d]
+constexpr uint32_t kKRow = kD * 2 + 16;        // K tile row: 256 bytes of data + 16 of padding
+constexpr uint32_t kKBytes = kBkv * kKRow;    // K tile   [64 kv][128 d]
 constexpr uint32_t kVBytes = kD * kBkv * 2;   // V^T tile [128 d][64 kv]
 constexpr float kSlack = 8.0f;                // log2 of how far a score may exceed the softmax reference
 
@@ -51,9 +52,10 @@ __device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// K tile: rows of 256 bytes (16 chunks of 16 B), chunk c of row r at position c ^ (r & 7) so that
-// 16-byte reads of 8 neighbouring rows cover all LDS banks.
-__device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return row * 256u + ((chunk ^ (row & 7u)) << 4); }
+// K tile: rows of 256 bytes (16 chunks of 16 B) plus 16 bytes of padding, so that the 16-byte reads
+// of 8 neighbouring rows cover all LDS banks and every read address of a lane is a constant away
+// from the lane's first one (an XOR swizzle would cost one vector instruction per read).
+__device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return row * kKRow + (chunk << 4); }
 // V^T tile: rows of 128 bytes (8 chunks of 16 B).  Within each group of 16 kv the four quads are
 // stored in the order 0, 2, 1, 3, so chunk 2g + h holds exactly the eight kv an MFMA step of the
 // P V product takes from lane half h.  The position also folds in row >> 3, because the transposing
