@@ -36,12 +36,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1055635.7 * 2.0 + 45176.8) * 1024,
-    "gemm_vanilla": (98377.0 * 2.0 + 32807.1) * 1024,
-    "attn_vanilla": (1554494.0 * 2.0 + 131844.2) * 1024,
-    "timeline_2^28": (1057678.9 * 2.0 + 2085829.0) * 1024,
-    "waits_2^28": (1056098.4 * 2.0 + 33216.0) * 1024,
-    "stages_2^28": (1067938.4 * 2.0 + 281870.5) * 1024,
+    "decode_2^28": (1055709.3 * 2.0 + 50104.8) * 1024,
+    "gemm_vanilla": (98358.5 * 2.0 + 32802.0) * 1024,
+    "attn_vanilla": (1069918.1 * 2.0 + 132370.5) * 1024,
+    "timeline_2^28": (1057390.3 * 2.0 + 2086248.9) * 1024,
+    "waits_2^28": (1056426.8 * 2.0 + 33216.0) * 1024,
+    "stages_2^28": (1068110.9 * 2.0 + 282205.5) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 

@@ -79,7 +79,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
   const uint32_t h32 = lane >> 5, l32 = lane & 31u;
   const uint32_t q_blocks = g.S / kBq;
-  const uint32_t wg = blockIdx.x;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  All query blocks of a
+  // (batch, head) go to one XCD, one head after the other, so that its K and V (2 MiB) are fetched
+  // into one L2 once instead of into all eight.  `wg` is the recorded workgroup: head-major.
+  uint32_t wg = blockIdx.x;
+  if (((g.n_wg / q_blocks) & 7u) == 0u) {
+    const uint32_t xcd = blockIdx.x & 7u, j = blockIdx.x >> 3;
+    wg = ((j / q_blocks) * 8u + xcd) * q_blocks + j % q_blocks;
+  }
   // long (late) query blocks first: causal work per block grows with its index
   const uint32_t qb = q_blocks - 1u - (wg % q_blocks);
   const uint32_t bh = wg / q_blocks;
