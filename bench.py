@@ -38,7 +38,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 TRAFFIC_BYTES = {
     "decode_2^28": (1055709.3 * 2.0 + 50104.8) * 1024,
     "gemm_vanilla": (98358.5 * 2.0 + 32802.0) * 1024,
-    "attn_vanilla": (1069918.1 * 2.0 + 132370.5) * 1024,
+    "attn_vanilla": (196750.2 * 2.0 + 131085.0) * 1024,
     "timeline_2^28": (1057390.3 * 2.0 + 2086248.9) * 1024,
     "waits_2^28": (1056426.8 * 2.0 + 33216.0) * 1024,
     "stages_2^28": (1068110.9 * 2.0 + 282205.5) * 1024,
