@@ -7,7 +7,7 @@
 // per (workgroup, region, iteration): {max dur, min start, max (start + dur), rows folded}.
 //
 // A streaming kernel: one decoder workgroup per recorded workgroup at a time (persistent, grid
-// stride), its table in LDS.  Hardware wave h reads the rows of recorded waves h, h + 4, ... with
+// stride), its table in LDS.  Hardware wave h reads the rows of recorded waves h, h + 8, ... with
 // 16-byte loads, four in flight per lane, and folds them with LDS atomics; the table then goes to
 // HBM with 16-byte stores and is reset in the same pass.  The rows of a region are kept
 // max_iter + 1 entries apart in LDS so that equal iterations of different regions use different banks.
@@ -17,7 +17,7 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 512;
 constexpr uint32_t kMaxTableBytes = 64 * 1024;
 
 struct StagesParams {
