@@ -61,6 +61,28 @@ def test_small_attention_matches_oracle_and_vanilla(kp, causal):
     assert_head_close(o_sc, q, k, v, 1, 2, causal, scale=0.2)
 
 
+def test_heads_in_multiples_of_eight_take_the_xcd_mapping(kp):
+    """With a multiple of 8 (batch x head) pairs the workgroups are renumbered so that all query blocks
+    of a head run on one XCD; every head must still come out right, and the recorded workgroup ids
+    stay head-major: workgroup w of the trace is head w // blocks, query block blocks - 1 - w % blocks."""
+    B, H, S = 2, 8, 384
+    q, k, v = inputs.attn_inputs(B, H, S, 128, seed=12)
+    o_van, _, shape = run_attn(kp, q, k, v, True, 0)
+    blocks = S // 128
+    assert shape == (B * H * blocks, 4, 3)
+    for b in range(B):
+        for h in range(H):
+            assert_head_close(o_van, q, k, v, b, h, True)
+    o_ins, trace, _ = run_attn(kp, q, k, v, True, 0b111, trace_cap=1024)
+    assert torch.equal(o_ins.view(torch.int16), o_van.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32)
+    hdr = raw[16:16 + 32 * shape[0]].reshape(shape[0], 32)
+    assert (hdr[:, 0] == np.arange(shape[0])).all()
+    # query block qb writes 6 records per KV tile and wave, 2 * (qb + 1) tiles
+    want = np.array([6 * 2 * (blocks - w % blocks) for w in range(shape[0])])
+    assert (hdr[:, 8] == want).all()
+
+
 def test_attention_special_cases(kp):
     q, k, v = inputs.attn_inputs(1, 1, 256, 128, seed=8)
     vc = torch.full_like(v, 0.75)
