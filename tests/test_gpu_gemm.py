@@ -190,6 +190,37 @@ def test_big_tile_trace_small_k(kp, oracle_mod):
     assert sorted(raw[16:16 + 32 * n_wg].reshape(n_wg, 32)[:, 0].tolist()) == list(range(n_wg))
 
 
+@pytest.mark.parametrize("cap_wave", [2, 16, 64, 256])
+def test_big_tile_lean_sites_with_short_rings(kp, oracle_mod, cap_wave):
+    """The large kernel keeps its record sites in registers and turns 64 of them into records at a time.
+    Rings shorter than such a batch (newest record wins inside the batch), rings that wrap across
+    batches and a ring that holds everything must all decode like the oracle says, with the drop
+    count of the closed form."""
+    from tests.gpu_util import assert_stats_equal
+
+    K = 2048                                                     # 32 K-steps: 3 sites each, 194 records per wave
+    a, b = inputs.gemm_inputs(1024, 1024, K, seed=13)
+    c, trace, (n_wg, waves, R) = run_gemm(kp, a, b, 0b1111, trace_cap=cap_wave * 8)
+    assert (n_wg, waves, R) == (16, 8, 4)
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * cap_wave, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    total = 2 * 3 * (K // 64) + 2
+    assert (raw[16:16 + 32 * n_wg].reshape(n_wg, 32)[:, 8:16] == total).all()
+    assert st["n_dropped"] == n_wg * waves * max(0, total - cap_wave)
+    assert st["n_slots_valid"] == n_wg * waves * min(total, cap_wave)
+    assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_disorder"] == 0
+    # the survivors are the newest records: sequence numbers total - cap_wave .. total - 1
+    recs = raw[16 + 32 * n_wg:].reshape(n_wg, waves, cap_wave, 2)
+    keep = min(total, cap_wave)
+    seq = np.sort(recs[:, :, :keep, 0] & 0xFFFFF, axis=2)   # a ring that wrapped is full: every slot is valid
+    assert (seq == np.arange(total - keep, total)).all()
+    assert_close_to_oracle(c, a, b)
+
+
 def test_full_size_gemm_4096(kp, oracle_mod):
     """The benchmark configuration: 4096^3, N(0,1) inputs, 4 regions, ring of 4096 records per
     workgroup.  Output is checked on sampled rows, the trace against closed forms and the oracle."""
