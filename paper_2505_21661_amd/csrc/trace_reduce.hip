@@ -86,7 +86,7 @@ __host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint3
   l.pw_min = o; o = align16(o + W * R * 4);
   l.ctr = o; o = align16(o + 16 * 8);
   l.tmp = o; o = align16(o + T_COUNT * 4);
-  l.misc = o; o = align16(o + 4 * 4);
+  l.misc = o; o = align16(o + 8 * 4);
   l.v = o; o = align16(o + 16 * 4);
   l.first = o; o = align16(o + 16 * 4);
   l.wave_tot = o; o = align16(o + (block / 64) * 4);
@@ -189,14 +189,14 @@ template <> struct SweepKey<unsigned long long> {
 template <int WMAX, int PLANES, typename KeyT>
 __device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* grid, const uint16_t* perm,
                                             uint32_t* oacc32, uint32_t W, uint32_t R, uint32_t cl2,
-                                            uint32_t pb, uint32_t ncell, uint32_t shift, uint32_t tid,
+                                            uint32_t pb, uint32_t ncell, uint32_t cw, uint32_t tid,
                                             uint32_t nthreads) {
   typedef SweepKey<KeyT> K;
   const KeyT none = ~(KeyT)0;
   const uint32_t capm = (1u << cl2) - 1u, pmask = (1u << pb) - 1u, gstride = ncell + 1;
   for (uint32_t i = tid; i < ncell; i += nthreads) {
     const uint32_t c = perm[i];
-    const uint32_t cbase = c << shift;
+    const uint32_t cbase = c * cw;
     KeyT key[WMAX];        // each wave's next record in this cell; all-ones = none
     uint32_t pl[PLANES];   // bit-sliced count of the waves that have each region open
 #pragma unroll
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L.pw_min);
   unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L.ctr);
   uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
-  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell shift
+  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] log2 of the power-of-two cell width, [2..4] cell width q << sh and 2^16 / q
   uint32_t* sV = reinterpret_cast<uint32_t*>(smem + L.v);
   uint32_t* sFirst = reinterpret_cast<uint32_t*>(smem + L.first);
   uint32_t* wave_tot = reinterpret_cast<uint32_t*>(smem + L.wave_tot);
@@ -339,8 +339,21 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       const uint64_t sp = te - tb;
       uint32_t shift = 0, ovf = 0;
       if (sp >> 32) ovf = 1; else while ((sp >> shift) >= ncell) ++shift;
+      // Cell width q << sh: the narrowest of {5, 6, 7, 8} << (shift - 3) with which ncell cells still
+      // cover the span, so that at least four cells in five are in use (a power of two alone may
+      // leave half of them empty, and fuller cells make the sweep's longest lane longer).
+      uint32_t q = 1u << shift, sh = 0;
+      if (!ovf && shift >= 3) {
+        sh = shift - 3; q = 8;
+        for (uint32_t qq = 5; qq < 8; ++qq)
+          if ((uint32_t)(sp >> sh) < ncell * qq) { q = qq; break; }
+        if (q == 8) { q = 4; sh = shift - 2; }
+      }
       misc[0] = ovf;
       misc[1] = shift;
+      misc[2] = sh;
+      misc[3] = q;
+      misc[4] = 65535u / q + 1u;  // ceil(2^16 / q): (x * m) >> 16 == x / q for x < 8192, q < 8
     }
     if (R > 16 || gen == 1u) {  // clear the staging area (always on this workgroup's first pass)
       u32x4* z = reinterpret_cast<u32x4*>(rec);
@@ -513,7 +526,13 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     const bool eligible = !misc[0] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
 
     if (eligible) {
-      const uint32_t shift = misc[1];
+      const uint32_t shift = misc[1], csh = misc[2], cm = misc[4], xmax = 8u * ncell - 1u;
+      const uint32_t cw = misc[3] << csh;  // cell width, at most 1 << shift
+      auto cell_of = [&](uint32_t t) -> uint32_t {  // t / cw, or some value >= ncell when t lies past the cells
+        uint32_t x = t >> csh;
+        x = x < xmax ? x : xmax;
+        return (x * cm) >> 16;
+      };
       // ---- C: open-region mask before every position (exclusive XOR scan per wave) -------------
       // ---- D: coarse time -> position table: grid[w][c] = first rank of wave w in a cell >= c ----
       {
@@ -524,7 +543,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         }
         uint32_t cprev_carry = 0, wide = 0;
         if (pbase > 0 && pbase < nrec) {
-          const uint32_t c1 = recw[2 * (pbase - 1)] >> shift;
+          const uint32_t c1 = cell_of(recw[2 * (pbase - 1)]);
           cprev_carry = c1 < ncell ? c1 : ncell - 1;
         }
         for (uint32_t qb = pbase; qb < pend; qb += 64) {
@@ -545,7 +564,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
             if (((qb + 64) & capm) == 0) carry = 0;  // next round starts a new wave segment
           }
           const uint32_t w = q0 >> cl2, k = q0 & capm, V = sV[w];
-          const uint32_t c0 = r0.x >> shift;
+          const uint32_t c0 = cell_of(r0.x);
           const uint32_t c = c0 < ncell ? c0 : ncell - 1;
           const uint32_t cp = wave_shr1(c, cprev_carry);
           cprev_carry = (uint32_t)__builtin_amdgcn_readlane((int)c, 63);
@@ -584,13 +603,13 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
       const uint32_t pb = p.pos_bits;
       if (!tmp[T_WIDE] && shift + pb <= 31u) {  // the all-ones key must stay free
-        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
+        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
       } else {
-        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
-        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, shift, tid, BLOCK);
+        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
+        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
+        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
       }
     }
     __syncthreads();
