@@ -34,7 +34,7 @@ __host__ __device__ inline Lds lds_layout(uint32_t nrec) {
   Lds l;
   uint32_t o = 0;
   l.rec = o; o = align16(o + nrec * 8);
-  l.tmp = o; o = align16(o + 2 * 4);     // [0] records accepted, [1] ranks occupied
+  l.tmp = o; o = align16(o + 4 * 4);     // [0] records accepted, [1] ranks occupied, [2] accepted outside their seq's slot
   l.v = o; o = align16(o + 16 * 4);      // records held per wave
   l.first = o; o = align16(o + 16 * 4);  // first surviving seq per wave
   l.end = o;
@@ -93,7 +93,7 @@ __device__ __forceinline__ void stage_workgroup(const Trace& p, unsigned char* s
     sV[tid] = V;
     sFirst[tid] = p.flush ? 0u : T - V;
   }
-  if (tid >= 64 && tid < 66) tmp[tid - 64] = 0;
+  if (tid >= 64 && tid < 67) tmp[tid - 64] = 0;
   if ((live_tag >> 16) == 1u) {
     u32x4* z = reinterpret_cast<u32x4*>(rec);
     for (uint32_t i = tid; i < nrec / 2; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
@@ -103,7 +103,7 @@ __device__ __forceinline__ void stage_workgroup(const Trace& p, unsigned char* s
   {
     const u32x4* recs = p.records + (size_t)wg * (nrec / 2);
     const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
-    uint32_t c_field = 0;
+    uint32_t c_field = 0, c_dis = 0;
     for (uint32_t i0 = tid; i0 < n16; i0 += 4 * BLOCK) {
       u32x4 v[4];
 #pragma unroll
@@ -126,15 +126,20 @@ __device__ __forceinline__ void stage_workgroup(const Trace& p, unsigned char* s
           const uint32_t region = (tag >> 24) & 0x7Fu;
           const bool good = s < V && k < V && ((tag >> 20) & 0xFu) == w && region < R;
           c_field += good ? 1u : 0u;
+          c_dis += (good && s != (tag & capm)) ? 1u : 0u;
           if (good) rec[(w << cl2) + k] = make_uint2(pay, region | ((tag >> 31) ? kMEnd : 0u) | live_tag);
         }
       }
     }
     c_field = wave_sum(c_field);
     if (lane == 0 && c_field) atomicAdd(&tmp[0], c_field);
+    if (__builtin_amdgcn_ballot_w64(c_dis != 0u) && lane == 0) tmp[2] = 1u;
   }
   __syncthreads();
   // ---- a duplicated seq leaves fewer occupied ranks than accepted records ------------------------
+  // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
+  // distinct ranks: only a workgroup with a record elsewhere needs the count.
+  if (tmp[2] == 0u) return;
   {
     uint32_t occ = 0;
     for (uint32_t q = tid; q < nrec; q += BLOCK) occ += is_live(recw[2 * q + 1], live_tag) ? 1u : 0u;

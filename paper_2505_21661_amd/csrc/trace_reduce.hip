@@ -403,13 +403,18 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
     __syncthreads();
     // ---- occupancy check: a duplicated seq leaves fewer occupied ranks than valid records ----
-    {
+    // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
+    // distinct ranks: only a workgroup with a record elsewhere needs the count.
+    const bool count_ranks = tmp[T_DISORDER] != 0u;
+    if (count_ranks) {
       uint32_t occ = 0;
       for (uint32_t q = pbase + lane; q < pend; q += 64) occ += is_live(recw[2 * q + 1]) ? 1u : 0u;
       add_tmp(tmp, T_OCCUPIED, occ);
+      __syncthreads();
+    } else if (tid == 0) {
+      tmp[T_OCCUPIED] = tmp[T_FIELDVALID];  // read again only after the next barrier
     }
-    __syncthreads();
-    if (tmp[T_OCCUPIED] != tmp[T_FIELDVALID]) {
+    if (count_ranks && tmp[T_OCCUPIED] != tmp[T_FIELDVALID]) {
       // Rare: some seq occurs twice.  The later slot must win, so redo this workgroup's
       // scatter in slot order, one thread per wave.
       __syncthreads();
