@@ -243,20 +243,28 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
 
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
- * region_mask: bit r (r < 31) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
+ * region_mask: bit r (r < 30) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
  * selects the flush strategy instead of the default circular one (Sec. 4.2: "Circular" keeps
  * the newest records in LDS and copies them out once at kernel exit; "Flush" writes a full
- * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..30 all zero
+ * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..29 all zero
  * launches the separately compiled uninstrumented kernel: no ring, no record sites; trace_buf
  * may then be NULL.  Instrumented and uninstrumented kernels produce bit-identical outputs.
  *
- * trace_buf: device, kp_trace_bytes(n_wg, waves, trace_cap) bytes, 16-byte aligned; headers and
+ * Bit 30 (KP_MASK_WAVE_GROUP) selects the granularity of the records (Sec. 3.1: the Granularity
+ * option of the lowering; Sec. 4.2: one profiling space per warp group): 0 one record stream per
+ * wave, 1 one per group of four consecutive waves, written by the first wave of the group on
+ * behalf of all four.  The trace then describes waves / 4 "waves" per workgroup (its
+ * waves_per_wg, the tag's wave field and total_written[] count streams), and every size below
+ * that speaks of waves speaks of streams.
+ *
+ * trace_buf: device, kp_trace_bytes(n_wg, streams, trace_cap) bytes, 16-byte aligned; headers and
  * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written
- * hold unspecified bytes).  trace_cap: record slots per workgroup in HBM; trace_cap / waves must
+ * hold unspecified bytes).  trace_cap: record slots per workgroup in HBM; trace_cap / streams must
  * be a power of two >= 2, else KP_ERR_TRACE_TOO_SMALL.  Circular: the whole ring also lives in
  * LDS (KP_ERR_UNSUPPORTED_SHAPE if it exceeds the kernel's LDS budget).
  */
 #define KP_MASK_FLUSH 0x80000000u
+#define KP_MASK_WAVE_GROUP 0x40000000u
 
 /* Launch geometry kp_gemm_instrumented will use for M x N x K: recorded workgroups, waves per
  * workgroup, number of regions.  KP_ERR_UNSUPPORTED_SHAPE if no kernel covers the shape. */
@@ -309,9 +317,10 @@ kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void
  * mode bit2 selects the metric the records carry (the MetricType of the paper's ReadCounterOp,
  * Sec. 3.1): 0 the shader clock (s_memtime), 1 the constant-rate 100 MHz clock (s_memrealtime); the
  * payloads and the workgroup header's t_begin / t_end are in that clock's ticks, and the header's
- * reserved word holds the same span on the other clock.
+ * reserved word holds the same span on the other clock.  mode bit3 selects wave-group granularity
+ * as KP_MASK_WAVE_GROUP does (waves must then be a multiple of 4; the trace holds waves / 4 streams).
  *   cycles     HOST pointer to n_regions values (n_regions <= 32)
- *   trace_buf  device, kp_trace_bytes(n_wg, waves, trace_cap) bytes; trace_cap as above
+ *   trace_buf  device, kp_trace_bytes(n_wg, streams, trace_cap) bytes; trace_cap as above
  */
 kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_wg, int waves, int mode,
                        void* trace_buf, size_t trace_cap, void* stream);

@@ -22,6 +22,7 @@ KP_ERR_HIP = -5
 
 KP_FLAG_FLUSH = 1
 KP_MASK_FLUSH = 1 << 31
+KP_MASK_WAVE_GROUP = 1 << 30  # one record stream per group of four waves
 
 
 class KperfError(RuntimeError):

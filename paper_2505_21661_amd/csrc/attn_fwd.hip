@@ -36,6 +36,7 @@ struct AttnArgs {
   uint32_t region_mask;
   void* trace;
   uint32_t cap_lds, cap_hbm, flush, n_wg;
+  uint32_t group_log2;  // 2^group_log2 waves share one record stream
 };
 
 constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
@@ -95,8 +96,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
 
   kp::Ring ring{};
   if constexpr (INSTR != 0)
-    ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
-                         g.cap_hbm, g.trace, g.n_wg, 4, wg);
+    ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
+                         g.cap_hbm, g.trace, g.n_wg, 4u >> g.group_log2, wg, g.group_log2);
   if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // Q fragments of this wave's 32 rows stay in registers: step s covers d = 16s .. 16s+15
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q + 4 * h32) = pk2;
     }
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     if constexpr (INSTR == 2) kp::lean_end(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -318,7 +319,9 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
     return kp::fail(KP_ERR_INVALID_ARG, "Q, K, V, O must be 16-byte aligned");
   if (!(scale > 0.f) || scale > 1e30f) return kp::fail(KP_ERR_INVALID_ARG, "scale must be positive and finite");
-  const uint32_t regions = region_mask & 0x7FFFFFFFu, flush = region_mask >> 31;
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP), flush = region_mask >> 31;
+  const uint32_t group_log2 = (region_mask & KP_MASK_WAVE_GROUP) ? 2u : 0u;
+  const size_t streams = 4u >> group_log2;
   const int n_wg = B * H * (S / kBq);
   hipStream_t st = static_cast<hipStream_t>(stream);
   AttnArgs g{};
@@ -327,6 +330,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   g.B = (uint32_t)B; g.H = (uint32_t)H; g.S = (uint32_t)S; g.causal = causal ? 1u : 0u;
   g.scale_log2 = scale * 1.4426950408889634f;
   g.region_mask = regions; g.trace = trace_buf; g.flush = flush; g.n_wg = (uint32_t)n_wg;
+  g.group_log2 = group_log2;
   const uint32_t tile_bytes = kKBytes + kVBytes;
   if (regions == 0) {
     hipLaunchKernelGGL(kp_attn_fwd<0>, dim3(n_wg), dim3(kAttnThreads), tile_bytes, st, g);
@@ -336,13 +340,13 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   if (!trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "trace_buf is NULL but region_mask enables regions");
   if (regions >> 3) return kp::fail(KP_ERR_INVALID_ARG, "region_mask enables regions this kernel does not have (3 regions)");
   if (((uintptr_t)trace_buf) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "trace_buf must be 16-byte aligned");
-  if (trace_cap % 4) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of 4 waves");
-  const size_t cap_wave = trace_cap / 4;
+  if (trace_cap % streams) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of %zu record streams", streams);
+  const size_t cap_wave = trace_cap / streams;
   if (!kp::is_pow2(cap_wave) || cap_wave < 2 || cap_wave > (1u << 19))
-    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/waves = %zu must be a power of two >= 2", cap_wave);
+    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/streams = %zu must be a power of two >= 2", cap_wave);
   uint32_t cap_lds = (uint32_t)cap_wave;
   if (flush && cap_lds > 64) cap_lds = 64;
-  const size_t ring_bytes = (size_t)cap_lds * 8 * 4;
+  const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
   static thread_local bool attr_set = false;
@@ -354,7 +358,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
     attr_set = true;
   }
   // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
-  if (!flush && regions == 7u && S <= (1 << 22))
+  if (!flush && !group_log2 && regions == 7u && S <= (1 << 22))
     hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   else
     hipLaunchKernelGGL(kp_attn_fwd<1>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);

@@ -7,7 +7,8 @@
 // length is given by the caller; a region of length 0 measures the bare cost of a START/END
 // record pair.  The decoded durations give ticks per FMA (timer unit) and the record cost.
 // The records can carry either of the two clocks the hardware offers (the MetricType of the
-// paper's ReadCounterOp, Sec. 3.1): the shader clock or the constant-rate 100 MHz clock.
+// paper's ReadCounterOp, Sec. 3.1): the shader clock or the constant-rate 100 MHz clock; and they
+// can be taken per wave or per group of four waves (its Granularity).
 #include "kp_common.h"
 #include "kp_record.h"
 
@@ -37,13 +38,14 @@ __device__ __forceinline__ void busy_sleep(uint32_t n) {
   for (uint32_t i = n; i; --i) asm volatile("s_sleep 1");
 }
 
-template <bool REALTIME>
+template <bool REALTIME, bool GROUPS>
 __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace, uint32_t cap_lds,
                                                         uint32_t cap_hbm, uint32_t flush, uint32_t n_wg,
-                                                        uint32_t waves, float* sink) {
+                                                        uint32_t streams, uint32_t group_log2, float* sink) {
   extern __shared__ __align__(16) uint32_t lds_ring[];  // ring first, the rest only limits occupancy
   __shared__ uint64_t t_begin[2];
-  kp::Ring r = kp::ring_init(lds_ring, t_begin, cap_lds, 0xFFFFFFFFu, flush, cap_hbm, trace, n_wg, waves, blockIdx.x);
+  kp::Ring r = kp::ring_init<GROUPS>(lds_ring, t_begin, cap_lds, 0xFFFFFFFFu, flush, cap_hbm, trace, n_wg, streams, blockIdx.x,
+                             group_log2);
   if constexpr (REALTIME) kp::ring_use_realtime(r);
   float x = (float)threadIdx.x;
   // Two identical passes: the first warms the instruction cache and is then discarded by
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
     if (pass == 0) kp::store_pending(r);
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
-  kp::TraceGeom g{n_wg, waves, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
+  kp::TraceGeom g{n_wg, streams, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
   kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, 0u);
 }
 
@@ -72,17 +74,20 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
                                   void* trace_buf, size_t trace_cap, void* stream) {
   kp::clear_error();
   if (!cycles || !trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
-  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~7))
+  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~15))
     return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
-  if (trace_cap % (size_t)waves) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of waves");
-  const size_t cap_wave = trace_cap / (size_t)waves;
+  const uint32_t group_log2 = (mode & 8) ? 2u : 0u;
+  if (group_log2 && (waves & 3)) return kp::fail(KP_ERR_INVALID_ARG, "wave-group records need a multiple of 4 waves, got %d", waves);
+  const size_t streams = (size_t)(waves >> group_log2);
+  if (trace_cap % streams) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of the %zu record streams", streams);
+  const size_t cap_wave = trace_cap / streams;
   if (!kp::is_pow2(cap_wave) || cap_wave < 2 || cap_wave > (1u << 19))
-    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/waves = %zu must be a power of two >= 2", cap_wave);
+    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/streams = %zu must be a power of two >= 2", cap_wave);
   const uint32_t flush = (mode & 2) ? 1u : 0u;
   // circular: the LDS sub-ring is the whole segment; flush: a small LDS sub-ring is spilled in chunks
   uint32_t cap_lds = (uint32_t)cap_wave;
   if (flush && cap_lds > 8) cap_lds = 8;
-  if ((size_t)cap_lds * 8 * waves > 64 * 1024)
+  if ((size_t)cap_lds * 8 * streams > 64 * 1024)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "ring of %zu records per workgroup exceeds 64 KiB of LDS", trace_cap);
   CalibArgs a{};
   for (int i = 0; i < n_regions; ++i) a.cycles[i] = cycles[i];
@@ -92,15 +97,16 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
   const uint32_t lds_bytes = 96 * 1024;
   static thread_local bool attr_set = false;
   if (!attr_set) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_calib_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    for (auto k : {kp_calib_kernel<false, false>, kp_calib_kernel<true, false>, kp_calib_kernel<false, true>,
+                   kp_calib_kernel<true, true>})
+      KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds_bytes));
     attr_set = true;
   }
-  auto kern = (mode & 4) ? kp_calib_kernel<true> : kp_calib_kernel<false>;
+  auto kern = group_log2 ? ((mode & 4) ? kp_calib_kernel<true, true> : kp_calib_kernel<false, true>)
+                         : ((mode & 4) ? kp_calib_kernel<true, false> : kp_calib_kernel<false, false>);
   hipLaunchKernelGGL(kern, dim3(n_wg), dim3(waves * 64), lds_bytes, static_cast<hipStream_t>(stream),
-                     a, trace_buf, cap_lds, (uint32_t)cap_wave, flush, (uint32_t)n_wg, (uint32_t)waves,
+                     a, trace_buf, cap_lds, (uint32_t)cap_wave, flush, (uint32_t)n_wg, (uint32_t)streams, group_log2,
                      static_cast<float*>(nullptr));
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;

@@ -31,6 +31,7 @@ struct GemmArgs {
   uint32_t region_mask;
   void* trace;
   uint32_t cap_lds, cap_hbm, flush, n_wg;
+  uint32_t group_log2;  // 2^group_log2 waves share one record stream
 };
 
 // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
@@ -85,7 +86,8 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   const uint32_t m0 = (wg / tiles_n) * BM, n0 = (wg % tiles_n) * BN;
   kp::Ring ring{};
   if constexpr (INSTR != 0)
-    ring = kp::ring_init(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4, wg);
+    ring = kp::ring_init<true>(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4u >> g.group_log2, wg,
+                         g.group_log2);
   kp::sites_begin<SITE>(ring);
 
   // global -> register mapping
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
     g.C[(size_t)row * g.N + col] = (uint16_t)f32_to_bf16_rne(acc[v]);
   }
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, 4, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -195,8 +197,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 
   kp::Ring ring{};
   if constexpr (INSTR != 0)
-    ring = kp::ring_init(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
-                         g.cap_hbm, g.trace, g.n_wg, WAVES, wg);
+    ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
+                         g.cap_hbm, g.trace, g.n_wg, (uint32_t)WAVES >> g.group_log2, wg, g.group_log2);
   kp::sites_begin<SITE>(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   }
   KP_BOUNDARY(ring, 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, WAVES, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
@@ -421,14 +423,17 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (!pick_shape(M, N, K, &s))
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "GEMM %dx%dx%d: M,N must be multiples of 64 and K of 32", M, N, K);
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "A, B, C must be 16-byte aligned");
-  const uint32_t regions = region_mask & 0x7FFFFFFFu;
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP);
   const uint32_t flush = region_mask >> 31;
+  const uint32_t group_log2 = (region_mask & KP_MASK_WAVE_GROUP) ? 2u : 0u;
+  const int streams = s.waves >> group_log2;
   const int n_wg = (M / s.bm) * (N / s.bn);
   hipStream_t st = static_cast<hipStream_t>(stream);
   GemmArgs g{};
   g.A = static_cast<const uint16_t*>(A); g.B = static_cast<const uint16_t*>(B); g.C = static_cast<uint16_t*>(C);
   g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
   g.region_mask = regions; g.trace = trace_buf; g.n_wg = (uint32_t)n_wg; g.flush = flush;
+  g.group_log2 = group_log2;
   const bool big = s.bm == 256;
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
     if (big) return launch_big_w<0>(s.waves, g, n_wg, 0, st);
@@ -439,17 +444,17 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (!trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "trace_buf is NULL but region_mask enables regions");
   if (regions >> s.regions) return kp::fail(KP_ERR_INVALID_ARG, "region_mask enables regions this kernel does not have (%d regions)", s.regions);
   if (((uintptr_t)trace_buf) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "trace_buf must be 16-byte aligned");
-  if (trace_cap % (size_t)s.waves) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of %d waves", s.waves);
-  const size_t cap_wave = trace_cap / (size_t)s.waves;
+  if (trace_cap % (size_t)streams) return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap must be a multiple of %d record streams", streams);
+  const size_t cap_wave = trace_cap / (size_t)streams;
   if (!kp::is_pow2(cap_wave) || cap_wave < 2 || cap_wave > (1u << 19))
-    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/waves = %zu must be a power of two >= 2", cap_wave);
+    return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/streams = %zu must be a power of two >= 2", cap_wave);
   uint32_t cap_lds = (uint32_t)cap_wave;
   if (flush && cap_lds > 64) cap_lds = 64;
-  const size_t ring_bytes = (size_t)cap_lds * 8 * s.waves;
+  const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
   // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
-  const bool lean = !flush && regions == (1u << s.regions) - 1u && K <= (1 << 22);
+  const bool lean = !flush && !group_log2 && regions == (1u << s.regions) - 1u && K <= (1 << 22);
   if (big) return lean ? launch_big_w<2>(s.waves, g, n_wg, ring_bytes, st) : launch_big_w<1>(s.waves, g, n_wg, ring_bytes, st);
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);

@@ -33,7 +33,9 @@ struct Ring {
   uint32_t lds_mask;   // LDS sub-ring capacity - 1
   uint32_t tag_wave;   // wave index << 20
   uint32_t t0_lo;      // low 32 bits of the workgroup's t_begin
-  uint32_t mask;       // enabled regions
+  uint32_t mask;       // enabled regions (none in a wave that does not write its group's stream)
+  uint32_t stream;     // record stream of this wave: wave index >> group_log2
+  uint32_t leader;     // 1 in the wave that writes the stream (the first wave of its group)
   uint32_t pend_tag;   // up to two records that share the last clock sample and are not in LDS yet
   uint32_t pend_tag2;  //   (an END and the START that follows it); kNoPending: none
   uint32_t stored;     // records already written to the LDS sub-ring
@@ -56,12 +58,20 @@ struct TraceGeom {
 
 __device__ __forceinline__ uint32_t wave_uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Workgroup prologue.  `ring_lds` holds waves * cap_lds slots.  `scratch_lds` (16 bytes) is only used
+// Workgroup prologue.  `ring_lds` holds streams * cap_lds slots.  `scratch_lds` (16 bytes) is only used
 // inside this call to hand thread 0's clock samples to every wave and may be reused afterwards.
+// Granularity (Sec. 3.1, the Granularity option; Sec. 4.2: one profiling space per warp group): with
+// group_log2 = g the 2^g consecutive waves of a group share one record stream, which the first wave of
+// the group writes on behalf of all; `streams` = waves per workgroup >> g.  Only the generic record
+// sites (boundary / record) honour it.  GROUPS = false ignores group_log2 (taken as 0) and leaves the
+// region mask as the caller gave it, so that a constant mask stays a constant in the record sites.
+template <bool GROUPS = false>
 __device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_lds, uint32_t cap_lds,
                                           uint32_t region_mask, uint32_t flush, uint32_t cap_hbm,
-                                          void* trace_buf, uint32_t n_wg, uint32_t waves, uint32_t wg) {
-  const uint32_t wave = wave_uniform(threadIdx.x >> 6);
+                                          void* trace_buf, uint32_t n_wg, uint32_t streams, uint32_t wg,
+                                          uint32_t group_log2 = 0) {
+  const uint32_t hw_wave = wave_uniform(threadIdx.x >> 6);
+  const uint32_t wave = GROUPS ? hw_wave >> group_log2 : hw_wave;  // the stream index stands where the wave index stood
   if (threadIdx.x == 0) {
     scratch_lds[0] = __builtin_readcyclecounter();
     scratch_lds[1] = __builtin_amdgcn_s_memrealtime();
@@ -81,7 +91,13 @@ __device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_
   r.lds_mask = cap_lds - 1;
   r.tag_wave = wave << 20;
   r.t0_lo = (uint32_t)r.t_begin;
+  r.stream = wave;
+  r.leader = 1u;
   r.mask = region_mask;
+  if constexpr (GROUPS) {
+    r.leader = (hw_wave & ((1u << group_log2) - 1u)) == 0u ? 1u : 0u;
+    r.mask = r.leader ? region_mask : 0u;
+  }
   r.pend_tag = kNoPending;
   r.pend_tag2 = kNoPending;
   r.stored = 0;
@@ -90,7 +106,7 @@ __device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_
   r.cap_hbm = cap_hbm;
   r.seg = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(trace_buf) + sizeof(kp_trace_hdr) +
                                       sizeof(kp_wg_hdr) * (size_t)n_wg) +
-          ((size_t)wg * waves + wave) * cap_hbm * 2;
+          ((size_t)wg * streams + wave) * cap_hbm * 2;
   return r;
 }
 
@@ -379,21 +395,23 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
   __syncthreads();  // t_end must not precede any wave's last record
   const uint64_t t_end = __builtin_readcyclecounter();
   const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
-  store_pending(r);
   unsigned char* base = static_cast<unsigned char*>(trace_buf);
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
-  if (r.flush) {
-    const uint32_t tail = r.cnt & r.lds_mask;           // records not yet copied
-    const uint32_t done = r.cnt - tail;
-    if (tail && done < r.cap_hbm) {
-      const uint32_t room = r.cap_hbm - done;
-      wave_copy_slots(r.sub, r.seg + (size_t)done * 2, tail < room ? tail : room);
-    }
-  } else {
-    wave_copy_slots(r.sub, r.seg, cap_lds);  // whole sub-ring; the decoder ignores slots >= total
-  }
+  const uint32_t lane = threadIdx.x & 63u;
   kp_wg_hdr* wh = reinterpret_cast<kp_wg_hdr*>(base + sizeof(kp_trace_hdr)) + wg;
-  if (lane == 0) wh->total_written[wave] = r.cnt;
+  if (r.leader) {  // the wave that wrote the stream also copies it out
+    store_pending(r);
+    if (r.flush) {
+      const uint32_t tail = r.cnt & r.lds_mask;           // records not yet copied
+      const uint32_t done = r.cnt - tail;
+      if (tail && done < r.cap_hbm) {
+        const uint32_t room = r.cap_hbm - done;
+        wave_copy_slots(r.sub, r.seg + (size_t)done * 2, tail < room ? tail : room);
+      }
+    } else {
+      wave_copy_slots(r.sub, r.seg, cap_lds);  // whole sub-ring; the decoder ignores slots >= total
+    }
+    if (lane == 0) wh->total_written[r.stream] = r.cnt;
+  }
   if (threadIdx.x == 0) {
     wh->wg_id = wg;
     wh->hw_id = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (11 << 11));  // HW_ID, low 12 bits

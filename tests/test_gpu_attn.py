@@ -116,6 +116,37 @@ def test_attention_trace_closed_form(kp, oracle_mod):
     assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_disorder"] == 0
 
 
+def test_attention_wave_group_records(kp, oracle_mod):
+    """KP_MASK_WAVE_GROUP: the four waves of a workgroup form one group, so the trace holds one
+    stream per workgroup, written by wave 0, with the per-wave record count."""
+    from tests.gpu_util import assert_stats_equal
+
+    B, H, S = 1, 2, 512
+    q, k, v = inputs.attn_inputs(B, H, S, 128, seed=10)
+    Q, K, V = q.cuda(), k.cuda(), v.cuda()
+    O, O0 = torch.empty_like(Q), torch.empty_like(Q)
+    n_wg, waves, R = kp.kp_attn_launch_shape(B, H, S, 128)
+    cap = 64
+    trace = torch.full((kp.kp_trace_bytes(n_wg, 1, cap),), 0x33, dtype=torch.uint8, device="cuda")
+    scale = 1.0 / np.sqrt(128.0)
+    kp.kp_attn_instrumented(Q, K, V, O, B, H, S, 128, True, scale, 0b111 | kp.KP_MASK_WAVE_GROUP, trace, cap)
+    kp.kp_attn_instrumented(Q, K, V, O0, B, H, S, 128, True, scale, 0, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(torch.int16), O0.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[2:8]) == (n_wg, 1, R, cap, 0, 0)
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, 1, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * cap, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    totals = np.array([6 * 2 * (qb + 1) for qb in range(S // 128)])
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert sorted(hdr[:, 8].tolist()) == sorted(list(totals) * (B * H)) and (hdr[:, 9:24] == 0).all()
+    assert st["n_slots_valid"] == B * H * int(totals.sum()) and st["n_dropped"] == 0
+    assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_disorder"] == 0
+
+
 def test_full_size_attention(kp, oracle_mod):
     """Benchmark configuration: batch 4, 32 heads, sequence 4096, head dim 128, causal, ring of 1024
     records per workgroup (256 per wave), which wraps for query blocks 21..31."""

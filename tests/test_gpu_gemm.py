@@ -221,6 +221,44 @@ def test_big_tile_lean_sites_with_short_rings(kp, oracle_mod, cap_wave):
     assert_close_to_oracle(c, a, b)
 
 
+@pytest.mark.parametrize("shape,flush", [((1024, 1024, 512), 0), ((1024, 1024, 512), 1), ((128, 128, 256), 0)])
+def test_wave_group_records(kp, oracle_mod, shape, flush):
+    """KP_MASK_WAVE_GROUP: one record stream per group of four waves (Sec. 3.1 Granularity, Sec. 4.2
+    buffer per warp group).  The trace holds waves / 4 streams with the per-wave record count each,
+    decodes like the oracle says, and C stays bit-identical to the uninstrumented kernel's."""
+    from tests.gpu_util import assert_stats_equal
+
+    M, N, K = shape
+    a, b = inputs.gemm_inputs(M, N, K, seed=14)
+    n_wg, waves, R = kp.kp_gemm_launch_shape(M, N, K)
+    streams, cap_stream = waves // 4, 256
+    A, B = a.cuda(), b.cuda()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    C0 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    trace = torch.full((kp.kp_trace_bytes(n_wg, streams, streams * cap_stream),), 0x77, dtype=torch.uint8, device="cuda")
+    mask = ((1 << R) - 1) | kp.KP_MASK_WAVE_GROUP | (kp.KP_MASK_FLUSH if flush else 0)
+    kp.kp_gemm_instrumented(A, B, C, M, N, K, mask, trace, streams * cap_stream)
+    kp.kp_gemm_instrumented(A, B, C0, M, N, K, 0, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16), C0.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[2:8]) == (n_wg, streams, R, cap_stream, 0, flush)
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, streams, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * streams * cap_stream, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    if waves == 8:   # large tile: three regions per K-step of 64 and one epilogue
+        per_stream, cnt = 2 * 3 * (K // 64) + 2, [n_wg * streams * (K // 64)] * 3 + [n_wg * streams]
+    else:            # small tile: three regions per K-step of 32
+        per_stream, cnt = 2 * 3 * (K // 32), [n_wg * streams * (K // 32)] * 3
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert (hdr[:, 8:8 + streams] == per_stream).all() and (hdr[:, 8 + streams:24] == 0).all()
+    assert st["n_slots_valid"] == n_wg * streams * per_stream and st["cnt"].tolist() == cnt
+    for k in ("n_orphan_start", "n_orphan_end", "n_invalid", "n_dropped", "n_disorder", "n_nonmonotonic"):
+        assert st[k] == 0, k
+
+
 def test_full_size_gemm_4096(kp, oracle_mod):
     """The benchmark configuration: 4096^3, N(0,1) inputs, 4 regions, ring of 4096 records per
     workgroup.  Output is checked on sampled rows, the trace against closed forms and the oracle."""

@@ -168,6 +168,52 @@ def test_flush_strategy(kp, oracle_mod):
     assert st["cnt"].tolist() == [n_wg * waves] * 8 + [0] * 4
 
 
+def run_calibrate_streams(kp, cycles, n_wg, waves, streams, mode, trace_cap):
+    buf = torch.full((kp.kp_trace_bytes(n_wg, streams, trace_cap),), 0x5A, dtype=torch.uint8, device="cuda")
+    kp.kp_calibrate(cycles, n_wg, waves, mode, buf, trace_cap)
+    torch.cuda.synchronize()
+    return buf, buf.cpu().numpy().view(np.uint32).copy()
+
+
+@pytest.mark.parametrize("mode", [8, 8 | 2, 8 | 4])
+def test_wave_group_granularity(kp, oracle_mod, mode):
+    """One record stream per group of four waves (the Granularity option of Sec. 3.1; Sec. 4.2 splits
+    the buffer by warp group): 8 waves leave 2 streams, each written by the first wave of its group."""
+    n_wg, waves, streams = 128, 8, 2
+    cap = 16 * streams
+    buf, raw = run_calibrate_streams(kp, CYCLES, n_wg, waves, streams, mode, cap)
+    flush = 1 if mode & 2 else 0
+    assert raw[0] == 0x4652504B and tuple(raw[2:8]) == (n_wg, streams, len(CYCLES), 16, 0, flush)
+    st = decode_both(kp, oracle_mod, buf, raw)
+    n_rec = n_wg * streams * 2 * len(CYCLES)
+    assert st["n_slots_valid"] == n_rec and st["n_pairs"] == n_rec // 2 and st["n_invalid"] == 0
+    assert st["n_dropped"] == 0 and st["n_disorder"] == 0 and st["n_nonmonotonic"] == 0
+    assert (st["per"]["n"] == 1).all() and st["per"].shape[:2] == (n_wg, streams)
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert (hdr[:, 8:8 + streams] == 2 * len(CYCLES)).all() and (hdr[:, 8 + streams:24] == 0).all()
+    # the tag's wave field numbers the streams
+    recs = raw[16 + 32 * n_wg:].reshape(n_wg, streams, 16, 2)[:, :, :2 * len(CYCLES)]
+    assert (((recs[..., 0] >> 20) & 0xF) == np.arange(streams)[None, :, None]).all()
+    # the stream measures what a single wave measures: region lengths like those of per-wave records
+    buf1, raw1 = run_calibrate(kp, CYCLES, n_wg, waves, mode & ~8, 16 * waves)
+    st1 = decode_both(kp, oracle_mod, buf1, raw1)
+    d_group = np.median(st["per"]["sum"].astype(np.float64), axis=(0, 1))
+    d_wave = np.median(st1["per"]["sum"].astype(np.float64), axis=(0, 1))
+    # (two kernels and two launches: the clock rate and the code around the sites differ a little)
+    assert np.all(np.abs(d_group[2:] - d_wave[2:]) <= 0.25 * d_wave[2:]), (d_group, d_wave)
+    assert np.all(np.diff(d_group) > 0)
+
+
+def test_wave_group_needs_whole_groups(kp):
+    buf = torch.zeros(kp.kp_trace_bytes(4, 2, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_calibrate(CYCLES, 4, 6, 8, buf, 64)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_calibrate(CYCLES, 4, 8, 16, buf, 64)  # unknown mode bit
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+
+
 def test_calibrate_errors(kp):
     buf = torch.zeros(kp.kp_trace_bytes(4, 4, 64), dtype=torch.uint8, device="cuda")
     for args, code in [((CYCLES, 4, 4, 0, buf, 63), kp.KP_ERR_TRACE_TOO_SMALL),
