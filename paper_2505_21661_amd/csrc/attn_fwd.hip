@@ -349,13 +349,15 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
-  static thread_local bool attr_set = false;
-  if (!attr_set) {
+  static thread_local int attr_dev = -1;  // the attribute is kept per device
+  int dev = 0;
+  KP_HIP_TRY(hipGetDevice(&dev));
+  if (attr_dev != dev) {
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-    attr_set = true;
+    attr_dev = dev;
   }
   // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
   if (!flush && !group_log2 && regions == 7u && S <= (1 << 22))

@@ -95,13 +95,15 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
   a.mode = (uint32_t)(mode & 1);
   // more than half of the CU's LDS per workgroup: one workgroup per CU, one wave per SIMD for waves <= 4
   const uint32_t lds_bytes = 96 * 1024;
-  static thread_local bool attr_set = false;
-  if (!attr_set) {
+  static thread_local int attr_dev = -1;  // the attribute is kept per device
+  int dev = 0;
+  KP_HIP_TRY(hipGetDevice(&dev));
+  if (attr_dev != dev) {
     for (auto k : {kp_calib_kernel<false, false>, kp_calib_kernel<true, false>, kp_calib_kernel<false, true>,
                    kp_calib_kernel<true, true>})
       KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds_bytes));
-    attr_set = true;
+    attr_dev = dev;
   }
   auto kern = group_log2 ? ((mode & 4) ? kp_calib_kernel<true, true> : kp_calib_kernel<false, true>)
                          : ((mode & 4) ? kp_calib_kernel<true, false> : kp_calib_kernel<false, false>);

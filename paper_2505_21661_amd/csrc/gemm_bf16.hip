@@ -385,11 +385,13 @@ bool pick_shape(int M, int N, int K, GemmShape* s) {
 
 template <int INSTR, int WAVES>
 kp_status launch_big(const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
-  static thread_local bool attr_set = false;
-  if (!attr_set) {
+  static thread_local int attr_dev = -1;  // the attribute is kept per device
+  int dev = 0;
+  KP_HIP_TRY(hipGetDevice(&dev));
+  if (attr_dev != dev) {
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-    attr_set = true;
+    attr_dev = dev;
   }
   hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
