@@ -83,6 +83,23 @@ def test_other_geometries(kp, oracle_mod, W, R, cap, total):
     check(raw, oracle_mod)
 
 
+@pytest.mark.parametrize("p0", [0.0, 1.0, 2.0, 3.0, 4.0, 5.0, 6.5, 8.0, 10.0, 12.0, 14.0])
+def test_spans_from_a_few_ticks_to_many_million(kp, oracle_mod, p0):
+    """The overlap sweep bins a workgroup's records into time cells whose width follows the workgroup's
+    span; spans from fewer ticks than cells to 2^27 ticks take every form of that width (and, at the
+    long end, the wide merge keys), and the phase offsets give every workgroup a different span."""
+    for W, cap, seed in ((8, 128, 1), (3, 1024, 2)):
+        spec = inputs.TraceSpec(n_wg=24, waves=W, n_regions=6, cap_wave=cap, total_per_wave=cap, seed=seed + int(10 * p0),
+                                dist="lognormal", p0=p0, p1=0.7, gap_max=1 if p0 < 3 else 32, phase_min=0,
+                                phase_max=int(2 ** min(p0 + 2, 12)) - 1, p_orphan=0.01)
+        raw, _ = inputs.gen_trace(spec)
+        n_wg = int(raw[2])
+        hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32).astype(np.uint64)
+        span = (hdr[:, 4] | (hdr[:, 5] << np.uint64(32))) - (hdr[:, 2] | (hdr[:, 3] << np.uint64(32)))
+        assert span.max() < 2 ** 32
+        check(raw, oracle_mod)
+
+
 def test_empty_trace(kp, oracle_mod):
     check(inputs.encode_trace([], 4, 3, 8), oracle_mod)
 
