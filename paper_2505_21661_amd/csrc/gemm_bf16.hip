@@ -53,7 +53,10 @@ template <int BK>
 __device__ __forceinline__ uint32_t tile_off(uint32_t row, uint32_t chunk) {
   constexpr uint32_t CPR = BK / 8;           // chunks per row
   constexpr uint32_t RPL = 128 / (BK * 2);   // rows per 128-byte bank line (BK <= 64)
-  const uint32_t s = (row / RPL) % CPR;
+  // With 128-byte rows (BK = 64) two neighbouring rows already differ in the upper half of the 16 chunk
+  // positions of a 256-byte bank line, so the XOR takes row bits 1..3: 16 consecutive rows then cover all
+  // 16 positions (with row bits 0..2, rows r and r + 8 shared one, and every operand read took twice as long).
+  const uint32_t s = BK == 64 ? (row >> 1) % CPR : (row / RPL) % CPR;
   return row * (BK * 2) + ((chunk ^ s) * 16);  // byte offset
 }
 
