@@ -207,9 +207,9 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Every thread stages the same share of a K step, so all waves reach the barrier together:
   //   A: 256 rows x 8 chunks of 16 bytes; thread t takes chunk (t & 7) of rows (t >> 3) + (T/8)*i;
-  //   B: blocks of 4 k x 8 n, 16 x 32 of them; a thread takes one block per T/32 k quads (which one: see
-  //      b_nb, b_kq0 below), loads the four rows of each (16 bytes each) and transposes them in registers
-  //      into eight 8-byte k-runs, one per column of the transposed tile.
+  //   B: blocks of 4 k x 8 n, 16 x 32 of them; thread t takes blocks t + T*j (k quad id >> 5, n block
+  //      id & 31), loads the four rows of each (16 bytes each) and transposes them in registers into
+  //      eight 8-byte k-runs, one per column of the transposed tile.
   // 2048/T + 4*(512/T) 16-byte global loads per thread and K step: vector-memory instructions are
   // issued at a fixed rate per CU whatever their width, so wide loads keep the issue time short.
   const uint32_t a_row = tid >> 3, a_chunk = tid & 7u;
@@ -218,13 +218,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < NA; ++i) a_dst[i] = tile_off<BK>(a_row + (T / 8) * i, a_chunk);
   // column c of a block goes to row 8*nb + c of the transposed tile, chunk kq / 2, half kq % 2
-  // The LDS takes 16 lanes of an 8-byte write per cycle, into 32 banks (128 bytes; rows are 128 bytes, so the
-  // row does not matter): lane bits 0..2 give the low bits of the n block, which the swizzle turns into
-  // eight different chunks, and bit 3 the parity of the k quad, i.e. the half of the chunk -- 16 different
-  // 8-byte slots per 16 lanes.  Bits 4, 5 are the upper bits of the n block.
-  const uint32_t b_nb = (tid & 7u) | ((tid & 48u) >> 1);
-  const uint32_t b_kq0 = ((tid >> 6) << 1) | ((tid >> 3) & 1u);
-  const uint16_t* src_b = g.B + (size_t)(b_kq0 * 4) * g.N + n0 + b_nb * 8;
+  const uint32_t b_nb = tid & 31u;
+  const uint16_t* src_b = g.B + (size_t)((tid >> 5) * 4) * g.N + n0 + b_nb * 8;
 
   u32x4 la[NA], lb[NB][4];  // staging registers: A chunks, B rows
   auto load_a = [&](uint32_t kt, int i) {
@@ -239,7 +234,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // word w of the four rows holds columns 2w (low halves) and 2w+1 (high halves)
   auto store_b = [&](uint32_t stage, int j, int w) {
     unsigned char* sB = smem + stage * STAGE + A_BYTES;
-    const uint32_t kq = b_kq0 + (T / 32) * (uint32_t)j;
+    const uint32_t kq = (tid >> 5) + (T / 32) * (uint32_t)j;
     const uint32_t w0 = lb[j][0][w], w1 = lb[j][1][w], w2 = lb[j][2][w], w3 = lb[j][3][w];
     u32x2 ev, od;
     // low halves / high halves of two words side by side: one v_perm_b32 each (bytes 0-3 of the
