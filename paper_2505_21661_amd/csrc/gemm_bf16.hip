@@ -68,9 +68,14 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 
 // END of one region and START of the next with a single clock sample.  INSTR: 0 no record sites,
 // 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
-// SITE is the form of the sites a kernel uses for INSTR (kp::site<>): the large kernel buffers its
-// lean sites in registers, the small one writes them to LDS at the next site.
+// SITE is the form of the sites a kernel uses for INSTR (kp::site<>): the large kernel defers its lean
+// sites and buffers them in registers, the small one writes them to LDS at the next site.
 #define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<SITE>(ring, end_r, start_r); } while (0)
+// The same for a kernel whose lean sites are deferred (SITE 4): the clock read goes into pair K and is
+// turned into records at the next KP_COMMIT, which stands right after a wait for all LDS traffic.
+#define KP_SITE_K(ring, K, end_r, start_r) do { if constexpr (INSTR != 0) { \
+    if constexpr (SITE == 4) kp::site_defer<K>(ring, end_r, start_r); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
+#define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 4) kp::sites_commit<N>(ring); } while (0)
 
 // ------------------------------------------------------------------------------------------
 // 64x64x32 tile, 4 waves as 2x2, each wave one 32x32 accumulator tile.
@@ -170,7 +175,7 @@ constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // bot
 
 template <int INSTR, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
-  constexpr int SITE = INSTR == 2 ? 3 : INSTR;
+  constexpr int SITE = INSTR == 2 ? 4 : INSTR;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
   static_assert(WAVES == 8 || WAVES == 4, "2 x 4 or 2 x 2 waves");
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     for (int ks = 0; ks < BK / 16; ++ks) {
       // ---- region 0: first half of the K step, with the A share of the staging;
       // ---- region 1: second half, with the B share
-      if (ks == BK / 32) KP_BOUNDARY(ring, 0, 1);
+      if (ks == BK / 32) KP_SITE_K(ring, 1, 0, 1);
       const uint32_t chunk = ks * 2 + (lane >> 5);
       bf16x8 af[4], bfr[TN];
 #pragma unroll
@@ -328,14 +333,15 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
         }
       }
     }
-    KP_BOUNDARY(ring, 1, 2);
+    KP_SITE_K(ring, 2, 1, 2);
     // ---- region 2: this wave's LDS writes have landed, every wave is done with the stage ---------
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, 3);
+    KP_COMMIT(ring, 3);  // the site that opened this K step, the one in its middle and the one above
+    if constexpr (MORE) KP_SITE_K(ring, 0, 2, 0); else KP_SITE_K(ring, 0, 2, 3);
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  KP_BOUNDARY(ring, kp::kNoRegion, 0);
+  KP_SITE_K(ring, 0, kp::kNoRegion, 0);
   for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
   if (KT >= 2) iteration(KT - 2, yes, no);
   iteration(KT - 1, no, no);
@@ -357,10 +363,11 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_BOUNDARY(ring, 3, kp::kNoRegion);
+  KP_SITE_K(ring, 1, 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
-    kp::sites_end<SITE>(ring);
+    if constexpr (SITE == 4) kp::deferred_end<2>(ring);  // the sites that opened and closed the epilogue
+    else kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
   }
 }

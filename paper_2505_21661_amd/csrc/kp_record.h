@@ -44,6 +44,8 @@ struct Ring {
   uint32_t slot;       // lean sites only: buffered sites (lanes of vts / vinfo in use)
   uint32_t pend_info;  // lean sites only: packed description of the site whose clock is pend_t
   uint32_t vts, vinfo; // lean sites only, per lane: clock and packed description of a buffered site
+  uint64_t dq_t[3];    // deferred sites only: raw clocks of up to three sites that are not buffered yet
+  uint32_t dq_info[3]; //   and their packed descriptions
   uint64_t t_begin;    // workgroup start: s_memtime
   uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
   // flush strategy only
@@ -268,29 +270,20 @@ __device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint
 // Before ring_finish() in a kernel that used the lean sites: hand the record count back.
 __device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 
-// A second form of the same site, which does not touch LDS at all.
+// A second form of the same site, which does not touch LDS at all: the register buffer.
 // The clock of a site and a packed description of its one or two records
-// go into lane `slot` of two VGPRs (v_writelane from SGPRs), and only every 64th site -- and the end
-// of the kernel -- turns the 64 buffered sites into records, each lane writing its own site's
-// records to the LDS sub-ring.  A site is then about a dozen instructions, two of them vector ones,
-// at the price of two VGPRs and a (rarely taken) branch per site.  Measured on the 4096^3 GEMM it
-// lowers the overhead from 4.4 % to 3.4 %; in the attention kernel, which has no VGPR to spare,
-// it raises it from 7.8 % to 10.2 %, so that kernel keeps the form above.
+// go into lane `slot` of two VGPRs (v_writelane from SGPRs), and only when the 64 lanes are used up
+// -- and at the end of the kernel -- the buffered sites become records, each lane writing its own
+// site's records to the LDS sub-ring.  Buffering a site is about a dozen instructions, two of them
+// vector ones, at the price of two VGPRs and a (rarely taken) branch.  Measured on the 4096^3 GEMM,
+// with every site buffered at the next site, it lowered the overhead from 4.4 % to 3.4 %; in the
+// attention kernel, which has no VGPR to spare, it raised it from 7.8 % to 10.2 %, so that kernel keeps
+// the form above.  The sites that use the buffer today are the deferred ones further down.
 //
 // Packed description: bits 15:0 low half of the running counter (tag_wave + sequence number) of the
 // site's first record, bits 23:16 tag byte (phase << 7 | region) of the first record, bits 31:24
 // tag byte of the second record, 0xFF where there is none.  The host only selects these sites when a
 // wave writes fewer than 2^20 records, so the counter never carries into the wave field.
-constexpr uint32_t kSiteNone = 0xFFFF0000u;
-
-__device__ __forceinline__ void buffered_begin(Ring& r) {
-  r.cw = r.tag_wave;
-  r.slot = 0u;
-  r.vts = 0u;
-  r.vinfo = 0u;
-  r.pend_info = kSiteNone;  // the first site retires this placeholder: no record
-  r.pend_t = r.t_begin;
-}
 
 // Turn the buffered sites (lanes below r.slot) into records of the LDS sub-ring.  Newest wins: a
 // record is left out when a later record of the same batch takes its slot (sub-rings shorter than a
@@ -333,26 +326,58 @@ __device__ __forceinline__ void buffer_pending_site(Ring& r) {
   r.slot += 1u;
 }
 
-__device__ __forceinline__ void boundary_buffered(Ring& r, uint32_t end_region, uint32_t start_region) {
+// A third form, for kernels that wait for all their LDS traffic at a barrier anyway.  Whoever uses a
+// clock value has to wait for everything counted in lgkmcnt, LDS reads and writes in flight included
+// (scalar-memory results come back out of order), and in the middle of a pipelined loop that wait
+// drains the LDS queue.  Here a site only issues the clock read into one of three scalar register pairs
+// (K, a compile-time index) and notes its description; sites_commit<N>(), placed right after the
+// kernel's own "s_waitcnt lgkmcnt(0); s_barrier", moves sites 0..N-1 into the register buffer in that
+// order.  The kernel must commit a pair before it issues into it again.  Measured on the 4096^3 GEMM
+// (three sites per K step, one barrier) the instrumented kernel goes from 144.7 to 142.0 us, the
+// overhead from 6.7 % to 4.1 %; the attention kernel, whose sites do not sit in the middle of pipelined
+// LDS traffic, gains nothing from it and spills two registers, so it keeps the second form.
+template <int K>
+__device__ __forceinline__ void site_defer(Ring& r, uint32_t end_region, uint32_t start_region) {
+  static_assert(K >= 0 && K < 3, "three deferred sites at most");
   __builtin_amdgcn_sched_barrier(0);
-  buffer_pending_site(r);
-  if (r.slot == 64u) flush_sites(r);  // uniform
-  r.pend_t = sample_clock();
+  r.dq_t[K] = sample_clock();
   if (end_region != kNoRegion && start_region != kNoRegion) {
-    r.pend_info = (r.cw & 0xFFFFu) | ((0x80u | end_region) << 16) | (start_region << 24);
+    r.dq_info[K] = (r.cw & 0xFFFFu) | ((0x80u | end_region) << 16) | (start_region << 24);
     r.cw += 2u;
   } else {
     const uint32_t b = end_region != kNoRegion ? (0x80u | end_region) : start_region;
-    r.pend_info = (r.cw & 0xFFFFu) | (b << 16) | (0xFFu << 24);
+    r.dq_info[K] = (r.cw & 0xFFFFu) | (b << 16) | (0xFFu << 24);
     r.cw += 1u;
   }
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// Before ring_finish() in a kernel that used the lean sites: retire the last site, write out what
-// the registers still hold and hand the record count back.
-__device__ __forceinline__ void buffered_end(Ring& r) {
-  buffer_pending_site(r);
+template <int N>
+__device__ __forceinline__ void sites_commit(Ring& r) {
+  static_assert(N >= 0 && N <= 3, "three deferred sites at most");
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    r.pend_t = r.dq_t[k];
+    r.pend_info = r.dq_info[k];
+    buffer_pending_site(r);
+  }
+  if (r.slot > 61u) flush_sites(r);  // uniform; the next commit brings up to three sites
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ void deferred_begin(Ring& r) {
+  r.cw = r.tag_wave;
+  r.slot = 0u;
+  r.vts = 0u;
+  r.vinfo = 0u;
+}
+
+// Before ring_finish(): commit the N sites still in flight, write out the register buffer and hand
+// the record count back.
+template <int N>
+__device__ __forceinline__ void deferred_end(Ring& r) {
+  sites_commit<N>(r);
   flush_sites(r);
   r.cnt = r.cw - r.tag_wave;
   r.stored = r.cnt;
@@ -361,22 +386,23 @@ __device__ __forceinline__ void buffered_end(Ring& r) {
 }
 
 // MODE 1: generic (region mask, either strategy); MODE 2: every region enabled, circular strategy,
-// records written to LDS at the next site; MODE 3: the same, sites buffered in registers.
+// records written to LDS at the next site; MODE 4: the same, deferred sites buffered in registers (the
+// kernel calls site_defer / sites_commit / deferred_end itself).
 template <int MODE>
 __device__ __forceinline__ void site(Ring& r, uint32_t end_region, uint32_t start_region) {
-  if constexpr (MODE == 3) boundary_buffered(r, end_region, start_region);
-  else if constexpr (MODE == 2) boundary_fast(r, end_region, start_region);
+  static_assert(MODE == 1 || MODE == 2, "deferred sites are placed with site_defer<K>()");
+  if constexpr (MODE == 2) boundary_fast(r, end_region, start_region);
   else boundary(r, end_region, start_region);
 }
 template <int MODE>
 __device__ __forceinline__ void sites_begin(Ring& r) {
-  if constexpr (MODE == 3) buffered_begin(r);
+  if constexpr (MODE == 4) deferred_begin(r);
   else if constexpr (MODE == 2) lean_begin(r);
 }
 template <int MODE>
 __device__ __forceinline__ void sites_end(Ring& r) {
-  if constexpr (MODE == 3) buffered_end(r);
-  else if constexpr (MODE == 2) lean_end(r);
+  static_assert(MODE != 4, "deferred sites end with deferred_end<N>()");
+  if constexpr (MODE == 2) lean_end(r);
 }
 
 template <bool REALTIME = false>

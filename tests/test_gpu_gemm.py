@@ -192,7 +192,7 @@ def test_big_tile_trace_small_k(kp, oracle_mod):
 
 @pytest.mark.parametrize("cap_wave", [2, 16, 64, 256])
 def test_big_tile_lean_sites_with_short_rings(kp, oracle_mod, cap_wave):
-    """The large kernel keeps its record sites in registers and turns 64 of them into records at a time.
+    """The large kernel keeps its record sites in registers and turns up to 63 of them into records at a time.
     Rings shorter than such a batch (newest record wins inside the batch), rings that wrap across
     batches and a ring that holds everything must all decode like the oracle says, with the drop
     count of the closed form."""
