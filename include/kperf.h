@@ -278,7 +278,9 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  *   M, N multiples of 256 with at least 16 tiles, K a multiple of 64: tile 256x256x64, 8 waves,
  *       per K-step, in this order: 0 first half of the MFMA steps, with the A share of the next
  *       K-step's staging (registers -> other LDS stage, refill from global memory) threaded between
- *       them, 1 second half with the B share, 2 wait (LDS writes landed + barrier); 3 epilogue, once
+ *       them, 1 second half with the B share, 2 wait (LDS writes landed + barrier; with every region
+ *       enabled and the circular strategy also the ~30 instructions that turn the K-step's three clock
+ *       samples into records); 3 epilogue, once
  *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
  *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
  * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.
