@@ -149,6 +149,18 @@ kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr
                               void* out_stats, void* stream);
 
 /*
+ * Timing aid for the decoder: kp_trace_reduce_hdr cut short.  Every recorded workgroup leaves the
+ * kernel after step `last_step` of the replay (Sec. 4.3): 1 records ordered by sequence number,
+ * 2 paired, durations and histogram accumulated; then the paired records of all waves are sorted
+ * by clock: 3 counted into time cells, 4 prefix sum over the cells, 5 placed by cell, 6 ranked
+ * inside their cell, 7 sorted sequence written; 8 region-pair overlap swept.  The differences
+ * between the run times of consecutive steps are the cost of each step.  out_stats is written but
+ * its contents are unspecified.
+ */
+kp_status kp_trace_reduce_steps(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                                void* out_stats, int last_step, void* stream);
+
+/*
  * Timeline rows of the same replay.  The paper decodes the profile buffer into one activity
  * struct per timed region instance for timeline front ends such as Chrome Trace (Sec. 3.2) and
  * associates loop iterations with the records (Sec. 3.3 "Iteration-based Timing").  One row per

@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.kp_trace_reduce.argtypes = [vp, sz, vp, vp]
         L.kp_trace_reduce_hdr.restype = ci
         L.kp_trace_reduce_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
+        L.kp_trace_reduce_steps.restype = ci
+        L.kp_trace_reduce_steps.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, ci, vp]
         L.kp_pairs_bytes.restype = sz
         L.kp_pairs_bytes.argtypes = [ci, ci, ci]
         L.kp_trace_pairs.restype = ci
@@ -160,6 +162,11 @@ def make_hdr(n_wg: int, waves_per_wg: int, n_regions: int, cap_wave: int, rec_co
 
 def kp_trace_reduce_hdr(raw, n: int, hdr_host: kp_trace_hdr, out_stats, stream=None) -> None:
     _check(lib().kp_trace_reduce_hdr(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_stats), _stream(stream)))
+
+
+def kp_trace_reduce_steps(raw, n: int, hdr_host: kp_trace_hdr, out_stats, last_step: int, stream=None) -> None:
+    _check(lib().kp_trace_reduce_steps(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_stats), last_step,
+                                       _stream(stream)))
 
 
 def kp_pairs_bytes(n_wg: int, waves_per_wg: int, cap_per_wg: int) -> int:

@@ -2,23 +2,30 @@
 //
 // The paper stores START/END records unpaired, per warp, in a ring whose tail survives, and
 // aligns them at "trace replay" on the host (Sec. 4.2 "SM-level Data Layout", "Shared Memory
-// Circular Buffer"; Sec. 4.3).  Here replay runs on the GPU: one decoder workgroup stages one
-// recorded workgroup's records in LDS as (clock, metadata) pairs and
-//   A  scatters every record to its rank (seq - first surviving seq), which undoes ring
-//      rotation and out-of-order flushes in O(1) per record,
-//   B  pairs each START with the next record of the same (wave, region) when that is an END,
-//      takes d = (u32)(ts_end - ts_start) minus the constant record cost (Sec. 4.3), and
-//      accumulates the per-(wave, region) sums and the log2 histogram with LDS atomics; the
-//      four ranks an END looks back at come from neighbouring lanes, not from LDS,
-//   C  XOR-scans the paired region bits of each wave into an "open regions" mask per position,
-//   D  builds a coarse time -> position table per wave and orders the time cells by how many
-//      records they hold, so that the lanes of a wave get cells of similar length,
-//   E  sweeps every time cell in clock order, one lane per cell, keeping a bit-sliced count of
-//      the waves that have each region open; when a record switches its region on or off for
-//      the whole workgroup, -t / +t goes to the region-pair accumulators (the integral of
-//      A_a(t)*A_b(t) collapses to a signed sum over its switching times),
-//   F  writes the per-(workgroup, wave, region) results and folds them into running totals.
-// Decoder workgroups are persistent; totals live in LDS and reach HBM once per workgroup.
+// Circular Buffer"; Sec. 4.3).  Here replay runs on the GPU: one persistent decoder workgroup
+// takes one recorded workgroup at a time and keeps it in LDS as a clock word and a metadata byte
+// per record.
+//   A  every record is scattered to its rank (seq - first surviving seq), which undoes ring
+//      rotation and out-of-order flushes in O(1) per record;
+//   B  a lane takes the records of 16 rounds of 64 consecutive ranks; an END is paired iff the
+//      nearest earlier record of its (wave, region) is a START -- usually the rank just below,
+//      which comes from the lane below (DPP); d = (u32)(ts_end - ts_start) minus the constant
+//      record cost (Sec. 4.3) goes to the per-(wave, region) sums and the log2 histogram with
+//      LDS atomics;
+//   C  the paired records of all waves are sorted by clock: counting sort into time cells (one
+//      LDS atomic per record gives cell and arrival slot), a prefix sum over the cells, and the
+//      rank among the few records of the same cell by comparing clocks;
+//   D  every lane sweeps 16 consecutive records of the sorted sequence.  The number of waves that
+//      have each region open is kept bit-sliced (plane k = bit k of every region's count); a first
+//      pass gives each lane's net change, a prefix sum over lanes and waves the state at the start
+//      of each lane's stretch, and in the second pass a record that takes its region's count from
+//      0 to 1 or from 1 to 0 adds -t / +t to the region-pair accumulators of all regions active
+//      at that instant (the integral of A_a(t)*A_b(t) collapses to a signed sum over its
+//      switching times);
+//   E  the per-(workgroup, wave, region) results go to HBM and into running totals, which live in
+//      LDS and reach HBM once per decoder workgroup.
+// A workgroup with a corrupt record (bad field, duplicated seq) has holes in its ranks; it is rare,
+// takes no part in the overlap statistics and is paired by a plain serial walk per (wave, region).
 #include "kp_common.h"
 
 namespace {
@@ -26,7 +33,10 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kSeqMask = 0xFFFFFu;
-constexpr uint32_t kMRegion = 0x1Fu, kMEnd = 0x20u, kMValid = 0x40u, kMPaired = 0x80u;
+// staged metadata byte: bits 5:0 region (63 = no record), 6 paired, 7 END
+constexpr uint32_t kRegion = 0x3Fu, kEmpty = 0x3Fu, kPaired = 0x40u, kEnd = 0x80u;
+constexpr int kNR = 16;                       // positions per lane
+constexpr uint32_t kWaveSpan = 64 * kNR;      // positions per hardware wave
 constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
 constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bins of different regions, different banks
@@ -35,9 +45,12 @@ constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bi
 enum { H_SLOTS_VALID = 0, H_PAIRS, H_ORPHAN_START, H_ORPHAN_END, H_INVALID, H_DROPPED, H_DISORDER,
        H_SPAN_OVF, H_NONMONO, H_OVERLAP_WGS, H_STATUS, H_NWG, H_WAVES, H_NREG, H_CAP, H_RSVD };
 
+// steps after which kp_trace_reduce_steps can leave a workgroup
+enum { kStepOrdered = 1, kStepPaired, kStepCounted, kStepCellSums, kStepPlaced, kStepRanked, kStepSorted, kStepSwept };
+
 // per-workgroup temporaries (u32 words in LDS)
-enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_ORPH_S, T_ORPH_E,
-       T_WIDE, T_COUNT };
+enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_STARTS, T_ENDS,
+       T_EVENTS, T_MARKS, T_COUNT };
 
 struct StatsLayout {  // offsets in u64 words
   size_t hist, cnt, sum, min, max, U, O, F, per, total;
@@ -59,67 +72,94 @@ struct DecodeParams {
   const u32x4* records;     // two records per 16-byte load
   uint64_t* out;
   uint32_t n_wg, W, R, cap, cap_log2, rec_cost, flush;
-  uint32_t nrec, span, span_log2, ncell, pos_bits;
+  uint32_t nrec;            // record slots per recorded workgroup
+  uint32_t ncopy;           // copies of the per-(wave, region) sums: 1, 2 or 4
+  uint32_t stop_after;      // 0: everything; else leave each workgroup after this step (timing only), see kStep*
 };
 
 struct LdsLayout {  // byte offsets
-  uint32_t rec, grid, perm, cinfo, bucket, hist, oacc, oacc32, reg_sum, reg_max, reg_min, pw_pack, pw_max,
-      pw_min, ctr, tmp, misc, v, first, wave_tot, total;
+  uint32_t clk, meta, cells, hist, oacc, oacc32, reg_sum, reg_max, reg_min, pw_pack, pw_max, pw_min, ctr, tmp,
+      misc, vf, wtot, ptot, total;
 };
 __host__ __device__ inline uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
-__host__ __device__ inline LdsLayout lds_layout(uint32_t nrec, uint32_t W, uint32_t R, uint32_t ncell, uint32_t block) {
+__host__ __device__ inline LdsLayout lds_layout(uint32_t block, uint32_t W, uint32_t R, uint32_t ncopy) {
   LdsLayout l;
+  const uint32_t npos = block * kNR;
   uint32_t o = 0;
-  l.rec = o; o = align16(o + (nrec + 1) * 8);          // one zero entry past the last position
-  l.grid = o; o = align16(o + W * (ncell + 1) * 2);    // one entry past the last cell per wave
-  l.perm = o; o = align16(o + ncell * 2);
-  l.cinfo = o; o = align16(o + ncell * 2);
-  l.bucket = o; o = align16(o + 64 * 4);
+  l.clk = o; o = align16(o + (npos + npos / 16) * 4);  // 4 words of padding after every 64
+  l.meta = o; o = align16(o + npos + 16);
+  l.cells = o; o = align16(o + (npos / 2 + 4) * 4);    // one 16-bit counter per time cell, npos cells, + the total
   l.hist = o; o = align16(o + R * kHistStride * 4);
   l.oacc = o; o = align16(o + R * R * 8);
   l.oacc32 = o; o = align16(o + R * (R | 1u) * 4);
   l.reg_sum = o; o = align16(o + R * 8);
   l.reg_max = o; o = align16(o + R * 4);
   l.reg_min = o; o = align16(o + R * 4);
-  l.pw_pack = o; o = align16(o + W * R * 8);
-  l.pw_max = o; o = align16(o + W * R * 4);
-  l.pw_min = o; o = align16(o + W * R * 4);
+  l.pw_pack = o; o = align16(o + ncopy * W * R * 8);
+  l.pw_max = o; o = align16(o + ncopy * W * R * 4);
+  l.pw_min = o; o = align16(o + ncopy * W * R * 4);
   l.ctr = o; o = align16(o + 16 * 8);
   l.tmp = o; o = align16(o + T_COUNT * 4);
-  l.misc = o; o = align16(o + 8 * 4);
-  l.v = o; o = align16(o + 16 * 4);
-  l.first = o; o = align16(o + 16 * 4);
-  l.wave_tot = o; o = align16(o + (block / 64) * 4);
+  l.misc = o; o = align16(o + 4 * 4);
+  l.vf = o; o = align16(o + 16 * 8);
+  l.wtot = o; o = align16(o + 16 * 4);
+  l.ptot = o; o = align16(o + 16 * 8 * 4);
   l.total = o;
   return l;
 }
 
-__device__ inline uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-  return v;
-}
-
-__device__ inline void add_tmp(uint32_t* tmp, int which, uint32_t v) {
-  v = wave_sum(v);
-  if ((threadIdx.x & 63) == 0 && v) atomicAdd(&tmp[which], v);
-}
+// Word of the clock array that holds position i: 4 words of padding after every 64, so that the
+// 64 lanes of a wave reading 16 consecutive words each (64 bytes apart) spread over all banks.
+__device__ __forceinline__ uint32_t clk_word(uint32_t i) { return i + ((i >> 6) << 2); }
 
 // Lane l receives the value of lane l-1; lane 0 receives `lane0` (DPP wave shift right by one).
 __device__ __forceinline__ uint32_t wave_shr1(uint32_t v, uint32_t lane0) {
   return (uint32_t)__builtin_amdgcn_update_dpp((int)lane0, (int)v, 0x138, 0xF, 0xF, false);
 }
 
-// Inclusive XOR scan over the 64 lanes: four shifts inside each row of 16, then the last lane of
-// row 0/2 into row 1/3 and the last lane of the lower half into the upper half.
-__device__ __forceinline__ uint32_t wave_xor_scan(uint32_t v) {
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);  // row_shr:1
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);  // row_shr:2
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
-  v ^= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
+// The DPP steps of an inclusive scan over the 64 lanes: four shifts inside each row of 16, then the
+// last lane of row 0/2 into row 1/3 and the last lane of the lower half into the upper half.  Lanes
+// without a source read 0.
+template <int STEP> __device__ __forceinline__ uint32_t scan_src(uint32_t v) {
+  if (STEP == 0) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  if (STEP == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  if (STEP == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  if (STEP == 3) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  if (STEP == 4) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);                 // row_bcast:31
+}
+
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t v) {
+  v += scan_src<0>(v); v += scan_src<1>(v); v += scan_src<2>(v);
+  v += scan_src<3>(v); v += scan_src<4>(v); v += scan_src<5>(v);
   return v;
+}
+
+// Sum over the wave, added to tmp[which] by the last lane.
+__device__ __forceinline__ void add_tmp(uint32_t* tmp, int which, uint32_t v) {
+  v = wave_scan_add(v);
+  if ((threadIdx.x & 63u) == 63u && v) atomicAdd(&tmp[which], v);
+}
+
+// a += b for bit-sliced numbers: plane k holds bit k of 32 independent counters, modulo 2^PLANES.
+template <int PLANES>
+__device__ __forceinline__ void planes_add(uint32_t (&a)[PLANES], const uint32_t (&b)[PLANES]) {
+  uint32_t c = 0;
+#pragma unroll
+  for (int k = 0; k < PLANES; ++k) {
+    const uint32_t s = a[k] ^ b[k];
+    const uint32_t g = a[k] & b[k];
+    a[k] = s ^ c;
+    c = g | (s & c);
+  }
+}
+
+// counter[bit of x] += 1 (dm = 0) or -= 1 (dm = all ones); x is zero or one-hot.
+template <int PLANES>
+__device__ __forceinline__ void planes_step(uint32_t (&pl)[PLANES], uint32_t x, uint32_t dm) {
+  uint32_t carry = x;
+#pragma unroll
+  for (int k = 0; k < PLANES; ++k) { const uint32_t o = pl[k]; pl[k] = o ^ carry; carry &= o ^ dm; }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -164,123 +204,16 @@ __global__ void kp_reduce_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uin
 }
 
 // ------------------------------------------------------------------------------------------
-// Overlap sweep.  One lane owns one time cell and merges the W per-wave record runs that fall
-// into it in the total order (clock, wave, rank).  The number of waves that have each region open
-// is kept bit-sliced: plane k holds bit k of every region's count, so "some wave has it open" is
-// the OR of the planes and one record costs a ripple of PLANES steps.  When a paired record takes
-// its region's count from 0 to 1 or from 1 to 0, -t or +t goes to the region-pair accumulators of
-// all regions active at that instant.
-//
-// A merge key is (clock, position).  The narrow form keeps the clock relative to the start of the
-// cell above `pos_bits` bits of position in one 32-bit word; it needs every clock of the cell to
-// be below the cell's end and cell width * positions to fit 32 bits.  The wide form is 64 bits.
-template <typename KeyT> struct SweepKey;
-template <> struct SweepKey<uint32_t> {
-  static __device__ __forceinline__ uint32_t make(uint32_t t, uint32_t pos, uint32_t cbase, uint32_t pb) { return ((t - cbase) << pb) | pos; }
-  static __device__ __forceinline__ uint32_t pos(uint32_t k, uint32_t pmask) { return k & pmask; }
-  static __device__ __forceinline__ uint32_t clock(uint32_t k, uint32_t cbase, uint32_t pb) { return cbase + (k >> pb); }
-};
-template <> struct SweepKey<unsigned long long> {
-  static __device__ __forceinline__ unsigned long long make(uint32_t t, uint32_t pos, uint32_t, uint32_t) { return ((unsigned long long)t << 32) | pos; }
-  static __device__ __forceinline__ uint32_t pos(unsigned long long k, uint32_t) { return (uint32_t)k; }
-  static __device__ __forceinline__ uint32_t clock(unsigned long long k, uint32_t, uint32_t) { return (uint32_t)(k >> 32); }
-};
-
-template <int WMAX, int PLANES, typename KeyT>
-__device__ __forceinline__ void sweep_cells(const uint2* rec, const uint16_t* grid, const uint16_t* perm,
-                                            uint32_t* oacc32, uint32_t W, uint32_t R, uint32_t cl2,
-                                            uint32_t pb, uint32_t ncell, uint32_t cw, uint32_t tid,
-                                            uint32_t nthreads) {
-  typedef SweepKey<KeyT> K;
-  const KeyT none = ~(KeyT)0;
-  const uint32_t capm = (1u << cl2) - 1u, pmask = (1u << pb) - 1u, gstride = ncell + 1;
-  for (uint32_t i = tid; i < ncell; i += nthreads) {
-    const uint32_t c = perm[i];
-    const uint32_t cbase = c * cw;
-    KeyT key[WMAX];        // each wave's next record in this cell; all-ones = none
-    uint32_t pl[PLANES];   // bit-sliced count of the waves that have each region open
-#pragma unroll
-    for (int k = 0; k < PLANES; ++k) pl[k] = 0u;
-    uint32_t n = 0;
-#pragma unroll
-    for (int w = 0; w < WMAX; ++w) {
-      key[w] = none;
-      if ((uint32_t)w < W) {
-        const uint32_t g0 = grid[w * gstride + c], g1 = grid[w * gstride + c + 1];
-        const uint32_t pos = ((uint32_t)w << cl2) + g0;
-        const uint2 r = rec[pos];  // metadata = regions this wave has open before rank g0
-        uint32_t carry = r.y;
-#pragma unroll
-        for (int k = 0; k < PLANES; ++k) { const uint32_t t = pl[k] & carry; pl[k] ^= carry; carry = t; }
-        key[w] = g0 < g1 ? K::make(r.x, pos, cbase, pb) : none;
-        n += g1 - g0;
-      }
-    }
-    for (; n; --n) {
-      KeyT best = key[0];
-#pragma unroll
-      for (int w = 1; w < WMAX; ++w) best = key[w] < best ? key[w] : best;
-      const uint32_t pos = K::pos(best, pmask), tt = K::clock(best, cbase, pb);
-      const uint32_t b = pos >> cl2;
-      const uint32_t g1 = grid[b * gstride + c + 1];
-      const uint2 cur = rec[pos];
-      uint2 nxt = rec[pos + 1];
-      asm volatile("" : "+v"(nxt.x));  // fetch the next clock with the masks, not behind the test below
-      const bool more = (pos & capm) + 1u < g1;
-      const KeyT nkey = more ? K::make(nxt.x, pos + 1u, cbase, pb) : none;
-#pragma unroll
-      for (int w = 0; w < WMAX; ++w) key[w] = key[w] == best ? nkey : key[w];
-      const uint32_t x = cur.y ^ nxt.y;  // the region bit this record toggles; 0 if unpaired
-      const bool is_end = (cur.y & x) != 0u;
-      uint32_t act_before = pl[0];
-#pragma unroll
-      for (int k = 1; k < PLANES; ++k) act_before |= pl[k];
-      {  // count[region] += 1 (START) or -= 1 (END)
-        const uint32_t dm = is_end ? 0xFFFFFFFFu : 0u;
-        uint32_t carry = x;
-#pragma unroll
-        for (int k = 0; k < PLANES; ++k) { const uint32_t o = pl[k]; pl[k] = o ^ carry; carry &= o ^ dm; }
-      }
-      uint32_t act_after = pl[0];
-#pragma unroll
-      for (int k = 1; k < PLANES; ++k) act_after |= pl[k];
-      const uint32_t act = is_end ? act_after : act_before;  // active regions other than this one
-      if (x & ~act) {  // the region was off before this START / is off after this END
-        // modulo 2^32: the totals of one workgroup lie below its span, which is below 2^32
-        uint32_t* row = oacc32 + (__ffs(x) - 1) * (R | 1u);
-        const uint32_t val = is_end ? tt : 0u - tt;
-        atomicAdd(&row[__ffs(x) - 1], val);
-        uint32_t set = act;
-        while (set) {
-          const uint32_t bb = __ffs(set) - 1;
-          set &= set - 1;
-          atomicAdd(&row[bb], val);
-        }
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// Position p = wave*cap_wave + rank indexes the staged records.  Every hardware wave of the
-// decoder owns `span` consecutive positions and walks them 64 at a time, lane l taking position
-// base + 64*round + l, so that neighbouring lanes hold neighbouring ranks.
-//
-// Staged metadata word: bits 4:0 region, 5 END, 6 valid, 7 paired, 31:16 generation.  With at
-// most 16 regions the staging area is not cleared between workgroups: a word counts only when
-// its generation is the current one (the open-region masks that phase C leaves behind have
-// generation 0, which is never current).  With more regions the masks reach into those bits, so
-// the area is cleared for every workgroup and the generation stays 0.
-template <int BLOCK>
+// Position p = wave*cap_wave + rank indexes the staged records.  Hardware wave h of the decoder
+// owns positions [h*1024, h*1024 + 1024) and lane l takes position h*1024 + 64*j + l in round j,
+// so that neighbouring lanes hold neighbouring ranks.
+template <int BLOCK, int PLANES>
 __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const LdsLayout L = lds_layout(p.nrec, p.W, p.R, p.ncell, BLOCK);
-  uint2* rec = reinterpret_cast<uint2*>(smem + L.rec);
-  uint32_t* recw = reinterpret_cast<uint32_t*>(smem + L.rec);  // word 2p = clock, 2p+1 = metadata
-  uint16_t* grid = reinterpret_cast<uint16_t*>(smem + L.grid);
-  uint16_t* perm = reinterpret_cast<uint16_t*>(smem + L.perm);
-  uint16_t* cinfo = reinterpret_cast<uint16_t*>(smem + L.cinfo);
-  uint32_t* bucket = reinterpret_cast<uint32_t*>(smem + L.bucket);
+  const LdsLayout L = lds_layout(BLOCK, p.W, p.R, p.ncopy);
+  uint32_t* clk = reinterpret_cast<uint32_t*>(smem + L.clk);
+  uint8_t* meta = smem + L.meta;
+  uint32_t* cells = reinterpret_cast<uint32_t*>(smem + L.cells);  // cell c: half (c & 1) of word c >> 1
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
   unsigned long long* oacc = reinterpret_cast<unsigned long long*>(smem + L.oacc);
   uint32_t* oacc32 = reinterpret_cast<uint32_t*>(smem + L.oacc32);  // this workgroup's sums modulo 2^32
@@ -292,109 +225,112 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L.pw_min);
   unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L.ctr);
   uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
-  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] log2 of the power-of-two cell width, [2..4] cell width q << sh and 2^16 / q
-  uint32_t* sV = reinterpret_cast<uint32_t*>(smem + L.v);
-  uint32_t* sFirst = reinterpret_cast<uint32_t*>(smem + L.first);
-  uint32_t* wave_tot = reinterpret_cast<uint32_t*>(smem + L.wave_tot);
+  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell scale
+  uint2* sVF = reinterpret_cast<uint2*>(smem + L.vf);           // per wave: records held, first surviving seq
+  uint32_t* wtot = reinterpret_cast<uint32_t*>(smem + L.wtot);
+  uint32_t* ptot = reinterpret_cast<uint32_t*>(smem + L.ptot);
 
-  const uint32_t tid = threadIdx.x, lane = tid & 63u, hw = tid >> 6;
-  const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec, ncell = p.ncell;
-  const uint32_t capm = cap - 1, cl2 = p.cap_log2, gstride = ncell + 1;
-  const uint32_t span = p.span;              // positions per hardware wave, power of two >= 64
-  const uint32_t pbase = hw * span;
-  const uint32_t pend = pbase + span < nrec ? pbase + span : nrec;  // may be <= pbase: idle wave
+  constexpr uint32_t NPOS = BLOCK * kNR, NCELL = NPOS;
+  // The last four words of the clock array are padding that no position maps to, and the metadata
+  // array has 16 spare bytes: stores of lanes that have nothing to store go there instead of branching.
+  constexpr uint32_t kSpareWord = NPOS + NPOS / 16 - 1;
+  const uint32_t tid_k = threadIdx.x;
+  const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec;
+  const uint32_t capm = cap - 1, cl2 = p.cap_log2;
   const StatsLayout SL = stats_layout(p.n_wg, W, R);
   if (p.out[H_STATUS] != 0) return;  // device header did not match the launch geometry
 
-  for (uint32_t i = tid; i < R * kHistStride; i += BLOCK) hist[i] = 0;
-  for (uint32_t i = tid; i < R * R; i += BLOCK) oacc[i] = 0;
-  for (uint32_t i = tid; i < R * (R | 1u); i += BLOCK) oacc32[i] = 0;
-  for (uint32_t i = tid; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
-  for (uint32_t i = tid; i < W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
-  if (tid < 16) ctr[tid] = 0;
-  if (tid == 0) rec[nrec] = make_uint2(0u, 0u);
+  for (uint32_t i = tid_k; i < R * kHistStride; i += BLOCK) hist[i] = 0;
+  for (uint32_t i = tid_k; i < R * R; i += BLOCK) oacc[i] = 0;
+  for (uint32_t i = tid_k; i < R * (R | 1u); i += BLOCK) oacc32[i] = 0;
+  for (uint32_t i = tid_k; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
+  for (uint32_t i = tid_k; i < p.ncopy * W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
+  if (tid_k < 16) ctr[tid_k] = 0;
   __syncthreads();
 
-  uint32_t iter = 0;
-  for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x, ++iter) {
+  for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
+    // A fresh copy of the thread index per workgroup that the optimiser cannot see through: without it
+    // the address arithmetic of all 16 rounds is computed once before the loop and held in registers
+    // for the whole kernel.
+    uint32_t tid = tid_k;
+    asm volatile("" : "+v"(tid));
+    const uint32_t lane = tid & 63u, hw = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const uint32_t pbase = hw * kWaveSpan;
+    const uint32_t qe = pbase + 2u * lane;     // even position of round 0; round j: qe + 128 j
+    // its clock word; round j: cwe + 136 j (pbase is a multiple of 1024, lanes 32.. are past one padding)
+    const uint32_t cwe = qe + (pbase >> 4) + ((lane >> 5) << 2);
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
-    const uint32_t gen = R > 16 ? 0u : 1u + iter % 0xFFFFu;
-    const uint32_t live_tag = (gen << 16) | kMValid, live_mask = 0xFFFF0000u | kMValid;
-    auto is_live = [&](uint32_t m) { return (m & live_mask) == live_tag; };
-    // ---- workgroup header -----------------------------------------------------------------
+    // ---- workgroup header, clear the staging state -----------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
       const uint32_t V = T < cap ? T : cap;
-      sV[tid] = V;
-      sFirst[tid] = p.flush ? 0u : T - V;
+      sVF[tid] = make_uint2(V, p.flush ? 0u : T - V);
       atomicAdd(&ctr[H_DROPPED], (unsigned long long)(T - V));
       atomicAdd(&ctr[H_SLOTS_VALID], (unsigned long long)V);
     }
-    if (tid >= 64 && tid < 64 + T_COUNT) tmp[tid - 64] = 0;
-    if (tid >= 128 && tid < 128 + BLOCK / 64) wave_tot[tid - 128] = 0;
-    if (tid >= 192 && tid < 256) bucket[tid - 192] = 0;
+    if (tid >= 64 - T_COUNT && tid < 64) tmp[tid - (64 - T_COUNT)] = 0;
     if (tid == 32) {
       const uint64_t tb = (uint64_t)wh[2] | ((uint64_t)wh[3] << 32);
       const uint64_t te = (uint64_t)wh[4] | ((uint64_t)wh[5] << 32);
       const uint64_t sp = te - tb;
-      uint32_t shift = 0, ovf = 0;
-      if (sp >> 32) ovf = 1; else while ((sp >> shift) >= ncell) ++shift;
-      // Cell width q << sh: the narrowest of {5, 6, 7, 8} << (shift - 3) with which ncell cells still
-      // cover the span, so that at least four cells in five are in use (a power of two alone may
-      // leave half of them empty, and fuller cells make the sweep's longest lane longer).
-      uint32_t q = 1u << shift, sh = 0;
-      if (!ovf && shift >= 3) {
-        sh = shift - 3; q = 8;
-        for (uint32_t qq = 5; qq < 8; ++qq)
-          if ((uint32_t)(sp >> sh) < ncell * qq) { q = qq; break; }
-        if (q == 8) { q = 4; sh = shift - 2; }
-      }
-      misc[0] = ovf;
-      misc[1] = shift;
-      misc[2] = sh;
-      misc[3] = q;
-      misc[4] = 65535u / q + 1u;  // ceil(2^16 / q): (x * m) >> 16 == x / q for x < 8192, q < 8
+      // cell of clock t: (t * scale) >> 32, i.e. the span divided into NCELL cells (clamped below)
+      uint64_t scale = ((uint64_t)NCELL << 32) / ((sp & 0xFFFFFFFFull) + 1ull);
+      misc[0] = (sp >> 32) ? 1u : 0u;
+      misc[1] = scale > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)scale;
     }
-    if (R > 16 || gen == 1u) {  // clear the staging area (always on this workgroup's first pass)
-      u32x4* z = reinterpret_cast<u32x4*>(rec);
-      for (uint32_t i = tid; i < nrec / 2; i += BLOCK) z[i] = u32x4{0u, 0u, 0u, 0u};
-    }
+    reinterpret_cast<u32x4*>(meta)[tid] = u32x4{0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu};
+    reinterpret_cast<u32x4*>(cells)[2 * tid] = u32x4{0u, 0u, 0u, 0u};
+    reinterpret_cast<u32x4*>(cells)[2 * tid + 1] = u32x4{0u, 0u, 0u, 0u};
+    if (tid == 0) reinterpret_cast<u32x4*>(cells)[2 * BLOCK] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
-    // table default: "no record of this wave at or after this cell"
-    for (uint32_t i = tid; i < W * gstride; i += BLOCK) grid[i] = (uint16_t)sV[i / gstride];
+
     // ---- A: load and scatter by rank ------------------------------------------------------
+    // Eight 16-byte units (two records each) per thread cover the workgroup.  Two records that go to an
+    // even rank and the rank above it (the usual case: both sit in the slot of their seq) leave with one
+    // 8-byte and one 2-byte store.
     {
       const u32x4* recs = p.records + (size_t)wg * (nrec / 2);
       const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
       uint32_t c_invalid = 0, c_field = 0, c_dis = 0;
-      for (uint32_t i0 = tid; i0 < n16; i0 += 4 * BLOCK) {
-        u32x4 v[4];
+      u32x4 v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t i = i0 + u * BLOCK;
-          v[u] = __builtin_nontemporal_load(recs + (i < n16 ? i : i0));
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t i = tid + u * BLOCK;
+        v[u] = __builtin_nontemporal_load(recs + (i < n16 ? i : n16 - 1));
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const uint32_t i = tid + u * BLOCK;
+        const bool live = i < n16;
+        const uint32_t f0 = 2 * (live ? i : n16 - 1);
+        const uint32_t w = f0 >> cl2;
+        const uint2 vf = sVF[w];
+        const uint32_t V = live ? vf.x : 0u, first = vf.y;
+        const uint32_t tag[2] = {v[u].x, v[u].z}, pay[2] = {v[u].y, v[u].w};
+        uint32_t k[2];
+        bool good[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const uint32_t s = (f0 + h) & capm;
+          const uint32_t seq = tag[h] & kSeqMask;
+          k[h] = (seq - first) & kSeqMask;
+          const uint32_t hi = tag[h] >> 20;  // phase | region | wave
+          const bool held = s < V;
+          good[h] = held && k[h] < V && (hi & 0xFu) == w && ((hi >> 4) & 0x7Fu) < R;
+          c_invalid += (held && !good[h]) ? 1u : 0u;
+          c_field += good[h] ? 1u : 0u;
+          c_dis += (good[h] && s != (seq & capm)) ? 1u : 0u;
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t i = i0 + u * BLOCK;
-          const bool live = i < n16;
-          const uint32_t f0 = 2 * (live ? i : i0);
-          const uint32_t w = f0 >> cl2;
-          const uint32_t V = live ? sV[w] : 0u, first = sFirst[w];
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const uint32_t tag = h ? v[u].z : v[u].x, pay = h ? v[u].w : v[u].y;
-            const uint32_t s = (f0 + h) & capm;
-            const uint32_t seq = tag & kSeqMask;
-            const uint32_t k = (seq - first) & kSeqMask;
-            const uint32_t region = (tag >> 24) & 0x7Fu;
-            const bool held = s < V;
-            const bool good = held && k < V && ((tag >> 20) & 0xFu) == w && region < R;
-            c_invalid += (held && !good) ? 1u : 0u;
-            c_field += good ? 1u : 0u;
-            c_dis += (good && s != (seq & capm)) ? 1u : 0u;
-            if (good) rec[(w << cl2) + k] = make_uint2(pay, region | ((tag >> 31) ? kMEnd : 0u) | live_tag);
-          }
+        const uint32_t pos0 = (w << cl2) + k[0], pos1 = (w << cl2) + k[1];
+        const bool twin = good[0] && good[1] && k[1] == k[0] + 1u && !(k[0] & 1u);
+        if (twin) {
+          *reinterpret_cast<uint2*>(clk + clk_word(pos0)) = make_uint2(pay[0], pay[1]);
+          *reinterpret_cast<uint16_t*>(meta + pos0) = (uint16_t)((tag[0] >> 24) | ((tag[1] >> 24) << 8));
+        }
+        const bool one0 = good[0] && !twin, one1 = good[1] && !twin;
+        if (__builtin_amdgcn_ballot_w64(one0 || one1)) {
+          if (one0) { clk[clk_word(pos0)] = pay[0]; meta[pos0] = (uint8_t)(tag[0] >> 24); }  // END flag and region (below 64)
+          if (one1) { clk[clk_word(pos1)] = pay[1]; meta[pos1] = (uint8_t)(tag[1] >> 24); }
         }
       }
       add_tmp(tmp, T_INVALID, c_invalid);
@@ -402,229 +338,429 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_DISORDER, c_dis);
     }
     __syncthreads();
-    // ---- occupancy check: a duplicated seq leaves fewer occupied ranks than valid records ----
+    if (p.stop_after == kStepOrdered) continue;
+
+    // ---- a duplicated seq leaves fewer occupied ranks than valid records ---------------------------
     // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
     // distinct ranks: only a workgroup with a record elsewhere needs the count.
-    const bool count_ranks = tmp[T_DISORDER] != 0u;
-    if (count_ranks) {
+    uint32_t n_occupied = tmp[T_FIELDVALID];
+    if (tmp[T_DISORDER] != 0u) {
+      const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
+      const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
       uint32_t occ = 0;
-      for (uint32_t q = pbase + lane; q < pend; q += 64) occ += is_live(recw[2 * q + 1]) ? 1u : 0u;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)  // bytes whose region field is not the "no record" code
+        occ += __popc((((mw[i] & 0x3F3F3F3Fu) ^ 0x3F3F3F3Fu) + 0x7F7F7F7Fu) & 0x80808080u);
       add_tmp(tmp, T_OCCUPIED, occ);
       __syncthreads();
-    } else if (tid == 0) {
-      tmp[T_OCCUPIED] = tmp[T_FIELDVALID];  // read again only after the next barrier
-    }
-    if (count_ranks && tmp[T_OCCUPIED] != tmp[T_FIELDVALID]) {
-      // Rare: some seq occurs twice.  The later slot must win, so redo this workgroup's
-      // scatter in slot order, one thread per wave.
-      __syncthreads();
-      for (uint32_t i = tid; i < nrec; i += BLOCK) recw[2 * i + 1] = 0;
-      if (tid == 0) { tmp[T_DISORDER] = 0; tmp[T_OCCUPIED] = 0; }
-      __syncthreads();
-      if (tid < W) {
-        const uint32_t w = tid, V = sV[w], first = sFirst[w];
-        const uint32_t* seg = reinterpret_cast<const uint32_t*>(p.records) + ((size_t)wg * nrec + (size_t)w * cap) * 2;
-        for (uint32_t s = 0; s < V; ++s) {
-          const uint32_t tag = seg[2 * s];
-          const uint32_t seq = tag & kSeqMask, k = (seq - first) & kSeqMask, region = (tag >> 24) & 0x7Fu;
-          if (k >= V || ((tag >> 20) & 0xFu) != w || region >= R) continue;
-          // the clock word remembers the winning slot for now
-          rec[w * cap + k] = make_uint2(s, region | ((tag >> 31) ? kMEnd : 0u) | live_tag);
-        }
-        uint32_t dis = 0, occ = 0;
-        for (uint32_t k = 0; k < V; ++k) {
-          if (!is_live(recw[2 * (w * cap + k) + 1])) continue;
-          const uint32_t s = recw[2 * (w * cap + k)];
-          dis += (s != ((seg[2 * s] & kSeqMask) & capm));
-          recw[2 * (w * cap + k)] = seg[2 * s + 1];
-          ++occ;
-        }
-        atomicAdd(&tmp[T_DISORDER], dis);
-        atomicAdd(&tmp[T_OCCUPIED], occ);
-      }
-      __syncthreads();
-    }
-    // ---- B: pairing, durations, per-(wave,region) statistics, monotonicity --------------------
-    // An END is paired iff the nearest earlier record of its (wave, region) is a START; every
-    // START that is not claimed this way is an orphan, so only ENDs have to search, and in
-    // traces of real kernels the START sits a few ranks back.  The metadata of the four ranks
-    // just below a lane's own comes from the lanes below it (the last four lanes of the previous
-    // round stand in for lanes 0..3); deeper searches are the rare slow path.  A pair whose
-    // START lies in an earlier hardware wave's span toggles the region bit of both spans'
-    // XOR totals, which phase C turns into each span's carry-in.
-    {
-      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0, x_span = 0;
-      uint32_t cm[4], ct = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t back = pbase > (uint32_t)j ? (uint32_t)j + 1u : 0u;
-        const uint2 r = rec[pbase < nrec ? pbase - back : 0u];
-        cm[j] = (back && is_live(r.y)) ? r.y : 0u;
-        if (j == 0) ct = r.x;
-      }
-      for (uint32_t qb = pbase; qb < pend; qb += 64) {
-        const bool in = qb + lane < pend;
-        const uint32_t q0 = in ? qb + lane : pend - 1;
-        const uint2 r0 = rec[q0];
-        const bool valid = in && is_live(r0.y);
-        const uint32_t m0 = valid ? r0.y : 0u, t0 = r0.x;
-        uint32_t m1 = wave_shr1(m0, cm[0]);
-        uint32_t m2 = wave_shr1(m1, cm[1]);
-        uint32_t m3 = wave_shr1(m2, cm[2]);
-        uint32_t m4 = wave_shr1(m3, cm[3]);
-        const uint32_t t1 = wave_shr1(t0, ct);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) cm[j] = (uint32_t)__builtin_amdgcn_readlane((int)m0, 63 - j);
-        ct = (uint32_t)__builtin_amdgcn_readlane((int)t0, 63);
-        const uint32_t k = q0 & capm, wofs = q0 - k, w = q0 >> cl2;
-        m1 = k > 0 ? m1 : 0u; m2 = k > 1 ? m2 : 0u; m3 = k > 2 ? m3 : 0u; m4 = k > 3 ? m4 : 0u;
-        const uint32_t region = m0 & kMRegion;
-        const bool is_end = (m0 & kMEnd) != 0u;  // m0 is 0 for a position that holds no record
-        const uint32_t want = kMValid | region, sel = kMValid | kMRegion;
-        const bool h1 = (m1 & sel) == want, h2 = (m2 & sel) == want, h3 = (m3 & sel) == want, h4 = (m4 & sel) == want;
-        bool have = h1 || h2 || h3 || h4;             // nearest earlier record of the same region
-        uint32_t pm = h1 ? m1 : (h2 ? m2 : (h3 ? m3 : m4));
-        uint32_t pq = q0 - (h1 ? 1u : (h2 ? 2u : (h3 ? 3u : 4u)));
-        bool have_prev = (m1 & kMValid) != 0u;        // previous record of this wave
-        uint32_t tprev = t1;
-        if (valid && k > 0 && (!have_prev || (is_end && !have && k > 4))) {  // slow path: walk back
-          have = false;
-          for (uint32_t kk = k; kk-- > 0;) {
-            const uint2 rq = rec[wofs + kk];
-            if (!is_live(rq.y)) continue;
-            if (!have_prev) { have_prev = true; tprev = rq.x; }
-            if (!is_end) break;
-            if ((rq.y & kMRegion) == region) { have = true; pm = rq.y; pq = wofs + kk; break; }
+      n_occupied = tmp[T_OCCUPIED];
+      if (n_occupied != tmp[T_FIELDVALID]) {
+        // Rare: some seq occurs twice.  The later slot must win, so redo this workgroup's
+        // scatter in slot order, one thread per wave.
+        __syncthreads();
+        reinterpret_cast<u32x4*>(meta)[tid] = u32x4{0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu};
+        if (tid == 0) { tmp[T_DISORDER] = 0; tmp[T_OCCUPIED] = 0; }
+        __syncthreads();
+        if (tid < W) {
+          const uint32_t w = tid, V = sVF[w].x, first = sVF[w].y;
+          const uint32_t* seg = reinterpret_cast<const uint32_t*>(p.records) + ((size_t)wg * nrec + (size_t)w * cap) * 2;
+          for (uint32_t s = 0; s < V; ++s) {
+            const uint32_t tag = seg[2 * s];
+            const uint32_t seq = tag & kSeqMask, k = (seq - first) & kSeqMask, region = (tag >> 24) & 0x7Fu;
+            if (k >= V || ((tag >> 20) & 0xFu) != w || region >= R) continue;
+            // the clock word remembers the winning slot for now
+            clk[clk_word(w * cap + k)] = s;
+            meta[w * cap + k] = (uint8_t)(tag >> 24);
           }
-        }
-        c_nonmono += (valid && have_prev && t0 < tprev) ? 1u : 0u;
-        c_starts += (valid && !is_end) ? 1u : 0u;
-        c_ends += is_end ? 1u : 0u;
-        if (is_end && have && !(pm & kMEnd)) {
-          ++c_pairs;
-          const uint32_t pt = recw[2 * pq];
-          recw[2 * pq + 1] = pm | kMPaired;
-          recw[2 * q0 + 1] = m0 | kMPaired;
-          if (pq < pbase) {
-            x_span ^= 1u << region;
-            atomicXor(&wave_tot[pq >> p.span_log2], 1u << region);
+          uint32_t dis = 0, occ2 = 0;
+          for (uint32_t k = 0; k < V; ++k) {
+            if ((meta[w * cap + k] & kRegion) == kEmpty) continue;
+            const uint32_t s = clk[clk_word(w * cap + k)];
+            dis += (s != ((seg[2 * s] & kSeqMask) & capm));
+            clk[clk_word(w * cap + k)] = seg[2 * s + 1];
+            ++occ2;
           }
-          const uint32_t d_raw = t0 - pt;
-          const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
-          const uint32_t e = w * R + region;
-          atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
-          atomicMax(&pw_max[e], d);
-          atomicMin(&pw_min[e], d);
-          atomicAdd(&hist[region * kHistStride + (d ? 31 - __clz(d) : 0)], 1u);
+          atomicAdd(&tmp[T_DISORDER], dis);
+          atomicAdd(&tmp[T_OCCUPIED], occ2);
+        }
+        __syncthreads();
+        n_occupied = tmp[T_OCCUPIED];
+      }
+    }
+    // ---- this lane's 16 positions: in round j the even position qe + 128 j and the one above it ---------
+    // (The arrays below are only ever assigned outside of branches: a conditional assignment makes the
+    // compiler carry each array through the branch as one 16-register value, copied at every merge.)
+    uint32_t t[kNR], mq[kNR / 4];  // clocks; metadata bytes, record i in byte i & 3 of word i >> 2
+#pragma unroll
+    for (int j = 0; j < kNR / 4; ++j) mq[j] = 0u;
+#pragma unroll
+    for (int j = 0; j < kNR / 2; ++j) {
+      const uint2 tt = *reinterpret_cast<const uint2*>(clk + cwe + 136u * j);
+      t[2 * j] = tt.x; t[2 * j + 1] = tt.y;
+      // positions past the last record slot stay cleared
+      mq[j >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t*>(meta + qe + 128u * j) << (16 * (j & 1));
+    }
+    auto meta_of = [&](int i) -> uint32_t { return (mq[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
+    auto set_paired = [&](int i, uint32_t yes) { mq[i >> 2] |= (yes << 6) << (8 * (i & 3)); };  // yes: 0 or 1
+    const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - n_occupied);
+    const uint32_t rec_cost = p.rec_cost;
+
+    // One pair: duration into the per-(wave, region) sums and the histogram.  The sums exist in up to
+    // four copies, one per quarter of the wave: lanes 16 apart tend to hold the same region, and LDS
+    // atomics of one instruction that hit one address are processed one after the other.
+    const uint32_t copy = (lane >> 4) & (p.ncopy - 1u);
+    auto account_pair = [&](uint32_t w, uint32_t region, uint32_t d_raw) {
+      const uint32_t d = d_raw > rec_cost ? d_raw - rec_cost : 0u;
+      const uint32_t e = (w * R + region) * p.ncopy + copy;
+      atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
+      atomicMax(&pw_max[e], d);
+      atomicMin(&pw_min[e], d);
+      atomicAdd(&hist[region * kHistStride + (31 - __clz(d | 1u))], 1u);
+    };
+
+    if (wg_invalid == 0u) {
+      // ---- B: pairing, durations, per-(wave,region) statistics, monotonicity ------------------------
+      // Every rank below a wave's record count holds a record here.  An END is paired iff the nearest
+      // earlier record of its (wave, region) is a START; every START that is not claimed this way is an
+      // orphan, so only ENDs search.  In traces of kernels whose regions follow one another the START
+      // sits one rank below: in the lane's own even position, or, for an END in the even position, in
+      // the odd position of the lane below (DPP; the last lane of the previous round stands in for lane
+      // 0).  An END whose lower neighbour belongs to another region walks back through LDS.
+      // A START learns that it is paired from its END: in the same lane directly, one lane up through a
+      // DPP shift of the claims, and when the END is in another hardware wave or found the START by
+      // walking, through a mark in the START's metadata byte that is read back after the barrier.
+      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0, claims = 0;
+      bool marked = false;
+      uint32_t cm = kEmpty, ct = 0;
+      if (pbase > 0 && pbase < nrec) { cm = meta[pbase - 1]; ct = clk[clk_word(pbase - 1)]; }
+      auto walk_back = [&](uint32_t qq, uint32_t mine, bool& have, uint32_t& sm, uint32_t& sq, uint32_t& sts) {
+        const uint32_t k = qq & capm, wofs = qq - k;
+        for (uint32_t kk = k - 1; kk-- > 0;) {
+          const uint32_t mm = meta[wofs + kk];
+          if (((mm ^ mine) & kRegion) == 0u) { have = true; sm = mm; sq = wofs + kk; sts = clk[clk_word(sq)]; break; }
+        }
+      };
+#pragma unroll
+      for (int j = 0; j < kNR / 2; ++j) {
+        const uint32_t q = qe + 128u * j;  // even position; the odd one is q + 1
+        const uint32_t m0 = meta_of(2 * j), m1 = meta_of(2 * j + 1), t0 = t[2 * j], t1 = t[2 * j + 1];
+        uint32_t pm = wave_shr1(m1, cm);
+        const uint32_t pt = wave_shr1(t1, ct);
+        cm = (uint32_t)__builtin_amdgcn_readlane((int)m1, 63);
+        ct = (uint32_t)__builtin_amdgcn_readlane((int)t1, 63);
+        const uint32_t k0 = q & capm, w = q >> cl2;
+        pm = k0 > 0 ? pm : kEmpty;
+        const bool v0 = (m0 & kRegion) != kEmpty, v1 = (m1 & kRegion) != kEmpty;
+        const bool e0 = v0 && (m0 & kEnd), e1 = v1 && (m1 & kEnd);
+        bool have0 = ((m0 ^ pm) & kRegion) == 0u;  // the rank below holds a record of the same region
+        bool have1 = ((m1 ^ m0) & kRegion) == 0u;
+        uint32_t sm0 = pm, sm1 = m0, st0 = pt, st1 = t0, sq0 = 0, sq1 = 0;  // the candidate START
+        const bool deep0 = e0 && !have0 && k0 > 1, deep1 = e1 && !have1 && k0 > 0;
+        if (__builtin_amdgcn_ballot_w64(deep0 || deep1)) {
+          if (deep0) walk_back(q, m0, have0, sm0, sq0, st0);
+          if (deep1) walk_back(q + 1, m1, have1, sm1, sq1, st1);
+        }
+        const bool p0 = e0 && have0 && !(sm0 & kEnd), p1 = e1 && have1 && !(sm1 & kEnd);
+        c_nonmono += ((v0 && k0 > 0 && t0 < pt) ? 1u : 0u) + ((v1 && t1 < t0) ? 1u : 0u);
+        c_starts += ((v0 && !e0) ? 1u : 0u) + ((v1 && !e1) ? 1u : 0u);
+        c_ends += (e0 ? 1u : 0u) + (e1 ? 1u : 0u);
+        c_pairs += (p0 ? 1u : 0u) + (p1 ? 1u : 0u);
+        const bool far0 = p0 && deep0, far1 = p1 && deep1, near0 = p0 && !deep0;
+        set_paired(2 * j, (p0 || (p1 && !deep1)) ? 1u : 0u);  // as END, or as the START of the odd position
+        set_paired(2 * j + 1, p1 ? 1u : 0u);
+        claims |= (near0 ? 1u : 0u) << j;
+        if (__builtin_amdgcn_ballot_w64(far0 || far1)) {
+          if (far0) meta[sq0] = (uint8_t)(sm0 | kPaired);
+          if (far1) meta[sq1] = (uint8_t)(sm1 | kPaired);
+          marked = true;
+        }
+        if (j == 0 && near0 && lane == 0u && pbase > 0) meta[pbase - 1] = (uint8_t)(sm0 | kPaired);
+        const bool both = p0 && p1;
+        if (p0 || p1) account_pair(w, (p1 ? m1 : m0) & kRegion, p1 ? t1 - st1 : t0 - st0);
+        if (__builtin_amdgcn_ballot_w64(both)) {
+          if (both) account_pair(w, m0 & kRegion, t0 - st0);
         }
       }
+      // the START claimed by the even position of the lane above (lane 63: of lane 0 in the next round)
+      const uint32_t claims0 = (uint32_t)__builtin_amdgcn_readlane((int)claims, 0);
 #pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) x_span ^= __shfl_xor(x_span, d, 64);
-      if (lane == 0 && x_span) atomicXor(&wave_tot[hw], x_span);
+      for (int j = 0; j < kNR / 2; ++j) {
+        const uint32_t next_round = j + 1 < kNR / 2 ? (claims0 >> (j + 1)) & 1u : 0u;
+        const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp((int)next_round, (int)((claims >> j) & 1u), 0x130, 0xF, 0xF,
+                                                                   false);  // wave_shl:1
+        set_paired(2 * j + 1, got);
+      }
+      if (marked && lane == 0u) tmp[T_MARKS] = 1u;
       add_tmp(tmp, T_NONMONO, c_nonmono);
       add_tmp(tmp, T_PAIRS, c_pairs);
-      add_tmp(tmp, T_ORPH_S, c_starts);  // turned into orphan counts once T_PAIRS is complete
-      add_tmp(tmp, T_ORPH_E, c_ends);
-    }
-    __syncthreads();
-    const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - tmp[T_OCCUPIED]);
-    const bool eligible = !misc[0] && wg_invalid == 0 && tmp[T_NONMONO] == 0;
-
-    if (eligible) {
-      const uint32_t shift = misc[1], csh = misc[2], cm = misc[4], xmax = 8u * ncell - 1u;
-      const uint32_t cw = misc[3] << csh;  // cell width, at most 1 << shift
-      auto cell_of = [&](uint32_t t) -> uint32_t {  // t / cw, or some value >= ncell when t lies past the cells
-        uint32_t x = t >> csh;
-        x = x < xmax ? x : xmax;
-        return (x * cm) >> 16;
-      };
-      // ---- C: open-region mask before every position (exclusive XOR scan per wave) -------------
-      // ---- D: coarse time -> position table: grid[w][c] = first rank of wave w in a cell >= c ----
-      {
-        uint32_t carry = 0;
-        if (span < cap) {  // this span continues a wave that started in an earlier span
-          const uint32_t firsthw = ((pbase >> cl2) << cl2) >> p.span_log2;
-          for (uint32_t i = firsthw; i < hw; ++i) carry ^= wave_tot[i];
-        }
-        uint32_t cprev_carry = 0, wide = 0;
-        if (pbase > 0 && pbase < nrec) {
-          const uint32_t c1 = cell_of(recw[2 * (pbase - 1)]);
-          cprev_carry = c1 < ncell ? c1 : ncell - 1;
-        }
-        for (uint32_t qb = pbase; qb < pend; qb += 64) {
-          const bool in = qb + lane < pend;
-          const uint32_t q0 = in ? qb + lane : pend - 1;
-          const uint2 r0 = rec[q0];
-          const bool paired = in && is_live(r0.y) && (r0.y & kMPaired);
-          const uint32_t x = paired ? (1u << (r0.y & kMRegion)) : 0u;
-          uint32_t v = x;
-          if (cap >= 64) {
-            v = wave_xor_scan(v);
+      add_tmp(tmp, T_STARTS, c_starts);  // orphans = STARTs - pairs, ENDs - pairs
+      add_tmp(tmp, T_ENDS, c_ends);
+    } else {
+      // ---- B, workgroup with holes: the definition, one thread per (wave, region) -----------------
+      for (uint32_t e = tid; e < W * R; e += BLOCK) {
+        const uint32_t w = e / R, r = e - w * R, V = sVF[w].x;
+        bool have_prev = false;
+        uint32_t prev_m = 0, prev_t = 0, n_pairs = 0, n_starts = 0, n_ends = 0;
+        for (uint32_t k = 0; k < V; ++k) {
+          const uint32_t mm = meta[w * cap + k];
+          if ((mm & kRegion) != r) continue;
+          const uint32_t ts = clk[clk_word(w * cap + k)];
+          if (mm & kEnd) {
+            ++n_ends;
+            if (have_prev && !(prev_m & kEnd)) { ++n_pairs; account_pair(w, r, ts - prev_t); }
           } else {
-            for (uint32_t d = 1; d < cap; d <<= 1) { const uint32_t y = __shfl_up(v, d, 64); if ((lane & capm) >= d) v ^= y; }
+            ++n_starts;
           }
-          const uint32_t ex = v ^ x ^ carry;
-          if (cap >= 64) {
-            carry ^= (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
-            if (((qb + 64) & capm) == 0) carry = 0;  // next round starts a new wave segment
-          }
-          const uint32_t w = q0 >> cl2, k = q0 & capm, V = sV[w];
-          const uint32_t c0 = cell_of(r0.x);
-          const uint32_t c = c0 < ncell ? c0 : ncell - 1;
-          const uint32_t cp = wave_shr1(c, cprev_carry);
-          cprev_carry = (uint32_t)__builtin_amdgcn_readlane((int)c, 63);
-          if (in && k < V) {
-            wide |= c0 >= ncell ? 1u : 0u;
-            uint16_t* g = grid + w * gstride;
-            for (uint32_t cc = k > 0 ? cp + 1 : 0u; cc <= c; ++cc) g[cc] = (uint16_t)k;
-          }
-          if (in) recw[2 * q0 + 1] = ex;
+          have_prev = true; prev_m = mm; prev_t = ts;
         }
-        if (wide) tmp[T_WIDE] = 1u;  // some clock lies past the recorded span: narrow merge keys are off
+        if (n_pairs) atomicAdd(&tmp[T_PAIRS], n_pairs);
+        if (n_starts) atomicAdd(&tmp[T_STARTS], n_starts);
+        if (n_ends) atomicAdd(&tmp[T_ENDS], n_ends);
       }
-      __syncthreads();
-      // ---- order the cells by record count (counting sort, fullest first) --------------------------
-      for (uint32_t c = tid; c < ncell; c += BLOCK) {
-        uint32_t n = 0;
-        for (uint32_t w = 0; w < W; ++w) n += (uint32_t)grid[w * gstride + c + 1] - (uint32_t)grid[w * gstride + c];
-        const uint32_t nb = n < 63u ? n : 63u;
-        const uint32_t slot = atomicAdd(&bucket[nb], 1u);
-        cinfo[c] = (uint16_t)(nb | (slot << 6));
-      }
-      __syncthreads();
-      if (tid < 64) {  // exclusive prefix over the buckets, from 63 down
-        const uint32_t mine = bucket[63 - tid];
-        uint32_t incl = mine;
-#pragma unroll
-        for (uint32_t d = 1; d < 64; d <<= 1) { const uint32_t y = __shfl_up(incl, d, 64); if (tid >= d) incl += y; }
-        bucket[63 - tid] = incl - mine;
-      }
-      __syncthreads();
-      for (uint32_t c = tid; c < ncell; c += BLOCK) {
-        const uint32_t ci = cinfo[c];
-        perm[bucket[ci & 63u] + (ci >> 6)] = (uint16_t)c;
-      }
-      __syncthreads();
-      // ---- E: region-pair overlap, one lane per time cell ------------------------------------------
-      const uint32_t pb = p.pos_bits;
-      if (!tmp[T_WIDE] && shift + pb <= 31u) {  // the all-ones key must stay free
-        if (W <= 4)      sweep_cells<4, 3, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
-        else             sweep_cells<16, 5, uint32_t>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
-      } else {
-        if (W <= 4)      sweep_cells<4, 3, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
-        else if (W <= 8) sweep_cells<8, 4, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
-        else             sweep_cells<16, 5, unsigned long long>(rec, grid, perm, oacc32, W, R, cl2, pb, ncell, cw, tid, BLOCK);
+      for (uint32_t w = tid; w < W; w += BLOCK) {
+        const uint32_t V = sVF[w].x;
+        bool have_prev = false;
+        uint32_t prev_t = 0, n = 0;
+        for (uint32_t k = 0; k < V; ++k) {
+          if ((meta[w * cap + k] & kRegion) == kEmpty) continue;
+          const uint32_t ts = clk[clk_word(w * cap + k)];
+          n += (have_prev && ts < prev_t) ? 1u : 0u;
+          have_prev = true; prev_t = ts;
+        }
+        if (n) atomicAdd(&tmp[T_NONMONO], n);
       }
     }
     __syncthreads();
+    const bool eligible = !misc[0] && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
 
-    // ---- F: per-(workgroup, wave, region) output, fold into running totals ------------------------
+    if (eligible && p.stop_after != kStepPaired) {
+      // ---- C: order the paired records of all waves by clock ---------------------------------------
+      // marks left by ENDs of other hardware waves (only the last position can have one) and by walks
+      set_paired(kNR - 1, ((uint32_t)meta[qe + 128u * (kNR / 2 - 1) + 1u] >> 6) & 1u);
+      if (tmp[T_MARKS]) {
+#pragma unroll
+        for (int j = 0; j < kNR / 2; ++j)
+          mq[j >> 1] |= ((uint32_t)*reinterpret_cast<const uint16_t*>(meta + qe + 128u * j) & 0x4040u) << (16 * (j & 1));
+      }
+      const uint32_t scale = misc[1];
+      // Straight-line code from here to the sorted sequence: the LDS operations of a lane's 16 records
+      // are issued together and no array is assigned inside a branch.
+      uint32_t ca[kNR];  // cell | arrival slot << 16; then: first place of the cell; then: place in the sorted sequence
+#pragma unroll
+      for (int i = 0; i < kNR; ++i) {
+        const bool ev = (meta_of(i) & kPaired) != 0u;
+        uint32_t c = __umulhi(t[i], scale);
+        c = c < NCELL - 1 ? c : NCELL - 1;
+        const uint32_t sh = (c & 1u) << 4;
+        // a record that is no event adds nothing, so that all 16 atomics are in flight together
+        const uint32_t old = atomicAdd(&cells[c >> 1], ev ? 1u << sh : 0u);
+        ca[i] = c | (((old >> sh) & 0xFFFFu) << 16);
+      }
+      __syncthreads();
+      if (p.stop_after == kStepCounted) continue;
+      {  // exclusive prefix sum over the cell counters, 16 cells (8 words) per thread
+        u32x4 a = reinterpret_cast<u32x4*>(cells)[2 * tid], b = reinterpret_cast<u32x4*>(cells)[2 * tid + 1];
+        uint32_t wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t run = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t lo = wv[i] & 0xFFFFu, hi = wv[i] >> 16;
+          wv[i] = run | ((run + lo) << 16);
+          run += lo + hi;
+        }
+        const uint32_t incl = wave_scan_add(run);
+        if (lane == 63) wtot[hw] = incl;
+        __syncthreads();
+        uint32_t base = incl - run;
+        for (uint32_t h = 0; h < hw; ++h) base += wtot[h];
+        const uint32_t both = base * 0x00010001u;
+        a = u32x4{wv[0] + both, wv[1] + both, wv[2] + both, wv[3] + both};
+        b = u32x4{wv[4] + both, wv[5] + both, wv[6] + both, wv[7] + both};
+        reinterpret_cast<u32x4*>(cells)[2 * tid] = a;
+        reinterpret_cast<u32x4*>(cells)[2 * tid + 1] = b;
+        if (tid == BLOCK - 1) { cells[NCELL / 2] = base + run; tmp[T_EVENTS] = base + run; }
+      }
+      __syncthreads();
+      if (p.stop_after == kStepCellSums) continue;
+      auto cell_start = [&](uint32_t c) -> uint32_t { return (cells[c >> 1] >> ((c & 1u) << 4)) & 0xFFFFu; };
+      // provisional place: cell start + arrival slot (plain index here, the padded layout comes with the
+      // final places)
+      uint32_t nm[kNR];  // records in the cell (0: this record is no event) | arrival slot << 16
+#pragma unroll
+      for (int i = 0; i < kNR; ++i) {
+        const uint32_t ev = 0u - ((meta_of(i) >> 6) & 1u);  // all ones for an event
+        const uint32_t c = ca[i] & 0xFFFFu, mine = ca[i] >> 16;
+        const uint32_t s0 = cell_start(c), s1 = cell_start(c + 1);
+        clk[ev ? s0 + mine : kSpareWord] = t[i];  // no branch: the others all write one unused word
+        ca[i] = s0;
+        nm[i] = ((s1 - s0) | (mine << 16)) & ev;
+      }
+      __syncthreads();
+      if (p.stop_after == kStepPlaced) continue;
+      // rank among the records of the same cell: by clock, then by arrival slot.  The first records of
+      // every cell are read unconditionally (a read past the cell is masked out of the count), fuller
+      // cells finish in a loop.
+      {
+        constexpr uint32_t kFlat = 4;
+        uint32_t n_max = 0;
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) n_max = (nm[i] & 0xFFFFu) > n_max ? (nm[i] & 0xFFFFu) : n_max;
+        // the record at arrival slot `it` of the cell comes before this one
+        auto before_me = [&](uint32_t tm, uint32_t t0, uint32_t it, uint32_t mine) -> uint32_t {
+          // written with bit operations: short-circuit conditions become branches around each LDS read
+          return (uint32_t)(tm < t0) | ((uint32_t)(tm == t0) & (uint32_t)(it < mine));  // the record's own entry gives 0
+        };
+#pragma unroll
+        for (uint32_t it = 0; it < kFlat; ++it) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            uint32_t tm[kNR / 2];
+#pragma unroll
+            for (int i = 0; i < kNR / 2; ++i) tm[i] = (clk + (ca[8 * half + i] & 0xFFFFu))[it];
+#pragma unroll
+            for (int i = 0; i < kNR / 2; ++i) {
+              const int r = 8 * half + i;
+              const uint32_t n = nm[r] & 0xFFFFu, mine = nm[r] >> 16;
+              ca[r] += ((uint32_t)(it < n) & before_me(tm[i], t[r], it, mine)) << 16;  // rank in the upper half for now
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        if (__builtin_amdgcn_ballot_w64(n_max > kFlat)) {
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) {
+            const uint32_t n = nm[i] & 0xFFFFu, s0 = ca[i] & 0xFFFFu, mine = nm[i] >> 16, t0 = t[i];
+            uint32_t more = 0;
+            for (uint32_t it = kFlat; __builtin_amdgcn_ballot_w64(it < n); ++it) {
+              if (it < n) more += before_me(clk[s0 + it], t0, it, mine);
+            }
+            ca[i] += more << 16;
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) ca[i] = (ca[i] & 0xFFFFu) + (ca[i] >> 16);
+      }
+      __syncthreads();
+      if (p.stop_after == kStepRanked) continue;
+#pragma unroll
+      for (int i = 0; i < kNR; ++i) {
+        const bool ev = (meta_of(i) & kPaired) != 0u;
+        clk[ev ? clk_word(ca[i]) : kSpareWord] = t[i];
+        meta[ev ? ca[i] : NPOS] = (uint8_t)(meta_of(i) & ~kPaired);
+      }
+      __syncthreads();
+      if (p.stop_after == kStepSorted) continue;
+
+      // ---- D: region-pair overlap, 16 consecutive records of the sorted sequence per lane ----------
+      {
+        const uint32_t n_events = tmp[T_EVENTS];
+        const uint32_t g0 = tid * kNR;
+        uint32_t st[kNR], sx[kNR];  // clock, region bit (0: no record)
+        const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
+        const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+        auto end_mask = [&](int i) -> uint32_t {  // all ones for an END
+          return (uint32_t)((int32_t)(mw[i >> 2] << (24 - 8 * (i & 3))) >> 31);
+        };
+        {
+          const u32x4* tv = reinterpret_cast<const u32x4*>(clk + clk_word(g0));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const u32x4 v = tv[i];
+            st[4 * i] = v.x; st[4 * i + 1] = v.y; st[4 * i + 2] = v.z; st[4 * i + 3] = v.w;
+          }
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) {
+            const uint32_t info = (mw[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+            sx[i] = g0 + i < n_events ? 1u << (info & 31u) : 0u;
+          }
+        }
+        uint32_t pl[PLANES];
+#pragma unroll
+        for (int k = 0; k < PLANES; ++k) pl[k] = 0u;
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, sx[i], end_mask(i));
+        // inclusive scan of the lanes' net changes, then the sum of the waves below
+        uint32_t inc[PLANES];
+#pragma unroll
+        for (int k = 0; k < PLANES; ++k) inc[k] = pl[k];
+        {
+          uint32_t o[PLANES];
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(inc[k]);
+          planes_add<PLANES>(inc, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(inc[k]);
+          planes_add<PLANES>(inc, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(inc[k]);
+          planes_add<PLANES>(inc, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(inc[k]);
+          planes_add<PLANES>(inc, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<4>(inc[k]);
+          planes_add<PLANES>(inc, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<5>(inc[k]);
+          planes_add<PLANES>(inc, o);
+        }
+        if (lane == 63) {
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) ptot[hw * 8 + k] = inc[k];
+        }
+        __syncthreads();
+        // state before this lane's stretch: lanes below in this wave + all waves below
+#pragma unroll
+        for (int k = 0; k < PLANES; ++k) pl[k] = wave_shr1(inc[k], 0u);
+        for (uint32_t h = 0; h < hw; ++h) {
+          uint32_t o[PLANES];
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = ptot[h * 8 + k];
+          planes_add<PLANES>(pl, o);
+        }
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) {
+          const uint32_t x = sx[i], dm = end_mask(i), tt = st[i];
+          uint32_t act_before = pl[0];
+#pragma unroll
+          for (int k = 1; k < PLANES; ++k) act_before |= pl[k];
+          planes_step<PLANES>(pl, x, dm);
+          uint32_t act_after = pl[0];
+#pragma unroll
+          for (int k = 1; k < PLANES; ++k) act_after |= pl[k];
+          const uint32_t act = dm ? act_after : act_before;  // active regions other than this one
+          if (x & ~act) {  // the region was off before this START / is off after this END
+            // modulo 2^32: the totals of one workgroup lie below its span, which is below 2^32
+            const uint32_t a = __ffs(x) - 1;
+            uint32_t* row = oacc32 + a * (R | 1u);
+            const uint32_t val = dm ? tt : 0u - tt;
+            atomicAdd(&row[a], val);
+            uint32_t set = act;
+            while (set) {
+              const uint32_t bb = __ffs(set) - 1;
+              set &= set - 1;
+              atomicAdd(&row[bb], val);
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (p.stop_after) continue;
+
+    // ---- E: per-(workgroup, wave, region) output, fold into running totals ------------------------
     for (uint32_t e = tid; e < W * R; e += BLOCK) {
-      const unsigned long long pk = pw_pack[e];
+      unsigned long long pk = 0;
+      uint32_t mx = 0, mn = 0xFFFFFFFFu;
+      for (uint32_t c = 0; c < p.ncopy; ++c) {
+        const uint32_t ec = e * p.ncopy + c;
+        pk += pw_pack[ec];
+        mx = pw_max[ec] > mx ? pw_max[ec] : mx;
+        mn = pw_min[ec] < mn ? pw_min[ec] : mn;
+        pw_pack[ec] = 0; pw_max[ec] = 0; pw_min[ec] = 0xFFFFFFFFu;
+      }
       const uint32_t n = (uint32_t)(pk >> 46);
       const unsigned long long s = pk & ((1ull << 46) - 1);
-      const uint32_t mx = pw_max[e], mn = pw_min[e];
       uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + e) * 2;
       dst[0] = s;
       dst[1] = (uint64_t)n | ((uint64_t)mx << 32);
@@ -634,7 +770,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         atomicMax(&reg_max[r], mx);
         atomicMin(&reg_min[r], mn);
       }
-      pw_pack[e] = 0; pw_max[e] = 0; pw_min[e] = 0xFFFFFFFFu;
     }
     // region-pair sums of this workgroup: the two one-sided sums of a pair add up, modulo 2^32, to the
     // time both regions were open (below the span, hence exact); the upper triangle keeps the totals
@@ -652,8 +787,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_DISORDER] += tmp[T_DISORDER];
       ctr[H_NONMONO] += tmp[T_NONMONO];
       ctr[H_PAIRS] += tmp[T_PAIRS];
-      ctr[H_ORPHAN_START] += tmp[T_ORPH_S] - tmp[T_PAIRS];
-      ctr[H_ORPHAN_END] += tmp[T_ORPH_E] - tmp[T_PAIRS];
+      ctr[H_ORPHAN_START] += tmp[T_STARTS] - tmp[T_PAIRS];
+      ctr[H_ORPHAN_END] += tmp[T_ENDS] - tmp[T_PAIRS];
       ctr[H_SPAN_OVF] += misc[0];
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
     }
@@ -662,28 +797,28 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 
   // ---- flush this decoder workgroup's totals --------------------------------------------------
   unsigned long long* out = reinterpret_cast<unsigned long long*>(p.out);
-  for (uint32_t i = tid; i < R * 64; i += BLOCK) {
+  for (uint32_t i = tid_k; i < R * 64; i += BLOCK) {
     const uint32_t h = hist[(i >> 6) * kHistStride + (i & 63u)];
     if (h) atomicAdd(&out[SL.hist + i], (unsigned long long)h);
   }
-  for (uint32_t i = tid; i < R * R; i += BLOCK)
+  for (uint32_t i = tid_k; i < R * R; i += BLOCK)
     if (oacc[i]) atomicAdd(&out[SL.F + i], oacc[i]);  // staged in the F area until finalize
-  for (uint32_t r = tid; r < R; r += BLOCK) {
+  for (uint32_t r = tid_k; r < R; r += BLOCK) {
     if (reg_min[r] != 0xFFFFFFFFu || reg_max[r] || reg_sum[r]) {
       atomicAdd(&out[SL.sum + r], reg_sum[r]);
       atomicMax(&out[SL.max + r], (unsigned long long)reg_max[r]);
       atomicMin(&out[SL.min + r], (unsigned long long)reg_min[r]);
     }
   }
-  if (tid < H_STATUS && ctr[tid]) atomicAdd(&out[tid], ctr[tid]);
+  if (tid_k < H_STATUS && ctr[tid_k]) atomicAdd(&out[tid_k], ctr[tid_k]);
 }
 
 // Launch shape of one kernel instantiation for one LDS size, queried once per device.
 struct LaunchCache { int dev = -1; uint32_t lds = 0; uint32_t max_grid = 0; };
 
-template <int BLOCK>
+template <int BLOCK, int PLANES>
 kp_status launch_main(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
-  auto kern = kp_reduce_main<BLOCK>;
+  auto kern = kp_reduce_main<BLOCK, PLANES>;
   static thread_local LaunchCache cache;
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
@@ -703,7 +838,14 @@ kp_status launch_main(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) 
   return KP_OK;
 }
 
-kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* out_stats, hipStream_t s) {
+template <int BLOCK>
+kp_status launch_planes(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
+  // counters of open waves per region run up to the number of waves
+  return p.W < 16 ? launch_main<BLOCK, 4>(p, lds_bytes, s) : launch_main<BLOCK, 5>(p, lds_bytes, s);
+}
+
+kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* out_stats, uint32_t stop_after,
+                      hipStream_t s) {
   if (h.magic != KP_TRACE_MAGIC || h.version != KP_TRACE_VERSION)
     return kp::fail(KP_ERR_BAD_TRACE, "trace header: bad magic/version (%08x, %u)", h.magic, h.version);
   if (h.waves_per_wg < 1 || h.waves_per_wg > KP_MAX_WAVES || h.n_regions < 1 || !kp::is_pow2(h.cap_wave))
@@ -722,16 +864,10 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     return kp::fail(KP_ERR_INVALID_ARG, "raw and out_stats must be 16-byte aligned");
 
   const uint32_t W = h.waves_per_wg, R = h.n_regions, cap = h.cap_wave;
-  const int block = nrec >= 8192 ? 1024 : (nrec >= 2048 ? 512 : 256);
-  // positions per hardware wave of the decoder: a power of two >= 64 covering nrec
-  uint32_t span = 64;
-  while (span * (uint32_t)(block / 64) < nrec) span <<= 1;
-  uint32_t span_log2 = 0;
-  while ((1u << span_log2) < span) ++span_log2;
-  // time cells per wave: at most one per record slot, 1024, and 8192 table entries over all waves
-  uint32_t ncell = cap < 1024 ? cap : 1024;
-  while (W * ncell > 8192) ncell >>= 1;
-  const LdsLayout L = lds_layout(nrec, W, R, ncell, block);
+  const int block = nrec > 4096 ? 1024 : (nrec > 1024 ? 256 : 64);  // 16 positions per lane
+  uint32_t ncopy = 4;  // as many copies of the per-(wave, region) sums as LDS has room for
+  while (ncopy > 1 && lds_layout(block, W, R, ncopy).total > kMaxLds) ncopy >>= 1;
+  const LdsLayout L = lds_layout(block, W, R, ncopy);
   if (L.total > kMaxLds)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder needs %u B of LDS for this geometry (limit %u)", L.total, kMaxLds);
 
@@ -752,11 +888,10 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     p.n_wg = h.n_wg; p.W = W; p.R = R; p.cap = cap;
     p.cap_log2 = 0; while ((1u << p.cap_log2) < cap) ++p.cap_log2;
     p.rec_cost = h.rec_cost; p.flush = h.flags & KP_FLAG_FLUSH;
-    p.nrec = nrec; p.span = span; p.span_log2 = span_log2; p.ncell = ncell;
-    p.pos_bits = 0; while ((1u << p.pos_bits) < nrec) ++p.pos_bits;
-    const kp_status st = block == 1024 ? launch_main<1024>(p, L.total, s)
-                       : block == 512  ? launch_main<512>(p, L.total, s)
-                                       : launch_main<256>(p, L.total, s);
+    p.nrec = nrec; p.ncopy = ncopy; p.stop_after = stop_after;
+    const kp_status st = block == 1024 ? launch_planes<1024>(p, L.total, s)
+                       : block == 256  ? launch_planes<256>(p, L.total, s)
+                                       : launch_planes<64>(p, L.total, s);
     if (st != KP_OK) return st;
   }
   hipLaunchKernelGGL(kp_reduce_finalize, dim3(1), dim3(256), 0, s, out, h.n_wg, W, R);
@@ -770,7 +905,16 @@ extern "C" kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_tra
                                          void* out_stats, void* stream) {
   kp::clear_error();
   if (!raw || !hdr_host || !out_stats) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
-  return reduce_impl(raw, n, *hdr_host, out_stats, static_cast<hipStream_t>(stream));
+  return reduce_impl(raw, n, *hdr_host, out_stats, 0u, static_cast<hipStream_t>(stream));
+}
+
+extern "C" kp_status kp_trace_reduce_steps(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                                           void* out_stats, int last_step, void* stream) {
+  kp::clear_error();
+  if (!raw || !hdr_host || !out_stats) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
+  if (last_step < kStepOrdered || last_step > kStepSwept)
+    return kp::fail(KP_ERR_INVALID_ARG, "last_step must be %d..%d", kStepOrdered, kStepSwept);
+  return reduce_impl(raw, n, *hdr_host, out_stats, (uint32_t)last_step, static_cast<hipStream_t>(stream));
 }
 
 extern "C" kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats, void* stream) {
@@ -780,5 +924,5 @@ extern "C" kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats,
   hipStream_t s = static_cast<hipStream_t>(stream);
   KP_HIP_TRY(hipMemcpyAsync(&h, raw, sizeof h, hipMemcpyDeviceToHost, s));
   KP_HIP_TRY(hipStreamSynchronize(s));
-  return reduce_impl(raw, n, h, out_stats, s);
+  return reduce_impl(raw, n, h, out_stats, 0u, s);
 }
