@@ -37,6 +37,7 @@ constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kRegion = 0x3Fu, kEmpty = 0x3Fu, kPaired = 0x40u, kEnd = 0x80u;
 constexpr int kNR = 16;                       // positions per lane
 constexpr uint32_t kWaveSpan = 64 * kNR;      // positions per hardware wave
+constexpr uint32_t kMaxCellWindow = 17;       // fullest time cell the sweep's register sort covers (halo 16)
 constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
 constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bins of different regions, different banks
@@ -50,7 +51,7 @@ enum { kStepOrdered = 1, kStepPaired, kStepCounted, kStepCellSums, kStepPlaced, 
 
 // per-workgroup temporaries (u32 words in LDS)
 enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_STARTS, T_ENDS,
-       T_EVENTS, T_MARKS, T_COUNT };
+       T_EVENTS, T_MARKS, T_WIDE, T_MAXCELL, T_COUNT };
 
 struct StatsLayout {  // offsets in u64 words
   size_t hist, cnt, sum, min, max, U, O, F, per, total;
@@ -162,6 +163,74 @@ __device__ __forceinline__ void planes_step(uint32_t (&pl)[PLANES], uint32_t x, 
   for (int k = 0; k < PLANES; ++k) { const uint32_t o = pl[k]; pl[k] = o ^ carry; carry &= o ^ dm; }
 }
 
+// The 16 records of the clock-sorted sequence that lane `tid` of the sweep owns, from a sequence that
+// is only ordered cell by cell (inside a cell the records stand in arrival order).  The lane reads a
+// window of its 16 places and HALO on either side, so that every cell with a record among the 16 lies
+// inside the window as long as no cell holds more than HALO + 1 records, and sorts the window in
+// registers: one word per record, clock << 5 | region << 1 | END (records with equal words are
+// interchangeable).  Cells follow one another in clock order, so sorting the words sorts every cell and
+// moves no record out of its cell.  Outputs: clock, region bit (0 past the end of the sequence), END bits.
+template <int HALO, uint32_t NPOS>
+__device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events,
+                                              uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
+  constexpr int N = kNR + 2 * HALO;
+  uint32_t key[N];
+  const uint32_t g0 = tid * kNR;
+  const int32_t wbeg = (int32_t)g0 - HALO;
+#pragma unroll
+  for (int x = 0; x < N / 4; ++x) {
+    int32_t e = wbeg + 4 * x;  // places outside the array are masked below
+    e = e < 0 ? 0 : (e > (int32_t)NPOS - 4 ? (int32_t)NPOS - 4 : e);
+    const u32x4 v = *reinterpret_cast<const u32x4*>(clk + clk_word((uint32_t)e));
+    key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
+  }
+  {
+    const u32x4 ma = reinterpret_cast<const u32x4*>(meta)[tid > 0 ? tid - 1 : 0];
+    const u32x4 mb = reinterpret_cast<const u32x4*>(meta)[tid];
+    const u32x4 mc = reinterpret_cast<const u32x4*>(meta)[tid + 1];  // the array has 16 spare bytes
+    const uint32_t m12[12] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w, mc.x, mc.y, mc.z, mc.w};
+#pragma unroll
+    for (int y = 0; y < N; ++y) {
+      constexpr int kFirst = 16 - HALO;  // byte of the first window place inside the three 16-byte blocks
+      key[y] = (key[y] << 5) | ((m12[(kFirst + y) >> 2] >> (8 * ((kFirst + y) & 3))) & 0x1Fu);
+    }
+  }
+  if (__builtin_amdgcn_ballot_w64(wbeg < 0 || (uint32_t)(wbeg + N) > n_events)) {
+#pragma unroll
+    for (int y = 0; y < N; ++y) {  // places outside the sequence: first or last
+      const int32_t e = wbeg + y;
+      key[y] = e < 0 ? 0u : ((uint32_t)e < n_events ? key[y] : 0xFFFFFFFFu);
+    }
+  }
+  // Batcher's odd-even merge sort: a fixed network (191 exchanges of two registers for 32 words, 384 for
+  // 48), every index known at compile time.
+#pragma unroll
+  for (int pp = 1; pp < N; pp <<= 1) {
+#pragma unroll
+    for (int k = pp; k >= 1; k >>= 1) {
+#pragma unroll
+      for (int j = k % pp; j + k < N; j += 2 * k) {
+#pragma unroll
+        for (int i = 0; i < (k < N - j - k ? k : N - j - k); ++i) {
+          if ((i + j) / (2 * pp) == (i + j + k) / (2 * pp)) {
+            const uint32_t x = key[i + j], y = key[i + j + k];
+            key[i + j] = x < y ? x : y;
+            key[i + j + k] = x < y ? y : x;
+          }
+        }
+      }
+    }
+  }
+  ends = 0;
+#pragma unroll
+  for (int i = 0; i < kNR; ++i) {
+    const uint32_t k = key[HALO + i];
+    st[i] = k >> 5;
+    sx[i] = g0 + i < n_events ? 1u << ((k >> 1) & 15u) : 0u;
+    ends |= (k & 1u) << i;
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // init: clear the global totals, set min to all-ones, check the device header against the
 // geometry the launch was sized for.
@@ -225,7 +294,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L.pw_min);
   unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L.ctr);
   uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
-  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell scale
+  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell scale, [2] span
   uint2* sVF = reinterpret_cast<uint2*>(smem + L.vf);           // per wave: records held, first surviving seq
   uint32_t* wtot = reinterpret_cast<uint32_t*>(smem + L.wtot);
   uint32_t* ptot = reinterpret_cast<uint32_t*>(smem + L.ptot);
@@ -260,6 +329,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // its clock word; round j: cwe + 136 j (pbase is a multiple of 1024, lanes 32.. are past one padding)
     const uint32_t cwe = qe + (pbase >> 4) + ((lane >> 5) << 2);
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
+#ifdef KP_DEBUG_COUNT
+    uint32_t dbg_maxcell = 0;
+#endif
     // ---- workgroup header, clear the staging state -----------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
@@ -277,6 +349,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       uint64_t scale = ((uint64_t)NCELL << 32) / ((sp & 0xFFFFFFFFull) + 1ull);
       misc[0] = (sp >> 32) ? 1u : 0u;
       misc[1] = scale > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)scale;
+      misc[2] = (uint32_t)sp;
     }
     reinterpret_cast<u32x4*>(meta)[tid] = u32x4{0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu};
     reinterpret_cast<u32x4*>(cells)[2 * tid] = u32x4{0u, 0u, 0u, 0u};
@@ -425,14 +498,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // orphan, so only ENDs search.  In traces of kernels whose regions follow one another the START
       // sits one rank below: in the lane's own even position, or, for an END in the even position, in
       // the odd position of the lane below (DPP; the last lane of the previous round stands in for lane
-      // 0).  An END whose lower neighbour belongs to another region walks back through LDS.
+      // 0).  Both positions of a round are tested at once on the two metadata bytes side by side.  An
+      // END whose lower neighbour belongs to another region walks back through LDS.
       // A START learns that it is paired from its END: in the same lane directly, one lane up through a
       // DPP shift of the claims, and when the END is in another hardware wave or found the START by
       // walking, through a mark in the START's metadata byte that is read back after the barrier.
-      uint32_t c_nonmono = 0, c_pairs = 0, c_starts = 0, c_ends = 0, claims = 0;
+      uint32_t n_nonmono = 0, n_pairs = 0, n_ends = 0;  // wave-uniform counts
+      uint32_t claims = 0;
       bool marked = false;
       uint32_t cm = kEmpty, ct = 0;
       if (pbase > 0 && pbase < nrec) { cm = meta[pbase - 1]; ct = clk[clk_word(pbase - 1)]; }
+      auto count = [](bool b) -> uint32_t { return (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(b)); };
       auto walk_back = [&](uint32_t qq, uint32_t mine, bool& have, uint32_t& sm, uint32_t& sq, uint32_t& sts) {
         const uint32_t k = qq & capm, wofs = qq - k;
         for (uint32_t kk = k - 1; kk-- > 0;) {
@@ -443,42 +519,52 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
       for (int j = 0; j < kNR / 2; ++j) {
         const uint32_t q = qe + 128u * j;  // even position; the odd one is q + 1
-        const uint32_t m0 = meta_of(2 * j), m1 = meta_of(2 * j + 1), t0 = t[2 * j], t1 = t[2 * j + 1];
-        uint32_t pm = wave_shr1(m1, cm);
+        const uint32_t m2 = (mq[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;  // byte 0: even position, byte 1: odd
+        const uint32_t t0 = t[2 * j], t1 = t[2 * j + 1];
+        uint32_t pm = wave_shr1(m2 >> 8, cm);
         const uint32_t pt = wave_shr1(t1, ct);
-        cm = (uint32_t)__builtin_amdgcn_readlane((int)m1, 63);
+        cm = (uint32_t)__builtin_amdgcn_readlane((int)m2, 63) >> 8;
         ct = (uint32_t)__builtin_amdgcn_readlane((int)t1, 63);
-        const uint32_t k0 = q & capm, w = q >> cl2;
+        const uint32_t k0 = q & capm;
         pm = k0 > 0 ? pm : kEmpty;
-        const bool v0 = (m0 & kRegion) != kEmpty, v1 = (m1 & kRegion) != kEmpty;
-        const bool e0 = v0 && (m0 & kEnd), e1 = v1 && (m1 & kEnd);
-        bool have0 = ((m0 ^ pm) & kRegion) == 0u;  // the rank below holds a record of the same region
-        bool have1 = ((m1 ^ m0) & kRegion) == 0u;
-        uint32_t sm0 = pm, sm1 = m0, st0 = pt, st1 = t0, sq0 = 0, sq1 = 0;  // the candidate START
-        const bool deep0 = e0 && !have0 && k0 > 1, deep1 = e1 && !have1 && k0 > 0;
-        if (__builtin_amdgcn_ballot_w64(deep0 || deep1)) {
+        const uint32_t p2 = ((m2 << 8) | pm) & 0xFFFFu;  // the record one rank below each of the two
+        const uint32_t x2 = m2 ^ p2;
+        // bit 7 of each of the two bytes: that byte of the argument is not zero
+        auto nonzero7 = [](uint32_t v) -> uint32_t { return ((v & 0x7F7Fu) + 0x7F7Fu) | v; };
+        const uint32_t end2 = m2 & 0x8080u;                                   // is an END (no record: 0)
+        const uint32_t differ2 = nonzero7(x2 & 0x3F3Fu) & end2;               // END, other region one rank below
+        const uint32_t near2 = ~nonzero7((x2 & 0xBFBFu) ^ 0x8080u) & end2;    // END, START of its region one rank below
+        const uint32_t none2 = ((m2 & 0x3F3Fu) + 0x4141u) & 0x8080u;          // holds no record
+        bool p0 = (near2 & 0x80u) != 0u, p1 = (near2 & 0x8000u) != 0u;
+        uint32_t st0 = pt, st1 = t0;  // clock of the START
+        const bool v0 = !(none2 & 0x80u), v1 = !(none2 & 0x8000u);
+        n_nonmono += count(v0 && k0 > 0 && t0 < pt) + count(v1 && t1 < t0);
+        n_ends += count((end2 & 0x80u) != 0u) + count((end2 & 0x8000u) != 0u);
+        // as END, or as the START of the odd position; the mark of an END sits one bit above its flag
+        uint32_t flags = (near2 >> 1) | ((near2 >> 9) & kPaired);
+        claims |= (p0 ? 1u : 0u) << j;
+        if (j == 0 && p0 && lane == 0u && pbase > 0) meta[pbase - 1] = (uint8_t)(pm | kPaired);
+        if (__builtin_amdgcn_ballot_w64(differ2 != 0u)) {
+          const uint32_t m0 = m2 & 0xFFu, m1 = m2 >> 8;
+          const bool deep0 = (differ2 & 0x80u) && k0 > 1, deep1 = (differ2 & 0x8000u) && k0 > 0;
+          bool have0 = false, have1 = false;
+          uint32_t sm0 = 0, sm1 = 0, sq0 = 0, sq1 = 0;
           if (deep0) walk_back(q, m0, have0, sm0, sq0, st0);
           if (deep1) walk_back(q + 1, m1, have1, sm1, sq1, st1);
-        }
-        const bool p0 = e0 && have0 && !(sm0 & kEnd), p1 = e1 && have1 && !(sm1 & kEnd);
-        c_nonmono += ((v0 && k0 > 0 && t0 < pt) ? 1u : 0u) + ((v1 && t1 < t0) ? 1u : 0u);
-        c_starts += ((v0 && !e0) ? 1u : 0u) + ((v1 && !e1) ? 1u : 0u);
-        c_ends += (e0 ? 1u : 0u) + (e1 ? 1u : 0u);
-        c_pairs += (p0 ? 1u : 0u) + (p1 ? 1u : 0u);
-        const bool far0 = p0 && deep0, far1 = p1 && deep1, near0 = p0 && !deep0;
-        set_paired(2 * j, (p0 || (p1 && !deep1)) ? 1u : 0u);  // as END, or as the START of the odd position
-        set_paired(2 * j + 1, p1 ? 1u : 0u);
-        claims |= (near0 ? 1u : 0u) << j;
-        if (__builtin_amdgcn_ballot_w64(far0 || far1)) {
+          const bool far0 = have0 && !(sm0 & kEnd), far1 = have1 && !(sm1 & kEnd);
           if (far0) meta[sq0] = (uint8_t)(sm0 | kPaired);
           if (far1) meta[sq1] = (uint8_t)(sm1 | kPaired);
-          marked = true;
+          flags |= (far0 ? kPaired : 0u) | (far1 ? kPaired << 8 : 0u);
+          marked = marked || far0 || far1;
+          p0 = p0 || far0; p1 = p1 || far1;
         }
-        if (j == 0 && near0 && lane == 0u && pbase > 0) meta[pbase - 1] = (uint8_t)(sm0 | kPaired);
+        mq[j >> 1] |= flags << (16 * (j & 1));
+        n_pairs += count(p0) + count(p1);
+        const uint32_t w = q >> cl2;
+        if (p0 || p1) account_pair(w, (p1 ? m2 >> 8 : m2) & kRegion, p1 ? t1 - st1 : t0 - st0);
         const bool both = p0 && p1;
-        if (p0 || p1) account_pair(w, (p1 ? m1 : m0) & kRegion, p1 ? t1 - st1 : t0 - st0);
         if (__builtin_amdgcn_ballot_w64(both)) {
-          if (both) account_pair(w, m0 & kRegion, t0 - st0);
+          if (both) account_pair(w, m2 & kRegion, t0 - st0);
         }
       }
       // the START claimed by the even position of the lane above (lane 63: of lane 0 in the next round)
@@ -490,11 +576,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
                                                                    false);  // wave_shl:1
         set_paired(2 * j + 1, got);
       }
-      if (marked && lane == 0u) tmp[T_MARKS] = 1u;
-      add_tmp(tmp, T_NONMONO, c_nonmono);
-      add_tmp(tmp, T_PAIRS, c_pairs);
-      add_tmp(tmp, T_STARTS, c_starts);  // orphans = STARTs - pairs, ENDs - pairs
-      add_tmp(tmp, T_ENDS, c_ends);
+      const bool any_marked = __builtin_amdgcn_ballot_w64(marked) != 0;
+      if (lane == 0u) {
+        if (any_marked) tmp[T_MARKS] = 1u;
+        if (n_nonmono) atomicAdd(&tmp[T_NONMONO], n_nonmono);
+        if (n_pairs) atomicAdd(&tmp[T_PAIRS], n_pairs);
+        if (n_ends) atomicAdd(&tmp[T_ENDS], n_ends);
+      }
+      if (tid == 0) tmp[T_STARTS] = n_occupied;  // records; orphans = records - ENDs - pairs, ENDs - pairs
     } else {
       // ---- B, workgroup with holes: the definition, one thread per (wave, region) -----------------
       for (uint32_t e = tid; e < W * R; e += BLOCK) {
@@ -514,7 +603,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           have_prev = true; prev_m = mm; prev_t = ts;
         }
         if (n_pairs) atomicAdd(&tmp[T_PAIRS], n_pairs);
-        if (n_starts) atomicAdd(&tmp[T_STARTS], n_starts);
+        if (n_starts + n_ends) atomicAdd(&tmp[T_STARTS], n_starts + n_ends);
         if (n_ends) atomicAdd(&tmp[T_ENDS], n_ends);
       }
       for (uint32_t w = tid; w < W; w += BLOCK) {
@@ -546,9 +635,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // Straight-line code from here to the sorted sequence: the LDS operations of a lane's 16 records
       // are issued together and no array is assigned inside a branch.
       uint32_t ca[kNR];  // cell | arrival slot << 16; then: first place of the cell; then: place in the sorted sequence
+      uint32_t t_max = 0;
 #pragma unroll
       for (int i = 0; i < kNR; ++i) {
         const bool ev = (meta_of(i) & kPaired) != 0u;
+        t_max = ev && t[i] > t_max ? t[i] : t_max;
         uint32_t c = __umulhi(t[i], scale);
         c = c < NCELL - 1 ? c : NCELL - 1;
         const uint32_t sh = (c & 1u) << 4;
@@ -556,20 +647,30 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         const uint32_t old = atomicAdd(&cells[c >> 1], ev ? 1u << sh : 0u);
         ca[i] = c | (((old >> sh) & 0xFFFFu) << 16);
       }
+      if (__builtin_amdgcn_ballot_w64(t_max > misc[2]) && lane == 0u) tmp[T_WIDE] = 1u;  // a clock past the span
       __syncthreads();
       if (p.stop_after == kStepCounted) continue;
       {  // exclusive prefix sum over the cell counters, 16 cells (8 words) per thread
         u32x4 a = reinterpret_cast<u32x4*>(cells)[2 * tid], b = reinterpret_cast<u32x4*>(cells)[2 * tid + 1];
         uint32_t wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        uint32_t run = 0;
+        uint32_t run = 0, fullest = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const uint32_t lo = wv[i] & 0xFFFFu, hi = wv[i] >> 16;
+          fullest = lo > fullest ? lo : fullest;
+          fullest = hi > fullest ? hi : fullest;
           wv[i] = run | ((run + lo) << 16);
           run += lo + hi;
         }
         const uint32_t incl = wave_scan_add(run);
         if (lane == 63) wtot[hw] = incl;
+        {  // fullest cell of the workgroup
+          uint32_t f = fullest, o;
+          o = scan_src<0>(f); f = o > f ? o : f; o = scan_src<1>(f); f = o > f ? o : f;
+          o = scan_src<2>(f); f = o > f ? o : f; o = scan_src<3>(f); f = o > f ? o : f;
+          o = scan_src<4>(f); f = o > f ? o : f; o = scan_src<5>(f); f = o > f ? o : f;
+          if (lane == 63) atomicMax(&tmp[T_MAXCELL], f);
+        }
         __syncthreads();
         uint32_t base = incl - run;
         for (uint32_t h = 0; h < hw; ++h) base += wtot[h];
@@ -583,6 +684,26 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       __syncthreads();
       if (p.stop_after == kStepCellSums) continue;
       auto cell_start = [&](uint32_t c) -> uint32_t { return (cells[c >> 1] >> ((c & 1u) << 4)) & 0xFFFFu; };
+      // sorted sequence entry besides the clock: region << 1 | END
+      auto info_of = [&](int i) -> uint32_t { return ((meta_of(i) & 0x1Fu) << 1) | (meta_of(i) >> 7); };
+      // When clock and region fit one word and no cell holds more than kMaxCellWindow records, the records stay
+      // in arrival order inside their cell here and every lane of the sweep sorts a window of the sequence
+      // in registers; otherwise the records are ranked inside their cell first.
+      const bool window_sort = R <= 16u && misc[2] < (1u << 27) && !tmp[T_WIDE] && tmp[T_MAXCELL] <= kMaxCellWindow;
+#ifdef KP_DEBUG_COUNT
+      if (tid == 0) { ctr[H_RSVD] += window_sort ? 1u : 0u; ctr[H_CAP] += tmp[T_MAXCELL]; dbg_maxcell = tmp[T_MAXCELL]; }
+#endif
+      if (window_sort) {
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) {
+          const bool ev = (meta_of(i) & kPaired) != 0u;
+          const uint32_t g = cell_start(ca[i] & 0xFFFFu) + (ca[i] >> 16);
+          clk[ev ? clk_word(g) : kSpareWord] = t[i];  // no branch: the others all write one unused word
+          meta[ev ? g : NPOS] = (uint8_t)info_of(i);
+        }
+        __syncthreads();
+        if (p.stop_after >= kStepPlaced && p.stop_after <= kStepSorted) continue;
+      } else {
       // provisional place: cell start + arrival slot (plain index here, the padded layout comes with the
       // final places)
       uint32_t nm[kNR];  // records in the cell (0: this record is no event) | arrival slot << 16
@@ -597,48 +718,18 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       __syncthreads();
       if (p.stop_after == kStepPlaced) continue;
-      // rank among the records of the same cell: by clock, then by arrival slot.  The first records of
-      // every cell are read unconditionally (a read past the cell is masked out of the count), fuller
-      // cells finish in a loop.
-      {
-        constexpr uint32_t kFlat = 4;
-        uint32_t n_max = 0;
+      // rank among the records of the same cell: by clock, then by arrival slot
 #pragma unroll
-        for (int i = 0; i < kNR; ++i) n_max = (nm[i] & 0xFFFFu) > n_max ? (nm[i] & 0xFFFFu) : n_max;
-        // the record at arrival slot `it` of the cell comes before this one
-        auto before_me = [&](uint32_t tm, uint32_t t0, uint32_t it, uint32_t mine) -> uint32_t {
-          // written with bit operations: short-circuit conditions become branches around each LDS read
-          return (uint32_t)(tm < t0) | ((uint32_t)(tm == t0) & (uint32_t)(it < mine));  // the record's own entry gives 0
-        };
-#pragma unroll
-        for (uint32_t it = 0; it < kFlat; ++it) {
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            uint32_t tm[kNR / 2];
-#pragma unroll
-            for (int i = 0; i < kNR / 2; ++i) tm[i] = (clk + (ca[8 * half + i] & 0xFFFFu))[it];
-#pragma unroll
-            for (int i = 0; i < kNR / 2; ++i) {
-              const int r = 8 * half + i;
-              const uint32_t n = nm[r] & 0xFFFFu, mine = nm[r] >> 16;
-              ca[r] += ((uint32_t)(it < n) & before_me(tm[i], t[r], it, mine)) << 16;  // rank in the upper half for now
-            }
-            __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < kNR; ++i) {
+        const uint32_t n = nm[i] & 0xFFFFu, s0 = ca[i], mine = nm[i] >> 16, t0 = t[i];
+        uint32_t before = 0;
+        for (uint32_t it = 0; __builtin_amdgcn_ballot_w64(it < n); ++it) {
+          if (it < n) {
+            const uint32_t tm = clk[s0 + it];
+            before += (uint32_t)(tm < t0) | ((uint32_t)(tm == t0) & (uint32_t)(it < mine));  // the record's own entry gives 0
           }
         }
-        if (__builtin_amdgcn_ballot_w64(n_max > kFlat)) {
-#pragma unroll
-          for (int i = 0; i < kNR; ++i) {
-            const uint32_t n = nm[i] & 0xFFFFu, s0 = ca[i] & 0xFFFFu, mine = nm[i] >> 16, t0 = t[i];
-            uint32_t more = 0;
-            for (uint32_t it = kFlat; __builtin_amdgcn_ballot_w64(it < n); ++it) {
-              if (it < n) more += before_me(clk[s0 + it], t0, it, mine);
-            }
-            ca[i] += more << 16;
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < kNR; ++i) ca[i] = (ca[i] & 0xFFFFu) + (ca[i] >> 16);
+        ca[i] = s0 + before;
       }
       __syncthreads();
       if (p.stop_after == kStepRanked) continue;
@@ -646,22 +737,24 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       for (int i = 0; i < kNR; ++i) {
         const bool ev = (meta_of(i) & kPaired) != 0u;
         clk[ev ? clk_word(ca[i]) : kSpareWord] = t[i];
-        meta[ev ? ca[i] : NPOS] = (uint8_t)(meta_of(i) & ~kPaired);
+        meta[ev ? ca[i] : NPOS] = (uint8_t)info_of(i);
       }
       __syncthreads();
       if (p.stop_after == kStepSorted) continue;
+      }
 
       // ---- D: region-pair overlap, 16 consecutive records of the sorted sequence per lane ----------
       {
         const uint32_t n_events = tmp[T_EVENTS];
         const uint32_t g0 = tid * kNR;
         uint32_t st[kNR], sx[kNR];  // clock, region bit (0: no record)
-        const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
-        const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
-        auto end_mask = [&](int i) -> uint32_t {  // all ones for an END
-          return (uint32_t)((int32_t)(mw[i >> 2] << (24 - 8 * (i & 3))) >> 31);
-        };
-        {
+        uint32_t ends = 0;           // bit i: record i is an END
+        if (window_sort) {
+          if (tmp[T_MAXCELL] <= 9u) sorted_window<8, NPOS>(clk, meta, tid, n_events, st, sx, ends);
+          else sorted_window<16, NPOS>(clk, meta, tid, n_events, st, sx, ends);
+        } else {
+          const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
+          const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
           const u32x4* tv = reinterpret_cast<const u32x4*>(clk + clk_word(g0));
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -671,9 +764,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
           for (int i = 0; i < kNR; ++i) {
             const uint32_t info = (mw[i >> 2] >> (8 * (i & 3))) & 0xFFu;
-            sx[i] = g0 + i < n_events ? 1u << (info & 31u) : 0u;
+            sx[i] = g0 + i < n_events ? 1u << (info >> 1) : 0u;
+            ends |= (info & 1u) << i;
           }
         }
+        auto end_mask = [&](int i) -> uint32_t { return (uint32_t)((int32_t)(ends << (31 - i)) >> 31); };  // all ones for an END
         uint32_t pl[PLANES];
 #pragma unroll
         for (int k = 0; k < PLANES; ++k) pl[k] = 0u;
@@ -763,6 +858,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       const unsigned long long s = pk & ((1ull << 46) - 1);
       uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + e) * 2;
       dst[0] = s;
+#ifdef KP_DEBUG_COUNT
+      if (e == 0) { dst[0] = dbg_maxcell; }
+#endif
       dst[1] = (uint64_t)n | ((uint64_t)mx << 32);
       if (n) {
         const uint32_t r = e % R;
@@ -787,7 +885,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_DISORDER] += tmp[T_DISORDER];
       ctr[H_NONMONO] += tmp[T_NONMONO];
       ctr[H_PAIRS] += tmp[T_PAIRS];
-      ctr[H_ORPHAN_START] += tmp[T_STARTS] - tmp[T_PAIRS];
+      ctr[H_ORPHAN_START] += tmp[T_STARTS] - tmp[T_ENDS] - tmp[T_PAIRS];  // T_STARTS counts the records
       ctr[H_ORPHAN_END] += tmp[T_ENDS] - tmp[T_PAIRS];
       ctr[H_SPAN_OVF] += misc[0];
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
@@ -811,6 +909,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
   }
   if (tid_k < H_STATUS && ctr[tid_k]) atomicAdd(&out[tid_k], ctr[tid_k]);
+#ifdef KP_DEBUG_COUNT
+  if (tid_k == H_RSVD || tid_k == H_CAP) atomicAdd(&out[tid_k], ctr[tid_k]);
+#endif
 }
 
 // Launch shape of one kernel instantiation for one LDS size, queried once per device.
