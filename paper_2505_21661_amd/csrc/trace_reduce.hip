@@ -170,6 +170,7 @@ __device__ __forceinline__ void planes_step(uint32_t (&pl)[PLANES], uint32_t x, 
 // registers: one word per record, clock << 5 | region << 1 | END (records with equal words are
 // interchangeable).  Cells follow one another in clock order, so sorting the words sorts every cell and
 // moves no record out of its cell.  Outputs: clock, region bit (0 past the end of the sequence), END bits.
+// (Only the lane's own 16 places come out right: the cell of the place after them may reach past the window.)
 template <int HALO, uint32_t NPOS>
 __device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events,
                                               uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
@@ -803,6 +804,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
           for (int k = 0; k < PLANES; ++k) ptot[hw * 8 + k] = inc[k];
         }
+        if (lane == 0) wtot[hw] = st[0];  // first clock of this wave's stretch, for the last lane of the wave below
         __syncthreads();
         // state before this lane's stretch: lanes below in this wave + all waves below
 #pragma unroll
@@ -813,6 +815,104 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           for (int k = 0; k < PLANES; ++k) o[k] = ptot[h * 8 + k];
           planes_add<PLANES>(pl, o);
         }
+        // ---- the sorted sequence as segments: the set of active regions after record k and the ticks
+        // until record k + 1.  O[a][b] = sum over segments of ticks * active(a) * active(b) is a 16 x K by
+        // K x 16 matrix product: the matrix cores take it 64 segments at a time (i8 operands: the ticks in
+        // 7-bit limbs, one product per limb), and no accumulator atomics are left in the sweep.
+        bool swept = false;
+        if (window_sort) {
+          uint32_t limb[3][4];  // limb l of the 16 lengths, one byte each
+          uint32_t any_len = 0;
+          // clock of the record after the lane's 16: the first one of the lane above
+          const uint32_t t_next = (uint32_t)__builtin_amdgcn_update_dpp((int)wtot[hw + 1 < BLOCK / 64 ? hw + 1 : hw], (int)st[0],
+                                                                        0x130, 0xF, 0xF, false);  // wave_shl:1
+#pragma unroll
+          for (int l = 0; l < 3; ++l)
+#pragma unroll
+            for (int y = 0; y < 4; ++y) limb[l][y] = 0u;
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) {
+            const uint32_t after = i + 1 < kNR ? st[i + 1] : t_next;
+            const uint32_t len = g0 + i + 1 < n_events ? after - st[i] : 0u;
+            any_len |= len;
+#pragma unroll
+            for (int l = 0; l < 3; ++l) limb[l][i >> 2] |= ((len >> (7 * l)) & 0x7Fu) << (8 * (i & 3));
+          }
+          {  // OR over the wave
+            uint32_t f = any_len;
+            f |= scan_src<0>(f); f |= scan_src<1>(f); f |= scan_src<2>(f);
+            f |= scan_src<3>(f); f |= scan_src<4>(f); f |= scan_src<5>(f);
+            any_len = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
+          }
+          if (any_len < (1u << 21)) {  // else: a gap of more than three limbs, the loop below takes this wave
+            swept = true;
+            const uint32_t n_limbs = any_len < (1u << 7) ? 1u : (any_len < (1u << 14) ? 2u : 3u);
+            uint32_t mk[kNR / 2];  // active sets after records 2x and 2x + 1
+#pragma unroll
+            for (int x = 0; x < kNR / 2; ++x) mk[x] = 0u;
+#pragma unroll
+            for (int i = 0; i < kNR; ++i) {
+              planes_step<PLANES>(pl, sx[i], end_mask(i));
+              uint32_t act = pl[0];
+#pragma unroll
+              for (int k = 1; k < PLANES; ++k) act |= pl[k];
+              mk[i >> 1] |= act << (16 * (i & 1));
+            }
+            // The lane's own 16 places of the sequence are free now (every window was read before the last
+            // barrier): they take the active sets and two limbs, the 16 metadata bytes the third limb.
+            u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
+            own[0] = u32x4{mk[0], mk[1], mk[2], mk[3]};
+            own[1] = u32x4{mk[4], mk[5], mk[6], mk[7]};
+            own[2] = u32x4{limb[0][0], limb[0][1], limb[0][2], limb[0][3]};
+            own[3] = u32x4{limb[1][0], limb[1][1], limb[1][2], limb[1][3]};
+            reinterpret_cast<u32x4*>(meta)[tid] = u32x4{limb[2][0], limb[2][1], limb[2][2], limb[2][3]};
+            __builtin_amdgcn_wave_barrier();
+            if ((tid & ~63u) * kNR < n_events) {  // this wave holds records
+              typedef int i32x4 __attribute__((ext_vector_type(4)));
+              i32x4 acc[3];
+#pragma unroll
+              for (int l = 0; l < 3; ++l) acc[l] = i32x4{0, 0, 0, 0};
+              const uint32_t j = lane & 15u;  // operand row / column: region j
+              const uint32_t sel = j < 8u ? 0x06040200u : 0x07050301u;  // low or high byte of four 16-bit sets
+              for (uint32_t n = 0; n < 16; ++n) {  // 64 segments: those of lanes 4n .. 4n + 3
+                const uint32_t src = (tid & ~63u) + 4u * n + (lane >> 4);
+                const u32x4* from = reinterpret_cast<const u32x4*>(clk + clk_word(src * kNR));
+                const u32x4 s0 = from[0], s1 = from[1];
+                const uint32_t w8[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                i32x4 bits, ones;
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                  const uint32_t g = __builtin_amdgcn_perm(w8[2 * y + 1], w8[2 * y], sel);
+                  const uint32_t b = (g >> (j & 7u)) & 0x01010101u;  // region j active in segments 4y .. 4y + 3
+                  bits[y] = (int)b;
+                  ones[y] = (int)((b << 8) - b);
+                }
+                const u32x4 l0 = from[2];
+                acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l0.x, (int)l0.y, (int)l0.z, (int)l0.w}, bits,
+                                                               acc[0], 0, 0, 0);
+                if (n_limbs > 1u) {
+                  const u32x4 l1 = from[3];
+                  acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l1.x, (int)l1.y, (int)l1.z, (int)l1.w}, bits,
+                                                                 acc[1], 0, 0, 0);
+                }
+                if (n_limbs > 2u) {
+                  const u32x4 l2 = reinterpret_cast<const u32x4*>(meta)[src];
+                  acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l2.x, (int)l2.y, (int)l2.z, (int)l2.w}, bits,
+                                                                 acc[2], 0, 0, 0);
+                }
+              }
+              // element v of a lane: row 4 * (lane / 16) + v, column lane % 16.  The product is symmetric and the
+              // fold below adds the two halves of a pair: the upper triangle takes the whole sum.
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const uint32_t a = 4u * (lane >> 4) + v, b = j;
+                const uint32_t total = (uint32_t)acc[0][v] + ((uint32_t)acc[1][v] << 7) + ((uint32_t)acc[2][v] << 14);
+                if (a <= b && b < R && total) atomicAdd(&oacc32[a * (R | 1u) + b], total);
+              }
+            }
+          }
+        }
+        if (!swept) {
 #pragma unroll
         for (int i = 0; i < kNR; ++i) {
           const uint32_t x = sx[i], dm = end_mask(i), tt = st[i];
@@ -837,6 +937,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
               atomicAdd(&row[bb], val);
             }
           }
+        }
         }
       }
     }
