@@ -333,11 +333,27 @@ kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void
  * payloads and the workgroup header's t_begin / t_end are in that clock's ticks, and the header's
  * reserved word holds the same span on the other clock.  mode bit3 selects wave-group granularity
  * as KP_MASK_WAVE_GROUP does (waves must then be a multiple of 4; the trace holds waves / 4 streams).
+ * mode bits 4 and 5 select the form of the record sites, which the instrumented kernels also choose
+ * among and which decides the constant a region is measured too long by: neither bit the generic sites
+ * (region mask, either strategy, either clock), bit 4 the lean sites (all regions, circular strategy:
+ * the attention kernel and the small GEMM), bit 5 the deferred sites of the 256x256x64 GEMM; with
+ * either bit, bits 1..3 must be 0 (KP_ERR_INVALID_ARG otherwise).
  *   cycles     HOST pointer to n_regions values (n_regions <= 32)
  *   trace_buf  device, kp_trace_bytes(n_wg, streams, trace_cap) bytes; trace_cap as above
  */
 kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_wg, int waves, int mode,
                        void* trace_buf, size_t trace_cap, void* stream);
+
+/*
+ * The constant that replay takes off every measured duration (Sec. 4.3: the record's own cost is
+ * compensated by offsetting a constant; Sec. 5.4 measures it).  A region is measured from the clock
+ * read of its START site to the clock read of its END site, which includes the instructions of the
+ * sites themselves: an empty region of kp_calibrate reads exactly that constant.  Every trace recorded
+ * after kp_set_rec_cost(ticks) carries `ticks` in kp_trace_hdr.rec_cost (process-wide, default 0; the
+ * value is read when a recording call is made, not when its kernel runs).
+ */
+void kp_set_rec_cost(uint32_t ticks);
+uint32_t kp_get_rec_cost(void);
 
 #ifdef __cplusplus
 }

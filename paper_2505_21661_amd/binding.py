@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.kp_stages_bytes.argtypes = [ci, ci, ci]
         L.kp_pairs_stages.restype = ci
         L.kp_pairs_stages.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+        L.kp_set_rec_cost.restype = None
+        L.kp_set_rec_cost.argtypes = [u32]
+        L.kp_get_rec_cost.restype = u32
+        L.kp_get_rec_cost.argtypes = []
         _optional(L)
         _lib = L
     return _lib
@@ -145,6 +149,14 @@ def kp_trace_bytes(n_wg: int, waves_per_wg: int, cap_per_wg: int) -> int:
 
 def kp_stats_bytes(n_wg: int, waves_per_wg: int, n_regions: int) -> int:
     return lib().kp_stats_bytes(n_wg, waves_per_wg, n_regions)
+
+
+def kp_set_rec_cost(ticks: int) -> None:
+    lib().kp_set_rec_cost(int(ticks))
+
+
+def kp_get_rec_cost() -> int:
+    return int(lib().kp_get_rec_cost())
 
 
 def kp_trace_reduce(raw, n: int, out_stats, stream=None) -> None:

@@ -36,6 +36,7 @@ struct AttnArgs {
   uint32_t region_mask;
   void* trace;
   uint32_t cap_lds, cap_hbm, flush, n_wg;
+  uint32_t rec_cost;  // ticks the decoder takes off every duration (kp_set_rec_cost)
   uint32_t group_log2;  // 2^group_log2 waves share one record stream
 };
 
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     if constexpr (INSTR == 2) kp::lean_end(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
+    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -348,7 +349,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   if (flush && cap_lds > 64) cap_lds = 64;
   const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
-  g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
+  g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   static thread_local int attr_dev = -1;  // the attribute is kept per device
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));

@@ -18,6 +18,7 @@ struct CalibArgs {
   uint32_t cycles[KP_MAX_REGIONS];
   uint32_t n_regions;
   uint32_t mode;
+  uint32_t rec_cost;
 };
 
 // n dependent FMAs (rounded down to a multiple of 16); each waits for the previous result.
@@ -38,7 +39,14 @@ __device__ __forceinline__ void busy_sleep(uint32_t n) {
   for (uint32_t i = n; i; --i) asm volatile("s_sleep 1");
 }
 
-template <bool REALTIME, bool GROUPS>
+__device__ __forceinline__ void busy(uint32_t mode, uint32_t len, float& x) {
+  if (mode == 0) busy_fma(len >> 2, x); else busy_sleep(len >> 6);
+}
+
+// SITE: the form of the record sites (kp_record.h): 1 generic, 2 lean (records written to LDS at the
+// next site), 4 deferred (clock reads parked in scalar registers, committed after the region).  The
+// instrumented kernels use all three; a region costs a different constant with each.
+template <bool REALTIME, bool GROUPS, int SITE>
 __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace, uint32_t cap_lds,
                                                         uint32_t cap_hbm, uint32_t flush, uint32_t n_wg,
                                                         uint32_t streams, uint32_t group_log2, float* sink) {
@@ -51,21 +59,40 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
   // Two identical passes: the first warms the instruction cache and is then discarded by
   // resetting the ring state, so that no recorded region pays for a cold code fetch.
   for (int pass = 0; pass < 2; ++pass) {
-    r.cnt = 0;
-    r.stored = 0;
-    r.pend_tag = kp::kNoPending;
-    r.pend_tag2 = kp::kNoPending;
-    for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
-      const uint32_t len = a.cycles[rg];
-      kp::record<REALTIME>(r, rg, kp::kPhaseStart);
-      if (a.mode == 0) busy_fma(len >> 2, x); else busy_sleep(len >> 6);
-      kp::record<REALTIME>(r, rg, kp::kPhaseEnd);
+    if constexpr (SITE == 1) {
+      r.cnt = 0;
+      r.stored = 0;
+      r.pend_tag = kp::kNoPending;
+      r.pend_tag2 = kp::kNoPending;
+      for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
+        kp::record<REALTIME>(r, rg, kp::kPhaseStart);
+        busy(a.mode, a.cycles[rg], x);
+        kp::record<REALTIME>(r, rg, kp::kPhaseEnd);
+      }
+      if (pass == 0) kp::store_pending(r);
+    } else if constexpr (SITE == 2) {
+      kp::lean_begin(r);
+      for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
+        kp::boundary_fast(r, kp::kNoRegion, rg);
+        busy(a.mode, a.cycles[rg], x);
+        kp::boundary_fast(r, rg, kp::kNoRegion);
+      }
+      if (pass == 0) (void)kp::clock_delta(r.pend_t, r.t0_lo);  // the last clock read has to land before the reset
+      else kp::lean_end(r);
+    } else {
+      kp::deferred_begin(r);
+      for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
+        kp::site_defer<0>(r, kp::kNoRegion, rg);
+        busy(a.mode, a.cycles[rg], x);
+        kp::site_defer<1>(r, rg, kp::kNoRegion);
+        kp::sites_commit<2>(r);
+      }
+      if (pass == 1) kp::deferred_end<0>(r);
     }
-    if (pass == 0) kp::store_pending(r);
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
   kp::TraceGeom g{n_wg, streams, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
-  kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, 0u);
+  kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, a.rec_cost);
 }
 
 }  // namespace
@@ -74,8 +101,11 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
                                   void* trace_buf, size_t trace_cap, void* stream) {
   kp::clear_error();
   if (!cycles || !trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
-  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~15))
+  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~63))
     return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
+  const int site = (mode & 16) ? 2 : ((mode & 32) ? 4 : 1);
+  if ((mode & 48) == 48 || (site != 1 && (mode & (2 | 4 | 8))))
+    return kp::fail(KP_ERR_INVALID_ARG, "mode=%d: the lean and deferred site forms record per wave, on the shader clock, circular", mode);
   const uint32_t group_log2 = (mode & 8) ? 2u : 0u;
   if (group_log2 && (waves & 3)) return kp::fail(KP_ERR_INVALID_ARG, "wave-group records need a multiple of 4 waves, got %d", waves);
   const size_t streams = (size_t)(waves >> group_log2);
@@ -93,20 +123,23 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
   for (int i = 0; i < n_regions; ++i) a.cycles[i] = cycles[i];
   a.n_regions = (uint32_t)n_regions;
   a.mode = (uint32_t)(mode & 1);
+  a.rec_cost = kp::rec_cost();
   // more than half of the CU's LDS per workgroup: one workgroup per CU, one wave per SIMD for waves <= 4
   const uint32_t lds_bytes = 96 * 1024;
   static thread_local int attr_dev = -1;  // the attribute is kept per device
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
   if (attr_dev != dev) {
-    for (auto k : {kp_calib_kernel<false, false>, kp_calib_kernel<true, false>, kp_calib_kernel<false, true>,
-                   kp_calib_kernel<true, true>})
+    for (auto k : {kp_calib_kernel<false, false, 1>, kp_calib_kernel<true, false, 1>, kp_calib_kernel<false, true, 1>,
+                   kp_calib_kernel<true, true, 1>, kp_calib_kernel<false, false, 2>, kp_calib_kernel<false, false, 4>})
       KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)lds_bytes));
     attr_dev = dev;
   }
-  auto kern = group_log2 ? ((mode & 4) ? kp_calib_kernel<true, true> : kp_calib_kernel<false, true>)
-                         : ((mode & 4) ? kp_calib_kernel<true, false> : kp_calib_kernel<false, false>);
+  auto kern = site == 2 ? kp_calib_kernel<false, false, 2>
+            : site == 4 ? kp_calib_kernel<false, false, 4>
+            : group_log2 ? ((mode & 4) ? kp_calib_kernel<true, true, 1> : kp_calib_kernel<false, true, 1>)
+                         : ((mode & 4) ? kp_calib_kernel<true, false, 1> : kp_calib_kernel<false, false, 1>);
   hipLaunchKernelGGL(kern, dim3(n_wg), dim3(waves * 64), lds_bytes, static_cast<hipStream_t>(stream),
                      a, trace_buf, cap_lds, (uint32_t)cap_wave, flush, (uint32_t)n_wg, (uint32_t)streams, group_log2,
                      static_cast<float*>(nullptr));

@@ -31,6 +31,7 @@ struct GemmArgs {
   uint32_t region_mask;
   void* trace;
   uint32_t cap_lds, cap_hbm, flush, n_wg;
+  uint32_t rec_cost;  // ticks the decoder takes off every duration (kp_set_rec_cost)
   uint32_t group_log2;  // 2^group_log2 waves share one record stream
 };
 
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     kp::sites_end<SITE>(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
+    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
     if constexpr (SITE == 4) kp::deferred_end<2>(ring);  // the sites that opened and closed the epilogue
     else kp::sites_end<SITE>(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, 0u);
+    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -464,7 +465,7 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (flush && cap_lds > 64) cap_lds = 64;
   const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
-  g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave;
+  g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
   const bool lean = !flush && !group_log2 && regions == (1u << s.regions) - 1u && K <= (1 << 22);
   if (big) return lean ? launch_big_w<2>(s.waves, g, n_wg, ring_bytes, st) : launch_big_w<1>(s.waves, g, n_wg, ring_bytes, st);

@@ -1,7 +1,12 @@
 // Size helpers and per-thread error text of the C ABI.
+#include <atomic>
+
 #include "kp_common.h"
 
 namespace kp {
+static std::atomic<uint32_t> g_rec_cost{0};
+uint32_t rec_cost() { return g_rec_cost.load(std::memory_order_relaxed); }
+
 char* last_error_buf() {
   static thread_local char buf[kLastErrorLen] = {0};
   return buf;
@@ -22,3 +27,6 @@ extern "C" size_t kp_stats_bytes(int n_wg, int waves_per_wg, int n_regions) {
   return sizeof(kp_stats_hdr) + 8 * (KP_HIST_BINS * R + 5 * R + 2 * R * R) +
          sizeof(kp_wave_region_stat) * (size_t)n_wg * waves_per_wg * R;
 }
+
+extern "C" void kp_set_rec_cost(uint32_t ticks) { kp::g_rec_cost.store(ticks, std::memory_order_relaxed); }
+extern "C" uint32_t kp_get_rec_cost(void) { return kp::rec_cost(); }

@@ -10,6 +10,7 @@
 namespace kp {
 
 char* last_error_buf();
+uint32_t rec_cost();  // the value of kp_set_rec_cost: goes into the header of every trace recorded from now on
 constexpr int kLastErrorLen = 512;
 
 inline kp_status fail(kp_status code, const char* fmt, ...) {

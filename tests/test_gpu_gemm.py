@@ -284,3 +284,34 @@ def test_full_size_gemm_4096(kp, oracle_mod):
     per = n_wg * waves
     assert st["cnt"].tolist() == [64 * per, 64 * per, 64 * per, per]
     assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_span_overflow_wgs"] == 0
+
+
+def test_real_trace_carries_the_record_cost(kp, oracle_mod):
+    """Replay takes the constant cost of a record off every duration (Sec. 4.3).  The cost set with
+    kp_set_rec_cost goes into the header of a trace recorded afterwards, and both decoders subtract it:
+    the durations of a real GEMM trace drop by exactly that much per pair (none of them is shorter)."""
+    from tests.gpu_util import assert_stats_equal
+
+    a, b = inputs.gemm_inputs(256, 256, 256, seed=0, dist="uniform")
+    stats = {}
+    for cost in (0, 37):
+        kp.kp_set_rec_cost(cost)
+        try:
+            _, trace, (n_wg, waves, R) = run_gemm(kp, a, b, 0b111, trace_cap=512)
+        finally:
+            kp.kp_set_rec_cost(0)
+        raw = trace.cpu().numpy().view(np.uint32).copy()
+        assert raw[6] == cost
+        out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+        kp.kp_trace_reduce(trace, n_wg * waves * 128, out)
+        torch.cuda.synchronize()
+        assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+        stats[cost] = (kp.parse_stats(out), raw)
+    st, raw = stats[37]
+    # the same trace decoded without the compensation: every pair is 37 ticks longer
+    raw0 = raw.copy()
+    raw0[6] = 0
+    st0 = oracle_mod.view_stats(oracle_mod.decode_bytes(raw0, 8))
+    assert st0["min"].min() > 37
+    assert np.array_equal(st0["sum"] - st["sum"], 37 * st["cnt"])
+    assert np.array_equal(st0["U"], st["U"])  # overlap uses the uncompensated intervals
