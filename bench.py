@@ -3,7 +3,9 @@
 
 One step = one pass of the whole hot path over one batch of seeded synthetic input:
   1. bf16 GEMM 4096^3: one warm launch, then uninstrumented / instrumented (all 4 regions, ring of
-     4096 records per workgroup) launched alternately, two of each
+     4096 records per workgroup) launched alternately, two of each; then the same for the
+     stage-by-stage schedule of the K step with its configured 5 regions (514 records per wave),
+     and two launches with a region masked off (generic record sites)
   2. kp_trace_reduce of the GEMM trace
   3. causal attention forward 4x32x4096x128: warm launch, then uninstrumented / instrumented
      (3 regions, ring of 1024 records per workgroup, wraps) alternately, two of each
@@ -46,6 +48,158 @@ TRAFFIC_BYTES = {
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
 
+def cpu_baseline(args, inputs, a, b, q, k, v) -> dict:
+    """The CPU oracle as it stands, timed on the host cores of the GPU machine on bounded samples of the
+    benchmark's own workloads (about 10 s for the decoder, a few seconds for the others)."""
+    import numpy as np
+
+    import oracle
+
+    host_cpus = os.cpu_count() or 1
+    threads = min(host_cpus, 16)
+    sample_log2 = min(args.log2_records, 23)
+    sraw, _ = inputs.gen_trace(inputs.spec_decode_standalone(sample_log2))
+    n = 1 << sample_log2
+
+    def decode_rate(n_threads: int, budget_s: float, max_reps: int) -> tuple[float, int]:
+        oracle.decode_bytes(sraw, n_threads)  # warm-up
+        c0 = time.perf_counter()
+        reps = 0
+        while True:
+            oracle.decode_bytes(sraw, n_threads)
+            reps += 1
+            if time.perf_counter() - c0 > budget_s or reps >= max_reps:
+                break
+        return reps * n / (time.perf_counter() - c0), reps
+
+    multi, reps = decode_rate(threads, 10.0, 20)
+    single, reps1 = decode_rate(1, 5.0, 2)
+    # dense legs: 128 rows of the 4096^3 GEMM, 128 query rows of one attention head (numpy fp64)
+    rows = np.arange(0, 4096, 32)
+    c0 = time.perf_counter()
+    oracle.ref_gemm(a, b, rows=rows)
+    t_gemm = time.perf_counter() - c0
+    rows_a = np.arange(31, 4096, 32)
+    c0 = time.perf_counter()
+    oracle.ref_attn(q[0, 0], k[0, 0], v[0, 0], causal=True, rows=rows_a)
+    t_attn = time.perf_counter() - c0
+    return {
+        "value": round(multi, 1),
+        "unit": "records/s (trace decode)",
+        "cores": threads,
+        "host_cpus": host_cpus,
+        "kind": "oracle",
+        "sample": f"{reps} x the first 2^{sample_log2} records' worth of the decode workload "
+                  f"({n // 16384} workgroups x 8 waves x 2048 records), OpenMP over workgroups",
+        "single_thread": {"value": round(single, 1), "unit": "records/s (trace decode)", "cores": 1,
+                          "sample": f"{reps1} x the same 2^{sample_log2} records"},
+        "gemm": {"value": round(2.0 * len(rows) * 4096 * 4096 / t_gemm / 1e9, 2), "unit": "GFLOP/s (fp64, numpy)",
+                 "sample": f"{len(rows)} of the 4096 output rows of the 4096^3 GEMM (conversion to fp64 included)"},
+        "attention": {"value": round(4.0 * float((rows_a + 1).sum()) * 128 / t_attn / 1e9, 2),
+                      "unit": "GFLOP/s (fp64, numpy; causal FLOPs)",
+                      "sample": f"{len(rows_a)} of the 4096 query rows of one (batch, head) of the attention workload"},
+    }
+
+
+def decode_steps(args) -> int:
+    """Cost of every step of the decoder (profiles/decode_steps.md is this table)."""
+    import numpy as np
+    import torch
+
+    import inputs
+    import paper_2505_21661_amd as kp
+
+    spec = inputs.spec_decode_standalone(args.log2_records)
+    raw, _ = inputs.gen_trace(spec)
+    n = spec.n_slots
+    dev_raw = torch.from_numpy(raw.view(np.int32)).cuda()
+    out = torch.zeros(kp.kp_stats_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device="cuda")
+    hdr = kp.make_hdr(spec.n_wg, spec.waves, spec.n_regions, spec.cap_wave)
+
+    def timed(f, reps=10):
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    steps = ["records ordered by sequence number (load, scatter by rank)", "paired, durations and histogram",
+             "paired records counted into time cells", "prefix sum over the cells", "records placed cell by cell",
+             "ranked inside their cell (only without the register sort)", "sorted sequence written (likewise)",
+             "register sort of the windows, region-pair overlap"]
+    rows, prev = [], 0.0
+    for i, what in enumerate(steps, 1):
+        t = timed(lambda: kp.kp_trace_reduce_steps(dev_raw, n, hdr, out, i))
+        rows.append({"step": i, "what": what, "ms_up_to_here": round(t, 4), "ms_of_step": round(t - prev, 4)})
+        prev = t
+    full = timed(lambda: kp.kp_trace_reduce_hdr(dev_raw, n, hdr, out))
+    rows.append({"step": 9, "what": "per-(workgroup, wave, region) output, totals, init and finalize kernels",
+                 "ms_up_to_here": round(full, 4), "ms_of_step": round(full - prev, 4)})
+    print(json.dumps({"records": n, "steps": rows, "hbm_frac": round(DECODE_BYTES_PER_RECORD * n / (full * 1e-3) / 1e9
+                                                                      / PEAK_HBM_GBS, 4)}))
+    return 0
+
+
+def probe(args) -> int:
+    """Every hot kernel twice (the second launch is the one to read), after a plain 1 GiB copy that scales
+    the HBM counters: FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; divide a kernel's reading by
+    the copy kernel's reading per GiB to get bytes."""
+    import numpy as np
+    import torch
+
+    import inputs
+    import paper_2505_21661_amd as kp
+
+    dev = "cuda"
+    src = torch.arange(1 << 28, dtype=torch.int32, device=dev)  # 1 GiB
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        torch.add(src, 1, out=dst)  # one elementwise kernel: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del src, dst
+    M = N = K = 4096
+    a, b = inputs.gemm_inputs(M, N, K, seed=2)
+    A, B = a.to(dev), b.to(dev)
+    C = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
+    n_wg, waves, R = kp.kp_gemm_launch_shape(M, N, K)
+    trace = torch.zeros(kp.kp_trace_bytes(n_wg, waves, 4096), dtype=torch.uint8, device=dev)
+    for mask in (0, 0b1111, kp.KP_MASK_PHASES, kp.KP_MASK_PHASES | 0b11111):
+        for _ in range(2):
+            kp.kp_gemm_instrumented(A, B, C, M, N, K, mask, trace if mask & 31 else None, 4096 if mask & 31 else 0)
+    torch.cuda.synchronize()
+    Bt, H, S, D = 4, 32, 4096, 128
+    q, k, v = inputs.attn_inputs(Bt, H, S, D, seed=3)
+    Q, Kt, V = q.to(dev), k.to(dev), v.to(dev)
+    O = torch.empty_like(Q)
+    for _ in range(2):
+        kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, 1.0 / math.sqrt(D), 0, None, 0)
+    torch.cuda.synchronize()
+    spec = inputs.spec_decode_standalone(args.log2_records)
+    raw, _ = inputs.gen_trace(spec)
+    n = spec.n_slots
+    d_raw = torch.from_numpy(raw.view(np.int32)).to(dev)
+    hdr = kp.make_hdr(spec.n_wg, spec.waves, spec.n_regions, spec.cap_wave)
+    stats = torch.zeros(kp.kp_stats_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
+    pairs = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8, device=dev)
+    waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
+    stages = torch.empty(kp.kp_stages_bytes(spec.n_wg, spec.n_regions, 64), dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        kp.kp_trace_reduce_hdr(d_raw, n, hdr, stats)
+    for _ in range(2):
+        kp.kp_trace_pairs_hdr(d_raw, n, hdr, pairs)
+    for _ in range(2):
+        kp.kp_trace_waits_hdr(d_raw, n, hdr, waits)
+    for _ in range(2):
+        kp.kp_pairs_stages(pairs, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions, 64, stages)
+    torch.cuda.synchronize()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,11 +207,21 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--log2-records", type=int, default=28, help="size of the standalone decode workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-steps", action="store_true",
+                    help="instead of the benchmark: time the decoder cut short after each of its steps "
+                         "(kp_trace_reduce_steps) and print the cost of every step")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark: launch every hot kernel twice, after a 1 GiB copy, "
+                         "for hardware-counter runs (rocprofv3 --pmc ... -- python3 bench.py --probe)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         return 2
+    if args.decode_steps:
+        return decode_steps(args)
+    if args.probe:
+        return probe(args)
 
     import numpy as np
     import torch
@@ -111,17 +275,22 @@ def main() -> int:
     # clock sags over a burst of MFMA kernels, and in this order both kinds sit at the same mean
     # position in the burst; every launch is inside the timed step.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_instr2", "gemm_vanilla2", "gemm_reduce",
+             "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm_masked", "gemm_masked2",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_instr2", "attn_vanilla2", "attn_reduce", "decode",
              "timeline", "waits", "stages"]
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
         gemm_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1111, g_trace, g_cap)
+        gemm5_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, kp.KP_MASK_PHASES, None, 0)
+        gemm5_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b11111 | kp.KP_MASK_PHASES, g_trace, g_cap)
+        gemm_m = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011, g_trace, g_cap)
         attn_v = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0, None, 0)
         attn_i = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0b111, a_trace, a_cap)
         calls = (
             gemm_v, gemm_v, gemm_i, gemm_i, gemm_v,
             lambda: kp.kp_trace_reduce_hdr(g_trace, g_wg * g_cap, g_hdr, g_stats),
+            gemm5_v, gemm5_i, gemm5_i, gemm5_v, gemm_m, gemm_m,
             attn_v, attn_v, attn_i, attn_i, attn_v,
             lambda: kp.kp_trace_reduce_hdr(a_trace, a_wg * a_cap, a_hdr, a_stats),
             lambda: kp.kp_trace_reduce_hdr(d_raw, d_n, d_hdr, d_stats),
@@ -153,7 +322,7 @@ def main() -> int:
     ms = {n: float(np.mean([all_events[s][i][0].elapsed_time(all_events[s][i][1]) for s in range(args.steps)]))
           for i, n in enumerate(names)}
 
-    for base in ("gemm", "attn"):
+    for base in ("gemm", "gemm5", "attn"):
         ms[base + "_vanilla"] = 0.5 * (ms[base + "_vanilla"] + ms.pop(base + "_vanilla2"))
         ms[base + "_instr"] = 0.5 * (ms[base + "_instr"] + ms.pop(base + "_instr2"))
     gemm_flop = 2.0 * M * N * K
@@ -161,6 +330,9 @@ def main() -> int:
     tf_van = gemm_flop / ms["gemm_vanilla"] / 1e9
     tf_ins = gemm_flop / ms["gemm_instr"] / 1e9
     overhead = (ms["gemm_instr"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
+    overhead5 = (ms["gemm5_instr"] - ms["gemm5_vanilla"]) / ms["gemm5_vanilla"] * 100.0
+    ms["gemm_masked"] = 0.5 * (ms["gemm_masked"] + ms.pop("gemm_masked2"))
+    overhead_masked = (ms["gemm_masked"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
     attn_tf_van = attn_flop / ms["attn_vanilla"] / 1e9
     attn_tf_ins = attn_flop / ms["attn_instr"] / 1e9
     attn_overhead = (ms["attn_instr"] - ms["attn_vanilla"]) / ms["attn_vanilla"] * 100.0
@@ -234,6 +406,18 @@ def main() -> int:
             "decode_entry_point": "kp_trace_reduce_hdr",
         },
         "overhead_pct": round(overhead, 3),
+        "overhead_pct_stage_by_stage": {
+            "value": round(overhead5, 3),
+            "what": "K step with its stages one after the other, 5 regions (load issue, wait, LDS write, MFMA, "
+                    "epilogue), 514 records per wave; against the same schedule without record sites",
+            "uninstrumented_tflops": round(gemm_flop / ms["gemm5_vanilla"] / 1e9, 2),
+            "instrumented_tflops": round(gemm_flop / ms["gemm5_instr"] / 1e9, 2),
+        },
+        "overhead_pct_generic_sites": {
+            "value": round(overhead_masked, 3),
+            "what": "default schedule with region 2 masked off (region_mask 0b1011): the generic record sites "
+                    "that a mask, the flush strategy or wave-group records select",
+        },
         "uninstrumented_tflops": round(tf_van, 2),
         "uninstrumented_frac_of_mfma_peak": round(tf_van / PEAK_BF16_TFLOPS, 4),
         "instrumented_frac_of_mfma_peak": round(tf_ins / PEAK_BF16_TFLOPS, 4),
@@ -310,28 +494,7 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        import oracle
-
-        cores = min(os.cpu_count() or 1, 16)
-        sample_log2 = min(args.log2_records, 23)
-        sraw, _ = inputs.gen_trace(inputs.spec_decode_standalone(sample_log2))
-        oracle.decode_bytes(sraw, cores)  # warm-up
-        c0 = time.perf_counter()
-        reps = 0
-        while True:
-            oracle.decode_bytes(sraw, cores)
-            reps += 1
-            if time.perf_counter() - c0 > 10.0 or reps >= 20:
-                break
-        c1 = time.perf_counter()
-        out["cpu_baseline"] = {
-            "value": round(reps * (1 << sample_log2) / (c1 - c0), 1),
-            "unit": "records/s (trace decode)",
-            "cores": cores,
-            "kind": "oracle",
-            "sample": f"{reps} x the first 2^{sample_log2} records' worth of the decode workload "
-                      f"({(1 << sample_log2) // 16384} workgroups x 8 waves x 2048 records), OpenMP over workgroups",
-        }
+        out["cpu_baseline"] = cpu_baseline(args, inputs, a, b, q, k, v)
     print(json.dumps(out))
     return 0
 

@@ -255,10 +255,10 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
 
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
- * region_mask: bit r (r < 30) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
+ * region_mask: bit r (r < 29) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
  * selects the flush strategy instead of the default circular one (Sec. 4.2: "Circular" keeps
  * the newest records in LDS and copies them out once at kernel exit; "Flush" writes a full
- * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..29 all zero
+ * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..28 all zero
  * launches the separately compiled uninstrumented kernel: no ring, no record sites; trace_buf
  * may then be NULL.  Instrumented and uninstrumented kernels produce bit-identical outputs.
  *
@@ -277,6 +277,7 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
  */
 #define KP_MASK_FLUSH 0x80000000u
 #define KP_MASK_WAVE_GROUP 0x40000000u
+#define KP_MASK_PHASES 0x20000000u
 
 /* Launch geometry kp_gemm_instrumented will use for M x N x K: recorded workgroups, waves per
  * workgroup, number of regions.  KP_ERR_UNSUPPORTED_SHAPE if no kernel covers the shape. */
@@ -293,6 +294,12 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  *       them, 1 second half with the B share, 2 wait (LDS writes landed + barrier; with every region
  *       enabled and the circular strategy also the ~30 instructions that turn the K-step's three clock
  *       samples into records); 3 epilogue, once
+ *       With bit 29 of region_mask (KP_MASK_PHASES; this tile only, KP_ERR_INVALID_ARG otherwise) the
+ *       stages of a K-step follow one another instead of being threaded into each other, and each is a
+ *       region (5 regions, kp_trace_hdr.n_regions = 5; 4 sites and 8 records per K-step and wave):
+ *       2 LDS write (the staging registers of the next K-step go to the other LDS stage), 0 global load
+ *       issue (for the K-step after that), 3 MFMA, 1 wait (LDS traffic landed + barrier); 4 epilogue,
+ *       once.  KP_MASK_PHASES with bits 0..4 all zero runs that schedule without record sites.
  *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
  *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
  * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.

@@ -23,6 +23,7 @@ KP_ERR_HIP = -5
 KP_FLAG_FLUSH = 1
 KP_MASK_FLUSH = 1 << 31
 KP_MASK_WAVE_GROUP = 1 << 30  # one record stream per group of four waves
+KP_MASK_PHASES = 1 << 29      # 256x256x64 GEMM: the stages of a K step one after the other, 5 regions
 
 
 class KperfError(RuntimeError):

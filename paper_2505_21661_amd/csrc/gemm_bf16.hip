@@ -10,7 +10,9 @@
 //
 //   tile 64x64x32, 4 waves  : regions 0 global load, 1 LDS store, 2 MFMA        (per K step)
 //   tile 256x256x64, 8 waves: regions 0 / 1 first / second half of a K step's MFMAs with the
-//                              staging of the next K step threaded in, 2 barrier wait, 3 epilogue (once)
+//                              staging of the next K step threaded in, 2 barrier wait, 3 epilogue (once);
+//                              or (KP_MASK_PHASES) a K step whose stages follow one another, each its own
+//                              region: 2 LDS write, 0 global load issue, 3 MFMA, 1 wait; 4 epilogue (once)
 #include <type_traits>
 
 #include "kp_common.h"
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64;
 constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // both stages
 
-template <int INSTR, int WAVES>
+template <int INSTR, int WAVES, bool PHASED>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   constexpr int SITE = INSTR == 2 ? 4 : INSTR;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
@@ -340,14 +342,65 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     KP_COMMIT(ring, 3);  // the site that opened this K step, the one in its middle and the one above
     if constexpr (MORE) KP_SITE_K(ring, 0, 2, 0); else KP_SITE_K(ring, 0, 2, 3);
   };
+  // The same K step with its stages one after the other, each a region of its own (the stage-by-stage
+  // instrumentation of a software-pipelined GEMM, Sec. 5.3): 2 the staging registers (K step kt+1) go to
+  // the other LDS stage, 0 the global loads of K step kt+2 are issued, 3 the MFMAs of K step kt, 1 the
+  // wait for this wave's LDS traffic and for the other waves.  Four sites and eight records per K step.
+  auto iteration_phased = [&](uint32_t kt, auto more_c, auto more2_c) {
+    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+    const uint32_t stage = kt & 1u;
+    const unsigned char* sA = smem + stage * STAGE;
+    const unsigned char* sB = sA + A_BYTES;
+    if constexpr (MORE) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) store_a(stage ^ 1u, i);
+#pragma unroll
+      for (int i = 0; i < 4 * NB; ++i) store_b(stage ^ 1u, i >> 2, i & 3);
+    }
+    KP_SITE_K(ring, 1, 2, 0);
+    if constexpr (MORE2) {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) load_a(kt + 2, i);
+#pragma unroll
+      for (int i = 0; i < 4 * NB; ++i) load_b(kt + 2, i >> 2, i & 3);
+    }
+    KP_SITE_K(ring, 2, 0, 3);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const uint32_t chunk = ks * 2 + (lane >> 5);
+      bf16x8 af[4], bfr[TN];
+#pragma unroll
+      for (int tm = 0; tm < 4; ++tm)
+        af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+        bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * (32 * TN) + tn * 32 + (lane & 31u), chunk));
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < 4; ++tm)
+          acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
+    }
+    KP_SITE_K(ring, 3, 3, 1);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    KP_COMMIT(ring, 4);
+    if constexpr (MORE) KP_SITE_K(ring, 0, 1, 2); else KP_SITE_K(ring, 0, 1, 4);
+  };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  KP_SITE_K(ring, 0, kp::kNoRegion, 0);
-  for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
-  if (KT >= 2) iteration(KT - 2, yes, no);
-  iteration(KT - 1, no, no);
+  if constexpr (PHASED) {
+    KP_SITE_K(ring, 0, kp::kNoRegion, 2);
+    for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration_phased(kt, yes, yes);
+    if (KT >= 2) iteration_phased(KT - 2, yes, no);
+    iteration_phased(KT - 1, no, no);
+  } else {
+    KP_SITE_K(ring, 0, kp::kNoRegion, 0);
+    for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
+    if (KT >= 2) iteration(KT - 2, yes, no);
+    iteration(KT - 1, no, no);
+  }
 
-  // ---- region 3: epilogue ------------------------------------------------------------------------
+  // ---- region 3 (4 with the stages apart): epilogue ---------------------------------------------------
   // transposed tile: register v of lane l is C[m, n] with m = l%32 and n = 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm) {
@@ -364,10 +417,10 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_SITE_K(ring, 1, 3, kp::kNoRegion);
+  KP_SITE_K(ring, 1, PHASED ? 4 : 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, 4, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
-    if constexpr (SITE == 4) kp::deferred_end<2>(ring);  // the sites that opened and closed the epilogue
+    kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
     else kp::sites_end<SITE>(ring);
     kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
@@ -394,24 +447,25 @@ bool pick_shape(int M, int N, int K, GemmShape* s) {
   return false;
 }
 
-template <int INSTR, int WAVES>
+template <int INSTR, int WAVES, bool PHASED>
 kp_status launch_big(const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
   static thread_local int attr_dev = -1;  // the attribute is kept per device
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
   if (attr_dev != dev) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES>),
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES, PHASED>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_dev = dev;
   }
-  hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
+  hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES, PHASED>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }
 
 template <int INSTR>
-kp_status launch_big_w(int /*waves*/, const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
-  return launch_big<INSTR, kBigWaves>(g, n_wg, ring_bytes, st);
+kp_status launch_big_w(bool phased, const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
+  return phased ? launch_big<INSTR, kBigWaves, true>(g, n_wg, ring_bytes, st)
+                : launch_big<INSTR, kBigWaves, false>(g, n_wg, ring_bytes, st);
 }
 
 }  // namespace
@@ -436,7 +490,12 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (!pick_shape(M, N, K, &s))
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "GEMM %dx%dx%d: M,N must be multiples of 64 and K of 32", M, N, K);
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "A, B, C must be 16-byte aligned");
-  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP);
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_PHASES);
+  const bool phased = (region_mask & KP_MASK_PHASES) != 0u;
+  if (phased) {
+    if (s.bm != 256) return kp::fail(KP_ERR_INVALID_ARG, "KP_MASK_PHASES: only the 256x256x64 kernel has the stage-by-stage K step");
+    s.regions = 5;
+  }
   const uint32_t flush = region_mask >> 31;
   const uint32_t group_log2 = (region_mask & KP_MASK_WAVE_GROUP) ? 2u : 0u;
   const int streams = s.waves >> group_log2;
@@ -449,7 +508,7 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.group_log2 = group_log2;
   const bool big = s.bm == 256;
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
-    if (big) return launch_big_w<0>(s.waves, g, n_wg, 0, st);
+    if (big) return launch_big_w<0>(phased, g, n_wg, 0, st);
     hipLaunchKernelGGL(kp_gemm_small<0>, dim3(n_wg), dim3(256), 0, st, g);
     KP_HIP_TRY(hipGetLastError());
     return KP_OK;
@@ -468,7 +527,7 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
   const bool lean = !flush && !group_log2 && regions == (1u << s.regions) - 1u && K <= (1 << 22);
-  if (big) return lean ? launch_big_w<2>(s.waves, g, n_wg, ring_bytes, st) : launch_big_w<1>(s.waves, g, n_wg, ring_bytes, st);
+  if (big) return lean ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st);
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());

@@ -41,11 +41,10 @@ struct Ring {
   uint32_t stored;     // records already written to the LDS sub-ring
   uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
   uint32_t cw;         // lean sites only: tag_wave + records written so far (stands in for cnt)
-  uint32_t slot;       // lean sites only: buffered sites (lanes of vts / vinfo in use)
-  uint32_t pend_info;  // lean sites only: packed description of the site whose clock is pend_t
-  uint32_t vts, vinfo; // lean sites only, per lane: clock and packed description of a buffered site
-  uint64_t dq_t[3];    // deferred sites only: raw clocks of up to three sites that are not buffered yet
-  uint32_t dq_info[3]; //   and their packed descriptions
+  uint32_t slot;       // deferred sites only: commits in the register buffer (lanes in use)
+  uint32_t bts[4], binfo[4];  // deferred sites only, per lane: clocks and packed descriptions of the sites of one commit
+  uint64_t dq_t[4];    // deferred sites only: raw clocks of up to four sites that are not buffered yet
+  uint32_t dq_info[4]; //   and their packed descriptions
   uint64_t t_begin;    // workgroup start: s_memtime
   uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
   // flush strategy only
@@ -270,75 +269,55 @@ __device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint
 // Before ring_finish() in a kernel that used the lean sites: hand the record count back.
 __device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 
-// A second form of the same site, which does not touch LDS at all: the register buffer.
-// The clock of a site and a packed description of its one or two records
-// go into lane `slot` of two VGPRs (v_writelane from SGPRs), and only when the 64 lanes are used up
-// -- and at the end of the kernel -- the buffered sites become records, each lane writing its own
-// site's records to the LDS sub-ring.  Buffering a site is about a dozen instructions, two of them
-// vector ones, at the price of two VGPRs and a (rarely taken) branch.  Measured on the 4096^3 GEMM,
-// with every site buffered at the next site, it lowered the overhead from 4.4 % to 3.4 %; in the
-// attention kernel, which has no VGPR to spare, it raised it from 7.8 % to 10.2 %, so that kernel keeps
-// the form above.  The sites that use the buffer today are the deferred ones further down.
+// A second form of the same site, which does not touch LDS at all, for kernels that wait for all their
+// LDS traffic at a barrier anyway.  Whoever uses a clock value has to wait for everything counted in
+// lgkmcnt, LDS reads and writes in flight included (scalar-memory results come back out of order), and
+// in the middle of a pipelined loop that wait drains the LDS queue.  Here a site only issues the clock
+// read into one of four scalar register pairs (K, a compile-time index) and notes its description;
+// sites_commit<N>(), placed right after the kernel's own "s_waitcnt lgkmcnt(0); s_barrier", moves sites
+// 0..N-1 into the register buffer: lane `slot` of 2 N vector registers takes the clocks and descriptions
+// of one commit (v_writelane from SGPRs, the lane index through M0, set once per commit), and only when
+// the 64 lanes are used up -- and at the end of the kernel -- the buffered sites become records, each lane
+// writing the records of its own commit to the LDS sub-ring.  A site costs the clock read and three scalar
+// instructions, a commit four instructions plus three per site.  The kernel must commit a pair before it
+// issues into it again.  Measured on the 4096^3 GEMM: overhead 4.4 % with the records written to LDS at
+// the next site, 3 % with three deferred sites per K step; the attention kernel, which has no VGPR to
+// spare and whose sites do not sit in the middle of pipelined LDS traffic, keeps the form above.
 //
 // Packed description: bits 15:0 low half of the running counter (tag_wave + sequence number) of the
 // site's first record, bits 23:16 tag byte (phase << 7 | region) of the first record, bits 31:24
-// tag byte of the second record, 0xFF where there is none.  The host only selects these sites when a
-// wave writes fewer than 2^20 records, so the counter never carries into the wave field.
+// tag byte of the second record, 0xFF where there is none; all ones: no site.  The host only selects
+// these sites when a wave writes fewer than 2^20 records, so the counter never carries into the wave field.
 
-// Turn the buffered sites (lanes below r.slot) into records of the LDS sub-ring.  Newest wins: a
+// Turn the buffered commits (lanes below r.slot) into records of the LDS sub-ring.  Newest wins: a
 // record is left out when a later record of the same batch takes its slot (sub-rings shorter than a
 // batch), because the order of two writes of one instruction to one address is not defined.
 __device__ __forceinline__ void flush_sites(Ring& r) {
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t info = r.vinfo, ts = r.vts;
-  const uint32_t c1 = r.cw - ((r.cw - (info & 0xFFFFu)) & 0xFFFFu);  // counter of the site's first record
-  const uint32_t c2 = c1 + 1u;
-  const uint32_t b1 = (info >> 16) & 0xFFu, b2 = info >> 24;
   const bool in = lane < r.slot;
-  if (in && b1 != 0xFFu && r.cw - 1u - c1 <= r.lds_mask) {
-    uint32_t* dst = r.sub + 2u * (c1 & r.lds_mask);
-    dst[0] = (b1 << 24) | c1;
-    dst[1] = ts;
-  }
-  if (in && b2 != 0xFFu && r.cw - 1u - c2 <= r.lds_mask) {
-    uint32_t* dst = r.sub + 2u * (c2 & r.lds_mask);
-    dst[0] = (b2 << 24) | c2;
-    dst[1] = ts;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t info = r.binfo[k], ts = r.bts[k];
+    const uint32_t c1 = r.cw - ((r.cw - (info & 0xFFFFu)) & 0xFFFFu);  // counter of the site's first record
+    const uint32_t c2 = c1 + 1u;
+    const uint32_t b1 = (info >> 16) & 0xFFu, b2 = info >> 24;
+    if (in && b1 != 0xFFu && r.cw - 1u - c1 <= r.lds_mask) {
+      uint32_t* dst = r.sub + 2u * (c1 & r.lds_mask);
+      dst[0] = (b1 << 24) | c1;
+      dst[1] = ts;
+    }
+    if (in && b2 != 0xFFu && r.cw - 1u - c2 <= r.lds_mask) {
+      uint32_t* dst = r.sub + 2u * (c2 & r.lds_mask);
+      dst[0] = (b2 << 24) | c2;
+      dst[1] = ts;
+    }
   }
   r.slot = 0u;
 }
 
-// Retire the previous site (its clock value returned long ago) into the register buffer.
-__device__ __forceinline__ void buffer_pending_site(Ring& r) {
-  const uint32_t ts = clock_delta(r.pend_t, r.t0_lo);
-  // v_writelane takes a single scalar register besides M0, so the lane index goes through M0,
-  // which is put back afterwards (the compiler does not expect inline assembly to change it)
-  uint32_t saved_m0;
-  asm volatile(
-      "s_mov_b32 %2, m0\n\t"
-      "s_mov_b32 m0, %5\n\t"
-      "s_nop 0\n\t"
-      "v_writelane_b32 %0, %3, m0\n\t"
-      "v_writelane_b32 %1, %4, m0\n\t"
-      "s_mov_b32 m0, %2"
-      : "+v"(r.vts), "+v"(r.vinfo), "=&s"(saved_m0)
-      : "s"(ts), "s"(r.pend_info), "s"(r.slot));
-  r.slot += 1u;
-}
-
-// A third form, for kernels that wait for all their LDS traffic at a barrier anyway.  Whoever uses a
-// clock value has to wait for everything counted in lgkmcnt, LDS reads and writes in flight included
-// (scalar-memory results come back out of order), and in the middle of a pipelined loop that wait
-// drains the LDS queue.  Here a site only issues the clock read into one of three scalar register pairs
-// (K, a compile-time index) and notes its description; sites_commit<N>(), placed right after the
-// kernel's own "s_waitcnt lgkmcnt(0); s_barrier", moves sites 0..N-1 into the register buffer in that
-// order.  The kernel must commit a pair before it issues into it again.  Measured on the 4096^3 GEMM
-// (three sites per K step, one barrier) the instrumented kernel goes from 144.7 to 142.0 us, the
-// overhead from 6.7 % to 4.1 %; the attention kernel, whose sites do not sit in the middle of pipelined
-// LDS traffic, gains nothing from it and spills two registers, so it keeps the second form.
 template <int K>
 __device__ __forceinline__ void site_defer(Ring& r, uint32_t end_region, uint32_t start_region) {
-  static_assert(K >= 0 && K < 3, "three deferred sites at most");
+  static_assert(K >= 0 && K < 4, "four deferred sites at most");
   __builtin_amdgcn_sched_barrier(0);
   r.dq_t[K] = sample_clock();
   if (end_region != kNoRegion && start_region != kNoRegion) {
@@ -352,32 +331,45 @@ __device__ __forceinline__ void site_defer(Ring& r, uint32_t end_region, uint32_
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int N>
+// Sites 0..N-1 into lane r.slot of the register buffer.  NMAX is the largest N the kernel commits with:
+// the descriptions N..NMAX-1 of the lane are marked empty (they may hold sites of an earlier batch),
+// those from NMAX up are never written and stay empty.
+template <int N, int NMAX = N>
 __device__ __forceinline__ void sites_commit(Ring& r) {
-  static_assert(N >= 0 && N <= 3, "three deferred sites at most");
+  static_assert(N >= 0 && N <= NMAX && NMAX <= 4, "four deferred sites at most");
   __builtin_amdgcn_sched_barrier(0);
+  // v_writelane takes a single scalar register besides M0, so the lane index goes through M0,
+  // which is put back afterwards (the compiler does not expect inline assembly to change it)
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0" : "=&s"(saved_m0) : "s"(r.slot));
 #pragma unroll
-  for (int k = 0; k < N; ++k) {
-    r.pend_t = r.dq_t[k];
-    r.pend_info = r.dq_info[k];
-    buffer_pending_site(r);
+  for (int k = 0; k < NMAX; ++k) {
+    if (k < N) {
+      const uint32_t ts = clock_delta(r.dq_t[k], r.t0_lo);
+      asm volatile("v_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
+                   : "+v"(r.bts[k]), "+v"(r.binfo[k]) : "s"(ts), "s"(r.dq_info[k]));
+    } else {
+      asm volatile("v_writelane_b32 %0, -1, m0" : "+v"(r.binfo[k]));
+    }
   }
-  if (r.slot > 61u) flush_sites(r);  // uniform; the next commit brings up to three sites
+  asm volatile("s_mov_b32 m0, %0" : : "s"(saved_m0));
+  r.slot += 1u;
+  if (r.slot > 63u) flush_sites(r);  // uniform
   __builtin_amdgcn_sched_barrier(0);
 }
 
 __device__ __forceinline__ void deferred_begin(Ring& r) {
   r.cw = r.tag_wave;
   r.slot = 0u;
-  r.vts = 0u;
-  r.vinfo = 0u;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { r.bts[k] = 0u; r.binfo[k] = 0xFFFFFFFFu; }
 }
 
 // Before ring_finish(): commit the N sites still in flight, write out the register buffer and hand
 // the record count back.
-template <int N>
+template <int N, int NMAX = N>
 __device__ __forceinline__ void deferred_end(Ring& r) {
-  sites_commit<N>(r);
+  if constexpr (N > 0) sites_commit<N, NMAX>(r);
   flush_sites(r);
   r.cnt = r.cw - r.tag_wave;
   r.stored = r.cnt;

@@ -330,9 +330,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // its clock word; round j: cwe + 136 j (pbase is a multiple of 1024, lanes 32.. are past one padding)
     const uint32_t cwe = qe + (pbase >> 4) + ((lane >> 5) << 2);
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
-#ifdef KP_DEBUG_COUNT
-    uint32_t dbg_maxcell = 0;
-#endif
     // ---- workgroup header, clear the staging state -----------------------------------------------
     if (tid < W) {
       const uint32_t T = wh[8 + tid];
@@ -691,9 +688,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // in arrival order inside their cell here and every lane of the sweep sorts a window of the sequence
       // in registers; otherwise the records are ranked inside their cell first.
       const bool window_sort = R <= 16u && misc[2] < (1u << 27) && !tmp[T_WIDE] && tmp[T_MAXCELL] <= kMaxCellWindow;
-#ifdef KP_DEBUG_COUNT
-      if (tid == 0) { ctr[H_RSVD] += window_sort ? 1u : 0u; ctr[H_CAP] += tmp[T_MAXCELL]; dbg_maxcell = tmp[T_MAXCELL]; }
-#endif
       if (window_sort) {
 #pragma unroll
         for (int i = 0; i < kNR; ++i) {
@@ -959,9 +953,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       const unsigned long long s = pk & ((1ull << 46) - 1);
       uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + e) * 2;
       dst[0] = s;
-#ifdef KP_DEBUG_COUNT
-      if (e == 0) { dst[0] = dbg_maxcell; }
-#endif
       dst[1] = (uint64_t)n | ((uint64_t)mx << 32);
       if (n) {
         const uint32_t r = e % R;
@@ -1010,9 +1001,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
   }
   if (tid_k < H_STATUS && ctr[tid_k]) atomicAdd(&out[tid_k], ctr[tid_k]);
-#ifdef KP_DEBUG_COUNT
-  if (tid_k == H_RSVD || tid_k == H_CAP) atomicAdd(&out[tid_k], ctr[tid_k]);
-#endif
 }
 
 // Launch shape of one kernel instantiation for one LDS size, queried once per device.

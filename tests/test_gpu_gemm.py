@@ -315,3 +315,77 @@ def test_real_trace_carries_the_record_cost(kp, oracle_mod):
     assert st0["min"].min() > 37
     assert np.array_equal(st0["sum"] - st["sum"], 37 * st["cnt"])
     assert np.array_equal(st0["U"], st["U"])  # overlap uses the uncompensated intervals
+
+
+def run_gemm_phased(kp, a, b, regions, trace_cap=None, extra=0):
+    """The 256x256x64 kernel with the stages of a K step one after the other (KP_MASK_PHASES, 5 regions)."""
+    M, K = a.shape
+    N = b.shape[1]
+    A, B = a.cuda(), b.cuda()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    n_wg, waves, _ = kp.kp_gemm_launch_shape(M, N, K)
+    trace = None
+    if regions:
+        trace = torch.full((kp.kp_trace_bytes(n_wg, waves, trace_cap),), 0x77, dtype=torch.uint8, device="cuda")
+    kp.kp_gemm_instrumented(A, B, C, M, N, K, regions | kp.KP_MASK_PHASES | extra, trace, trace_cap or 0)
+    torch.cuda.synchronize()
+    return C, trace, (n_wg, waves, 5)
+
+
+@pytest.mark.parametrize("shape", [(1024, 1024, 512), (4096, 4096, 4096)])
+def test_stage_by_stage_regions(kp, oracle_mod, shape):
+    """The configured region set of the large GEMM (Sec. 5.3: a software-pipelined GEMM timed stage by
+    stage): load issue, wait, LDS write, MFMA once per K-step and one epilogue, (4 x K/64 + 1) x 2
+    records per wave (514 at K = 4096) into a ring of 4096 records per workgroup.  C is bit-identical
+    to the default kernel's, the trace decodes like the oracle says and holds the closed-form counts."""
+    from tests.gpu_util import assert_stats_equal
+
+    M, N, K = shape
+    a, b = inputs.gemm_inputs(M, N, K, seed=2 if M == 4096 else 21)
+    c_ref, _, _ = run_gemm(kp, a, b, 0)
+    c_van, _, _ = run_gemm_phased(kp, a, b, 0)
+    assert torch.equal(c_van.view(torch.int16), c_ref.view(torch.int16))
+    c_ins, trace, (n_wg, waves, R) = run_gemm_phased(kp, a, b, 0b11111, trace_cap=4096)
+    assert torch.equal(c_ins.view(torch.int16), c_ref.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[2:8]) == (n_wg, waves, 5, 512, 0, 0)
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * 512, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    steps, per = K // 64, n_wg * waves
+    total = (4 * steps + 1) * 2
+    assert (raw[16:16 + 32 * n_wg].reshape(n_wg, 32)[:, 8:16] == total).all()
+    # 514 records per wave at K = 4096 into 512 slots: the two oldest, START and END of the first LDS write, are lost
+    lost = max(0, total - 512)
+    assert lost in (0, 2) and st["n_dropped"] == per * lost
+    assert st["n_slots_valid"] == per * (total - lost) and st["n_pairs"] == per * (total - lost) // 2
+    assert st["cnt"].tolist() == [steps * per, steps * per, (steps - lost // 2) * per, steps * per, per]
+    for k in ("n_orphan_start", "n_orphan_end", "n_invalid", "n_disorder", "n_nonmonotonic", "n_span_overflow_wgs"):
+        assert st[k] == 0, k
+    # regions of one wave follow one another: their total time fits in the workgroup span
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32).astype(np.uint64)
+    span = ((hdr[:, 4] | (hdr[:, 5] << np.uint64(32))) - (hdr[:, 2] | (hdr[:, 3] << np.uint64(32)))).astype(np.int64)
+    assert (st["per"]["sum"].sum(axis=2).astype(np.int64) <= span[:, None]).all()
+    # a subset of the regions (generic record sites) and the flush strategy leave C alone too
+    c_m, trace_m, _ = run_gemm_phased(kp, a, b, 0b01010, trace_cap=4096)
+    assert torch.equal(c_m.view(torch.int16), c_ref.view(torch.int16))
+    raw_m = trace_m.cpu().numpy().view(np.uint32).copy()
+    out_m = torch.zeros_like(out)
+    kp.kp_trace_reduce(trace_m, n_wg * waves * 512, out_m)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw_m, 8), out_m.cpu().numpy(), oracle_mod)
+    assert kp.parse_stats(out_m)["cnt"].tolist() == [0, steps * per, 0, steps * per, 0]
+
+
+def test_stage_by_stage_needs_the_large_tile(kp):
+    a, b = inputs.gemm_inputs(256, 256, 256, seed=0)
+    with pytest.raises(kp.KperfError) as e:
+        run_gemm_phased(kp, a, b, 0)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    a, b = inputs.gemm_inputs(1024, 1024, 256, seed=0)
+    n_wg, waves, _ = kp.kp_gemm_launch_shape(1024, 1024, 256)
+    with pytest.raises(kp.KperfError) as e:
+        run_gemm_phased(kp, a, b, 0b100000, trace_cap=4096)   # region 5 does not exist
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
