@@ -6,24 +6,29 @@
 // takes one recorded workgroup at a time and keeps it in LDS as a clock word and a metadata byte
 // per record.
 //   A  every record is scattered to its rank (seq - first surviving seq), which undoes ring
-//      rotation and out-of-order flushes in O(1) per record;
-//   B  a lane takes the records of 16 rounds of 64 consecutive ranks; an END is paired iff the
-//      nearest earlier record of its (wave, region) is a START -- usually the rank just below,
-//      which comes from the lane below (DPP); d = (u32)(ts_end - ts_start) minus the constant
-//      record cost (Sec. 4.3) goes to the per-(wave, region) sums and the log2 histogram with
-//      LDS atomics;
+//      rotation and out-of-order flushes in O(1) per record; the records of the next workgroup
+//      are requested before the results of the current one are written;
+//   B  a lane takes the records of 8 rounds of 128 consecutive ranks, two neighbours per round;
+//      an END is paired iff the nearest earlier record of its (wave, region) is a START --
+//      usually the rank just below, in the same lane or the lane below (DPP);
+//      d = (u32)(ts_end - ts_start) minus the constant record cost (Sec. 4.3) goes to the
+//      per-(wave, region) sums and the log2 histogram with LDS atomics;
 //   C  the paired records of all waves are sorted by clock: counting sort into time cells (one
-//      LDS atomic per record gives cell and arrival slot), a prefix sum over the cells, and the
-//      rank among the few records of the same cell by comparing clocks;
-//   D  every lane sweeps 16 consecutive records of the sorted sequence.  The number of waves that
-//      have each region open is kept bit-sliced (plane k = bit k of every region's count); a first
-//      pass gives each lane's net change, a prefix sum over lanes and waves the state at the start
-//      of each lane's stretch, and in the second pass a record that takes its region's count from
-//      0 to 1 or from 1 to 0 adds -t / +t to the region-pair accumulators of all regions active
-//      at that instant (the integral of A_a(t)*A_b(t) collapses to a signed sum over its
-//      switching times);
+//      LDS atomic per record gives cell and arrival slot) and a prefix sum over the cells put
+//      them in cell order;
+//   D  every lane takes 16 consecutive records of that sequence and finishes the order in
+//      registers (a sorting network over its own records, then a merge of its outer halves with
+//      the neighbouring lanes').  The number of waves that have each region open is kept
+//      bit-sliced (plane k = bit k of every region's count); a first pass gives each lane's net
+//      change, a prefix sum over lanes and waves the state at the start of each lane's stretch,
+//      and the second pass the set of open regions after every record.  The time two regions
+//      are both open is the sum over the stretches between records of length * open(a) * open(b):
+//      a matrix product, taken by the matrix cores 64 stretches at a time;
 //   E  the per-(workgroup, wave, region) results go to HBM and into running totals, which live in
 //      LDS and reach HBM once per decoder workgroup.
+// Traces outside what the register sort covers (more than 16 regions, a span of 2^26 ticks or
+// more, a time cell with more than 17 records) rank the records inside their cell by comparing
+// clocks and add every switch of a region to the region-pair sums with LDS atomics.
 // A workgroup with a corrupt record (bad field, duplicated seq) has holes in its ranks; it is rare,
 // takes no part in the overlap statistics and is paired by a plain serial walk per (wave, region).
 #include "kp_common.h"
@@ -163,16 +168,127 @@ __device__ __forceinline__ void planes_step(uint32_t (&pl)[PLANES], uint32_t x, 
   for (int k = 0; k < PLANES; ++k) { const uint32_t o = pl[k]; pl[k] = o ^ carry; carry &= o ^ dm; }
 }
 
+// Batcher's odd-even merge sort of N registers: a fixed network (63 exchanges for 16 words, 384 for 48),
+// every index known at compile time.
+template <int N>
+__device__ __forceinline__ void network_sort(uint32_t (&key)[N]) {
+#pragma unroll
+  for (int pp = 1; pp < N; pp <<= 1) {
+#pragma unroll
+    for (int k = pp; k >= 1; k >>= 1) {
+#pragma unroll
+      for (int j = k % pp; j + k < N; j += 2 * k) {
+#pragma unroll
+        for (int i = 0; i < (k < N - j - k ? k : N - j - k); ++i) {
+          if ((i + j) / (2 * pp) == (i + j + k) / (2 * pp)) {
+            const uint32_t x = key[i + j], y = key[i + j + k];
+            key[i + j] = x < y ? x : y;
+            key[i + j + k] = x < y ? y : x;
+          }
+        }
+      }
+    }
+  }
+}
+
+// Ascending order of 8 registers that first rise and then fall (or the reverse): 12 exchanges.
+__device__ __forceinline__ void bitonic_merge8(uint32_t (&v)[8]) {
+#pragma unroll
+  for (int k = 4; k >= 1; k >>= 1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if ((i & k) == 0) {
+        const uint32_t x = v[i], y = v[i + k];
+        v[i] = x < y ? x : y;
+        v[i + k] = x < y ? y : x;
+      }
+    }
+  }
+}
+
+// The sweep works on one word per record of the sequence: clock << 6 | region << 1 | END; records with
+// equal words are interchangeable.  A place past the end of the sequence holds `fake`: the largest
+// clock of the workgroup with a region number that no record has, so that it sorts last, opens no
+// region and the stretch in front of it has an honest length.
+__device__ __forceinline__ void sweep_outputs(const uint32_t (&key)[kNR], uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
+  ends = 0;
+#pragma unroll
+  for (int i = 0; i < kNR; ++i) {
+    const uint32_t k = key[i];
+    st[i] = k >> 6;
+    sx[i] = 1u << ((k >> 1) & 31u);  // bit 31 for a place past the end: above every region
+    ends |= (k & 1u) << i;
+  }
+}
+
 // The 16 records of the clock-sorted sequence that lane `tid` of the sweep owns, from a sequence that
-// is only ordered cell by cell (inside a cell the records stand in arrival order).  The lane reads a
-// window of its 16 places and HALO on either side, so that every cell with a record among the 16 lies
-// inside the window as long as no cell holds more than HALO + 1 records, and sorts the window in
-// registers: one word per record, clock << 5 | region << 1 | END (records with equal words are
-// interchangeable).  Cells follow one another in clock order, so sorting the words sorts every cell and
-// moves no record out of its cell.  Outputs: clock, region bit (0 past the end of the sequence), END bits.
-// (Only the lane's own 16 places come out right: the cell of the place after them may reach past the window.)
+// is only ordered cell by cell (inside a cell the records stand in arrival order).  Cells follow one
+// another in clock order, so sorting the words sorts every cell and moves no record out of its cell.
+//
+// Form for cells of at most 9 records: the lane sorts its own 16 places and puts them back; a cell that
+// lies across the boundary to the next lane then has at most 8 records on either side, all of them in
+// the upper half here and in the lower half there, so merging these two halves (both sorted) and
+// handing the lower 8 back to this lane, the upper 8 to the next one finishes the job.  Each lane does
+// that for its lower half with the lane below and for its upper half with the lane above: the larger
+// (smaller) of element i of one run and element 7 - i of the other are the upper (lower) 8 of the two
+// runs, in rising-then-falling order.  Contains one workgroup barrier.
+template <uint32_t NPOS>
+__device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
+                                           uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
+  uint32_t key[kNR];
+  const uint32_t g0 = tid * kNR;
+  u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
+  {
+    const u32x4 mb = reinterpret_cast<const u32x4*>(meta)[tid];
+    const uint32_t m4[4] = {mb.x, mb.y, mb.z, mb.w};
+#pragma unroll
+    for (int x = 0; x < kNR / 4; ++x) {
+      const u32x4 v = own[x];
+      key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
+    }
+#pragma unroll
+    for (int y = 0; y < kNR; ++y) key[y] = (key[y] << 6) | ((m4[y >> 2] >> (8 * (y & 3))) & 0x3Fu);
+  }
+  if (__builtin_amdgcn_ballot_w64(g0 + kNR > n_events)) {
+#pragma unroll
+    for (int y = 0; y < kNR; ++y) key[y] = g0 + y < n_events ? key[y] : fake;
+  }
+  network_sort<kNR>(key);
+  own[0] = u32x4{key[0], key[1], key[2], key[3]};
+  own[1] = u32x4{key[4], key[5], key[6], key[7]};
+  own[2] = u32x4{key[8], key[9], key[10], key[11]};
+  own[3] = u32x4{key[12], key[13], key[14], key[15]};
+  __syncthreads();
+  {
+    const u32x4* below = reinterpret_cast<const u32x4*>(clk + clk_word((tid > 0 ? tid - 1 : 0) * kNR));
+    const u32x4* above = reinterpret_cast<const u32x4*>(clk + clk_word((tid + 1 < NPOS / kNR ? tid + 1 : tid) * kNR));
+    const u32x4 b0 = below[2], b1 = below[3], a0 = above[0], a1 = above[1];
+    const uint32_t lo_gate = tid > 0 ? 0xFFFFFFFFu : 0u;               // no lane below: nothing comes up
+    const uint32_t hi_fill = tid + 1 < NPOS / kNR ? 0u : 0xFFFFFFFFu;  // no lane above: nothing comes down
+    const uint32_t bw[8] = {b0.x & lo_gate, b0.y & lo_gate, b0.z & lo_gate, b0.w & lo_gate,
+                            b1.x & lo_gate, b1.y & lo_gate, b1.z & lo_gate, b1.w & lo_gate};
+    const uint32_t aw[8] = {a0.x | hi_fill, a0.y | hi_fill, a0.z | hi_fill, a0.w | hi_fill,
+                            a1.x | hi_fill, a1.y | hi_fill, a1.z | hi_fill, a1.w | hi_fill};
+    uint32_t lo[8], hi[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      lo[i] = key[7 - i] > bw[i] ? key[7 - i] : bw[i];         // upper 8 of (upper half below, own lower half)
+      hi[i] = key[8 + i] < aw[7 - i] ? key[8 + i] : aw[7 - i];  // lower 8 of (own upper half, lower half above)
+    }
+    bitonic_merge8(lo);
+    bitonic_merge8(hi);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { key[i] = lo[i]; key[8 + i] = hi[i]; }
+  }
+  sweep_outputs(key, st, sx, ends);
+}
+
+// Form for cells of up to HALO + 1 records: the lane reads a window of its 16 places and HALO on either
+// side, so that every cell with a record among the 16 lies inside the window, and sorts the whole
+// window.  (Only the lane's own 16 places come out right: the cell of the place after them may reach
+// past the window.)
 template <int HALO, uint32_t NPOS>
-__device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events,
+__device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
                                               uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
   constexpr int N = kNR + 2 * HALO;
   uint32_t key[N];
@@ -193,43 +309,21 @@ __device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t
 #pragma unroll
     for (int y = 0; y < N; ++y) {
       constexpr int kFirst = 16 - HALO;  // byte of the first window place inside the three 16-byte blocks
-      key[y] = (key[y] << 5) | ((m12[(kFirst + y) >> 2] >> (8 * ((kFirst + y) & 3))) & 0x1Fu);
+      key[y] = (key[y] << 6) | ((m12[(kFirst + y) >> 2] >> (8 * ((kFirst + y) & 3))) & 0x3Fu);
     }
   }
   if (__builtin_amdgcn_ballot_w64(wbeg < 0 || (uint32_t)(wbeg + N) > n_events)) {
 #pragma unroll
     for (int y = 0; y < N; ++y) {  // places outside the sequence: first or last
       const int32_t e = wbeg + y;
-      key[y] = e < 0 ? 0u : ((uint32_t)e < n_events ? key[y] : 0xFFFFFFFFu);
+      key[y] = e < 0 ? 0u : ((uint32_t)e < n_events ? key[y] : fake);
     }
   }
-  // Batcher's odd-even merge sort: a fixed network (191 exchanges of two registers for 32 words, 384 for
-  // 48), every index known at compile time.
+  network_sort<N>(key);
+  uint32_t mine[kNR];
 #pragma unroll
-  for (int pp = 1; pp < N; pp <<= 1) {
-#pragma unroll
-    for (int k = pp; k >= 1; k >>= 1) {
-#pragma unroll
-      for (int j = k % pp; j + k < N; j += 2 * k) {
-#pragma unroll
-        for (int i = 0; i < (k < N - j - k ? k : N - j - k); ++i) {
-          if ((i + j) / (2 * pp) == (i + j + k) / (2 * pp)) {
-            const uint32_t x = key[i + j], y = key[i + j + k];
-            key[i + j] = x < y ? x : y;
-            key[i + j + k] = x < y ? y : x;
-          }
-        }
-      }
-    }
-  }
-  ends = 0;
-#pragma unroll
-  for (int i = 0; i < kNR; ++i) {
-    const uint32_t k = key[HALO + i];
-    st[i] = k >> 5;
-    sx[i] = g0 + i < n_events ? 1u << ((k >> 1) & 15u) : 0u;
-    ends |= (k & 1u) << i;
-  }
+  for (int i = 0; i < kNR; ++i) mine[i] = key[HALO + i];
+  sweep_outputs(mine, st, sx, ends);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -318,6 +412,26 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   if (tid_k < 16) ctr[tid_k] = 0;
   __syncthreads();
 
+  // The records of a workgroup (eight 16-byte units, two records each, per thread) and the words of its
+  // header are requested one workgroup ahead, before the previous workgroup's results are written, so
+  // that the memory latency runs under that tail and under the clearing of the staging state.
+  u32x4 v[8];
+  uint32_t h_total;  // lane & 15 -> records written by that wave
+  uint2 h_begin, h_end;
+  auto request = [&](uint32_t g, uint32_t t) {
+    const uint32_t* whn = p.wg_hdrs + (size_t)32 * g;
+    h_total = whn[8 + (t & 15u)];
+    h_begin = *reinterpret_cast<const uint2*>(whn + 2);
+    h_end = *reinterpret_cast<const uint2*>(whn + 4);
+    const u32x4* recs = p.records + (size_t)g * (nrec / 2);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t i = t + u * BLOCK;
+      v[u] = __builtin_nontemporal_load(recs + (i < nrec / 2 ? i : nrec / 2 - 1));
+    }
+  };
+  request(blockIdx.x, tid_k);
+
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
     // A fresh copy of the thread index per workgroup that the optimiser cannot see through: without it
     // the address arithmetic of all 16 rounds is computed once before the loop and held in registers
@@ -329,10 +443,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     const uint32_t qe = pbase + 2u * lane;     // even position of round 0; round j: qe + 128 j
     // its clock word; round j: cwe + 136 j (pbase is a multiple of 1024, lanes 32.. are past one padding)
     const uint32_t cwe = qe + (pbase >> 4) + ((lane >> 5) << 2);
-    const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
     // ---- workgroup header, clear the staging state -----------------------------------------------
     if (tid < W) {
-      const uint32_t T = wh[8 + tid];
+      const uint32_t T = h_total;
       const uint32_t V = T < cap ? T : cap;
       sVF[tid] = make_uint2(V, p.flush ? 0u : T - V);
       atomicAdd(&ctr[H_DROPPED], (unsigned long long)(T - V));
@@ -340,8 +453,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
     if (tid >= 64 - T_COUNT && tid < 64) tmp[tid - (64 - T_COUNT)] = 0;
     if (tid == 32) {
-      const uint64_t tb = (uint64_t)wh[2] | ((uint64_t)wh[3] << 32);
-      const uint64_t te = (uint64_t)wh[4] | ((uint64_t)wh[5] << 32);
+      const uint64_t tb = (uint64_t)h_begin.x | ((uint64_t)h_begin.y << 32);
+      const uint64_t te = (uint64_t)h_end.x | ((uint64_t)h_end.y << 32);
       const uint64_t sp = te - tb;
       // cell of clock t: (t * scale) >> 32, i.e. the span divided into NCELL cells (clamped below)
       uint64_t scale = ((uint64_t)NCELL << 32) / ((sp & 0xFFFFFFFFull) + 1ull);
@@ -350,25 +463,26 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       misc[2] = (uint32_t)sp;
     }
     reinterpret_cast<u32x4*>(meta)[tid] = u32x4{0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu};
+    {  // a position without a record reads as the largest clock: it never counts as a step back in time
+      u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(tid * kNR));
+      const u32x4 ones{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+      own[0] = ones; own[1] = ones; own[2] = ones; own[3] = ones;
+    }
     reinterpret_cast<u32x4*>(cells)[2 * tid] = u32x4{0u, 0u, 0u, 0u};
     reinterpret_cast<u32x4*>(cells)[2 * tid + 1] = u32x4{0u, 0u, 0u, 0u};
     if (tid == 0) reinterpret_cast<u32x4*>(cells)[2 * BLOCK] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
-    // ---- A: load and scatter by rank ------------------------------------------------------
+    uint32_t wg_invalid = 0;
+    bool eligible = false;
+    do {  // (left early only when single steps are timed)
+    // ---- A: scatter by rank ------------------------------------------------------------------
     // Eight 16-byte units (two records each) per thread cover the workgroup.  Two records that go to an
     // even rank and the rank above it (the usual case: both sit in the slot of their seq) leave with one
     // 8-byte and one 2-byte store.
     {
-      const u32x4* recs = p.records + (size_t)wg * (nrec / 2);
       const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
       uint32_t c_invalid = 0, c_field = 0, c_dis = 0;
-      u32x4 v[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const uint32_t i = tid + u * BLOCK;
-        v[u] = __builtin_nontemporal_load(recs + (i < n16 ? i : n16 - 1));
-      }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const uint32_t i = tid + u * BLOCK;
@@ -409,7 +523,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_DISORDER, c_dis);
     }
     __syncthreads();
-    if (p.stop_after == kStepOrdered) continue;
+    if (p.stop_after == kStepOrdered) break;
 
     // ---- a duplicated seq leaves fewer occupied ranks than valid records ---------------------------
     // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
@@ -473,7 +587,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
     auto meta_of = [&](int i) -> uint32_t { return (mq[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
     auto set_paired = [&](int i, uint32_t yes) { mq[i >> 2] |= (yes << 6) << (8 * (i & 3)); };  // yes: 0 or 1
-    const uint32_t wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - n_occupied);
+    wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - n_occupied);
     const uint32_t rec_cost = p.rec_cost;
 
     // One pair: duration into the per-(wave, region) sums and the histogram.  The sums exist in up to
@@ -482,11 +596,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     const uint32_t copy = (lane >> 4) & (p.ncopy - 1u);
     auto account_pair = [&](uint32_t w, uint32_t region, uint32_t d_raw) {
       const uint32_t d = d_raw > rec_cost ? d_raw - rec_cost : 0u;
-      const uint32_t e = (w * R + region) * p.ncopy + copy;
+      const uint32_t e = __umul24(__umul24(w, R) + region, p.ncopy) + copy;
       atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
       atomicMax(&pw_max[e], d);
       atomicMin(&pw_min[e], d);
-      atomicAdd(&hist[region * kHistStride + (31 - __clz(d | 1u))], 1u);
+      atomicAdd(&hist[__umul24(region, kHistStride) + (31 - __clz(d | 1u))], 1u);
     };
 
     if (wg_invalid == 0u) {
@@ -501,7 +615,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       // A START learns that it is paired from its END: in the same lane directly, one lane up through a
       // DPP shift of the claims, and when the END is in another hardware wave or found the START by
       // walking, through a mark in the START's metadata byte that is read back after the barrier.
-      uint32_t n_nonmono = 0, n_pairs = 0, n_ends = 0;  // wave-uniform counts
+      uint32_t n_nonmono = 0;  // wave-uniform count
       uint32_t claims = 0;
       bool marked = false;
       uint32_t cm = kEmpty, ct = 0;
@@ -524,7 +638,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         cm = (uint32_t)__builtin_amdgcn_readlane((int)m2, 63) >> 8;
         ct = (uint32_t)__builtin_amdgcn_readlane((int)t1, 63);
         const uint32_t k0 = q & capm;
-        pm = k0 > 0 ? pm : kEmpty;
+        const bool lowest = k0 == 0u;  // first rank of a recorded wave: no record below
+        pm = lowest ? kEmpty : pm;
         const uint32_t p2 = ((m2 << 8) | pm) & 0xFFFFu;  // the record one rank below each of the two
         const uint32_t x2 = m2 ^ p2;
         // bit 7 of each of the two bytes: that byte of the argument is not zero
@@ -532,12 +647,10 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         const uint32_t end2 = m2 & 0x8080u;                                   // is an END (no record: 0)
         const uint32_t differ2 = nonzero7(x2 & 0x3F3Fu) & end2;               // END, other region one rank below
         const uint32_t near2 = ~nonzero7((x2 & 0xBFBFu) ^ 0x8080u) & end2;    // END, START of its region one rank below
-        const uint32_t none2 = ((m2 & 0x3F3Fu) + 0x4141u) & 0x8080u;          // holds no record
         bool p0 = (near2 & 0x80u) != 0u, p1 = (near2 & 0x8000u) != 0u;
         uint32_t st0 = pt, st1 = t0;  // clock of the START
-        const bool v0 = !(none2 & 0x80u), v1 = !(none2 & 0x8000u);
-        n_nonmono += count(v0 && k0 > 0 && t0 < pt) + count(v1 && t1 < t0);
-        n_ends += count((end2 & 0x80u) != 0u) + count((end2 & 0x8000u) != 0u);
+        // (a position without a record holds the largest clock, and so do all above it in its wave)
+        n_nonmono += count(!lowest && t0 < pt) + count(t1 < t0);
         // as END, or as the START of the odd position; the mark of an END sits one bit above its flag
         uint32_t flags = (near2 >> 1) | ((near2 >> 9) & kPaired);
         claims |= (p0 ? 1u : 0u) << j;
@@ -557,7 +670,6 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           p0 = p0 || far0; p1 = p1 || far1;
         }
         mq[j >> 1] |= flags << (16 * (j & 1));
-        n_pairs += count(p0) + count(p1);
         const uint32_t w = q >> cl2;
         if (p0 || p1) account_pair(w, (p1 ? m2 >> 8 : m2) & kRegion, p1 ? t1 - st1 : t0 - st0);
         const bool both = p0 && p1;
@@ -574,12 +686,22 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
                                                                    false);  // wave_shl:1
         set_paired(2 * j + 1, got);
       }
+      // ENDs, and ENDs that are paired (the flag sits one bit below): counted on the packed bytes
+      uint32_t n_ends = 0, n_pairs = 0;
+#pragma unroll
+      for (int x = 0; x < kNR / 4; ++x) {
+        n_ends += __popc(mq[x] & 0x80808080u);
+        n_pairs += __popc(mq[x] & (mq[x] << 1) & 0x80808080u);
+      }
+      n_pairs = wave_scan_add(n_ends | (n_pairs << 16));  // both at most 1024 per wave
       const bool any_marked = __builtin_amdgcn_ballot_w64(marked) != 0;
       if (lane == 0u) {
         if (any_marked) tmp[T_MARKS] = 1u;
         if (n_nonmono) atomicAdd(&tmp[T_NONMONO], n_nonmono);
-        if (n_pairs) atomicAdd(&tmp[T_PAIRS], n_pairs);
-        if (n_ends) atomicAdd(&tmp[T_ENDS], n_ends);
+      }
+      if (lane == 63u) {
+        atomicAdd(&tmp[T_PAIRS], n_pairs >> 16);
+        atomicAdd(&tmp[T_ENDS], n_pairs & 0xFFFFu);
       }
       if (tid == 0) tmp[T_STARTS] = n_occupied;  // records; orphans = records - ENDs - pairs, ENDs - pairs
     } else {
@@ -618,7 +740,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
     }
     __syncthreads();
-    const bool eligible = !misc[0] && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
+    eligible = !misc[0] && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
 
     if (eligible && p.stop_after != kStepPaired) {
       // ---- C: order the paired records of all waves by clock ---------------------------------------
@@ -647,7 +769,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       if (__builtin_amdgcn_ballot_w64(t_max > misc[2]) && lane == 0u) tmp[T_WIDE] = 1u;  // a clock past the span
       __syncthreads();
-      if (p.stop_after == kStepCounted) continue;
+      if (p.stop_after == kStepCounted) break;
       {  // exclusive prefix sum over the cell counters, 16 cells (8 words) per thread
         u32x4 a = reinterpret_cast<u32x4*>(cells)[2 * tid], b = reinterpret_cast<u32x4*>(cells)[2 * tid + 1];
         uint32_t wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -671,7 +793,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         }
         __syncthreads();
         uint32_t base = incl - run;
-        for (uint32_t h = 0; h < hw; ++h) base += wtot[h];
+        {  // + the totals of the waves below: lane h of the first row takes wave h's
+          uint32_t below = (lane & 15u) < hw ? wtot[lane & 15u] : 0u;
+          below += scan_src<0>(below); below += scan_src<1>(below); below += scan_src<2>(below); below += scan_src<3>(below);
+          base += (uint32_t)__builtin_amdgcn_readlane((int)below, 15);
+        }
         const uint32_t both = base * 0x00010001u;
         a = u32x4{wv[0] + both, wv[1] + both, wv[2] + both, wv[3] + both};
         b = u32x4{wv[4] + both, wv[5] + both, wv[6] + both, wv[7] + both};
@@ -680,14 +806,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         if (tid == BLOCK - 1) { cells[NCELL / 2] = base + run; tmp[T_EVENTS] = base + run; }
       }
       __syncthreads();
-      if (p.stop_after == kStepCellSums) continue;
+      if (p.stop_after == kStepCellSums) break;
       auto cell_start = [&](uint32_t c) -> uint32_t { return (cells[c >> 1] >> ((c & 1u) << 4)) & 0xFFFFu; };
       // sorted sequence entry besides the clock: region << 1 | END
       auto info_of = [&](int i) -> uint32_t { return ((meta_of(i) & 0x1Fu) << 1) | (meta_of(i) >> 7); };
       // When clock and region fit one word and no cell holds more than kMaxCellWindow records, the records stay
       // in arrival order inside their cell here and every lane of the sweep sorts a window of the sequence
       // in registers; otherwise the records are ranked inside their cell first.
-      const bool window_sort = R <= 16u && misc[2] < (1u << 27) && !tmp[T_WIDE] && tmp[T_MAXCELL] <= kMaxCellWindow;
+      const bool window_sort = R <= 16u && misc[2] < (1u << 26) && !tmp[T_WIDE] && tmp[T_MAXCELL] <= kMaxCellWindow;
       if (window_sort) {
 #pragma unroll
         for (int i = 0; i < kNR; ++i) {
@@ -697,7 +823,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           meta[ev ? g : NPOS] = (uint8_t)info_of(i);
         }
         __syncthreads();
-        if (p.stop_after >= kStepPlaced && p.stop_after <= kStepSorted) continue;
+        if (p.stop_after >= kStepPlaced && p.stop_after <= kStepSorted) break;
       } else {
       // provisional place: cell start + arrival slot (plain index here, the padded layout comes with the
       // final places)
@@ -712,7 +838,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         nm[i] = ((s1 - s0) | (mine << 16)) & ev;
       }
       __syncthreads();
-      if (p.stop_after == kStepPlaced) continue;
+      if (p.stop_after == kStepPlaced) break;
       // rank among the records of the same cell: by clock, then by arrival slot
 #pragma unroll
       for (int i = 0; i < kNR; ++i) {
@@ -727,7 +853,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         ca[i] = s0 + before;
       }
       __syncthreads();
-      if (p.stop_after == kStepRanked) continue;
+      if (p.stop_after == kStepRanked) break;
 #pragma unroll
       for (int i = 0; i < kNR; ++i) {
         const bool ev = (meta_of(i) & kPaired) != 0u;
@@ -735,7 +861,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         meta[ev ? ca[i] : NPOS] = (uint8_t)info_of(i);
       }
       __syncthreads();
-      if (p.stop_after == kStepSorted) continue;
+      if (p.stop_after == kStepSorted) break;
       }
 
       // ---- D: region-pair overlap, 16 consecutive records of the sorted sequence per lane ----------
@@ -745,8 +871,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         uint32_t st[kNR], sx[kNR];  // clock, region bit (0: no record)
         uint32_t ends = 0;           // bit i: record i is an END
         if (window_sort) {
-          if (tmp[T_MAXCELL] <= 9u) sorted_window<8, NPOS>(clk, meta, tid, n_events, st, sx, ends);
-          else sorted_window<16, NPOS>(clk, meta, tid, n_events, st, sx, ends);
+          const uint32_t fake = (misc[2] << 6) | 0x3Fu;
+          if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, meta, tid, n_events, fake, st, sx, ends);
+          else sorted_window<16, NPOS>(clk, meta, tid, n_events, fake, st, sx, ends);
         } else {
           const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
           const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
@@ -803,10 +930,24 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         // state before this lane's stretch: lanes below in this wave + all waves below
 #pragma unroll
         for (int k = 0; k < PLANES; ++k) pl[k] = wave_shr1(inc[k], 0u);
-        for (uint32_t h = 0; h < hw; ++h) {
-          uint32_t o[PLANES];
+        if (hw > 0) {  // lane h of a row takes wave h's net change; a scan over the row, then the entry of wave hw - 1
+          uint32_t wsum[PLANES], o[PLANES];
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = ptot[h * 8 + k];
+          for (int k = 0; k < PLANES; ++k) wsum[k] = ptot[(lane & 15u) * 8 + k];
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(wsum[k]);
+          planes_add<PLANES>(wsum, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(wsum[k]);
+          planes_add<PLANES>(wsum, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(wsum[k]);
+          planes_add<PLANES>(wsum, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(wsum[k]);
+          planes_add<PLANES>(wsum, o);
+#pragma unroll
+          for (int k = 0; k < PLANES; ++k) o[k] = (uint32_t)__builtin_amdgcn_readlane((int)wsum[k], (int)(hw - 1u));
           planes_add<PLANES>(pl, o);
         }
         // ---- the sorted sequence as segments: the set of active regions after record k and the ticks
@@ -818,16 +959,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           uint32_t limb[3][4];  // limb l of the 16 lengths, one byte each
           uint32_t any_len = 0;
           // clock of the record after the lane's 16: the first one of the lane above
-          const uint32_t t_next = (uint32_t)__builtin_amdgcn_update_dpp((int)wtot[hw + 1 < BLOCK / 64 ? hw + 1 : hw], (int)st[0],
-                                                                        0x130, 0xF, 0xF, false);  // wave_shl:1
+          const uint32_t t_above = hw + 1 < BLOCK / 64 ? wtot[hw + 1 < BLOCK / 64 ? hw + 1 : hw] : misc[2];
+          const uint32_t t_next = (uint32_t)__builtin_amdgcn_update_dpp((int)t_above, (int)st[0], 0x130, 0xF, 0xF, false);  // wave_shl:1
 #pragma unroll
           for (int l = 0; l < 3; ++l)
 #pragma unroll
             for (int y = 0; y < 4; ++y) limb[l][y] = 0u;
 #pragma unroll
           for (int i = 0; i < kNR; ++i) {
-            const uint32_t after = i + 1 < kNR ? st[i + 1] : t_next;
-            const uint32_t len = g0 + i + 1 < n_events ? after - st[i] : 0u;
+            // (places past the end of the sequence carry the workgroup's last clock: stretches of length 0
+            // behind a last one in which no region is open)
+            const uint32_t len = (i + 1 < kNR ? st[i + 1] : t_next) - st[i];
             any_len |= len;
 #pragma unroll
             for (int l = 0; l < 3; ++l) limb[l][i >> 2] |= ((len >> (7 * l)) & 0x7Fu) << (8 * (i & 3));
@@ -841,16 +983,16 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           if (any_len < (1u << 21)) {  // else: a gap of more than three limbs, the loop below takes this wave
             swept = true;
             const uint32_t n_limbs = any_len < (1u << 7) ? 1u : (any_len < (1u << 14) ? 2u : 3u);
-            uint32_t mk[kNR / 2];  // active sets after records 2x and 2x + 1
-#pragma unroll
-            for (int x = 0; x < kNR / 2; ++x) mk[x] = 0u;
+            uint32_t mk[kNR / 2];  // active sets after records 2x and 2x + 1, 16 bits each
+            uint32_t act_even = 0u;
 #pragma unroll
             for (int i = 0; i < kNR; ++i) {
               planes_step<PLANES>(pl, sx[i], end_mask(i));
               uint32_t act = pl[0];
 #pragma unroll
               for (int k = 1; k < PLANES; ++k) act |= pl[k];
-              mk[i >> 1] |= act << (16 * (i & 1));
+              if (i & 1) mk[i >> 1] = __builtin_amdgcn_perm(act, act_even, 0x05040100u);  // the low halves of the two
+              else act_even = act;
             }
             // The lane's own 16 places of the sequence are free now (every window was read before the last
             // barrier): they take the active sets and two limbs, the 16 metadata bytes the third limb.
@@ -867,20 +1009,20 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
               for (int l = 0; l < 3; ++l) acc[l] = i32x4{0, 0, 0, 0};
               const uint32_t j = lane & 15u;  // operand row / column: region j
-              const uint32_t sel = j < 8u ? 0x06040200u : 0x07050301u;  // low or high byte of four 16-bit sets
+              const uint32_t up = 15u - j;      // shift that takes bit j of a 16-bit set to its top
               for (uint32_t n = 0; n < 16; ++n) {  // 64 segments: those of lanes 4n .. 4n + 3
                 const uint32_t src = (tid & ~63u) + 4u * n + (lane >> 4);
                 const u32x4* from = reinterpret_cast<const u32x4*>(clk + clk_word(src * kNR));
                 const u32x4 s0 = from[0], s1 = from[1];
                 const uint32_t w8[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-                i32x4 bits, ones;
+                // One byte per segment, all ones if region j is open in it: the byte permute's selectors 8..11
+                // replicate the top bits of the four halves of its two operands.  As an i8 operand such a byte
+                // is -1, so the products below come out negated.
+                i32x4 ones;
 #pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                  const uint32_t g = __builtin_amdgcn_perm(w8[2 * y + 1], w8[2 * y], sel);
-                  const uint32_t b = (g >> (j & 7u)) & 0x01010101u;  // region j active in segments 4y .. 4y + 3
-                  bits[y] = (int)b;
-                  ones[y] = (int)((b << 8) - b);
-                }
+                for (int y = 0; y < 4; ++y)
+                  ones[y] = (int)__builtin_amdgcn_perm(w8[2 * y + 1] << up, w8[2 * y] << up, 0x0B0A0908u);
+                const i32x4 bits = ones;
                 const u32x4 l0 = from[2];
                 acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l0.x, (int)l0.y, (int)l0.z, (int)l0.w}, bits,
                                                                acc[0], 0, 0, 0);
@@ -900,16 +1042,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 #pragma unroll
               for (int v = 0; v < 4; ++v) {
                 const uint32_t a = 4u * (lane >> 4) + v, b = j;
-                const uint32_t total = (uint32_t)acc[0][v] + ((uint32_t)acc[1][v] << 7) + ((uint32_t)acc[2][v] << 14);
+                const uint32_t total = 0u - ((uint32_t)acc[0][v] + ((uint32_t)acc[1][v] << 7) + ((uint32_t)acc[2][v] << 14));
                 if (a <= b && b < R && total) atomicAdd(&oacc32[a * (R | 1u) + b], total);
               }
             }
           }
         }
         if (!swept) {
+        const uint32_t region_bits = 0xFFFFFFFFu >> (32u - R);  // places past the end carry a bit above the regions
 #pragma unroll
         for (int i = 0; i < kNR; ++i) {
-          const uint32_t x = sx[i], dm = end_mask(i), tt = st[i];
+          const uint32_t x = sx[i] & region_bits, dm = end_mask(i), tt = st[i];
           uint32_t act_before = pl[0];
 #pragma unroll
           for (int k = 1; k < PLANES; ++k) act_before |= pl[k];
@@ -924,7 +1067,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
             uint32_t* row = oacc32 + a * (R | 1u);
             const uint32_t val = dm ? tt : 0u - tt;
             atomicAdd(&row[a], val);
-            uint32_t set = act;
+            uint32_t set = act & region_bits;
             while (set) {
               const uint32_t bb = __ffs(set) - 1;
               set &= set - 1;
@@ -936,7 +1079,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
     }
     __syncthreads();
-    if (p.stop_after) continue;
+    } while (0);
+    {
+      const uint32_t ahead = wg + gridDim.x;
+      request(ahead < p.n_wg ? ahead : wg, tid);  // (the last one asks for its own again: nothing is assigned in a branch)
+    }
+    if (p.stop_after) { __syncthreads(); continue; }  // the next workgroup's clearing must not overtake a slower wave
 
     // ---- E: per-(workgroup, wave, region) output, fold into running totals ------------------------
     for (uint32_t e = tid; e < W * R; e += BLOCK) {
