@@ -83,36 +83,35 @@ struct DecodeParams {
   uint32_t stop_after;      // 0: everything; else leave each workgroup after this step (timing only), see kStep*
 };
 
-struct LdsLayout {  // byte offsets
-  uint32_t clk, meta, cells, hist, oacc, oacc32, reg_sum, reg_max, reg_min, pw_pack, pw_max, pw_min, ctr, tmp,
-      misc, vf, wtot, ptot, total;
+__host__ __device__ constexpr uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
+constexpr uint32_t kMaxPerWave = 1024;  // entries of the per-(wave, region) sums, copies included
+
+// LDS of a decoder workgroup of BLOCK threads, byte offsets.  Every array is sized for the largest
+// geometry the kernel takes, so that all addresses are compile-time constants.
+template <int BLOCK>
+struct Lds {
+  static constexpr uint32_t npos = BLOCK * kNR;
+  static constexpr uint32_t clk = 0;                                       // 4 words of padding after every 64
+  static constexpr uint32_t meta = align16(clk + (npos + npos / 16) * 4);
+  static constexpr uint32_t cells = align16(meta + npos + 16);             // one 16-bit counter per time cell, npos cells, + the total
+  static constexpr uint32_t ctr = align16(cells + (npos / 2 + 4) * 4);
+  static constexpr uint32_t tmp = ctr + 16 * 8;
+  static constexpr uint32_t misc = align16(tmp + T_COUNT * 4);
+  static constexpr uint32_t vf = misc + 4 * 4;
+  static constexpr uint32_t wtot = vf + 16 * 8;
+  static constexpr uint32_t ptot = wtot + 16 * 4;
+  static constexpr uint32_t hist = ptot + 16 * 8 * 4;
+  static constexpr uint32_t oacc = align16(hist + KP_MAX_REGIONS * kHistStride * 4);
+  static constexpr uint32_t oacc32 = oacc + KP_MAX_REGIONS * KP_MAX_REGIONS * 8;
+  static constexpr uint32_t reg_sum = align16(oacc32 + KP_MAX_REGIONS * (KP_MAX_REGIONS + 1) * 4);
+  static constexpr uint32_t reg_max = reg_sum + KP_MAX_REGIONS * 8;
+  static constexpr uint32_t reg_min = reg_max + KP_MAX_REGIONS * 4;
+  static constexpr uint32_t pw_pack = reg_min + KP_MAX_REGIONS * 4;
+  static constexpr uint32_t pw_max = pw_pack + kMaxPerWave * 8;
+  static constexpr uint32_t pw_min = pw_max + kMaxPerWave * 4;
+  static constexpr uint32_t total = pw_min + kMaxPerWave * 4;
+  static_assert(total <= kMaxLds, "decoder LDS exceeds one CU");
 };
-__host__ __device__ inline uint32_t align16(uint32_t x) { return (x + 15u) & ~15u; }
-__host__ __device__ inline LdsLayout lds_layout(uint32_t block, uint32_t W, uint32_t R, uint32_t ncopy) {
-  LdsLayout l;
-  const uint32_t npos = block * kNR;
-  uint32_t o = 0;
-  l.clk = o; o = align16(o + (npos + npos / 16) * 4);  // 4 words of padding after every 64
-  l.meta = o; o = align16(o + npos + 16);
-  l.cells = o; o = align16(o + (npos / 2 + 4) * 4);    // one 16-bit counter per time cell, npos cells, + the total
-  l.hist = o; o = align16(o + R * kHistStride * 4);
-  l.oacc = o; o = align16(o + R * R * 8);
-  l.oacc32 = o; o = align16(o + R * (R | 1u) * 4);
-  l.reg_sum = o; o = align16(o + R * 8);
-  l.reg_max = o; o = align16(o + R * 4);
-  l.reg_min = o; o = align16(o + R * 4);
-  l.pw_pack = o; o = align16(o + ncopy * W * R * 8);
-  l.pw_max = o; o = align16(o + ncopy * W * R * 4);
-  l.pw_min = o; o = align16(o + ncopy * W * R * 4);
-  l.ctr = o; o = align16(o + 16 * 8);
-  l.tmp = o; o = align16(o + T_COUNT * 4);
-  l.misc = o; o = align16(o + 4 * 4);
-  l.vf = o; o = align16(o + 16 * 8);
-  l.wtot = o; o = align16(o + 16 * 4);
-  l.ptot = o; o = align16(o + 16 * 8 * 4);
-  l.total = o;
-  return l;
-}
 
 // Word of the clock array that holds position i: 4 words of padding after every 64, so that the
 // 64 lanes of a wave reading 16 consecutive words each (64 bytes apart) spread over all banks.
@@ -373,26 +372,26 @@ __global__ void kp_reduce_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uin
 // so that neighbouring lanes hold neighbouring ranks.
 template <int BLOCK, int PLANES>
 __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const LdsLayout L = lds_layout(BLOCK, p.W, p.R, p.ncopy);
-  uint32_t* clk = reinterpret_cast<uint32_t*>(smem + L.clk);
-  uint8_t* meta = smem + L.meta;
-  uint32_t* cells = reinterpret_cast<uint32_t*>(smem + L.cells);  // cell c: half (c & 1) of word c >> 1
-  uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
-  unsigned long long* oacc = reinterpret_cast<unsigned long long*>(smem + L.oacc);
-  uint32_t* oacc32 = reinterpret_cast<uint32_t*>(smem + L.oacc32);  // this workgroup's sums modulo 2^32
-  unsigned long long* reg_sum = reinterpret_cast<unsigned long long*>(smem + L.reg_sum);
-  uint32_t* reg_max = reinterpret_cast<uint32_t*>(smem + L.reg_max);
-  uint32_t* reg_min = reinterpret_cast<uint32_t*>(smem + L.reg_min);
-  unsigned long long* pw_pack = reinterpret_cast<unsigned long long*>(smem + L.pw_pack);
-  uint32_t* pw_max = reinterpret_cast<uint32_t*>(smem + L.pw_max);
-  uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L.pw_min);
-  unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L.ctr);
-  uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L.tmp);
-  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);  // [0] span overflow, [1] cell scale, [2] span
-  uint2* sVF = reinterpret_cast<uint2*>(smem + L.vf);           // per wave: records held, first surviving seq
-  uint32_t* wtot = reinterpret_cast<uint32_t*>(smem + L.wtot);
-  uint32_t* ptot = reinterpret_cast<uint32_t*>(smem + L.ptot);
+  using L = Lds<BLOCK>;
+  __shared__ __align__(16) unsigned char smem[L::total];
+  uint32_t* clk = reinterpret_cast<uint32_t*>(smem + L::clk);
+  uint8_t* meta = smem + L::meta;
+  uint32_t* cells = reinterpret_cast<uint32_t*>(smem + L::cells);  // cell c: half (c & 1) of word c >> 1
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L::hist);
+  unsigned long long* oacc = reinterpret_cast<unsigned long long*>(smem + L::oacc);
+  uint32_t* oacc32 = reinterpret_cast<uint32_t*>(smem + L::oacc32);  // this workgroup's sums modulo 2^32
+  unsigned long long* reg_sum = reinterpret_cast<unsigned long long*>(smem + L::reg_sum);
+  uint32_t* reg_max = reinterpret_cast<uint32_t*>(smem + L::reg_max);
+  uint32_t* reg_min = reinterpret_cast<uint32_t*>(smem + L::reg_min);
+  unsigned long long* pw_pack = reinterpret_cast<unsigned long long*>(smem + L::pw_pack);
+  uint32_t* pw_max = reinterpret_cast<uint32_t*>(smem + L::pw_max);
+  uint32_t* pw_min = reinterpret_cast<uint32_t*>(smem + L::pw_min);
+  unsigned long long* ctr = reinterpret_cast<unsigned long long*>(smem + L::ctr);
+  uint32_t* tmp = reinterpret_cast<uint32_t*>(smem + L::tmp);
+  uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L::misc);  // [0] span overflow, [1] cell scale, [2] span
+  uint2* sVF = reinterpret_cast<uint2*>(smem + L::vf);           // per wave: records held, first surviving seq
+  uint32_t* wtot = reinterpret_cast<uint32_t*>(smem + L::wtot);
+  uint32_t* ptot = reinterpret_cast<uint32_t*>(smem + L::ptot);
 
   constexpr uint32_t NPOS = BLOCK * kNR, NCELL = NPOS;
   // The last four words of the clock array are padding that no position maps to, and the metadata
@@ -1152,34 +1151,32 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 }
 
 // Launch shape of one kernel instantiation for one LDS size, queried once per device.
-struct LaunchCache { int dev = -1; uint32_t lds = 0; uint32_t max_grid = 0; };
+struct LaunchCache { int dev = -1; uint32_t max_grid = 0; };
 
 template <int BLOCK, int PLANES>
-kp_status launch_main(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
+kp_status launch_main(const DecodeParams& p, hipStream_t s) {
   auto kern = kp_reduce_main<BLOCK, PLANES>;
   static thread_local LaunchCache cache;
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
-  if (cache.dev != dev || cache.lds != lds_bytes) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+  if (cache.dev != dev) {
     int per_cu = 0, cus = 0;
-    KP_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, BLOCK, lds_bytes));
-    if (per_cu < 1) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder kernel does not fit one CU (LDS %u B)", lds_bytes);
+    KP_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, BLOCK, 0));
+    if (per_cu < 1) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder kernel does not fit one CU (LDS %u B)", Lds<BLOCK>::total);
     KP_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    cache.dev = dev; cache.lds = lds_bytes; cache.max_grid = (uint32_t)per_cu * (uint32_t)cus;
+    cache.dev = dev; cache.max_grid = (uint32_t)per_cu * (uint32_t)cus;
   }
   uint32_t grid = cache.max_grid;
   if (grid > p.n_wg) grid = p.n_wg;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds_bytes, s, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), 0, s, p);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }
 
 template <int BLOCK>
-kp_status launch_planes(const DecodeParams& p, uint32_t lds_bytes, hipStream_t s) {
+kp_status launch_planes(const DecodeParams& p, hipStream_t s) {
   // counters of open waves per region run up to the number of waves
-  return p.W < 16 ? launch_main<BLOCK, 4>(p, lds_bytes, s) : launch_main<BLOCK, 5>(p, lds_bytes, s);
+  return p.W < 16 ? launch_main<BLOCK, 4>(p, s) : launch_main<BLOCK, 5>(p, s);
 }
 
 kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* out_stats, uint32_t stop_after,
@@ -1203,11 +1200,8 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
 
   const uint32_t W = h.waves_per_wg, R = h.n_regions, cap = h.cap_wave;
   const int block = nrec > 4096 ? 1024 : (nrec > 1024 ? 256 : 64);  // 16 positions per lane
-  uint32_t ncopy = 4;  // as many copies of the per-(wave, region) sums as LDS has room for
-  while (ncopy > 1 && lds_layout(block, W, R, ncopy).total > kMaxLds) ncopy >>= 1;
-  const LdsLayout L = lds_layout(block, W, R, ncopy);
-  if (L.total > kMaxLds)
-    return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "decoder needs %u B of LDS for this geometry (limit %u)", L.total, kMaxLds);
+  uint32_t ncopy = 4;  // as many copies of the per-(wave, region) sums as their LDS array has room for
+  while (ncopy > 1 && ncopy * W * R > kMaxPerWave) ncopy >>= 1;
 
   uint64_t* out = static_cast<uint64_t*>(out_stats);
   const uint8_t* base = static_cast<const uint8_t*>(raw);
@@ -1227,9 +1221,9 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     p.cap_log2 = 0; while ((1u << p.cap_log2) < cap) ++p.cap_log2;
     p.rec_cost = h.rec_cost; p.flush = h.flags & KP_FLAG_FLUSH;
     p.nrec = nrec; p.ncopy = ncopy; p.stop_after = stop_after;
-    const kp_status st = block == 1024 ? launch_planes<1024>(p, L.total, s)
-                       : block == 256  ? launch_planes<256>(p, L.total, s)
-                                       : launch_planes<64>(p, L.total, s);
+    const kp_status st = block == 1024 ? launch_planes<1024>(p, s)
+                       : block == 256  ? launch_planes<256>(p, s)
+                                       : launch_planes<64>(p, s);
     if (st != KP_OK) return st;
   }
   hipLaunchKernelGGL(kp_reduce_finalize, dim3(1), dim3(256), 0, s, out, h.n_wg, W, R);
