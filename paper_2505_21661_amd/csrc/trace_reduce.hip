@@ -33,6 +33,8 @@
 // takes no part in the overlap statistics and is paired by a plain serial walk per (wave, region).
 #include "kp_common.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -398,16 +400,22 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   // array has 16 spare bytes: stores of lanes that have nothing to store go there instead of branching.
   constexpr uint32_t kSpareWord = NPOS + NPOS / 16 - 1;
   const uint32_t tid_k = threadIdx.x;
-  const uint32_t W = p.W, R = p.R, cap = p.cap, nrec = p.nrec;
-  const uint32_t capm = cap - 1, cl2 = p.cap_log2;
-  const StatsLayout SL = stats_layout(p.n_wg, W, R);
+  // The kernel arguments arrive as one block of scalar registers.  Each one used in the loop gets a
+  // register of its own through an opaque move: when scalar registers run short the compiler then parks
+  // and fetches single values instead of the whole block.
+  auto own_reg = [](uint32_t x) -> uint32_t { uint32_t y; asm("s_mov_b32 %0, %1" : "=s"(y) : "s"(x)); return y; };
+  const uint32_t W = own_reg(p.W), R = own_reg(p.R), cap = own_reg(p.cap), nrec = own_reg(p.nrec);
+  const uint32_t capm = cap - 1, cl2 = own_reg(p.cap_log2);
+  const uint32_t n_wg = own_reg(p.n_wg), n_copies = own_reg(p.ncopy), stop_after = own_reg(p.stop_after);
+  const uint32_t rec_cost = own_reg(p.rec_cost), flush = own_reg(p.flush);
+  const StatsLayout SL = stats_layout(n_wg, W, R);
   if (p.out[H_STATUS] != 0) return;  // device header did not match the launch geometry
 
   for (uint32_t i = tid_k; i < R * kHistStride; i += BLOCK) hist[i] = 0;
   for (uint32_t i = tid_k; i < R * R; i += BLOCK) oacc[i] = 0;
   for (uint32_t i = tid_k; i < R * (R | 1u); i += BLOCK) oacc32[i] = 0;
   for (uint32_t i = tid_k; i < R; i += BLOCK) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
-  for (uint32_t i = tid_k; i < p.ncopy * W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
+  for (uint32_t i = tid_k; i < n_copies * W * R; i += BLOCK) { pw_pack[i] = 0; pw_max[i] = 0; pw_min[i] = 0xFFFFFFFFu; }
   if (tid_k < 16) ctr[tid_k] = 0;
   __syncthreads();
 
@@ -417,21 +425,26 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   u32x4 v[8];
   uint32_t h_total;  // lane & 15 -> records written by that wave
   uint2 h_begin, h_end;
-  auto request = [&](uint32_t g, uint32_t t) {
-    const uint32_t* whn = p.wg_hdrs + (size_t)32 * g;
-    h_total = whn[8 + (t & 15u)];
-    h_begin = *reinterpret_cast<const uint2*>(whn + 2);
-    h_end = *reinterpret_cast<const uint2*>(whn + 4);
+  constexpr int kEarly = 4;  // units requested before the matrix products of the sweep; the rest follow it
+  auto request_units = [&](uint32_t g, uint32_t t, auto first, auto last) {
     const u32x4* recs = p.records + (size_t)g * (nrec / 2);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = decltype(first)::value; u < decltype(last)::value; ++u) {
       const uint32_t i = t + u * BLOCK;
       v[u] = __builtin_nontemporal_load(recs + (i < nrec / 2 ? i : nrec / 2 - 1));
     }
   };
-  request(blockIdx.x, tid_k);
+  auto request_rest = [&](uint32_t g, uint32_t t) {
+    const uint32_t* whn = p.wg_hdrs + (size_t)32 * g;
+    h_total = whn[8 + (t & 15u)];
+    h_begin = *reinterpret_cast<const uint2*>(whn + 2);
+    h_end = *reinterpret_cast<const uint2*>(whn + 4);
+    request_units(g, t, std::integral_constant<int, kEarly>{}, std::integral_constant<int, 8>{});
+  };
+  request_units(blockIdx.x, tid_k, std::integral_constant<int, 0>{}, std::integral_constant<int, kEarly>{});
+  request_rest(blockIdx.x, tid_k);
 
-  for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
+  for (uint32_t wg = blockIdx.x; wg < n_wg; wg += gridDim.x) {
     // A fresh copy of the thread index per workgroup that the optimiser cannot see through: without it
     // the address arithmetic of all 16 rounds is computed once before the loop and held in registers
     // for the whole kernel.
@@ -446,7 +459,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     if (tid < W) {
       const uint32_t T = h_total;
       const uint32_t V = T < cap ? T : cap;
-      sVF[tid] = make_uint2(V, p.flush ? 0u : T - V);
+      sVF[tid] = make_uint2(V, flush ? 0u : T - V);
       atomicAdd(&ctr[H_DROPPED], (unsigned long long)(T - V));
       atomicAdd(&ctr[H_SLOTS_VALID], (unsigned long long)V);
     }
@@ -474,6 +487,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
 
     uint32_t wg_invalid = 0;
     bool eligible = false;
+    uint32_t products = 0;  // limbs of the stretch lengths when the sweep hands its sets to the matrix cores, else 0
+    const uint32_t wg_ahead = wg + gridDim.x < n_wg ? wg + gridDim.x : wg;  // (the last one asks for its own again)
     do {  // (left early only when single steps are timed)
     // ---- A: scatter by rank ------------------------------------------------------------------
     // Eight 16-byte units (two records each) per thread cover the workgroup.  Two records that go to an
@@ -522,7 +537,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       add_tmp(tmp, T_DISORDER, c_dis);
     }
     __syncthreads();
-    if (p.stop_after == kStepOrdered) break;
+    if (stop_after == kStepOrdered) break;
 
     // ---- a duplicated seq leaves fewer occupied ranks than valid records ---------------------------
     // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
@@ -587,15 +602,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     auto meta_of = [&](int i) -> uint32_t { return (mq[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
     auto set_paired = [&](int i, uint32_t yes) { mq[i >> 2] |= (yes << 6) << (8 * (i & 3)); };  // yes: 0 or 1
     wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - n_occupied);
-    const uint32_t rec_cost = p.rec_cost;
 
     // One pair: duration into the per-(wave, region) sums and the histogram.  The sums exist in up to
     // four copies, one per quarter of the wave: lanes 16 apart tend to hold the same region, and LDS
     // atomics of one instruction that hit one address are processed one after the other.
-    const uint32_t copy = (lane >> 4) & (p.ncopy - 1u);
+    const uint32_t copy = (lane >> 4) & (n_copies - 1u);
     auto account_pair = [&](uint32_t w, uint32_t region, uint32_t d_raw) {
       const uint32_t d = d_raw > rec_cost ? d_raw - rec_cost : 0u;
-      const uint32_t e = __umul24(__umul24(w, R) + region, p.ncopy) + copy;
+      const uint32_t e = __umul24(__umul24(w, R) + region, n_copies) + copy;
       atomicAdd(&pw_pack[e], (1ull << 46) | (unsigned long long)d);
       atomicMax(&pw_max[e], d);
       atomicMin(&pw_min[e], d);
@@ -741,7 +755,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     __syncthreads();
     eligible = !misc[0] && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
 
-    if (eligible && p.stop_after != kStepPaired) {
+    if (eligible && stop_after != kStepPaired) {
       // ---- C: order the paired records of all waves by clock ---------------------------------------
       // marks left by ENDs of other hardware waves (only the last position can have one) and by walks
       set_paired(kNR - 1, ((uint32_t)meta[qe + 128u * (kNR / 2 - 1) + 1u] >> 6) & 1u);
@@ -768,7 +782,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       if (__builtin_amdgcn_ballot_w64(t_max > misc[2]) && lane == 0u) tmp[T_WIDE] = 1u;  // a clock past the span
       __syncthreads();
-      if (p.stop_after == kStepCounted) break;
+      if (stop_after == kStepCounted) break;
       {  // exclusive prefix sum over the cell counters, 16 cells (8 words) per thread
         u32x4 a = reinterpret_cast<u32x4*>(cells)[2 * tid], b = reinterpret_cast<u32x4*>(cells)[2 * tid + 1];
         uint32_t wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -805,7 +819,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         if (tid == BLOCK - 1) { cells[NCELL / 2] = base + run; tmp[T_EVENTS] = base + run; }
       }
       __syncthreads();
-      if (p.stop_after == kStepCellSums) break;
+      if (stop_after == kStepCellSums) break;
       auto cell_start = [&](uint32_t c) -> uint32_t { return (cells[c >> 1] >> ((c & 1u) << 4)) & 0xFFFFu; };
       // sorted sequence entry besides the clock: region << 1 | END
       auto info_of = [&](int i) -> uint32_t { return ((meta_of(i) & 0x1Fu) << 1) | (meta_of(i) >> 7); };
@@ -822,7 +836,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           meta[ev ? g : NPOS] = (uint8_t)info_of(i);
         }
         __syncthreads();
-        if (p.stop_after >= kStepPlaced && p.stop_after <= kStepSorted) break;
+        if (stop_after >= kStepPlaced && stop_after <= kStepSorted) break;
       } else {
       // provisional place: cell start + arrival slot (plain index here, the padded layout comes with the
       // final places)
@@ -837,7 +851,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         nm[i] = ((s1 - s0) | (mine << 16)) & ev;
       }
       __syncthreads();
-      if (p.stop_after == kStepPlaced) break;
+      if (stop_after == kStepPlaced) break;
       // rank among the records of the same cell: by clock, then by arrival slot
 #pragma unroll
       for (int i = 0; i < kNR; ++i) {
@@ -852,7 +866,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         ca[i] = s0 + before;
       }
       __syncthreads();
-      if (p.stop_after == kStepRanked) break;
+      if (stop_after == kStepRanked) break;
 #pragma unroll
       for (int i = 0; i < kNR; ++i) {
         const bool ev = (meta_of(i) & kPaired) != 0u;
@@ -860,7 +874,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         meta[ev ? ca[i] : NPOS] = (uint8_t)info_of(i);
       }
       __syncthreads();
-      if (p.stop_after == kStepSorted) break;
+      if (stop_after == kStepSorted) break;
       }
 
       // ---- D: region-pair overlap, 16 consecutive records of the sorted sequence per lane ----------
@@ -1001,50 +1015,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
             own[2] = u32x4{limb[0][0], limb[0][1], limb[0][2], limb[0][3]};
             own[3] = u32x4{limb[1][0], limb[1][1], limb[1][2], limb[1][3]};
             reinterpret_cast<u32x4*>(meta)[tid] = u32x4{limb[2][0], limb[2][1], limb[2][2], limb[2][3]};
-            __builtin_amdgcn_wave_barrier();
-            if ((tid & ~63u) * kNR < n_events) {  // this wave holds records
-              typedef int i32x4 __attribute__((ext_vector_type(4)));
-              i32x4 acc[3];
-#pragma unroll
-              for (int l = 0; l < 3; ++l) acc[l] = i32x4{0, 0, 0, 0};
-              const uint32_t j = lane & 15u;  // operand row / column: region j
-              const uint32_t up = 15u - j;      // shift that takes bit j of a 16-bit set to its top
-              for (uint32_t n = 0; n < 16; ++n) {  // 64 segments: those of lanes 4n .. 4n + 3
-                const uint32_t src = (tid & ~63u) + 4u * n + (lane >> 4);
-                const u32x4* from = reinterpret_cast<const u32x4*>(clk + clk_word(src * kNR));
-                const u32x4 s0 = from[0], s1 = from[1];
-                const uint32_t w8[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-                // One byte per segment, all ones if region j is open in it: the byte permute's selectors 8..11
-                // replicate the top bits of the four halves of its two operands.  As an i8 operand such a byte
-                // is -1, so the products below come out negated.
-                i32x4 ones;
-#pragma unroll
-                for (int y = 0; y < 4; ++y)
-                  ones[y] = (int)__builtin_amdgcn_perm(w8[2 * y + 1] << up, w8[2 * y] << up, 0x0B0A0908u);
-                const i32x4 bits = ones;
-                const u32x4 l0 = from[2];
-                acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l0.x, (int)l0.y, (int)l0.z, (int)l0.w}, bits,
-                                                               acc[0], 0, 0, 0);
-                if (n_limbs > 1u) {
-                  const u32x4 l1 = from[3];
-                  acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l1.x, (int)l1.y, (int)l1.z, (int)l1.w}, bits,
-                                                                 acc[1], 0, 0, 0);
-                }
-                if (n_limbs > 2u) {
-                  const u32x4 l2 = reinterpret_cast<const u32x4*>(meta)[src];
-                  acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l2.x, (int)l2.y, (int)l2.z, (int)l2.w}, bits,
-                                                                 acc[2], 0, 0, 0);
-                }
-              }
-              // element v of a lane: row 4 * (lane / 16) + v, column lane % 16.  The product is symmetric and the
-              // fold below adds the two halves of a pair: the upper triangle takes the whole sum.
-#pragma unroll
-              for (int v = 0; v < 4; ++v) {
-                const uint32_t a = 4u * (lane >> 4) + v, b = j;
-                const uint32_t total = 0u - ((uint32_t)acc[0][v] + ((uint32_t)acc[1][v] << 7) + ((uint32_t)acc[2][v] << 14));
-                if (a <= b && b < R && total) atomicAdd(&oacc32[a * (R | 1u) + b], total);
-              }
-            }
+            products = (tid & ~63u) * kNR < n_events ? n_limbs : 0u;  // this wave holds records
           }
         }
         if (!swept) {
@@ -1077,20 +1048,64 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         }
       }
     }
-    __syncthreads();
     } while (0);
-    {
-      const uint32_t ahead = wg + gridDim.x;
-      request(ahead < p.n_wg ? ahead : wg, tid);  // (the last one asks for its own again: nothing is assigned in a branch)
+    // The first records of the next workgroup travel while the matrix cores work.
+    request_units(wg_ahead, tid, std::integral_constant<int, 0>{}, std::integral_constant<int, kEarly>{});
+    if (products) {  // wave-uniform
+      const uint32_t n_limbs = products;
+      __builtin_amdgcn_wave_barrier();
+      typedef int i32x4 __attribute__((ext_vector_type(4)));
+      i32x4 acc[3];
+#pragma unroll
+      for (int l = 0; l < 3; ++l) acc[l] = i32x4{0, 0, 0, 0};
+      const uint32_t j = lane & 15u;  // operand row / column: region j
+      const uint32_t up = 15u - j;      // shift that takes bit j of a 16-bit set to its top
+      for (uint32_t n = 0; n < 16; ++n) {  // 64 segments: those of lanes 4n .. 4n + 3
+        const uint32_t src = (tid & ~63u) + 4u * n + (lane >> 4);
+        const u32x4* from = reinterpret_cast<const u32x4*>(clk + clk_word(src * kNR));
+        const u32x4 s0 = from[0], s1 = from[1];
+        const uint32_t w8[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        // One byte per segment, all ones if region j is open in it: the byte permute's selectors 8..11
+        // replicate the top bits of the four halves of its two operands.  As an i8 operand such a byte
+        // is -1, so the products below come out negated.
+        i32x4 ones;
+#pragma unroll
+        for (int y = 0; y < 4; ++y)
+          ones[y] = (int)__builtin_amdgcn_perm(w8[2 * y + 1] << up, w8[2 * y] << up, 0x0B0A0908u);
+        const i32x4 bits = ones;
+        const u32x4 l0 = from[2];
+        acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l0.x, (int)l0.y, (int)l0.z, (int)l0.w}, bits,
+                                                       acc[0], 0, 0, 0);
+        if (n_limbs > 1u) {
+          const u32x4 l1 = from[3];
+          acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l1.x, (int)l1.y, (int)l1.z, (int)l1.w}, bits,
+                                                         acc[1], 0, 0, 0);
+        }
+        if (n_limbs > 2u) {
+          const u32x4 l2 = reinterpret_cast<const u32x4*>(meta)[src];
+          acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones & i32x4{(int)l2.x, (int)l2.y, (int)l2.z, (int)l2.w}, bits,
+                                                         acc[2], 0, 0, 0);
+        }
+      }
+      // element v of a lane: row 4 * (lane / 16) + v, column lane % 16.  The product is symmetric and the
+      // fold below adds the two halves of a pair: the upper triangle takes the whole sum.
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const uint32_t a = 4u * (lane >> 4) + v, b = j;
+        const uint32_t total = 0u - ((uint32_t)acc[0][v] + ((uint32_t)acc[1][v] << 7) + ((uint32_t)acc[2][v] << 14));
+        if (a <= b && b < R && total) atomicAdd(&oacc32[a * (R | 1u) + b], total);
+      }
     }
-    if (p.stop_after) { __syncthreads(); continue; }  // the next workgroup's clearing must not overtake a slower wave
+    __syncthreads();
+    request_rest(wg_ahead, tid);
+    if (stop_after) continue;
 
     // ---- E: per-(workgroup, wave, region) output, fold into running totals ------------------------
     for (uint32_t e = tid; e < W * R; e += BLOCK) {
       unsigned long long pk = 0;
       uint32_t mx = 0, mn = 0xFFFFFFFFu;
-      for (uint32_t c = 0; c < p.ncopy; ++c) {
-        const uint32_t ec = e * p.ncopy + c;
+      for (uint32_t c = 0; c < n_copies; ++c) {
+        const uint32_t ec = e * n_copies + c;
         pk += pw_pack[ec];
         mx = pw_max[ec] > mx ? pw_max[ec] : mx;
         mn = pw_min[ec] < mn ? pw_min[ec] : mn;
