@@ -425,7 +425,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   u32x4 v[8];
   uint32_t h_total;  // lane & 15 -> records written by that wave
   uint2 h_begin, h_end;
-  constexpr int kEarly = 4;  // units requested before the matrix products of the sweep; the rest follow it
+  constexpr int kEarly = 6;  // units requested before the matrix products of the sweep; the rest follow it
   auto request_units = [&](uint32_t g, uint32_t t, auto first, auto last) {
     const u32x4* recs = p.records + (size_t)g * (nrec / 2);
 #pragma unroll
@@ -468,10 +468,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       const uint64_t tb = (uint64_t)h_begin.x | ((uint64_t)h_begin.y << 32);
       const uint64_t te = (uint64_t)h_end.x | ((uint64_t)h_end.y << 32);
       const uint64_t sp = te - tb;
-      // cell of clock t: (t * scale) >> 32, i.e. the span divided into NCELL cells (clamped below)
-      uint64_t scale = ((uint64_t)NCELL << 32) / ((sp & 0xFFFFFFFFull) + 1ull);
+      // cell of clock t: (t * scale) >> 32, i.e. the span divided into NCELL cells (clamped below).  Any
+      // scale near NCELL * 2^32 / (span + 1) orders the cells by time, so a floating-point quotient does:
+      // a 64-bit integer division is some 150 instructions that every wave of the workgroup waits for.
+      const double scale = (double)NCELL * 4294967296.0 / ((double)(uint32_t)sp + 1.0);
       misc[0] = (sp >> 32) ? 1u : 0u;
-      misc[1] = scale > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)scale;
+      misc[1] = scale >= 4294967295.0 ? 0xFFFFFFFFu : (uint32_t)scale;
       misc[2] = (uint32_t)sp;
     }
     reinterpret_cast<u32x4*>(meta)[tid] = u32x4{0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu, 0x3F3F3F3Fu};
@@ -1144,8 +1146,11 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       ctr[H_SPAN_OVF] += misc[0];
       ctr[H_OVERLAP_WGS] += eligible ? 1u : 0u;
     }
-    __syncthreads();
+    // No barrier here: the arrays this tail reads and resets are next written in B, two barriers on, and
+    // what the head of the next workgroup writes first (temporaries, header words) is touched here only by
+    // thread 0, whose own wave writes them there.
   }
+  __syncthreads();
 
   // ---- flush this decoder workgroup's totals --------------------------------------------------
   unsigned long long* out = reinterpret_cast<unsigned long long*>(p.out);
