@@ -5,7 +5,8 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
   1. bf16 GEMM 4096^3: one warm launch, then uninstrumented / instrumented (all 4 regions, ring of
      4096 records per workgroup) launched alternately, two of each; then the same for the
      stage-by-stage schedule of the K step with its configured 5 regions (514 records per wave),
-     and two launches with a region masked off (generic record sites)
+     and two launches each with a region masked off (generic record sites), with the 64-lane store on
+     top of that, and with the constant-rate clock on top of that
   2. kp_trace_reduce of the GEMM trace
   3. causal attention forward 4x32x4096x128: warm launch, then uninstrumented / instrumented
      (3 regions, ring of 1024 records per workgroup, wraps) alternately, two of each
@@ -275,7 +276,8 @@ def main() -> int:
     # clock sags over a burst of MFMA kernels, and in this order both kinds sit at the same mean
     # position in the burst; every launch is inside the timed step.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_instr2", "gemm_vanilla2", "gemm_reduce",
-             "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm_masked", "gemm_masked2",
+             "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm_masked", "gemm_collab", "gemm_realtime",
+             "gemm_realtime2", "gemm_collab2", "gemm_masked2",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_instr2", "attn_vanilla2", "attn_reduce", "decode",
              "timeline", "waits", "stages"]
 
@@ -285,12 +287,14 @@ def main() -> int:
         gemm5_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, kp.KP_MASK_PHASES, None, 0)
         gemm5_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b11111 | kp.KP_MASK_PHASES, g_trace, g_cap)
         gemm_m = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011, g_trace, g_cap)
+        gemm_c = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011 | kp.KP_MASK_COLLAB, g_trace, g_cap)
+        gemm_r = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011 | kp.KP_MASK_REALTIME, g_trace, g_cap)
         attn_v = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0, None, 0)
         attn_i = lambda: kp.kp_attn_instrumented(Q, Kt, V, O, Bt, H, S, D, True, scale, 0b111, a_trace, a_cap)
         calls = (
             gemm_v, gemm_v, gemm_i, gemm_i, gemm_v,
             lambda: kp.kp_trace_reduce_hdr(g_trace, g_wg * g_cap, g_hdr, g_stats),
-            gemm5_v, gemm5_i, gemm5_i, gemm5_v, gemm_m, gemm_m,
+            gemm5_v, gemm5_i, gemm5_i, gemm5_v, gemm_m, gemm_c, gemm_r, gemm_r, gemm_c, gemm_m,
             attn_v, attn_v, attn_i, attn_i, attn_v,
             lambda: kp.kp_trace_reduce_hdr(a_trace, a_wg * a_cap, a_hdr, a_stats),
             lambda: kp.kp_trace_reduce_hdr(d_raw, d_n, d_hdr, d_stats),
@@ -331,7 +335,8 @@ def main() -> int:
     tf_ins = gemm_flop / ms["gemm_instr"] / 1e9
     overhead = (ms["gemm_instr"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
     overhead5 = (ms["gemm5_instr"] - ms["gemm5_vanilla"]) / ms["gemm5_vanilla"] * 100.0
-    ms["gemm_masked"] = 0.5 * (ms["gemm_masked"] + ms.pop("gemm_masked2"))
+    for leg in ("gemm_masked", "gemm_collab", "gemm_realtime"):
+        ms[leg] = 0.5 * (ms[leg] + ms.pop(leg + "2"))
     overhead_masked = (ms["gemm_masked"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
     attn_tf_van = attn_flop / ms["attn_vanilla"] / 1e9
     attn_tf_ins = attn_flop / ms["attn_instr"] / 1e9
@@ -417,6 +422,10 @@ def main() -> int:
             "value": round(overhead_masked, 3),
             "what": "default schedule with region 2 masked off (region_mask 0b1011): the generic record sites "
                     "that a mask, the flush strategy or wave-group records select",
+            "with_64_lane_store_and_hw_ids": round((ms["gemm_collab"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0, 3),
+            "with_constant_rate_clock": round((ms["gemm_realtime"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0, 3),
+            "variants": "same mask with KP_MASK_COLLAB (Sec. 4.2: all lanes store the record, hardware ids in the "
+                        "workgroup header) and with KP_MASK_REALTIME (Sec. 3.1 MetricType: 100 MHz clock)",
         },
         "uninstrumented_tflops": round(tf_van, 2),
         "uninstrumented_frac_of_mfma_peak": round(tf_van / PEAK_BF16_TFLOPS, 4),

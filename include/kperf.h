@@ -58,6 +58,8 @@ enum {
 #define KP_TRACE_MAGIC 0x4652504Bu /* bytes 'K','P','R','F' */
 #define KP_TRACE_VERSION 1u
 #define KP_FLAG_FLUSH 1u            /* kp_trace_hdr.flags bit 0: 0 circular, 1 flush */
+#define KP_FLAG_REALTIME 2u         /* bit 1: payloads, t_begin and t_end are ticks of the constant-rate 100 MHz clock */
+#define KP_FLAG_HW_IDS 4u           /* bit 2: kp_wg_hdr.wave_hw_id[] holds the hardware id of every record stream's wave */
 #define KP_MAX_WAVES 16
 #define KP_MAX_REGIONS 32           /* decoder limit; the tag field itself holds 7 bits */
 #define KP_HIST_BINS 64
@@ -80,7 +82,8 @@ typedef struct kp_wg_hdr {
   uint64_t t_end;                         /* 64-bit clock at flush                         */
   uint64_t reserved;
   uint32_t total_written[KP_MAX_WAVES];   /* records each wave tried to write              */
-  uint32_t pad[8];
+  uint16_t wave_hw_id[KP_MAX_WAVES];      /* KP_FLAG_HW_IDS: low 12 bits of the hardware id register of the wave
+                                             that wrote the stream (wave slot, SIMD, pipe, CU; Sec. 4.2), else 0 */
 } kp_wg_hdr;               /* 128 bytes */
 
 /* ---- statistics block written by the decoder ------------------------------------------------
@@ -255,10 +258,10 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
 
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
- * region_mask: bit r (r < 29) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
+ * region_mask: bit r (r < 27) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
  * selects the flush strategy instead of the default circular one (Sec. 4.2: "Circular" keeps
  * the newest records in LDS and copies them out once at kernel exit; "Flush" writes a full
- * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..28 all zero
+ * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..26 all zero
  * launches the separately compiled uninstrumented kernel: no ring, no record sites; trace_buf
  * may then be NULL.  Instrumented and uninstrumented kernels produce bit-identical outputs.
  *
@@ -269,6 +272,17 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
  * waves_per_wg, the tag's wave field and total_written[] count streams), and every size below
  * that speaks of waves speaks of streams.
  *
+ * Bit 28 (KP_MASK_REALTIME) selects the metric of the records (Sec. 3.1: the MetricType of the
+ * counter read): 0 the shader clock, 1 the constant-rate 100 MHz clock; the trace then carries
+ * KP_FLAG_REALTIME, its payloads and the headers' t_begin / t_end are in that clock's ticks and
+ * kp_wg_hdr.reserved holds the span on the shader clock.
+ *
+ * Bit 27 (KP_MASK_COLLAB) selects the store of Sec. 4.2 ("AMD"): all 64 lanes of the wave write the
+ * record to the same LDS address instead of one lane under a narrowed execution mask, and every
+ * stream's wave leaves the low 12 bits of its hardware id register in kp_wg_hdr.wave_hw_id[]
+ * (KP_FLAG_HW_IDS).  The records themselves are the same either way.
+ * Bits 27, 28 and 30 and the flush strategy go through the generic record sites.
+ *
  * trace_buf: device, kp_trace_bytes(n_wg, streams, trace_cap) bytes, 16-byte aligned; headers and
  * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written
  * hold unspecified bytes).  trace_cap: record slots per workgroup in HBM; trace_cap / streams must
@@ -278,6 +292,8 @@ kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap
 #define KP_MASK_FLUSH 0x80000000u
 #define KP_MASK_WAVE_GROUP 0x40000000u
 #define KP_MASK_PHASES 0x20000000u
+#define KP_MASK_REALTIME 0x10000000u
+#define KP_MASK_COLLAB 0x08000000u
 
 /* Launch geometry kp_gemm_instrumented will use for M x N x K: recorded workgroups, waves per
  * workgroup, number of regions.  KP_ERR_UNSUPPORTED_SHAPE if no kernel covers the shape. */
@@ -344,7 +360,8 @@ kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void
  * among and which decides the constant a region is measured too long by: neither bit the generic sites
  * (region mask, either strategy, either clock), bit 4 the lean sites (all regions, circular strategy:
  * the attention kernel and the small GEMM), bit 5 the deferred sites of the 256x256x64 GEMM; with
- * either bit, bits 1..3 must be 0 (KP_ERR_INVALID_ARG otherwise).
+ * either bit, bits 1..3 and 6 must be 0 (KP_ERR_INVALID_ARG otherwise).  mode bit6 selects the
+ * store of KP_MASK_COLLAB (all lanes write the record; hardware ids in the workgroup header).
  *   cycles     HOST pointer to n_regions values (n_regions <= 32)
  *   trace_buf  device, kp_trace_bytes(n_wg, streams, trace_cap) bytes; trace_cap as above
  */

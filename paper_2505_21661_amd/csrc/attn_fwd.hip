@@ -38,6 +38,8 @@ struct AttnArgs {
   uint32_t cap_lds, cap_hbm, flush, n_wg;
   uint32_t rec_cost;  // ticks the decoder takes off every duration (kp_set_rec_cost)
   uint32_t group_log2;  // 2^group_log2 waves share one record stream
+  uint32_t collab;      // 1: all lanes store a record, hardware ids go to the workgroup header
+  uint32_t flags;       // kp_trace_hdr.flags of the trace
 };
 
 constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
@@ -99,6 +101,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, 4u >> g.group_log2, wg, g.group_log2);
+  ring.collab = g.collab;
+  if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
   if constexpr (INSTR == 2) kp::lean_begin(ring);
 
   // Q fragments of this wave's 32 rows stay in registers: step s covers d = 16s .. 16s+15
@@ -288,9 +292,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       *reinterpret_cast<u32x2*>(orow + 32 * dt + 8 * q + 4 * h32) = pk2;
     }
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flags};
     if constexpr (INSTR == 2) kp::lean_end(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -320,7 +324,9 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
     return kp::fail(KP_ERR_INVALID_ARG, "Q, K, V, O must be 16-byte aligned");
   if (!(scale > 0.f) || scale > 1e30f) return kp::fail(KP_ERR_INVALID_ARG, "scale must be positive and finite");
-  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP), flush = region_mask >> 31;
+  if (region_mask & KP_MASK_PHASES) return kp::fail(KP_ERR_INVALID_ARG, "KP_MASK_PHASES belongs to the GEMM");
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_REALTIME | KP_MASK_COLLAB), flush = region_mask >> 31;
+  const bool realtime = (region_mask & KP_MASK_REALTIME) != 0u, collab = (region_mask & KP_MASK_COLLAB) != 0u;
   const uint32_t group_log2 = (region_mask & KP_MASK_WAVE_GROUP) ? 2u : 0u;
   const size_t streams = 4u >> group_log2;
   const int n_wg = B * H * (S / kBq);
@@ -332,6 +338,8 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   g.scale_log2 = scale * 1.4426950408889634f;
   g.region_mask = regions; g.trace = trace_buf; g.flush = flush; g.n_wg = (uint32_t)n_wg;
   g.group_log2 = group_log2;
+  g.collab = collab ? 1u : 0u;
+  g.flags = (flush ? KP_FLAG_FLUSH : 0u) | (realtime ? KP_FLAG_REALTIME : 0u) | (collab ? KP_FLAG_HW_IDS : 0u);
   const uint32_t tile_bytes = kKBytes + kVBytes;
   if (regions == 0) {
     hipLaunchKernelGGL(kp_attn_fwd<0>, dim3(n_wg), dim3(kAttnThreads), tile_bytes, st, g);
@@ -358,11 +366,15 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<3>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     attr_dev = dev;
   }
   // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
-  if (!flush && !group_log2 && regions == 7u && S <= (1 << 22))
+  if (!flush && !group_log2 && !realtime && !collab && regions == 7u && S <= (1 << 22))
     hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  else if (realtime)
+    hipLaunchKernelGGL(kp_attn_fwd<3>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   else
     hipLaunchKernelGGL(kp_attn_fwd<1>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());

@@ -19,6 +19,7 @@ struct CalibArgs {
   uint32_t n_regions;
   uint32_t mode;
   uint32_t rec_cost;
+  uint32_t collab;  // all lanes store a record, hardware ids go to the workgroup header
 };
 
 // n dependent FMAs (rounded down to a multiple of 16); each waits for the previous result.
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
   kp::Ring r = kp::ring_init<GROUPS>(lds_ring, t_begin, cap_lds, 0xFFFFFFFFu, flush, cap_hbm, trace, n_wg, streams, blockIdx.x,
                              group_log2);
   if constexpr (REALTIME) kp::ring_use_realtime(r);
+  r.collab = a.collab;
   float x = (float)threadIdx.x;
   // Two identical passes: the first warms the instruction cache and is then discarded by
   // resetting the ring state, so that no recorded region pays for a cold code fetch.
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
     }
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
-  kp::TraceGeom g{n_wg, streams, a.n_regions, cap_hbm, flush ? KP_FLAG_FLUSH : 0u};
+  kp::TraceGeom g{n_wg, streams, a.n_regions, cap_hbm,
+                  (flush ? KP_FLAG_FLUSH : 0u) | (REALTIME ? KP_FLAG_REALTIME : 0u) | (a.collab ? KP_FLAG_HW_IDS : 0u)};
   kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, a.rec_cost);
 }
 
@@ -101,10 +104,10 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
                                   void* trace_buf, size_t trace_cap, void* stream) {
   kp::clear_error();
   if (!cycles || !trace_buf) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
-  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~63))
+  if (n_regions < 1 || n_regions > KP_MAX_REGIONS || n_wg < 1 || waves < 1 || waves > KP_MAX_WAVES || (mode & ~127))
     return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
   const int site = (mode & 16) ? 2 : ((mode & 32) ? 4 : 1);
-  if ((mode & 48) == 48 || (site != 1 && (mode & (2 | 4 | 8))))
+  if ((mode & 48) == 48 || (site != 1 && (mode & (2 | 4 | 8 | 64))))
     return kp::fail(KP_ERR_INVALID_ARG, "mode=%d: the lean and deferred site forms record per wave, on the shader clock, circular", mode);
   const uint32_t group_log2 = (mode & 8) ? 2u : 0u;
   if (group_log2 && (waves & 3)) return kp::fail(KP_ERR_INVALID_ARG, "wave-group records need a multiple of 4 waves, got %d", waves);
@@ -124,6 +127,7 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
   a.n_regions = (uint32_t)n_regions;
   a.mode = (uint32_t)(mode & 1);
   a.rec_cost = kp::rec_cost();
+  a.collab = (mode & 64) ? 1u : 0u;
   // more than half of the CU's LDS per workgroup: one workgroup per CU, one wave per SIMD for waves <= 4
   const uint32_t lds_bytes = 96 * 1024;
   static thread_local int attr_dev = -1;  // the attribute is kept per device

@@ -35,6 +35,8 @@ struct GemmArgs {
   uint32_t cap_lds, cap_hbm, flush, n_wg;
   uint32_t rec_cost;  // ticks the decoder takes off every duration (kp_set_rec_cost)
   uint32_t group_log2;  // 2^group_log2 waves share one record stream
+  uint32_t collab;      // 1: all lanes store a record, hardware ids go to the workgroup header
+  uint32_t flags;       // kp_trace_hdr.flags of the trace
 };
 
 // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
@@ -99,6 +101,8 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init<true>(ring_lds, t_begin, g.cap_lds, g.region_mask, g.flush, g.cap_hbm, g.trace, g.n_wg, 4u >> g.group_log2, wg,
                          g.group_log2);
+  ring.collab = g.collab;
+  if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
   kp::sites_begin<SITE>(ring);
 
   // global -> register mapping
@@ -159,9 +163,9 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
     g.C[(size_t)row * g.N + col] = (uint16_t)f32_to_bf16_rne(acc[v]);
   }
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flags};
     kp::sites_end<SITE>(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -210,6 +214,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   if constexpr (INSTR != 0)
     ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, (uint32_t)WAVES >> g.group_log2, wg, g.group_log2);
+  ring.collab = g.collab;
+  if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
   kp::sites_begin<SITE>(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
@@ -419,10 +425,10 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   }
   KP_SITE_K(ring, 1, PHASED ? 4 : 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
-    kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flush ? KP_FLAG_FLUSH : 0u};
+    kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
     if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
     else kp::sites_end<SITE>(ring);
-    kp::ring_finish(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -490,7 +496,8 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (!pick_shape(M, N, K, &s))
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "GEMM %dx%dx%d: M,N must be multiples of 64 and K of 32", M, N, K);
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "A, B, C must be 16-byte aligned");
-  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_PHASES);
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_PHASES | KP_MASK_REALTIME | KP_MASK_COLLAB);
+  const bool realtime = (region_mask & KP_MASK_REALTIME) != 0u, collab = (region_mask & KP_MASK_COLLAB) != 0u;
   const bool phased = (region_mask & KP_MASK_PHASES) != 0u;
   if (phased) {
     if (s.bm != 256) return kp::fail(KP_ERR_INVALID_ARG, "KP_MASK_PHASES: only the 256x256x64 kernel has the stage-by-stage K step");
@@ -506,6 +513,8 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.M = (uint32_t)M; g.N = (uint32_t)N; g.K = (uint32_t)K;
   g.region_mask = regions; g.trace = trace_buf; g.n_wg = (uint32_t)n_wg; g.flush = flush;
   g.group_log2 = group_log2;
+  g.collab = collab ? 1u : 0u;
+  g.flags = (flush ? KP_FLAG_FLUSH : 0u) | (realtime ? KP_FLAG_REALTIME : 0u) | (collab ? KP_FLAG_HW_IDS : 0u);
   const bool big = s.bm == 256;
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
     if (big) return launch_big_w<0>(phased, g, n_wg, 0, st);
@@ -526,9 +535,11 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
-  const bool lean = !flush && !group_log2 && regions == (1u << s.regions) - 1u && K <= (1 << 22);
-  if (big) return lean ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st);
+  const bool lean = !flush && !group_log2 && !realtime && !collab && regions == (1u << s.regions) - 1u && K <= (1 << 22);
+  if (big) return lean ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st)
+                       : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
+  else if (realtime) hipLaunchKernelGGL(kp_gemm_small<3>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;

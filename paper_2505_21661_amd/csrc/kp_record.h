@@ -36,6 +36,7 @@ struct Ring {
   uint32_t mask;       // enabled regions (none in a wave that does not write its group's stream)
   uint32_t stream;     // record stream of this wave: wave index >> group_log2
   uint32_t leader;     // 1 in the wave that writes the stream (the first wave of its group)
+  uint32_t collab;     // generic sites only: 1 = all 64 lanes store a record to the same address (Sec. 4.2)
   uint32_t pend_tag;   // up to two records that share the last clock sample and are not in LDS yet
   uint32_t pend_tag2;  //   (an END and the START that follows it); kNoPending: none
   uint32_t stored;     // records already written to the LDS sub-ring
@@ -94,6 +95,7 @@ __device__ __forceinline__ Ring ring_init(uint32_t* ring_lds, uint64_t* scratch_
   r.t0_lo = (uint32_t)r.t_begin;
   r.stream = wave;
   r.leader = 1u;
+  r.collab = 0u;
   r.mask = region_mask;
   if constexpr (GROUPS) {
     r.leader = (hw_wave & ((1u << group_log2) - 1u)) == 0u ? 1u : 0u;
@@ -131,19 +133,32 @@ __device__ __forceinline__ void wave_copy_slots(const uint32_t* src, uint32_t* d
 // values into VGPRs, one ds_write2_b32, restore EXEC.
 __device__ __forceinline__ void store_one(Ring& r, uint32_t tag, uint32_t ts) {
   const uint32_t addr = r.sub_lds + ((tag & r.lds_mask) << 3);  // seq sits in the low tag bits
-  uint64_t saved_exec;
   uint32_t va, v0, v1;
-  asm volatile(
-      "s_mov_b64 %0, exec\n\t"
-      "s_mov_b64 exec, 1\n\t"
-      "v_mov_b32 %1, %4\n\t"
-      "v_mov_b32 %2, %5\n\t"
-      "v_mov_b32 %3, %6\n\t"
-      "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
-      "s_mov_b64 exec, %0"
-      : "=&s"(saved_exec), "=&v"(va), "=&v"(v0), "=&v"(v1)
-      : "s"(addr), "s"(tag), "s"(ts)
-      : "memory");
+  if (r.collab) {
+    // The paper's store for AMD (Sec. 4.2): every lane writes the same record to the same address,
+    // so the execution mask stays as it is.
+    asm volatile(
+        "v_mov_b32 %0, %3\n\t"
+        "v_mov_b32 %1, %4\n\t"
+        "v_mov_b32 %2, %5\n\t"
+        "ds_write2_b32 %0, %1, %2 offset1:1"
+        : "=&v"(va), "=&v"(v0), "=&v"(v1)
+        : "s"(addr), "s"(tag), "s"(ts)
+        : "memory");
+  } else {
+    uint64_t saved_exec;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 %1, %4\n\t"
+        "v_mov_b32 %2, %5\n\t"
+        "v_mov_b32 %3, %6\n\t"
+        "ds_write2_b32 %1, %2, %3 offset1:1\n\t"
+        "s_mov_b64 exec, %0"
+        : "=&s"(saved_exec), "=&v"(va), "=&v"(v0), "=&v"(v1)
+        : "s"(addr), "s"(tag), "s"(ts)
+        : "memory");
+  }
   r.stored += 1;
   if (r.flush && (r.stored & r.lds_mask) == 0u) {
     if (r.stored <= r.cap_hbm)
@@ -377,14 +392,15 @@ __device__ __forceinline__ void deferred_end(Ring& r) {
   r.pend_tag2 = kNoPending;
 }
 
-// MODE 1: generic (region mask, either strategy); MODE 2: every region enabled, circular strategy,
-// records written to LDS at the next site; MODE 4: the same, deferred sites buffered in registers (the
-// kernel calls site_defer / sites_commit / deferred_end itself).
+// MODE 1: generic (region mask, either strategy, either store); MODE 3: generic, on the constant-rate
+// clock; MODE 2: every region enabled, circular strategy, records written to LDS at the next site;
+// MODE 4: the same, deferred sites buffered in registers (the kernel calls site_defer / sites_commit /
+// deferred_end itself).
 template <int MODE>
 __device__ __forceinline__ void site(Ring& r, uint32_t end_region, uint32_t start_region) {
-  static_assert(MODE == 1 || MODE == 2, "deferred sites are placed with site_defer<K>()");
+  static_assert(MODE == 1 || MODE == 2 || MODE == 3, "deferred sites are placed with site_defer<K>()");
   if constexpr (MODE == 2) boundary_fast(r, end_region, start_region);
-  else boundary(r, end_region, start_region);
+  else boundary<MODE == 3>(r, end_region, start_region);
 }
 template <int MODE>
 __device__ __forceinline__ void sites_begin(Ring& r) {
@@ -428,7 +444,11 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
     } else {
       wave_copy_slots(r.sub, r.seg, cap_lds);  // whole sub-ring; the decoder ignores slots >= total
     }
-    if (lane == 0) wh->total_written[r.stream] = r.cnt;
+    if (lane == 0) {
+      wh->total_written[r.stream] = r.cnt;
+      if (g.flags & KP_FLAG_HW_IDS)
+        wh->wave_hw_id[r.stream] = (uint16_t)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (11 << 11));  // HW_ID, low 12 bits
+    }
   }
   if (threadIdx.x == 0) {
     wh->wg_id = wg;
@@ -438,7 +458,7 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
     wh->t_end = REALTIME ? rt_end : t_end;
     wh->reserved = REALTIME ? t_end - r.t_begin : rt_end - r.rt_begin;
     for (uint32_t w = g.waves; w < KP_MAX_WAVES; ++w) wh->total_written[w] = 0;
-    for (int i = 0; i < 8; ++i) wh->pad[i] = 0;
+    for (uint32_t w = (g.flags & KP_FLAG_HW_IDS) ? g.waves : 0u; w < KP_MAX_WAVES; ++w) wh->wave_hw_id[w] = 0;
     if (wg == 0) {
       kp_trace_hdr* h = reinterpret_cast<kp_trace_hdr*>(base);
       h->magic = KP_TRACE_MAGIC; h->version = KP_TRACE_VERSION;

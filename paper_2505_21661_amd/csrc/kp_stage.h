@@ -177,7 +177,7 @@ inline kp_status trace_from_header(const void* raw, size_t n, const kp_trace_hdr
   if ((size_t)h.n_wg * h.waves_per_wg * h.cap_wave != n)
     return kp::fail(KP_ERR_BAD_TRACE, "trace header describes %zu record slots, caller passed %zu",
                     (size_t)h.n_wg * h.waves_per_wg * h.cap_wave, n);
-  if ((h.flags & ~KP_FLAG_FLUSH) != 0) return kp::fail(KP_ERR_BAD_TRACE, "trace header: unknown flags %x", h.flags);
+  if ((h.flags & ~(KP_FLAG_FLUSH | KP_FLAG_REALTIME | KP_FLAG_HW_IDS)) != 0) return kp::fail(KP_ERR_BAD_TRACE, "trace header: unknown flags %x", h.flags);
   const uint32_t nrec = h.waves_per_wg * h.cap_wave;
   if (nrec > kMaxRecPerWg)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "%u records per workgroup exceed the LDS staging limit %u", nrec, kMaxRecPerWg);

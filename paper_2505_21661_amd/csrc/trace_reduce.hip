@@ -1208,7 +1208,7 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
   if ((size_t)h.n_wg * h.waves_per_wg * h.cap_wave != n)
     return kp::fail(KP_ERR_BAD_TRACE, "trace header describes %zu record slots, caller passed %zu",
                     (size_t)h.n_wg * h.waves_per_wg * h.cap_wave, n);
-  if ((h.flags & ~KP_FLAG_FLUSH) != 0) return kp::fail(KP_ERR_BAD_TRACE, "trace header: unknown flags %x", h.flags);
+  if ((h.flags & ~(KP_FLAG_FLUSH | KP_FLAG_REALTIME | KP_FLAG_HW_IDS)) != 0) return kp::fail(KP_ERR_BAD_TRACE, "trace header: unknown flags %x", h.flags);
   if (h.n_regions > KP_MAX_REGIONS)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "n_regions=%u exceeds the decoder limit %d", h.n_regions, KP_MAX_REGIONS);
   if (h.cap_wave < 2) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "cap_wave must be at least 2");

@@ -147,6 +147,50 @@ def test_attention_wave_group_records(kp, oracle_mod):
     assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_disorder"] == 0
 
 
+@pytest.mark.parametrize("option", ["realtime", "collab", "collab_flush"])
+def test_attention_record_variants(kp, oracle_mod, option):
+    """KP_MASK_REALTIME (constant-rate clock in the records, Sec. 3.1 MetricType) and KP_MASK_COLLAB
+    (64-lane store and hardware ids in the header, Sec. 4.2) on the attention kernel: the output stays
+    bit-identical, the trace decodes like the oracle says and holds 6 records per KV tile and wave."""
+    from tests.gpu_util import assert_stats_equal
+
+    B, H, S = 1, 2, 512
+    q, k, v = inputs.attn_inputs(B, H, S, 128, seed=12)
+    Q, K, V = q.cuda(), k.cuda(), v.cuda()
+    O, O0 = torch.empty_like(Q), torch.empty_like(Q)
+    n_wg, waves, R = kp.kp_attn_launch_shape(B, H, S, 128)
+    cap_wave = 64
+    bits = {"realtime": kp.KP_MASK_REALTIME, "collab": kp.KP_MASK_COLLAB, "collab_flush": kp.KP_MASK_COLLAB | kp.KP_MASK_FLUSH}[option]
+    flags = {"realtime": kp.KP_FLAG_REALTIME, "collab": kp.KP_FLAG_HW_IDS, "collab_flush": kp.KP_FLAG_HW_IDS | 1}[option]
+    trace = torch.full((kp.kp_trace_bytes(n_wg, waves, waves * cap_wave),), 0x44, dtype=torch.uint8, device="cuda")
+    scale = 1.0 / np.sqrt(128.0)
+    kp.kp_attn_instrumented(Q, K, V, O, B, H, S, 128, True, scale, 0b111 | bits, trace, waves * cap_wave)
+    kp.kp_attn_instrumented(Q, K, V, O0, B, H, S, 128, True, scale, 0, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(torch.int16), O0.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[2:6]) == (n_wg, waves, R, cap_wave) and raw[7] == flags
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * cap_wave, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    totals = np.array([6 * 2 * (qb + 1) for qb in range(S // 128)])
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert sorted(hdr[:, 8].tolist()) == sorted(list(totals) * (B * H)) and (hdr[:, 8:12] == hdr[:, 8:9]).all()
+    assert st["n_slots_valid"] == waves * B * H * int(totals.sum()) and st["n_dropped"] == 0
+    assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_orphan_start"] == 0 and st["n_orphan_end"] == 0
+    ids = hdr[:, 24:32].copy().view(np.uint16).reshape(n_wg, 16)
+    if option == "realtime":
+        assert (ids == 0).all()
+        h64 = hdr[:, 2:8].copy().view(np.uint64)
+        ghz = h64[:, 2].astype(np.float64).sum() / (h64[:, 1] - h64[:, 0]).astype(np.float64).sum() * 0.1
+        assert 1.0 < ghz < 2.6, ghz
+    else:
+        assert (ids[:, waves:] == 0).all() and ((ids[:, :waves] >> 8) == (ids[:, :1] >> 8)).all()
+        assert all(len(set((row & 0x3F).tolist())) == waves for row in ids[:, :waves])
+
+
 def test_full_size_attention(kp, oracle_mod):
     """Benchmark configuration: batch 4, 32 heads, sequence 4096, head dim 128, causal, ring of 1024
     records per workgroup (256 per wave), which wraps for query blocks 21..31."""

@@ -389,3 +389,98 @@ def test_stage_by_stage_needs_the_large_tile(kp):
     with pytest.raises(kp.KperfError) as e:
         run_gemm_phased(kp, a, b, 0b100000, trace_cap=4096)   # region 5 does not exist
     assert e.value.status == kp.KP_ERR_INVALID_ARG
+
+
+def _wg_headers(raw, n_wg):
+    return raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(1024, 1024, 512), (128, 128, 256)])
+def test_constant_rate_clock_records(kp, oracle_mod, shape):
+    """KP_MASK_REALTIME: the records carry the constant-rate 100 MHz clock (the MetricType of the counter
+    read, Sec. 3.1).  Same records, decoded like the oracle says, C bit-identical; the workgroup spans
+    on the two clocks give a shader clock between 1 and 2.6 GHz."""
+    from tests.gpu_util import assert_stats_equal
+
+    M, N, K = shape
+    a, b = inputs.gemm_inputs(M, N, K, seed=21)
+    n_wg, waves, R = kp.kp_gemm_launch_shape(M, N, K)
+    cap_wave = 256
+    A, B = a.cuda(), b.cuda()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    C0 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    trace = torch.full((kp.kp_trace_bytes(n_wg, waves, waves * cap_wave),), 0x55, dtype=torch.uint8, device="cuda")
+    kp.kp_gemm_instrumented(A, B, C, M, N, K, ((1 << R) - 1) | kp.KP_MASK_REALTIME, trace, waves * cap_wave)
+    kp.kp_gemm_instrumented(A, B, C0, M, N, K, 0, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16), C0.view(torch.int16))
+    raw = trace.cpu().numpy().view(np.uint32).copy()
+    assert tuple(raw[2:6]) == (n_wg, waves, R, cap_wave) and raw[7] == kp.KP_FLAG_REALTIME
+    out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+    kp.kp_trace_reduce(trace, n_wg * waves * cap_wave, out)
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    st = kp.parse_stats(out)
+    steps = K // 64 if waves == 8 else K // 32
+    assert st["cnt"].tolist() == [n_wg * waves * steps] * 3 + ([n_wg * waves] if waves == 8 else [])
+    for k in ("n_orphan_start", "n_orphan_end", "n_invalid", "n_dropped", "n_disorder", "n_nonmonotonic"):
+        assert st[k] == 0, k
+    hdr64 = _wg_headers(raw, n_wg)[:, 2:8].copy().view(np.uint64)   # t_begin, t_end, reserved
+    span_rt = (hdr64[:, 1] - hdr64[:, 0]).astype(np.float64)        # 100 MHz ticks
+    span_clk = hdr64[:, 2].astype(np.float64)                        # the same stretch on the shader clock
+    ghz = span_clk.sum() / span_rt.sum() * 0.1
+    assert 1.0 < ghz < 2.6, ghz
+    # a duration in 100 MHz ticks cannot exceed its workgroup's span
+    assert int(st["max"].max()) <= int(span_rt.max())
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape,extra", [((1024, 1024, 512), 0), ((1024, 1024, 512), "flush"), ((128, 128, 256), 0)])
+def test_collaborative_store_gives_the_same_records(kp, oracle_mod, shape, extra):
+    """KP_MASK_COLLAB (Sec. 4.2, the store for AMD): all 64 lanes write a record to one address, and the
+    wave's hardware id goes to the workgroup header.  The tag words are those of the one-lane store, the
+    decode matches the oracle, C is bit-identical, and the ids of a workgroup's waves name one compute
+    unit and distinct (SIMD, wave slot) pairs."""
+    from tests.gpu_util import assert_stats_equal
+
+    M, N, K = shape
+    a, b = inputs.gemm_inputs(M, N, K, seed=22)
+    n_wg, waves, R = kp.kp_gemm_launch_shape(M, N, K)
+    cap_wave = 128
+    A, B = a.cuda(), b.cuda()
+    flush = kp.KP_MASK_FLUSH if extra == "flush" else 0
+    regions = (1 << R) - 1 - 2     # region 1 off: both runs go through the generic sites
+    traces, outs = [], []
+    for collab in (0, kp.KP_MASK_COLLAB):
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        trace = torch.full((kp.kp_trace_bytes(n_wg, waves, waves * cap_wave),), 0x33, dtype=torch.uint8, device="cuda")
+        kp.kp_gemm_instrumented(A, B, C, M, N, K, regions | flush | collab, trace, waves * cap_wave)
+        torch.cuda.synchronize()
+        traces.append(trace.cpu().numpy().view(np.uint32).copy())
+        outs.append(C.view(torch.int16).cpu())
+        st_out = torch.zeros(kp.kp_stats_bytes(n_wg, waves, R), dtype=torch.uint8, device="cuda")
+        kp.kp_trace_reduce(trace, n_wg * waves * cap_wave, st_out)
+        torch.cuda.synchronize()
+        assert_stats_equal(oracle_mod.decode_bytes(traces[-1], 8), st_out.cpu().numpy(), oracle_mod)
+    C0 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kp.kp_gemm_instrumented(A, B, C0, M, N, K, 0, None, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], C0.view(torch.int16).cpu()) and torch.equal(outs[1], outs[0])
+    plain, collab = traces
+    assert plain[7] == (1 if flush else 0) and collab[7] == (1 if flush else 0) | kp.KP_FLAG_HW_IDS
+    h0, h1 = _wg_headers(plain, n_wg), _wg_headers(collab, n_wg)
+    assert (h0[:, 8:24] == h1[:, 8:24]).all()                       # records written per wave
+    assert (h0[:, 24:32] == 0).all()
+    first = 16 + 32 * n_wg
+    rec0 = plain[first:].reshape(n_wg, waves, cap_wave, 2)
+    rec1 = collab[first:].reshape(n_wg, waves, cap_wave, 2)
+    held = np.minimum(h0[:, 8:8 + waves], cap_wave)                 # slots that hold a record
+    valid = np.arange(cap_wave)[None, None, :] < held[:, :, None]
+    assert (rec0[..., 0][valid] == rec1[..., 0][valid]).all()       # the tag words
+    ids = h1[:, 24:32].copy().view(np.uint16).reshape(n_wg, 16)
+    assert (ids[:, waves:] == 0).all() and (ids < 4096).all()
+    cu = ids[:, :waves] >> 8
+    assert (cu == cu[:, :1]).all()                                  # one compute unit per workgroup
+    slot = ids[:, :waves] & 0x3F                                    # wave slot and SIMD
+    assert all(len(set(row.tolist())) == waves for row in slot)
