@@ -13,6 +13,7 @@ library or its Python binding, and shares no code with them.
                  timing)
   ref_waits.c  : waits behind asynchronous operations from the START / END / START
                  placement (Sec. 4.3, asynchronous instructions)
+  ref_critical.c : the chain of stages each of which waited for the one before it (critical path)
   ref_stages.c : stage latencies per (workgroup, region, iteration) folded from the timeline
                  rows (Sec. 3.3 critical-path analysis, Sec. 5.2 / Table 4 overlap models)
   ref_dense.py : the dense kernels that get instrumented -- GEMM and causal
@@ -43,7 +44,7 @@ HEADER_FIELDS = (
 PER_DTYPE = np.dtype([("sum", "<u8"), ("n", "<u4"), ("max", "<u4")])
 
 
-_SOURCES = ("ref_decode.c", "ref_pairs.c", "ref_waits.c", "ref_stages.c")
+_SOURCES = ("ref_decode.c", "ref_pairs.c", "ref_waits.c", "ref_stages.c", "ref_critical.c")
 
 
 def build(force: bool = False) -> str:
@@ -75,6 +76,10 @@ def _load():
         lib.kpo_stages_bytes.argtypes = [ctypes.c_uint32] * 3
         lib.kpo_stages.restype = ctypes.c_int
         lib.kpo_stages.argtypes = [ctypes.c_void_p] + [ctypes.c_uint32] * 5 + [ctypes.c_void_p, ctypes.c_size_t]
+        lib.kpo_critical_bytes.restype = ctypes.c_size_t
+        lib.kpo_critical_bytes.argtypes = [ctypes.c_uint32] * 2
+        lib.kpo_critical.restype = ctypes.c_int
+        lib.kpo_critical.argtypes = [ctypes.c_void_p] + [ctypes.c_uint32] * 3 + [ctypes.c_void_p, ctypes.c_size_t]
         _lib = lib
     return _lib
 
@@ -231,6 +236,38 @@ def stages(raw: np.ndarray, max_iter: int):
     """Reference stage table of a raw trace: timeline rows first, then the fold."""
     n_wg, waves, R, cap = (int(x) for x in raw[2:6])
     return view_stages(stages_raw(pairs_raw(raw), n_wg, waves, cap, R, max_iter), n_wg, R, max_iter)
+
+
+PATH_DTYPE = np.dtype([("n_stages", "<u4"), ("last_stage", "<u4"), ("first_start", "<u4"), ("last_end", "<u4"),
+                       ("sum_latency", "<u8"), ("bubbles", "<u8")])
+
+
+def stage_block(table: np.ndarray) -> np.ndarray:
+    """Bytes of a stage block around a table[n_wg, n_regions, max_iter] of STAGE_DTYPE (header words zero)."""
+    t = np.ascontiguousarray(table, dtype=STAGE_DTYPE)
+    return np.concatenate([np.zeros(32, dtype=np.uint8), t.reshape(-1).view(np.uint8)])
+
+
+def critical_raw(stage_blk: np.ndarray, n_wg: int, n_regions: int, max_iter: int) -> np.ndarray:
+    """Critical path of every workgroup of a stage block (bytes, as stages_raw returns it); returns the block bytes."""
+    blk = np.ascontiguousarray(stage_blk).view(np.uint8)
+    assert blk.size >= 32 + 16 * n_wg * n_regions * max_iter
+    out = np.full(_load().kpo_critical_bytes(n_wg, n_regions), 0xEE, dtype=np.uint8)
+    rc = _load().kpo_critical(blk.ctypes.data, n_wg, n_regions, max_iter, out.ctypes.data, out.size)
+    if rc != 0:
+        raise ValueError(f"kpo_critical rejected its arguments (rc={rc})")
+    return out
+
+
+def view_critical(buf: np.ndarray, n_wg: int, n_regions: int):
+    """Split a critical-path block into (header dict, per-region array[R, 2], rows[n_wg])."""
+    b = np.ascontiguousarray(buf).view(np.uint8)
+    h = b[:64].view("<u8")
+    hdr = {"n_wg": int(h[0]), "n_regions": int(h[1]), "max_iter": int(h[2]), "n_paths": int(h[3]),
+           "n_path_stages": int(h[4]), "sum_latency": int(h[5]), "sum_bubbles": int(h[6])}
+    per_region = b[64 : 64 + 16 * n_regions].view("<u8").reshape(n_regions, 2)
+    rows = b[64 + 16 * n_regions : 64 + 16 * n_regions + 32 * n_wg].view(PATH_DTYPE)
+    return hdr, per_region, rows
 
 
 from .ref_dense import ref_gemm, ref_attn, bf16_round  # noqa: E402,F401
