@@ -256,6 +256,40 @@ size_t kp_stages_bytes(int n_wg, int n_regions, int max_iter);
 kp_status kp_pairs_stages(const void* pairs, int n_wg, int waves_per_wg, int cap_per_wg, int n_regions,
                           int max_iter, void* out_stages, void* stream);
 
+/* ---- critical path over the stage table ------------------------------------------------------
+ *
+ * The paper reads the critical path of a kernel whose warp groups work on different stages off its
+ * timeline: a chain of stages, each of which could only start when the one before it had finished
+ * (Sec. 3.3 "Critical-path Analysis"; Sec. 5.2), and models the latency of such a kernel as the sum
+ * of the latencies of the stages on that path (Table 4, WS model).  kp_stages_critical takes the
+ * chain of every recorded workgroup from its stage table (entries with n_waves = 0 are no stages):
+ *   the stages are ordered by (max_end, region * max_iter + iteration);
+ *   the path ends in the last stage of that order;
+ *   the stage before a stage X of the path is the latest stage of that order, earlier than X, with
+ *   max_end <= X.min_start (the one X waited for); without one, X is the first stage of the path.
+ * Clocks are compared as plain 32-bit unsigned numbers.
+ *   stages      device, the block kp_pairs_stages wrote for (n_wg, n_regions, max_iter); read only
+ *   out_paths   device, kp_critical_bytes(n_wg, n_regions) bytes, 16-byte aligned, fully written:
+ *               8 u64 {n_wg, n_regions, max_iter, workgroups with a path, stages on all paths, sum of
+ *               their latencies (max_dur), sum of all bubbles, 0}; per region 2 u64 {stages on paths,
+ *               their latencies}; kp_path_row rows[n_wg]
+ * Asynchronous on `stream`.  KP_ERR_INVALID_ARG for NULL or misaligned pointers and bad sizes;
+ * KP_ERR_UNSUPPORTED_SHAPE when n_regions * max_iter exceeds 4096 (the stages of one workgroup are
+ * sorted in LDS).
+ */
+typedef struct {
+  uint32_t n_stages;     /* stages on the path                                                        */
+  uint32_t last_stage;   /* region << 16 | iteration of the stage that ends last; all ones: no stage  */
+  uint32_t first_start;  /* min_start of the first stage of the path                                  */
+  uint32_t last_end;     /* max_end of the last                                                       */
+  uint64_t sum_latency;  /* sum of max_dur over the path                                              */
+  uint64_t bubbles;      /* ticks between the end of a stage of the path and the start of the next    */
+} kp_path_row;
+
+size_t kp_critical_bytes(int n_wg, int n_regions);
+kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int max_iter, void* out_paths,
+                             void* stream);
+
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
  * region_mask: bit r (r < 27) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)

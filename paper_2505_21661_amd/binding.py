@@ -93,6 +93,10 @@ def lib() -> ctypes.CDLL:
         L.kp_stages_bytes.argtypes = [ci, ci, ci]
         L.kp_pairs_stages.restype = ci
         L.kp_pairs_stages.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+        L.kp_critical_bytes.restype = sz
+        L.kp_critical_bytes.argtypes = [ci, ci]
+        L.kp_stages_critical.restype = ci
+        L.kp_stages_critical.argtypes = [vp, ci, ci, ci, vp, vp]
         L.kp_set_rec_cost.restype = None
         L.kp_set_rec_cost.argtypes = [u32]
         L.kp_get_rec_cost.restype = u32
@@ -259,6 +263,27 @@ def kp_pairs_stages(pairs, n_wg: int, waves_per_wg: int, cap_per_wg: int, n_regi
 
 
 STAGE_ROW_DTYPE = [("max_dur", "<u4"), ("min_start", "<u4"), ("max_end", "<u4"), ("n_waves", "<u4")]
+PATH_ROW_DTYPE = [("n_stages", "<u4"), ("last_stage", "<u4"), ("first_start", "<u4"), ("last_end", "<u4"),
+                  ("sum_latency", "<u8"), ("bubbles", "<u8")]
+
+
+def kp_critical_bytes(n_wg: int, n_regions: int) -> int:
+    return int(lib().kp_critical_bytes(n_wg, n_regions))
+
+
+def kp_stages_critical(stages, n_wg: int, n_regions: int, max_iter: int, out_paths, stream=None) -> None:
+    _check(lib().kp_stages_critical(_ptr(stages), n_wg, n_regions, max_iter, _ptr(out_paths), _stream(stream)))
+
+
+def parse_critical(buf, n_wg: int, n_regions: int):
+    """Split a critical-path block (host bytes) into (header dict, per-region array[R, 2], rows[n_wg])."""
+    b = np.ascontiguousarray(buf.cpu().numpy() if hasattr(buf, "numpy") else buf).view(np.uint8)
+    h = b[:64].view("<u8")
+    hdr = {"n_wg": int(h[0]), "n_regions": int(h[1]), "max_iter": int(h[2]), "n_paths": int(h[3]),
+           "n_path_stages": int(h[4]), "sum_latency": int(h[5]), "sum_bubbles": int(h[6])}
+    per_region = b[64 : 64 + 16 * n_regions].view("<u8").reshape(n_regions, 2)
+    rows = b[64 + 16 * n_regions : 64 + 16 * n_regions + 32 * n_wg].view(np.dtype(PATH_ROW_DTYPE))
+    return hdr, per_region, rows
 
 
 def parse_stages(buf, n_wg: int, n_regions: int, max_iter: int):
