@@ -15,6 +15,7 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
   6. kp_trace_pairs of the same records: one timeline row per paired region instance
   7. kp_trace_waits of the same records: the waits behind asynchronous operations
   8. kp_pairs_stages of the timeline rows: stage latency per (workgroup, region, iteration)
+  9. kp_stages_critical of that table: the critical path of every workgroup
 All inputs are resident in HBM before the timed region starts.  Every kernel is bracketed by
 HIP events on the launch stream inside the timed region; the per-kernel figures below are
 averages over the timed steps.
@@ -189,6 +190,7 @@ def probe(args) -> int:
     pairs = torch.empty(kp.kp_pairs_bytes(spec.n_wg, spec.waves, spec.waves * spec.cap_wave), dtype=torch.uint8, device=dev)
     waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
     stages = torch.empty(kp.kp_stages_bytes(spec.n_wg, spec.n_regions, 64), dtype=torch.uint8, device=dev)
+    paths = torch.empty(kp.kp_critical_bytes(spec.n_wg, spec.n_regions), dtype=torch.uint8, device=dev)
     for _ in range(2):
         kp.kp_trace_reduce_hdr(d_raw, n, hdr, stats)
     for _ in range(2):
@@ -197,6 +199,8 @@ def probe(args) -> int:
         kp.kp_trace_waits_hdr(d_raw, n, hdr, waits)
     for _ in range(2):
         kp.kp_pairs_stages(pairs, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions, 64, stages)
+    for _ in range(2):
+        kp.kp_stages_critical(stages, spec.n_wg, spec.n_regions, 64, paths)
     torch.cuda.synchronize()
     return 0
 
@@ -269,6 +273,7 @@ def main() -> int:
     d_waits = torch.empty(kp.kp_waits_bytes(spec.n_wg, spec.waves, spec.n_regions), dtype=torch.uint8, device=dev)
     d_iters = 64  # iterations kept per region: the workload runs about 64 pairs per wave and region
     d_stages = torch.empty(kp.kp_stages_bytes(spec.n_wg, spec.n_regions, d_iters), dtype=torch.uint8, device=dev)
+    d_paths = torch.empty(kp.kp_critical_bytes(spec.n_wg, spec.n_regions), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
     # The dense kernels run after one warm launch (the preceding decode of a 2 GiB trace leaves L2 and
@@ -279,7 +284,7 @@ def main() -> int:
              "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm_masked", "gemm_collab", "gemm_realtime",
              "gemm_realtime2", "gemm_collab2", "gemm_masked2",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_instr2", "attn_vanilla2", "attn_reduce", "decode",
-             "timeline", "waits", "stages"]
+             "timeline", "waits", "stages", "critical"]
 
     def step(events=None):
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
@@ -302,6 +307,7 @@ def main() -> int:
             lambda: kp.kp_trace_waits_hdr(d_raw, d_n, d_hdr, d_waits),
             lambda: kp.kp_pairs_stages(d_pairs, spec.n_wg, spec.waves, spec.waves * spec.cap_wave, spec.n_regions,
                                        d_iters, d_stages),
+            lambda: kp.kp_stages_critical(d_stages, spec.n_wg, spec.n_regions, d_iters, d_paths),
         )
         for i, call in enumerate(calls):
             if events is not None:
@@ -362,6 +368,11 @@ def main() -> int:
     assert sg_hdr[0] + sg_hdr[1] == pair_count and sg_hdr[2] == 0, "stage table lost rows"
     sg_bytes = 16.0 * pair_count + 4.0 * n_seg + 16.0 * spec.n_wg * spec.n_regions * d_iters
     sg_gbs = sg_bytes / (ms["stages"] * 1e-3) / 1e9
+    # critical path: 16 B read per (wg, region, iteration), 32 B written per workgroup
+    cp_hdr, cp_region, _ = kp.parse_critical(d_paths, spec.n_wg, spec.n_regions)
+    assert cp_hdr["n_paths"] == spec.n_wg and cp_hdr["n_path_stages"] == int(cp_region[:, 0].sum()), "critical-path block is off"
+    cp_bytes = 16.0 * spec.n_wg * spec.n_regions * d_iters + 32.0 * spec.n_wg
+    cp_gbs = cp_bytes / (ms["critical"] * 1e-3) / 1e9
 
     # Overhead model of the paper, eq. (1): T_theoretical = T_vanilla + N_record * Cycle_record, with the
     # per-record cost taken from the calibration kernel (an empty START/END region, i.e. two records)
@@ -438,6 +449,9 @@ def main() -> int:
         "timeline_records_per_s": round(d_n / (ms["timeline"] * 1e-3), 1),
         "waits_records_per_s": round(d_n / (ms["waits"] * 1e-3), 1),
         "stages_rows_per_s": round(pair_count / (ms["stages"] * 1e-3), 1),
+        "critical_stages_per_s": round(spec.n_wg * spec.n_regions * d_iters / (ms["critical"] * 1e-3), 1),
+        "critical_path": {"stages_on_paths": cp_hdr["n_path_stages"], "mean_stages_per_workgroup": round(cp_hdr["n_path_stages"] / spec.n_wg, 1),
+                          "bubble_share": round(cp_hdr["sum_bubbles"] / max(1, cp_hdr["sum_bubbles"] + cp_hdr["sum_latency"]), 4)},
         "kernel_ms": {n: round(x, 4) for n, x in ms.items()},
         "overhead_model_eq1": eq1,
         "paper_context": {"overhead_pct": 8.2, "hardware": "H100 / MI300X (not split), Triton GEMM/FA3"},
@@ -499,6 +513,16 @@ def main() -> int:
             "frac": round(sg_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(sg_bytes),
             "traffic": round(TRAFFIC_BYTES["stages_2^28"]) if args.log2_records == 28 else None,
+        },
+        "roofline_critical": {
+            "kernel": "kp_critical_main (critical path of every workgroup over that stage table)",
+            "bound": "hbm",
+            "achieved": round(cp_gbs, 2),
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": round(cp_gbs / PEAK_HBM_GBS, 4),
+            "algorithmic_bytes": round(cp_bytes),
+            "traffic": None,
         },
     }
 
