@@ -425,7 +425,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
   u32x4 v[8];
   uint32_t h_total;  // lane & 15 -> records written by that wave
   uint2 h_begin, h_end;
-  constexpr int kEarly = 6;  // units requested before the matrix products of the sweep; the rest follow it
+  constexpr int kEarly = 6;  // units requested before the matrix products of the sweep of the workgroup before
   auto request_units = [&](uint32_t g, uint32_t t, auto first, auto last) {
     const u32x4* recs = p.records + (size_t)g * (nrec / 2);
 #pragma unroll
@@ -434,15 +434,14 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       v[u] = __builtin_nontemporal_load(recs + (i < nrec / 2 ? i : nrec / 2 - 1));
     }
   };
-  auto request_rest = [&](uint32_t g, uint32_t t) {
+  auto request_header = [&](uint32_t g, uint32_t t) {
     const uint32_t* whn = p.wg_hdrs + (size_t)32 * g;
     h_total = whn[8 + (t & 15u)];
     h_begin = *reinterpret_cast<const uint2*>(whn + 2);
     h_end = *reinterpret_cast<const uint2*>(whn + 4);
-    request_units(g, t, std::integral_constant<int, kEarly>{}, std::integral_constant<int, 8>{});
   };
   request_units(blockIdx.x, tid_k, std::integral_constant<int, 0>{}, std::integral_constant<int, kEarly>{});
-  request_rest(blockIdx.x, tid_k);
+  request_header(blockIdx.x, tid_k);
 
   for (uint32_t wg = blockIdx.x; wg < n_wg; wg += gridDim.x) {
     // A fresh copy of the thread index per workgroup that the optimiser cannot see through: without it
@@ -455,6 +454,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     const uint32_t qe = pbase + 2u * lane;     // even position of round 0; round j: qe + 128 j
     // its clock word; round j: cwe + 136 j (pbase is a multiple of 1024, lanes 32.. are past one padding)
     const uint32_t cwe = qe + (pbase >> 4) + ((lane >> 5) << 2);
+    // the last units of this workgroup's records: they travel while the staging state is cleared
+    request_units(wg, tid, std::integral_constant<int, kEarly>{}, std::integral_constant<int, 8>{});
     // ---- workgroup header, clear the staging state -----------------------------------------------
     if (tid < W) {
       const uint32_t T = h_total;
@@ -755,6 +756,10 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
     }
     __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(t[i]));  // (opaque across the barrier, see below)
+#pragma unroll
+    for (int i = 0; i < kNR / 4; ++i) asm volatile("" : "+v"(mq[i]));
     eligible = !misc[0] && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
 
     if (eligible && stop_after != kStepPaired) {
@@ -785,6 +790,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       if (__builtin_amdgcn_ballot_w64(t_max > misc[2]) && lane == 0u) tmp[T_WIDE] = 1u;  // a clock past the span
       __syncthreads();
       if (stop_after == kStepCounted) break;
+      // (the registers that cross this barrier are made opaque: values derived from them for the next
+      // phase would otherwise be computed before it and held in registers across it)
+#pragma unroll
+      for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(t[i]), "+v"(ca[i]));
+#pragma unroll
+      for (int i = 0; i < kNR / 4; ++i) asm volatile("" : "+v"(mq[i]));
       {  // exclusive prefix sum over the cell counters, 16 cells (8 words) per thread
         u32x4 a = reinterpret_cast<u32x4*>(cells)[2 * tid], b = reinterpret_cast<u32x4*>(cells)[2 * tid + 1];
         uint32_t wv[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
@@ -822,6 +833,12 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
       __syncthreads();
       if (stop_after == kStepCellSums) break;
+      // (the registers that cross this barrier are made opaque: values derived from them for the next
+      // phase would otherwise be computed before it and held in registers across it)
+#pragma unroll
+      for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(t[i]), "+v"(ca[i]));
+#pragma unroll
+      for (int i = 0; i < kNR / 4; ++i) asm volatile("" : "+v"(mq[i]));
       auto cell_start = [&](uint32_t c) -> uint32_t { return (cells[c >> 1] >> ((c & 1u) << 4)) & 0xFFFFu; };
       // sorted sequence entry besides the clock: region << 1 | END
       auto info_of = [&](int i) -> uint32_t { return ((meta_of(i) & 0x1Fu) << 1) | (meta_of(i) >> 7); };
@@ -942,6 +959,9 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         }
         if (lane == 0) wtot[hw] = st[0];  // first clock of this wave's stretch, for the last lane of the wave below
         __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(st[i]), "+v"(sx[i]));  // (opaque across the barrier, as above)
+        asm volatile("" : "+v"(ends));
         // state before this lane's stretch: lanes below in this wave + all waves below
 #pragma unroll
         for (int k = 0; k < PLANES; ++k) pl[k] = wave_shr1(inc[k], 0u);
@@ -1099,7 +1119,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       }
     }
     __syncthreads();
-    request_rest(wg_ahead, tid);
+    request_header(wg_ahead, tid);
     if (stop_after) continue;
 
     // ---- E: per-(workgroup, wave, region) output, fold into running totals ------------------------
