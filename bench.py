@@ -40,12 +40,13 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1056115.7 * 2.0 + 51128.8) * 1024,
-    "gemm_vanilla": (98358.5 * 2.0 + 32793.0) * 1024,
-    "attn_vanilla": (196736.8 * 2.0 + 131076.1) * 1024,
-    "timeline_2^28": (1057855.2 * 2.0 + 2085601.0) * 1024,
-    "waits_2^28": (1057637.7 * 2.0 + 33216.0) * 1024,
-    "stages_2^28": (1043571.6 * 2.0 + 274372.8) * 1024,
+    "decode_2^28": (1079943.2 * 2.0 + 61288.7) * 1024,
+    "gemm_vanilla": (98362.0 * 2.0 + 32822.8) * 1024,
+    "attn_vanilla": (196743.1 * 2.0 + 131076.3) * 1024,
+    "timeline_2^28": (1057669.4 * 2.0 + 2085621.6) * 1024,
+    "waits_2^28": (1057609.0 * 2.0 + 33216.0) * 1024,
+    "stages_2^28": (1043564.3 * 2.0 + 273224.0) * 1024,
+    "critical_2^28": (132126.5 * 2.0 + 992.0) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
@@ -522,7 +523,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(cp_gbs / PEAK_HBM_GBS, 4),
             "algorithmic_bytes": round(cp_bytes),
-            "traffic": None,
+            "traffic": round(TRAFFIC_BYTES["critical_2^28"]) if args.log2_records == 28 else None,
         },
     }
 
