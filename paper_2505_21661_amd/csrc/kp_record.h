@@ -212,14 +212,14 @@ template <bool REALTIME = false>
 __device__ __forceinline__ void boundary(Ring& r, uint32_t end_region, uint32_t start_region) {
   __builtin_amdgcn_sched_barrier(0);
   store_pending(r);  // also when nothing is pending: the previous sample must have landed before the next
-  const uint64_t now = sample_clock<REALTIME>();
+  // the sample goes straight into the register pair its consumer names: no copy of a value in flight
+  r.pend_t = sample_clock<REALTIME>();
   const bool on_e = end_region != kNoRegion && ((r.mask >> (end_region & 31u)) & 1u) != 0u;     // scalar
   const bool on_s = start_region != kNoRegion && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
   r.pend_tag = on_e ? ((1u << 31) | (end_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
   r.cnt += on_e ? 1u : 0u;
   r.pend_tag2 = on_s ? ((start_region << 24) | r.tag_wave | (r.cnt & 0xFFFFFu)) : kNoPending;
   r.cnt += on_s ? 1u : 0u;
-  r.pend_t = now;
   __builtin_amdgcn_sched_barrier(0);
 }
 
