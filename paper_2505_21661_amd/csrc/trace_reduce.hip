@@ -211,16 +211,10 @@ __device__ __forceinline__ void bitonic_merge8(uint32_t (&v)[8]) {
 // equal words are interchangeable.  A place past the end of the sequence holds `fake`: the largest
 // clock of the workgroup with a region number that no record has, so that it sorts last, opens no
 // region and the stretch in front of it has an honest length.
-__device__ __forceinline__ void sweep_outputs(const uint32_t (&key)[kNR], uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
-  ends = 0;
-#pragma unroll
-  for (int i = 0; i < kNR; ++i) {
-    const uint32_t k = key[i];
-    st[i] = k >> 6;
-    sx[i] = 1u << ((k >> 1) & 31u);  // bit 31 for a place past the end: above every region
-    ends |= (k & 1u) << i;
-  }
-}
+// Fields of such a word.
+__device__ __forceinline__ uint32_t key_clock(uint32_t k) { return k >> 6; }
+__device__ __forceinline__ uint32_t key_region_bit(uint32_t k) { return 1u << ((k >> 1) & 31u); }  // bit 31 for a place past the end: above every region
+__device__ __forceinline__ uint32_t key_end_mask(uint32_t k) { return (uint32_t)__builtin_amdgcn_sbfe((int)k, 0, 1); }  // all ones for an END
 
 // The 16 records of the clock-sorted sequence that lane `tid` of the sweep owns, from a sequence that
 // is only ordered cell by cell (inside a cell the records stand in arrival order).  Cells follow one
@@ -235,8 +229,7 @@ __device__ __forceinline__ void sweep_outputs(const uint32_t (&key)[kNR], uint32
 // runs, in rising-then-falling order.  Contains one workgroup barrier.
 template <uint32_t NPOS>
 __device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
-                                           uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
-  uint32_t key[kNR];
+                                           uint32_t (&key)[kNR]) {
   const uint32_t g0 = tid * kNR;
   u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
   {
@@ -281,7 +274,6 @@ __device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, u
 #pragma unroll
     for (int i = 0; i < 8; ++i) { key[i] = lo[i]; key[8 + i] = hi[i]; }
   }
-  sweep_outputs(key, st, sx, ends);
 }
 
 // Form for cells of up to HALO + 1 records: the lane reads a window of its 16 places and HALO on either
@@ -290,7 +282,7 @@ __device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, u
 // past the window.)
 template <int HALO, uint32_t NPOS>
 __device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
-                                              uint32_t (&st)[kNR], uint32_t (&sx)[kNR], uint32_t& ends) {
+                                              uint32_t (&mine)[kNR]) {
   constexpr int N = kNR + 2 * HALO;
   uint32_t key[N];
   const uint32_t g0 = tid * kNR;
@@ -321,10 +313,8 @@ __device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t
     }
   }
   network_sort<N>(key);
-  uint32_t mine[kNR];
 #pragma unroll
   for (int i = 0; i < kNR; ++i) mine[i] = key[HALO + i];
-  sweep_outputs(mine, st, sx, ends);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -900,151 +890,69 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
       {
         const uint32_t n_events = tmp[T_EVENTS];
         const uint32_t g0 = tid * kNR;
-        uint32_t st[kNR], sx[kNR];  // clock, region bit (0: no record)
-        uint32_t ends = 0;           // bit i: record i is an END
-        if (window_sort) {
-          const uint32_t fake = (misc[2] << 6) | 0x3Fu;
-          if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, meta, tid, n_events, fake, st, sx, ends);
-          else sorted_window<16, NPOS>(clk, meta, tid, n_events, fake, st, sx, ends);
-        } else {
-          const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
-          const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
-          const u32x4* tv = reinterpret_cast<const u32x4*>(clk + clk_word(g0));
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const u32x4 v = tv[i];
-            st[4 * i] = v.x; st[4 * i + 1] = v.y; st[4 * i + 2] = v.z; st[4 * i + 3] = v.w;
-          }
-#pragma unroll
-          for (int i = 0; i < kNR; ++i) {
-            const uint32_t info = (mw[i >> 2] >> (8 * (i & 3))) & 0xFFu;
-            sx[i] = g0 + i < n_events ? 1u << (info >> 1) : 0u;
-            ends |= (info & 1u) << i;
-          }
-        }
-        auto end_mask = [&](int i) -> uint32_t { return (uint32_t)((int32_t)(ends << (31 - i)) >> 31); };  // all ones for an END
-        uint32_t pl[PLANES];
+        const uint32_t region_bits = 0xFFFFFFFFu >> (32u - R);  // places past the end carry a bit above the regions
+        uint32_t pl[PLANES], inc[PLANES];
 #pragma unroll
         for (int k = 0; k < PLANES; ++k) pl[k] = 0u;
+        // From each lane's net change (pl) to the state before its stretch (pl again): an inclusive scan
+        // over the lanes, the waves' totals through LDS and one barrier, a scan over those.  `first_clock`
+        // is the clock of the lane's first record, left for the last lane of the wave below.
+        auto state_before = [&](uint32_t first_clock) {
 #pragma unroll
-        for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, sx[i], end_mask(i));
-        // inclusive scan of the lanes' net changes, then the sum of the waves below
-        uint32_t inc[PLANES];
+          for (int k = 0; k < PLANES; ++k) inc[k] = pl[k];
+          {
+            uint32_t o[PLANES];
 #pragma unroll
-        for (int k = 0; k < PLANES; ++k) inc[k] = pl[k];
-        {
-          uint32_t o[PLANES];
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(inc[k]);
+            planes_add<PLANES>(inc, o);
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(inc[k]);
-          planes_add<PLANES>(inc, o);
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(inc[k]);
+            planes_add<PLANES>(inc, o);
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(inc[k]);
-          planes_add<PLANES>(inc, o);
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(inc[k]);
+            planes_add<PLANES>(inc, o);
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(inc[k]);
-          planes_add<PLANES>(inc, o);
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(inc[k]);
+            planes_add<PLANES>(inc, o);
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(inc[k]);
-          planes_add<PLANES>(inc, o);
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<4>(inc[k]);
+            planes_add<PLANES>(inc, o);
 #pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<4>(inc[k]);
-          planes_add<PLANES>(inc, o);
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<5>(inc[k]);
-          planes_add<PLANES>(inc, o);
-        }
-        if (lane == 63) {
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) ptot[hw * 8 + k] = inc[k];
-        }
-        if (lane == 0) wtot[hw] = st[0];  // first clock of this wave's stretch, for the last lane of the wave below
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(st[i]), "+v"(sx[i]));  // (opaque across the barrier, as above)
-        asm volatile("" : "+v"(ends));
-        // state before this lane's stretch: lanes below in this wave + all waves below
-#pragma unroll
-        for (int k = 0; k < PLANES; ++k) pl[k] = wave_shr1(inc[k], 0u);
-        if (hw > 0) {  // lane h of a row takes wave h's net change; a scan over the row, then the entry of wave hw - 1
-          uint32_t wsum[PLANES], o[PLANES];
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) wsum[k] = ptot[(lane & 15u) * 8 + k];
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(wsum[k]);
-          planes_add<PLANES>(wsum, o);
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(wsum[k]);
-          planes_add<PLANES>(wsum, o);
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(wsum[k]);
-          planes_add<PLANES>(wsum, o);
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(wsum[k]);
-          planes_add<PLANES>(wsum, o);
-#pragma unroll
-          for (int k = 0; k < PLANES; ++k) o[k] = (uint32_t)__builtin_amdgcn_readlane((int)wsum[k], (int)(hw - 1u));
-          planes_add<PLANES>(pl, o);
-        }
-        // ---- the sorted sequence as segments: the set of active regions after record k and the ticks
-        // until record k + 1.  O[a][b] = sum over segments of ticks * active(a) * active(b) is a 16 x K by
-        // K x 16 matrix product: the matrix cores take it 64 segments at a time (i8 operands: the ticks in
-        // 7-bit limbs, one product per limb), and no accumulator atomics are left in the sweep.
-        bool swept = false;
-        if (window_sort) {
-          uint32_t limb[3][4];  // limb l of the 16 lengths, one byte each
-          uint32_t any_len = 0;
-          // clock of the record after the lane's 16: the first one of the lane above
-          const uint32_t t_above = hw + 1 < BLOCK / 64 ? wtot[hw + 1 < BLOCK / 64 ? hw + 1 : hw] : misc[2];
-          const uint32_t t_next = (uint32_t)__builtin_amdgcn_update_dpp((int)t_above, (int)st[0], 0x130, 0xF, 0xF, false);  // wave_shl:1
-#pragma unroll
-          for (int l = 0; l < 3; ++l)
-#pragma unroll
-            for (int y = 0; y < 4; ++y) limb[l][y] = 0u;
-#pragma unroll
-          for (int i = 0; i < kNR; ++i) {
-            // (places past the end of the sequence carry the workgroup's last clock: stretches of length 0
-            // behind a last one in which no region is open)
-            const uint32_t len = (i + 1 < kNR ? st[i + 1] : t_next) - st[i];
-            any_len |= len;
-#pragma unroll
-            for (int l = 0; l < 3; ++l) limb[l][i >> 2] |= ((len >> (7 * l)) & 0x7Fu) << (8 * (i & 3));
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<5>(inc[k]);
+            planes_add<PLANES>(inc, o);
           }
-          {  // OR over the wave
-            uint32_t f = any_len;
-            f |= scan_src<0>(f); f |= scan_src<1>(f); f |= scan_src<2>(f);
-            f |= scan_src<3>(f); f |= scan_src<4>(f); f |= scan_src<5>(f);
-            any_len = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
+          if (lane == 63) {
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) ptot[hw * 8 + k] = inc[k];
           }
-          if (any_len < (1u << 21)) {  // else: a gap of more than three limbs, the loop below takes this wave
-            swept = true;
-            const uint32_t n_limbs = any_len < (1u << 7) ? 1u : (any_len < (1u << 14) ? 2u : 3u);
-            uint32_t mk[kNR / 2];  // active sets after records 2x and 2x + 1, 16 bits each
-            uint32_t act_even = 0u;
+          if (lane == 0) wtot[hw] = first_clock;
+          __syncthreads();
 #pragma unroll
-            for (int i = 0; i < kNR; ++i) {
-              planes_step<PLANES>(pl, sx[i], end_mask(i));
-              uint32_t act = pl[0];
+          for (int k = 0; k < PLANES; ++k) pl[k] = wave_shr1(inc[k], 0u);
+          if (hw > 0) {  // lane h of a row takes wave h's net change; a scan over the row, then the entry of wave hw - 1
+            uint32_t wsum[PLANES], o[PLANES];
 #pragma unroll
-              for (int k = 1; k < PLANES; ++k) act |= pl[k];
-              if (i & 1) mk[i >> 1] = __builtin_amdgcn_perm(act, act_even, 0x05040100u);  // the low halves of the two
-              else act_even = act;
-            }
-            // The lane's own 16 places of the sequence are free now (every window was read before the last
-            // barrier): they take the active sets and two limbs, the 16 metadata bytes the third limb.
-            u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
-            own[0] = u32x4{mk[0], mk[1], mk[2], mk[3]};
-            own[1] = u32x4{mk[4], mk[5], mk[6], mk[7]};
-            own[2] = u32x4{limb[0][0], limb[0][1], limb[0][2], limb[0][3]};
-            own[3] = u32x4{limb[1][0], limb[1][1], limb[1][2], limb[1][3]};
-            reinterpret_cast<u32x4*>(meta)[tid] = u32x4{limb[2][0], limb[2][1], limb[2][2], limb[2][3]};
-            products = (tid & ~63u) * kNR < n_events ? n_limbs : 0u;  // this wave holds records
+            for (int k = 0; k < PLANES; ++k) wsum[k] = ptot[(lane & 15u) * 8 + k];
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<0>(wsum[k]);
+            planes_add<PLANES>(wsum, o);
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<1>(wsum[k]);
+            planes_add<PLANES>(wsum, o);
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<2>(wsum[k]);
+            planes_add<PLANES>(wsum, o);
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) o[k] = scan_src<3>(wsum[k]);
+            planes_add<PLANES>(wsum, o);
+#pragma unroll
+            for (int k = 0; k < PLANES; ++k) o[k] = (uint32_t)__builtin_amdgcn_readlane((int)wsum[k], (int)(hw - 1u));
+            planes_add<PLANES>(pl, o);
           }
-        }
-        if (!swept) {
-        const uint32_t region_bits = 0xFFFFFFFFu >> (32u - R);  // places past the end carry a bit above the regions
-#pragma unroll
-        for (int i = 0; i < kNR; ++i) {
-          const uint32_t x = sx[i] & region_bits, dm = end_mask(i), tt = st[i];
+        };
+        // One record of the sequence for the general way of adding up: a region that switches on or off
+        // adds -t / +t to its sums with every region open at that instant (LDS atomics).
+        auto switch_record = [&](uint32_t x, uint32_t dm, uint32_t tt) {
           uint32_t act_before = pl[0];
 #pragma unroll
           for (int k = 1; k < PLANES; ++k) act_before |= pl[k];
@@ -1066,7 +974,106 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
               atomicAdd(&row[bb], val);
             }
           }
-        }
+        };
+        if (window_sort) {
+          // ---- the order is finished in registers; one word per record from here on ------------------
+          uint32_t key[kNR];
+          const uint32_t fake = (misc[2] << 6) | 0x3Fu;
+          if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, meta, tid, n_events, fake, key);
+          else sorted_window<16, NPOS>(clk, meta, tid, n_events, fake, key);
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, key_region_bit(key[i]), key_end_mask(key[i]));
+          state_before(key_clock(key[0]));
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) asm volatile("" : "+v"(key[i]));  // (opaque across the barrier, as above)
+          // ---- the sorted sequence as segments: the set of active regions after record k and the ticks
+          // until record k + 1.  O[a][b] = sum over segments of ticks * active(a) * active(b) is a 16 x K by
+          // K x 16 matrix product: the matrix cores take it 64 segments at a time (i8 operands: the ticks in
+          // 7-bit limbs, one product per limb), and no accumulator atomics are left in the sweep.
+          // clock of the record after the lane's 16: the first one of the lane above
+          const uint32_t t_above = hw + 1 < BLOCK / 64 ? wtot[hw + 1 < BLOCK / 64 ? hw + 1 : hw] : misc[2];
+          const uint32_t t_next = (uint32_t)__builtin_amdgcn_update_dpp((int)t_above, (int)key_clock(key[0]), 0x130, 0xF, 0xF, false);  // wave_shl:1
+          // (places past the end of the sequence carry the workgroup's last clock: stretches of length 0
+          // behind a last one in which no region is open)
+          uint32_t len[kNR];
+          uint32_t any_len = 0;
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) {
+            len[i] = (i + 1 < kNR ? key_clock(key[i + 1]) : t_next) - key_clock(key[i]);
+            any_len |= len[i];
+          }
+          {  // OR over the wave
+            uint32_t f = any_len;
+            f |= scan_src<0>(f); f |= scan_src<1>(f); f |= scan_src<2>(f);
+            f |= scan_src<3>(f); f |= scan_src<4>(f); f |= scan_src<5>(f);
+            any_len = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
+          }
+          if (any_len < (1u << 21)) {  // else: a gap of more than three limbs, the general way takes this wave
+            const uint32_t n_limbs = any_len < (1u << 7) ? 1u : (any_len < (1u << 14) ? 2u : 3u);
+            // The lane's own 16 places of the sequence are free now (every neighbour read them before the last
+            // barrier): they take the active sets and two limbs, the 16 metadata bytes the third limb.
+            u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
+            {
+              uint32_t l0[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+              for (int i = 0; i < kNR; ++i) l0[i >> 2] |= (len[i] & 0x7Fu) << (8 * (i & 3));
+              own[2] = u32x4{l0[0], l0[1], l0[2], l0[3]};
+            }
+            if (n_limbs > 1u) {
+              uint32_t l1[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+              for (int i = 0; i < kNR; ++i) l1[i >> 2] |= ((len[i] >> 7) & 0x7Fu) << (8 * (i & 3));
+              own[3] = u32x4{l1[0], l1[1], l1[2], l1[3]};
+            }
+            if (n_limbs > 2u) {
+              uint32_t l2[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+              for (int i = 0; i < kNR; ++i) l2[i >> 2] |= ((len[i] >> 14) & 0x7Fu) << (8 * (i & 3));
+              reinterpret_cast<u32x4*>(meta)[tid] = u32x4{l2[0], l2[1], l2[2], l2[3]};
+            }
+            uint32_t mk[kNR / 2];  // active sets after records 2x and 2x + 1, 16 bits each
+            uint32_t act_even = 0u;
+#pragma unroll
+            for (int i = 0; i < kNR; ++i) {
+              planes_step<PLANES>(pl, key_region_bit(key[i]), key_end_mask(key[i]));
+              uint32_t act = pl[0];
+#pragma unroll
+              for (int k = 1; k < PLANES; ++k) act |= pl[k];
+              if (i & 1) mk[i >> 1] = __builtin_amdgcn_perm(act, act_even, 0x05040100u);  // the low halves of the two
+              else act_even = act;
+            }
+            own[0] = u32x4{mk[0], mk[1], mk[2], mk[3]};
+            own[1] = u32x4{mk[4], mk[5], mk[6], mk[7]};
+            products = (tid & ~63u) * kNR < n_events ? n_limbs : 0u;  // this wave holds records
+          } else {
+#pragma unroll
+            for (int i = 0; i < kNR; ++i)
+              switch_record(key_region_bit(key[i]) & region_bits, key_end_mask(key[i]), key_clock(key[i]));
+          }
+        } else {
+          // ---- the general way: the sequence is already in order, clocks up to 32 bits, up to 32 regions --
+          uint32_t st[kNR], sx[kNR];  // clock, region bit (0: no record)
+          uint32_t ends = 0;           // bit i: record i is an END
+          const u32x4 mv = reinterpret_cast<const u32x4*>(meta)[tid];
+          const uint32_t mw[4] = {mv.x, mv.y, mv.z, mv.w};
+          const u32x4* tv = reinterpret_cast<const u32x4*>(clk + clk_word(g0));
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const u32x4 v = tv[i];
+            st[4 * i] = v.x; st[4 * i + 1] = v.y; st[4 * i + 2] = v.z; st[4 * i + 3] = v.w;
+          }
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) {
+            const uint32_t info = (mw[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+            sx[i] = g0 + i < n_events ? 1u << (info >> 1) : 0u;
+            ends |= (info & 1u) << i;
+          }
+          auto end_mask = [&](int i) -> uint32_t { return (uint32_t)((int32_t)(ends << (31 - i)) >> 31); };  // all ones for an END
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, sx[i], end_mask(i));
+          state_before(st[0]);
+#pragma unroll
+          for (int i = 0; i < kNR; ++i) switch_record(sx[i], end_mask(i), st[i]);
         }
       }
     }
