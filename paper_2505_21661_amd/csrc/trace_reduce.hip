@@ -44,7 +44,7 @@ constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kRegion = 0x3Fu, kEmpty = 0x3Fu, kPaired = 0x40u, kEnd = 0x80u;
 constexpr int kNR = 16;                       // positions per lane
 constexpr uint32_t kWaveSpan = 64 * kNR;      // positions per hardware wave
-constexpr uint32_t kMaxCellWindow = 17;       // fullest time cell the sweep's register sort covers (halo 16)
+constexpr uint32_t kMaxCellWindow = 17;       // fullest time cell the sweep's register sort covers
 constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
 constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bins of different regions, different banks
@@ -276,45 +276,73 @@ __device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, u
   }
 }
 
-// Form for cells of up to HALO + 1 records: the lane reads a window of its 16 places and HALO on either
-// side, so that every cell with a record among the 16 lies inside the window, and sorts the whole
-// window.  (Only the lane's own 16 places come out right: the cell of the place after them may reach
-// past the window.)
-template <int HALO, uint32_t NPOS>
-__device__ __forceinline__ void sorted_window(const uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
-                                              uint32_t (&mine)[kNR]) {
-  constexpr int N = kNR + 2 * HALO;
-  uint32_t key[N];
+// Ascending order of 16 registers that first rise and then fall (or the reverse): 32 exchanges.
+__device__ __forceinline__ void bitonic_merge16(uint32_t (&v)[kNR]) {
+#pragma unroll
+  for (int k = 8; k >= 1; k >>= 1) {
+#pragma unroll
+    for (int i = 0; i < kNR; ++i) {
+      if ((i & k) == 0) {
+        const uint32_t x = v[i], y = v[i + k];
+        v[i] = x < y ? x : y;
+        v[i + k] = x < y ? y : x;
+      }
+    }
+  }
+}
+
+// Form for cells of up to 17 records: a cell then lies in at most two neighbouring lanes, with up to 16
+// records in either.  The lane sorts its own 16 places; then lanes 2m and 2m + 1 merge their runs (the
+// lower lane keeps the lower 16 of the 32, the upper lane the upper 16), and after that lanes 2m + 1 and
+// 2m + 2 do the same.  The second merge moves no record across the boundary the first one settled: what
+// it hands down to lane 2m + 1 belongs to the cell that lies across the boundary above, and that cell
+// has no record in lane 2m (it would hold 18).  Contains three workgroup barriers.
+template <uint32_t NPOS>
+__device__ __forceinline__ void sorted_pairs(uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
+                                             uint32_t (&key)[kNR]) {
   const uint32_t g0 = tid * kNR;
-  const int32_t wbeg = (int32_t)g0 - HALO;
-#pragma unroll
-  for (int x = 0; x < N / 4; ++x) {
-    int32_t e = wbeg + 4 * x;  // places outside the array are masked below
-    e = e < 0 ? 0 : (e > (int32_t)NPOS - 4 ? (int32_t)NPOS - 4 : e);
-    const u32x4 v = *reinterpret_cast<const u32x4*>(clk + clk_word((uint32_t)e));
-    key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
-  }
+  u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
   {
-    const u32x4 ma = reinterpret_cast<const u32x4*>(meta)[tid > 0 ? tid - 1 : 0];
     const u32x4 mb = reinterpret_cast<const u32x4*>(meta)[tid];
-    const u32x4 mc = reinterpret_cast<const u32x4*>(meta)[tid + 1];  // the array has 16 spare bytes
-    const uint32_t m12[12] = {ma.x, ma.y, ma.z, ma.w, mb.x, mb.y, mb.z, mb.w, mc.x, mc.y, mc.z, mc.w};
+    const uint32_t m4[4] = {mb.x, mb.y, mb.z, mb.w};
 #pragma unroll
-    for (int y = 0; y < N; ++y) {
-      constexpr int kFirst = 16 - HALO;  // byte of the first window place inside the three 16-byte blocks
-      key[y] = (key[y] << 6) | ((m12[(kFirst + y) >> 2] >> (8 * ((kFirst + y) & 3))) & 0x3Fu);
+    for (int x = 0; x < kNR / 4; ++x) {
+      const u32x4 v = own[x];
+      key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
     }
-  }
-  if (__builtin_amdgcn_ballot_w64(wbeg < 0 || (uint32_t)(wbeg + N) > n_events)) {
 #pragma unroll
-    for (int y = 0; y < N; ++y) {  // places outside the sequence: first or last
-      const int32_t e = wbeg + y;
-      key[y] = e < 0 ? 0u : ((uint32_t)e < n_events ? key[y] : fake);
+    for (int y = 0; y < kNR; ++y) key[y] = (key[y] << 6) | ((m4[y >> 2] >> (8 * (y & 3))) & 0x3Fu);
+  }
+  if (__builtin_amdgcn_ballot_w64(g0 + kNR > n_events)) {
+#pragma unroll
+    for (int y = 0; y < kNR; ++y) key[y] = g0 + y < n_events ? key[y] : fake;
+  }
+  network_sort<kNR>(key);
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    own[0] = u32x4{key[0], key[1], key[2], key[3]};
+    own[1] = u32x4{key[4], key[5], key[6], key[7]};
+    own[2] = u32x4{key[8], key[9], key[10], key[11]};
+    own[3] = u32x4{key[12], key[13], key[14], key[15]};
+    __syncthreads();
+    // round 0: partner of lane t is t ^ 1; round 1: the other neighbour (the first and the last lane have none)
+    const bool upper = ((tid ^ (uint32_t)round) & 1u) != 0u;  // this lane keeps the upper 16 of the merge
+    const bool alone = round == 1 && (tid == 0u || tid + 1u == NPOS / kNR);
+    const uint32_t partner = upper ? tid - 1u : tid + 1u;
+    const u32x4* other = reinterpret_cast<const u32x4*>(clk + clk_word((alone ? tid : partner) * kNR));
+    const u32x4 p0 = other[0], p1 = other[1], p2 = other[2], p3 = other[3];
+    const uint32_t pw[kNR] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w, p2.x, p2.y, p2.z, p2.w, p3.x, p3.y, p3.z, p3.w};
+    // the larger (smaller) of element i of one run and element 15 - i of the other: the upper (lower) 16
+    const uint32_t neutral = upper ? 0u : 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < kNR; ++i) {
+      const uint32_t x = key[i], y = alone ? neutral : pw[kNR - 1 - i];
+      const uint32_t lo = x < y ? x : y, hi = x < y ? y : x;
+      key[i] = upper ? hi : lo;
     }
+    bitonic_merge16(key);
+    if (round == 0) __syncthreads();  // every lane has read its partner's run before it is overwritten
   }
-  network_sort<N>(key);
-#pragma unroll
-  for (int i = 0; i < kNR; ++i) mine[i] = key[HALO + i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -980,7 +1008,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           uint32_t key[kNR];
           const uint32_t fake = (misc[2] << 6) | 0x3Fu;
           if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, meta, tid, n_events, fake, key);
-          else sorted_window<16, NPOS>(clk, meta, tid, n_events, fake, key);
+          else sorted_pairs<NPOS>(clk, meta, tid, n_events, fake, key);
 #pragma unroll
           for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, key_region_bit(key[i]), key_end_mask(key[i]));
           state_before(key_clock(key[0]));
