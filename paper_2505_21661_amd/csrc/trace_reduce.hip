@@ -58,7 +58,7 @@ enum { kStepOrdered = 1, kStepPaired, kStepCounted, kStepCellSums, kStepPlaced, 
 
 // per-workgroup temporaries (u32 words in LDS)
 enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_STARTS, T_ENDS,
-       T_EVENTS, T_MARKS, T_WIDE, T_MAXCELL, T_COUNT };
+       T_EVENTS, T_MARKS, T_WIDE, T_MAXCELL, T_HELD, T_COUNT };  // T_HELD stays last
 
 struct StatsLayout {  // offsets in u64 words
   size_t hist, cnt, sum, min, max, U, O, F, per, total;
@@ -100,7 +100,7 @@ struct Lds {
   static constexpr uint32_t tmp = ctr + 16 * 8;
   static constexpr uint32_t misc = align16(tmp + T_COUNT * 4);
   static constexpr uint32_t vf = misc + 4 * 4;
-  static constexpr uint32_t wtot = vf + 16 * 8;
+  static constexpr uint32_t wtot = vf + 32 * 8;
   static constexpr uint32_t ptot = wtot + 16 * 4;
   static constexpr uint32_t hist = ptot + 16 * 8 * 4;
   static constexpr uint32_t oacc = align16(hist + KP_MAX_REGIONS * kHistStride * 4);
@@ -475,14 +475,17 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // the last units of this workgroup's records: they travel while the staging state is cleared
     request_units(wg, tid, std::integral_constant<int, kEarly>{}, std::integral_constant<int, 8>{});
     // ---- workgroup header, clear the staging state -----------------------------------------------
-    if (tid < W) {
-      const uint32_t T = h_total;
+    if (tid <= KP_MAX_WAVES) {  // (entries from W up: no records)
+      const uint32_t T = tid < W ? h_total : 0u;
       const uint32_t V = T < cap ? T : cap;
       sVF[tid] = make_uint2(V, flush ? 0u : T - V);
       atomicAdd(&ctr[H_DROPPED], (unsigned long long)(T - V));
       atomicAdd(&ctr[H_SLOTS_VALID], (unsigned long long)V);
     }
-    if (tid >= 64 - T_COUNT && tid < 64) tmp[tid - (64 - T_COUNT)] = 0;
+    if (tid < 64) {  // clear the temporaries; the last one takes the records the waves hold together
+      const uint32_t held = wave_scan_add(tid < W ? (h_total < cap ? h_total : cap) : 0u);
+      if (tid >= 64 - T_COUNT) tmp[tid - (64 - T_COUNT)] = tid == 63u ? held : 0u;
+    }
     if (tid == 32) {
       const uint64_t tb = (uint64_t)h_begin.x | ((uint64_t)h_begin.y << 32);
       const uint64_t te = (uint64_t)h_end.x | ((uint64_t)h_end.y << 32);
@@ -515,45 +518,36 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     // Eight 16-byte units (two records each) per thread cover the workgroup.  Two records that go to an
     // even rank and the rank above it (the usual case: both sit in the slot of their seq) leave with one
     // 8-byte and one 2-byte store.
+    // (Slots that hold a record and fail a check are what is left of the header's record count.)
     {
-      const uint32_t n16 = nrec / 2;  // 16-byte units, two records each
-      uint32_t c_invalid = 0, c_field = 0, c_dis = 0;
+      uint32_t c_field = 0, c_dis = 0;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const uint32_t i = tid + u * BLOCK;
-        const bool live = i < n16;
-        const uint32_t f0 = 2 * (live ? i : n16 - 1);
-        const uint32_t w = f0 >> cl2;
+        const uint32_t f0 = 2u * (tid + u * BLOCK);
+        // a unit past the last record slot falls into a wave past the last one, which holds no records
+        const uint32_t wv = f0 >> cl2, w = wv < KP_MAX_WAVES ? wv : KP_MAX_WAVES, s0 = f0 & capm;
         const uint2 vf = sVF[w];
-        const uint32_t V = live ? vf.x : 0u, first = vf.y;
-        const uint32_t tag[2] = {v[u].x, v[u].z}, pay[2] = {v[u].y, v[u].w};
-        uint32_t k[2];
-        bool good[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const uint32_t s = (f0 + h) & capm;
-          const uint32_t seq = tag[h] & kSeqMask;
-          k[h] = (seq - first) & kSeqMask;
-          const uint32_t hi = tag[h] >> 20;  // phase | region | wave
-          const bool held = s < V;
-          good[h] = held && k[h] < V && (hi & 0xFu) == w && ((hi >> 4) & 0x7Fu) < R;
-          c_invalid += (held && !good[h]) ? 1u : 0u;
-          c_field += good[h] ? 1u : 0u;
-          c_dis += (good[h] && s != (seq & capm)) ? 1u : 0u;
-        }
-        const uint32_t pos0 = (w << cl2) + k[0], pos1 = (w << cl2) + k[1];
-        const bool twin = good[0] && good[1] && k[1] == k[0] + 1u && !(k[0] & 1u);
+        const uint32_t V = vf.x, first = vf.y;
+        const uint32_t tag0 = v[u].x, pay0 = v[u].y, tag1 = v[u].z, pay1 = v[u].w;
+        // rank: the low 20 bits of tag - first are those of seq - first
+        const uint32_t k0 = (tag0 - first) & kSeqMask, k1 = (tag1 - first) & kSeqMask;
+        const bool good0 = s0 < V && k0 < V && ((tag0 >> 20) & 0xFu) == w && ((tag0 >> 24) & 0x7Fu) < R;
+        const bool good1 = s0 + 1u < V && k1 < V && ((tag1 >> 20) & 0xFu) == w && ((tag1 >> 24) & 0x7Fu) < R;
+        c_field += (good0 ? 1u : 0u) + (good1 ? 1u : 0u);
+        c_dis += ((good0 && ((tag0 ^ s0) & capm) != 0u) ? 1u : 0u) + ((good1 && ((tag1 ^ (s0 + 1u)) & capm) != 0u) ? 1u : 0u);
+        const uint32_t base = f0 - s0;  // first position of the recorded wave
+        const uint32_t pos0 = base + k0, pos1 = base + k1;
+        // an even rank and the one above it: k1 - k0 == 1 and k0 even
+        const bool twin = good0 && good1 && (((k1 - k0) ^ 1u) | (k0 & 1u)) == 0u;
         if (twin) {
-          *reinterpret_cast<uint2*>(clk + clk_word(pos0)) = make_uint2(pay[0], pay[1]);
-          *reinterpret_cast<uint16_t*>(meta + pos0) = (uint16_t)((tag[0] >> 24) | ((tag[1] >> 24) << 8));
-        }
-        const bool one0 = good[0] && !twin, one1 = good[1] && !twin;
-        if (__builtin_amdgcn_ballot_w64(one0 || one1)) {
-          if (one0) { clk[clk_word(pos0)] = pay[0]; meta[pos0] = (uint8_t)(tag[0] >> 24); }  // END flag and region (below 64)
-          if (one1) { clk[clk_word(pos1)] = pay[1]; meta[pos1] = (uint8_t)(tag[1] >> 24); }
+          uint32_t* dst = clk + clk_word(pos0);
+          dst[0] = pay0; dst[1] = pay1;
+          *reinterpret_cast<uint16_t*>(meta + pos0) = (uint16_t)__builtin_amdgcn_perm(tag1, tag0, 0x0C0C0703u);  // END flag and region of both
+        } else {
+          if (good0) { clk[clk_word(pos0)] = pay0; meta[pos0] = (uint8_t)(tag0 >> 24); }
+          if (good1) { clk[clk_word(pos1)] = pay1; meta[pos1] = (uint8_t)(tag1 >> 24); }
         }
       }
-      add_tmp(tmp, T_INVALID, c_invalid);
       add_tmp(tmp, T_FIELDVALID, c_field);
       add_tmp(tmp, T_DISORDER, c_dis);
     }
@@ -622,7 +616,7 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
     }
     auto meta_of = [&](int i) -> uint32_t { return (mq[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
     auto set_paired = [&](int i, uint32_t yes) { mq[i >> 2] |= (yes << 6) << (8 * (i & 3)); };  // yes: 0 or 1
-    wg_invalid = tmp[T_INVALID] + (tmp[T_FIELDVALID] - n_occupied);
+    wg_invalid = tmp[T_HELD] - n_occupied;  // slots that hold a record and did not make it into the ordered sequence
 
     // One pair: duration into the per-(wave, region) sums and the histogram.  The sums exist in up to
     // four copies, one per quarter of the wave: lanes 16 apart tend to hold the same region, and LDS
