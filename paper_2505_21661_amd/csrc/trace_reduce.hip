@@ -228,20 +228,13 @@ __device__ __forceinline__ uint32_t key_end_mask(uint32_t k) { return (uint32_t)
 // (smaller) of element i of one run and element 7 - i of the other are the upper (lower) 8 of the two
 // runs, in rising-then-falling order.  Contains one workgroup barrier.
 template <uint32_t NPOS>
-__device__ __forceinline__ void sorted_own(uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
-                                           uint32_t (&key)[kNR]) {
+__device__ __forceinline__ void sorted_own(uint32_t* clk, uint32_t tid, uint32_t n_events, uint32_t fake, uint32_t (&key)[kNR]) {
   const uint32_t g0 = tid * kNR;
   u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
-  {
-    const u32x4 mb = reinterpret_cast<const u32x4*>(meta)[tid];
-    const uint32_t m4[4] = {mb.x, mb.y, mb.z, mb.w};
 #pragma unroll
-    for (int x = 0; x < kNR / 4; ++x) {
-      const u32x4 v = own[x];
-      key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
-    }
-#pragma unroll
-    for (int y = 0; y < kNR; ++y) key[y] = (key[y] << 6) | ((m4[y >> 2] >> (8 * (y & 3))) & 0x3Fu);
+  for (int x = 0; x < kNR / 4; ++x) {
+    const u32x4 v = own[x];
+    key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
   }
   if (__builtin_amdgcn_ballot_w64(g0 + kNR > n_events)) {
 #pragma unroll
@@ -298,20 +291,13 @@ __device__ __forceinline__ void bitonic_merge16(uint32_t (&v)[kNR]) {
 // it hands down to lane 2m + 1 belongs to the cell that lies across the boundary above, and that cell
 // has no record in lane 2m (it would hold 18).  Contains three workgroup barriers.
 template <uint32_t NPOS>
-__device__ __forceinline__ void sorted_pairs(uint32_t* clk, const uint8_t* meta, uint32_t tid, uint32_t n_events, uint32_t fake,
-                                             uint32_t (&key)[kNR]) {
+__device__ __forceinline__ void sorted_pairs(uint32_t* clk, uint32_t tid, uint32_t n_events, uint32_t fake, uint32_t (&key)[kNR]) {
   const uint32_t g0 = tid * kNR;
   u32x4* own = reinterpret_cast<u32x4*>(clk + clk_word(g0));
-  {
-    const u32x4 mb = reinterpret_cast<const u32x4*>(meta)[tid];
-    const uint32_t m4[4] = {mb.x, mb.y, mb.z, mb.w};
 #pragma unroll
-    for (int x = 0; x < kNR / 4; ++x) {
-      const u32x4 v = own[x];
-      key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
-    }
-#pragma unroll
-    for (int y = 0; y < kNR; ++y) key[y] = (key[y] << 6) | ((m4[y >> 2] >> (8 * (y & 3))) & 0x3Fu);
+  for (int x = 0; x < kNR / 4; ++x) {
+    const u32x4 v = own[x];
+    key[4 * x] = v.x; key[4 * x + 1] = v.y; key[4 * x + 2] = v.z; key[4 * x + 3] = v.w;
   }
   if (__builtin_amdgcn_ballot_w64(g0 + kNR > n_events)) {
 #pragma unroll
@@ -863,8 +849,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
         for (int i = 0; i < kNR; ++i) {
           const bool ev = (meta_of(i) & kPaired) != 0u;
           const uint32_t g = cell_start(ca[i] & 0xFFFFu) + (ca[i] >> 16);
-          clk[ev ? clk_word(g) : kSpareWord] = t[i];  // no branch: the others all write one unused word
-          meta[ev ? g : NPOS] = (uint8_t)info_of(i);
+          // the word the sweep sorts: clock << 6 | region << 1 | END (no branch: the others all write one unused word)
+          clk[ev ? clk_word(g) : kSpareWord] = (t[i] << 6) | info_of(i);
         }
         __syncthreads();
         if (stop_after >= kStepPlaced && stop_after <= kStepSorted) break;
@@ -1001,8 +987,8 @@ __global__ __launch_bounds__(BLOCK) void kp_reduce_main(DecodeParams p) {
           // ---- the order is finished in registers; one word per record from here on ------------------
           uint32_t key[kNR];
           const uint32_t fake = (misc[2] << 6) | 0x3Fu;
-          if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, meta, tid, n_events, fake, key);
-          else sorted_pairs<NPOS>(clk, meta, tid, n_events, fake, key);
+          if (tmp[T_MAXCELL] <= 9u) sorted_own<NPOS>(clk, tid, n_events, fake, key);
+          else sorted_pairs<NPOS>(clk, tid, n_events, fake, key);
 #pragma unroll
           for (int i = 0; i < kNR; ++i) planes_step<PLANES>(pl, key_region_bit(key[i]), key_end_mask(key[i]));
           state_before(key_clock(key[0]));
