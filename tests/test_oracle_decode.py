@@ -313,3 +313,25 @@ def test_slot_permutation_only_changes_disorder(oracle_mod):
 def test_thread_count_does_not_change_the_result(oracle_mod):
     raw, _ = inputs.gen_trace(inputs.spec_decode_standalone(16))
     assert np.array_equal(oracle_mod.decode_bytes(raw, 1), oracle_mod.decode_bytes(raw, 5))
+
+
+# ---- the format's own limits: up to 128 regions, long rings ------------------------------------
+
+@pytest.mark.parametrize("R,cap,waves", [(33, 16, 2), (64, 8, 3), (128, 16, 2), (100, 64, 1), (127, 4, 16)])
+def test_many_regions_against_brute_force(oracle_mod, R, cap, waves):
+    """The tag names up to 128 regions (7 bits): the same brute force, with region numbers that use the
+    whole field."""
+    for k in range(2):
+        raw = inputs.messy_trace(7 * R + cap + k, n_wg=3, waves=waves, n_regions=R, cap_wave=cap,
+                                 p_bad=0.03 * k, allow_nonmono=False, flush=bool(k))
+        assert_same(brute_decode(raw), oracle_mod.decode(raw))
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_long_rings_against_brute_force(oracle_mod, seed):
+    """Rings of 1024 and 4096 records per wave, wrapped, with swapped slots and orphans."""
+    spec = inputs.TraceSpec(n_wg=2, waves=2 + seed, n_regions=[3, 40, 6][seed], cap_wave=[1024, 1024, 4096][seed],
+                            total_per_wave=[1500, 1024, 5000][seed], total_var=100, seed=50 + seed, dist="exp", p0=6.0,
+                            gap_max=4, phase_max=30, p_orphan=0.05, p_swap=0.01, swap_max=7, rec_cost=1)
+    raw, _ = inputs.gen_trace(spec)
+    assert_same(brute_decode(raw), oracle_mod.decode(raw))
