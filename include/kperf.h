@@ -61,7 +61,8 @@ enum {
 #define KP_FLAG_REALTIME 2u         /* bit 1: payloads, t_begin and t_end are ticks of the constant-rate 100 MHz clock */
 #define KP_FLAG_HW_IDS 4u           /* bit 2: kp_wg_hdr.wave_hw_id[] holds the hardware id of every record stream's wave */
 #define KP_MAX_WAVES 16
-#define KP_MAX_REGIONS 32           /* decoder limit; the tag field itself holds 7 bits */
+#define KP_MAX_REGIONS 32           /* regions of the recording kernels and of the decoder's fast path */
+#define KP_MAX_TAG_REGIONS 128      /* regions the tag's 7-bit field can name: the decoders' limit */
 #define KP_HIST_BINS 64
 
 typedef struct kp_trace_hdr {
@@ -142,10 +143,13 @@ size_t kp_stats_bytes(int n_wg, int waves_per_wg, int n_regions);
  * the geometry from a HOST copy of the header instead and never synchronises; if the device
  * header disagrees, no statistics are produced and kp_stats_hdr.status is set to 1.
  *
- * Limits: waves_per_wg <= 16, n_regions <= 32, cap_wave a power of two >= 2, and one
- * workgroup's records must fit the decoder's LDS staging (waves_per_wg * cap_wave <= 16384,
- * less for n_regions > 16): otherwise KP_ERR_UNSUPPORTED_SHAPE.  Header/`n` mismatch:
- * KP_ERR_BAD_TRACE.
+ * Limits: waves_per_wg <= 16, n_regions <= 128, cap_wave a power of two, 2 <= cap_wave <= 2^20.
+ * A trace with n_regions <= 32 and waves_per_wg * cap_wave <= 16384 is decoded by a kernel that
+ * keeps one workgroup's records in LDS; any other one by a kernel that makes several passes over
+ * the records in device memory and keeps one bit per record slot of a workgroup in LDS, next to
+ * accumulators whose size grows with n_regions: waves_per_wg * cap_wave <= 2^19 for up to 64
+ * regions, <= 2^17 for 128 (KP_ERR_UNSUPPORTED_SHAPE beyond; kp_last_error names the bytes).
+ * Header/`n` mismatch, unknown flags, n_regions > 128: KP_ERR_BAD_TRACE.
  */
 kp_status kp_trace_reduce(const void* raw, size_t n, void* out_stats, void* stream);
 kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
@@ -158,7 +162,8 @@ kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr
  * by clock: 3 counted into time cells, 4 prefix sum over the cells, 5 placed by cell, 6 ranked
  * inside their cell, 7 sorted sequence written; 8 region-pair overlap swept.  The differences
  * between the run times of consecutive steps are the cost of each step.  out_stats is written but
- * its contents are unspecified.
+ * its contents are unspecified.  Only for traces that the LDS-resident kernel takes (n_regions <= 32,
+ * waves_per_wg * cap_wave <= 16384); KP_ERR_UNSUPPORTED_SHAPE otherwise.
  */
 kp_status kp_trace_reduce_steps(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
                                 void* out_stats, int last_step, void* stream);

@@ -31,11 +31,13 @@
 // clocks and add every switch of a region to the region-pair sums with LDS atomics.
 // A workgroup with a corrupt record (bad field, duplicated seq) has holes in its ranks; it is rare,
 // takes no part in the overlap statistics and is paired by a plain serial walk per (wave, region).
-#include "kp_common.h"
+#include "kp_reduce.h"
 
 #include <type_traits>
 
 namespace {
+
+using namespace kp_reduce;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -49,31 +51,12 @@ constexpr uint32_t kMaxRecPerWg = 16384;
 constexpr uint32_t kMaxLds = 160 * 1024;
 constexpr uint32_t kHistStride = 65;  // histogram rows 65 words apart: equal bins of different regions, different banks
 
-// positions inside kp_stats_hdr, in u64 words
-enum { H_SLOTS_VALID = 0, H_PAIRS, H_ORPHAN_START, H_ORPHAN_END, H_INVALID, H_DROPPED, H_DISORDER,
-       H_SPAN_OVF, H_NONMONO, H_OVERLAP_WGS, H_STATUS, H_NWG, H_WAVES, H_NREG, H_CAP, H_RSVD };
-
 // steps after which kp_trace_reduce_steps can leave a workgroup
 enum { kStepOrdered = 1, kStepPaired, kStepCounted, kStepCellSums, kStepPlaced, kStepRanked, kStepSorted, kStepSwept };
 
 // per-workgroup temporaries (u32 words in LDS)
 enum { T_INVALID = 0, T_FIELDVALID, T_DISORDER, T_OCCUPIED, T_NONMONO, T_PAIRS, T_STARTS, T_ENDS,
        T_EVENTS, T_MARKS, T_WIDE, T_MAXCELL, T_HELD, T_COUNT };  // T_HELD stays last
-
-struct StatsLayout {  // offsets in u64 words
-  size_t hist, cnt, sum, min, max, U, O, F, per, total;
-};
-__host__ __device__ inline StatsLayout stats_layout(uint32_t n_wg, uint32_t W, uint32_t R) {
-  StatsLayout l;
-  l.hist = 16;
-  l.cnt = l.hist + (size_t)64 * R;
-  l.sum = l.cnt + R; l.min = l.sum + R; l.max = l.min + R; l.U = l.max + R;
-  l.O = l.U + R;
-  l.F = l.O + (size_t)R * R;
-  l.per = l.F + (size_t)R * R;
-  l.total = l.per + (size_t)2 * n_wg * W * R;
-  return l;
-}
 
 struct DecodeParams {
   const uint32_t* wg_hdrs;  // 32 words per recorded workgroup
@@ -349,26 +332,25 @@ __global__ void kp_reduce_init(const uint32_t* trace_hdr, uint64_t* out, uint32_
   }
 }
 
-// finalize: cnt from the histogram, O = Otmp + Otmp^T off the diagonal, U = diag, F = O/U.
+// finalize (one workgroup): cnt from the histogram, O = Otmp + Otmp^T off the diagonal, U = diag,
+// F = O/U.  Otmp is what the main kernels staged in the F area.
 __global__ void kp_reduce_finalize(uint64_t* out, uint32_t n_wg, uint32_t W, uint32_t R) {
-  __shared__ uint64_t tmp[KP_MAX_REGIONS * KP_MAX_REGIONS];
   const StatsLayout l = stats_layout(n_wg, W, R);
   const uint32_t tid = threadIdx.x;
-  for (uint32_t i = tid; i < R * R; i += blockDim.x) tmp[i] = out[l.F + i];  // staged Otmp
-  if (tid < R) {
+  for (uint32_t r = tid; r < R; r += blockDim.x) {
     uint64_t c = 0;
-    for (int b = 0; b < 64; ++b) c += out[l.hist + (size_t)tid * 64 + b];
-    out[l.cnt + tid] = c;
+    for (int b = 0; b < 64; ++b) c += out[l.hist + (size_t)r * 64 + b];
+    out[l.cnt + r] = c;
+    out[l.U + r] = out[l.F + (size_t)r * R + r];
   }
-  __syncthreads();
   for (uint32_t i = tid; i < R * R; i += blockDim.x) {
     const uint32_t a = i / R, b = i % R;
-    const uint64_t u = tmp[a * R + a];
-    const uint64_t o = (a == b) ? u : tmp[a * R + b] + tmp[b * R + a];
-    out[l.O + i] = o;
-    double f = u ? (double)o / (double)u : 0.0;
-    reinterpret_cast<double*>(out)[l.F + i] = f;
-    if (a == b) out[l.U + a] = u;
+    out[l.O + i] = a == b ? out[l.F + i] : out[l.F + i] + out[l.F + (size_t)b * R + a];
+  }
+  __syncthreads();  // (a workgroup's own global stores are visible to it after the barrier)
+  for (uint32_t i = tid; i < R * R; i += blockDim.x) {
+    const uint64_t u = out[l.U + i / R], o = out[l.O + i];
+    reinterpret_cast<double*>(out)[l.F + i] = u ? (double)o / (double)u : 0.0;
   }
 }
 
@@ -1244,12 +1226,20 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
     return kp::fail(KP_ERR_BAD_TRACE, "trace header describes %zu record slots, caller passed %zu",
                     (size_t)h.n_wg * h.waves_per_wg * h.cap_wave, n);
   if ((h.flags & ~(KP_FLAG_FLUSH | KP_FLAG_REALTIME | KP_FLAG_HW_IDS)) != 0) return kp::fail(KP_ERR_BAD_TRACE, "trace header: unknown flags %x", h.flags);
-  if (h.n_regions > KP_MAX_REGIONS)
-    return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "n_regions=%u exceeds the decoder limit %d", h.n_regions, KP_MAX_REGIONS);
+  if (h.n_regions > KP_MAX_TAG_REGIONS)
+    return kp::fail(KP_ERR_BAD_TRACE, "trace header: n_regions=%u, the tag holds %d", h.n_regions, KP_MAX_TAG_REGIONS);
   if (h.cap_wave < 2) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "cap_wave must be at least 2");
+  if (h.cap_wave > (1u << 20)) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "cap_wave=%u exceeds the range of seq", h.cap_wave);
   const uint32_t nrec = h.waves_per_wg * h.cap_wave;
-  if (nrec > kMaxRecPerWg)
-    return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "%u records per workgroup exceed the LDS staging limit %u", nrec, kMaxRecPerWg);
+  // geometries the LDS-resident kernel is not built for go to the multi-pass kernel
+  const bool wide = h.n_regions > KP_MAX_REGIONS || nrec > kMaxRecPerWg;
+  if (wide) {
+    const kp_status st = wide_supported(h);
+    if (st != KP_OK) return st;
+  }
+  if (wide && stop_after)
+    return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "single steps exist for the LDS-resident decoder only (n_regions <= %d, %u records per workgroup)",
+                    KP_MAX_REGIONS, kMaxRecPerWg);
   if (((uintptr_t)raw & 15u) || ((uintptr_t)out_stats & 15u))
     return kp::fail(KP_ERR_INVALID_ARG, "raw and out_stats must be 16-byte aligned");
 
@@ -1267,7 +1257,11 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
                      reinterpret_cast<const uint32_t*>(base), out, h.n_wg, W, R, cap, h.flags);
   KP_HIP_TRY(hipGetLastError());
 
-  if (h.n_wg > 0) {
+  if (h.n_wg > 0 && wide) {
+    const kp_status st = launch_wide(reinterpret_cast<const uint32_t*>(base + sizeof(kp_trace_hdr)),
+                                     base + sizeof(kp_trace_hdr) + sizeof(kp_wg_hdr) * (size_t)h.n_wg, out, h, s);
+    if (st != KP_OK) return st;
+  } else if (h.n_wg > 0) {
     DecodeParams p;
     p.wg_hdrs = reinterpret_cast<const uint32_t*>(base + sizeof(kp_trace_hdr));
     p.records = reinterpret_cast<const u32x4*>(base + sizeof(kp_trace_hdr) + sizeof(kp_wg_hdr) * (size_t)h.n_wg);

@@ -116,13 +116,13 @@ def test_errors(kp):
     with pytest.raises(kp.KperfError) as e:
         kp.kp_trace_reduce(torch.from_numpy(bad.view(np.int32)).cuda(), n_wg * W * cap, out)
     assert e.value.status == kp.KP_ERR_BAD_TRACE
-    # too many records per workgroup for the LDS staging
+    # more record slots per workgroup than any kernel takes; more regions than the tag names
     with pytest.raises(kp.KperfError) as e:
-        kp.kp_trace_reduce_hdr(dev, 16 * 2048, kp.make_hdr(1, 16, 4, 2048), out)
+        kp.kp_trace_reduce_hdr(dev, 16 * (1 << 16), kp.make_hdr(1, 16, 4, 1 << 16), out)
     assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
     with pytest.raises(kp.KperfError) as e:
-        kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, 40, cap), out)
-    assert e.value.status == kp.KP_ERR_UNSUPPORTED_SHAPE
+        kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, 129, cap), out)
+    assert e.value.status == kp.KP_ERR_BAD_TRACE
     # host header that disagrees with the device header: flagged in the stats block, no statistics
     kp.kp_trace_reduce_hdr(dev, n_wg * W * cap, kp.make_hdr(n_wg, W, R + 1, cap),
                            torch.zeros(kp.kp_stats_bytes(n_wg, W, R + 1), dtype=torch.uint8, device="cuda"))
