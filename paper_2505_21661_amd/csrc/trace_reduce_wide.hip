@@ -5,8 +5,10 @@
 // unpaired and aligned at replay, the constant record cost is subtracted), same statistics block, in
 // several passes over a recorded workgroup's records, which stay in HBM:
 //   0  every slot is checked once (fields, slot against seq).  Only a workgroup with a record outside
-//      the slot of its seq needs more: which slot wins each rank is then found a range of ranks at a
-//      time, by scanning all slots into a rank -> slot table (the later slot wins: atomic max);
+//      the slot of its seq needs more: those records go on a list, and which slot wins each rank is
+//      then found a range of ranks at a time from the slots the ranks belong in and the list (the
+//      later slot wins: atomic max into a rank -> slot table); a workgroup with more such records
+//      than the list holds scans all its slots for every range instead;
 //   1  pairing, a range of ranks of every wave at a time: the records of the range are put into LDS in
 //      rank order and one thread per (wave, region) walks them, which is the definition of the pairing
 //      (an END is paired iff the nearest earlier record of its wave and region is a START).  The
@@ -33,6 +35,7 @@ using namespace kp_reduce;
 constexpr int kBlock = 1024;
 constexpr uint32_t kWavesHw = kBlock / 64;
 constexpr uint32_t kK = 2048;               // records in LDS at a time: 2 per thread
+constexpr uint32_t kList = 2048;            // records outside the slot of their seq that a workgroup can list
 constexpr uint32_t kSlab = kK / kWavesHw;   // sorted events per hardware wave
 constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kHistStride = 65;        // histogram rows 65 words apart: equal bins of different regions, different banks
@@ -42,17 +45,18 @@ constexpr uint32_t kMaxLds = 160 * 1024;
 
 // per-workgroup temporaries (u32 words in LDS)
 enum { T_FIELDVALID = 0, T_DISORDER, T_OCCUPIED, T_WINNER_DISORDER, T_NONMONO, T_PAIRS, T_ORPHAN_START, T_ORPHAN_END, T_WINDOW_END,
-       T_ADVANCED, T_COUNT };
+       T_ADVANCED, T_LISTED, T_COUNT };
 
 struct WideLds {  // byte offsets
-  uint32_t keys, table, bitmap, otri, hist, reg_sum, reg_max, reg_min, n_open, slab_delta, ctr, tmp, vf, pos, adv, total;
+  uint32_t keys, table, list, bitmap, otri, hist, reg_sum, reg_max, reg_min, n_open, slab_delta, ctr, tmp, vf, pos, adv, total;
 };
 inline uint32_t up16(uint32_t x) { return (x + 15u) & ~15u; }
 WideLds wide_lds(uint32_t R, uint32_t nrec) {
   WideLds l;
   l.keys = 0;
   l.table = l.keys + kK * 8;
-  l.bitmap = l.table + kK * 4;
+  l.list = l.table + kK * 4;
+  l.bitmap = l.list + kList * 4;
   l.otri = up16(l.bitmap + ((nrec + 31) / 32) * 4);
   l.hist = l.otri + R * (R + 1) / 2 * 8;
   l.reg_sum = up16(l.hist + R * kHistStride * 4);
@@ -88,6 +92,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + p.lds.keys);
   uint32_t* table = reinterpret_cast<uint32_t*>(smem + p.lds.table);    // rank -> winning slot + 1, for the ranks in LDS
+  uint32_t* list = reinterpret_cast<uint32_t*>(smem + p.lds.list);      // wave << 20 | slot of the records outside the slot of their seq
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(smem + p.lds.bitmap);  // bit wave * cap + rank: the record is a paired START or END
   unsigned long long* otri = reinterpret_cast<unsigned long long*>(smem + p.lds.otri);  // pair (a <= b) at b (b + 1) / 2 + a
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem + p.lds.hist);
@@ -114,15 +119,17 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
   if (tid < 16) ctr[tid] = 0;
   __syncthreads();
 
-  // the (wave, region) walks of this thread: entry e = wave * R + region, entries tid and tid + kBlock
-  uint32_t ew[2], er[2];
+  // The (wave, region) walks of this thread: entry e = wave * R + region.  Consecutive entries go to
+  // different hardware waves: a walk's lane is busy at one record in R while the other lanes of its
+  // hardware wave wait, so the walks that are busy at the same time should not share one.
+  uint32_t ee[2], ew[2], er[2];
   bool ehas[2];
 #pragma unroll
   for (int x = 0; x < 2; ++x) {
-    const uint32_t e = tid + x * kBlock;
-    ehas[x] = e < W * R;
-    ew[x] = ehas[x] ? e / R : 0u;
-    er[x] = e - ew[x] * R;
+    ee[x] = hw + kWavesHw * (lane + 64u * x);
+    ehas[x] = ee[x] < W * R;
+    ew[x] = ehas[x] ? ee[x] / R : 0u;
+    er[x] = ee[x] - ew[x] * R;
   }
 
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
@@ -168,7 +175,11 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
         const uint32_t s = i & capm;
         const bool good = rank_of(rec, i >> cl2, s) != 0xFFFFFFFFu;
         c_field += good ? 1u : 0u;
-        c_dis += (good && ((rec.x ^ s) & capm) != 0u) ? 1u : 0u;
+        if (good && ((rec.x ^ s) & capm) != 0u) {
+          ++c_dis;
+          const uint32_t at = atomicAdd(&tmp[T_LISTED], 1u);
+          if (at < kList) list[at] = ((i >> cl2) << 20) | s;
+        }
       }
       c_field = wave_sum(c_field);
       c_dis = wave_sum(c_dis);
@@ -181,6 +192,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
     // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
     // distinct ranks, and rank k of a wave is in slot (first + k) mod cap.
     const bool displaced = tmp[T_DISORDER] != 0u;
+    const uint32_t n_listed = tmp[T_LISTED] <= kList ? tmp[T_LISTED] : 0xFFFFFFFFu;  // all ones: the list is not complete
     uint32_t n_occupied = tmp[T_FIELDVALID], n_disorder = 0;
 
     // The ranks pos[w] .. pos[w] + C of every wave: which slot holds each (the later slot wins).
@@ -188,12 +200,25 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
       __syncthreads();  // pos[] is written, the table's last readers are done
       table[tid] = 0; table[tid + kBlock] = 0;
       __syncthreads();
-      for (uint32_t i = tid; i < nrec; i += kBlock) {
-        const uint32_t w = i >> cl2, s = i & capm;
-        const uint32_t k = rank_of(recs[i], w, s);
-        if (k == 0xFFFFFFFFu) continue;
+      auto offer = [&](uint32_t w, uint32_t s) {
+        const uint32_t k = rank_of(recs[(size_t)w * cap + s], w, s);
+        if (k == 0xFFFFFFFFu) return;
         const uint32_t d = k - pos[w];
         if (d < C) atomicMax(&table[(w << rsh) + d], s + 1u);
+      };
+      if (n_listed != 0xFFFFFFFFu) {
+        // a record in the slot of its seq: rank k of a wave is in slot (first + k) mod cap; the others: listed
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const uint32_t idx = tid + x * kBlock, w = idx >> rsh;
+          if (w >= W) continue;
+          const uint2 vf = sVF[w];
+          const uint32_t k = pos[w] + (idx & (C - 1u));
+          if (k < vf.x) offer(w, (vf.y + k) & capm);
+        }
+        for (uint32_t i = tid; i < n_listed; i += kBlock) offer(list[i] >> 20, list[i] & 0xFFFFFu);
+      } else {
+        for (uint32_t i = tid; i < nrec; i += kBlock) offer(i >> cl2, i & capm);
       }
       __syncthreads();
     };
@@ -265,9 +290,15 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
           if (!ehas[x]) continue;
           const uint32_t w = ew[x], V = sVF[w].x, mine = 0x100u | er[x];
           const uint32_t nj = V > k0 ? (V - k0 < C ? V - k0 : C) : 0u;
-          const uint2* ent = reinterpret_cast<const uint2*>(keys) + (w << rsh);
-          for (uint32_t j = 0; j < nj; ++j) {
-            const uint32_t m = ent[j].x, ts = ent[j].y;
+          const uint4* ent = reinterpret_cast<const uint4*>(keys + (w << rsh));  // two entries per load
+          // four entries per step, so that their loads are in flight together (places past the wave's last
+          // record hold no record; the range is a multiple of four long)
+          for (uint32_t j4 = 0; j4 < nj; j4 += 4u) {
+            const uint4 e01 = ent[j4 / 2u], e23 = ent[j4 / 2u + 1u];
+            const uint32_t ms[4] = {e01.x, e01.z, e23.x, e23.z}, tss[4] = {e01.y, e01.w, e23.y, e23.w};
+#pragma unroll
+            for (uint32_t u = 0; u < 4u; ++u) {
+            const uint32_t j = j4 + u, m = ms[u], ts = tss[u];
             if (!(m & 0x100u)) continue;  // no record at this rank
             if (er[x] == 0u) {
               nonmono += (have_any[x] && ts < last_ts[x]) ? 1u : 0u;
@@ -291,6 +322,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
               ++orphan_e[x];
             }
             have_prev[x] = true; prev_end[x] = is_end; prev_ts[x] = ts; prev_k[x] = k0 + j;
+            }
           }
         }
       }
@@ -298,7 +330,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
       for (int x = 0; x < 2; ++x) {
         if (!ehas[x]) continue;
         orphan_s[x] += (have_prev[x] && !prev_end[x]) ? 1u : 0u;  // START at the end of the sequence
-        uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + tid + x * kBlock) * 2;
+        uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + ee[x]) * 2;
         dst[0] = sum[x];
         dst[1] = (uint64_t)n[x] | ((uint64_t)mx[x] << 32);
         if (n[x]) {
@@ -364,38 +396,38 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
         const bool inside = mine[x] != kNoKey && (uint32_t)(mine[x] >> 9) <= window_end;
         const bool next_inside = next != kNoKey && (uint32_t)(next >> 9) <= window_end;
         if (inside && !next_inside) { adv[w] = j + 1u; tmp[T_ADVANCED] = 1u; }  // the records inside are the first ones of the range
-        mine[x] = (inside && !(mine[x] & 0x100u)) ? mine[x] : kNoKey;
+        mine[x] = inside ? mine[x] : kNoKey;  // (records that are no events stay: every wave's run stays in clock order)
       }
       __syncthreads();
       keys[tid] = mine[0]; keys[tid + kBlock] = mine[1];
       __syncthreads();
       if (tmp[T_ADVANCED] == 0u) break;  // (cannot happen, see above)
-      // ascending bitonic sort of the kK keys
-      for (uint32_t size = 2; size <= kK; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-          const uint32_t lo = ((tid & ~(stride - 1u)) << 1) | (tid & (stride - 1u)), hi = lo | stride;
-          const bool up = (lo & size) == 0u;
+      // The runs of the waves (C places each, in clock order; places without a record at the end) are merged
+      // by clock, pairs of runs of `size / 2` at a time: the first step compares place i of the lower run
+      // with place size/2 - 1 - i of the upper one, the others are the half-cleaners of a bitonic merge.
+      for (uint32_t size = 2u * C; size <= kK; size <<= 1) {
+        const uint32_t half = size >> 1;
+        {
+          const uint32_t blk = (tid / half) * size, i = tid & (half - 1u), lo = blk + i, hi = blk + size - 1u - i;
           const unsigned long long a = keys[lo], b = keys[hi];
-          if ((a > b) == up) { keys[lo] = b; keys[hi] = a; }
+          if ((a >> 9) > (b >> 9)) { keys[lo] = b; keys[hi] = a; }
+          __syncthreads();
+        }
+        for (uint32_t stride = half >> 1; stride > 0; stride >>= 1) {
+          const uint32_t lo = ((tid & ~(stride - 1u)) << 1) | (tid & (stride - 1u)), hi = lo | stride;
+          const unsigned long long a = keys[lo], b = keys[hi];
+          if ((a >> 9) > (b >> 9)) { keys[lo] = b; keys[hi] = a; }
           __syncthreads();
         }
       }
-      // slab of this hardware wave: net change per region
-      const unsigned long long* slab = keys + hw * kSlab;
-      {
-        int32_t d_lo = 0, d_hi = 0;
-        for (uint32_t i = 0; i < kSlab; ++i) {
-          const uint32_t low = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)slab[i]);
-          const uint32_t high = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(slab[i] >> 32));
-          if ((low & high) == 0xFFFFFFFFu) break;  // past the last event
-          const uint32_t r = (low >> 1) & 0x7Fu;
-          const int32_t dv = (low & 1u) ? -1 : 1;
-          d_lo += r == lane ? dv : 0;
-          d_hi += r == lane + 64u ? dv : 0;
-        }
-        slab_delta[hw * kRegStride + lane] = d_lo;
-        slab_delta[hw * kRegStride + 64u + lane] = d_hi;
-      }
+      // slab of this hardware wave, two places per lane: lane l holds places l and 64 + l
+      const unsigned long long place0 = keys[hw * kSlab + lane], place1 = keys[hw * kSlab + 64u + lane];
+      const uint32_t low0 = (uint32_t)place0, high0 = (uint32_t)(place0 >> 32), low1 = (uint32_t)place1, high1 = (uint32_t)(place1 >> 32);
+      // net change per region over the slab
+      slab_delta[hw * kRegStride + lane] = 0;
+      slab_delta[hw * kRegStride + 64u + lane] = 0;  // (LDS operations of one wave take effect in order)
+      if (place0 != kNoKey && !(low0 & 0x100u)) atomicAdd(&slab_delta[hw * kRegStride + ((low0 >> 1) & 0x7Fu)], (low0 & 1u) ? -1 : 1);
+      if (place1 != kNoKey && !(low1 & 0x100u)) atomicAdd(&slab_delta[hw * kRegStride + ((low1 >> 1) & 0x7Fu)], (low1 & 1u) ? -1 : 1);
       __syncthreads();
       {
         int32_t c_lo = n_open[lane], c_hi = n_open[64u + lane];  // waves that have region lane, lane + 64 open
@@ -403,31 +435,64 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
           c_lo += slab_delta[h * kRegStride + lane];
           c_hi += slab_delta[h * kRegStride + 64u + lane];
         }
-        for (uint32_t i = 0; i < kSlab; ++i) {
-          const uint32_t low = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)slab[i]);
-          const uint32_t high = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(slab[i] >> 32));
-          if ((low & high) == 0xFFFFFFFFu) break;
-          const uint32_t r = (low >> 1) & 0x7Fu, t = (low >> 9) | (high << 23);
-          const bool is_end = (low & 1u) != 0u, upper = r >= 64u, owner = (r & 63u) == lane;
-          const int32_t c = upper ? c_hi : c_lo;
-          // the region opens (no wave had it open) or closes (the last wave that had it open)
-          const bool switches = __builtin_amdgcn_ballot_w64(owner && c == (is_end ? 1 : 0)) != 0ull;
-          if (switches) {
+        // Which events open or close their region: the number of waves that have the region open right
+        // before the event is the number at the slab's start plus the STARTs minus the ENDs of the region
+        // at earlier places of the slab.  The lanes whose event has the same region come from one ballot per
+        // bit of the region number.
+        const bool ev0 = place0 != kNoKey && !(low0 & 0x100u), ev1 = place1 != kNoKey && !(low1 & 0x100u);
+        const uint32_t r0 = (low0 >> 1) & 0x7Fu, r1 = (low1 >> 1) & 0x7Fu;
+        const bool end0 = (low0 & 1u) != 0u, end1 = (low1 & 1u) != 0u;
+        uint64_t same00 = __builtin_amdgcn_ballot_w64(ev0);  // places 0..63 with the region of this lane's place there
+        uint64_t same01 = same00;                              // places 0..63 with the region of this lane's place 64 + lane
+        uint64_t same11 = __builtin_amdgcn_ballot_w64(ev1);  // places 64..127 with that region
+#pragma unroll
+        for (uint32_t b = 0; b < 7u; ++b) {
+          const uint64_t set0 = __builtin_amdgcn_ballot_w64(ev0 && ((r0 >> b) & 1u));
+          const uint64_t set1 = __builtin_amdgcn_ballot_w64(ev1 && ((r1 >> b) & 1u));
+          same00 &= ((r0 >> b) & 1u) ? set0 : ~set0;
+          same01 &= ((r1 >> b) & 1u) ? set0 : ~set0;
+          same11 &= ((r1 >> b) & 1u) ? set1 : ~set1;
+        }
+        const uint64_t ends0 = __builtin_amdgcn_ballot_w64(ev0 && end0), ends1 = __builtin_amdgcn_ballot_w64(ev1 && end1);
+        const uint64_t below = (1ull << lane) - 1ull;
+        auto net = [](uint64_t places, uint64_t ends) -> int32_t {  // STARTs minus ENDs among `places`
+          return (int32_t)__popcll(places & ~ends) - (int32_t)__popcll(places & ends);
+        };
+        // the counts at the slab's start sit in the lane of the region
+        const int32_t at0_lo = __shfl(c_lo, (int)(r0 & 63u), 64), at0_hi = __shfl(c_hi, (int)(r0 & 63u), 64);
+        const int32_t at1_lo = __shfl(c_lo, (int)(r1 & 63u), 64), at1_hi = __shfl(c_hi, (int)(r1 & 63u), 64);
+        const int32_t before0 = (r0 < 64u ? at0_lo : at0_hi) + net(same00 & below, ends0);
+        const int32_t before1 = (r1 < 64u ? at1_lo : at1_hi) + net(same01, ends0) + net(same11 & below, ends1);
+        // the region opens (no wave had it open) or closes (the last wave that had it open)
+        const uint64_t switch0 = __builtin_amdgcn_ballot_w64(ev0 && before0 == (end0 ? 1 : 0));
+        const uint64_t switch1 = __builtin_amdgcn_ballot_w64(ev1 && before1 == (end1 ? 1 : 0));
+        // Only these events change the set of open regions; they are taken one after the other, each
+        // lane holding whether its two regions (lane, lane + 64) are open.
+        bool open_lo = c_lo > 0, open_hi = c_hi > 0;
+        auto take = [&](uint64_t todo, uint32_t low_v, uint32_t high_v) {
+          while (todo) {
+            const int src = (int)__builtin_ctzll(todo);
+            todo &= todo - 1ull;
+            const uint32_t low = (uint32_t)__builtin_amdgcn_readlane((int)low_v, src);
+            const uint32_t high = (uint32_t)__builtin_amdgcn_readlane((int)high_v, src);
+            const uint32_t r = (low >> 1) & 0x7Fu, t = (low >> 9) | (high << 23);
+            const bool is_end = (low & 1u) != 0u;
             const unsigned long long val = is_end ? (unsigned long long)t : 0ull - (unsigned long long)t;
             const uint32_t b0 = lane, b1 = lane + 64u;
-            if (b0 < R && (b0 == r || c_lo > 0)) {
+            if (b0 < R && (b0 == r || open_lo)) {
               const uint32_t a = b0 < r ? b0 : r, b = b0 < r ? r : b0;
               atomicAdd(&otri[b * (b + 1u) / 2u + a], val);
             }
-            if (b1 < R && (b1 == r || c_hi > 0)) {
+            if (b1 < R && (b1 == r || open_hi)) {
               const uint32_t a = b1 < r ? b1 : r, b = b1 < r ? r : b1;
               atomicAdd(&otri[b * (b + 1u) / 2u + a], val);
             }
+            if (b0 == r) open_lo = !is_end;
+            if (b1 == r) open_hi = !is_end;
           }
-          if (owner) {
-            if (upper) c_hi += is_end ? -1 : 1; else c_lo += is_end ? -1 : 1;
-          }
-        }
+        };
+        take(switch0, low0, high0);
+        take(switch1, low1, high1);
       }
       __syncthreads();
       if (tid < kRegStride) {
