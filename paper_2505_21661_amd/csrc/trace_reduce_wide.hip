@@ -9,21 +9,23 @@
 //      then found a range of ranks at a time from the slots the ranks belong in and the list (the
 //      later slot wins: atomic max into a rank -> slot table); a workgroup with more such records
 //      than the list holds scans all its slots for every range instead;
-//   1  pairing, a range of ranks of every wave at a time: the records of the range are put into LDS in
-//      rank order and one thread per (wave, region) walks them, which is the definition of the pairing
-//      (an END is paired iff the nearest earlier record of its wave and region is a START).  The
-//      thread keeps the region's last record and its sums in registers from range to range; a paired
-//      START and END each set their bit in a bitmap of the workgroup's ranks;
+//   1  pairing (an END is paired iff the nearest earlier record of its wave and region is a START):
+//      hardware wave w walks recorded wave w, 64 ranks at a time, one per lane; the lanes that hold a
+//      lane's region come from one ballot per bit of the region number, the last record of every region
+//      in the ranks before from a table in LDS.  Durations go to the histogram and the region's extrema
+//      in LDS and to the (workgroup, wave, region) row in HBM with atomics; a paired START and END each
+//      set their bit in a bitmap of the workgroup's ranks;
 //   2  overlap, a window of time at a time: every wave offers its next range of ranks, the window
 //      ends at the earliest last clock among the waves that have more to offer, the marked records
 //      inside the window are sorted by clock (bitonic, in LDS) and swept.  Each hardware wave sweeps a
-//      slab of the sorted events with one lane per region (two regions per lane): a first pass gives
-//      the slab's net change of the number of waves that have each region open, a prefix over the
-//      slabs the state at the slab's start.  The time two regions are both open is the sum over the
-//      ends of their common stretches minus the sum over the beginnings; a common stretch of a and b
-//      begins when one of them opens while the other is open and ends when one closes while the other
-//      is open, so every event that opens or closes a region adds its clock, signed, to the sums of
-//      that region with every open region (modulo 2^64: the total is exact).
+//      slab of the sorted events, two events per lane: LDS atomics give the slab's net change of the
+//      number of waves that have each region open, a prefix over the slabs the numbers at the slab's
+//      start, ballots over the events of a region the number right before each event.  The time two
+//      regions are both open is the sum over the ends of their common stretches minus the sum over the
+//      beginnings; a common stretch of a and b begins when one of them opens while the other is open
+//      and ends when one closes while the other is open, so every event that opens or closes a region
+//      adds its clock, signed, to the sums of that region with every open region (modulo 2^64: the
+//      total is exact).
 // Nothing but the inputs and the statistics block is touched in HBM.
 #include "kp_reduce.h"
 #include "kp_stage.h"
@@ -35,7 +37,7 @@ using namespace kp_reduce;
 constexpr int kBlock = 1024;
 constexpr uint32_t kWavesHw = kBlock / 64;
 constexpr uint32_t kK = 2048;               // records in LDS at a time: 2 per thread
-constexpr uint32_t kList = 2048;            // records outside the slot of their seq that a workgroup can list
+constexpr uint32_t kListMin = 512, kListMax = 8192;  // records outside the slot of their seq that a workgroup can list: what LDS has room for
 constexpr uint32_t kSlab = kK / kWavesHw;   // sorted events per hardware wave
 constexpr uint32_t kSeqMask = 0xFFFFFu;
 constexpr uint32_t kHistStride = 65;        // histogram rows 65 words apart: equal bins of different regions, different banks
@@ -48,15 +50,15 @@ enum { T_FIELDVALID = 0, T_DISORDER, T_OCCUPIED, T_WINNER_DISORDER, T_NONMONO, T
        T_ADVANCED, T_LISTED, T_COUNT };
 
 struct WideLds {  // byte offsets
-  uint32_t keys, table, list, bitmap, otri, hist, reg_sum, reg_max, reg_min, n_open, slab_delta, ctr, tmp, vf, pos, adv, total;
+  uint32_t keys, table, bitmap, otri, hist, reg_sum, reg_max, reg_min, n_open, slab_delta, ctr, tmp, vf, pos, adv, seen, rows, list, total;
+  uint32_t rows_in_lds, list_cap;
 };
 inline uint32_t up16(uint32_t x) { return (x + 15u) & ~15u; }
-WideLds wide_lds(uint32_t R, uint32_t nrec) {
+WideLds wide_lds(uint32_t W, uint32_t R, uint32_t nrec) {
   WideLds l;
   l.keys = 0;
   l.table = l.keys + kK * 8;
-  l.list = l.table + kK * 4;
-  l.bitmap = l.list + kList * 4;
+  l.bitmap = l.table + kK * 4;
   l.otri = up16(l.bitmap + ((nrec + 31) / 32) * 4);
   l.hist = l.otri + R * (R + 1) / 2 * 8;
   l.reg_sum = up16(l.hist + R * kHistStride * 4);
@@ -70,7 +72,16 @@ WideLds wide_lds(uint32_t R, uint32_t nrec) {
   static_assert(T_COUNT <= 16, "temporaries");
   l.pos = l.vf + 32 * 8;
   l.adv = l.pos + 16 * 4;
-  l.total = l.adv + 16 * 4;
+  l.seen = l.adv + 16 * 4;
+  l.rows = l.seen + kWavesHw * 16;
+  // what is left goes to the (wave, region) rows of the workgroup in flight, if they fit next to the
+  // smallest list, and then to the list
+  const uint32_t rows_bytes = W * R * 16;
+  l.rows_in_lds = l.rows + rows_bytes + kListMin * 8 <= kMaxLds ? 1u : 0u;
+  l.list = l.rows + (l.rows_in_lds ? rows_bytes : 0u);
+  l.list_cap = kListMin;
+  while (l.list_cap < kListMax && l.list + l.list_cap * 2 * 8 <= kMaxLds) l.list_cap *= 2;
+  l.total = l.list + l.list_cap * 8;
   return l;
 }
 
@@ -92,7 +103,9 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + p.lds.keys);
   uint32_t* table = reinterpret_cast<uint32_t*>(smem + p.lds.table);    // rank -> winning slot + 1, for the ranks in LDS
-  uint32_t* list = reinterpret_cast<uint32_t*>(smem + p.lds.list);      // wave << 20 | slot of the records outside the slot of their seq
+  // the records outside the slot of their seq: (wave << 20 | rank) << 20 | slot, sorted
+  unsigned long long* list = reinterpret_cast<unsigned long long*>(smem + p.lds.list);
+  uint32_t* rows_lds = reinterpret_cast<uint32_t*>(smem + p.lds.rows);  // {u64 sum; u32 n; u32 max} per (wave, region), if p.lds.rows_in_lds
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(smem + p.lds.bitmap);  // bit wave * cap + rank: the record is a paired START or END
   unsigned long long* otri = reinterpret_cast<unsigned long long*>(smem + p.lds.otri);  // pair (a <= b) at b (b + 1) / 2 + a
   uint32_t* hist = reinterpret_cast<uint32_t*>(smem + p.lds.hist);
@@ -106,6 +119,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
   uint2* sVF = reinterpret_cast<uint2*>(smem + p.lds.vf);               // per wave: records held, first surviving seq
   uint32_t* pos = reinterpret_cast<uint32_t*>(smem + p.lds.pos);        // per wave: first rank of the range in LDS
   uint32_t* adv = reinterpret_cast<uint32_t*>(smem + p.lds.adv);        // per wave: ranks the window took
+  uint32_t* seen_all = reinterpret_cast<uint32_t*>(smem + p.lds.seen);  // per hardware wave: the regions in its slab, one bit each
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u, hw = tid >> 6;
   const uint32_t W = p.W, R = p.R, cap = p.cap, capm = cap - 1u, cl2 = p.cap_log2, nrec = p.nrec;
@@ -118,19 +132,6 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
   for (uint32_t i = tid; i < R; i += kBlock) { reg_sum[i] = 0; reg_max[i] = 0; reg_min[i] = 0xFFFFFFFFu; }
   if (tid < 16) ctr[tid] = 0;
   __syncthreads();
-
-  // The (wave, region) walks of this thread: entry e = wave * R + region.  Consecutive entries go to
-  // different hardware waves: a walk's lane is busy at one record in R while the other lanes of its
-  // hardware wave wait, so the walks that are busy at the same time should not share one.
-  uint32_t ee[2], ew[2], er[2];
-  bool ehas[2];
-#pragma unroll
-  for (int x = 0; x < 2; ++x) {
-    ee[x] = hw + kWavesHw * (lane + 64u * x);
-    ehas[x] = ee[x] < W * R;
-    ew[x] = ehas[x] ? ee[x] / R : 0u;
-    er[x] = ee[x] - ew[x] * R;
-  }
 
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
     const uint32_t* wh = p.wg_hdrs + (size_t)32 * wg;
@@ -150,6 +151,17 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
     if (tid < T_COUNT) tmp[tid] = 0;
     if (tid < kRegStride) n_open[tid] = 0;
     for (uint32_t i = tid; i < (nrec + 31u) / 32u; i += kBlock) bitmap[i] = 0;
+    for (uint32_t e = tid; e < W * R; e += kBlock) {
+      keys[e] = 0ull;  // no last record of (wave, region) yet
+      // pass 1 adds every pair to its row with atomics: in LDS, or in the statistics block itself
+      if (p.lds.rows_in_lds) {
+        reinterpret_cast<uint4*>(rows_lds)[e] = make_uint4(0u, 0u, 0u, 0u);
+      } else {
+        uint64_t* row = p.out + SL.per + ((size_t)wg * W * R + e) * 2;
+        row[0] = 0ull; row[1] = 0ull;
+      }
+    }
+    __threadfence();
     __syncthreads();
     uint32_t held = 0, max_v = 0;
     for (uint32_t w = 0; w < W; ++w) {
@@ -178,7 +190,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
         if (good && ((rec.x ^ s) & capm) != 0u) {
           ++c_dis;
           const uint32_t at = atomicAdd(&tmp[T_LISTED], 1u);
-          if (at < kList) list[at] = ((i >> cl2) << 20) | s;
+          if (at < p.lds.list_cap) list[at] = ((unsigned long long)(((i >> cl2) << 20) | rank_of(rec, i >> cl2, s)) << 20) | s;
         }
       }
       c_field = wave_sum(c_field);
@@ -192,44 +204,64 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
     // Records that all sit in the slot of their own seq have distinct seq modulo the ring size, hence
     // distinct ranks, and rank k of a wave is in slot (first + k) mod cap.
     const bool displaced = tmp[T_DISORDER] != 0u;
-    const uint32_t n_listed = tmp[T_LISTED] <= kList ? tmp[T_LISTED] : 0xFFFFFFFFu;  // all ones: the list is not complete
-    uint32_t n_occupied = tmp[T_FIELDVALID], n_disorder = 0;
+    // A workgroup with such records: which slot holds rank k (the later slot wins) comes from the sorted
+    // list of those records, next to the slot the rank belongs in; a workgroup with more of them than the
+    // list holds scans all its slots into a rank -> slot table, a range of ranks at a time.
+    const bool listed = displaced && tmp[T_LISTED] <= p.lds.list_cap, tabled = displaced && !listed;
+    const uint32_t n_listed = listed ? tmp[T_LISTED] : 0u;
+    if (listed) {
+      // sorted (bitonic) over the smallest power of two of places that holds it
+      uint32_t n_sort = kListMin;
+      while (n_sort < n_listed) n_sort <<= 1;
+      for (uint32_t i = tid; i < n_sort; i += kBlock) {
+        if (i >= n_listed) list[i] = kNoKey;
+      }
+      __syncthreads();
+      for (uint32_t size = 2; size <= n_sort; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+          for (uint32_t i = tid; i < n_sort / 2u; i += kBlock) {
+            const uint32_t lo = ((i & ~(stride - 1u)) << 1) | (i & (stride - 1u)), hi = lo | stride;
+            const bool up = (lo & size) == 0u;
+            const unsigned long long x = list[lo], y = list[hi];
+            if ((x > y) == up) { list[lo] = y; list[hi] = x; }
+          }
+          __syncthreads();
+        }
+      }
+    }
+    // first place of the sorted list whose (wave << 20 | rank) is not below `prefix`
+    auto list_lower_bound = [&](uint32_t prefix) -> uint32_t {
+      uint32_t lo = 0, hi = n_listed;
+      while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if ((uint32_t)(list[mid] >> 20) < prefix) lo = mid + 1u; else hi = mid;
+      }
+      return lo;
+    };
 
     // The ranks pos[w] .. pos[w] + C of every wave: which slot holds each (the later slot wins).
     auto build_table = [&]() {
       __syncthreads();  // pos[] is written, the table's last readers are done
       table[tid] = 0; table[tid + kBlock] = 0;
       __syncthreads();
-      auto offer = [&](uint32_t w, uint32_t s) {
-        const uint32_t k = rank_of(recs[(size_t)w * cap + s], w, s);
-        if (k == 0xFFFFFFFFu) return;
+      for (uint32_t i = tid; i < nrec; i += kBlock) {
+        const uint32_t w = i >> cl2, s = i & capm;
+        const uint32_t k = rank_of(recs[i], w, s);
+        if (k == 0xFFFFFFFFu) continue;
         const uint32_t d = k - pos[w];
         if (d < C) atomicMax(&table[(w << rsh) + d], s + 1u);
-      };
-      if (n_listed != 0xFFFFFFFFu) {
-        // a record in the slot of its seq: rank k of a wave is in slot (first + k) mod cap; the others: listed
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const uint32_t idx = tid + x * kBlock, w = idx >> rsh;
-          if (w >= W) continue;
-          const uint2 vf = sVF[w];
-          const uint32_t k = pos[w] + (idx & (C - 1u));
-          if (k < vf.x) offer(w, (vf.y + k) & capm);
-        }
-        for (uint32_t i = tid; i < n_listed; i += kBlock) offer(list[i] >> 20, list[i] & 0xFFFFFu);
-      } else {
-        for (uint32_t i = tid; i < nrec; i += kBlock) offer(i >> cl2, i & capm);
       }
       __syncthreads();
     };
     // The record at place idx of the ranks in LDS, (wave idx >> rsh, rank pos + (idx & (C - 1))); false: none.
+    // (With a list: for workgroups in which no two records have the same rank, as pass 2 requires.)
     auto fetch = [&](uint32_t idx, uint2& rec) -> bool {
       const uint32_t w = idx >> rsh, j = idx & (C - 1u);
       if (w >= W) return false;
       const uint2 vf = sVF[w];
       const uint32_t k = pos[w] + j;
       if (k >= vf.x) return false;
-      if (displaced) {
+      if (tabled) {
         const uint32_t t = table[idx];
         if (t == 0u) return false;
         rec = recs[(size_t)w * cap + (t - 1u)];
@@ -237,10 +269,16 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
       }
       const uint32_t s = (vf.y + k) & capm;
       rec = recs[(size_t)w * cap + s];
-      return rank_of(rec, w, s) == k;
+      if (rank_of(rec, w, s) == k) return true;
+      if (!listed) return false;
+      const uint32_t at = list_lower_bound((w << 20) | k);
+      if (at >= n_listed || (uint32_t)(list[at] >> 20) != ((w << 20) | k)) return false;
+      rec = recs[(size_t)w * cap + ((uint32_t)list[at] & 0xFFFFFu)];
+      return true;
     };
 
-    if (displaced) {
+    uint32_t n_occupied = 0, n_disorder = 0;
+    if (tabled) {
       uint32_t occ = 0, dis = 0;
       for (uint32_t k0 = 0; k0 < max_v; k0 += C) {
         if (tid < 16) pos[tid] = k0;
@@ -258,92 +296,161 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
       occ = wave_sum(occ);
       dis = wave_sum(dis);
       if (lane == 0) { atomicAdd(&tmp[T_OCCUPIED], occ); atomicAdd(&tmp[T_WINNER_DISORDER], dis); }
+    }
+
+    // ---- pass 1: pairing, durations, per-(wave, region) statistics, monotonicity ---------------------
+    // Hardware wave w takes recorded wave w, 64 consecutive ranks at a time, one per lane.  The nearest
+    // earlier record of a lane's (wave, region) is the highest lower lane with the same region (the lanes
+    // with a lane's region: one ballot per bit of the region number) or, when there is none, the last
+    // record of that region in the ranks before, which the wave keeps in a table of its own.
+    {
+      uint2* last = reinterpret_cast<uint2*>(keys) + hw * R;  // per region: {clock, 1 << 31 | END << 30 | rank} of its last record
+      uint32_t n_pairs = 0, orphan_s = 0, orphan_e = 0, nonmono = 0, occupied = 0, moved = 0;  // (the same in all lanes)
+      bool carry_has = false;
+      uint32_t carry_ts = 0;  // clock of the wave's last record so far
+      const uint64_t below = (1ull << lane) - 1ull;
+      uint64_t* rows = p.out + SL.per + ((size_t)wg * W + hw) * R * 2;
+      uint32_t* rows_here = rows_lds + hw * R * 4u;
+      auto group = [&](uint32_t k, bool ok, uint2 rec) {  // this lane: rank k, its record if ok
+        const uint32_t r = (rec.x >> 24) & 0x7Fu, ts = rec.y;
+        const bool is_end = (rec.x >> 31) != 0u;
+        const uint64_t there = __builtin_amdgcn_ballot_w64(ok);
+        if (there == 0ull) return;
+        {  // clocks must not decrease from one record of the wave to the next
+          const uint64_t lower = there & below;
+          const uint32_t before = (uint32_t)__shfl((int)ts, lower ? 63 - (int)__builtin_clzll(lower) : 0, 64);
+          const bool has = lower != 0ull || carry_has;
+          nonmono += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(ok && has && ts < (lower ? before : carry_ts)));
+          carry_ts = (uint32_t)__builtin_amdgcn_readlane((int)ts, 63 - (int)__builtin_clzll(there));
+          carry_has = true;
+        }
+        uint64_t same = there;
+#pragma unroll
+        for (uint32_t b = 0; b < 7u; ++b) {
+          const uint64_t set = __builtin_amdgcn_ballot_w64(ok && ((r >> b) & 1u));
+          same &= ((r >> b) & 1u) ? set : ~set;
+        }
+        const uint64_t lower = same & below;
+        const int src = lower ? 63 - (int)__builtin_clzll(lower) : 0;
+        uint32_t pred_ts = (uint32_t)__shfl((int)ts, src, 64);
+        uint32_t pred_info = (uint32_t)__shfl((int)(0x80000000u | ((uint32_t)is_end << 30) | k), src, 64);
+        if (ok && lower == 0ull) { const uint2 c = last[r]; pred_ts = c.x; pred_info = c.y; }
+        if (ok && (same >> lane) >> 1 == 0ull) last[r] = make_uint2(ts, 0x80000000u | ((uint32_t)is_end << 30) | k);  // the region's last record here
+        const bool pred_start = ok && (pred_info >> 30) == 2u;  // there is one and it is a START
+        const bool pair = pred_start && is_end;
+        orphan_s += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(pred_start && !is_end));  // START START
+        orphan_e += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(ok && is_end && !pred_start));
+        const uint64_t pairs = __builtin_amdgcn_ballot_w64(pair);
+        n_pairs += (uint32_t)__popcll(pairs);
+        if (pair) {
+          const uint32_t d_raw = ts - pred_ts;
+          const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
+          atomicAdd(&hist[r * kHistStride + (31 - __clz(d | 1u))], 1u);
+          atomicAdd(&reg_sum[r], (unsigned long long)d);
+          atomicMax(&reg_max[r], d);
+          atomicMin(&reg_min[r], d);
+          const uint32_t b0 = hw * cap + (pred_info & kSeqMask), b1 = hw * cap + k;
+          atomicOr(&bitmap[b0 >> 5], 1u << (b0 & 31u));
+          atomicOr(&bitmap[b1 >> 5], 1u << (b1 & 31u));
+          // row {u64 sum; u32 n; u32 max}, cleared above
+          if (p.lds.rows_in_lds) {
+            uint32_t* row = rows_here + 4u * r;
+            atomicAdd(reinterpret_cast<unsigned long long*>(row), (unsigned long long)d);
+            atomicAdd(row + 2, 1u);
+            atomicMax(row + 3, d);
+          } else {
+            uint64_t* row = rows + 2u * r;
+            atomicAdd(reinterpret_cast<unsigned long long*>(row), (unsigned long long)d);
+            atomicAdd(reinterpret_cast<uint32_t*>(row) + 2, 1u);
+            atomicMax(reinterpret_cast<uint32_t*>(row) + 3, d);
+          }
+        }
+      };
+      const uint32_t V = hw < W ? sVF[hw < W ? hw : 0u].x : 0u;
+      if (!tabled) {
+        // rank k belongs in slot (first + k) mod cap; nothing is shared with the other waves
+        const uint32_t first = sVF[hw < W ? hw : 0u].y;
+        uint32_t cursor = 0, cursor_end = 0;  // this wave's stretch of the sorted list
+        if (listed && hw < W) { cursor = list_lower_bound(hw << 20); cursor_end = list_lower_bound((hw + 1u) << 20); }
+        for (uint32_t k0 = 0; k0 < V; k0 += 256u) {
+          uint2 rec[4];
+          bool ok[4];
+          uint32_t slot[4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {  // (the loads are in flight together)
+            const uint32_t k = k0 + 64u * g + lane;
+            slot[g] = (first + k) & capm;
+            rec[g] = recs[(size_t)hw * cap + (k < V ? slot[g] : 0u)];
+            ok[g] = k < V && rank_of(rec[g], hw, slot[g]) == k;
+          }
+          if (cursor < cursor_end && ((uint32_t)(list[cursor] >> 20) & kSeqMask) < k0 + 256u) {
+            // listed records whose rank is among these: a later slot displaces an earlier one
+            bool moved_here[4] = {false, false, false, false};
+            while (cursor < cursor_end) {
+              const unsigned long long key = list[cursor];
+              const uint32_t rank = (uint32_t)(key >> 20) & kSeqMask, s = (uint32_t)key & 0xFFFFFu;
+              if (rank >= k0 + 256u) break;
+              ++cursor;
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                if (rank == k0 + 64u * g + lane && (!ok[g] || s > slot[g])) { slot[g] = s; ok[g] = true; moved_here[g] = true; }
+              }
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              if (moved_here[g]) rec[g] = recs[(size_t)hw * cap + slot[g]];
+            }
+          }
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            occupied += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(ok[g]));
+            moved += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(ok[g] && ((rec[g].x ^ slot[g]) & capm) != 0u));
+            group(k0 + 64u * g + lane, ok[g], rec[g]);
+          }
+        }
+      } else {
+        for (uint32_t k0 = 0; k0 < max_v; k0 += C) {
+          if (tid < 16) pos[tid] = k0;
+          build_table();
+          for (uint32_t j0 = 0; j0 < C && k0 + j0 < V; j0 += 128u) {
+            uint2 rec[2];
+            bool ok[2];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+              const uint32_t j = j0 + 64u * g + lane, t = table[(hw << rsh) + j];
+              ok[g] = t != 0u;
+              rec[g] = recs[(size_t)hw * cap + (ok[g] ? t - 1u : 0u)];
+            }
+#pragma unroll
+            for (int g = 0; g < 2; ++g) group(k0 + j0 + 64u * g + lane, ok[g], rec[g]);
+          }
+        }
+      }
+      if (lane == 0 && hw < W) {
+        if (n_pairs) atomicAdd(&tmp[T_PAIRS], n_pairs);
+        if (orphan_s) atomicAdd(&tmp[T_ORPHAN_START], orphan_s);
+        if (orphan_e) atomicAdd(&tmp[T_ORPHAN_END], orphan_e);
+        if (nonmono) atomicAdd(&tmp[T_NONMONO], nonmono);
+        if (occupied) atomicAdd(&tmp[T_OCCUPIED], occupied);
+        if (moved) atomicAdd(&tmp[T_WINNER_DISORDER], moved);
+      }
       __syncthreads();
+      // a region whose last record is a START: that START has no END
+      uint32_t open_ended = 0;
+      for (uint32_t e = tid; e < W * R; e += kBlock) {
+        open_ended += (reinterpret_cast<const uint2*>(keys)[e].y >> 30) == 2u ? 1u : 0u;
+        if (p.lds.rows_in_lds) {
+          uint64_t* row = p.out + SL.per + ((size_t)wg * W * R + e) * 2;
+          row[0] = reinterpret_cast<const uint64_t*>(rows_lds)[2u * e];
+          row[1] = reinterpret_cast<const uint64_t*>(rows_lds)[2u * e + 1u];
+        }
+      }
+      open_ended = wave_sum(open_ended);
+      if (lane == 0 && open_ended) atomicAdd(&tmp[T_ORPHAN_START], open_ended);
       n_occupied = tmp[T_OCCUPIED];
       n_disorder = tmp[T_WINNER_DISORDER];
     }
     const uint32_t wg_invalid = held - n_occupied;  // slots that hold a record and did not make it into the ordered sequence
-
-    // ---- pass 1: pairing, durations, per-(wave, region) statistics, monotonicity ---------------------
-    {
-      bool have_prev[2] = {false, false}, prev_end[2] = {false, false};
-      uint32_t prev_ts[2] = {0, 0}, prev_k[2] = {0, 0};
-      uint32_t n[2] = {0, 0}, mx[2] = {0, 0}, mn[2] = {0xFFFFFFFFu, 0xFFFFFFFFu}, orphan_s[2] = {0, 0}, orphan_e[2] = {0, 0};
-      unsigned long long sum[2] = {0, 0};
-      bool have_any[2] = {false, false};  // (region 0's walk of a wave also checks the wave's clocks)
-      uint32_t last_ts[2] = {0, 0}, nonmono = 0;
-      for (uint32_t k0 = 0; k0 < max_v; k0 += C) {
-        __syncthreads();  // the walks over the previous range are done
-        if (tid < 16) pos[tid] = k0;
-        if (displaced) build_table(); else __syncthreads();
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const uint32_t idx = tid + x * kBlock;
-          uint2 rec = make_uint2(0u, 0u);
-          const bool ok = fetch(idx, rec);
-          // clock | 1 << 8 | END << 7 | region
-          keys[idx] = ok ? ((unsigned long long)rec.y << 32) | 0x100u | (rec.x >> 24) : 0ull;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          if (!ehas[x]) continue;
-          const uint32_t w = ew[x], V = sVF[w].x, mine = 0x100u | er[x];
-          const uint32_t nj = V > k0 ? (V - k0 < C ? V - k0 : C) : 0u;
-          const uint4* ent = reinterpret_cast<const uint4*>(keys + (w << rsh));  // two entries per load
-          // four entries per step, so that their loads are in flight together (places past the wave's last
-          // record hold no record; the range is a multiple of four long)
-          for (uint32_t j4 = 0; j4 < nj; j4 += 4u) {
-            const uint4 e01 = ent[j4 / 2u], e23 = ent[j4 / 2u + 1u];
-            const uint32_t ms[4] = {e01.x, e01.z, e23.x, e23.z}, tss[4] = {e01.y, e01.w, e23.y, e23.w};
-#pragma unroll
-            for (uint32_t u = 0; u < 4u; ++u) {
-            const uint32_t j = j4 + u, m = ms[u], ts = tss[u];
-            if (!(m & 0x100u)) continue;  // no record at this rank
-            if (er[x] == 0u) {
-              nonmono += (have_any[x] && ts < last_ts[x]) ? 1u : 0u;
-              last_ts[x] = ts; have_any[x] = true;
-            }
-            if ((m & 0x17Fu) != mine) continue;
-            const bool is_end = (m & 0x80u) != 0u;
-            if (!is_end) {
-              orphan_s[x] += (have_prev[x] && !prev_end[x]) ? 1u : 0u;  // START START
-            } else if (have_prev[x] && !prev_end[x]) {
-              const uint32_t d_raw = ts - prev_ts[x];
-              const uint32_t d = d_raw > p.rec_cost ? d_raw - p.rec_cost : 0u;
-              ++n[x]; sum[x] += d;
-              mx[x] = d > mx[x] ? d : mx[x];
-              mn[x] = d < mn[x] ? d : mn[x];
-              atomicAdd(&hist[er[x] * kHistStride + (31 - __clz(d | 1u))], 1u);
-              const uint32_t b0 = w * cap + prev_k[x], b1 = w * cap + k0 + j;
-              atomicOr(&bitmap[b0 >> 5], 1u << (b0 & 31u));
-              atomicOr(&bitmap[b1 >> 5], 1u << (b1 & 31u));
-            } else {
-              ++orphan_e[x];
-            }
-            have_prev[x] = true; prev_end[x] = is_end; prev_ts[x] = ts; prev_k[x] = k0 + j;
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        if (!ehas[x]) continue;
-        orphan_s[x] += (have_prev[x] && !prev_end[x]) ? 1u : 0u;  // START at the end of the sequence
-        uint64_t* dst = p.out + SL.per + ((size_t)wg * W * R + ee[x]) * 2;
-        dst[0] = sum[x];
-        dst[1] = (uint64_t)n[x] | ((uint64_t)mx[x] << 32);
-        if (n[x]) {
-          atomicAdd(&reg_sum[er[x]], sum[x]);
-          atomicMax(&reg_max[er[x]], mx[x]);
-          atomicMin(&reg_min[er[x]], mn[x]);
-          atomicAdd(&tmp[T_PAIRS], n[x]);
-        }
-        if (orphan_s[x]) atomicAdd(&tmp[T_ORPHAN_START], orphan_s[x]);
-        if (orphan_e[x]) atomicAdd(&tmp[T_ORPHAN_END], orphan_e[x]);
-      }
-      if (nonmono) atomicAdd(&tmp[T_NONMONO], nonmono);
-    }
     __syncthreads();
     const bool eligible = !span_overflow && wg_invalid == 0u && tmp[T_NONMONO] == 0u;
     if (tid == 0) {
@@ -369,7 +476,7 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
       __syncthreads();
       if (tid == 0) { tmp[T_WINDOW_END] = 0xFFFFFFFFu; tmp[T_ADVANCED] = 0; }
       if (tid < 16) adv[tid] = 0;
-      if (displaced) build_table(); else __syncthreads();
+      if (tabled) build_table(); else __syncthreads();
       // clock << 9 | not marked << 8 | region << 1 | END
       unsigned long long mine[2];
 #pragma unroll
@@ -466,33 +573,43 @@ __global__ __launch_bounds__(kBlock) void kp_reduce_wide(WideParams p) {
         // the region opens (no wave had it open) or closes (the last wave that had it open)
         const uint64_t switch0 = __builtin_amdgcn_ballot_w64(ev0 && before0 == (end0 ? 1 : 0));
         const uint64_t switch1 = __builtin_amdgcn_ballot_w64(ev1 && before1 == (end1 ? 1 : 0));
-        // Only these events change the set of open regions; they are taken one after the other, each
-        // lane holding whether its two regions (lane, lane + 64) are open.
-        bool open_lo = c_lo > 0, open_hi = c_hi > 0;
-        auto take = [&](uint64_t todo, uint32_t low_v, uint32_t high_v) {
-          while (todo) {
-            const int src = (int)__builtin_ctzll(todo);
-            todo &= todo - 1ull;
-            const uint32_t low = (uint32_t)__builtin_amdgcn_readlane((int)low_v, src);
-            const uint32_t high = (uint32_t)__builtin_amdgcn_readlane((int)high_v, src);
-            const uint32_t r = (low >> 1) & 0x7Fu, t = (low >> 9) | (high << 23);
-            const bool is_end = (low & 1u) != 0u;
-            const unsigned long long val = is_end ? (unsigned long long)t : 0ull - (unsigned long long)t;
-            const uint32_t b0 = lane, b1 = lane + 64u;
-            if (b0 < R && (b0 == r || open_lo)) {
-              const uint32_t a = b0 < r ? b0 : r, b = b0 < r ? r : b0;
-              atomicAdd(&otri[b * (b + 1u) / 2u + a], val);
-            }
-            if (b1 < R && (b1 == r || open_hi)) {
-              const uint32_t a = b1 < r ? b1 : r, b = b1 < r ? r : b1;
-              atomicAdd(&otri[b * (b + 1u) / 2u + a], val);
-            }
-            if (b0 == r) open_lo = !is_end;
-            if (b1 == r) open_hi = !is_end;
+        // Each of these events adds its clock, signed, to the sums of its region with every region that is
+        // open at that moment (and with itself: the time the region is open at all).  Region by region,
+        // over the regions that are open at the slab's start or occur in it: whether region b is open
+        // right before an event is again the count at the start plus the STARTs minus the ENDs of b at the
+        // places before it.
+        const bool sw0 = (switch0 >> lane) & 1ull, sw1 = (switch1 >> lane) & 1ull;
+        const uint32_t t0 = (low0 >> 9) | (high0 << 23), t1 = (low1 >> 9) | (high1 << 23);
+        const unsigned long long val0 = end0 ? (unsigned long long)t0 : 0ull - (unsigned long long)t0;
+        const unsigned long long val1 = end1 ? (unsigned long long)t1 : 0ull - (unsigned long long)t1;
+        uint32_t* seen = seen_all + hw * 4u;  // bit r: region r occurs in the slab
+        if (lane < 4u) seen[lane] = 0u;       // (LDS operations of one wave take effect in order)
+        if (ev0) atomicOr(&seen[r0 >> 5], 1u << (r0 & 31u));
+        if (ev1) atomicOr(&seen[r1 >> 5], 1u << (r1 & 31u));
+        const uint64_t starts0 = __builtin_amdgcn_ballot_w64(ev0 && !end0), starts1 = __builtin_amdgcn_ballot_w64(ev1 && !end1);
+        auto with_region = [&](uint32_t b) {  // (b is the same in all lanes)
+          const int32_t lo_c = __builtin_amdgcn_readlane(c_lo, (int)(b & 63u)), hi_c = __builtin_amdgcn_readlane(c_hi, (int)(b & 63u));
+          const int32_t base = b < 64u ? lo_c : hi_c;
+          const uint64_t is_b0 = __builtin_amdgcn_ballot_w64(ev0 && r0 == b), is_b1 = __builtin_amdgcn_ballot_w64(ev1 && r1 == b);
+          const uint64_t s0 = is_b0 & starts0, e0 = is_b0 & ends0, s1 = is_b1 & starts1, e1 = is_b1 & ends1;
+          const int32_t all0 = (int32_t)__popcll(s0) - (int32_t)__popcll(e0);
+          const int32_t cnt0 = base + (int32_t)__popcll(s0 & below) - (int32_t)__popcll(e0 & below);
+          const int32_t cnt1 = base + all0 + (int32_t)__popcll(s1 & below) - (int32_t)__popcll(e1 & below);
+          if (sw0 && (r0 == b || cnt0 > 0)) {
+            const uint32_t lo_r = r0 < b ? r0 : b, hi_r = r0 < b ? b : r0;
+            atomicAdd(&otri[hi_r * (hi_r + 1u) / 2u + lo_r], val0);
+          }
+          if (sw1 && (r1 == b || cnt1 > 0)) {
+            const uint32_t lo_r = r1 < b ? r1 : b, hi_r = r1 < b ? b : r1;
+            atomicAdd(&otri[hi_r * (hi_r + 1u) / 2u + lo_r], val1);
           }
         };
-        take(switch0, low0, high0);
-        take(switch1, low1, high1);
+        const uint32_t seen0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen[0]), seen1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen[1]);
+        const uint32_t seen2 = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen[2]), seen3 = (uint32_t)__builtin_amdgcn_readfirstlane((int)seen[3]);
+        for (uint64_t todo = __builtin_amdgcn_ballot_w64(c_lo > 0) | seen0 | ((uint64_t)seen1 << 32); todo; todo &= todo - 1ull)
+          with_region((uint32_t)__builtin_ctzll(todo));
+        for (uint64_t todo = __builtin_amdgcn_ballot_w64(c_hi > 0) | seen2 | ((uint64_t)seen3 << 32); todo; todo &= todo - 1ull)
+          with_region(64u + (uint32_t)__builtin_ctzll(todo));
       }
       __syncthreads();
       if (tid < kRegStride) {
@@ -531,7 +648,7 @@ namespace kp_reduce {
 
 kp_status wide_supported(const kp_trace_hdr& h) {
   const uint32_t nrec = h.waves_per_wg * h.cap_wave;
-  const uint32_t need = wide_lds(h.n_regions, nrec).total;
+  const uint32_t need = wide_lds(h.waves_per_wg, h.n_regions, nrec).total;
   if (need > kMaxLds)
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE,
                     "%u record slots per workgroup with %u regions: the decoder needs %u B of LDS (limit %u)", nrec,
@@ -553,7 +670,7 @@ kp_status launch_wide(const uint32_t* wg_hdrs, const void* records, uint64_t* ou
   p.nrec = p.W * p.cap;
   uint32_t wl2 = 0; while ((1u << wl2) < p.W) ++wl2;
   p.range_log2 = 11u - wl2;  // kK = 2^11 places
-  p.lds = wide_lds(p.R, p.nrec);
+  p.lds = wide_lds(p.W, p.R, p.nrec);
   static thread_local kp_stage::LaunchCache cache;
   uint32_t grid = 0;
   const kp_status st = kp_stage::resident_grid(kp_reduce_wide, kBlock, p.lds.total, &cache, &grid);

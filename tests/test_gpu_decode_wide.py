@@ -89,6 +89,17 @@ def test_generated_traces(kp, oracle_mod, W, R, cap, total):
     assert st["n_pairs"] > 0 and st["n_overlap_wgs"] > 0
 
 
+@pytest.mark.parametrize("W,R,cap,p_swap", [(16, 8, 4096, 0.2), (16, 128, 1024, 0.15), (3, 40, 16384, 0.3), (8, 16, 8192, 0.004)])
+def test_heavily_shuffled_rings(kp, oracle_mod, W, R, cap, p_swap):
+    """So many records outside the slot of their sequence number that the kernel's list of them overflows
+    (it then scans all slots for every range of ranks), and, in the last case, a list that is nearly full."""
+    spec = inputs.TraceSpec(n_wg=4, waves=W, n_regions=R, cap_wave=cap, total_per_wave=cap + cap // 2, total_var=cap // 4,
+                            seed=W + R, dist="lognormal", p0=4.0, p1=1.0, p_orphan=0.02, p_swap=p_swap, swap_max=40)
+    raw, _ = inputs.gen_trace(spec)
+    st = check(raw, oracle_mod)
+    assert st["n_disorder"] > 0.5 * p_swap * st["n_slots_valid"] and st["n_overlap_wgs"] > 0
+
+
 def test_clean_generated_trace_all_workgroups_in_the_overlap(kp, oracle_mod):
     spec = inputs.TraceSpec(n_wg=300, waves=16, n_regions=48, cap_wave=512, total_per_wave=512, total_var=60, seed=77,
                             dist="lognormal", p0=4.5, p1=0.8)
