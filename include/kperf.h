@@ -156,6 +156,15 @@ kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_trace_hdr* hdr
                               void* out_stats, void* stream);
 
 /*
+ * Timing aid: kp_trace_reduce_hdr that also records two events of the caller's (hipEvent_t handles,
+ * created with timing enabled; either may be NULL) on `stream`: main_begin after the kernel that
+ * clears the block, right before the kernel that does the replay of Sec. 4.3, main_end right after it,
+ * before the kernel that derives O and F from the sums.  Their distance is that one kernel's run time.
+ */
+kp_status kp_trace_reduce_hdr_events(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                                     void* out_stats, void* stream, void* main_begin, void* main_end);
+
+/*
  * Timing aid for the decoder: kp_trace_reduce_hdr cut short.  Every recorded workgroup leaves the
  * kernel after step `last_step` of the replay (Sec. 4.3): 1 records ordered by sequence number,
  * 2 paired, durations and histogram accumulated; then the paired records of all waves are sorted

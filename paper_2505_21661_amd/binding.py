@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.kp_trace_reduce.argtypes = [vp, sz, vp, vp]
         L.kp_trace_reduce_hdr.restype = ci
         L.kp_trace_reduce_hdr.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp]
+        L.kp_trace_reduce_hdr_events.restype = ci
+        L.kp_trace_reduce_hdr_events.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, vp, vp, vp]
         L.kp_trace_reduce_steps.restype = ci
         L.kp_trace_reduce_steps.argtypes = [vp, sz, ctypes.POINTER(kp_trace_hdr), vp, ci, vp]
         L.kp_pairs_bytes.restype = sz
@@ -183,6 +185,20 @@ def make_hdr(n_wg: int, waves_per_wg: int, n_regions: int, cap_wave: int, rec_co
 
 def kp_trace_reduce_hdr(raw, n: int, hdr_host: kp_trace_hdr, out_stats, stream=None) -> None:
     _check(lib().kp_trace_reduce_hdr(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_stats), _stream(stream)))
+
+
+def kp_trace_reduce_hdr_events(raw, n: int, hdr_host: kp_trace_hdr, out_stats, main_begin, main_end, stream=None) -> None:
+    """main_begin, main_end: torch.cuda.Event objects with timing enabled that have been recorded before (an
+    event's handle exists from its first record on), raw hipEvent_t handles as int, or None."""
+    def handle(ev):
+        if ev is None or isinstance(ev, int):
+            return ev
+        h = ev.cuda_event
+        if not h:
+            raise ValueError("record the event once before passing it: it has no handle yet")
+        return h
+    _check(lib().kp_trace_reduce_hdr_events(_ptr(raw), n, ctypes.byref(hdr_host), _ptr(out_stats), _stream(stream),
+                                            handle(main_begin), handle(main_end)))
 
 
 def kp_trace_reduce_steps(raw, n: int, hdr_host: kp_trace_hdr, out_stats, last_step: int, stream=None) -> None:

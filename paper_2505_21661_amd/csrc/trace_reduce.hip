@@ -1217,7 +1217,7 @@ kp_status launch_planes(const DecodeParams& p, hipStream_t s) {
 }
 
 kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* out_stats, uint32_t stop_after,
-                      hipStream_t s) {
+                      hipStream_t s, hipEvent_t main_begin = nullptr, hipEvent_t main_end = nullptr) {
   if (h.magic != KP_TRACE_MAGIC || h.version != KP_TRACE_VERSION)
     return kp::fail(KP_ERR_BAD_TRACE, "trace header: bad magic/version (%08x, %u)", h.magic, h.version);
   if (h.waves_per_wg < 1 || h.waves_per_wg > KP_MAX_WAVES || h.n_regions < 1 || !kp::is_pow2(h.cap_wave))
@@ -1257,6 +1257,7 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
                      reinterpret_cast<const uint32_t*>(base), out, h.n_wg, W, R, cap, h.flags);
   KP_HIP_TRY(hipGetLastError());
 
+  if (main_begin) KP_HIP_TRY(hipEventRecord(main_begin, s));
   if (h.n_wg > 0 && wide) {
     const kp_status st = launch_wide(reinterpret_cast<const uint32_t*>(base + sizeof(kp_trace_hdr)),
                                      base + sizeof(kp_trace_hdr) + sizeof(kp_wg_hdr) * (size_t)h.n_wg, out, h, s);
@@ -1275,6 +1276,7 @@ kp_status reduce_impl(const void* raw, size_t n, const kp_trace_hdr& h, void* ou
                                        : launch_planes<64>(p, s);
     if (st != KP_OK) return st;
   }
+  if (main_end) KP_HIP_TRY(hipEventRecord(main_end, s));
   hipLaunchKernelGGL(kp_reduce_finalize, dim3(1), dim3(256), 0, s, out, h.n_wg, W, R);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
@@ -1287,6 +1289,14 @@ extern "C" kp_status kp_trace_reduce_hdr(const void* raw, size_t n, const kp_tra
   kp::clear_error();
   if (!raw || !hdr_host || !out_stats) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
   return reduce_impl(raw, n, *hdr_host, out_stats, 0u, static_cast<hipStream_t>(stream));
+}
+
+extern "C" kp_status kp_trace_reduce_hdr_events(const void* raw, size_t n, const kp_trace_hdr* hdr_host,
+                                                void* out_stats, void* stream, void* main_begin, void* main_end) {
+  kp::clear_error();
+  if (!raw || !hdr_host || !out_stats) return kp::fail(KP_ERR_INVALID_ARG, "NULL argument");
+  return reduce_impl(raw, n, *hdr_host, out_stats, 0u, static_cast<hipStream_t>(stream),
+                     static_cast<hipEvent_t>(main_begin), static_cast<hipEvent_t>(main_end));
 }
 
 extern "C" kp_status kp_trace_reduce_steps(const void* raw, size_t n, const kp_trace_hdr* hdr_host,

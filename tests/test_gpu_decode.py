@@ -180,3 +180,29 @@ def test_decode_workload_full_size(kp, oracle_mod):
     assert np.array_equal(want_stages, stages.cpu().numpy())
     del want_rows, got_rows, want_stages
     assert np.array_equal(oracle_mod.waits_raw(raw), waits.cpu().numpy())
+
+
+def test_events_around_the_main_kernel(kp, oracle_mod):
+    """kp_trace_reduce_hdr_events: the same statistics, and two events of the caller's recorded around the
+    replay kernel (their distance is below that of events around the whole call)."""
+    from tests.gpu_util import assert_stats_equal
+
+    raw, _ = inputs.gen_trace(inputs.spec_decode_standalone(20))
+    n_wg, W, R, cap = (int(x) for x in raw[2:6])
+    dev = torch.from_numpy(raw.view(np.int32)).cuda()
+    out = torch.full((kp.kp_stats_bytes(n_wg, W, R),), 0x5A, dtype=torch.uint8, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in ev:
+        e.record()
+    torch.cuda.synchronize()
+    hdr = kp.make_hdr(n_wg, W, R, cap)
+    ev[0].record()
+    kp.kp_trace_reduce_hdr_events(dev, n_wg * W * cap, hdr, out, ev[1], ev[2])
+    ev[3].record()
+    torch.cuda.synchronize()
+    assert_stats_equal(oracle_mod.decode_bytes(raw, 8), out.cpu().numpy(), oracle_mod)
+    assert 0.0 < ev[1].elapsed_time(ev[2]) <= ev[0].elapsed_time(ev[3])
+    kp.kp_trace_reduce_hdr_events(dev, n_wg * W * cap, hdr, out, None, None)   # events are optional
+    torch.cuda.synchronize()
+    with pytest.raises(ValueError):
+        kp.kp_trace_reduce_hdr_events(dev, n_wg * W * cap, hdr, out, torch.cuda.Event(enable_timing=True), None)
