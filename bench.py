@@ -40,12 +40,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1079943.2 * 2.0 + 61288.7) * 1024,
-    "gemm_vanilla": (98362.0 * 2.0 + 32822.8) * 1024,
-    "attn_vanilla": (196743.1 * 2.0 + 131076.3) * 1024,
-    "timeline_2^28": (1057669.4 * 2.0 + 2085621.6) * 1024,
-    "waits_2^28": (1057609.0 * 2.0 + 33216.0) * 1024,
-    "stages_2^28": (1043564.3 * 2.0 + 273224.0) * 1024,
+    "decode_2^28": (1079756.0 * 2.0 + 37816.8) * 1024,
+    "gemm_vanilla": (98362.0 * 2.0 + 32778.8) * 1024,
+    "attn_vanilla": (196738.3 * 2.0 + 131073.6) * 1024,
+    "timeline_2^28": (1058364.5 * 2.0 + 2086381.4) * 1024,
+    "waits_2^28": (1057362.6 * 2.0 + 33216.0) * 1024,
+    "stages_2^28": (1043573.1 * 2.0 + 274514.5) * 1024,
     "critical_2^28": (132126.5 * 2.0 + 992.0) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
