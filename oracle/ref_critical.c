@@ -6,9 +6,9 @@
  *
  * The paper reads the critical path of a warp-specialised kernel off its timeline: a chain of stages
  * in different warp groups, each of which could only start once the one before it had finished
- * (Sec. 3.3 "Critical-path Analysis"; Sec. 5.2: "the critical path consisting of 4 GEMMs and 2 loading
- * stages", a stage "blocked by" another one), and models the kernel's latency as the sum of the
- * latencies of the stages on it (Table 4, WS model).  It gives no algorithm.  This project's reading,
+ * (Sec. 3.3, critical-path analysis; in the case study of Sec. 5.2 the path is made of GEMM and loading
+ * stages, one blocking the next), and models the kernel's latency as the sum of the latencies of the
+ * stages on it (Table 4, WS model).  It gives no algorithm.  This project's reading,
  * on the stage table (one entry {max_dur, min_start, max_end, n_waves} per workgroup, region and
  * iteration; an entry with n_waves = 0 is no stage):
  *   - the stages of a workgroup are ordered by (max_end, region * max_iter + iteration);
