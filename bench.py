@@ -316,7 +316,7 @@ def main() -> int:
     # statistics decoder takes 1.78 ms in a step without the dense kernels, 1.89 ms right behind them and
     # 1.82 ms as the last leg of the step, behind the other four trace kernels, where it runs here.
     names = ["gemm_warm", "gemm_vanilla", "gemm_instr", "gemm_instr2", "gemm_vanilla2", "gemm_reduce",
-             "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm_masked", "gemm_collab", "gemm_realtime",
+             "gemm5_unfenced", "gemm5_vanilla", "gemm5_instr", "gemm5_instr2", "gemm5_vanilla2", "gemm5_unfenced2", "gemm_masked", "gemm_collab", "gemm_realtime",
              "gemm_realtime2", "gemm_collab2", "gemm_masked2",
              "attn_warm", "attn_vanilla", "attn_instr", "attn_instr2", "attn_vanilla2", "attn_reduce",
              "timeline", "waits", "stages", "critical", "decode"]
@@ -325,6 +325,7 @@ def main() -> int:
         gemm_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0, None, 0)
         gemm_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1111, g_trace, g_cap)
         gemm5_v = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, kp.KP_MASK_PHASES, None, 0)
+        gemm5_u = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, kp.KP_MASK_PHASES | kp.KP_MASK_UNFENCED, None, 0)
         gemm5_i = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b11111 | kp.KP_MASK_PHASES, g_trace, g_cap)
         gemm_m = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011, g_trace, g_cap)
         gemm_c = lambda: kp.kp_gemm_instrumented(A, Bm, C, M, N, K, 0b1011 | kp.KP_MASK_COLLAB, g_trace, g_cap)
@@ -334,7 +335,7 @@ def main() -> int:
         calls = (
             gemm_v, gemm_v, gemm_i, gemm_i, gemm_v,
             lambda: kp.kp_trace_reduce_hdr(g_trace, g_wg * g_cap, g_hdr, g_stats),
-            gemm5_v, gemm5_i, gemm5_i, gemm5_v, gemm_m, gemm_c, gemm_r, gemm_r, gemm_c, gemm_m,
+            gemm5_u, gemm5_v, gemm5_i, gemm5_i, gemm5_v, gemm5_u, gemm_m, gemm_c, gemm_r, gemm_r, gemm_c, gemm_m,
             attn_v, attn_v, attn_i, attn_i, attn_v,
             lambda: kp.kp_trace_reduce_hdr(a_trace, a_wg * a_cap, a_hdr, a_stats),
             lambda: kp.kp_trace_pairs_hdr(d_raw, d_n, d_hdr, d_pairs),
@@ -382,7 +383,7 @@ def main() -> int:
     tf_ins = gemm_flop / ms["gemm_instr"] / 1e9
     overhead = (ms["gemm_instr"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
     overhead5 = (ms["gemm5_instr"] - ms["gemm5_vanilla"]) / ms["gemm5_vanilla"] * 100.0
-    for leg in ("gemm_masked", "gemm_collab", "gemm_realtime"):
+    for leg in ("gemm_masked", "gemm_collab", "gemm_realtime", "gemm5_unfenced"):
         ms[leg] = 0.5 * (ms[leg] + ms.pop(leg + "2"))
     overhead_masked = (ms["gemm_masked"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0
     attn_tf_van = attn_flop / ms["attn_vanilla"] / 1e9
@@ -467,9 +468,13 @@ def main() -> int:
         "overhead_pct_stage_by_stage": {
             "value": round(overhead5, 3),
             "what": "K step with its stages one after the other, 5 regions (load issue, wait, LDS write, MFMA, "
-                    "epilogue), 514 records per wave; against the same schedule without record sites",
+                    "epilogue), 514 records per wave; against the same schedule without record sites, i.e. with a "
+                    "bare scheduling fence wherever the instrumented kernel has a site (a site pins its place in the "
+                    "instruction stream; without the fences the compiler threads the stages through one another again)",
             "uninstrumented_tflops": round(gemm_flop / ms["gemm5_vanilla"] / 1e9, 2),
             "instrumented_tflops": round(gemm_flop / ms["gemm5_instr"] / 1e9, 2),
+            "unfenced_uninstrumented_tflops": round(gemm_flop / ms["gemm5_unfenced"] / 1e9, 2),
+            "overhead_pct_against_unfenced": round((ms["gemm5_instr"] - ms["gemm5_unfenced"]) / ms["gemm5_unfenced"] * 100.0, 3),
         },
         "overhead_pct_generic_sites": {
             "value": round(overhead_masked, 3),

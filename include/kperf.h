@@ -306,7 +306,7 @@ kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int ma
 
 /* ---- instrumented targets ---------------------------------------------------------------------
  *
- * region_mask: bit r (r < 27) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
+ * region_mask: bit r (r < 26) enables the record sites of region r; bit 31 (KP_MASK_FLUSH)
  * selects the flush strategy instead of the default circular one (Sec. 4.2: "Circular" keeps
  * the newest records in LDS and copies them out once at kernel exit; "Flush" writes a full
  * LDS sub-ring back to HBM whenever it fills up).  region_mask with bits 0..26 all zero
@@ -342,6 +342,7 @@ kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int ma
 #define KP_MASK_PHASES 0x20000000u
 #define KP_MASK_REALTIME 0x10000000u
 #define KP_MASK_COLLAB 0x08000000u
+#define KP_MASK_UNFENCED 0x04000000u
 
 /* Launch geometry kp_gemm_instrumented will use for M x N x K: recorded workgroups, waves per
  * workgroup, number of regions.  KP_ERR_UNSUPPORTED_SHAPE if no kernel covers the shape. */
@@ -355,15 +356,19 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  *   M, N multiples of 256 with at least 16 tiles, K a multiple of 64: tile 256x256x64, 8 waves,
  *       per K-step, in this order: 0 first half of the MFMA steps, with the A share of the next
  *       K-step's staging (registers -> other LDS stage, refill from global memory) threaded between
- *       them, 1 second half with the B share, 2 wait (LDS writes landed + barrier; with every region
- *       enabled and the circular strategy also the ~30 instructions that turn the K-step's three clock
- *       samples into records); 3 epilogue, once
+ *       them, 1 second half with the B share and the wait for this wave's LDS writes, 2 barrier (with
+ *       every region enabled and the circular strategy also the ~30 instructions that turn the K-step's
+ *       three clock samples into records); 3 epilogue, once
  *       With bit 29 of region_mask (KP_MASK_PHASES; this tile only, KP_ERR_INVALID_ARG otherwise) the
  *       stages of a K-step follow one another instead of being threaded into each other, and each is a
  *       region (5 regions, kp_trace_hdr.n_regions = 5; 4 sites and 8 records per K-step and wave):
  *       2 LDS write (the staging registers of the next K-step go to the other LDS stage), 0 global load
  *       issue (for the K-step after that), 3 MFMA, 1 wait (LDS traffic landed + barrier); 4 epilogue,
- *       once.  KP_MASK_PHASES with bits 0..4 all zero runs that schedule without record sites.
+ *       once.  KP_MASK_PHASES with bits 0..4 all zero runs that schedule without record sites: a record
+ *       site keeps its place in the instruction stream, so where the instrumented kernel has a site
+ *       this one has a bare scheduling fence and the stages stay apart; with bit 26 (KP_MASK_UNFENCED)
+ *       as well the fences are left out and the compiler threads the stages as it likes (for the
+ *       comparison of the two; KP_ERR_INVALID_ARG with any region bit or without KP_MASK_PHASES).
  *   otherwise M, N multiples of 64 and K of 32: tile 64x64x32, 4 waves,
  *       0 global load, 1 LDS store, 2 MFMA (each once per K-step)
  * Other shapes: KP_ERR_UNSUPPORTED_SHAPE.

@@ -26,6 +26,7 @@ KP_MASK_WAVE_GROUP = 1 << 30  # one record stream per group of four waves
 KP_MASK_PHASES = 1 << 29      # 256x256x64 GEMM: the stages of a K step one after the other, 5 regions
 KP_MASK_REALTIME = 1 << 28    # records carry the constant-rate 100 MHz clock
 KP_MASK_COLLAB = 1 << 27      # all lanes store a record; hardware ids of the waves in the workgroup header
+KP_MASK_UNFENCED = 1 << 26    # with KP_MASK_PHASES and no region: the staged K step without scheduling fences
 KP_FLAG_REALTIME = 2
 KP_FLAG_HW_IDS = 4
 

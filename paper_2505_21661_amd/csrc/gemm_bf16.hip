@@ -180,8 +180,12 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64;
 constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // both stages
 
-template <int INSTR, int WAVES, bool PHASED>
+template <int INSTR, int WAVES, int SCHEDULE>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
+  // SCHEDULE 0: staging threaded through the MFMAs; 1: the stages of a K step one after the other; 2: the
+  // same source without the scheduling fences between the stages (uninstrumented only)
+  constexpr bool PHASED = SCHEDULE != 0;
+  static_assert(SCHEDULE != 2 || INSTR == 0, "the unfenced stage-by-stage form has no record sites");
   constexpr int SITE = INSTR == 2 ? 4 : INSTR;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
@@ -342,9 +346,14 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
         }
       }
     }
+    // The clock read of a site counts in the same counter as LDS traffic, so a read issued in front of
+    // "wait for LDS, then barrier" would be waited for in full.  The wait for this wave's LDS writes
+    // therefore comes first, then the site, then the barrier: the read returns while the wave waits for
+    // the others, and the commit behind the barrier waits for it.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     KP_SITE_K(ring, 2, 1, 2);
-    // ---- region 2: this wave's LDS writes have landed, every wave is done with the stage ---------
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // ---- region 2: every wave is done with the stage ----------------------------------------------
+    asm volatile("s_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
     KP_COMMIT(ring, 3);  // the site that opened this K step, the one in its middle and the one above
     if constexpr (MORE) KP_SITE_K(ring, 0, 2, 0); else KP_SITE_K(ring, 0, 2, 3);
   };
@@ -352,6 +361,12 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // instrumentation of a software-pipelined GEMM, Sec. 5.3): 2 the staging registers (K step kt+1) go to
   // the other LDS stage, 0 the global loads of K step kt+2 are issued, 3 the MFMAs of K step kt, 1 the
   // wait for this wave's LDS traffic and for the other waves.  Four sites and eight records per K step.
+  // A record site pins its place in the instruction stream (it is a scheduling fence: nothing moves across
+  // the clock read).  Without sites the compiler would be free to thread the stages through one another
+  // again, and "the same schedule without record sites" would be another, faster schedule (measured: 135.5
+  // against 140 us): so the uninstrumented form has a bare scheduling fence wherever the instrumented one
+  // has a site.  SCHEDULE 2 leaves them out, for that comparison.
+  auto stage_fence = [] { if constexpr (INSTR == 0 && SCHEDULE == 1) __builtin_amdgcn_sched_barrier(0); };
   auto iteration_phased = [&](uint32_t kt, auto more_c, auto more2_c) {
     constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
     const uint32_t stage = kt & 1u;
@@ -364,6 +379,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       for (int i = 0; i < 4 * NB; ++i) store_b(stage ^ 1u, i >> 2, i & 3);
     }
     KP_SITE_K(ring, 1, 2, 0);
+    stage_fence();
     if constexpr (MORE2) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) load_a(kt + 2, i);
@@ -371,6 +387,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       for (int i = 0; i < 4 * NB; ++i) load_b(kt + 2, i >> 2, i & 3);
     }
     KP_SITE_K(ring, 2, 0, 3);
+    stage_fence();
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const uint32_t chunk = ks * 2 + (lane >> 5);
@@ -387,10 +404,13 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
         for (int tm = 0; tm < 4; ++tm)
           acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // (nothing of this wave's is in flight any more: see above)
     KP_SITE_K(ring, 3, 3, 1);
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    stage_fence();
+    asm volatile("s_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
     KP_COMMIT(ring, 4);
     if constexpr (MORE) KP_SITE_K(ring, 0, 1, 2); else KP_SITE_K(ring, 0, 1, 4);
+    stage_fence();
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
@@ -453,25 +473,25 @@ bool pick_shape(int M, int N, int K, GemmShape* s) {
   return false;
 }
 
-template <int INSTR, int WAVES, bool PHASED>
+template <int INSTR, int WAVES, int SCHEDULE>
 kp_status launch_big(const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
   static thread_local int attr_dev = -1;  // the attribute is kept per device
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
   if (attr_dev != dev) {
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES, PHASED>),
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_gemm_big<INSTR, WAVES, SCHEDULE>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_dev = dev;
   }
-  hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES, PHASED>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
+  hipLaunchKernelGGL((kp_gemm_big<INSTR, WAVES, SCHEDULE>), dim3(n_wg), dim3(WAVES * 64), kBigTileBytes + ring_bytes, st, g);
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }
 
 template <int INSTR>
 kp_status launch_big_w(bool phased, const GemmArgs& g, int n_wg, size_t ring_bytes, hipStream_t st) {
-  return phased ? launch_big<INSTR, kBigWaves, true>(g, n_wg, ring_bytes, st)
-                : launch_big<INSTR, kBigWaves, false>(g, n_wg, ring_bytes, st);
+  return phased ? launch_big<INSTR, kBigWaves, 1>(g, n_wg, ring_bytes, st)
+                : launch_big<INSTR, kBigWaves, 0>(g, n_wg, ring_bytes, st);
 }
 
 }  // namespace
@@ -496,13 +516,16 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   if (!pick_shape(M, N, K, &s))
     return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "GEMM %dx%dx%d: M,N must be multiples of 64 and K of 32", M, N, K);
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) return kp::fail(KP_ERR_INVALID_ARG, "A, B, C must be 16-byte aligned");
-  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_PHASES | KP_MASK_REALTIME | KP_MASK_COLLAB);
+  const uint32_t regions = region_mask & ~(KP_MASK_FLUSH | KP_MASK_WAVE_GROUP | KP_MASK_PHASES | KP_MASK_REALTIME | KP_MASK_COLLAB | KP_MASK_UNFENCED);
+  const bool unfenced = (region_mask & KP_MASK_UNFENCED) != 0u;
   const bool realtime = (region_mask & KP_MASK_REALTIME) != 0u, collab = (region_mask & KP_MASK_COLLAB) != 0u;
   const bool phased = (region_mask & KP_MASK_PHASES) != 0u;
   if (phased) {
     if (s.bm != 256) return kp::fail(KP_ERR_INVALID_ARG, "KP_MASK_PHASES: only the 256x256x64 kernel has the stage-by-stage K step");
     s.regions = 5;
   }
+  if (unfenced && (!phased || regions != 0u))
+    return kp::fail(KP_ERR_INVALID_ARG, "KP_MASK_UNFENCED goes with KP_MASK_PHASES and no region");
   const uint32_t flush = region_mask >> 31;
   const uint32_t group_log2 = (region_mask & KP_MASK_WAVE_GROUP) ? 2u : 0u;
   const int streams = s.waves >> group_log2;
@@ -517,6 +540,7 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.flags = (flush ? KP_FLAG_FLUSH : 0u) | (realtime ? KP_FLAG_REALTIME : 0u) | (collab ? KP_FLAG_HW_IDS : 0u);
   const bool big = s.bm == 256;
   if (regions == 0) {  // uninstrumented baseline: no ring, no record sites
+    if (big && unfenced) return launch_big<0, kBigWaves, 2>(g, n_wg, 0, st);
     if (big) return launch_big_w<0>(phased, g, n_wg, 0, st);
     hipLaunchKernelGGL(kp_gemm_small<0>, dim3(n_wg), dim3(256), 0, st, g);
     KP_HIP_TRY(hipGetLastError());

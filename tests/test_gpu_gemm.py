@@ -345,6 +345,8 @@ def test_stage_by_stage_regions(kp, oracle_mod, shape):
     c_ref, _, _ = run_gemm(kp, a, b, 0)
     c_van, _, _ = run_gemm_phased(kp, a, b, 0)
     assert torch.equal(c_van.view(torch.int16), c_ref.view(torch.int16))
+    c_loose, _, _ = run_gemm_phased(kp, a, b, 0, extra=kp.KP_MASK_UNFENCED)   # the same source without scheduling fences
+    assert torch.equal(c_loose.view(torch.int16), c_ref.view(torch.int16))
     c_ins, trace, (n_wg, waves, R) = run_gemm_phased(kp, a, b, 0b11111, trace_cap=4096)
     assert torch.equal(c_ins.view(torch.int16), c_ref.view(torch.int16))
     raw = trace.cpu().numpy().view(np.uint32).copy()
@@ -388,6 +390,15 @@ def test_stage_by_stage_needs_the_large_tile(kp):
     n_wg, waves, _ = kp.kp_gemm_launch_shape(1024, 1024, 256)
     with pytest.raises(kp.KperfError) as e:
         run_gemm_phased(kp, a, b, 0b100000, trace_cap=4096)   # region 5 does not exist
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    # the unfenced form exists without record sites only, and only of the staged schedule
+    with pytest.raises(kp.KperfError) as e:
+        run_gemm_phased(kp, a, b, 0b11111, trace_cap=4096, extra=kp.KP_MASK_UNFENCED)
+    assert e.value.status == kp.KP_ERR_INVALID_ARG
+    A, B = a.cuda(), b.cuda()
+    with pytest.raises(kp.KperfError) as e:
+        kp.kp_gemm_instrumented(A, B, torch.empty(1024, 1024, dtype=torch.bfloat16, device="cuda"), 1024, 1024, 256,
+                                kp.KP_MASK_UNFENCED, None, 0)
     assert e.value.status == kp.KP_ERR_INVALID_ARG
 
 
