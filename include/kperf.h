@@ -387,8 +387,9 @@ kp_status kp_attn_launch_shape(int B, int H, int S, int D, int* n_wg, int* waves
  * The paper's flash-attention study times the two GEMMs and the softmax of every KV iteration
  * (Sec. 5.2, Table 3); the regions here, once per KV tile of 64 keys, are
  *   0 Q K^T (MFMA), 1 online softmax, 2 P V (MFMA);
- * END of region 2 and START of region 0 of the next tile share one clock sample taken before the
- * barrier between the tiles, so from the second tile on region 0 begins with the wait for its K tile.
+ * END of region 2 and START of region 0 of the next tile share one clock sample.  The samples that
+ * close regions 0 and 2 are taken right behind the workgroup barrier that follows the region's work, so
+ * the wait at that barrier belongs to the region that ends there.
  * One workgroup (4 waves) handles 128 query rows; with causal masking block q records
  * 6 * 2 * (q + 1) times per wave.  region_mask, trace_buf, trace_cap as for the GEMM.
  */
