@@ -462,7 +462,7 @@ def main() -> int:
             "workload": "instrumented bf16 GEMM M=N=K=4096 (256x256x64 tiles, 4 regions, ring 4096 rec/WG) "
                         "+ causal attention 4x32x4096x128 (3 regions, ring 1024 rec/WG) "
                         f"+ trace decode of 2^{args.log2_records} synthetic records (16384 WG x 8 waves x 16 regions at 2^28)",
-            "decode_entry_point": "kp_trace_reduce_hdr",
+            "decode_entry_point": "kp_trace_reduce_hdr_events",
         },
         "overhead_pct": round(overhead, 3),
         "overhead_pct_stage_by_stage": {
