@@ -5,8 +5,8 @@
  * the HIP library.  Only tests, the smoke check and the benchmark's cpu_baseline leg may call it.
  *
  * The paper decodes the raw profile buffer into one C struct per timed region instance, which
- * front ends turn into a timeline (Sec. 3.2 "decoded into a similar format to the CUPTI Activity
- * API", Chrome Trace), and associates loop iterations with the records for its iteration-based
+ * front ends turn into a timeline (Sec. 3.2: activity structs in the manner of the vendor's activity
+ * API, Chrome Trace), and associates loop iterations with the records for its iteration-based
  * timing use case (Sec. 3.3 "Iteration-based Timing").  It stores START/END records unpaired and
  * aligns them at replay (Sec. 4.2); a constant record overhead is subtracted (Sec. 4.3).
  * The row layout, the order of the rows and the iteration index are this project's reading:
