@@ -192,8 +192,10 @@ kp_status kp_trace_reduce_steps(const void* raw, size_t n, const kp_trace_hdr* h
  *   u32 count[n_wg * waves_per_wg], padded with zeros to a multiple of 4 entries, then
  *   kp_pair_row rows[n_wg * waves_per_wg][cap_wave / 2]; the rows of a wave are ordered by their END
  *   records and only the first count[wg * waves_per_wg + wave] of them are written.
- * Arguments, synchronisation, limits (n_regions <= 128 here) and errors as for kp_trace_reduce /
- * kp_trace_reduce_hdr; a device header that disagrees with hdr_host gives undefined rows.
+ * Arguments, synchronisation and errors as for kp_trace_reduce / kp_trace_reduce_hdr; a device header
+ * that disagrees with hdr_host gives undefined rows.  Limits: n_regions <= 128, and one workgroup's
+ * records are staged in LDS: waves_per_wg * cap_wave <= 16384 (KP_ERR_UNSUPPORTED_SHAPE beyond; this
+ * kernel has no multi-pass form).
  */
 typedef struct {
   uint32_t start;
