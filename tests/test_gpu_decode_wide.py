@@ -100,6 +100,28 @@ def test_heavily_shuffled_rings(kp, oracle_mod, W, R, cap, p_swap):
     assert st["n_disorder"] > 0.5 * p_swap * st["n_slots_valid"] and st["n_overlap_wgs"] > 0
 
 
+def test_sequence_numbers_that_wrap(kp, oracle_mod):
+    """Waves that wrote more than 2^20 records: the 20-bit sequence numbers wrap around inside the
+    surviving tail of the ring; the rank is still seq - first modulo 2^20.  Built from a generated trace by
+    adding a multiple of the ring size to every sequence number and to the waves' record counts."""
+    W, cap = 8, 4096
+    spec = inputs.TraceSpec(n_wg=3, waves=W, n_regions=40, cap_wave=cap, total_per_wave=5000, total_var=600,
+                            seed=31, dist="exp", p0=30.0, gap_max=4, phase_max=10, p_orphan=0.01, p_swap=0.002)
+    raw, _ = inputs.gen_trace(spec)
+    shift = (1 << 20) - cap
+    raw = raw.copy()
+    hdrs = raw[16:16 + 32 * 3].reshape(3, 32)
+    assert (hdrs[:, 8:8 + W] > cap).all()            # every ring has wrapped, so every slot holds a record
+    hdrs[:, 8:8 + W] += shift
+    recs = raw[16 + 32 * 3:].reshape(-1, 2)
+    recs[:, 0] = (recs[:, 0] & 0xFFF00000) | ((recs[:, 0] + shift) & 0xFFFFF)
+    first = hdrs[:, 8:8 + W].astype(np.int64) - cap
+    assert (first < (1 << 20)).all() and (first + cap > (1 << 20)).all()   # the wrap lies inside the tail
+    st = check(raw, oracle_mod)
+    assert st["n_invalid"] == 0 and st["n_pairs"] > 3 * W * cap // 3 and st["n_overlap_wgs"] == 3
+    assert st["n_dropped"] == int((hdrs[:, 8:8 + W].astype(np.int64) - cap).sum())
+
+
 def test_clean_generated_trace_all_workgroups_in_the_overlap(kp, oracle_mod):
     spec = inputs.TraceSpec(n_wg=300, waves=16, n_regions=48, cap_wave=512, total_per_wave=512, total_var=60, seed=77,
                             dist="lognormal", p0=4.5, p1=0.8)
