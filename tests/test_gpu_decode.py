@@ -206,3 +206,22 @@ def test_events_around_the_main_kernel(kp, oracle_mod):
     torch.cuda.synchronize()
     with pytest.raises(ValueError):
         kp.kp_trace_reduce_hdr_events(dev, n_wg * W * cap, hdr, out, torch.cuda.Event(enable_timing=True), None)
+
+
+def test_sequence_numbers_that_wrap(kp, oracle_mod):
+    """Waves that wrote more than 2^20 records: the 20-bit sequence numbers wrap around inside the surviving
+    tail of the ring (a generated trace with a multiple of the ring size added to every sequence number and
+    to the waves' record counts)."""
+    W, cap, n_wg = 8, 2048, 5
+    spec = inputs.TraceSpec(n_wg=n_wg, waves=W, n_regions=16, cap_wave=cap, total_per_wave=2600, total_var=400,
+                            seed=32, dist="exp", p0=30.0, gap_max=4, phase_max=10, p_orphan=0.01, p_swap=0.002)
+    raw, _ = inputs.gen_trace(spec)
+    shift = (1 << 20) - cap
+    raw = raw.copy()
+    hdrs = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    assert (hdrs[:, 8:8 + W] > cap).all()
+    hdrs[:, 8:8 + W] += shift
+    recs = raw[16 + 32 * n_wg:].reshape(-1, 2)
+    recs[:, 0] = (recs[:, 0] & 0xFFF00000) | ((recs[:, 0] + shift) & 0xFFFFF)
+    check(raw, oracle_mod)
+    check(raw, oracle_mod, use_hdr=True)
