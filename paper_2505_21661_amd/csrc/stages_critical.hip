@@ -68,8 +68,8 @@ __global__ __launch_bounds__(kBlock) void kp_critical_main(CriticalParams p) {
   uint8_t* mark = reinterpret_cast<uint8_t*>(jump1 + P);
   unsigned long long* reg_tot = reinterpret_cast<unsigned long long*>(smem + 25 * (size_t)P);  // [R][2], 8-byte aligned: P >= 64
   unsigned long long* wg_tot = reg_tot + 2 * R;   // stages, latency, bubbles
-  uint32_t* wg_small = reinterpret_cast<uint32_t*>(wg_tot + 3);  // [0] valid stages, [1] min start on the path
-  unsigned long long* all_tot = reinterpret_cast<unsigned long long*>(wg_small + 2);  // paths, stages, latency, bubbles
+  uint32_t* wg_small = reinterpret_cast<uint32_t*>(wg_tot + 3);  // [0] valid stages, [1] min start on the path, [2] a region's keys are out of order
+  unsigned long long* all_tot = reinterpret_cast<unsigned long long*>(wg_small + 4);  // paths, stages, latency, bubbles
 
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   for (uint32_t i = tid; i < 2 * R; i += kBlock) reg_tot[i] = 0ull;
@@ -79,33 +79,63 @@ __global__ __launch_bounds__(kBlock) void kp_critical_main(CriticalParams p) {
   for (uint32_t wg = blockIdx.x; wg < p.n_wg; wg += gridDim.x) {
     const u32x4* tab = p.table + (size_t)wg * N;
     if (tid < 3) wg_tot[tid] = 0ull;
-    if (tid == 0) { wg_small[0] = 0u; wg_small[1] = 0xFFFFFFFFu; }
+    if (tid == 0) { wg_small[0] = 0u; wg_small[1] = 0xFFFFFFFFu; wg_small[2] = 0u; }
     __syncthreads();
     // ---- 1: keys ----------------------------------------------------------------------------------
+    // The iterations of a region usually end one after the other, so that the keys of a region (a run of I
+    // consecutive entries) are in order as they come; that is checked while the keys are made (an entry that
+    // is no stage has the largest key: it must be behind the stages of its run).
     uint32_t n_mine = 0;
+    const bool runs = I >= 2u && (I & (I - 1u)) == 0u;  // runs that the merge steps below can start from
+    bool disorder = false;
     for (uint32_t i = tid; i < P; i += kBlock) {
       unsigned long long k = ~0ull;
       if (i < N) {
         const u32x4 e = tab[i];
         start[i] = e.y; lat[i] = e.x;
         if (e.w != 0u) { k = ((unsigned long long)e.z << 32) | i; ++n_mine; }
+        if (runs && (i & (I - 1u)) != 0u) {
+          const u32x4 before = tab[i - 1u];
+          const unsigned long long kb = before.w != 0u ? ((unsigned long long)before.z << 32) | (i - 1u) : ~0ull;
+          disorder = disorder || kb > k;
+        }
       }
       key[i] = k;
       mark[i] = 0;
     }
     n_mine = wave_sum32(n_mine);
     if (lane == 0 && n_mine) atomicAdd(&wg_small[0], n_mine);
-    // bitonic sort, ascending
-    for (uint32_t k = 2; k <= P; k <<= 1) {
-      for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-        __syncthreads();
+    if (__builtin_amdgcn_ballot_w64(disorder) != 0ull && lane == 0) wg_small[2] = 1u;
+    __syncthreads();
+    // Ascending sort by merging: blocks of k/2 keys in order become blocks of k.  The first step of a merge
+    // compares key i of the lower block with key k/2 - 1 - i of the upper one (the smaller k/2 keys of the
+    // two end up below, the larger above, each a rising-then-falling sequence), the steps after it are the
+    // half-cleaners of a bitonic merge.  With every region's run in order the merging starts at blocks of I.
+    // A thread takes the pairs t = tid, tid + 256, ..., so the 64 pairs of a hardware wave lie in one block of
+    // 128 consecutive keys whenever the two keys of a pair are at most 64 apart (and, in a first step, the
+    // blocks hold at most 128 keys): such steps touch no key of another wave, and since the LDS operations
+    // of one wave take effect in order, two of them in a row need no workgroup barrier between them.
+    auto between = [&](bool local_before, bool local_after) {
+      if (local_before && local_after) { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); __builtin_amdgcn_wave_barrier(); }
+      else __syncthreads();
+    };
+    for (uint32_t k = (runs && wg_small[2] == 0u) ? 2u * I : 2u; k <= P; k <<= 1) {
+      const uint32_t half = k >> 1;
+      for (uint32_t t = tid; t < P / 2; t += kBlock) {
+        const uint32_t blk = (t / half) * k, i = t & (half - 1u), lo = blk + i, hi = blk + k - 1u - i;
+        const unsigned long long a = key[lo], b = key[hi];
+        if (a > b) { key[lo] = b; key[hi] = a; }
+      }
+      // (the step after this one: the half-cleaner at distance half / 2, or the first step of the next size)
+      between(k <= 128u, half >= 2u ? (half >> 1) <= 64u : 2u * k <= 128u);
+      for (uint32_t j = half >> 1; j > 0; j >>= 1) {
         for (uint32_t t = tid; t < P / 2; t += kBlock) {
           const uint32_t lo = ((t & ~(j - 1u)) << 1) | (t & (j - 1u));  // the element of the pair with bit j clear
           const uint32_t hi = lo | j;
           const unsigned long long a = key[lo], b = key[hi];
-          const bool up = (lo & k) == 0u;
-          if ((a > b) == up) { key[lo] = b; key[hi] = a; }
+          if (a > b) { key[lo] = b; key[hi] = a; }
         }
+        between(j <= 64u, j >= 2u ? true : 2u * k <= 128u);
       }
     }
     __syncthreads();
@@ -225,7 +255,7 @@ extern "C" kp_status kp_stages_critical(const void* stages, int n_wg, int n_regi
   hipLaunchKernelGGL(kp_critical_init, dim3(1), dim3(256), 0, s, p.hdr, p.n_wg, p.R, p.I);
   KP_HIP_TRY(hipGetLastError());
   if (n_wg == 0) return KP_OK;
-  const uint32_t lds = 25u * p.P + 16u * p.R + 24u + 8u + 32u;
+  const uint32_t lds = 25u * p.P + 16u * p.R + 24u + 16u + 32u;
   static thread_local LaunchCache cache;
   int dev = 0;
   KP_HIP_TRY(hipGetDevice(&dev));
