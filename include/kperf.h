@@ -426,7 +426,7 @@ kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_wg, int wave
 
 /*
  * The constant that replay takes off every measured duration (Sec. 4.3: the record's own cost is
- * compensated by offsetting a constant; Sec. 5.4 measures it).  A region is measured from the clock
+ * taken out as one constant per record; Sec. 5.4 measures it).  A region is measured from the clock
  * read of its START site to the clock read of its END site, which includes the instructions of the
  * sites themselves: an empty region of kp_calibrate reads exactly that constant.  Every trace recorded
  * after kp_set_rec_cost(ticks) carries `ticks` in kp_trace_hdr.rec_cost (process-wide, default 0; the

@@ -2,7 +2,7 @@
 //
 // The paper reads the critical path of a kernel whose warp groups work on different stages off the
 // timeline: a chain of stages each of which could only start when the one before it had finished
-// (Sec. 3.3 "Critical-path Analysis"; Sec. 5.2, where a load is found "blocked by" a barrier of another
+// (Sec. 3.3 "Critical-path Analysis"; Sec. 5.2, where a load turns out to be held up by a barrier of another
 // warp group), and takes the sum of the latencies along it as the kernel's latency (Table 4, WS model).
 // Here the chain is taken per recorded workgroup from its stage table: stages ordered by (max_end,
 // index); the path ends in the last one; the stage before X is the latest stage of that order, earlier
