@@ -331,7 +331,10 @@ kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int ma
  * record to the same LDS address instead of one lane under a narrowed execution mask, and every
  * stream's wave leaves the low 12 bits of its hardware id register in kp_wg_hdr.wave_hw_id[]
  * (KP_FLAG_HW_IDS).  The records themselves are the same either way.
- * Bits 27, 28 and 30 and the flush strategy go through the generic record sites.
+ * Bit 27 and the flush strategy go through the generic record sites (a site writes the records of the
+ * site before it to LDS); in the 256x256x64 GEMM every other combination keeps the cheaper sites that
+ * buffer their records in registers, elsewhere bits 28 and 30 and a partial region mask take the
+ * generic sites too.
  *
  * trace_buf: device, kp_trace_bytes(n_wg, streams, trace_cap) bytes, 16-byte aligned; headers and
  * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written

@@ -79,7 +79,7 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 // The same for a kernel whose lean sites are deferred (SITE 4): the clock read goes into pair K and is
 // turned into records at the next KP_COMMIT, which stands right after a wait for all LDS traffic.
 #define KP_SITE_K(ring, K, end_r, start_r) do { if constexpr (INSTR != 0) { \
-    if constexpr (SITE == 4) kp::site_defer<K>(ring, end_r, start_r); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
+    if constexpr (SITE == 4) kp::site_defer<K, (INSTR >= 4), (INSTR == 5)>(ring, end_r, start_r); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
 #define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 4) kp::sites_commit<N>(ring); } while (0)
 
 // ------------------------------------------------------------------------------------------
@@ -186,7 +186,11 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // same source without the scheduling fences between the stages (uninstrumented only)
   constexpr bool PHASED = SCHEDULE != 0;
   static_assert(SCHEDULE != 2 || INSTR == 0, "the unfenced stage-by-stage form has no record sites");
-  constexpr int SITE = INSTR == 2 ? 4 : INSTR;
+  // INSTR 2: every region, shader clock; 4: the region mask decides (wave-group records included), 5: the
+  // same on the constant-rate clock -- all three with the register-buffered sites; 1 and 3 are the generic
+  // sites, which the flush strategy and the 64-lane store need
+  constexpr int SITE = (INSTR == 2 || INSTR >= 4) ? 4 : INSTR;
+  constexpr bool REALTIME = INSTR == 3 || INSTR == 5;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
   static_assert(WAVES == 8 || WAVES == 4, "2 x 4 or 2 x 2 waves");
@@ -219,7 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, (uint32_t)WAVES >> g.group_log2, wg, g.group_log2);
   ring.collab = g.collab;
-  if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
+  if constexpr (REALTIME) kp::ring_use_realtime(ring);
   kp::sites_begin<SITE>(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
@@ -448,7 +452,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
     if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
     else kp::sites_end<SITE>(ring);
-    kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
   }
 }
 
@@ -560,8 +564,12 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
   const bool lean = !flush && !group_log2 && !realtime && !collab && regions == (1u << s.regions) - 1u && K <= (1 << 22);
+  // The large kernel buffers its sites in registers whenever the strategy is circular and one lane stores:
+  // with a region mask, wave-group records or the constant-rate clock too (the mask is tested at the site).
+  const bool buffered = !flush && !collab && K <= (1 << 22);
   if (big) return lean ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st)
-                       : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
+                : buffered ? (realtime ? launch_big_w<5>(phased, g, n_wg, ring_bytes, st) : launch_big_w<4>(phased, g, n_wg, ring_bytes, st))
+                           : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else if (realtime) hipLaunchKernelGGL(kp_gemm_small<3>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);

@@ -330,19 +330,24 @@ __device__ __forceinline__ void flush_sites(Ring& r) {
   r.slot = 0u;
 }
 
-template <int K>
+// MASKED: the region mask of the ring decides which of the site's records exist (a site with none
+// still reads the clock and is committed as "no site"); wave-group records come with it, since a wave
+// that does not lead its group has an empty mask.  REALTIME: the constant-rate clock.
+template <int K, bool MASKED = false, bool REALTIME = false>
 __device__ __forceinline__ void site_defer(Ring& r, uint32_t end_region, uint32_t start_region) {
   static_assert(K >= 0 && K < 4, "four deferred sites at most");
   __builtin_amdgcn_sched_barrier(0);
-  r.dq_t[K] = sample_clock();
-  if (end_region != kNoRegion && start_region != kNoRegion) {
-    r.dq_info[K] = (r.cw & 0xFFFFu) | ((0x80u | end_region) << 16) | (start_region << 24);
-    r.cw += 2u;
-  } else {
-    const uint32_t b = end_region != kNoRegion ? (0x80u | end_region) : start_region;
-    r.dq_info[K] = (r.cw & 0xFFFFu) | (b << 16) | (0xFFu << 24);
-    r.cw += 1u;
+  r.dq_t[K] = sample_clock<REALTIME>();
+  bool on_e = end_region != kNoRegion, on_s = start_region != kNoRegion;  // (scalar; constants without a mask)
+  if constexpr (MASKED) {
+    on_e = on_e && ((r.mask >> (end_region & 31u)) & 1u) != 0u;
+    on_s = on_s && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
   }
+  // (selects, no branches: tag byte 0xFF stands for "no record", whatever the counter bits beside it say)
+  const uint32_t b1 = on_e ? (0x80u | end_region) : (on_s ? start_region : 0xFFu);
+  const uint32_t b2 = (on_e && on_s) ? start_region : 0xFFu;
+  r.dq_info[K] = (r.cw & 0xFFFFu) | (b1 << 16) | (b2 << 24);
+  r.cw += (on_e ? 1u : 0u) + (on_s ? 1u : 0u);
   __builtin_amdgcn_sched_barrier(0);
 }
 
