@@ -71,7 +71,14 @@ __device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) {
 
 // END of one region and/or START of the next with a single clock sample.  INSTR: 0 no record sites,
 // 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
-#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<INSTR>(ring, end_r, start_r); } while (0)
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0 && INSTR != 4) kp::site<INSTR>(ring, end_r, start_r); } while (0)
+#define KP_CHAIN(K, ring) do { if constexpr (INSTR == 4) kp::site_chain<K>(ring); } while (0)
+
+// The chain of record sites: one ahead of the loop (opens region 0), three per KV tile.
+struct AttnChain {
+  __device__ uint32_t end_region(uint32_t site) const { return (site - 1u) % 3u; }
+  __device__ uint32_t start_region(uint32_t site) const { return site % 3u; }
+};
 
 template <int INSTR>
 __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
@@ -104,6 +111,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   ring.collab = g.collab;
   if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
   if constexpr (INSTR == 2) kp::lean_begin(ring);
+  if constexpr (INSTR == 4) kp::chain_begin(ring);
 
   // Q fragments of this wave's 32 rows stay in registers: step s covers d = 16s .. 16s+15
   const uint32_t qrow = q0 + wave * 32 + l32;
@@ -200,6 +208,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // would also wait for the two record stores the site has just issued, every tile (measured: 1.5
     // points of overhead).  The wait at the barrier thereby belongs to the region that ends here.
     KP_BOUNDARY(ring, 0, 1);
+    KP_CHAIN(1, ring);
     if constexpr (MORE) store_k();
     if constexpr (MORE2) load_k(kv0 + 2 * kBkv);
 
@@ -245,6 +254,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       }
     l_run += psum;
     KP_BOUNDARY(ring, 1, 2);
+    KP_CHAIN(2, ring);
     __builtin_amdgcn_s_setprio(2);
 
     // ---- region 2: O^T += V^T P^T ---------------------------------------------------------------------
@@ -272,10 +282,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // One site closes region 2 and opens region 0 of the next tile: a tile costs three sites, not four.
     // Behind the barrier for the same reason as above.
     if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, kp::kNoRegion);
+    if constexpr (INSTR == 4) {
+      kp::chain_commit<3>(ring);
+      KP_CHAIN(0, ring);
+    }
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   KP_BOUNDARY(ring, kp::kNoRegion, 0);
+  KP_CHAIN(0, ring);
   // only the last two tiles of a causal block can reach past the diagonal
   for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, yes, no);
   tile(n_tiles - 2, yes, no, yes);
@@ -297,7 +312,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flags};
     if constexpr (INSTR == 2) kp::lean_end(ring);
-    kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    if constexpr (INSTR == 4) {
+      kp::chain_commit<1>(ring);
+      kp::chain_end(ring);
+      kp::ring_finish<false>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, AttnChain{});
+    } else {
+      kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    }
   }
 }
 
@@ -371,10 +392,15 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<3>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<4>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     attr_dev = dev;
   }
   // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
-  if (!flush && !group_log2 && !realtime && !collab && regions == 7u && S <= (1 << 22))
+  const bool lean = !flush && !group_log2 && !realtime && !collab && regions == 7u && S <= (1 << 22);
+  if (lean && cap_lds >= 8u)
+    hipLaunchKernelGGL(kp_attn_fwd<4>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  else if (lean)
     hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
   else if (realtime)
     hipLaunchKernelGGL(kp_attn_fwd<3>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);

@@ -78,9 +78,28 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 #define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<SITE>(ring, end_r, start_r); } while (0)
 // The same for a kernel whose lean sites are deferred (SITE 4): the clock read goes into pair K and is
 // turned into records at the next KP_COMMIT, which stands right after a wait for all LDS traffic.
+// SITE 6: the sites of the kernel form a chain known at compile time, the loop keeps only their clocks
+// (kp::site_chain / chain_commit) and the records are made when the trace is copied out.
 #define KP_SITE_K(ring, K, end_r, start_r) do { if constexpr (INSTR != 0) { \
-    if constexpr (SITE == 4) kp::site_defer<K, (INSTR >= 4), (INSTR == 5)>(ring, end_r, start_r); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
-#define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 4) kp::sites_commit<N>(ring); } while (0)
+    if constexpr (SITE == 6) kp::site_chain<K>(ring); \
+    else if constexpr (SITE == 4) kp::site_defer<K, (INSTR >= 4), (INSTR == 5)>(ring, end_r, start_r); \
+    else kp::site<SITE>(ring, end_r, start_r); } } while (0)
+#define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0) { \
+    if constexpr (SITE == 6) kp::chain_commit<N>(ring); else if constexpr (SITE == 4) kp::sites_commit<N>(ring); } } while (0)
+
+// The chain of the large kernel's record sites (n sites in all).  Threaded schedule: regions 0, 1, 2 in
+// turn, three sites per K step; stages apart: regions 2, 0, 3, 1 in turn, four sites per K step.  The last
+// site of the loop opens the epilogue region instead (3, or 4 with the stages apart), the very last closes it.
+template <bool PHASED>
+struct GemmChain {
+  uint32_t n;
+  __device__ uint32_t in_turn(uint32_t i) const {
+    if constexpr (PHASED) return (0x1302u >> ((i & 3u) * 4u)) & 0xFu;  // 2, 0, 3, 1
+    else return i % 3u;
+  }
+  __device__ uint32_t end_region(uint32_t site) const { return site + 1u == n ? (PHASED ? 4u : 3u) : in_turn(site - 1u); }
+  __device__ uint32_t start_region(uint32_t site) const { return site + 2u == n ? (PHASED ? 4u : 3u) : in_turn(site); }
+};
 
 // ------------------------------------------------------------------------------------------
 // 64x64x32 tile, 4 waves as 2x2, each wave one 32x32 accumulator tile.
@@ -189,7 +208,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // INSTR 2: every region, shader clock; 4: the region mask decides (wave-group records included), 5: the
   // same on the constant-rate clock -- all three with the register-buffered sites; 1 and 3 are the generic
   // sites, which the flush strategy and the 64-lane store need
-  constexpr int SITE = (INSTR == 2 || INSTR >= 4) ? 4 : INSTR;
+  constexpr int SITE = INSTR == 2 ? 6 : INSTR >= 4 ? 4 : INSTR;
   constexpr bool REALTIME = INSTR == 3 || INSTR == 5;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
@@ -450,9 +469,15 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   KP_SITE_K(ring, 1, PHASED ? 4 : 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
-    if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
-    else kp::sites_end<SITE>(ring);
-    kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    if constexpr (SITE == 6) {
+      kp::chain_commit<2>(ring);  // the sites that opened and closed the epilogue
+      kp::chain_end(ring);
+      kp::ring_finish<false>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, GemmChain<PHASED>{ring.cw});
+    } else {
+      if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
+      else kp::sites_end<SITE>(ring);
+      kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
+    }
   }
 }
 
@@ -567,7 +592,7 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
   // The large kernel buffers its sites in registers whenever the strategy is circular and one lane stores:
   // with a region mask, wave-group records or the constant-rate clock too (the mask is tested at the site).
   const bool buffered = !flush && !collab && K <= (1 << 22);
-  if (big) return lean ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st)
+  if (big) return lean && g.cap_lds >= 8u ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st)
                 : buffered ? (realtime ? launch_big_w<5>(phased, g, n_wg, ring_bytes, st) : launch_big_w<4>(phased, g, n_wg, ring_bytes, st))
                            : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);

@@ -18,6 +18,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "kperf.h"
 
 namespace kp {
@@ -397,6 +399,93 @@ __device__ __forceinline__ void deferred_end(Ring& r) {
   r.pend_tag2 = kNoPending;
 }
 
+// A third form, for kernels whose record sites form a chain that is known when the kernel is compiled:
+// the first site opens a region, every later site closes the region before it and opens the next, the
+// last one only closes.  Which records site i writes is then a function of i alone, so the loop keeps
+// nothing but the clocks: a site is the clock read into scalar pair K (site_chain<K>, one instruction),
+// and chain_commit<N>() puts the low clock words of sites 0..N-1 of the batch into lanes 0..N-1 of one
+// transient vector register and stores them with a single ds_write_b32 into a ring of 4-byte entries, one
+// per site (13 instructions per commit plus one per site).  The records themselves -- tags and clock minus
+// workgroup start -- are made from that ring when the workgroup copies its trace out (ring_finish with a
+// CHAIN functor that names the two regions of site i).  The ring holds as many sites as the record ring
+// holds records, which covers the sites of the newest cap records.  Measured on the attention kernel
+// (three sites per KV tile): 51 instructions per tile and wave with the records written at the sites
+// cost 10 %, whether they took six LDS instructions or two.
+template <int K>
+__device__ __forceinline__ void site_chain(Ring& r) {
+  static_assert(K >= 0 && K < 4, "four sites per batch at most");
+  __builtin_amdgcn_sched_barrier(0);
+  r.dq_t[K] = sample_clock();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int N>
+__device__ __forceinline__ void chain_commit(Ring& r) {
+  static_assert(N >= 1 && N <= 4, "four sites per batch at most");
+  __builtin_amdgcn_sched_barrier(0);
+  uint32_t vt = 0u;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    // the wait names the register pair as its output, so nothing can read the pair ahead of it
+    uint64_t t = r.dq_t[k];
+    if (k == 0) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(t));
+    else asm volatile("" : "+s"(t));
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(vt) : "s"((uint32_t)t), "n"(k));
+  }
+  const uint32_t lane = __builtin_amdgcn_mbcnt_lo(~0u, 0u);  // (the lane index in lanes 0..31, enough for four)
+  const uint32_t addr = r.sub_lds + (((r.cw + lane) & r.lds_mask) << 2);
+  uint64_t saved_exec;
+  asm volatile(
+      "s_mov_b64 %0, exec\n\t"
+      "s_mov_b64 exec, %3\n\t"
+      "ds_write_b32 %1, %2\n\t"
+      "s_mov_b64 exec, %0"
+      : "=&s"(saved_exec)
+      : "v"(addr), "v"(vt), "n"((1 << N) - 1)
+      : "memory");
+  r.cw += (uint32_t)N;
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// r.cw counts sites in this form
+__device__ __forceinline__ void chain_begin(Ring& r) { r.cw = 0u; }
+// Before ring_finish(), after the last commit: the first and the last site wrote one record, the others two.
+__device__ __forceinline__ void chain_end(Ring& r) {
+  r.cnt = r.cw >= 2u ? 2u * r.cw - 2u : 0u;
+  r.stored = r.cnt;
+  r.pend_tag = kNoPending;
+  r.pend_tag2 = kNoPending;
+}
+
+struct NoChain {};
+
+// Records of the newest cap_lds sequence numbers from the ring of site clocks, straight to the wave's HBM
+// segment (slot = sequence number modulo capacity, as the record sites would have placed them; slots that
+// were never written are cleared).  Sequence number 0 is the START of site 0; 2 i - 1 and 2 i are the END and
+// the START of site i.
+template <class CHAIN>
+__device__ __forceinline__ void chain_copy_out(const Ring& r, uint32_t cap_lds, CHAIN chain) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const uint32_t lane = threadIdx.x & 63u, total = r.cnt;
+  for (uint32_t i = lane * 2; i < cap_lds; i += 128) {  // the capacity is a power of two >= 2
+    uint32_t w[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t slot = i + (uint32_t)h;
+      uint32_t tag = 0u, ts = 0u;
+      if (slot < total) {
+        const uint32_t q = total - 1u - ((total - 1u - slot) & r.lds_mask);  // the newest record of this slot
+        const uint32_t site = (q + 1u) >> 1, end = q & 1u;
+        const uint32_t region = end ? chain.end_region(site) : chain.start_region(site);
+        tag = (end << 31) | (region << 24) | r.tag_wave | (q & 0xFFFFFu);
+        ts = r.sub[site & r.lds_mask] - r.t0_lo;
+      }
+      w[2 * h] = tag; w[2 * h + 1] = ts;
+    }
+    *reinterpret_cast<u32x4*>(r.seg + 2 * (size_t)i) = u32x4{w[0], w[1], w[2], w[3]};
+  }
+}
+
 // MODE 1: generic (region mask, either strategy, either store); MODE 3: generic, on the constant-rate
 // clock; MODE 2: every region enabled, circular strategy, records written to LDS at the next site;
 // MODE 4: the same, deferred sites buffered in registers (the kernel calls site_defer / sites_commit /
@@ -410,6 +499,7 @@ __device__ __forceinline__ void site(Ring& r, uint32_t end_region, uint32_t star
 template <int MODE>
 __device__ __forceinline__ void sites_begin(Ring& r) {
   if constexpr (MODE == 4) deferred_begin(r);
+  else if constexpr (MODE == 6) chain_begin(r);
   else if constexpr (MODE == 2) lean_begin(r);
 }
 template <int MODE>
@@ -428,9 +518,9 @@ __device__ __forceinline__ void record(Ring& r, uint32_t region, uint32_t phase)
 __device__ __forceinline__ void ring_use_realtime(Ring& r) { r.t0_lo = (uint32_t)r.rt_begin; }
 
 // Workgroup epilogue: copy what is still in LDS to HBM and write the headers.
-template <bool REALTIME = false>
+template <bool REALTIME = false, class CHAIN = NoChain>
 __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* trace_buf, TraceGeom g, uint32_t wg,
-                                            uint32_t rec_cost) {
+                                            uint32_t rec_cost, CHAIN chain = CHAIN{}) {
   __syncthreads();  // t_end must not precede any wave's last record
   const uint64_t t_end = __builtin_readcyclecounter();
   const uint64_t rt_end = __builtin_amdgcn_s_memrealtime();
@@ -438,6 +528,9 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
   const uint32_t lane = threadIdx.x & 63u;
   kp_wg_hdr* wh = reinterpret_cast<kp_wg_hdr*>(base + sizeof(kp_trace_hdr)) + wg;
   if (r.leader) {  // the wave that wrote the stream also copies it out
+    if constexpr (!std::is_same<CHAIN, NoChain>::value) {
+      chain_copy_out(r, cap_lds, chain);
+    } else {
     store_pending(r);
     if (r.flush) {
       const uint32_t tail = r.cnt & r.lds_mask;           // records not yet copied
@@ -448,6 +541,7 @@ __device__ __forceinline__ void ring_finish(Ring& r, uint32_t cap_lds, void* tra
       }
     } else {
       wave_copy_slots(r.sub, r.seg, cap_lds);  // whole sub-ring; the decoder ignores slots >= total
+    }
     }
     if (lane == 0) {
       wh->total_written[r.stream] = r.cnt;

@@ -219,6 +219,39 @@ def test_full_size_attention(kp, oracle_mod):
     assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_span_overflow_wgs"] == 0
 
 
+@pytest.mark.parametrize("trace_cap", [16, 64, 1024])
+def test_attention_chain_sites_write_the_generic_sites_records(kp, trace_cap):
+    """With every region enabled the kernel keeps only the clocks of its sites in LDS and makes the records
+    when it copies the trace out (from 8 slots per wave up; below that the records are written at the sites).
+    Slot by slot the tags must be those the generic sites write (KP_MASK_COLLAB selects them), also where the
+    ring wrapped, and along the sequence numbers of a wave the clocks must not decrease."""
+    B, H, S = 1, 2, 640
+    q, k, v = inputs.attn_inputs(B, H, S, 128, seed=21)
+    dev = (q.cuda(), k.cuda(), v.cuda())
+    _, t_chain, (n_wg, waves, R) = run_attn(kp, q, k, v, True, 0b111, trace_cap=trace_cap, dev=dev)
+    _, t_gen, _ = run_attn(kp, q, k, v, True, 0b111 | kp.KP_MASK_COLLAB, trace_cap=trace_cap, dev=dev)
+    cap = trace_cap // waves
+    a, b = (t.cpu().numpy().view(np.uint32).copy() for t in (t_chain, t_gen))
+    assert tuple(a[2:6]) == tuple(b[2:6]) == (n_wg, waves, R, cap)
+    ha, hb = (x[16:16 + 32 * n_wg].reshape(n_wg, 32) for x in (a, b))
+    assert (ha[:, 8:24] == hb[:, 8:24]).all() and (ha[:, 0] == hb[:, 0]).all()
+    ra, rb = (x[16 + 32 * n_wg:].reshape(n_wg, waves, cap, 2) for x in (a, b))
+    for w in range(n_wg):
+        for j in range(waves):
+            total = int(ha[w, 8 + j])
+            n = min(total, cap)
+            assert total == 6 * 2 * (S // 128 - w % (S // 128))
+            assert (ra[w, j, :n, 0] == rb[w, j, :n, 0]).all(), (w, j)
+            assert (ra[w, j, n:] == 0).all()
+            seq = ra[w, j, :n, 0] & 0xFFFFF
+            order = np.argsort(seq)
+            assert (np.sort(seq) == np.arange(total - n, total)).all()
+            ts = ra[w, j, :n, 1][order].astype(np.int64)
+            assert (np.diff(ts) >= 0).all() and ts[0] > 0
+            span = int(ha[w, 4:6].copy().view(np.uint64)[0] - ha[w, 2:4].copy().view(np.uint64)[0])
+            assert ts[-1] < span
+
+
 def test_attention_errors(kp):
     t = torch.zeros(1, 1, 128, 128, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(kp.KperfError) as e:
