@@ -332,9 +332,10 @@ kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int ma
  * stream's wave leaves the low 12 bits of its hardware id register in kp_wg_hdr.wave_hw_id[]
  * (KP_FLAG_HW_IDS).  The records themselves are the same either way.
  * Bit 27 and the flush strategy go through the generic record sites (a site writes the records of the
- * site before it to LDS); in the 256x256x64 GEMM every other combination keeps the cheaper sites that
- * buffer their records in registers, elsewhere bits 28 and 30 and a partial region mask take the
- * generic sites too.
+ * site before it to LDS); in the 256x256x64 GEMM and the attention kernel every other combination keeps
+ * the cheaper chained sites (the loop stores only the clocks of its sites, a fixed sequence, and the
+ * records are made from them when the trace is copied out: the same records in the same slots), in the
+ * small GEMM bits 28 and 30 and a partial region mask take the generic sites too.
  *
  * trace_buf: device, kp_trace_bytes(n_wg, streams, trace_cap) bytes, 16-byte aligned; headers and
  * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written
@@ -417,8 +418,9 @@ kp_status kp_attn_instrumented(const void* Q, const void* K, const void* V, void
  * as KP_MASK_WAVE_GROUP does (waves must then be a multiple of 4; the trace holds waves / 4 streams).
  * mode bits 4 and 5 select the form of the record sites, which the instrumented kernels also choose
  * among and which decides the constant a region is measured too long by: neither bit the generic sites
- * (region mask, either strategy, either clock), bit 4 the lean sites (all regions, circular strategy:
- * the attention kernel and the small GEMM), bit 5 the deferred sites of the 256x256x64 GEMM; with
+ * (region mask, either strategy, either clock, either store), bit 4 the lean sites (all regions, circular
+ * strategy: the small GEMM), bit 5 the chained sites of the 256x256x64 GEMM and the attention kernel (the
+ * loop keeps only the clocks of the sites, the records are made when the trace is copied out); with
  * either bit, bits 1..3 and 6 must be 0 (KP_ERR_INVALID_ARG otherwise).  mode bit6 selects the
  * store of KP_MASK_COLLAB (all lanes write the record; hardware ids in the workgroup header).
  *   cycles     HOST pointer to n_regions values (n_regions <= 32)

@@ -70,14 +70,20 @@ __device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) {
 }
 
 // END of one region and/or START of the next with a single clock sample.  INSTR: 0 no record sites,
-// 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
-#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0 && INSTR != 4) kp::site<INSTR>(ring, end_r, start_r); } while (0)
-#define KP_CHAIN(K, ring) do { if constexpr (INSTR == 4) kp::site_chain<K>(ring); } while (0)
+// 1 generic sites (region mask, either buffer strategy, either store), 3 the same on the constant-rate clock,
+// 4 chained sites (circular strategy, one lane stores; region mask and wave-group records included: the loop
+// keeps only the clocks and the records are made when the trace is copied out), 5 chained, constant-rate clock.
+#define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR == 1 || INSTR == 3) kp::site<INSTR>(ring, end_r, start_r); } while (0)
+#define KP_CHAIN(K, ring) do { if constexpr (INSTR >= 4) kp::site_chain<K, (INSTR == 5)>(ring); } while (0)
 
-// The chain of record sites: one ahead of the loop (opens region 0), three per KV tile.
+// The sequence of record sites: one ahead of the loop (opens region 0), three per KV tile, the last only closes.
 struct AttnChain {
-  __device__ uint32_t end_region(uint32_t site) const { return (site - 1u) % 3u; }
-  __device__ uint32_t start_region(uint32_t site) const { return site % 3u; }
+  static constexpr uint32_t kRegions = 3u;
+  static constexpr bool kDense = true;
+  // n = 3 tiles + 1: every enabled region leaves two records per tile
+  __device__ uint32_t total(uint32_t n, uint32_t mask) const { return 2u * ((n - 1u) / 3u) * (uint32_t)__builtin_popcount(mask & 7u); }
+  __device__ uint32_t end_region(uint32_t site, uint32_t) const { return site == 0u ? kp::kNoRegion : (site - 1u) % 3u; }
+  __device__ uint32_t start_region(uint32_t site, uint32_t n) const { return site + 1u == n ? kp::kNoRegion : site % 3u; }
 };
 
 template <int INSTR>
@@ -109,9 +115,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     ring = kp::ring_init<true>(ring_lds, reinterpret_cast<uint64_t*>(smem), g.cap_lds, g.region_mask, g.flush,
                          g.cap_hbm, g.trace, g.n_wg, 4u >> g.group_log2, wg, g.group_log2);
   ring.collab = g.collab;
-  if constexpr (INSTR == 3) kp::ring_use_realtime(ring);
-  if constexpr (INSTR == 2) kp::lean_begin(ring);
-  if constexpr (INSTR == 4) kp::chain_begin(ring);
+  if constexpr (INSTR == 3 || INSTR == 5) kp::ring_use_realtime(ring);
+  // (with wave groups the host adds 16 bytes behind the ring for the waves that do not record)
+  if constexpr (INSTR >= 4) kp::chain_begin(ring, (uint32_t)(uintptr_t)ring_lds + (4u >> g.group_log2) * g.cap_lds * 8u);
 
   // Q fragments of this wave's 32 rows stay in registers: step s covers d = 16s .. 16s+15
   const uint32_t qrow = q0 + wave * 32 + l32;
@@ -282,7 +288,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // One site closes region 2 and opens region 0 of the next tile: a tile costs three sites, not four.
     // Behind the barrier for the same reason as above.
     if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, kp::kNoRegion);
-    if constexpr (INSTR == 4) {
+    if constexpr (INSTR >= 4) {
       kp::chain_commit<3>(ring);
       KP_CHAIN(0, ring);
     }
@@ -311,11 +317,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     }
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flags};
-    if constexpr (INSTR == 2) kp::lean_end(ring);
-    if constexpr (INSTR == 4) {
+    if constexpr (INSTR >= 4) {
       kp::chain_commit<1>(ring);
-      kp::chain_end(ring);
-      kp::ring_finish<false>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, AttnChain{});
+      kp::ring_finish<INSTR == 5>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, AttnChain{});
     } else {
       kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
     }
@@ -379,7 +383,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
     return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/streams = %zu must be a power of two >= 2", cap_wave);
   uint32_t cap_lds = (uint32_t)cap_wave;
   if (flush && cap_lds > 64) cap_lds = 64;
-  const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
+  const size_t ring_bytes = (size_t)cap_lds * 8 * streams + (group_log2 ? 16 : 0);  // (16: see chain_begin)
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
   static thread_local int attr_dev = -1;  // the attribute is kept per device
@@ -388,7 +392,7 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
   if (attr_dev != dev) {
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<1>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<2>),
+    KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<5>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     KP_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kp_attn_fwd<3>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
@@ -396,16 +400,15 @@ extern "C" kp_status kp_attn_instrumented(const void* Q, const void* K, const vo
                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
     attr_dev = dev;
   }
-  // every region, circular, and fewer than 2^20 records per wave (6 per KV tile): lean record sites
-  const bool lean = !flush && !group_log2 && !realtime && !collab && regions == 7u && S <= (1 << 22);
-  if (lean && cap_lds >= 8u)
-    hipLaunchKernelGGL(kp_attn_fwd<4>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
-  else if (lean)
-    hipLaunchKernelGGL(kp_attn_fwd<2>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
-  else if (realtime)
+  // circular strategy and one lane stores: chained record sites
+  if (!flush && !collab) {
+    if (realtime) hipLaunchKernelGGL(kp_attn_fwd<5>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+    else hipLaunchKernelGGL(kp_attn_fwd<4>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  } else if (realtime) {
     hipLaunchKernelGGL(kp_attn_fwd<3>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
-  else
+  } else {
     hipLaunchKernelGGL(kp_attn_fwd<1>, dim3(n_wg), dim3(kAttnThreads), tile_bytes + ring_bytes, st, g);
+  }
   KP_HIP_TRY(hipGetLastError());
   return KP_OK;
 }

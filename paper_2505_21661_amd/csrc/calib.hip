@@ -45,8 +45,17 @@ __device__ __forceinline__ void busy(uint32_t mode, uint32_t len, float& x) {
 }
 
 // SITE: the form of the record sites (kp_record.h): 1 generic, 2 lean (records written to LDS at the
-// next site), 4 deferred (clock reads parked in scalar registers, committed after the region).  The
-// instrumented kernels use all three; a region costs a different constant with each.
+// next site), 4 chained (clock reads parked in scalar registers, their clocks stored after the region, the
+// records made when the trace is copied out).  The instrumented kernels use all three; a region costs a
+// different constant with each.
+struct CalibChain {  // site 2 r opens region r, site 2 r + 1 closes it (every region enabled)
+  static constexpr uint32_t kRegions = KP_MAX_REGIONS;
+  static constexpr bool kDense = false;
+  __device__ uint32_t total(uint32_t n, uint32_t) const { return n; }
+  __device__ uint32_t end_region(uint32_t site, uint32_t) const { return (site & 1u) ? site >> 1 : kp::kNoRegion; }
+  __device__ uint32_t start_region(uint32_t site, uint32_t) const { return (site & 1u) ? kp::kNoRegion : site >> 1; }
+};
+
 template <bool REALTIME, bool GROUPS, int SITE>
 __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace, uint32_t cap_lds,
                                                         uint32_t cap_hbm, uint32_t flush, uint32_t n_wg,
@@ -82,20 +91,20 @@ __global__ __launch_bounds__(1024) void kp_calib_kernel(CalibArgs a, void* trace
       if (pass == 0) (void)kp::clock_delta(r.pend_t, r.t0_lo);  // the last clock read has to land before the reset
       else kp::lean_end(r);
     } else {
-      kp::deferred_begin(r);
+      kp::chain_begin(r);
       for (uint32_t rg = 0; rg < a.n_regions; ++rg) {
-        kp::site_defer<0>(r, kp::kNoRegion, rg);
+        kp::site_chain<0>(r);
         busy(a.mode, a.cycles[rg], x);
-        kp::site_defer<1>(r, rg, kp::kNoRegion);
-        kp::sites_commit<2>(r);
+        kp::site_chain<1>(r);
+        kp::chain_commit<2>(r);
       }
-      if (pass == 1) kp::deferred_end<0>(r);
     }
   }
   if (x == 12345.6789f && sink) *sink = x;  // keeps the FMA chain alive
   kp::TraceGeom g{n_wg, streams, a.n_regions, cap_hbm,
                   (flush ? KP_FLAG_FLUSH : 0u) | (REALTIME ? KP_FLAG_REALTIME : 0u) | (a.collab ? KP_FLAG_HW_IDS : 0u)};
-  kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, a.rec_cost);
+  if constexpr (SITE == 4) kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, a.rec_cost, CalibChain{});
+  else kp::ring_finish<REALTIME>(r, cap_lds, trace, g, blockIdx.x, a.rec_cost);
 }
 
 }  // namespace
@@ -108,7 +117,7 @@ extern "C" kp_status kp_calibrate(const uint32_t* cycles, int n_regions, int n_w
     return kp::fail(KP_ERR_INVALID_ARG, "n_regions=%d n_wg=%d waves=%d mode=%d", n_regions, n_wg, waves, mode);
   const int site = (mode & 16) ? 2 : ((mode & 32) ? 4 : 1);
   if ((mode & 48) == 48 || (site != 1 && (mode & (2 | 4 | 8 | 64))))
-    return kp::fail(KP_ERR_INVALID_ARG, "mode=%d: the lean and deferred site forms record per wave, on the shader clock, circular", mode);
+    return kp::fail(KP_ERR_INVALID_ARG, "mode=%d: the lean and chained site forms record per wave, on the shader clock, circular", mode);
   const uint32_t group_log2 = (mode & 8) ? 2u : 0u;
   if (group_log2 && (waves & 3)) return kp::fail(KP_ERR_INVALID_ARG, "wave-group records need a multiple of 4 waves, got %d", waves);
   const size_t streams = (size_t)(waves >> group_log2);

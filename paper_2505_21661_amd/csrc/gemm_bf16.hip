@@ -72,33 +72,40 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 }
 
 // END of one region and START of the next with a single clock sample.  INSTR: 0 no record sites,
-// 1 generic sites (region mask, either buffer strategy), 2 lean sites (all regions, circular).
-// SITE is the form of the sites a kernel uses for INSTR (kp::site<>): the large kernel defers its lean
-// sites and buffers them in registers, the small one writes them to LDS at the next site.
+// 1 generic sites (region mask, either buffer strategy, either store), 3 the same on the constant-rate
+// clock, 2 lean sites (small kernel: all regions, circular) or chained sites (large kernel: circular, one
+// lane stores; the region mask and wave-group records included), 5 chained sites on the constant-rate clock.
+// SITE is the form of the sites a kernel uses for INSTR (kp::site<>; 6: chained).
 #define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR != 0) kp::site<SITE>(ring, end_r, start_r); } while (0)
-// The same for a kernel whose lean sites are deferred (SITE 4): the clock read goes into pair K and is
-// turned into records at the next KP_COMMIT, which stands right after a wait for all LDS traffic.
-// SITE 6: the sites of the kernel form a chain known at compile time, the loop keeps only their clocks
-// (kp::site_chain / chain_commit) and the records are made when the trace is copied out.
+// The same for the large kernel, whose sites are a fixed sequence: chained, the loop keeps only the clock
+// of site K of the batch (kp::site_chain) and KP_COMMIT, which stands right after a wait for all LDS
+// traffic, stores the batch's clocks; the records are made when the trace is copied out.
 #define KP_SITE_K(ring, K, end_r, start_r) do { if constexpr (INSTR != 0) { \
-    if constexpr (SITE == 6) kp::site_chain<K>(ring); \
-    else if constexpr (SITE == 4) kp::site_defer<K, (INSTR >= 4), (INSTR == 5)>(ring, end_r, start_r); \
-    else kp::site<SITE>(ring, end_r, start_r); } } while (0)
-#define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0) { \
-    if constexpr (SITE == 6) kp::chain_commit<N>(ring); else if constexpr (SITE == 4) kp::sites_commit<N>(ring); } } while (0)
+    if constexpr (SITE == 6) kp::site_chain<K, (INSTR == 5)>(ring); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
+#define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 6) kp::chain_commit<N>(ring); } while (0)
 
-// The chain of the large kernel's record sites (n sites in all).  Threaded schedule: regions 0, 1, 2 in
+// The sequence of the large kernel's record sites (n sites in all).  Threaded schedule: regions 0, 1, 2 in
 // turn, three sites per K step; stages apart: regions 2, 0, 3, 1 in turn, four sites per K step.  The last
 // site of the loop opens the epilogue region instead (3, or 4 with the stages apart), the very last closes it.
 template <bool PHASED>
 struct GemmChain {
-  uint32_t n;
-  __device__ uint32_t in_turn(uint32_t i) const {
+  static constexpr uint32_t kEpilogue = PHASED ? 4u : 3u, kRegions = kEpilogue + 1u;
+  static constexpr bool kDense = true;
+  // n = (3 or 4) K steps + 2: every enabled region of the loop leaves two records per K step, the epilogue two
+  __device__ uint32_t total(uint32_t n, uint32_t mask) const {
+    const uint32_t steps = (n - 2u) / (PHASED ? 4u : 3u);
+    return 2u * steps * (uint32_t)__builtin_popcount(mask & ((1u << kEpilogue) - 1u)) + 2u * ((mask >> kEpilogue) & 1u);
+  }
+  __device__ static uint32_t in_turn(uint32_t i) {
     if constexpr (PHASED) return (0x1302u >> ((i & 3u) * 4u)) & 0xFu;  // 2, 0, 3, 1
     else return i % 3u;
   }
-  __device__ uint32_t end_region(uint32_t site) const { return site + 1u == n ? (PHASED ? 4u : 3u) : in_turn(site - 1u); }
-  __device__ uint32_t start_region(uint32_t site) const { return site + 2u == n ? (PHASED ? 4u : 3u) : in_turn(site); }
+  __device__ uint32_t end_region(uint32_t site, uint32_t n) const {
+    return site == 0u ? kp::kNoRegion : site + 1u == n ? kEpilogue : in_turn(site - 1u);
+  }
+  __device__ uint32_t start_region(uint32_t site, uint32_t n) const {
+    return site + 1u == n ? kp::kNoRegion : site + 2u == n ? kEpilogue : in_turn(site);
+  }
 };
 
 // ------------------------------------------------------------------------------------------
@@ -205,10 +212,10 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // same source without the scheduling fences between the stages (uninstrumented only)
   constexpr bool PHASED = SCHEDULE != 0;
   static_assert(SCHEDULE != 2 || INSTR == 0, "the unfenced stage-by-stage form has no record sites");
-  // INSTR 2: every region, shader clock; 4: the region mask decides (wave-group records included), 5: the
-  // same on the constant-rate clock -- all three with the register-buffered sites; 1 and 3 are the generic
-  // sites, which the flush strategy and the 64-lane store need
-  constexpr int SITE = INSTR == 2 ? 6 : INSTR >= 4 ? 4 : INSTR;
+  // INSTR 2 and 5 (constant-rate clock): chained sites; 1 and 3 are the generic sites, which the flush
+  // strategy and the 64-lane store need
+  static_assert(INSTR != 4, "no such form");
+  constexpr int SITE = (INSTR == 2 || INSTR == 5) ? 6 : INSTR;
   constexpr bool REALTIME = INSTR == 3 || INSTR == 5;
   constexpr int BM = kBigBM, BN = kBigBN, BK = kBigBK;
   constexpr int TN = WAVES == 8 ? 2 : 4;   // 32-column MFMA tiles per wave (wave tile 128 x 32*TN)
@@ -243,7 +250,9 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
                          g.cap_hbm, g.trace, g.n_wg, (uint32_t)WAVES >> g.group_log2, wg, g.group_log2);
   ring.collab = g.collab;
   if constexpr (REALTIME) kp::ring_use_realtime(ring);
-  kp::sites_begin<SITE>(ring);
+  // (with wave groups the host adds 16 bytes behind the ring for the waves that do not record)
+  if constexpr (SITE == 6) kp::chain_begin(ring, (uint32_t)(uintptr_t)ring_lds + ((uint32_t)WAVES >> g.group_log2) * g.cap_lds * 8u);
+  else kp::sites_begin<SITE>(ring);
 
   // ---- global -> register -> LDS mapping ---------------------------------------------------
   // Every thread stages the same share of a K step, so all waves reach the barrier together:
@@ -471,11 +480,9 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
     if constexpr (SITE == 6) {
       kp::chain_commit<2>(ring);  // the sites that opened and closed the epilogue
-      kp::chain_end(ring);
-      kp::ring_finish<false>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, GemmChain<PHASED>{ring.cw});
+      kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, GemmChain<PHASED>{});
     } else {
-      if constexpr (SITE == 4) kp::deferred_end<2, PHASED ? 4 : 3>(ring);  // the sites that opened and closed the epilogue
-      else kp::sites_end<SITE>(ring);
+      kp::sites_end<SITE>(ring);
       kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
     }
   }
@@ -584,17 +591,16 @@ extern "C" kp_status kp_gemm_instrumented(const void* A, const void* B, void* C,
     return kp::fail(KP_ERR_TRACE_TOO_SMALL, "trace_cap/streams = %zu must be a power of two >= 2", cap_wave);
   uint32_t cap_lds = (uint32_t)cap_wave;
   if (flush && cap_lds > 64) cap_lds = 64;
-  const size_t ring_bytes = (size_t)cap_lds * 8 * streams;
+  const size_t ring_bytes = (size_t)cap_lds * 8 * streams + (group_log2 ? 16 : 0);  // (16: see chain_begin)
   if (ring_bytes > 32 * 1024) return kp::fail(KP_ERR_UNSUPPORTED_SHAPE, "LDS ring of %zu bytes exceeds the 32 KiB budget", ring_bytes);
   g.cap_lds = cap_lds; g.cap_hbm = (uint32_t)cap_wave; g.rec_cost = kp::rec_cost();
-  // every region, circular, and fewer than 2^20 records per wave (at most 8 per K step): lean record sites
+  // small kernel: every region, circular, and fewer than 2^20 records per wave (6 per K step): lean record sites
   const bool lean = !flush && !group_log2 && !realtime && !collab && regions == (1u << s.regions) - 1u && K <= (1 << 22);
-  // The large kernel buffers its sites in registers whenever the strategy is circular and one lane stores:
-  // with a region mask, wave-group records or the constant-rate clock too (the mask is tested at the site).
-  const bool buffered = !flush && !collab && K <= (1 << 22);
-  if (big) return lean && g.cap_lds >= 8u ? launch_big_w<2>(phased, g, n_wg, ring_bytes, st)
-                : buffered ? (realtime ? launch_big_w<5>(phased, g, n_wg, ring_bytes, st) : launch_big_w<4>(phased, g, n_wg, ring_bytes, st))
-                           : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
+  // The large kernel chains its sites whenever the strategy is circular and one lane stores: the region mask,
+  // wave-group records and the constant-rate clock all keep that form.
+  const bool chained = !flush && !collab;
+  if (big) return chained ? (realtime ? launch_big_w<5>(phased, g, n_wg, ring_bytes, st) : launch_big_w<2>(phased, g, n_wg, ring_bytes, st))
+                          : (realtime ? launch_big_w<3>(phased, g, n_wg, ring_bytes, st) : launch_big_w<1>(phased, g, n_wg, ring_bytes, st));
   if (lean) hipLaunchKernelGGL(kp_gemm_small<2>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else if (realtime) hipLaunchKernelGGL(kp_gemm_small<3>, dim3(n_wg), dim3(256), ring_bytes, st, g);
   else      hipLaunchKernelGGL(kp_gemm_small<1>, dim3(n_wg), dim3(256), ring_bytes, st, g);

@@ -43,11 +43,9 @@ struct Ring {
   uint32_t pend_tag2;  //   (an END and the START that follows it); kNoPending: none
   uint32_t stored;     // records already written to the LDS sub-ring
   uint64_t pend_t;     // its raw 64-bit clock; untouched until the store so nothing waits on s_memtime
-  uint32_t cw;         // lean sites only: tag_wave + records written so far (stands in for cnt)
-  uint32_t slot;       // deferred sites only: commits in the register buffer (lanes in use)
-  uint32_t bts[4], binfo[4];  // deferred sites only, per lane: clocks and packed descriptions of the sites of one commit
-  uint64_t dq_t[4];    // deferred sites only: raw clocks of up to four sites that are not buffered yet
-  uint32_t dq_info[4]; //   and their packed descriptions
+  uint32_t cw;         // lean sites: tag_wave + records written so far (stands in for cnt); chained sites: sites so far
+  uint32_t cmask;      // chained sites only: entries of the clock ring - 1
+  uint64_t dq_t[4];    // chained sites only: raw clocks of up to four sites that are not in the clock ring yet
   uint64_t t_begin;    // workgroup start: s_memtime
   uint64_t rt_begin;   // workgroup start: s_memrealtime (constant rate)
   // flush strategy only
@@ -286,136 +284,32 @@ __device__ __forceinline__ void boundary_fast(Ring& r, uint32_t end_region, uint
 // Before ring_finish() in a kernel that used the lean sites: hand the record count back.
 __device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 
-// A second form of the same site, which does not touch LDS at all, for kernels that wait for all their
-// LDS traffic at a barrier anyway.  Whoever uses a clock value has to wait for everything counted in
-// lgkmcnt, LDS reads and writes in flight included (scalar-memory results come back out of order), and
-// in the middle of a pipelined loop that wait drains the LDS queue.  Here a site only issues the clock
-// read into one of four scalar register pairs (K, a compile-time index) and notes its description;
-// sites_commit<N>(), placed right after the kernel's own "s_waitcnt lgkmcnt(0); s_barrier", moves sites
-// 0..N-1 into the register buffer: lane `slot` of 2 N vector registers takes the clocks and descriptions
-// of one commit (v_writelane from SGPRs, the lane index through M0, set once per commit), and only when
-// the 64 lanes are used up -- and at the end of the kernel -- the buffered sites become records, each lane
-// writing the records of its own commit to the LDS sub-ring.  A site costs the clock read and three scalar
-// instructions, a commit four instructions plus three per site.  The kernel must commit a pair before it
-// issues into it again.  Measured on the 4096^3 GEMM: overhead 4.4 % with the records written to LDS at
-// the next site, 3 % with three deferred sites per K step; the attention kernel, which has no VGPR to
-// spare and whose sites do not sit in the middle of pipelined LDS traffic, keeps the form above.
-//
-// Packed description: bits 15:0 low half of the running counter (tag_wave + sequence number) of the
-// site's first record, bits 23:16 tag byte (phase << 7 | region) of the first record, bits 31:24
-// tag byte of the second record, 0xFF where there is none; all ones: no site.  The host only selects
-// these sites when a wave writes fewer than 2^20 records, so the counter never carries into the wave field.
-
-// Turn the buffered commits (lanes below r.slot) into records of the LDS sub-ring.  Newest wins: a
-// record is left out when a later record of the same batch takes its slot (sub-rings shorter than a
-// batch), because the order of two writes of one instruction to one address is not defined.
-__device__ __forceinline__ void flush_sites(Ring& r) {
-  const uint32_t lane = threadIdx.x & 63u;
-  const bool in = lane < r.slot;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const uint32_t info = r.binfo[k], ts = r.bts[k];
-    const uint32_t c1 = r.cw - ((r.cw - (info & 0xFFFFu)) & 0xFFFFu);  // counter of the site's first record
-    const uint32_t c2 = c1 + 1u;
-    const uint32_t b1 = (info >> 16) & 0xFFu, b2 = info >> 24;
-    if (in && b1 != 0xFFu && r.cw - 1u - c1 <= r.lds_mask) {
-      uint32_t* dst = r.sub + 2u * (c1 & r.lds_mask);
-      dst[0] = (b1 << 24) | c1;
-      dst[1] = ts;
-    }
-    if (in && b2 != 0xFFu && r.cw - 1u - c2 <= r.lds_mask) {
-      uint32_t* dst = r.sub + 2u * (c2 & r.lds_mask);
-      dst[0] = (b2 << 24) | c2;
-      dst[1] = ts;
-    }
-  }
-  r.slot = 0u;
-}
-
-// MASKED: the region mask of the ring decides which of the site's records exist (a site with none
-// still reads the clock and is committed as "no site"); wave-group records come with it, since a wave
-// that does not lead its group has an empty mask.  REALTIME: the constant-rate clock.
-template <int K, bool MASKED = false, bool REALTIME = false>
-__device__ __forceinline__ void site_defer(Ring& r, uint32_t end_region, uint32_t start_region) {
-  static_assert(K >= 0 && K < 4, "four deferred sites at most");
-  __builtin_amdgcn_sched_barrier(0);
-  r.dq_t[K] = sample_clock<REALTIME>();
-  bool on_e = end_region != kNoRegion, on_s = start_region != kNoRegion;  // (scalar; constants without a mask)
-  if constexpr (MASKED) {
-    on_e = on_e && ((r.mask >> (end_region & 31u)) & 1u) != 0u;
-    on_s = on_s && ((r.mask >> (start_region & 31u)) & 1u) != 0u;
-  }
-  // (selects, no branches: tag byte 0xFF stands for "no record", whatever the counter bits beside it say)
-  const uint32_t b1 = on_e ? (0x80u | end_region) : (on_s ? start_region : 0xFFu);
-  const uint32_t b2 = (on_e && on_s) ? start_region : 0xFFu;
-  r.dq_info[K] = (r.cw & 0xFFFFu) | (b1 << 16) | (b2 << 24);
-  r.cw += (on_e ? 1u : 0u) + (on_s ? 1u : 0u);
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// Sites 0..N-1 into lane r.slot of the register buffer.  NMAX is the largest N the kernel commits with:
-// the descriptions N..NMAX-1 of the lane are marked empty (they may hold sites of an earlier batch),
-// those from NMAX up are never written and stay empty.
-template <int N, int NMAX = N>
-__device__ __forceinline__ void sites_commit(Ring& r) {
-  static_assert(N >= 0 && N <= NMAX && NMAX <= 4, "four deferred sites at most");
-  __builtin_amdgcn_sched_barrier(0);
-  // v_writelane takes a single scalar register besides M0, so the lane index goes through M0,
-  // which is put back afterwards (the compiler does not expect inline assembly to change it)
-  uint32_t saved_m0;
-  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0" : "=&s"(saved_m0) : "s"(r.slot));
-#pragma unroll
-  for (int k = 0; k < NMAX; ++k) {
-    if (k < N) {
-      const uint32_t ts = clock_delta(r.dq_t[k], r.t0_lo);
-      asm volatile("v_writelane_b32 %0, %2, m0\n\tv_writelane_b32 %1, %3, m0"
-                   : "+v"(r.bts[k]), "+v"(r.binfo[k]) : "s"(ts), "s"(r.dq_info[k]));
-    } else {
-      asm volatile("v_writelane_b32 %0, -1, m0" : "+v"(r.binfo[k]));
-    }
-  }
-  asm volatile("s_mov_b32 m0, %0" : : "s"(saved_m0));
-  r.slot += 1u;
-  if (r.slot > 63u) flush_sites(r);  // uniform
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-__device__ __forceinline__ void deferred_begin(Ring& r) {
-  r.cw = r.tag_wave;
-  r.slot = 0u;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) { r.bts[k] = 0u; r.binfo[k] = 0xFFFFFFFFu; }
-}
-
-// Before ring_finish(): commit the N sites still in flight, write out the register buffer and hand
-// the record count back.
-template <int N, int NMAX = N>
-__device__ __forceinline__ void deferred_end(Ring& r) {
-  if constexpr (N > 0) sites_commit<N, NMAX>(r);
-  flush_sites(r);
-  r.cnt = r.cw - r.tag_wave;
-  r.stored = r.cnt;
-  r.pend_tag = kNoPending;
-  r.pend_tag2 = kNoPending;
-}
-
-// A third form, for kernels whose record sites form a chain that is known when the kernel is compiled:
-// the first site opens a region, every later site closes the region before it and opens the next, the
-// last one only closes.  Which records site i writes is then a function of i alone, so the loop keeps
-// nothing but the clocks: a site is the clock read into scalar pair K (site_chain<K>, one instruction),
-// and chain_commit<N>() puts the low clock words of sites 0..N-1 of the batch into lanes 0..N-1 of one
-// transient vector register and stores them with a single ds_write_b32 into a ring of 4-byte entries, one
-// per site (13 instructions per commit plus one per site).  The records themselves -- tags and clock minus
-// workgroup start -- are made from that ring when the workgroup copies its trace out (ring_finish with a
-// CHAIN functor that names the two regions of site i).  The ring holds as many sites as the record ring
-// holds records, which covers the sites of the newest cap records.  Measured on the attention kernel
-// (three sites per KV tile): 51 instructions per tile and wave with the records written at the sites
-// cost 10 %, whether they took six LDS instructions or two.
-template <int K>
+// A second form, for kernels whose record sites are a fixed sequence known when the kernel is compiled
+// (site i closes region e(i) and/or opens region s(i), whatever the data): which records site i writes is
+// then a function of i and the region mask alone, so the loop keeps nothing but the clocks.  A site is the
+// clock read into one of four scalar register pairs (site_chain<K>, one instruction; no wait, no LDS
+// traffic, so it can stand in the middle of pipelined LDS traffic), and chain_commit<N>(), placed where
+// the kernel has waited for its LDS traffic anyway, puts the low clock words of sites 0..N-1 of the batch
+// into lanes 0..N-1 of one transient vector register and stores them with a single ds_write_b32 into a
+// ring of 4-byte entries, one per site: about 14 instructions per commit plus one per site, no vector
+// register held across the loop.  The records themselves -- tags, sequence numbers, clock minus workgroup
+// start -- are made from that ring when the workgroup copies its trace out (ring_finish with a CHAIN
+// functor: end_region(i, n) and start_region(i, n) of site i out of n, kNoRegion for none), exactly those
+// the generic sites would have left in the ring: the region mask decides which exist, a wave that does not
+// lead its group writes none, and slot = sequence number modulo capacity.
+// The clock ring has 2 * capacity entries (the LDS the record ring would take), so it covers the newest
+// `capacity` records as long as the enabled records average one per two sites or more, which holds in the
+// kernels here for every mask that enables a region.  Whoever uses a clock value has to wait for
+// everything counted in lgkmcnt, LDS reads and writes in flight included (scalar-memory results come back
+// out of order); the commit is the only place that does.
+// Measured: attention kernel (three sites per KV tile) 10 % with the records written at the sites (51
+// instructions per tile and wave, whether they took six LDS instructions or two) against 3 %; large GEMM
+// with four sites per K step 6-8 % with the sites buffered in vector registers against 3 %.
+template <int K, bool REALTIME = false>
 __device__ __forceinline__ void site_chain(Ring& r) {
   static_assert(K >= 0 && K < 4, "four sites per batch at most");
   __builtin_amdgcn_sched_barrier(0);
-  r.dq_t[K] = sample_clock();
+  r.dq_t[K] = sample_clock<REALTIME>();
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -433,7 +327,7 @@ __device__ __forceinline__ void chain_commit(Ring& r) {
     asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(vt) : "s"((uint32_t)t), "n"(k));
   }
   const uint32_t lane = __builtin_amdgcn_mbcnt_lo(~0u, 0u);  // (the lane index in lanes 0..31, enough for four)
-  const uint32_t addr = r.sub_lds + (((r.cw + lane) & r.lds_mask) << 2);
+  const uint32_t addr = r.sub_lds + (((r.cw + lane) & r.cmask) << 2);
   uint64_t saved_exec;
   asm volatile(
       "s_mov_b64 %0, exec\n\t"
@@ -447,26 +341,45 @@ __device__ __forceinline__ void chain_commit(Ring& r) {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// r.cw counts sites in this form
-__device__ __forceinline__ void chain_begin(Ring& r) { r.cw = 0u; }
-// Before ring_finish(), after the last commit: the first and the last site wrote one record, the others two.
-__device__ __forceinline__ void chain_end(Ring& r) {
-  r.cnt = r.cw >= 2u ? 2u * r.cw - 2u : 0u;
-  r.stored = r.cnt;
-  r.pend_tag = kNoPending;
-  r.pend_tag2 = kNoPending;
+// r.cw counts sites in this form.  A wave that does not write its group's stream stores its clocks to
+// `spare_lds` instead, the LDS byte address of four bytes nobody reads (needed with wave groups only): an
+// instruction sequence that is the same for every wave costs less than two more scalar instructions per commit
+// (measured on the GEMM with four sites per K step: 3 % against 6 %).
+__device__ __forceinline__ void chain_begin(Ring& r, uint32_t spare_lds = 0u) {
+  r.cw = 0u;
+  r.cmask = 2u * r.lds_mask + 1u;
+  if (!r.leader) {  // (uniform)
+    r.sub_lds = spare_lds;
+    r.cmask = 0u;
+  }
 }
 
 struct NoChain {};
 
-// Records of the newest cap_lds sequence numbers from the ring of site clocks, straight to the wave's HBM
-// segment (slot = sequence number modulo capacity, as the record sites would have placed them; slots that
-// were never written are cleared).  Sequence number 0 is the START of site 0; 2 i - 1 and 2 i are the END and
-// the START of site i.
+// Inclusive sum over the lanes of a wave in six data-parallel-primitive adds (shifts inside rows of 16,
+// then the last lane of a row into the rows above); every lane must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);  // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);  // row_bcast:15
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);  // row_bcast:31
+  return v;
+}
+
+// The trace segment of this wave from the ring of site clocks, straight to HBM (slot = sequence number
+// modulo capacity, as the record sites would have placed them; slots that were never written are
+// cleared).  Every lane of the wave takes part.  CHAIN also gives total(n, mask), the records n sites
+// leave under a region mask, and two constants: kRegions, and kDense, which says that every site but the
+// first and the last both closes and opens a region.
+//
+// With every region enabled in a dense sequence the record of a slot follows from the slot alone: the
+// newest sequence number q in that slot, then site (q + 1) / 2, its END for odd q and its START for even q.
 template <class CHAIN>
-__device__ __forceinline__ void chain_copy_out(const Ring& r, uint32_t cap_lds, CHAIN chain) {
+__device__ __forceinline__ void chain_copy_out_dense(const Ring& r, uint32_t cap_lds, CHAIN chain, uint32_t total) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  const uint32_t lane = threadIdx.x & 63u, total = r.cnt;
+  const uint32_t lane = threadIdx.x & 63u, n_sites = r.cw;
   for (uint32_t i = lane * 2; i < cap_lds; i += 128) {  // the capacity is a power of two >= 2
     uint32_t w[4];
 #pragma unroll
@@ -474,11 +387,11 @@ __device__ __forceinline__ void chain_copy_out(const Ring& r, uint32_t cap_lds, 
       const uint32_t slot = i + (uint32_t)h;
       uint32_t tag = 0u, ts = 0u;
       if (slot < total) {
-        const uint32_t q = total - 1u - ((total - 1u - slot) & r.lds_mask);  // the newest record of this slot
+        const uint32_t q = total - 1u - ((total - 1u - slot) & r.lds_mask);
         const uint32_t site = (q + 1u) >> 1, end = q & 1u;
-        const uint32_t region = end ? chain.end_region(site) : chain.start_region(site);
+        const uint32_t region = end ? chain.end_region(site, n_sites) : chain.start_region(site, n_sites);
         tag = (end << 31) | (region << 24) | r.tag_wave | (q & 0xFFFFFu);
-        ts = r.sub[site & r.lds_mask] - r.t0_lo;
+        ts = r.sub[site & r.cmask] - r.t0_lo;
       }
       w[2 * h] = tag; w[2 * h + 1] = ts;
     }
@@ -486,25 +399,66 @@ __device__ __forceinline__ void chain_copy_out(const Ring& r, uint32_t cap_lds, 
   }
 }
 
+// In general the sites are walked from the last one back, 64 at a time, until the newest `cap_lds` records
+// are out: a prefix sum over the lanes says how many records lie behind those of a lane's site.
+template <class CHAIN>
+__device__ __forceinline__ void chain_copy_out(Ring& r, uint32_t cap_lds, CHAIN chain) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const uint32_t lane = threadIdx.x & 63u, n_sites = r.cw;
+  const uint32_t total = chain.total(n_sites, r.mask);
+  r.cnt = total;
+  if constexpr (CHAIN::kDense) {
+    constexpr uint32_t kAll = (1u << CHAIN::kRegions) - 1u;
+    if ((r.mask & kAll) == kAll) {  // (uniform)
+      chain_copy_out_dense(r, cap_lds, chain, total);
+      return;
+    }
+  }
+  for (uint32_t slot = total + lane; slot < cap_lds; slot += 64u)
+    *reinterpret_cast<u32x2*>(r.seg + 2 * (size_t)slot) = u32x2{0u, 0u};
+  uint32_t covered = 0u;  // records newer than the sites still to come
+  for (uint32_t base = n_sites; base > 0u && covered < cap_lds && n_sites - base <= r.cmask; base = base > 64u ? base - 64u : 0u) {
+    const bool in = lane < base && n_sites - base + lane <= r.cmask;  // (its clock is still in the ring)
+    const uint32_t i = in ? base - 1u - lane : 0u;
+    // the regions site i closes and opens, kNoRegion where it does not or the mask says no
+    uint32_t e = in ? chain.end_region(i, n_sites) : kNoRegion;
+    uint32_t s = in ? chain.start_region(i, n_sites) : kNoRegion;
+    if (e != kNoRegion && ((r.mask >> (e & 31u)) & 1u) == 0u) e = kNoRegion;
+    if (s != kNoRegion && ((r.mask >> (s & 31u)) & 1u) == 0u) s = kNoRegion;
+    const uint32_t n = (e != kNoRegion ? 1u : 0u) + (s != kNoRegion ? 1u : 0u);
+    const uint32_t incl = wave_inclusive_sum(n);
+    uint32_t newer = covered + incl - n;  // records behind this site's
+    const uint32_t ts = r.sub[i & r.cmask] - r.t0_lo;
+    if (s != kNoRegion) {  // the START is the later of a site's two records
+      if (newer < cap_lds) {
+        const uint32_t q = total - 1u - newer;
+        *reinterpret_cast<u32x2*>(r.seg + 2 * (size_t)(q & r.lds_mask)) = u32x2{(s << 24) | r.tag_wave | (q & 0xFFFFFu), ts};
+      }
+      newer += 1u;
+    }
+    if (e != kNoRegion && newer < cap_lds) {
+      const uint32_t q = total - 1u - newer;
+      *reinterpret_cast<u32x2*>(r.seg + 2 * (size_t)(q & r.lds_mask)) = u32x2{(1u << 31) | (e << 24) | r.tag_wave | (q & 0xFFFFFu), ts};
+    }
+    covered += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+  }
+}
+
 // MODE 1: generic (region mask, either strategy, either store); MODE 3: generic, on the constant-rate
-// clock; MODE 2: every region enabled, circular strategy, records written to LDS at the next site;
-// MODE 4: the same, deferred sites buffered in registers (the kernel calls site_defer / sites_commit /
-// deferred_end itself).
+// clock; MODE 2: every region enabled, circular strategy, records written to LDS at the next site.
+// (Chained sites are placed with site_chain / chain_commit by the kernel itself.)
 template <int MODE>
 __device__ __forceinline__ void site(Ring& r, uint32_t end_region, uint32_t start_region) {
-  static_assert(MODE == 1 || MODE == 2 || MODE == 3, "deferred sites are placed with site_defer<K>()");
+  static_assert(MODE == 1 || MODE == 2 || MODE == 3, "chained sites are placed with site_chain<K>()");
   if constexpr (MODE == 2) boundary_fast(r, end_region, start_region);
   else boundary<MODE == 3>(r, end_region, start_region);
 }
 template <int MODE>
 __device__ __forceinline__ void sites_begin(Ring& r) {
-  if constexpr (MODE == 4) deferred_begin(r);
-  else if constexpr (MODE == 6) chain_begin(r);
-  else if constexpr (MODE == 2) lean_begin(r);
+  if constexpr (MODE == 2) lean_begin(r);
 }
 template <int MODE>
 __device__ __forceinline__ void sites_end(Ring& r) {
-  static_assert(MODE != 4, "deferred sites end with deferred_end<N>()");
   if constexpr (MODE == 2) lean_end(r);
 }
 

@@ -219,17 +219,18 @@ def test_full_size_attention(kp, oracle_mod):
     assert st["n_invalid"] == 0 and st["n_nonmonotonic"] == 0 and st["n_span_overflow_wgs"] == 0
 
 
-@pytest.mark.parametrize("trace_cap", [16, 64, 1024])
-def test_attention_chain_sites_write_the_generic_sites_records(kp, trace_cap):
-    """With every region enabled the kernel keeps only the clocks of its sites in LDS and makes the records
-    when it copies the trace out (from 8 slots per wave up; below that the records are written at the sites).
-    Slot by slot the tags must be those the generic sites write (KP_MASK_COLLAB selects them), also where the
-    ring wrapped, and along the sequence numbers of a wave the clocks must not decrease."""
+@pytest.mark.parametrize("regions", [0b111, 0b101, 0b010])
+@pytest.mark.parametrize("trace_cap", [8, 64, 1024])
+def test_attention_chained_sites_write_the_generic_sites_records(kp, regions, trace_cap):
+    """The kernel keeps only the clocks of its record sites in LDS and makes the records when it copies the
+    trace out.  Slot by slot the tags must be those the generic sites write (KP_MASK_COLLAB selects them), with
+    a region mask and where the ring wrapped too, and along the sequence numbers of a wave the clocks must
+    not decrease."""
     B, H, S = 1, 2, 640
     q, k, v = inputs.attn_inputs(B, H, S, 128, seed=21)
     dev = (q.cuda(), k.cuda(), v.cuda())
-    _, t_chain, (n_wg, waves, R) = run_attn(kp, q, k, v, True, 0b111, trace_cap=trace_cap, dev=dev)
-    _, t_gen, _ = run_attn(kp, q, k, v, True, 0b111 | kp.KP_MASK_COLLAB, trace_cap=trace_cap, dev=dev)
+    _, t_chain, (n_wg, waves, R) = run_attn(kp, q, k, v, True, regions, trace_cap=trace_cap, dev=dev)
+    _, t_gen, _ = run_attn(kp, q, k, v, True, regions | kp.KP_MASK_COLLAB, trace_cap=trace_cap, dev=dev)
     cap = trace_cap // waves
     a, b = (t.cpu().numpy().view(np.uint32).copy() for t in (t_chain, t_gen))
     assert tuple(a[2:6]) == tuple(b[2:6]) == (n_wg, waves, R, cap)
@@ -240,7 +241,7 @@ def test_attention_chain_sites_write_the_generic_sites_records(kp, trace_cap):
         for j in range(waves):
             total = int(ha[w, 8 + j])
             n = min(total, cap)
-            assert total == 6 * 2 * (S // 128 - w % (S // 128))
+            assert total == 2 * bin(regions).count("1") * 2 * (S // 128 - w % (S // 128))
             assert (ra[w, j, :n, 0] == rb[w, j, :n, 0]).all(), (w, j)
             assert (ra[w, j, n:] == 0).all()
             seq = ra[w, j, :n, 0] & 0xFFFFF

@@ -192,10 +192,9 @@ def test_big_tile_trace_small_k(kp, oracle_mod):
 
 @pytest.mark.parametrize("cap_wave", [2, 16, 64, 256])
 def test_big_tile_lean_sites_with_short_rings(kp, oracle_mod, cap_wave):
-    """With every region enabled the large kernel keeps only the clocks of its sites and makes the records
-    when it copies the trace out; below 8 slots per wave it buffers the sites in registers instead and turns up
-    to 63 of them into records at a time (newest record wins inside such a batch).  Rings that wrap and a
-    ring that holds everything must all decode like the oracle says, with the drop count of the closed form."""
+    """The large kernel keeps only the clocks of its sites (in a ring of twice as many entries as the trace has
+    slots per wave) and makes the records when it copies the trace out.  Rings of two slots, rings that wrap and
+    a ring that holds everything must all decode like the oracle says, with the drop count of the closed form."""
     from tests.gpu_util import assert_stats_equal
 
     K = 2048                                                     # 32 K-steps: 3 sites each, 194 records per wave
@@ -221,12 +220,13 @@ def test_big_tile_lean_sites_with_short_rings(kp, oracle_mod, cap_wave):
     assert_close_to_oracle(c, a, b)
 
 
-@pytest.mark.parametrize("phased", [False, True])
-@pytest.mark.parametrize("cap_wave", [4, 32, 512])
-def test_big_tile_chain_sites_write_the_generic_sites_records(kp, phased, cap_wave):
-    """Records made from the clocks of the sites when the trace is copied out (every region enabled, 8 slots
-    per wave or more; 4 slots: the register-buffered sites) against the records the generic sites write
-    (KP_MASK_COLLAB selects them): the same tag in every slot, for both schedules of the K loop, also where
+@pytest.mark.parametrize("phased,regions", [(False, 0b1111), (False, 0b1011), (False, 0b0100), (False, 0b1000),
+                                            (True, 0b11111), (True, 0b01010), (True, 0b10001)])
+@pytest.mark.parametrize("cap_wave", [2, 32, 512])
+def test_big_tile_chained_sites_write_the_generic_sites_records(kp, phased, regions, cap_wave):
+    """The large kernel keeps only the clocks of its record sites and makes the records when it copies the
+    trace out.  Against the records the generic sites write (KP_MASK_COLLAB selects them): the same record
+    count and the same tag in every slot, for both schedules of the K loop and for region masks, also where
     the ring wrapped; clocks that do not decrease along the sequence numbers of a wave and stay inside the
     workgroup's span; cleared slots behind the last record."""
     K = 1024                                                     # 16 K-steps
@@ -235,7 +235,7 @@ def test_big_tile_chain_sites_write_the_generic_sites_records(kp, phased, cap_wa
     n_wg, waves, _ = kp.kp_gemm_launch_shape(1024, 1024, K)
     assert (n_wg, waves) == (16, 8)
     R = 5 if phased else 4
-    base = ((1 << R) - 1) | (kp.KP_MASK_PHASES if phased else 0)
+    base = regions | (kp.KP_MASK_PHASES if phased else 0)
     raws = []
     for extra in (0, kp.KP_MASK_COLLAB):
         C = torch.empty(1024, 1024, dtype=torch.bfloat16, device="cuda")
@@ -246,13 +246,13 @@ def test_big_tile_chain_sites_write_the_generic_sites_records(kp, phased, cap_wa
     x, y = raws
     assert tuple(x[2:6]) == tuple(y[2:6]) == (n_wg, waves, R, cap_wave)
     hx, hy = (r[16:16 + 32 * n_wg].reshape(n_wg, 32) for r in (x, y))
-    total = 2 * (4 if phased else 3) * (K // 64) + 2
-    assert (hx[:, 8:8 + waves] == total).all() and (hy[:, 8:8 + waves] == total).all()
+    per_step = [2 * bin(regions & 0b0111).count("1"), 2 * bin(regions & 0b01111).count("1")][phased]
+    total = per_step * (K // 64) + 2 * ((regions >> (R - 1)) & 1)
+    assert (hx[:, 8:8 + waves] == total).all() and (hy[:, 8:8 + waves] == total).all() and (hx[:, 8 + waves:24] == 0).all()
     rx, ry = (r[16 + 32 * n_wg:].reshape(n_wg, waves, cap_wave, 2) for r in (x, y))
     n = min(total, cap_wave)
     assert (rx[:, :, :n, 0] == ry[:, :, :n, 0]).all()
-    if cap_wave >= 8:
-        assert (rx[:, :, n:] == 0).all()
+    assert (rx[:, :, n:] == 0).all()
     seq = rx[:, :, :n, 0] & 0xFFFFF
     order = np.argsort(seq, axis=2)
     assert (np.take_along_axis(seq, order, 2) == np.arange(total - n, total)).all()

@@ -87,7 +87,7 @@ def calibrate_unit(kp, oracle_mod, mode):
 
 
 LENGTHS = [256, 1024, 4096, 16384]
-SITE_FORMS = {"generic": 0, "lean": 16, "deferred": 32}
+SITE_FORMS = {"generic": 0, "lean": 16, "chained": 32}
 
 
 def measure_known_lengths(kp, oracle_mod, mode):
@@ -119,7 +119,7 @@ def test_known_lengths_within_3_percent(kp, oracle_mod, form):
 @pytest.mark.skip(reason="64 dependent FMAs are about 450 clock ticks, 3 % of that is 13 ticks; the fixed cost of a region "
                   "(calibrated on a 2048-cycle region of another launch) differs by up to 16 ticks for so short a "
                   "region and the counter advances in steps of 4: measured -3.4 % (generic sites), -2.9 % (lean), "
-                  "+0.5 % (deferred)")
+                  "+0.5 % (sites buffered in registers, an earlier form of the chained ones)")
 @pytest.mark.parametrize("form", list(SITE_FORMS))
 def test_region_of_256_cycles_within_3_percent(kp, oracle_mod, form):
     d, expected = measure_known_lengths(kp, oracle_mod, SITE_FORMS[form])
@@ -281,7 +281,7 @@ def test_wave_group_needs_whole_groups(kp):
     with pytest.raises(kp.KperfError) as e:
         kp.kp_calibrate(CYCLES, 4, 8, 128, buf, 64)  # unknown mode bit
     assert e.value.status == kp.KP_ERR_INVALID_ARG
-    for bad in (16 | 32, 16 | 2, 32 | 4, 16 | 8, 16 | 64):  # two site forms at once; lean / deferred sites with another option
+    for bad in (16 | 32, 16 | 2, 32 | 4, 16 | 8, 16 | 64):  # two site forms at once; lean / chained sites with another option
         with pytest.raises(kp.KperfError) as e:
             kp.kp_calibrate(CYCLES, 4, 8, bad, buf, 64)
         assert e.value.status == kp.KP_ERR_INVALID_ARG
