@@ -5,8 +5,8 @@ One step = one pass of the whole hot path over one batch of seeded synthetic inp
   1. bf16 GEMM 4096^3: one warm launch, then uninstrumented / instrumented (all 4 regions, ring of
      4096 records per workgroup) launched alternately, two of each; then the same for the
      stage-by-stage schedule of the K step with its configured 5 regions (514 records per wave),
-     and two launches each with a region masked off (generic record sites), with the 64-lane store on
-     top of that, and with the constant-rate clock on top of that
+     and two launches each with a region masked off, with the constant-rate clock on top of that, with
+     the 64-lane store (generic record sites) and with the flush strategy
   2. kp_trace_reduce of the GEMM trace
   3. causal attention forward 4x32x4096x128: warm launch, then uninstrumented / instrumented
      (3 regions, ring of 1024 records per workgroup, wraps) alternately, two of each
@@ -479,12 +479,13 @@ def main() -> int:
         },
         "overhead_pct_masked_sites": {
             "value": round(overhead_masked, 3),
-            "what": "default schedule with region 2 masked off (region_mask 0b1011): the register-buffered sites "
-                    "test the mask (a region mask, wave-group records and the constant-rate clock all keep them)",
+            "what": "default schedule with region 2 masked off (region_mask 0b1011): the loop still keeps only the "
+                    "clocks of its sites, and the mask decides which records are made from them when the trace is "
+                    "copied out (a region mask, wave-group records and the constant-rate clock all keep that form)",
             "with_constant_rate_clock": round((ms["gemm_realtime"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0, 3),
         },
         "overhead_pct_generic_sites": {
-            "what": "the generic record sites (records go to LDS at the next site), which the 64-lane store of "
+            "what": "the generic record sites (a site writes its records to LDS at the next site), which the 64-lane store of "
                     "Sec. 4.2 (KP_MASK_COLLAB, region_mask 0b1011, hardware ids in the workgroup header) and the "
                     "flush strategy (KP_MASK_FLUSH, all regions, 64-slot sub-rings copied out when full) need",
             "with_64_lane_store_and_hw_ids": round((ms["gemm_collab"] - ms["gemm_vanilla"]) / ms["gemm_vanilla"] * 100.0, 3),

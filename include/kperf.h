@@ -341,7 +341,8 @@ kp_status kp_stages_critical(const void* stages, int n_wg, int n_regions, int ma
  * records are fully written by the kernel (no pre-zeroing needed; slots beyond total_written
  * hold unspecified bytes).  trace_cap: record slots per workgroup in HBM; trace_cap / streams must
  * be a power of two >= 2, else KP_ERR_TRACE_TOO_SMALL.  Circular: the whole ring also lives in
- * LDS (KP_ERR_UNSUPPORTED_SHAPE if it exceeds the kernel's LDS budget).
+ * LDS (KP_ERR_UNSUPPORTED_SHAPE if it exceeds the kernel's LDS budget: 32 KiB, of which wave-group
+ * records take 16 bytes for themselves).
  */
 #define KP_MASK_FLUSH 0x80000000u
 #define KP_MASK_WAVE_GROUP 0x40000000u

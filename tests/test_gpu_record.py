@@ -118,8 +118,8 @@ def test_known_lengths_within_3_percent(kp, oracle_mod, form):
 
 @pytest.mark.skip(reason="64 dependent FMAs are about 450 clock ticks, 3 % of that is 13 ticks; the fixed cost of a region "
                   "(calibrated on a 2048-cycle region of another launch) differs by up to 16 ticks for so short a "
-                  "region and the counter advances in steps of 4: measured -3.4 % (generic sites), -2.9 % (lean), "
-                  "+0.5 % (sites buffered in registers, an earlier form of the chained ones)")
+                  "region and the counter advances in steps of 4: measured -3.4 % (generic sites), -0.9 % (lean), "
+                  "+4.2 % (chained)")
 @pytest.mark.parametrize("form", list(SITE_FORMS))
 def test_region_of_256_cycles_within_3_percent(kp, oracle_mod, form):
     d, expected = measure_known_lengths(kp, oracle_mod, SITE_FORMS[form])
