@@ -40,13 +40,13 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from hardware counters (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, the factors
 # read off a plain 1 GiB copy); procedure and readings are in profiles/pmc_hbm_traffic.md.
 TRAFFIC_BYTES = {
-    "decode_2^28": (1079627.4 * 2.0 + 37816.8) * 1024,
-    "gemm_vanilla": (98365.0 * 2.0 + 32779.9) * 1024,
-    "attn_vanilla": (196735.5 * 2.0 + 131084.3) * 1024,
-    "timeline_2^28": (1058094.1 * 2.0 + 2085667.0) * 1024,
-    "waits_2^28": (1057476.8 * 2.0 + 33216.0) * 1024,
-    "stages_2^28": (1043571.2 * 2.0 + 274729.3) * 1024,
-    "critical_2^28": (132139.6 * 2.0 + 992.0) * 1024,
+    "decode_2^28": (1079450.8 * 2.0 + 37816.8) * 1024,
+    "gemm_vanilla": (98365.0 * 2.0 + 32796.2) * 1024,
+    "attn_vanilla": (196729.4 * 2.0 + 131100.3) * 1024,
+    "timeline_2^28": (1057962.5 * 2.0 + 2085926.4) * 1024,
+    "waits_2^28": (1056935.8 * 2.0 + 33216.0) * 1024,
+    "stages_2^28": (1043570.7 * 2.0 + 274535.0) * 1024,
+    "critical_2^28": (132139.5 * 2.0 + 992.0) * 1024,
 }
 DECODE_BYTES_PER_RECORD = 8.0 + 16.0 * 16 / 2048 + 128.0 / 16384  # record + per-(wg,wave,region) out + wg header
 
