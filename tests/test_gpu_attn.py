@@ -253,6 +253,49 @@ def test_attention_chained_sites_write_the_generic_sites_records(kp, regions, tr
             assert ts[-1] < span
 
 
+@pytest.mark.parametrize("case", range(8))
+def test_attention_chained_sites_with_every_option(kp, case):
+    """Seeded combinations of region mask, wave-group records, constant-rate clock, causal or not, ring capacity
+    and sequence length: the chained sites must leave the record counts and tags of the generic sites
+    (KP_MASK_COLLAB on top of the same options), slot by slot, and clocks that do not decrease along a stream."""
+    rng = np.random.default_rng(300 + case)
+    regions = int(rng.integers(1, 8))
+    group = bool(rng.integers(2))
+    realtime = bool(rng.integers(2))
+    causal = bool(rng.integers(2))
+    S = int(rng.choice([128, 384, 1024]))
+    cap_wave = int(rng.choice([2, 16, 256]))
+    q, k, v = inputs.attn_inputs(1, 3, S, 128, seed=60 + case)
+    dev = (q.cuda(), k.cuda(), v.cuda())
+    n_wg, waves, R = kp.kp_attn_launch_shape(1, 3, S, 128)
+    streams = 1 if group else waves
+    opts = regions | (kp.KP_MASK_WAVE_GROUP if group else 0) | (kp.KP_MASK_REALTIME if realtime else 0)
+    raws = []
+    for extra in (0, kp.KP_MASK_COLLAB):
+        O = torch.empty(1, 3, S, 128, dtype=torch.bfloat16, device="cuda")
+        trace = torch.full((kp.kp_trace_bytes(n_wg, streams, cap_wave * streams),), 0x5C, dtype=torch.uint8, device="cuda")
+        kp.kp_attn_instrumented(*dev, O, 1, 3, S, 128, causal, 0.09, opts | extra, trace, cap_wave * streams)
+        torch.cuda.synchronize()
+        raws.append(trace.cpu().numpy().view(np.uint32).copy())
+    x, y = raws
+    what = (regions, group, realtime, causal, S, cap_wave)
+    assert tuple(x[2:6]) == tuple(y[2:6]) == (n_wg, streams, R, cap_wave), what
+    hx, hy = (r[16:16 + 32 * n_wg].reshape(n_wg, 32) for r in (x, y))
+    rx, ry = (r[16 + 32 * n_wg:].reshape(n_wg, streams, cap_wave, 2) for r in (x, y))
+    assert (hx[:, 8:24] == hy[:, 8:24]).all(), what
+    blocks = S // 128
+    for w in range(n_wg):
+        tiles = 2 * (blocks - w % blocks) if causal else S // 64
+        total = int(hx[w, 8])
+        assert total == 2 * bin(regions).count("1") * tiles, what
+        n = min(total, cap_wave)
+        assert (rx[w, :, :n, 0] == ry[w, :, :n, 0]).all(), what
+        assert (rx[w, :, n:] == 0).all()
+        order = np.argsort(rx[w, :, :n, 0] & 0xFFFFF, axis=1)
+        ts = np.take_along_axis(rx[w, :, :n, 1], order, 1).astype(np.int64)
+        assert (np.diff(ts, axis=1) >= 0).all() and (ts > 0).all(), what
+
+
 def test_attention_errors(kp):
     t = torch.zeros(1, 1, 128, 128, dtype=torch.bfloat16, device="cuda")
     with pytest.raises(kp.KperfError) as e:

@@ -262,6 +262,53 @@ def test_big_tile_chained_sites_write_the_generic_sites_records(kp, phased, regi
     assert (ts.reshape(n_wg, -1).max(axis=1) < span[:, 0]).all()
 
 
+def _streams_of(raw, n_wg, streams, cap):
+    hdr = raw[16:16 + 32 * n_wg].reshape(n_wg, 32)
+    return hdr, raw[16 + 32 * n_wg:].reshape(n_wg, streams, cap, 2)
+
+
+@pytest.mark.parametrize("case", range(10))
+def test_big_tile_chained_sites_with_every_option(kp, case):
+    """Seeded combinations of schedule, region mask, wave-group records, constant-rate clock, ring capacity and
+    K: the chained sites must leave the record counts and tags of the generic sites (KP_MASK_COLLAB on top of
+    the same options), slot by slot, and clocks that do not decrease along a stream."""
+    rng = np.random.default_rng(100 + case)
+    phased = bool(rng.integers(2))
+    R = 5 if phased else 4
+    regions = int(rng.integers(1, 1 << R))
+    group = bool(rng.integers(2))
+    realtime = bool(rng.integers(2))
+    K = int(rng.choice([64, 192, 1024, 4096]))
+    cap_wave = int(rng.choice([2, 8, 64, 512]))
+    a, b = inputs.gemm_inputs(1024, 1024, K, seed=40 + case)
+    A, B = a.cuda(), b.cuda()
+    n_wg, waves, _ = kp.kp_gemm_launch_shape(1024, 1024, K)
+    assert (n_wg, waves) == (16, 8)
+    streams = waves // 4 if group else waves
+    opts = regions | (kp.KP_MASK_PHASES if phased else 0) | (kp.KP_MASK_WAVE_GROUP if group else 0) | (kp.KP_MASK_REALTIME if realtime else 0)
+    raws = []
+    for extra in (0, kp.KP_MASK_COLLAB):
+        C = torch.empty(1024, 1024, dtype=torch.bfloat16, device="cuda")
+        trace = torch.full((kp.kp_trace_bytes(n_wg, streams, cap_wave * streams),), 0x5C, dtype=torch.uint8, device="cuda")
+        kp.kp_gemm_instrumented(A, B, C, 1024, 1024, K, opts | extra, trace, cap_wave * streams)
+        torch.cuda.synchronize()
+        raws.append(trace.cpu().numpy().view(np.uint32).copy())
+    x, y = raws
+    assert tuple(x[2:6]) == tuple(y[2:6]) == (n_wg, streams, R, cap_wave), (phased, regions, group, realtime, K, cap_wave)
+    (hx, rx), (hy, ry) = (_streams_of(r, n_wg, streams, cap_wave) for r in (x, y))
+    assert (hx[:, 8:24] == hy[:, 8:24]).all()
+    total = int(hx[0, 8])
+    steps = K // 64
+    assert total == 2 * steps * bin(regions & ((1 << (R - 1)) - 1)).count("1") + 2 * ((regions >> (R - 1)) & 1)
+    n = min(total, cap_wave)
+    assert (rx[:, :, :n, 0] == ry[:, :, :n, 0]).all(), (phased, regions, group, realtime, K, cap_wave)
+    assert (rx[:, :, n:] == 0).all()
+    if n:
+        order = np.argsort(rx[:, :, :n, 0] & 0xFFFFF, axis=2)
+        ts = np.take_along_axis(rx[:, :, :n, 1], order, 2).astype(np.int64)
+        assert (np.diff(ts, axis=2) >= 0).all() and (ts > 0).all()
+
+
 @pytest.mark.parametrize("shape,flush", [((1024, 1024, 512), 0), ((1024, 1024, 512), 1), ((128, 128, 256), 0)])
 def test_wave_group_records(kp, oracle_mod, shape, flush):
     """KP_MASK_WAVE_GROUP: one record stream per group of four waves (Sec. 3.1 Granularity, Sec. 4.2
