@@ -9,7 +9,9 @@
 // (one lane writes) is deferred to the next record site, so no site ever waits for the clock
 // value it has just requested (the paper's split into ReadCounterOp and StoreCounterOp,
 // Sec. 3.1).  A region's measured length therefore includes the constant cost of storing its
-// own START record, which the decoder's rec_cost subtracts.
+// own START record, which the decoder's rec_cost subtracts.  Kernels whose sites are a fixed sequence go
+// one step further (chained sites, below): inside the loop they store only the clocks, one 4-byte entry
+// per site, and the records are made from those when the trace is copied out.
 //
 // Circular strategy: the sub-ring is overwritten cyclically and copied to HBM once, at exit.
 // Flush strategy: whenever a sub-ring fills up, its wave copies it to the next chunk of its HBM
