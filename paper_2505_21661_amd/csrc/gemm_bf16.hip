@@ -296,6 +296,29 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, kq >> 1) + (kq & 1u) * 8u) = od;
   };
 
+  // Threaded schedule: the A tile goes from global memory straight to LDS (global_load_lds_dwordx4: lane l of
+  // a wave lands at byte 16 l of a 1 KiB block whose base M0 holds), without staging registers and LDS write
+  // instructions.  Wave w fills blocks 4 w .. 4 w + 3 of a stage's A tile, 8 rows each: lane l is row l / 8 of
+  // the block and chunk position l % 8, and fetches the chunk that the tile's swizzle puts there.  The loads
+  // are issued from inline assembly: the compiler would make the next LDS access of any kind wait for such a
+  // load (it cannot tell the load's destination from the tile being read).  They are therefore not in its
+  // count of outstanding vector-memory operations; they complete in order with the others, so its own waits
+  // stay sufficient (they may wait for more), and the kernel waits for them itself before the barrier.
+  constexpr bool DIRECT = !PHASED;
+  const uint32_t d_lds0 = kp::wave_uniform((uint32_t)(uintptr_t)smem + 4096u * wave);
+  const uint16_t* d_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t row = 32u * wave + 8u * (uint32_t)i + (lane >> 3);
+    const uint32_t chunk = (lane & 7u) ^ ((row >> 1) & 7u);  // tile_off<64>: position = chunk ^ (row / 2) % 8
+    d_src[i] = g.A + (size_t)(m0 + row) * g.K + chunk * 8u;
+  }
+  auto direct_a = [&](uint32_t kt, uint32_t stage, int i) {
+    const uint16_t* src = d_src[i] + (size_t)kt * BK;
+    const uint32_t dst = d_lds0 + stage * STAGE + (uint32_t)i * 1024u;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
+  };
+
   const uint32_t wm = WAVES == 8 ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
   const uint32_t wn = WAVES == 8 ? wave & 3u : wave & 1u;
   f32x16 acc[TN][4];                               // [tn][tm], transposed tiles (rows = n, cols = m)
@@ -306,27 +329,39 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 
   // prologue: K step 0 into stage 0, K step 1 into the staging registers
   const uint32_t KT = g.K / BK;
+  if constexpr (DIRECT) {
+    static_assert(NA == 4 && WAVES == 8 && BK == 64, "four 1 KiB blocks of 8 rows per wave");
 #pragma unroll
-  for (int i = 0; i < NA; ++i) load_a(0, i);
+    for (int i = 0; i < 4; ++i) direct_a(0, 0, i);
+  } else {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) load_a(0, i);
+  }
 #pragma unroll
   for (int i = 0; i < 4 * NB; ++i) load_b(0, i >> 2, i & 3);
+  if constexpr (!DIRECT) {
 #pragma unroll
-  for (int i = 0; i < NA; ++i) store_a(0, i);
+    for (int i = 0; i < NA; ++i) store_a(0, i);
+  }
 #pragma unroll
   for (int i = 0; i < 4 * NB; ++i) store_b(0, i >> 2, i & 3);
+  if constexpr (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the A tile of K step 0 has landed
   if (KT > 1) {
+    if constexpr (!DIRECT) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) load_a(1, i);
+      for (int i = 0; i < NA; ++i) load_a(1, i);
+    }
 #pragma unroll
     for (int i = 0; i < 4 * NB; ++i) load_b(1, i >> 2, i & 3);
   }
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-  // Iteration kt runs the MFMAs of K step kt on LDS stage kt & 1 and, threaded between them, moves
-  // K step kt+1 from the staging registers to the other stage; every register is refilled with its
-  // share of K step kt+2 right after it has been written out, so each load has one whole iteration
-  // to arrive and nothing but the barrier separates two iterations.  The barrier waits for LDS
-  // traffic only, never for the global loads.
+  // Iteration kt runs the MFMAs of K step kt on LDS stage kt & 1.  It starts by sending the A tile of K
+  // step kt+1 from global memory straight to the other stage; threaded between the MFMAs of its second
+  // half, the B share of K step kt+1 moves from the staging registers to that stage, and every register is
+  // refilled with its share of K step kt+2 right after it has been written out, so each of those loads has
+  // one whole iteration to arrive.  At the end the wave waits for its A loads and its LDS traffic, never
+  // for the B loads, then for the other waves.
   // MORE / MORE2 (K step kt+1 / kt+2 exists) are compile-time so that the steady-state body is one
   // basic block: with branches between the pieces the compiler's wait-count tracking gives up and
   // waits for ALL outstanding loads before every LDS write.
@@ -335,11 +370,21 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const uint32_t stage = kt & 1u;
     const unsigned char* sA = smem + stage * STAGE;
     const unsigned char* sB = sA + A_BYTES;
+    if constexpr (DIRECT && MORE) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) direct_a(kt + 1, stage ^ 1u, i);
+      __builtin_amdgcn_sched_barrier(0);  // ahead of every other vector-memory operation of the iteration
+    }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      // ---- region 0: first half of the K step, with the A share of the staging;
-      // ---- region 1: second half, with the B share
-      if (ks == BK / 32) KP_SITE_K(ring, 1, 0, 1);
+      // ---- region 0: first half of the K step (the A tile of the next one is on its way to LDS);
+      // ---- region 1: second half, with the B share of the staging
+      if (ks == BK / 32) {
+        KP_SITE_K(ring, 1, 0, 1);
+        // (without sites: a scheduling fence in the site's place, so that the B share stays in the second half
+        // there too -- its first use of a staging register waits for every load issued before it)
+        if constexpr (DIRECT && INSTR == 0) __builtin_amdgcn_sched_barrier(0);
+      }
       const uint32_t chunk = ks * 2 + (lane >> 5);
       bf16x8 af[4], bfr[TN];
 #pragma unroll
@@ -361,10 +406,12 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
             // MFMA and vector-memory instructions move across): left alone, the scheduler sinks all
             // of them to the end of the iteration and the next iteration waits for them at once.
             if (slot < NA) {                                    // A chunk `slot`: out to LDS, refill
-              if constexpr (MORE) store_a(stage ^ 1u, slot);
-              __builtin_amdgcn_sched_barrier(0x386);
-              if constexpr (MORE2) load_a(kt + 2, slot);
-              __builtin_amdgcn_sched_barrier(0x386);
+              if constexpr (!DIRECT) {
+                if constexpr (MORE) store_a(stage ^ 1u, slot);
+                __builtin_amdgcn_sched_barrier(0x386);
+                if constexpr (MORE2) load_a(kt + 2, slot);
+                __builtin_amdgcn_sched_barrier(0x386);
+              }
             } else if (slot >= S / 2 && slot < S / 2 + 4 * NB) {  // B block j, columns 2w and 2w+1
               const int q = slot - S / 2;
               if constexpr (MORE) store_b(stage ^ 1u, q >> 2, q & 3);
@@ -382,6 +429,12 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     // "wait for LDS, then barrier" would be waited for in full.  The wait for this wave's LDS writes
     // therefore comes first, then the site, then the barrier: the read returns while the wave waits for
     // the others, and the commit behind the barrier waits for it.
+    if constexpr (DIRECT && MORE) {
+      // the A tile of the next K step has landed; the 4 B rows requested after it may still travel
+      static_assert(NB == 1, "four B loads behind the A tile's");
+      if constexpr (MORE2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     KP_SITE_K(ring, 2, 1, 2);
     // ---- region 2: every wave is done with the stage ----------------------------------------------
