@@ -49,7 +49,6 @@ __device__ __forceinline__ void busy(uint32_t mode, uint32_t len, float& x) {
 // records made when the trace is copied out).  The instrumented kernels use all three; a region costs a
 // different constant with each.
 struct CalibChain {  // site 2 r opens region r, site 2 r + 1 closes it (every region enabled)
-  static constexpr uint32_t kRegions = KP_MAX_REGIONS;
   static constexpr bool kDense = false;
   __device__ uint32_t total(uint32_t n, uint32_t) const { return n; }
   __device__ uint32_t end_region(uint32_t site, uint32_t) const { return (site & 1u) ? site >> 1 : kp::kNoRegion; }

@@ -198,9 +198,11 @@ __global__ __launch_bounds__(256) void kp_gemm_small(GemmArgs g) {
 
 // ------------------------------------------------------------------------------------------
 // 256x256x64 tile, 8 waves as 2 (M) x 4 (N); each wave owns 128x64 of C as 4x2 MFMA tiles.
-// LDS holds two stages of the A tile [256][64] and of the transposed B tile [256 n][64 k]
-// (128 KiB); the K loop is software-pipelined over the two stages: while the MFMAs consume
-// stage s, K step +1 moves from registers to stage s^1 and the global loads of K step +2 are in flight.
+// LDS holds two stages of the A tile [256][64] and of the B tile (128 KiB); the K loop is software-pipelined
+// over the two stages.  Default schedule: while the MFMAs consume stage s, the tiles of K step +1 travel from
+// global memory straight to stage s^1 (no staging registers; B stays row-major and is transposed by the LDS
+// read).  Stage-by-stage schedule: K step +1 moves from staging registers to stage s^1 (B transposed in
+// registers into a [256 n][64 k] tile) and the global loads of K step +2 are in flight.
 // MFMA operands are swapped (B^T rows as the first operand) so that a lane ends up with four
 // consecutive columns of one C row per accumulator quad and can store them as 8 bytes.
 constexpr int kBigBM = 256, kBigBN = 256, kBigBK = 64;
@@ -254,7 +256,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   if constexpr (SITE == 6) kp::chain_begin(ring, (uint32_t)(uintptr_t)ring_lds + ((uint32_t)WAVES >> g.group_log2) * g.cap_lds * 8u);
   else kp::sites_begin<SITE>(ring);
 
-  // ---- global -> register -> LDS mapping ---------------------------------------------------
+  // ---- global -> register -> LDS mapping (stage-by-stage schedule) ---------------------------
   // Every thread stages the same share of a K step, so all waves reach the barrier together:
   //   A: 256 rows x 8 chunks of 16 bytes; thread t takes chunk (t & 7) of rows (t >> 3) + (T/8)*i;
   //   B: blocks of 4 k x 8 n, 16 x 32 of them; thread t takes blocks t + T*j (k quad id >> 5, n block
@@ -296,7 +298,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     *reinterpret_cast<u32x2*>(sB + tile_off_bt(n + 1u, kq >> 1) + (kq & 1u) * 8u) = od;
   };
 
-  // Threaded schedule: the A tile goes from global memory straight to LDS (global_load_lds_dwordx4: lane l of
+  // ---- global -> LDS (default schedule) ------------------------------------------------------
+  // The A tile goes from global memory straight to LDS (global_load_lds_dwordx4: lane l of
   // a wave lands at byte 16 l of a 1 KiB block whose base M0 holds), without staging registers and LDS write
   // instructions.  Wave w fills blocks 4 w .. 4 w + 3 of a stage's A tile, 8 rows each: lane l is row l / 8 of
   // the block and chunk position l % 8, and fetches the chunk that the tile's swizzle puts there.  The loads
@@ -319,122 +322,144 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
   };
 
+  // The B tile likewise, as it lies in memory: 64 rows (k) of 256 n, 512 bytes each; chunk c (8 n) of row k at
+  // chunk position c ^ 4 (k % 4).  Wave w fills blocks 4 w .. 4 w + 3 of 1 KiB, two rows each.
+  const uint16_t* db_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t row = 8u * wave + 2u * (uint32_t)i + (lane >> 5);
+    const uint32_t chunk = (lane & 31u) ^ (4u * (row & 3u));
+    db_src[i] = g.B + (size_t)row * g.N + n0 + chunk * 8u;
+  }
+  auto direct_b = [&](uint32_t kt, uint32_t stage, int i) {
+    const uint16_t* src = db_src[i] + (size_t)kt * BK * g.N;
+    const uint32_t dst = d_lds0 + stage * STAGE + A_BYTES + (uint32_t)i * 1024u;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
+  };
+
   const uint32_t wm = WAVES == 8 ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
   const uint32_t wn = WAVES == 8 ? wave & 3u : wave & 1u;
+  // Operand reads of the row-major B tile: ds_read_b64_tr_b16 hands lane j of a group of 16 lanes the elements
+  // j, 16 + j, 32 + j, 48 + j of the 64 that the group's lanes address (4 each, lane after lane).  With lane i
+  // of a group addressing B[k0 + i / 4][n0 + 4 (i % 4) ..+3], lane j receives B[k0 .. k0 + 3][n0 + j]: four
+  // consecutive k of one column; two such reads make the eight k of the lane's MFMA operand.  Groups 0 and 1 are
+  // columns 0-15 and 16-31 of the k octet 0, groups 2 and 3 the same columns of octet 1.
+  uint32_t b_rd[TN];
+  {
+    const uint32_t bi = lane & 15u, bg = lane >> 4;
+    const uint32_t k = 8u * (bg >> 1) + (bi >> 2);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const uint32_t n = wn * (32 * TN) + (uint32_t)tn * 32u + 16u * (bg & 1u) + 4u * (bi & 3u);
+      b_rd[tn] = k * 512u + ((((n >> 3) ^ (4u * (bi >> 2)))) << 4) + 8u * ((n >> 2) & 1u);
+    }
+  }
+  auto read_b = [&](const unsigned char* sBt, int ks, int tn) -> bf16x8 {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+    const unsigned char* at = sBt + b_rd[tn] + (uint32_t)(16 * ks) * 512u;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(at));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(at + 4u * 512u));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
   f32x16 acc[TN][4];                               // [tn][tm], transposed tiles (rows = n, cols = m)
 #pragma unroll
   for (int a = 0; a < TN; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = f32x16{0};
 
-  // prologue: K step 0 into stage 0, K step 1 into the staging registers
+  // prologue: K step 0 into stage 0 (and, stage by stage, K step 1 into the staging registers)
   const uint32_t KT = g.K / BK;
   if constexpr (DIRECT) {
-    static_assert(NA == 4 && WAVES == 8 && BK == 64, "four 1 KiB blocks of 8 rows per wave");
+    static_assert(WAVES == 8 && BK == 64, "four 1 KiB blocks of either tile per wave");
 #pragma unroll
     for (int i = 0; i < 4; ++i) direct_a(0, 0, i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) direct_b(0, 0, i);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tiles of K step 0 have landed
   } else {
 #pragma unroll
     for (int i = 0; i < NA; ++i) load_a(0, i);
-  }
 #pragma unroll
-  for (int i = 0; i < 4 * NB; ++i) load_b(0, i >> 2, i & 3);
-  if constexpr (!DIRECT) {
+    for (int i = 0; i < 4 * NB; ++i) load_b(0, i >> 2, i & 3);
 #pragma unroll
     for (int i = 0; i < NA; ++i) store_a(0, i);
-  }
 #pragma unroll
-  for (int i = 0; i < 4 * NB; ++i) store_b(0, i >> 2, i & 3);
-  if constexpr (DIRECT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the A tile of K step 0 has landed
-  if (KT > 1) {
-    if constexpr (!DIRECT) {
+    for (int i = 0; i < 4 * NB; ++i) store_b(0, i >> 2, i & 3);
+    if (KT > 1) {
 #pragma unroll
       for (int i = 0; i < NA; ++i) load_a(1, i);
-    }
 #pragma unroll
-    for (int i = 0; i < 4 * NB; ++i) load_b(1, i >> 2, i & 3);
+      for (int i = 0; i < 4 * NB; ++i) load_b(1, i >> 2, i & 3);
+    }
   }
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-  // Iteration kt runs the MFMAs of K step kt on LDS stage kt & 1.  It starts by sending the A tile of K
-  // step kt+1 from global memory straight to the other stage; threaded between the MFMAs of its second
-  // half, the B share of K step kt+1 moves from the staging registers to that stage, and every register is
-  // refilled with its share of K step kt+2 right after it has been written out, so each of those loads has
-  // one whole iteration to arrive.  At the end the wave waits for its A loads and its LDS traffic, never
-  // for the B loads, then for the other waves.
-  // MORE / MORE2 (K step kt+1 / kt+2 exists) are compile-time so that the steady-state body is one
-  // basic block: with branches between the pieces the compiler's wait-count tracking gives up and
-  // waits for ALL outstanding loads before every LDS write.
+  // Default schedule.  Iteration kt runs the MFMAs of K step kt on LDS stage kt & 1.  It starts by sending
+  // both tiles of K step kt+1 from global memory to the other stage, eight loads per wave that have the whole
+  // iteration to land; the wave waits for them, and for its LDS reads, right before the barrier.  The operands
+  // of MFMA step ks+1 are requested before the MFMAs of step ks are issued, and the MFMAs of a K step's last
+  // step are issued behind the barrier, after the loads and the first operand reads of the next iteration:
+  // a wave comes back from the barrier with matrix work at hand while the first operands of the new stage
+  // are on their way.
+  // MORE (K step kt+1 exists) is compile-time so that the steady-state body is one basic block.
+  // operands of the last MFMA step of a K step: its MFMAs are issued behind the barrier, in the next iteration
+  bf16x8 af_p[4], bf_p[TN];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) af_p[i] = bf16x8{0};
+#pragma unroll
+  for (int i = 0; i < TN; ++i) bf_p[i] = bf16x8{0};
+  auto mfma_pending = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < 4; ++tm)
+        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_p[tn], af_p[tm], acc[tn][tm], 0, 0, 0);
+  };
   auto iteration = [&](uint32_t kt, auto more_c, auto more2_c) {
-    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value;
+    constexpr bool MORE = decltype(more_c)::value;
     const uint32_t stage = kt & 1u;
     const unsigned char* sA = smem + stage * STAGE;
     const unsigned char* sB = sA + A_BYTES;
-    if constexpr (DIRECT && MORE) {
+    if constexpr (MORE) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) direct_a(kt + 1, stage ^ 1u, i);
-      __builtin_amdgcn_sched_barrier(0);  // ahead of every other vector-memory operation of the iteration
-    }
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      // ---- region 0: first half of the K step (the A tile of the next one is on its way to LDS);
-      // ---- region 1: second half, with the B share of the staging
-      if (ks == BK / 32) {
-        KP_SITE_K(ring, 1, 0, 1);
-        // (without sites: a scheduling fence in the site's place, so that the B share stays in the second half
-        // there too -- its first use of a staging register waits for every load issued before it)
-        if constexpr (DIRECT && INSTR == 0) __builtin_amdgcn_sched_barrier(0);
-      }
-      const uint32_t chunk = ks * 2 + (lane >> 5);
-      bf16x8 af[4], bfr[TN];
+      for (int i = 0; i < 4; ++i) direct_b(kt + 1, stage ^ 1u, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // operands of MFMA step ks + 1 are requested before the MFMAs of step ks are issued
+    bf16x8 af[2][4], bfr[2][TN];
+    auto read_step = [&](int ks, int buf) __attribute__((always_inline)) {
+      const uint32_t chunk = (uint32_t)ks * 2u + (lane >> 5);
 #pragma unroll
       for (int tm = 0; tm < 4; ++tm)
-        af[tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
+        af[buf][tm] = *reinterpret_cast<const bf16x8*>(sA + tile_off<BK>(wm * 128 + tm * 32 + (lane & 31u), chunk));
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) bfr[buf][tn] = read_b(sB, ks, tn);
+    };
+    read_step(0, 0);
+    mfma_pending();  // the last MFMA step of the K step before (zeros the first time)
+#pragma unroll
+    for (int ks = 0; ks + 1 < BK / 16; ++ks) {
+      // ---- region 0: first half of the K step; region 1: second half
+      if (ks == 1) KP_SITE_K(ring, 1, 0, 1);  // 16 MFMAs on either side
+      read_step(ks + 1, (ks + 1) & 1);
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
-        bfr[tn] = *reinterpret_cast<const bf16x8*>(sB + tile_off_bt(wn * (32 * TN) + tn * 32 + (lane & 31u), chunk));
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
+        for (int tm = 0; tm < 4; ++tm)
+          acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][tn], af[ks & 1][tm], acc[tn][tm], 0, 0, 0);
+    }
 #pragma unroll
-        for (int tm = 0; tm < 4; ++tm) {
-          acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tn], af[tm], acc[tn][tm], 0, 0, 0);
-          // one staging piece after every second MFMA: 8*TN slots per K step, NA + 8*NB used
-          if (tm & 1) {
-            constexpr int S = 8 * TN;
-            const int slot = ks * (2 * TN) + tn * 2 + (tm >> 1);
-            // The global loads keep their place between the MFMAs (the two fences let everything but
-            // MFMA and vector-memory instructions move across): left alone, the scheduler sinks all
-            // of them to the end of the iteration and the next iteration waits for them at once.
-            if (slot < NA) {                                    // A chunk `slot`: out to LDS, refill
-              if constexpr (!DIRECT) {
-                if constexpr (MORE) store_a(stage ^ 1u, slot);
-                __builtin_amdgcn_sched_barrier(0x386);
-                if constexpr (MORE2) load_a(kt + 2, slot);
-                __builtin_amdgcn_sched_barrier(0x386);
-              }
-            } else if (slot >= S / 2 && slot < S / 2 + 4 * NB) {  // B block j, columns 2w and 2w+1
-              const int q = slot - S / 2;
-              if constexpr (MORE) store_b(stage ^ 1u, q >> 2, q & 3);
-            } else if (slot >= S / 2 + 4 * NB && slot < S / 2 + 8 * NB) {  // B rows: refill
-              const int q = slot - S / 2 - 4 * NB;
-              __builtin_amdgcn_sched_barrier(0x386);
-              if constexpr (MORE2) load_b(kt + 2, q >> 2, q & 3);
-              __builtin_amdgcn_sched_barrier(0x386);
-            }
-          }
-        }
-      }
-    }
-    // The clock read of a site counts in the same counter as LDS traffic, so a read issued in front of
-    // "wait for LDS, then barrier" would be waited for in full.  The wait for this wave's LDS writes
-    // therefore comes first, then the site, then the barrier: the read returns while the wave waits for
-    // the others, and the commit behind the barrier waits for it.
-    if constexpr (DIRECT && MORE) {
-      // the A tile of the next K step has landed; the 4 B rows requested after it may still travel
-      static_assert(NB == 1, "four B loads behind the A tile's");
-      if constexpr (MORE2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+    for (int i = 0; i < 4; ++i) af_p[i] = af[(BK / 16 - 1) & 1][i];
+#pragma unroll
+    for (int i = 0; i < TN; ++i) bf_p[i] = bfr[(BK / 16 - 1) & 1][i];
+    // the tiles of the next K step have landed (no other vector-memory operation is in flight in the loop)
+    if constexpr (MORE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     KP_SITE_K(ring, 2, 1, 2);
     // ---- region 2: every wave is done with the stage ----------------------------------------------
@@ -509,6 +534,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
     if (KT >= 2) iteration(KT - 2, yes, no);
     iteration(KT - 1, no, no);
+    mfma_pending();
   }
 
   // ---- region 3 (4 with the stages apart): epilogue ---------------------------------------------------

@@ -373,8 +373,8 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
 // The trace segment of this wave from the ring of site clocks, straight to HBM (slot = sequence number
 // modulo capacity, as the record sites would have placed them; slots that were never written are
 // cleared).  Every lane of the wave takes part.  CHAIN also gives total(n, mask), the records n sites
-// leave under a region mask, and two constants: kRegions, and kDense, which says that every site but the
-// first and the last both closes and opens a region.
+// leave under a region mask, and kDense, which says that every site but the first and the last both closes and
+// opens a region (such a sequence also states kRegions, the number of its regions).
 //
 // With every region enabled in a dense sequence the record of a slot follows from the slot alone: the
 // newest sequence number q in that slot, then site (q + 1) / 2, its END for odd q and its START for even q.
