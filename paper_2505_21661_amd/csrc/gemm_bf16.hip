@@ -316,12 +316,6 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const uint32_t chunk = (lane & 7u) ^ ((row >> 1) & 7u);  // tile_off<64>: position = chunk ^ (row / 2) % 8
     d_src[i] = g.A + (size_t)(m0 + row) * g.K + chunk * 8u;
   }
-  auto direct_a = [&](uint32_t kt, uint32_t stage, int i) {
-    const uint16_t* src = d_src[i] + (size_t)kt * BK;
-    const uint32_t dst = d_lds0 + stage * STAGE + (uint32_t)i * 1024u;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
-  };
-
   // The B tile likewise, as it lies in memory: 64 rows (k) of 256 n, 512 bytes each; chunk c (8 n) of row k at
   // chunk position c ^ 4 (k % 4).  Wave w fills blocks 4 w .. 4 w + 3 of 1 KiB, two rows each.
   const uint16_t* db_src[4];
@@ -331,10 +325,21 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const uint32_t chunk = (lane & 31u) ^ (4u * (row & 3u));
     db_src[i] = g.B + (size_t)row * g.N + n0 + chunk * 8u;
   }
-  auto direct_b = [&](uint32_t kt, uint32_t stage, int i) {
-    const uint16_t* src = db_src[i] + (size_t)kt * BK * g.N;
-    const uint32_t dst = d_lds0 + stage * STAGE + A_BYTES + (uint32_t)i * 1024u;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
+  // One load: M0 (the LDS base) is put back afterwards, the compiler does not expect inline assembly to change
+  // it; one wait state between the write of M0 and the load that uses it.  The eight loads of a K step stay
+  // separate statements: issued back to back from one block of assembly they made the uninstrumented kernel 4 %
+  // slower (the address arithmetic of the next load no longer sits between two loads).
+  auto direct_load = [&](const uint16_t* src, uint32_t dst) {
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(src), "s"(dst) : "memory");
+  };
+  auto direct_tiles = [&](uint32_t kt, uint32_t stage) {
+    const uint32_t dst = d_lds0 + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) direct_load(d_src[i] + (size_t)kt * BK, dst + (uint32_t)i * 1024u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) direct_load(db_src[i] + (size_t)kt * BK * g.N, dst + A_BYTES + (uint32_t)i * 1024u);
   };
 
   const uint32_t wm = WAVES == 8 ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
@@ -375,10 +380,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   const uint32_t KT = g.K / BK;
   if constexpr (DIRECT) {
     static_assert(WAVES == 8 && BK == 64, "four 1 KiB blocks of either tile per wave");
-#pragma unroll
-    for (int i = 0; i < 4; ++i) direct_a(0, 0, i);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) direct_b(0, 0, i);
+    direct_tiles(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the tiles of K step 0 have landed
   } else {
 #pragma unroll
@@ -425,10 +427,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const unsigned char* sA = smem + stage * STAGE;
     const unsigned char* sB = sA + A_BYTES;
     if constexpr (MORE) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) direct_a(kt + 1, stage ^ 1u, i);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) direct_b(kt + 1, stage ^ 1u, i);
+      direct_tiles(kt + 1, stage ^ 1u);
       __builtin_amdgcn_sched_barrier(0);
     }
     // operands of MFMA step ks + 1 are requested before the MFMAs of step ks are issued
