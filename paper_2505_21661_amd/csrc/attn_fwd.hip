@@ -78,7 +78,7 @@ __device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) {
 
 // The sequence of record sites: one ahead of the loop (opens region 0), three per KV tile, the last only closes.
 struct AttnChain {
-  static constexpr uint32_t kRegions = 3u;
+  static constexpr uint32_t kRegions = 3u, kLead = 0u;
   static constexpr bool kDense = true;
   // n = 3 tiles + 1: every enabled region leaves two records per tile
   __device__ uint32_t total(uint32_t n, uint32_t mask) const { return 2u * ((n - 1u) / 3u) * (uint32_t)__builtin_popcount(mask & 7u); }

@@ -84,16 +84,21 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
     if constexpr (SITE == 6) kp::site_chain<K, (INSTR == 5)>(ring); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
 #define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 6) kp::chain_commit<N>(ring); } while (0)
 
-// The sequence of the large kernel's record sites (n sites in all).  Threaded schedule: regions 0, 1, 2 in
-// turn, three sites per K step; stages apart: regions 2, 0, 3, 1 in turn, four sites per K step.  The last
-// site of the loop opens the epilogue region instead (3, or 4 with the stages apart), the very last closes it.
+// The sequence of the large kernel's record sites (n sites in all).  Default schedule: regions 0, 1, 2 in turn,
+// three sites per K step; site 0 writes no record, it only fills the first place of the first batch, so that
+// every batch of the loop is "the site in front of the last barrier, the one behind it and the one in the
+// middle of this K step" and is committed before the next site in front of a barrier is sampled: no commit
+// waits for a clock it has just asked for, which on the last wave to reach the barrier would be time on the
+// critical path of every K step.  Stages apart: regions 2, 0, 3, 1 in turn, four sites per K step, committed
+// behind the barrier (every wave waits there in region 1 anyway); no leading site.  The last site of the loop
+// opens the epilogue region instead (3, or 4 with the stages apart), the very last closes it.
 template <bool PHASED>
 struct GemmChain {
-  static constexpr uint32_t kEpilogue = PHASED ? 4u : 3u, kRegions = kEpilogue + 1u;
+  static constexpr uint32_t kEpilogue = PHASED ? 4u : 3u, kRegions = kEpilogue + 1u, kLead = PHASED ? 0u : 1u;
   static constexpr bool kDense = true;
-  // n = (3 or 4) K steps + 2: every enabled region of the loop leaves two records per K step, the epilogue two
+  // n = kLead + (3 or 4) K steps + 2: every enabled region of the loop leaves two records per K step, the epilogue two
   __device__ uint32_t total(uint32_t n, uint32_t mask) const {
-    const uint32_t steps = (n - 2u) / (PHASED ? 4u : 3u);
+    const uint32_t steps = (n - 2u - kLead) / (PHASED ? 4u : 3u);
     return 2u * steps * (uint32_t)__builtin_popcount(mask & ((1u << kEpilogue) - 1u)) + 2u * ((mask >> kEpilogue) & 1u);
   }
   __device__ static uint32_t in_turn(uint32_t i) {
@@ -101,10 +106,10 @@ struct GemmChain {
     else return i % 3u;
   }
   __device__ uint32_t end_region(uint32_t site, uint32_t n) const {
-    return site == 0u ? kp::kNoRegion : site + 1u == n ? kEpilogue : in_turn(site - 1u);
+    return site <= kLead ? kp::kNoRegion : site + 1u == n ? kEpilogue : in_turn(site - 1u - kLead);
   }
   __device__ uint32_t start_region(uint32_t site, uint32_t n) const {
-    return site + 1u == n ? kp::kNoRegion : site + 2u == n ? kEpilogue : in_turn(site);
+    return (site < kLead || site + 1u == n) ? kp::kNoRegion : site + 2u == n ? kEpilogue : in_turn(site - kLead);
   }
 };
 
@@ -334,6 +339,11 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
                  : "=&s"(saved_m0) : "v"(src), "s"(dst) : "memory");
   };
+  auto direct_one = [&](uint32_t kt, uint32_t stage, int idx) {
+    const uint32_t dst = d_lds0 + stage * STAGE;
+    if (idx < 4) direct_load(d_src[idx] + (size_t)kt * BK, dst + (uint32_t)idx * 1024u);
+    else direct_load(db_src[idx - 4] + (size_t)kt * BK * g.N, dst + A_BYTES + (uint32_t)(idx - 4) * 1024u);
+  };
   auto direct_tiles = [&](uint32_t kt, uint32_t stage) {
     const uint32_t dst = d_lds0 + stage * STAGE;
 #pragma unroll
@@ -426,10 +436,6 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     const uint32_t stage = kt & 1u;
     const unsigned char* sA = smem + stage * STAGE;
     const unsigned char* sB = sA + A_BYTES;
-    if constexpr (MORE) {
-      direct_tiles(kt + 1, stage ^ 1u);
-      __builtin_amdgcn_sched_barrier(0);
-    }
     // operands of MFMA step ks + 1 are requested before the MFMAs of step ks are issued
     bf16x8 af[2][4], bfr[2][TN];
     auto read_step = [&](int ks, int buf) __attribute__((always_inline)) {
@@ -441,30 +447,51 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       for (int tn = 0; tn < TN; ++tn) bfr[buf][tn] = read_b(sB, ks, tn);
     };
     read_step(0, 0);
-    mfma_pending();  // the last MFMA step of the K step before (zeros the first time)
+    // the last MFMA step of the K step before (zeros the first time); one load of the next K step's tiles
+    // behind every second MFMA of the first sixteen: the loads of all waves queue up in one unit of the CU,
+    // and a wave that issues its eight in a row waits there with no matrix work in flight
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < 4; ++tm) {
+        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_p[tn], af_p[tm], acc[tn][tm], 0, 0, 0);
+        if constexpr (MORE) if (tm & 1) {
+          __builtin_amdgcn_sched_barrier(0);
+          direct_one(kt + 1, stage ^ 1u, tn * 2 + (tm >> 1));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
 #pragma unroll
     for (int ks = 0; ks + 1 < BK / 16; ++ks) {
       // ---- region 0: first half of the K step; region 1: second half
-      if (ks == 1) KP_SITE_K(ring, 1, 0, 1);  // 16 MFMAs on either side
+      if (ks == 1) KP_SITE_K(ring, 2, 0, 1);  // 16 MFMAs on either side
       read_step(ks + 1, (ks + 1) & 1);
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int tm = 0; tm < 4; ++tm)
+        for (int tm = 0; tm < 4; ++tm) {
           acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][tn], af[ks & 1][tm], acc[tn][tm], 0, 0, 0);
+          if constexpr (MORE) if (ks == 0 && (tm & 1)) {
+            __builtin_amdgcn_sched_barrier(0);
+            direct_one(kt + 1, stage ^ 1u, 4 + tn * 2 + (tm >> 1));
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) af_p[i] = af[(BK / 16 - 1) & 1][i];
 #pragma unroll
     for (int i = 0; i < TN; ++i) bf_p[i] = bfr[(BK / 16 - 1) & 1][i];
     // the tiles of the next K step have landed (no other vector-memory operation is in flight in the loop)
+    KP_COMMIT(ring, 3);  // the site in front of the barrier before, the one behind it and the one in the middle
     if constexpr (MORE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    KP_SITE_K(ring, 2, 1, 2);
+    KP_SITE_K(ring, 0, 1, 2);
     // ---- region 2: every wave is done with the stage ----------------------------------------------
-    asm volatile("s_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
-    KP_COMMIT(ring, 3);  // the site that opened this K step, the one in its middle and the one above
-    if constexpr (MORE) KP_SITE_K(ring, 0, 2, 0); else KP_SITE_K(ring, 0, 2, 3);
+    // (chained sites: nothing behind the barrier uses the clock just asked for, so nothing waits for it there)
+    if constexpr (SITE == 1 || SITE == 3) asm volatile("s_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_barrier" ::: "memory");
+    if constexpr (MORE) KP_SITE_K(ring, 1, 2, 0); else KP_SITE_K(ring, 1, 2, 3);
   };
   // The same K step with its stages one after the other, each a region of its own (the stage-by-stage
   // instrumentation of a software-pipelined GEMM, Sec. 5.3): 2 the staging registers (K step kt+1) go to
@@ -529,7 +556,8 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     if (KT >= 2) iteration_phased(KT - 2, yes, no);
     iteration_phased(KT - 1, no, no);
   } else {
-    KP_SITE_K(ring, 0, kp::kNoRegion, 0);
+    if constexpr (SITE == 6) kp::site_chain<0, REALTIME>(ring);  // (fills the first place of the first batch)
+    KP_SITE_K(ring, 1, kp::kNoRegion, 0);
     for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
     if (KT >= 2) iteration(KT - 2, yes, no);
     iteration(KT - 1, no, no);
@@ -553,11 +581,12 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_SITE_K(ring, 1, PHASED ? 4 : 3, kp::kNoRegion);
+  KP_SITE_K(ring, PHASED ? 1 : 2, PHASED ? 4 : 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
     if constexpr (SITE == 6) {
-      kp::chain_commit<2>(ring);  // the sites that opened and closed the epilogue
+      // the sites that opened and closed the epilogue and, in the default schedule, the one in front of the last barrier
+      kp::chain_commit<PHASED ? 2 : 3>(ring);
       kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, GemmChain<PHASED>{});
     } else {
       kp::sites_end<SITE>(ring);

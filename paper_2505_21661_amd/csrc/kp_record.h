@@ -377,7 +377,8 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
 // opens a region (such a sequence also states kRegions, the number of its regions).
 //
 // With every region enabled in a dense sequence the record of a slot follows from the slot alone: the
-// newest sequence number q in that slot, then site (q + 1) / 2, its END for odd q and its START for even q.
+// newest sequence number q in that slot, then site (q + 1) / 2 (behind kLead leading sites without records),
+// its END for odd q and its START for even q.
 template <class CHAIN>
 __device__ __forceinline__ void chain_copy_out_dense(const Ring& r, uint32_t cap_lds, CHAIN chain, uint32_t total) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -390,7 +391,7 @@ __device__ __forceinline__ void chain_copy_out_dense(const Ring& r, uint32_t cap
       uint32_t tag = 0u, ts = 0u;
       if (slot < total) {
         const uint32_t q = total - 1u - ((total - 1u - slot) & r.lds_mask);
-        const uint32_t site = (q + 1u) >> 1, end = q & 1u;
+        const uint32_t site = ((q + 1u) >> 1) + CHAIN::kLead, end = q & 1u;
         const uint32_t region = end ? chain.end_region(site, n_sites) : chain.start_region(site, n_sites);
         tag = (end << 31) | (region << 24) | r.tag_wave | (q & 0xFFFFFu);
         ts = r.sub[site & r.cmask] - r.t0_lo;
