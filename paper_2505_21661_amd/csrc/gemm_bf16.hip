@@ -85,16 +85,16 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 #define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 6) kp::chain_commit<N>(ring); } while (0)
 
 // The sequence of the large kernel's record sites (n sites in all).  Default schedule: regions 0, 1, 2 in turn,
-// three sites per K step; site 0 writes no record, it only fills the first place of the first batch, so that
-// every batch of the loop is "the site in front of the last barrier, the one behind it and the one in the
-// middle of this K step" and is committed before the next site in front of a barrier is sampled: no commit
-// waits for a clock it has just asked for, which on the last wave to reach the barrier would be time on the
-// critical path of every K step.  Stages apart: regions 2, 0, 3, 1 in turn, four sites per K step, committed
+// three sites per K step; sites 0 and 1 write no record, they only fill the first two places of the first
+// batch, so that every batch of the loop is "the site in the middle of the K step before, the one in front of
+// its barrier and the one behind it" and is committed once the first MFMAs of the next K step have been
+// issued: no commit waits for a clock it has just asked for, and none stands between a wave and the barrier,
+// where its instructions and the latency of its LDS write would be time on the critical path of every K step.  Stages apart: regions 2, 0, 3, 1 in turn, four sites per K step, committed
 // behind the barrier (every wave waits there in region 1 anyway); no leading site.  The last site of the loop
 // opens the epilogue region instead (3, or 4 with the stages apart), the very last closes it.
 template <bool PHASED>
 struct GemmChain {
-  static constexpr uint32_t kEpilogue = PHASED ? 4u : 3u, kRegions = kEpilogue + 1u, kLead = PHASED ? 0u : 1u;
+  static constexpr uint32_t kEpilogue = PHASED ? 4u : 3u, kRegions = kEpilogue + 1u, kLead = PHASED ? 0u : 2u;
   static constexpr bool kDense = true;
   // n = kLead + (3 or 4) K steps + 2: every enabled region of the loop leaves two records per K step, the epilogue two
   __device__ uint32_t total(uint32_t n, uint32_t mask) const {
@@ -461,10 +461,11 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+    KP_COMMIT(ring, 3);  // the sites of the K step before: in its middle, in front of its barrier and behind it
 #pragma unroll
     for (int ks = 0; ks + 1 < BK / 16; ++ks) {
       // ---- region 0: first half of the K step; region 1: second half
-      if (ks == 1) KP_SITE_K(ring, 2, 0, 1);  // 16 MFMAs on either side
+      if (ks == 1) KP_SITE_K(ring, 0, 0, 1);  // 16 MFMAs on either side
       read_step(ks + 1, (ks + 1) & 1);
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
@@ -483,15 +484,14 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < TN; ++i) bf_p[i] = bfr[(BK / 16 - 1) & 1][i];
     // the tiles of the next K step have landed (no other vector-memory operation is in flight in the loop)
-    KP_COMMIT(ring, 3);  // the site in front of the barrier before, the one behind it and the one in the middle
     if constexpr (MORE) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    KP_SITE_K(ring, 0, 1, 2);
+    KP_SITE_K(ring, 1, 1, 2);
     // ---- region 2: every wave is done with the stage ----------------------------------------------
     // (chained sites: nothing behind the barrier uses the clock just asked for, so nothing waits for it there)
     if constexpr (SITE == 1 || SITE == 3) asm volatile("s_barrier\n\ts_waitcnt lgkmcnt(0)" ::: "memory");
     else asm volatile("s_barrier" ::: "memory");
-    if constexpr (MORE) KP_SITE_K(ring, 1, 2, 0); else KP_SITE_K(ring, 1, 2, 3);
+    if constexpr (MORE) KP_SITE_K(ring, 2, 2, 0); else KP_SITE_K(ring, 2, 2, 3);
   };
   // The same K step with its stages one after the other, each a region of its own (the stage-by-stage
   // instrumentation of a software-pipelined GEMM, Sec. 5.3): 2 the staging registers (K step kt+1) go to
@@ -556,12 +556,16 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
     if (KT >= 2) iteration_phased(KT - 2, yes, no);
     iteration_phased(KT - 1, no, no);
   } else {
-    if constexpr (SITE == 6) kp::site_chain<0, REALTIME>(ring);  // (fills the first place of the first batch)
-    KP_SITE_K(ring, 1, kp::kNoRegion, 0);
+    if constexpr (SITE == 6) {  // (they fill the first two places of the first batch)
+      kp::site_chain<0, REALTIME>(ring);
+      kp::site_chain<1, REALTIME>(ring);
+    }
+    KP_SITE_K(ring, 2, kp::kNoRegion, 0);
     for (uint32_t kt = 0; kt + 2 < KT; ++kt) iteration(kt, yes, yes);
     if (KT >= 2) iteration(KT - 2, yes, no);
     iteration(KT - 1, no, no);
     mfma_pending();
+    KP_COMMIT(ring, 3);
   }
 
   // ---- region 3 (4 with the stages apart): epilogue ---------------------------------------------------
@@ -581,12 +585,12 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
       }
     }
   }
-  KP_SITE_K(ring, PHASED ? 1 : 2, PHASED ? 4 : 3, kp::kNoRegion);
+  KP_SITE_K(ring, PHASED ? 1 : 0, PHASED ? 4 : 3, kp::kNoRegion);
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, (uint32_t)WAVES >> g.group_log2, PHASED ? 5u : 4u, g.cap_hbm, g.flags};
     if constexpr (SITE == 6) {
-      // the sites that opened and closed the epilogue and, in the default schedule, the one in front of the last barrier
-      kp::chain_commit<PHASED ? 2 : 3>(ring);
+      // the site that closed the epilogue and, with the stages apart, the one that opened it
+      kp::chain_commit<PHASED ? 2 : 1>(ring);
       kp::ring_finish<REALTIME>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, GemmChain<PHASED>{});
     } else {
       kp::sites_end<SITE>(ring);
