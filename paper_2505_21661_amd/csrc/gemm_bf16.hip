@@ -424,6 +424,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   for (int i = 0; i < 4; ++i) af_p[i] = bf16x8{0};
 #pragma unroll
   for (int i = 0; i < TN; ++i) bf_p[i] = bf16x8{0};
+  constexpr int kLoadEvery = 2;  // (measured: 1 and 3 are 3 to 7 % slower)
   auto mfma_pending = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
@@ -446,20 +447,25 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn) bfr[buf][tn] = read_b(sB, ks, tn);
     };
+    // load d of the next K step's tiles goes behind MFMA kLoadEvery * d + kLoadEvery - 1 of the iteration's 32
+    auto load_behind = [&](uint32_t kt_, uint32_t stage_, int mfma) __attribute__((always_inline)) {
+      if (mfma % kLoadEvery == kLoadEvery - 1 && mfma / kLoadEvery < 8) {
+        __builtin_amdgcn_sched_barrier(0);
+        direct_one(kt_ + 1, stage_ ^ 1u, mfma / kLoadEvery);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
     read_step(0, 0);
-    // the last MFMA step of the K step before (zeros the first time); one load of the next K step's tiles
-    // behind every second MFMA of the first sixteen: the loads of all waves queue up in one unit of the CU,
-    // and a wave that issues its eight in a row waits there with no matrix work in flight
+    // the last MFMA step of the K step before (zeros the first time).  The loads of the next K step's tiles go
+    // behind every second MFMA of the first sixteen: the loads of all waves queue up in one unit of the CU, and a
+    // wave that issues its eight in a row waits there with no matrix work in flight; spread further, the last
+    // ones land too late
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
       for (int tm = 0; tm < 4; ++tm) {
         acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_p[tn], af_p[tm], acc[tn][tm], 0, 0, 0);
-        if constexpr (MORE) if (tm & 1) {
-          __builtin_amdgcn_sched_barrier(0);
-          direct_one(kt + 1, stage ^ 1u, tn * 2 + (tm >> 1));
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        if constexpr (MORE) load_behind(kt, stage, tn * 4 + tm);
       }
     KP_COMMIT(ring, 3);  // the sites of the K step before: in its middle, in front of its barrier and behind it
 #pragma unroll
@@ -472,11 +478,7 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
 #pragma unroll
         for (int tm = 0; tm < 4; ++tm) {
           acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][tn], af[ks & 1][tm], acc[tn][tm], 0, 0, 0);
-          if constexpr (MORE) if (ks == 0 && (tm & 1)) {
-            __builtin_amdgcn_sched_barrier(0);
-            direct_one(kt + 1, stage ^ 1u, 4 + tn * 2 + (tm >> 1));
-            __builtin_amdgcn_sched_barrier(0);
-          }
+          if constexpr (MORE) load_behind(kt, stage, 8 * (ks + 1) + tn * 4 + tm);
         }
     }
 #pragma unroll
