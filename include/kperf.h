@@ -361,11 +361,11 @@ kp_status kp_gemm_launch_shape(int M, int N, int K, int* n_wg, int* waves_per_wg
  * software-pipelined GEMMs stage by stage (Sec. 5.3 "Profiling Overhead", GEMM-SWP-2/3); the
  * regions here are
  *   M, N multiples of 256 with at least 16 tiles, K a multiple of 64: tile 256x256x64, 8 waves,
- *       per K-step, in this order: 0 first half of the MFMA steps, with the A share of the next
- *       K-step's staging (registers -> other LDS stage, refill from global memory) threaded between
- *       them, 1 second half with the B share and the wait for this wave's LDS writes, 2 barrier (with
- *       every region enabled and the circular strategy also the ~30 instructions that turn the K-step's
- *       three clock samples into records); 3 epilogue, once
+ *       per K-step, in this order: 0 the first sixteen MFMAs issued in the K-step's turn of the loop (the last
+ *       eight of the K-step before, whose operands were read ahead of the barrier, and the first eight of
+ *       this one), with the eight loads that send the next K-step's tiles from global memory straight to the
+ *       other LDS stage threaded between them; 1 the other sixteen and the wait for those loads and for this
+ *       wave's LDS reads; 2 barrier; 3 epilogue, once (it starts with the last eight MFMAs)
  *       With bit 29 of region_mask (KP_MASK_PHASES; this tile only, KP_ERR_INVALID_ARG otherwise) the
  *       stages of a K-step follow one another instead of being threaded into each other, and each is a
  *       region (5 regions, kp_trace_hdr.n_regions = 5; 4 sites and 8 records per K-step and wave):
