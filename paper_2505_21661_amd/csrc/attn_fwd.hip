@@ -4,11 +4,11 @@
 // The paper's case study profiles a flash-attention kernel whose regions are the two GEMMs and
 // the softmax of every KV iteration (Sec. 5.2, Table 3: GEMM0 = Q K^T, softmax, GEMM1 = P V).
 // This is the library's own MFMA kernel with the same three regions per KV tile of 64:
-//   region 0  S^T = K Q^T     (MFMA); from the second tile on it opens with the barrier that makes
-//             the K tile visible
-//   region 1  online softmax   (VALU, fp32); opens with the barrier and LDS writes that stage the
-//             next K tile, which overlap the other waves' softmax
-//   region 2  O^T += V^T P^T   (MFMA)
+//   region 0  S^T = K Q^T     (MFMA); closes behind the barrier that follows it
+//   region 1  online softmax   (VALU, fp32); opens with the four loads that send this wave's share of the
+//             next K tile from global memory straight to LDS
+//   region 2  O^T += V^T P^T   (MFMA; V is transposed by the LDS read); closes behind the barrier that
+//             follows it, and the next V tile is requested there
 // One workgroup = 4 waves = 128 query rows of one (batch, head); each wave owns 32 rows.  The
 // products are formed transposed so that a lane holds all scores of ONE query row: the row
 // maximum and sum are then in-lane reductions plus one exchange with the lane 32 away, and the
@@ -43,9 +43,9 @@ struct AttnArgs {
 };
 
 constexpr int kD = 128, kBq = 128, kBkv = 64, kAttnThreads = 256;
-constexpr uint32_t kKRow = kD * 2 + 16;        // K tile row: 256 bytes of data + 16 of padding
-constexpr uint32_t kKBytes = kBkv * kKRow;    // K tile   [64 kv][128 d]
-constexpr uint32_t kVBytes = kD * kBkv * 2;   // V^T tile [128 d][64 kv]
+constexpr uint32_t kRow = kD * 2;             // a row of either tile: one kv, 128 d, 256 bytes in 16 chunks of 16
+constexpr uint32_t kKBytes = kBkv * kRow;     // K tile [64 kv][128 d]
+constexpr uint32_t kVBytes = kBkv * kRow;     // V tile [64 kv][128 d], as it lies in memory
 constexpr float kSlack = 8.0f;                // log2 of how far a score may exceed the softmax reference
 
 // two fp32 -> packed bf16 pair (lo in bits 15:0), round to nearest even: one v_cvt_pk_bf16_f32
@@ -56,18 +56,15 @@ __device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// K tile: rows of 256 bytes (16 chunks of 16 B) plus 16 bytes of padding, so that the 16-byte reads
-// of 8 neighbouring rows cover all LDS banks and every read address of a lane is a constant away
-// from the lane's first one (an XOR swizzle would cost one vector instruction per read).
-__device__ __forceinline__ uint32_t k_off(uint32_t row, uint32_t chunk) { return row * kKRow + (chunk << 4); }
-// V^T tile: rows of 128 bytes (8 chunks of 16 B).  Within each group of 16 kv the four quads are
-// stored in the order 0, 2, 1, 3, so chunk 2g + h holds exactly the eight kv an MFMA step of the
-// P V product takes from lane half h.  The position also folds in row >> 3, because the transposing
-// writes hit rows that are 8 apart; rows 64..127 keep the two 8-byte halves of a chunk swapped so
-// that those writes spread over all banks.
-__device__ __forceinline__ uint32_t v_off(uint32_t row, uint32_t chunk) {
-  return row * 128u + ((chunk ^ ((row ^ (row >> 3)) & 7u)) << 4);
-}
+// Both tiles go from global memory straight to LDS (global_load_lds_dwordx4: lane l of a wave lands at byte
+// 16 l of a 1 KiB block, i.e. of four rows), so a tile's layout is a permutation of the 16 chunks inside each
+// row, which the loading lane applies by fetching the chunk that belongs at its place.
+// K tile: chunk c of row kv at position c ^ (kv % 16): the 16-byte operand reads of 16 neighbouring rows (one
+// pass of a 16-byte LDS read) cover all banks.
+// V tile: chunk c of row kv at position c ^ 4 (kv % 4).  Its operand reads transpose: ds_read_b64_tr_b16 hands
+// lane j of a group of 16 lanes the elements j, 16 + j, 32 + j, 48 + j of the 64 that the group's lanes address
+// (4 each), so with lane i addressing V[kv0 + i / 4][d0 + 4 (i % 4) ..+3] lane j receives V[kv0 .. kv0 + 3][d0 + j];
+// the XOR spreads the four rows and two column groups of a pass over all banks.
 
 // END of one region and/or START of the next with a single clock sample.  INSTR: 0 no record sites,
 // 1 generic sites (region mask, either buffer strategy, either store), 3 the same on the constant-rate clock,
@@ -126,41 +123,55 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   for (int s = 0; s < 8; ++s)
     qf[s] = *reinterpret_cast<const bf16x8*>(g.Q + head + (size_t)qrow * kD + 16 * s + 8 * h32);
 
-  // global -> LDS mapping
-  // K: 64 rows x 16 chunks; thread takes chunk (tid & 15) of rows (tid >> 4) + 16*i
-  const uint32_t k_row = tid >> 4, k_chunk = tid & 15u;
-  // V: thread takes 8 d (group tid & 15) of 4 consecutive kv (quad tid >> 4) and writes them transposed
-  const uint32_t v_dg = tid & 15u, v_kq = tid >> 4;
-  u32x4 k_reg[4], v_reg[4];
-  auto load_k = [&](uint32_t kv0) {
-    const uint16_t* kp_ = g.K + head + (size_t)(kv0 + k_row) * kD + k_chunk * 8;
+  // global -> LDS: either tile is 16 blocks of 1 KiB (four rows); wave w loads blocks 4 w .. 4 w + 3 of it.
+  // Lane i of block j is row 4 j + i / 16, chunk position i % 16.
+  const uint32_t lds0 = kp::wave_uniform((uint32_t)(uintptr_t)smem + 4096u * wave);
+  const uint16_t* k_src[4];
+  const uint16_t* v_src[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) k_reg[i] = *reinterpret_cast<const u32x4*>(kp_ + (size_t)(16 * i) * kD);
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t row = 16u * wave + 4u * (uint32_t)i + (lane >> 4), pos = lane & 15u;
+    k_src[i] = g.K + head + (size_t)row * kD + ((pos ^ (row & 15u)) << 3);
+    v_src[i] = g.V + head + (size_t)row * kD + ((pos ^ (4u * (row & 3u))) << 3);
+  }
+  // One load: M0 (the LDS base) is put back afterwards, the compiler does not expect inline assembly to change
+  // it.  From inline assembly because the compiler would make the next LDS access of any kind wait for such a
+  // load; hidden from its count of outstanding vector-memory operations the loads still complete in order, and
+  // the kernel waits for them itself in front of the barrier that precedes the tile's use.
+  auto direct_load = [&](const uint16_t* src, uint32_t dst) {
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(src), "s"(dst) : "memory");
+  };
+  auto load_k = [&](uint32_t kv0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) direct_load(k_src[i] + (size_t)kv0 * kD, lds0 + (uint32_t)i * 1024u);
   };
   auto load_v = [&](uint32_t kv0) {
-    const uint16_t* vp = g.V + head + (size_t)(kv0 + v_kq * 4) * kD + v_dg * 8;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v_reg[i] = *reinterpret_cast<const u32x4*>(vp + (size_t)i * kD);
+    for (int i = 0; i < 4; ++i) direct_load(v_src[i] + (size_t)kv0 * kD, lds0 + kKBytes + (uint32_t)i * 1024u);
   };
-  auto store_k = [&]() {
+  // operand reads: K row 32 tk + l32, chunk 2 s + h32; V for the kv of MFMA step (tk, s) and the d of tile dt
+  uint32_t k_rd[8], v_rd[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(sK + k_off(k_row + 16 * i, k_chunk)) = k_reg[i];
-  };
-  auto store_v = [&]() {
-    const uint32_t chunk = (v_kq >> 2) * 2u + (v_kq & 1u);
-    const uint32_t half = ((v_kq >> 1) ^ (v_dg >> 3)) & 1u;
+  for (int sx = 0; sx < 8; ++sx) k_rd[sx] = l32 * kRow + (((2u * (uint32_t)sx + h32) ^ (l32 & 15u)) << 4);
+  {
+    const uint32_t i = lane & 15u, grp = lane >> 4;  // groups 0, 1: d 0-15, 16-31 of the tile; 2, 3 the same for h = 1
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {  // word j of every row: d = 8*dg + 2j (low half) and 2j + 1 (high half)
-      const uint32_t w0 = v_reg[0][j], w1 = v_reg[1][j], w2 = v_reg[2][j], w3 = v_reg[3][j];
-      u32x2 ev, od;
-      // low halves / high halves of two words side by side: one v_perm_b32 each (bytes 0-3 of the
-      // selector's space are the second operand, 4-7 the first)
-      ev.x = __builtin_amdgcn_perm(w1, w0, 0x05040100u); ev.y = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
-      od.x = __builtin_amdgcn_perm(w1, w0, 0x07060302u); od.y = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
-      const uint32_t d = v_dg * 8u + 2u * (uint32_t)j;
-      *reinterpret_cast<u32x2*>(sV + v_off(d, chunk) + 8u * half) = ev;
-      *reinterpret_cast<u32x2*>(sV + v_off(d + 1u, chunk) + 8u * half) = od;
+    for (int dt = 0; dt < 4; ++dt) {
+      const uint32_t d = 32u * (uint32_t)dt + 16u * (grp & 1u) + 4u * (i & 3u);
+      v_rd[dt] = (4u * (grp >> 1) + (i >> 2)) * kRow + (((d >> 3) ^ (4u * (i >> 2))) << 4) + 8u * ((d >> 2) & 1u);
     }
+  }
+  auto read_v = [&](uint32_t kv_step, int dt) -> bf16x8 {  // kv_step: first kv of the MFMA step (a multiple of 16)
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    typedef __attribute__((address_space(3))) s16x4* lds_s16x4;
+    const unsigned char* at = sV + v_rd[dt] + kv_step * kRow;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(at));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(at + 8u * kRow));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
   };
 
   f32x16 oacc[4];  // O^T tiles: rows d = 32*dt + 8j + 4h + i, column q = lane % 32
@@ -169,22 +180,18 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   float m_run = -INFINITY, l_run = 0.f;
 
   const uint32_t n_tiles = g.causal ? (q0 + kBq) / kBkv : g.S / kBkv;
-  // Staging overlaps arithmetic: the K tile is only read by region 0 and the V^T tile only by
-  // region 2, so K tile t+1 is written after the barrier that follows region 0 of tile t (while the
-  // softmax runs), and V^T tile t during region 0 of tile t itself, between the MFMAs of K Q^T (every
-  // wave left region 2 of tile t-1 before the barrier that precedes it).  Each staging register is
-  // refilled from global memory right after it has been written out: a whole tile ahead.
+  // Staging overlaps arithmetic: the K tile is only read by region 0 and the V tile only by region 2, so K tile
+  // t+1 is requested behind the barrier that follows region 0 of tile t (and travels while softmax and P V run)
+  // and V tile t+1 behind the barrier that follows region 2 of tile t; each is waited for in front of the
+  // barrier that precedes its use.
   load_k(0);
   load_v(0);
-  store_k();
-  load_k(kBkv);  // there are always at least two tiles (S is a multiple of 128)
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-  // One KV tile.  MORE / MORE2 (tile t+1 / t+2 exists) and MASK (the tile may reach past the diagonal)
-  // are compile-time: the steady-state body has no branch around its loads and LDS writes, so the
-  // compiler can wait for exactly the loads a write needs instead of for all outstanding ones.  The
-  // barriers wait for LDS traffic only, never for the global loads of later tiles.
-  auto tile = [&](uint32_t t, auto more_c, auto more2_c, auto mask_c) {
-    constexpr bool MORE = decltype(more_c)::value, MORE2 = decltype(more2_c)::value, MASK = decltype(mask_c)::value;
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  // One KV tile.  MORE (tile t+1 exists) and MASK (the tile may reach past the diagonal) are compile-time: the
+  // steady-state body has no branch.  Each barrier waits for this wave's LDS traffic and for the tile it
+  // requested one barrier earlier.
+  auto tile = [&](uint32_t t, auto more_c, auto mask_c) {
+    constexpr bool MORE = decltype(more_c)::value, MASK = decltype(mask_c)::value;
     const uint32_t kv0 = t * kBkv;
 
     // ---- region 0: S^T = K Q^T, with the staging of V^T tile t threaded in ------------------------
@@ -194,29 +201,26 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // the MFMA goes first and the matrix pipe stays fed, while the softmax fills the gaps (measured:
     // 3 % faster than equal priorities, the opposite order 3 % slower).
     __builtin_amdgcn_s_setprio(1);
-    store_v();
-    if constexpr (MORE) load_v(kv0 + kBkv);
     f32x16 sacc[2];
     sacc[0] = f32x16{0}; sacc[1] = f32x16{0};
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
 #pragma unroll
       for (int tk = 0; tk < 2; ++tk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + k_off(32 * tk + l32, 2 * s + h32));
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + k_rd[s] + (uint32_t)tk * 32u * kRow);
         sacc[tk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[tk], 0, 0, 0);
       }
     }
     __builtin_amdgcn_s_setprio(0);
 
-    // every wave is done with K tile t and V^T tile t is visible; K tile t+1 goes to LDS while the softmax runs
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // every wave is done with K tile t and V tile t has landed; K tile t+1 travels while softmax and P V run
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // The site sits behind the barrier, not in front of it: in front, the barrier's wait for LDS traffic
     // would also wait for the two record stores the site has just issued, every tile (measured: 1.5
     // points of overhead).  The wait at the barrier thereby belongs to the region that ends here.
     KP_BOUNDARY(ring, 0, 1);
     KP_CHAIN(1, ring);
-    if constexpr (MORE) store_k();
-    if constexpr (MORE2) load_k(kv0 + 2 * kBkv);
+    if constexpr (MORE) load_k(kv0 + kBkv);
 
     // ---- region 1: online softmax (this lane: query row qrow, 32 of the tile's 64 kv) -------------
     const bool diag = MASK && g.causal && (kv0 + kBkv > q0 + wave * 32);  // tile reaches past this wave's first row
@@ -275,16 +279,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          const uint32_t row = 32 * dt + l32;
-          u32x4 vw = *reinterpret_cast<const u32x4*>(sV + v_off(row, 4 * tk + 2 * s + h32));
-          if (dt >= 2) vw = u32x4{vw.z, vw.w, vw.x, vw.y};  // rows 64.. store the chunk halves swapped
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf, oacc[dt], 0, 0, 0);
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v(32u * (uint32_t)tk + 16u * (uint32_t)s, dt), pf, oacc[dt], 0, 0, 0);
         }
       }
     __builtin_amdgcn_s_setprio(0);
 
-    // every wave is done with V^T tile t, and K tile t+1 is visible
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // every wave is done with V tile t, and K tile t+1 has landed
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // One site closes region 2 and opens region 0 of the next tile: a tile costs three sites, not four.
     // Behind the barrier for the same reason as above.
     if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, kp::kNoRegion);
@@ -292,15 +293,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       kp::chain_commit<3>(ring);
       KP_CHAIN(0, ring);
     }
+    if constexpr (MORE) load_v(kv0 + kBkv);
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   KP_BOUNDARY(ring, kp::kNoRegion, 0);
   KP_CHAIN(0, ring);
   // only the last two tiles of a causal block can reach past the diagonal
-  for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, yes, no);
-  tile(n_tiles - 2, yes, no, yes);
-  tile(n_tiles - 1, no, no, yes);
+  for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, no);
+  tile(n_tiles - 2, yes, yes);
+  tile(n_tiles - 1, no, yes);
 
   // epilogue: O[q][d] = O^T[d][q] / l
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
