@@ -73,14 +73,19 @@ __device__ __forceinline__ uint32_t bf16_pack_rne(float lo, float hi) {
 #define KP_BOUNDARY(ring, end_r, start_r) do { if constexpr (INSTR == 1 || INSTR == 3) kp::site<INSTR>(ring, end_r, start_r); } while (0)
 #define KP_CHAIN(K, ring) do { if constexpr (INSTR >= 4) kp::site_chain<K, (INSTR == 5)>(ring); } while (0)
 
-// The sequence of record sites: one ahead of the loop (opens region 0), three per KV tile, the last only closes.
+// The sequence of record sites: two that write no record (they fill the first batch), one ahead of the loop
+// (opens region 0), three per KV tile, the last only closes.  A tile's three sites are committed as one batch
+// inside region 0 of the next tile, once its first MFMAs have been issued: nothing but the clock reads stands
+// behind a barrier, where every wave of the workgroup would pay for it at the same time.
 struct AttnChain {
-  static constexpr uint32_t kRegions = 3u, kLead = 0u;
+  static constexpr uint32_t kRegions = 3u, kLead = 2u;
   static constexpr bool kDense = true;
-  // n = 3 tiles + 1: every enabled region leaves two records per tile
-  __device__ uint32_t total(uint32_t n, uint32_t mask) const { return 2u * ((n - 1u) / 3u) * (uint32_t)__builtin_popcount(mask & 7u); }
-  __device__ uint32_t end_region(uint32_t site, uint32_t) const { return site == 0u ? kp::kNoRegion : (site - 1u) % 3u; }
-  __device__ uint32_t start_region(uint32_t site, uint32_t n) const { return site + 1u == n ? kp::kNoRegion : site % 3u; }
+  // n = 2 + 1 + 3 tiles: every enabled region leaves two records per tile
+  __device__ uint32_t total(uint32_t n, uint32_t mask) const { return 2u * ((n - 3u) / 3u) * (uint32_t)__builtin_popcount(mask & 7u); }
+  __device__ uint32_t end_region(uint32_t site, uint32_t) const { return site <= kLead ? kp::kNoRegion : (site - 1u - kLead) % 3u; }
+  __device__ uint32_t start_region(uint32_t site, uint32_t n) const {
+    return (site < kLead || site + 1u == n) ? kp::kNoRegion : (site - kLead) % 3u;
+  }
 };
 
 template <int INSTR>
@@ -210,6 +215,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + k_rd[s] + (uint32_t)tk * 32u * kRow);
         sacc[tk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[tk], 0, 0, 0);
       }
+      // the three sites of the tile before (ahead of the first tile: the one that opened region 0)
+      if constexpr (INSTR >= 4) if (s == 3) kp::chain_commit<3>(ring);
     }
     __builtin_amdgcn_s_setprio(0);
 
@@ -219,7 +226,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // would also wait for the two record stores the site has just issued, every tile (measured: 1.5
     // points of overhead).  The wait at the barrier thereby belongs to the region that ends here.
     KP_BOUNDARY(ring, 0, 1);
-    KP_CHAIN(1, ring);
+    KP_CHAIN(0, ring);
     if constexpr (MORE) load_k(kv0 + kBkv);
 
     // ---- region 1: online softmax (this lane: query row qrow, 32 of the tile's 64 kv) -------------
@@ -264,7 +271,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
       }
     l_run += psum;
     KP_BOUNDARY(ring, 1, 2);
-    KP_CHAIN(2, ring);
+    KP_CHAIN(1, ring);
     __builtin_amdgcn_s_setprio(2);
 
     // ---- region 2: O^T += V^T P^T ---------------------------------------------------------------------
@@ -289,16 +296,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
     // One site closes region 2 and opens region 0 of the next tile: a tile costs three sites, not four.
     // Behind the barrier for the same reason as above.
     if constexpr (MORE) KP_BOUNDARY(ring, 2, 0); else KP_BOUNDARY(ring, 2, kp::kNoRegion);
-    if constexpr (INSTR >= 4) {
-      kp::chain_commit<3>(ring);
-      KP_CHAIN(0, ring);
-    }
+    KP_CHAIN(2, ring);
     if constexpr (MORE) load_v(kv0 + kBkv);
   };
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
   KP_BOUNDARY(ring, kp::kNoRegion, 0);
-  KP_CHAIN(0, ring);
+  KP_CHAIN(0, ring);  // (the first two fill the first batch and write no record)
+  KP_CHAIN(1, ring);
+  KP_CHAIN(2, ring);
   // only the last two tiles of a causal block can reach past the diagonal
   for (uint32_t t = 0; t + 2 < n_tiles; ++t) tile(t, yes, no);
   tile(n_tiles - 2, yes, yes);
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void kp_attn_fwd(AttnArgs g) {
   if constexpr (INSTR != 0) {
     kp::TraceGeom tg{g.n_wg, 4u >> g.group_log2, 3, g.cap_hbm, g.flags};
     if constexpr (INSTR >= 4) {
-      kp::chain_commit<1>(ring);
+      kp::chain_commit<3>(ring);  // the sites of the last tile
       kp::ring_finish<INSTR == 5>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost, AttnChain{});
     } else {
       kp::ring_finish<INSTR == 3>(ring, g.cap_lds, g.trace, tg, wg, g.rec_cost);
