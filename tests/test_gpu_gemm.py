@@ -171,6 +171,22 @@ def test_big_tile_gemm_matches_oracle_and_vanilla(kp):
     assert torch.equal(c.cpu().view(torch.int16), b2.view(torch.int16))
 
 
+@pytest.mark.parametrize("M,N,K", [(768, 1536, 192), (2048, 512, 64), (1280, 1024, 448), (512, 2304, 128)])
+def test_big_tile_other_shapes(kp, M, N, K):
+    """Tile grids that are not square, with and without the XCD-block mapping of workgroups to tiles, one to
+    seven K steps: both schedules of the K loop against the fp64 oracle, instrumented bit-identical."""
+    a, b = inputs.gemm_inputs(M, N, K, seed=M + N + K)
+    c_van, _, shape = run_gemm(kp, a, b, 0)
+    assert shape == ((M // 256) * (N // 256), 8, 4)
+    assert_close_to_oracle(c_van, a, b)
+    c_ins, _, _ = run_gemm(kp, a, b, 0b1111, trace_cap=1024)
+    assert torch.equal(c_ins.view(torch.int16), c_van.view(torch.int16))
+    c_ph, _, _ = run_gemm_phased(kp, a, b, 0)
+    assert torch.equal(c_ph.view(torch.int16), c_van.view(torch.int16))
+    c_ph5, _, _ = run_gemm_phased(kp, a, b, 0b11111, trace_cap=1024)
+    assert torch.equal(c_ph5.view(torch.int16), c_van.view(torch.int16))
+
+
 def test_big_tile_trace_small_k(kp, oracle_mod):
     from tests.gpu_util import assert_stats_equal
 
