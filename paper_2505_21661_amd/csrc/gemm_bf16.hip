@@ -314,42 +314,46 @@ __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
   // stay sufficient (they may wait for more), and the kernel waits for them itself before the barrier.
   constexpr bool DIRECT = !PHASED;
   const uint32_t d_lds0 = kp::wave_uniform((uint32_t)(uintptr_t)smem + 4096u * wave);
-  const uint16_t* d_src[4];
+  uint32_t d_off[4];  // byte offsets from the tile's first element (the base stays in scalar registers)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t row = 32u * wave + 8u * (uint32_t)i + (lane >> 3);
     const uint32_t chunk = (lane & 7u) ^ ((row >> 1) & 7u);  // tile_off<64>: position = chunk ^ (row / 2) % 8
-    d_src[i] = g.A + (size_t)(m0 + row) * g.K + chunk * 8u;
+    d_off[i] = (row * g.K + chunk * 8u) * 2u;
   }
+  const uint16_t* a_base = g.A + (size_t)m0 * g.K;
   // The B tile likewise, as it lies in memory: 64 rows (k) of 256 n, 512 bytes each; chunk c (8 n) of row k at
   // chunk position c ^ 4 (k % 4).  Wave w fills blocks 4 w .. 4 w + 3 of 1 KiB, two rows each.
-  const uint16_t* db_src[4];
+  uint32_t db_off[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t row = 8u * wave + 2u * (uint32_t)i + (lane >> 5);
     const uint32_t chunk = (lane & 31u) ^ (4u * (row & 3u));
-    db_src[i] = g.B + (size_t)row * g.N + n0 + chunk * 8u;
+    db_off[i] = (row * g.N + chunk * 8u) * 2u;
   }
-  // One load: M0 (the LDS base) is put back afterwards, the compiler does not expect inline assembly to change
-  // it; one wait state between the write of M0 and the load that uses it.  The eight loads of a K step stay
+  const uint16_t* b_base = g.B + n0;
+  // One load, its global address a scalar base (the tile's first element in this K step) plus the lane's 32-bit
+  // byte offset, which never changes: no vector arithmetic per load (with a 64-bit pointer per lane and load
+  // the kernel was 3.5 % slower).  M0 (the LDS base) is put back afterwards, the compiler does not expect
+  // inline assembly to change it; one wait state between the write of M0 and the load that uses it.  The eight loads of a K step stay
   // separate statements: issued back to back from one block of assembly they made the uninstrumented kernel 4 %
   // slower (the address arithmetic of the next load no longer sits between two loads).
-  auto direct_load = [&](const uint16_t* src, uint32_t dst) {
+  auto direct_load = [&](const uint16_t* base, uint32_t off, uint32_t dst) {
     uint32_t saved_m0;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0) : "v"(src), "s"(dst) : "memory");
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(off), "s"(dst), "s"(base) : "memory");
   };
   auto direct_one = [&](uint32_t kt, uint32_t stage, int idx) {
     const uint32_t dst = d_lds0 + stage * STAGE;
-    if (idx < 4) direct_load(d_src[idx] + (size_t)kt * BK, dst + (uint32_t)idx * 1024u);
-    else direct_load(db_src[idx - 4] + (size_t)kt * BK * g.N, dst + A_BYTES + (uint32_t)(idx - 4) * 1024u);
+    if (idx < 4) direct_load(a_base + (size_t)kt * BK, d_off[idx], dst + (uint32_t)idx * 1024u);
+    else direct_load(b_base + (size_t)kt * BK * g.N, db_off[idx - 4], dst + A_BYTES + (uint32_t)(idx - 4) * 1024u);
   };
   auto direct_tiles = [&](uint32_t kt, uint32_t stage) {
     const uint32_t dst = d_lds0 + stage * STAGE;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) direct_load(d_src[i] + (size_t)kt * BK, dst + (uint32_t)i * 1024u);
+    for (int i = 0; i < 4; ++i) direct_load(a_base + (size_t)kt * BK, d_off[i], dst + (uint32_t)i * 1024u);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) direct_load(db_src[i] + (size_t)kt * BK * g.N, dst + A_BYTES + (uint32_t)i * 1024u);
+    for (int i = 0; i < 4; ++i) direct_load(b_base + (size_t)kt * BK * g.N, db_off[i], dst + A_BYTES + (uint32_t)i * 1024u);
   };
 
   const uint32_t wm = WAVES == 8 ? wave >> 2 : wave >> 1;  // wave position: 2 x 4 or 2 x 2
