@@ -318,7 +318,7 @@ __device__ __forceinline__ void site_chain(Ring& r) {
 template <int N>
 __device__ __forceinline__ void chain_commit(Ring& r) {
   static_assert(N >= 1 && N <= 4, "four sites per batch at most");
-  __builtin_amdgcn_sched_barrier(0);
+  // (no scheduling fence: the commit's instructions may sit between the MFMAs around it)
   uint32_t vt = 0u;
 #pragma unroll
   for (int k = 0; k < N; ++k) {
@@ -340,7 +340,6 @@ __device__ __forceinline__ void chain_commit(Ring& r) {
       : "v"(addr), "v"(vt), "n"((1 << N) - 1)
       : "memory");
   r.cw += (uint32_t)N;
-  __builtin_amdgcn_sched_barrier(0);
 }
 
 // r.cw counts sites in this form.  A wave that does not write its group's stream stores its clocks to
