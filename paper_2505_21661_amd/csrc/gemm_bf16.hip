@@ -81,7 +81,7 @@ __device__ __forceinline__ uint32_t tile_off_bt(uint32_t row, uint32_t chunk) {
 // of site K of the batch (kp::site_chain) and KP_COMMIT, which stands right after a wait for all LDS
 // traffic, stores the batch's clocks; the records are made when the trace is copied out.
 #define KP_SITE_K(ring, K, end_r, start_r) do { if constexpr (INSTR != 0) { \
-    if constexpr (SITE == 6) kp::site_chain<K, (INSTR == 5)>(ring); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
+    if constexpr (SITE == 6) kp::site_chain<K, (INSTR == 5), kMayCross>(ring); else kp::site<SITE>(ring, end_r, start_r); } } while (0)
 #define KP_COMMIT(ring, N) do { if constexpr (INSTR != 0 && SITE == 6) kp::chain_commit<N>(ring); } while (0)
 
 // The sequence of the large kernel's record sites (n sites in all).  Default schedule: regions 0, 1, 2 in turn,
@@ -215,6 +215,9 @@ constexpr uint32_t kBigTileBytes = 2u * (kBigBM + kBigBN) * kBigBK * 2u;  // bot
 
 template <int INSTR, int WAVES, int SCHEDULE>
 __global__ __launch_bounds__(WAVES * 64) void kp_gemm_big(GemmArgs g) {
+  // default schedule: vector, scalar and LDS-read instructions may be scheduled across a chained site; the
+  // regions are halves of the K step's MFMAs, which stay on their side (stages apart: nothing crosses)
+  constexpr int kMayCross = SCHEDULE == 0 ? 0x106 : 0;
   // SCHEDULE 0: staging threaded through the MFMAs; 1: the stages of a K step one after the other; 2: the
   // same source without the scheduling fences between the stages (uninstrumented only)
   constexpr bool PHASED = SCHEDULE != 0;

@@ -307,12 +307,15 @@ __device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 // Measured: attention kernel (three sites per KV tile) 10 % with the records written at the sites (51
 // instructions per tile and wave, whether they took six LDS instructions or two) against 3 %; large GEMM
 // with four sites per K step 6-8 % with the sites buffered in vector registers against 3 %.
-template <int K, bool REALTIME = false>
+// MAY_CROSS: the kinds of instruction the scheduler may move across the site (a sched_barrier mask; 0: none).
+// A kernel whose regions are defined by its matrix instructions can let vector, scalar and LDS-read
+// instructions cross (0x106) and keep the matrix and memory instructions on their side of the clock read.
+template <int K, bool REALTIME = false, int MAY_CROSS = 0>
 __device__ __forceinline__ void site_chain(Ring& r) {
   static_assert(K >= 0 && K < 4, "four sites per batch at most");
-  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_sched_barrier(MAY_CROSS);
   r.dq_t[K] = sample_clock<REALTIME>();
-  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_sched_barrier(MAY_CROSS);
 }
 
 template <int N>
