@@ -307,6 +307,8 @@ __device__ __forceinline__ void lean_end(Ring& r) { r.cnt = r.cw - r.tag_wave; }
 // Measured: attention kernel (three sites per KV tile) 10 % with the records written at the sites (51
 // instructions per tile and wave, whether they took six LDS instructions or two) against 3 %; large GEMM
 // with four sites per K step 6-8 % with the sites buffered in vector registers against 3 %.
+// Every pair that a site samples into must be read by a later commit on every path: a pair whose value is
+// never read is free for the compiler to reuse at once, and the clock would then land in whatever lives there.
 // MAY_CROSS: the kinds of instruction the scheduler may move across the site (a sched_barrier mask; 0: none).
 // A kernel whose regions are defined by its matrix instructions can let vector, scalar and LDS-read
 // instructions cross (0x106) and keep the matrix and memory instructions on their side of the clock read.
