@@ -396,7 +396,9 @@ kp_status kp_attn_launch_shape(int B, int H, int S, int D, int* n_wg, int* waves
  *   0 Q K^T (MFMA), 1 online softmax, 2 P V (MFMA);
  * END of region 2 and START of region 0 of the next tile share one clock sample.  The samples that
  * close regions 0 and 2 are taken right behind the workgroup barrier that follows the region's work, so
- * the wait at that barrier belongs to the region that ends there.
+ * the wait at that barrier belongs to the region that ends there (it also waits for the tile that the next
+ * region reads: the K and V tiles go from global memory straight to LDS, each requested one barrier ahead
+ * of its use -- the next K tile at the head of region 1, the next V tile at the head of region 0).
  * One workgroup (4 waves) handles 128 query rows; with causal masking block q records
  * 6 * 2 * (q + 1) times per wave.  region_mask, trace_buf, trace_cap as for the GEMM.
  */
